@@ -1,0 +1,124 @@
+"""ctypes front end of ops.c.  Test infrastructure only.
+
+All tensors are float32 numpy arrays in NHWC order holding values that are
+representable in the storage type named by `dtype` ("f32", "f16", "bf16").
+"""
+import ctypes as C
+import numpy as np
+from . import build as _build
+
+_DT = {"f32": 0, "f16": 1, "bf16": 2}
+_ACT = {"none": 0, "relu": 1, "relu6": 2}
+_lib = None
+_fp = C.POINTER(C.c_float)
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(_build.build())
+        _lib.orc_round_store.restype = C.c_double
+        _lib.orc_round_store.argtypes = [C.c_double, C.c_int]
+        _lib.orc_conv_point.restype = C.c_double
+        _lib.orc_num_threads.restype = C.c_int
+    return _lib
+
+
+def _p(a):
+    if a is None:
+        return None
+    assert a.dtype == np.float32 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(_fp)
+
+
+def out_dim(n, pad, k, stride):
+    return (n + 2 * pad - k) // stride + 1
+
+
+def round_store(v, dtype):
+    return lib().orc_round_store(float(v), _DT[dtype])
+
+
+def round_array(a, dtype):
+    a = np.ascontiguousarray(a, dtype=np.float32).copy()
+    lib().orc_round_array(_p(a), C.c_size_t(a.size), _DT[dtype])
+    return a
+
+
+def num_threads():
+    return lib().orc_num_threads()
+
+
+def _out(y, n, p, q, k, c_off, c_tot):
+    c_tot = c_tot or k
+    if y is None:
+        y = np.zeros((n, p, q, c_tot), dtype=np.float32)
+    assert y.shape == (n, p, q, c_tot) and c_off + k <= c_tot
+    return y, c_tot
+
+
+def conv(x, w, bias=None, stride=(1, 1), pad=(0, 0), act="none", res=None, dtype="f32",
+         y=None, c_off=0, c_tot=0):
+    n, h, wd, c = x.shape
+    k, r, s, c2 = w.shape
+    assert c == c2
+    p, q = out_dim(h, pad[0], r, stride[0]), out_dim(wd, pad[1], s, stride[1])
+    y, c_tot = _out(y, n, p, q, k, c_off, c_tot)
+    res_ct = 0
+    if res is not None:
+        assert res.shape[:3] == (n, p, q) and res.shape[3] >= k
+        res_ct = res.shape[3]
+    lib().orc_conv(_p(x), n, h, wd, c, _p(w), k, r, s, stride[0], stride[1], pad[0], pad[1],
+                   _p(bias), _p(res), res_ct, _ACT[act], _DT[dtype], _p(y), c_off, c_tot)
+    return y
+
+
+def dwconv(x, w, bias=None, stride=(1, 1), pad=(0, 0), act="none", dtype="f32", y=None, c_off=0, c_tot=0):
+    n, h, wd, c = x.shape
+    c2, r, s = w.shape
+    assert c == c2
+    p, q = out_dim(h, pad[0], r, stride[0]), out_dim(wd, pad[1], s, stride[1])
+    y, c_tot = _out(y, n, p, q, c, c_off, c_tot)
+    lib().orc_dwconv(_p(x), n, h, wd, c, _p(w), r, s, stride[0], stride[1], pad[0], pad[1],
+                     _p(bias), _ACT[act], _DT[dtype], _p(y), c_off, c_tot)
+    return y
+
+
+def _pool(fn, x, k, stride, pad, dtype, y, c_off, c_tot):
+    n, h, wd, c = x.shape
+    p, q = out_dim(h, pad[0], k[0], stride[0]), out_dim(wd, pad[1], k[1], stride[1])
+    y, c_tot = _out(y, n, p, q, c, c_off, c_tot)
+    fn(_p(x), n, h, wd, c, k[0], k[1], stride[0], stride[1], pad[0], pad[1], _DT[dtype], _p(y), c_off, c_tot)
+    return y
+
+
+def maxpool(x, k, stride, pad=(0, 0), dtype="f32", y=None, c_off=0, c_tot=0):
+    return _pool(lib().orc_maxpool, x, k, stride, pad, dtype, y, c_off, c_tot)
+
+
+def avgpool(x, k, stride, pad=(0, 0), dtype="f32", y=None, c_off=0, c_tot=0):
+    return _pool(lib().orc_avgpool, x, k, stride, pad, dtype, y, c_off, c_tot)
+
+
+def global_avgpool(x, dtype="f32", y=None, c_off=0, c_tot=0):
+    n, h, wd, c = x.shape
+    y, c_tot = _out(y, n, 1, 1, c, c_off, c_tot)
+    lib().orc_global_avgpool(_p(x), n, h, wd, c, _DT[dtype], _p(y), c_off, c_tot)
+    return y
+
+
+def fc(x, w, bias=None, act="none", dtype="f32"):
+    n = x.shape[0]
+    j = int(np.prod(x.shape[1:]))
+    k, j2 = w.shape
+    assert j == j2
+    y = np.zeros((n, 1, 1, k), dtype=np.float32)
+    lib().orc_fc(_p(np.ascontiguousarray(x.reshape(n, j))), n, j, _p(w), k, _p(bias), _ACT[act], _DT[dtype], _p(y))
+    return y
+
+
+def conv_point(x, w, stride, pad, n, p, q, k):
+    """Unrounded, bias-free value of one convolution output element."""
+    _, h, wd, c = x.shape
+    _, r, s, _ = w.shape
+    return lib().orc_conv_point(_p(x), h, wd, c, _p(w), r, s, stride[0], stride[1], pad[0], pad[1], n, p, q, k)

@@ -1,0 +1,148 @@
+"""The paper's scheduling layer, written out plainly.  Test infrastructure only.
+
+  expand()       T(G, rho): pointer matrix -> stages            (Sec. III-B Eqs. 3-6, Sec. III-C Eq. 8)
+  issue_order()  order in which the main thread launches a stage (Sec. III-D, BFS vs DFS)
+  coordinate_descent(), random_search()                          (Sec. III-C, Alg. 1)
+
+Readings where the paper is silent:
+  * A pointer is the 1-based index of the last operator of a stage, inclusive
+    (Eq. 3: (3,5,7) over [1..10] gives [1,2,3],[4,5],[6,7],[8,9,10]); the last
+    stage takes the remainder; 0 means "nothing yet"; equal neighbours give an
+    empty slice, which Eq. 5 allows ("S3(None)").
+  * Per-stage concurrency c: the tenants with a non-empty slice are ranked in
+    tenant order; rank j runs on the stream of the tenant of rank j mod c, after
+    the lower-ranked tenants mapped to the same stream.
+  * Candidate rows of Alg. 1 are P draws, uniform on [0, len_i], sorted.  Random
+    search draws every pointer independently and unsorted, and discards a matrix
+    with a non-monotone row (the paper's "infeasible solutions are filtered out").
+  * Random draws come from a counter-based generator so that an independent
+    implementation can reproduce them: draw(seed, a, b, c, d) below.
+"""
+
+M64 = (1 << 64) - 1
+
+
+def mix64(z):
+    z = (z + 0x9E3779B97F4A7C15) & M64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & M64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & M64
+    return z ^ (z >> 31)
+
+
+def draw(seed, a, b, c, d):
+    h = mix64(seed & M64)
+    for v in (a, b, c, d):
+        h = mix64(h ^ (v & M64))
+    return h
+
+
+def validate(lens, rho):
+    """rho: N rows of P pointers.  Returns None if valid, else a reason."""
+    if len(rho) != len(lens):
+        return "row count"
+    for row, n in zip(rho, lens):
+        prev = 0
+        for v in row:
+            if v < prev:
+                return "non-monotone"
+            if v > n:
+                return "beyond sequence"
+            prev = v
+    return None
+
+
+def expand(lens, rho):
+    """T(G, rho): returns stages[s][i] = (begin, end), 0-based half-open slice of
+    tenant i's operator list launched in stage s.  P pointers give P+1 stages."""
+    assert validate(lens, rho) is None
+    n_stages = (len(rho[0]) if rho else 0) + 1
+    stages = []
+    for s in range(n_stages):
+        st = []
+        for row, n in zip(rho, lens):
+            begin = row[s - 1] if s > 0 else 0
+            end = row[s] if s < n_stages - 1 else n
+            st.append((begin, end))
+        stages.append(st)
+    return stages
+
+
+def stream_map(stage, concurrency):
+    """Host stream (a tenant index) of every tenant active in the stage."""
+    active = [i for i, (b, e) in enumerate(stage) if e > b]
+    c = max(1, min(concurrency, len(active))) if active else 1
+    return {t: active[j % c] for j, t in enumerate(active)}
+
+
+def issue_order(stage, concurrency, order="bfs"):
+    """Launch sequence of one stage: list of (stream, tenant, op_index)."""
+    smap = stream_map(stage, concurrency)
+    queues = {}
+    for t in sorted(smap):
+        b, e = stage[t]
+        queues.setdefault(smap[t], []).extend((t, i) for i in range(b, e))
+    streams = sorted(queues)
+    out = []
+    if order == "dfs":
+        for s in streams:
+            out.extend((s, t, i) for t, i in queues[s])
+        return out
+    depth = 0
+    while True:
+        any_left = False
+        for s in streams:
+            if depth < len(queues[s]):
+                t, i = queues[s][depth]
+                out.append((s, t, i))
+                any_left = True
+        if not any_left:
+            return out
+        depth += 1
+
+
+def even_split(lens, n_pointers):
+    """Initial pointer matrix: stage boundaries at ceil(len * j / (P+1))."""
+    return [[-(-n * (j + 1) // (n_pointers + 1)) for j in range(n_pointers)] for n in lens]
+
+
+def sample_row(seed, rnd, model, cand, n_pointers, length):
+    return sorted(draw(seed, rnd, model, cand, j) % (length + 1) for j in range(n_pointers))
+
+
+def coordinate_descent(lens, n_pointers, rounds, n_cand, cost, seed, init=None):
+    """Alg. 1.  `cost(rho)` stands for "profile the latency by multiple runs".
+    Returns (best_rho, best_cost, records); records lists every evaluated
+    (rho, cost) in evaluation order; the best is the earliest minimum."""
+    rho = [list(r) for r in (init if init is not None else even_split(lens, n_pointers))]
+    records = []
+    for r in range(rounds):
+        for i in range(len(lens)):
+            best_row, best_lat = None, None
+            for m in range(n_cand):
+                row = sample_row(seed, r, i, m, n_pointers, lens[i])
+                cand = [list(x) for x in rho]
+                cand[i] = row
+                lat = cost(cand)
+                records.append((cand, lat))
+                if best_lat is None or lat < best_lat:
+                    best_row, best_lat = row, lat
+            rho[i] = best_row
+    best = min(range(len(records)), key=lambda j: (records[j][1], j))
+    return records[best][0], records[best][1], records
+
+
+def random_search(lens, n_pointers, evaluations, cost, seed):
+    """Random search: whole matrices, independent unsorted draws, infeasible ones skipped."""
+    records = []
+    skipped = 0
+    for e in range(evaluations):
+        rho = [[draw(seed, e, i, 0x52, j) % (lens[i] + 1) for j in range(n_pointers)]
+               for i in range(len(lens))]
+        if validate(lens, rho) is not None:
+            skipped += 1
+            continue
+        records.append((rho, cost(rho)))
+    if not records:
+        return None, None, records, skipped
+    best = min(range(len(records)), key=lambda j: (records[j][1], j))
+    return records[best][0], records[best][1], records, skipped

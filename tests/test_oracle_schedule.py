@@ -1,0 +1,137 @@
+"""Pins for the oracle's scheduling layer: the paper's worked examples, invariants, Alg. 1 control flow."""
+import os
+import random
+import pytest
+from oracle import schedule as S
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _lines(name):
+    with open(os.path.join(GOLD, name)) as f:
+        return [l.split() for l in f if l.strip() and not l.startswith("#")]
+
+
+def test_pointer_example_eq3():
+    rows = _lines("pointer_example.txt")
+    n = int(rows[0][0])
+    rho = [int(v) for v in rows[1]]
+    want = [[int(v) for v in r] for r in rows[2:]]
+    stages = S.expand([n], [rho])
+    got = [list(range(b + 1, e + 1)) for (b, e), in stages]
+    assert got == want
+    assert len(stages) == len(rho) + 1          # P pointers => P+1 stages
+
+
+def test_stage_example_eqs4_5():
+    want = {}
+    for st, sm, first, last in _lines("stage_example.txt"):
+        want[(int(st), int(sm))] = (int(first), int(last))
+    # pointer rows consistent with the two printed stages; stream lengths beyond them are free
+    lens = [10, 4, 5]
+    rho = [[3, 5], [1, 2], [2, 2]]
+    stages = S.expand(lens, rho)
+    for (st, sm), (first, last) in want.items():
+        b, e = stages[st - 1][sm - 1]
+        if first == 0:
+            assert b == e                        # "None": empty slice is legal
+        else:
+            assert (b + 1, e) == (first, last)
+
+
+def test_expand_invariants_random():
+    rng = random.Random(5)
+    for _ in range(200):
+        n = rng.randint(1, 6)
+        p = rng.randint(0, 5)
+        lens = [rng.randint(1, 30) for _ in range(n)]
+        rho = [sorted(rng.randint(0, L) for _ in range(p)) for L in lens]
+        stages = S.expand(lens, rho)
+        assert len(stages) == p + 1
+        for i, L in enumerate(lens):
+            seq = [j for st in stages for j in range(*st[i])]
+            assert seq == list(range(L))         # order kept, every operator exactly once
+
+
+def test_validate_rejects():
+    assert S.validate([5], [[3, 2]]) == "non-monotone"
+    assert S.validate([5], [[3, 6]]) == "beyond sequence"
+    assert S.validate([5, 5], [[1]]) == "row count"
+    assert S.validate([5], [[0, 0, 5, 5]]) is None
+
+
+def test_issue_order_bfs_dfs():
+    stage = [(0, 3), (0, 1), (0, 2)]
+    bfs = S.issue_order(stage, 3, "bfs")
+    assert [(s + 1, i + 1) for s, t, i in bfs] == [(1, 1), (2, 1), (3, 1), (1, 2), (3, 2), (1, 3)]
+    dfs = S.issue_order(stage, 3, "dfs")
+    assert [(s + 1, i + 1) for s, t, i in dfs] == [(1, 1), (1, 2), (1, 3), (2, 1), (3, 1), (3, 2)]
+    # per-stream order is the tenant's own order in both
+    for order in (bfs, dfs):
+        for t in range(3):
+            assert [i for s, tt, i in order if tt == t] == list(range(*stage[t]))
+
+
+def test_concurrency_multiplexing():
+    stage = [(0, 2), (0, 0), (1, 3), (0, 1)]
+    seq = S.issue_order(stage, 1, "bfs")       # sequential: one stream, tenants in order
+    assert seq == [(0, 0, 0), (0, 0, 1), (0, 2, 1), (0, 2, 2), (0, 3, 0)]
+    two = S.issue_order(stage, 2, "bfs")       # active tenants 0,2,3 -> streams 0,2,0
+    assert S.stream_map(stage, 2) == {0: 0, 2: 2, 3: 0}
+    assert two == [(0, 0, 0), (2, 2, 1), (0, 0, 1), (2, 2, 2), (0, 3, 0)]
+    assert S.stream_map(stage, 9) == {0: 0, 2: 2, 3: 3}
+
+
+def test_counter_rng_reference_values():
+    # splitmix64's published first outputs for seed 0 pin the mixing function
+    assert S.mix64(0) == 0xE220A8397B1DCDAF
+    assert S.mix64(0x9E3779B97F4A7C15) == 0x6E789E6AA1B965F4
+    assert S.draw(1, 2, 3, 4, 5) == S.mix64(S.mix64(S.mix64(S.mix64(S.mix64(1) ^ 2) ^ 3) ^ 4) ^ 5)
+
+
+def test_coordinate_descent_control_flow():
+    lens = [12, 7, 20]
+    P, R, M = 2, 4, 5
+    target = [[4, 9], [2, 5], [10, 15]]
+    calls = []
+
+    def cost(rho):
+        calls.append([list(r) for r in rho])
+        return sum((a - b) ** 2 for r, t in zip(rho, target) for a, b in zip(r, t)) + 1.0
+
+    best, best_cost, rec = S.coordinate_descent(lens, P, R, M, cost, seed=11)
+    assert len(rec) == R * len(lens) * M == len(calls)
+    assert [r for r, _ in rec] == calls
+    assert best_cost == min(c for _, c in rec)
+    assert rec[[c for _, c in rec].index(best_cost)][0] == best       # earliest minimum
+    # row update: within a (round, model) group only row i varies, other rows equal the
+    # previous groups' argmin rows
+    cur = S.even_split(lens, P)
+    idx = 0
+    for r in range(R):
+        for i in range(len(lens)):
+            group = rec[idx: idx + M]
+            idx += M
+            for m, (rho, _) in enumerate(group):
+                for j in range(len(lens)):
+                    if j != i:
+                        assert rho[j] == cur[j]
+                assert rho[i] == S.sample_row(11, r, i, m, P, lens[i])
+                assert S.validate(lens, rho) is None
+            cur[i] = min(group, key=lambda g: g[1])[0][i]
+    # separable cost: descent improves on the even split
+    assert best_cost <= cost(S.even_split(lens, P))
+
+
+def test_random_search_filters_infeasible():
+    lens = [9, 9]
+    seen = []
+    best, c, rec, skipped = S.random_search(lens, 3, 200, lambda rho: seen.append(rho) or float(sum(map(sum, rho))), seed=3)
+    assert skipped > 0 and len(rec) + skipped == 200
+    assert all(S.validate(lens, r) is None for r, _ in rec)
+    assert c == min(x for _, x in rec)
+
+
+def test_even_split():
+    assert S.even_split([10, 3], 1) == [[5], [2]]
+    assert S.even_split([8], 3) == [[2, 4, 6]]
