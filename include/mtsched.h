@@ -1,0 +1,245 @@
+/*
+ * mtsched - staged, multi-stream forward pass of several CNN tenants on one MI355X.
+ *
+ * C ABI of the library.  The calls follow the problem statement of
+ * "Automated Runtime-Aware Scheduling for Multi-Tenant DNN Inference on GPU"
+ * (arXiv 2111.14255), Sec. III: N independent models, each a serial operator
+ * sequence (Eq. 1) bound to its own GPU stream (Eq. 2); per-model pointers
+ * (Eq. 3) split the sequences into stages (Eqs. 4-5) separated by
+ * synchronisation barriers; the list of stages is the schedule (Eq. 6); a
+ * profile-driven search over the pointer matrix (Eq. 8, Alg. 1) picks the
+ * schedule with the lowest makespan (Sec. III-A: earliest start to latest end).
+ *
+ * Conventions
+ *  - Every call returns an int32_t status: MT_OK (0) or a negative mt_status.
+ *    After a failure mt_last_error() returns a description (thread-local).
+ *  - Handles are opaque and owned by the library; destroy them with the
+ *    matching *_destroy call.  Passing NULL where a handle is required is
+ *    MT_ERR_INVALID_ARG.
+ *  - "host" pointers are ordinary CPU memory, borrowed for the duration of the
+ *    call and copied if needed.  "device" pointers are HIP device memory of
+ *    the context's GPU, borrowed and never freed by the library.
+ *  - Activations are NHWC.  Convolution weights are K-R-S-C (output channel,
+ *    filter row, filter column, input channel); depthwise weights are C-R-S;
+ *    fully-connected weights are K-J with J = H*W*C of the input flattened in
+ *    H,W,C order.  Weights are given in the model's storage type, bias in fp32.
+ *  - Arithmetic: products of storage-type values accumulated in fp32; bias,
+ *    residual and activation applied in fp32; one round-to-nearest-even to the
+ *    storage type on store.  The result of an operator does not depend on the
+ *    schedule, stream, CU share or co-running operators: outputs are
+ *    bit-identical across all schedules of the same tenants.
+ *  - One context is used from one host thread at a time (the paper issues all
+ *    operators from a single main thread, Sec. III-D).
+ */
+#ifndef MTSCHED_H
+#define MTSCHED_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MT_MAX_TENANTS 16
+#define MT_MAX_STAGES 16
+
+typedef struct mt_ctx mt_ctx;
+typedef struct mt_model mt_model;
+typedef struct mt_schedule mt_schedule;
+
+typedef enum mt_status {
+    MT_OK = 0,
+    MT_ERR_INVALID_ARG = -1,
+    MT_ERR_INVALID_SCHEDULE = -2,
+    MT_ERR_SHAPE_MISMATCH = -3,
+    MT_ERR_OUT_OF_MEMORY = -4,
+    MT_ERR_HIP = -5,
+    MT_ERR_NOT_FINALIZED = -6
+} mt_status;
+
+typedef enum mt_dtype { MT_F32 = 0, MT_F16 = 1, MT_BF16 = 2 } mt_dtype;
+
+/* Operator kinds named by the paper's problem statement (Sec. III-A: conv, bn, relu, pooling);
+ * bn is folded into the preceding convolution's weights and relu is an epilogue flag. */
+typedef enum mt_op_kind {
+    MT_CONV = 0,
+    MT_DWCONV = 1,
+    MT_MAXPOOL = 2,
+    MT_AVGPOOL = 3,          /* divisor = number of in-bounds taps */
+    MT_GLOBAL_AVGPOOL = 4,
+    MT_FC = 5
+} mt_op_kind;
+
+typedef enum mt_act { MT_ACT_NONE = 0, MT_ACT_RELU = 1, MT_ACT_RELU6 = 2 } mt_act;
+
+typedef enum mt_issue_order { MT_ISSUE_BFS = 0, MT_ISSUE_DFS = 1 } mt_issue_order;
+
+/* One operator of a model's serial sequence (Sec. III-B, Eq. 1).
+ * Tensors are named by integers; tensor 0 is the model input.  out = floor((in + 2*pad - k)/stride) + 1. */
+typedef struct mt_op_desc {
+    int32_t kind;          /* mt_op_kind */
+    int32_t in_tensor;     /* must have been written by an earlier operator (or be 0) */
+    int32_t res_tensor;    /* CONV only: tensor added before the activation, -1 = none */
+    int32_t out_tensor;    /* >= 1 */
+    int32_t out_c;         /* CONV / FC: output channels; ignored otherwise */
+    int32_t out_c_offset;  /* first channel written inside out_tensor (channel concatenation without a copy) */
+    int32_t out_c_total;   /* channel count of out_tensor; 0 = exactly the channels written */
+    int32_t r, s;          /* window (CONV, DWCONV, pools); ignored for GLOBAL_AVGPOOL and FC */
+    int32_t stride_h, stride_w;
+    int32_t pad_h, pad_w;  /* symmetric per axis; max-pool padding is never selected */
+    int32_t act;           /* mt_act; CONV, DWCONV, FC */
+} mt_op_desc;
+
+/* What the library derived for one operator; lets a harness compute roofline figures
+ * from the library's own view of the graph. */
+typedef struct mt_op_info {
+    int32_t kind;
+    int32_t in_h, in_w, in_c;
+    int32_t out_h, out_w, out_c;     /* channels written */
+    int32_t kernel_id;               /* which device kernel family and tile runs it (see mt_kernel_name) */
+    int32_t split_k;                 /* K-splits of the implicit GEMM (1 = none) */
+    int32_t grid_blocks;             /* workgroups launched */
+    double flops;                    /* 2 * multiply-accumulates, whole batch */
+    double bytes;                    /* algorithmic traffic: inputs + weights + bias (+ residual) read once, output written once */
+} mt_op_info;
+
+typedef struct mt_device_info {
+    int32_t cu_count;
+    int32_t wavefront_size;
+    int32_t lds_bytes_per_block;
+    int32_t clock_khz;
+    int64_t l2_bytes;
+    int64_t hbm_bytes;
+    char name[64];
+    char arch[64];
+} mt_device_info;
+
+/* Timings of one mt_run, from HIP events recorded on the device.
+ * makespan_ms: from the event recorded before the first operator of any tenant may start to the
+ * event recorded after the last operator of every tenant has finished (Sec. III-A objective).
+ * stage_ms[s]: from the previous barrier (or the start) to the barrier that ends stage s.
+ * host_issue_ms: wall time the issuing thread spent launching (Sec. III-D "invoking overhead"). */
+typedef struct mt_timings {
+    float makespan_ms;
+    float host_issue_ms;
+    int32_t n_launches;
+    int32_t n_stages;
+    float stage_ms[MT_MAX_STAGES];
+} mt_timings;
+
+/* ---- error reporting ---------------------------------------------------------------- */
+const char *mt_last_error(void);
+const char *mt_kernel_name(int32_t kernel_id);
+
+/* ---- context ------------------------------------------------------------------------ */
+/* Binds to HIP device `device`, creates the main stream and timing events. */
+int32_t mt_create(int32_t device, mt_ctx **out);
+int32_t mt_destroy(mt_ctx *ctx);
+int32_t mt_get_device_info(const mt_ctx *ctx, mt_device_info *out);
+
+/* ---- model construction (host only; no GPU needed) ----------------------------------- */
+/* Operators are added in the serial order that becomes the model's sequence M_i (Eq. 1). */
+int32_t mt_model_begin(int32_t dtype, int32_t batch, int32_t in_h, int32_t in_w, int32_t in_c, mt_model **out);
+int32_t mt_model_add_op(mt_model *m, const mt_op_desc *desc, int32_t *out_op_index);
+/* Shape inference and validation: every input produced earlier, window fits, channel ranges agree. */
+int32_t mt_model_end(mt_model *m);
+int32_t mt_model_destroy(mt_model *m);
+int32_t mt_model_num_ops(const mt_model *m, int32_t *out);
+int32_t mt_model_op_info(const mt_model *m, int32_t op_index, mt_op_info *out);
+int32_t mt_model_out_features(const mt_model *m, int64_t *out);
+/* w: host, storage type, layout as above, exactly w_bytes bytes; bias: host fp32 [n_bias] or NULL (zeros). */
+int32_t mt_model_set_weights(mt_model *m, int32_t op_index, const void *w, size_t w_bytes,
+                             const float *bias, size_t n_bias);
+/* Bytes of device memory a registered copy of the model needs (weights, activations, workspaces). */
+int32_t mt_model_arena_bytes(const mt_model *m, size_t *out);
+
+/* Batch-norm folding helper (graph-level fusion, Sec. II-A(b)); fp32, in place.
+ * w: host [k][per_k]; gamma/beta/mean/var: host [k]; bias_out: host [k].
+ * w[k][:] *= gamma[k]/sqrt(var[k]+eps);  bias_out[k] = beta[k] - mean[k]*gamma[k]/sqrt(var[k]+eps). */
+int32_t mt_fold_bn(float *w, int64_t k, int64_t per_k, const float *gamma, const float *beta,
+                   const float *mean, const float *var, float eps, float *bias_out);
+
+/* ---- registration -------------------------------------------------------------------- */
+/* Uploads a finalised model with all weights set and makes it tenant `*out_tenant` (0, 1, ...)
+ * of the context.  device_arena: device memory of at least mt_model_arena_bytes() bytes, 256-byte
+ * aligned, borrowed until mt_destroy; NULL lets the library allocate.  The model handle may be
+ * destroyed afterwards. */
+int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t arena_bytes, int32_t *out_tenant);
+int32_t mt_num_tenants(const mt_ctx *ctx, int32_t *out);
+int32_t mt_tenant_num_ops(const mt_ctx *ctx, int32_t tenant, int32_t *out);
+int32_t mt_tenant_op_info(const mt_ctx *ctx, int32_t tenant, int32_t op_index, mt_op_info *out);
+/* Debug aid: copies tensor `tensor_id` of a tenant (as left by the last run) to host memory. */
+int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, void *host_dst, size_t bytes);
+
+/* ---- schedule (Sec. III-B) ----------------------------------------------------------- */
+/* pointers: host [n_tenants][n_stages-1], row i non-decreasing, 0 <= value <= length of M_i.  A pointer is
+ * the 1-based index of the last operator of a stage (Eq. 3); the last stage takes the remainder; equal
+ * neighbours give an empty slice (Eq. 5, "None").  n_tenants must equal the number of registered tenants.
+ * stage_concurrency: host [n_stages] or NULL (= n_tenants each).  In a stage with concurrency c the tenants
+ * that have work are ranked in tenant order and rank j is issued on the stream of rank j mod c; c = 1 runs
+ * them one after another on one stream (the sequential baseline), c >= active tenants is the paper's
+ * one-stream-per-model.
+ * cu_share: host [n_tenants] or NULL.  Number of compute units tenant i's stream may use; 0 = all.
+ * issue_order: MT_ISSUE_BFS issues one operator per stream round-robin (Sec. III-D), MT_ISSUE_DFS stream by stream.
+ * flags: MT_SCHED_GRAPH captures the whole schedule into a HIP graph on the first run and replays it
+ * afterwards (CU shares are ignored in that mode: graph nodes do not inherit stream CU masks). */
+#define MT_SCHED_GRAPH 1
+int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, const int32_t *pointers,
+                           const int32_t *stage_concurrency, const int32_t *cu_share,
+                           int32_t issue_order, int32_t flags, mt_schedule **out);
+int32_t mt_schedule_destroy(mt_schedule *s);
+
+/* Host-only views of the schedule generation function T(G, rho) (Eq. 8) and of the launch order (Sec. III-D).
+ * lens: host [n_tenants] sequence lengths.  slices_out: host [n_stages][n_tenants][2], 0-based half-open. */
+int32_t mt_expand_pointers(int32_t n_tenants, const int32_t *lens, int32_t n_stages, const int32_t *pointers,
+                           int32_t *slices_out);
+/* slices: host [n_tenants][2] of one stage.  order_out: host [sum of slice lengths][3] = (stream, tenant, op). */
+int32_t mt_issue_order_of_stage(int32_t n_tenants, const int32_t *slices, int32_t concurrency,
+                                int32_t issue_order, int32_t *order_out, int32_t *n_out);
+
+/* ---- run ----------------------------------------------------------------------------- */
+/* inputs: host array of n_tenants device pointers, tenant i's [batch,H,W,C] input in its storage type
+ * (may alias).  outputs: host array of n_tenants device pointers receiving the last operator's tensor.
+ * Blocks until every tenant has finished.  t may be NULL. */
+int32_t mt_run(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *const *outputs, mt_timings *t);
+
+/* Measurement aid: runs each operator of one tenant `repeats` times back to back on one stream between
+ * two events and reports the mean duration per launch.  op_ms: host [num ops]. */
+int32_t mt_profile_ops(mt_ctx *ctx, int32_t tenant, const void *input, void *output, int32_t repeats, float *op_ms);
+
+/* ---- search (Sec. III-C, Alg. 1) ------------------------------------------------------ */
+typedef enum mt_search_algo { MT_SEARCH_COORDINATE = 0, MT_SEARCH_RANDOM = 1 } mt_search_algo;
+
+typedef struct mt_search_opts {
+    int32_t algo;          /* mt_search_algo */
+    int32_t n_stages;      /* P + 1 */
+    int32_t rounds;        /* R.  Random search evaluates rounds * n_tenants * candidates matrices. */
+    int32_t candidates;    /* M candidate rows per (round, model) */
+    int32_t runs;          /* timed runs averaged per candidate ("profile the latency by multiple runs") */
+    int32_t warmup;        /* untimed runs per candidate */
+    int32_t issue_order;   /* mt_issue_order */
+    int32_t flags;         /* schedule flags used while profiling */
+    uint64_t seed;
+} mt_search_opts;
+
+/* cost callback: pointers is host [n_tenants][n_stages-1]; returns the latency to minimise. */
+typedef double (*mt_cost_fn)(const int32_t *pointers, void *user);
+
+/* The search itself, on any cost function (host only).  Candidate rows are n_stages-1 draws, uniform on
+ * [0, len_i], sorted; draws come from a counter-based generator keyed by (seed, round, model, candidate, j).
+ * best_pointers: host [n_tenants][n_stages-1].  rec_pointers / rec_cost: optional host buffers for the record
+ * memory D (every evaluated matrix and its cost, in evaluation order), capacity max_records. */
+int32_t mt_search_pointers(int32_t n_tenants, const int32_t *lens, const mt_search_opts *opts,
+                           mt_cost_fn cost, void *user, int32_t *best_pointers, double *best_cost,
+                           int32_t *rec_pointers, double *rec_cost, int32_t max_records, int32_t *n_records);
+
+/* The same search with the profiled makespan of mt_run as cost, all tenants on their own stream. */
+int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *inputs, void *const *outputs,
+                  int32_t *best_pointers, double *best_cost,
+                  int32_t *rec_pointers, double *rec_cost, int32_t max_records, int32_t *n_records);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MTSCHED_H */

@@ -1,0 +1,56 @@
+// Storage types and conversions used by every kernel (device side).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mt {
+
+typedef _Float16 f16;
+struct bf16 {
+    uint16_t v;
+};
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(f16 v) { return (float)v; }
+__device__ __forceinline__ float to_f32(bf16 v) { return __uint_as_float(((uint32_t)v.v) << 16); }
+
+__device__ __forceinline__ void from_f32(float f, float &o) { o = f; }
+__device__ __forceinline__ void from_f32(float f, f16 &o) { o = (f16)f; }   // v_cvt_f16_f32: nearest even
+__device__ __forceinline__ void from_f32(float f, bf16 &o) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) {
+        o.v = (uint16_t)((u >> 16) | 0x0040u);   // quiet NaN
+    } else {
+        u += 0x7fffu + ((u >> 16) & 1u);          // nearest even; carries into the exponent, up to infinity
+        o.v = (uint16_t)(u >> 16);
+    }
+}
+
+__device__ __forceinline__ float apply_act(float v, int act) {
+    if (act == MT_ACT_RELU) return v > 0.f ? v : 0.f;
+    if (act == MT_ACT_RELU6) return v < 0.f ? 0.f : (v > 6.f ? 6.f : v);
+    return v;
+}
+
+// V consecutive elements of T moved as one access when V*sizeof(T) is 4, 8 or 16 bytes.
+template <typename T, int V>
+struct alignas(sizeof(T) * V) Pack {
+    T e[V];
+};
+
+template <typename T, int V>
+__device__ __forceinline__ void load_pack(const T *p, float (&out)[V]) {
+    Pack<T, V> t = *reinterpret_cast<const Pack<T, V> *>(p);
+#pragma unroll
+    for (int i = 0; i < V; ++i) out[i] = to_f32(t.e[i]);
+}
+
+template <typename T, int V>
+__device__ __forceinline__ void store_pack(T *p, const float (&in)[V]) {
+    Pack<T, V> t;
+#pragma unroll
+    for (int i = 0; i < V; ++i) from_f32(in[i], t.e[i]);
+    *reinterpret_cast<Pack<T, V> *>(p) = t;
+}
+
+}  // namespace mt

@@ -1,0 +1,76 @@
+// Internal declarations shared by the host runtime and the kernel launchers.
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/mtsched.h"
+
+namespace mt {
+
+// ---- error plumbing -------------------------------------------------------------------
+int32_t fail(int32_t code, const std::string &msg);
+
+// ---- scheduling layer (host only) ------------------------------------------------------
+struct IssueItem {
+    int32_t stream, tenant, op;
+};
+int32_t validate_pointers(int32_t n_tenants, const int32_t *lens, int32_t n_stages, const int32_t *pointers);
+void expand_pointers(int32_t n_tenants, const int32_t *lens, int32_t n_stages, const int32_t *pointers, int32_t *slices);
+void stream_map(int32_t n_tenants, const int32_t *slices, int32_t concurrency, int32_t *host_stream);
+std::vector<IssueItem> issue_order(int32_t n_tenants, const int32_t *slices, int32_t concurrency, int32_t order);
+int32_t search_pointers(int32_t n_tenants, const int32_t *lens, const mt_search_opts *o, mt_cost_fn cost, void *user,
+                        int32_t *best_pointers, double *best_cost, int32_t *rec_pointers, double *rec_cost,
+                        int32_t max_records, int32_t *n_records);
+
+// ---- kernel families -------------------------------------------------------------------
+// The kernel and tile of an operator are a pure function of its shape and storage type, never of the
+// stream, CU share or stage it runs in; that is what makes outputs bit-identical across schedules.
+enum KernelId : int32_t {
+    K_CONV_DIRECT = 0,      // one thread per output element, any shape, any storage type
+    K_IGEMM_128x128 = 1,    // MFMA implicit GEMM, 128 output channels x 128 pixels per workgroup
+    K_IGEMM_64x64 = 2,      // MFMA implicit GEMM, 64 x 64
+    K_IGEMM_64x16 = 3,      // MFMA implicit GEMM, 64 output channels x 16 pixels (tiny-M layers, FC)
+    K_DWCONV = 4,
+    K_MAXPOOL = 5,
+    K_AVGPOOL = 6,
+    K_GAP = 7,
+    K_IGEMM_128x64 = 8,     // 128 output channels x 64 pixels
+    K_COUNT
+};
+
+// Everything a launcher needs for one operator.  Pointers are resolved per run (the first operator may
+// read the caller's input buffer, the last one writes the caller's output buffer).
+struct OpArgs {
+    int32_t kind, kernel_id, dtype;
+    int32_t N, H, W, C;          // input tensor
+    int32_t K, R, S;             // output channels written, window
+    int32_t P, Q;                // output spatial size
+    int32_t sh, sw, ph, pw;
+    int32_t act;
+    int32_t res_ct;              // channel count of the residual tensor (0 = no residual)
+    int32_t y_coff, y_ct;        // channel offset / channel count of the output tensor
+    int32_t vec;                 // channels per thread of the channel-wise kernels (1, 4 or 8)
+    // implicit GEMM
+    int32_t gemm_k;              // R*S*C
+    int32_t k_pad;               // packed weight row length (multiple of the k tile)
+    int32_t n_pad;               // packed weight rows (multiple of the channel tile)
+    int32_t split_k;
+    int32_t vec_a;               // 1: input channels are a multiple of 8 (16-byte im2col loads)
+    int32_t grid_x, grid_y, grid_z, block;
+    const void *x;
+    const void *w;
+    const float *bias;
+    const void *res;
+    void *y;
+    float *ws;                   // split-K partial sums
+    uint32_t *counters;          // split-K arrival counters, one per output tile, zero between launches
+};
+
+// Launchers (defined in the .hip files).  Return a hipError_t as int.
+int launch_direct(const OpArgs &a, void *stream);
+int launch_igemm(const OpArgs &a, void *stream);
+int launch_fill_u32(uint32_t *p, size_t n, uint32_t v, void *stream);
+
+}  // namespace mt

@@ -1,0 +1,297 @@
+// Channel-wise, bandwidth-bound operators (depthwise conv, pooling, global average pooling) and the
+// generic direct convolution used for fp32 storage.  Activations are NHWC, so consecutive lanes of a
+// wavefront touch consecutive channel vectors: every global access of a wave is one contiguous run.
+#include <hip/hip_runtime.h>
+
+#include "internal.h"
+#include "device_types.h"
+
+namespace mt {
+
+// ---------------------------------------------------------------------------------------------
+// Direct convolution / fully connected: one thread per output element, output channel fastest.
+// Sum order is fixed (r, s, c), so the result does not depend on the launch environment.
+template <typename T>
+__global__ void __launch_bounds__(256) conv_direct_kernel(OpArgs a) {
+    const int64_t total = (int64_t)a.N * a.P * a.Q * a.K;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= total) return;
+    const int k = (int)(gid % a.K);
+    int64_t m = gid / a.K;
+    const int q = (int)(m % a.Q);
+    const int p = (int)((m / a.Q) % a.P);
+    const int n = (int)(m / ((int64_t)a.Q * a.P));
+    const T *x = (const T *)a.x;
+    const T *w = (const T *)a.w + (int64_t)k * a.R * a.S * a.C;
+    float acc = 0.f;
+    for (int r = 0; r < a.R; ++r) {
+        const int ih = p * a.sh - a.ph + r;
+        if (ih < 0 || ih >= a.H) continue;
+        for (int s = 0; s < a.S; ++s) {
+            const int iw = q * a.sw - a.pw + s;
+            if (iw < 0 || iw >= a.W) continue;
+            const T *xp = x + (((int64_t)n * a.H + ih) * a.W + iw) * a.C;
+            const T *wp = w + ((int64_t)r * a.S + s) * a.C;
+            for (int c = 0; c < a.C; ++c) acc = fmaf(to_f32(xp[c]), to_f32(wp[c]), acc);
+        }
+    }
+    if (a.bias) acc += a.bias[k];
+    if (a.res) acc += to_f32(((const T *)a.res)[m * a.res_ct + k]);
+    acc = apply_act(acc, a.act);
+    T o;
+    from_f32(acc, o);
+    ((T *)a.y)[m * a.y_ct + a.y_coff + k] = o;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Depthwise convolution.  One thread per (pixel, V-channel vector); weights repacked as [R][S][C] so
+// that the weight vector of a tap is one contiguous load, shared by every pixel through the caches.
+// For stride 1 the lanes that hold the left and right neighbour pixels of the same channel vector sit
+// CV lanes away in the wave: the three taps of a filter row are obtained by loading only the centre
+// column and exchanging it with the neighbours through wavefront shuffles; lanes at a wave or image-row
+// edge fall back to a load.
+template <typename T, int V, bool SHUFFLE>
+__global__ void __launch_bounds__(256) dwconv_kernel(OpArgs a) {
+    const int CV = a.C / V;
+    const int64_t total = (int64_t)a.N * a.P * a.Q * CV;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool live = gid < total;
+    const int64_t g = live ? gid : total - 1;   // dead lanes shadow a real element so shuffles stay defined
+    const int cv = (int)(g % CV);
+    int64_t m = g / CV;
+    const int q = (int)(m % a.Q);
+    const int p = (int)((m / a.Q) % a.P);
+    const int n = (int)(m / ((int64_t)a.Q * a.P));
+    const int c0 = cv * V;
+    const T *x = (const T *)a.x;
+    const T *w = (const T *)a.w;
+    float acc[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc[i] = 0.f;
+
+    if constexpr (SHUFFLE) {
+        // stride 1, S == 3, pad_w == 1: column of tap s is q - 1 + s.
+        const int lane = threadIdx.x & 63;
+        const int src_l = lane - CV, src_r = lane + CV;
+        // The neighbour lane holds pixel q-1 / q+1 of the same image row iff it is inside the wave and this
+        // pixel is not at the row edge (gid is linear in (n,p,q,cv), so +-CV lanes is +-1 pixel).
+        const bool l_ok = src_l >= 0 && q > 0;
+        const bool r_ok = src_r < 64 && q + 1 < a.Q && (gid + CV) < total;
+        for (int r = 0; r < a.R; ++r) {
+            const int ih = p - a.ph + r;
+            const bool row_ok = ih >= 0 && ih < a.H;
+            const T *xrow = x + (((int64_t)n * a.H + (row_ok ? ih : 0)) * a.W) * a.C + c0;
+            float ctr[V], lft[V], rgt[V];
+#pragma unroll
+            for (int i = 0; i < V; ++i) ctr[i] = 0.f;
+            if (row_ok) load_pack<T, V>(xrow + (int64_t)q * a.C, ctr);
+#pragma unroll
+            for (int i = 0; i < V; ++i) {
+                lft[i] = __shfl(ctr[i], src_l & 63);
+                rgt[i] = __shfl(ctr[i], src_r & 63);
+            }
+            if (!l_ok) {
+#pragma unroll
+                for (int i = 0; i < V; ++i) lft[i] = 0.f;
+                if (row_ok && q > 0) load_pack<T, V>(xrow + (int64_t)(q - 1) * a.C, lft);
+            }
+            if (!r_ok) {
+#pragma unroll
+                for (int i = 0; i < V; ++i) rgt[i] = 0.f;
+                if (row_ok && q + 1 < a.W) load_pack<T, V>(xrow + (int64_t)(q + 1) * a.C, rgt);
+            }
+            float w0[V], w1[V], w2[V];
+            load_pack<T, V>(w + ((int64_t)r * 3 + 0) * a.C + c0, w0);
+            load_pack<T, V>(w + ((int64_t)r * 3 + 1) * a.C + c0, w1);
+            load_pack<T, V>(w + ((int64_t)r * 3 + 2) * a.C + c0, w2);
+#pragma unroll
+            for (int i = 0; i < V; ++i) {
+                acc[i] = fmaf(lft[i], w0[i], acc[i]);
+                acc[i] = fmaf(ctr[i], w1[i], acc[i]);
+                acc[i] = fmaf(rgt[i], w2[i], acc[i]);
+            }
+        }
+    } else {
+        for (int r = 0; r < a.R; ++r) {
+            const int ih = p * a.sh - a.ph + r;
+            if (ih < 0 || ih >= a.H) continue;
+            for (int s = 0; s < a.S; ++s) {
+                const int iw = q * a.sw - a.pw + s;
+                if (iw < 0 || iw >= a.W) continue;
+                float xv[V], wv[V];
+                load_pack<T, V>(x + (((int64_t)n * a.H + ih) * a.W + iw) * a.C + c0, xv);
+                load_pack<T, V>(w + ((int64_t)r * a.S + s) * a.C + c0, wv);
+#pragma unroll
+                for (int i = 0; i < V; ++i) acc[i] = fmaf(xv[i], wv[i], acc[i]);
+            }
+        }
+    }
+    if (!live) return;
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        if (a.bias) acc[i] += a.bias[c0 + i];
+        acc[i] = apply_act(acc[i], a.act);
+    }
+    store_pack<T, V>((T *)a.y + m * a.y_ct + a.y_coff + c0, acc);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Window pooling: one thread per (output pixel, V-channel vector).
+template <typename T, int V, bool IS_MAX>
+__global__ void __launch_bounds__(256) pool_kernel(OpArgs a) {
+    const int CV = a.C / V;
+    const int64_t total = (int64_t)a.N * a.P * a.Q * CV;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= total) return;
+    const int cv = (int)(gid % CV);
+    int64_t m = gid / CV;
+    const int q = (int)(m % a.Q);
+    const int p = (int)((m / a.Q) % a.P);
+    const int n = (int)(m / ((int64_t)a.Q * a.P));
+    const int c0 = cv * V;
+    const T *x = (const T *)a.x;
+    float acc[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc[i] = IS_MAX ? -INFINITY : 0.f;
+    int cnt = 0;
+    for (int r = 0; r < a.R; ++r) {
+        const int ih = p * a.sh - a.ph + r;
+        if (ih < 0 || ih >= a.H) continue;
+        for (int s = 0; s < a.S; ++s) {
+            const int iw = q * a.sw - a.pw + s;
+            if (iw < 0 || iw >= a.W) continue;
+            float xv[V];
+            load_pack<T, V>(x + (((int64_t)n * a.H + ih) * a.W + iw) * a.C + c0, xv);
+#pragma unroll
+            for (int i = 0; i < V; ++i) acc[i] = IS_MAX ? fmaxf(acc[i], xv[i]) : acc[i] + xv[i];
+            ++cnt;
+        }
+    }
+    if (!IS_MAX) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] = acc[i] / (float)cnt;
+    }
+    store_pack<T, V>((T *)a.y + m * a.y_ct + a.y_coff + c0, acc);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Global average pooling.  A wavefront owns one (image, group of channel vectors): its 64 lanes are
+// arranged as LANES_HW spatial slices x LANES_C channel vectors; each lane sums its slice in order and
+// the slices are combined by a fixed butterfly of wavefront shuffles, so the sum order is fixed.
+template <typename T, int V>
+__global__ void __launch_bounds__(256) gap_kernel(OpArgs a, int lanes_c) {
+    const int CV = a.C / V;
+    const int lanes_hw = 64 / lanes_c;
+    const int groups = (CV + lanes_c - 1) / lanes_c;            // wave tasks per image
+    const int wave = (int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+    const int lane = threadIdx.x & 63;
+    if (wave >= a.N * groups) return;                            // whole wave exits together
+    const int n = wave / groups;
+    const int cv = (wave % groups) * lanes_c + (lane % lanes_c);
+    const int slice = lane / lanes_c;
+    const int HW = a.H * a.W;
+    const bool cv_ok = cv < CV;
+    const T *x = (const T *)a.x + (int64_t)n * HW * a.C + (cv_ok ? cv : 0) * V;
+    float acc[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc[i] = 0.f;
+    for (int i = slice; i < HW; i += lanes_hw) {
+        float xv[V];
+        load_pack<T, V>(x + (int64_t)i * a.C, xv);
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc[j] += xv[j];
+    }
+    for (int off = 32; off >= lanes_c; off >>= 1) {
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc[j] += __shfl_xor(acc[j], off);
+    }
+    if (slice == 0 && cv_ok) {
+#pragma unroll
+        for (int j = 0; j < V; ++j) acc[j] = acc[j] / (float)HW;
+        store_pack<T, V>((T *)a.y + (int64_t)n * a.y_ct + a.y_coff + cv * V, acc);
+    }
+}
+
+__global__ void fill_u32_kernel(uint32_t *p, size_t n, uint32_t v) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+static int launch_typed(const OpArgs &a, hipStream_t st) {
+    const dim3 block(256);
+    auto blocks = [](int64_t threads) { return dim3((unsigned)((threads + 255) / 256)); };
+    constexpr int VMAX = 16 / sizeof(T);          // 16-byte accesses
+    switch (a.kernel_id) {
+        case K_CONV_DIRECT:
+            hipLaunchKernelGGL(conv_direct_kernel<T>, blocks((int64_t)a.N * a.P * a.Q * a.K), block, 0, st, a);
+            break;
+        case K_DWCONV: {
+            const bool shuffle = a.sh == 1 && a.sw == 1 && a.S == 3 && a.pw == 1 && a.vec == VMAX &&
+                                 (a.C / VMAX) < 64 && 64 % (a.C / VMAX) == 0;
+            if (a.vec == VMAX) {
+                const int64_t th = (int64_t)a.N * a.P * a.Q * (a.C / VMAX);
+                if (shuffle)
+                    hipLaunchKernelGGL((dwconv_kernel<T, VMAX, true>), blocks(th), block, 0, st, a);
+                else
+                    hipLaunchKernelGGL((dwconv_kernel<T, VMAX, false>), blocks(th), block, 0, st, a);
+            } else {
+                hipLaunchKernelGGL((dwconv_kernel<T, 1, false>), blocks((int64_t)a.N * a.P * a.Q * a.C), block, 0, st, a);
+            }
+            break;
+        }
+        case K_MAXPOOL:
+        case K_AVGPOOL: {
+            const bool mx = a.kernel_id == K_MAXPOOL;
+            if (a.vec == VMAX) {
+                const int64_t th = (int64_t)a.N * a.P * a.Q * (a.C / VMAX);
+                if (mx)
+                    hipLaunchKernelGGL((pool_kernel<T, VMAX, true>), blocks(th), block, 0, st, a);
+                else
+                    hipLaunchKernelGGL((pool_kernel<T, VMAX, false>), blocks(th), block, 0, st, a);
+            } else {
+                const int64_t th = (int64_t)a.N * a.P * a.Q * a.C;
+                if (mx)
+                    hipLaunchKernelGGL((pool_kernel<T, 1, true>), blocks(th), block, 0, st, a);
+                else
+                    hipLaunchKernelGGL((pool_kernel<T, 1, false>), blocks(th), block, 0, st, a);
+            }
+            break;
+        }
+        case K_GAP: {
+            const int V = a.vec == VMAX ? VMAX : 1;
+            const int CV = a.C / V;
+            int lanes_c = 1;
+            while (lanes_c < 16 && lanes_c < CV) lanes_c <<= 1;    // at least 4 spatial slices per wave
+            const int groups = (CV + lanes_c - 1) / lanes_c;
+            const int64_t th = (int64_t)a.N * groups * 64;
+            if (V == VMAX)
+                hipLaunchKernelGGL((gap_kernel<T, VMAX>), blocks(th), block, 0, st, a, lanes_c);
+            else
+                hipLaunchKernelGGL((gap_kernel<T, 1>), blocks(th), block, 0, st, a, lanes_c);
+            break;
+        }
+        default:
+            return (int)hipErrorInvalidValue;
+    }
+    return (int)hipGetLastError();
+}
+
+int launch_direct(const OpArgs &a, void *stream) {
+    hipStream_t st = (hipStream_t)stream;
+    switch (a.dtype) {
+        case MT_F32: return launch_typed<float>(a, st);
+        case MT_F16: return launch_typed<f16>(a, st);
+        case MT_BF16: return launch_typed<bf16>(a, st);
+    }
+    return (int)hipErrorInvalidValue;
+}
+
+int launch_fill_u32(uint32_t *p, size_t n, uint32_t v, void *stream) {
+    if (n == 0) return 0;
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, p, n, v);
+    return (int)hipGetLastError();
+}
+
+}  // namespace mt

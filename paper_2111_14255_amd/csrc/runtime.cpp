@@ -1,0 +1,820 @@
+// Host runtime: model construction and shape inference, kernel planning, registration (weight packing and
+// upload), schedule deployment on per-tenant HIP streams with event barriers, timing, profile-driven search.
+// Paper: Sec. III-A (problem), III-B (IR: stream, pointer, stage, schedule), III-C (search), III-D (issue order).
+#include <hip/hip_runtime_api.h>
+#include <hip/hip_ext.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cmath>
+#include <cstring>
+#include <map>
+#include <memory>
+
+#include "internal.h"
+
+using namespace mt;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t align_up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+inline int elt_size(int dtype) { return dtype == MT_F32 ? 4 : 2; }
+
+struct TensorInfo {
+    int h = 0, w = 0, c = 0;
+    bool defined = false;
+    size_t offset = 0, bytes = 0;
+};
+
+struct OpRec {
+    mt_op_desc d{};
+    int in_h = 0, in_w = 0, in_c = 0, out_h = 0, out_w = 0, out_c = 0;
+    OpArgs plan{};                 // shape part filled by mt_model_end
+    std::vector<uint8_t> w_host;   // raw weights as given
+    std::vector<float> bias_host;
+    bool has_weights = false;
+    size_t w_off = 0, w_bytes = 0, bias_off = 0, ws_off = 0, ws_bytes = 0, cnt_off = 0, cnt_bytes = 0;
+    double flops = 0, bytes = 0;
+};
+
+}  // namespace
+
+struct mt_model {
+    int dtype = 0, batch = 0, in_h = 0, in_w = 0, in_c = 0;
+    std::vector<OpRec> ops;
+    std::vector<TensorInfo> tensors;
+    bool finalized = false;
+    size_t arena_bytes = 0;
+    int final_tensor = -1;
+};
+
+namespace {
+
+bool needs_weights(int kind) { return kind == MT_CONV || kind == MT_DWCONV || kind == MT_FC; }
+
+// Tile and split choice of the implicit GEMM: a pure function of the GEMM shape.
+void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
+    auto cdiv = [](int a, int b) { return (a + b - 1) / b; };
+    int bn, bm, kid;
+    if (M <= 32) {
+        kid = K_IGEMM_64x16; bn = 64; bm = 16;
+    } else if (Kc >= 96 && cdiv(M, 128) * cdiv(Kc, 128) >= 512) {
+        kid = K_IGEMM_128x128; bn = 128; bm = 128;
+    } else if (Kc >= 96 && cdiv(M, 64) * cdiv(Kc, 128) >= 256) {
+        kid = K_IGEMM_128x64; bn = 128; bm = 64;
+    } else {
+        kid = K_IGEMM_64x64; bn = 64; bm = 64;
+    }
+    p.kernel_id = kid;
+    p.k_pad = cdiv(gemm_k, 32) * 32;
+    p.n_pad = cdiv(Kc, bn) * bn;
+    const int tiles = cdiv(M, bm) * (p.n_pad / bn);
+    const int nkt = p.k_pad / 32;
+    const int target = (kid == K_IGEMM_64x16) ? 2048 : 768;
+    int split = 1;
+    if (tiles < target / 2) {
+        split = std::min({cdiv(target, tiles), std::max(1, nkt / 4), 64});
+        const int per = cdiv(nkt, split);
+        split = cdiv(nkt, per);            // no empty split
+    }
+    p.split_k = std::max(1, split);
+    const int total = tiles * p.split_k;
+    p.grid_x = cdiv(total, 8) * 8;
+    p.grid_y = p.grid_z = 1;
+    p.block = 256;
+}
+
+int32_t finalize_model(mt_model *m) {
+    m->tensors.clear();
+    m->tensors.resize(1);
+    m->tensors[0].h = m->in_h; m->tensors[0].w = m->in_w; m->tensors[0].c = m->in_c; m->tensors[0].defined = true;
+    const int es = elt_size(m->dtype);
+    for (size_t i = 0; i < m->ops.size(); ++i) {
+        OpRec &o = m->ops[i];
+        const mt_op_desc &d = o.d;
+        auto bad = [&](const std::string &why) { return fail(MT_ERR_SHAPE_MISMATCH, "op " + std::to_string(i) + ": " + why); };
+        if (d.in_tensor < 0 || d.in_tensor >= (int)m->tensors.size() || !m->tensors[d.in_tensor].defined)
+            return bad("input tensor is not produced by an earlier operator");
+        if (d.out_tensor < 1) return bad("output tensor id must be >= 1");
+        if (d.out_tensor == d.in_tensor) return bad("in-place operators are not supported");
+        const TensorInfo in = m->tensors[d.in_tensor];
+        o.in_h = in.h; o.in_w = in.w; o.in_c = in.c;
+        int R = d.r, S = d.s, sh = d.stride_h, sw = d.stride_w, ph = d.pad_h, pw = d.pad_w;
+        if (d.kind == MT_GLOBAL_AVGPOOL || d.kind == MT_FC) { R = in.h; S = in.w; sh = sw = 1; ph = pw = 0; }
+        if (R < 1 || S < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0) return bad("bad window / stride / padding");
+        if (ph >= R || pw >= S) return bad("padding must be smaller than the window");
+        if (in.h + 2 * ph < R || in.w + 2 * pw < S) return bad("window larger than the padded input");
+        o.out_h = (in.h + 2 * ph - R) / sh + 1;
+        o.out_w = (in.w + 2 * pw - S) / sw + 1;
+        o.out_c = (d.kind == MT_CONV || d.kind == MT_FC) ? d.out_c : in.c;
+        if (o.out_c < 1) return bad("output channels must be >= 1");
+        if (d.act < MT_ACT_NONE || d.act > MT_ACT_RELU6) return bad("unknown activation");
+        const int ctot = d.out_c_total ? d.out_c_total : o.out_c;
+        if (d.out_c_offset < 0 || d.out_c_offset + o.out_c > ctot) return bad("channel range exceeds the output tensor");
+        if ((int)m->tensors.size() <= d.out_tensor) m->tensors.resize(d.out_tensor + 1);
+        TensorInfo &out = m->tensors[d.out_tensor];
+        if (out.defined) {
+            if (out.h != o.out_h || out.w != o.out_w || out.c != ctot) return bad("output tensor shape disagrees with an earlier writer");
+        } else {
+            out.h = o.out_h; out.w = o.out_w; out.c = ctot; out.defined = true;
+        }
+        int res_ct = 0;
+        if (d.res_tensor >= 0) {
+            if (d.kind != MT_CONV) return bad("residual is supported on CONV only");
+            if (d.res_tensor >= (int)m->tensors.size() || !m->tensors[d.res_tensor].defined || d.res_tensor == d.out_tensor)
+                return bad("residual tensor is not produced by an earlier operator");
+            const TensorInfo &rt = m->tensors[d.res_tensor];
+            if (rt.h != o.out_h || rt.w != o.out_w || rt.c < o.out_c) return bad("residual tensor shape mismatch");
+            res_ct = rt.c;
+        }
+        OpArgs &p = o.plan;
+        p = OpArgs{};
+        p.kind = d.kind; p.dtype = m->dtype;
+        p.N = m->batch; p.H = in.h; p.W = in.w; p.C = in.c;
+        p.K = o.out_c; p.R = R; p.S = S; p.P = o.out_h; p.Q = o.out_w;
+        p.sh = sh; p.sw = sw; p.ph = ph; p.pw = pw; p.act = d.act;
+        p.res_ct = res_ct; p.y_coff = d.out_c_offset; p.y_ct = ctot;
+        p.split_k = 1; p.block = 256; p.vec = 1;
+        const int vmax = 16 / es;
+        const double out_elems = (double)m->batch * o.out_h * o.out_w * o.out_c;
+        const double in_elems = (double)m->batch * in.h * in.w * in.c;
+        switch (d.kind) {
+            case MT_CONV:
+            case MT_FC: {
+                const int gemm_k = R * S * in.c;
+                p.gemm_k = gemm_k;
+                o.flops = 2.0 * out_elems * gemm_k;
+                o.bytes = (in_elems + out_elems + (double)o.out_c * gemm_k + (res_ct ? out_elems : 0)) * es + 4.0 * o.out_c;
+                if (m->dtype == MT_F32) {
+                    p.kernel_id = K_CONV_DIRECT;
+                } else {
+                    // a fully connected layer is a 1x1 convolution over a 1x1 map with H*W*C channels
+                    if (d.kind == MT_FC) { p.H = p.W = 1; p.C = gemm_k; p.R = p.S = 1; }
+                    p.vec_a = (p.C % 8 == 0) ? 1 : 0;
+                    plan_igemm(p, m->batch * o.out_h * o.out_w, o.out_c, gemm_k);
+                }
+                break;
+            }
+            case MT_DWCONV:
+                p.kernel_id = K_DWCONV;
+                p.vec = (in.c % vmax == 0 && ctot % vmax == 0 && d.out_c_offset % vmax == 0) ? vmax : 1;
+                o.flops = 2.0 * out_elems * R * S;
+                o.bytes = (in_elems + out_elems + (double)in.c * R * S) * es + 4.0 * in.c;
+                break;
+            case MT_MAXPOOL:
+            case MT_AVGPOOL:
+            case MT_GLOBAL_AVGPOOL:
+                p.kernel_id = d.kind == MT_MAXPOOL ? K_MAXPOOL : d.kind == MT_AVGPOOL ? K_AVGPOOL : K_GAP;
+                p.vec = (in.c % vmax == 0 && ctot % vmax == 0 && d.out_c_offset % vmax == 0) ? vmax : 1;
+                o.flops = 0;
+                o.bytes = (in_elems + out_elems) * es;
+                break;
+            default:
+                return bad("unknown operator kind");
+        }
+    }
+    if (m->ops.empty()) return fail(MT_ERR_SHAPE_MISMATCH, "model has no operators");
+    m->final_tensor = m->ops.back().d.out_tensor;
+
+    // ---- arena layout: weights, activations, split-K workspaces -----------------------------
+    size_t off = 0;
+    for (OpRec &o : m->ops) {
+        const OpArgs &p = o.plan;
+        if (needs_weights(p.kind)) {
+            bool igemm = p.kernel_id != K_CONV_DIRECT && (p.kind == MT_CONV || p.kind == MT_FC);
+            size_t wcount = igemm ? (size_t)p.n_pad * p.k_pad
+                                  : (p.kind == MT_DWCONV ? (size_t)p.C * p.R * p.S : (size_t)p.K * o.plan.R * o.plan.S * p.C);
+            if (p.kind == MT_FC && !igemm) wcount = (size_t)p.K * o.in_h * o.in_w * o.in_c;
+            o.w_off = off; o.w_bytes = wcount * es; off += align_up(o.w_bytes);
+            const size_t nb = igemm ? p.n_pad : p.K;
+            o.bias_off = off; off += align_up(nb * sizeof(float));
+        }
+        if (p.split_k > 1) {
+            const int bn = p.kernel_id == K_IGEMM_64x16 || p.kernel_id == K_IGEMM_64x64 ? 64 : 128;
+            const int bm = p.kernel_id == K_IGEMM_64x16 ? 16 : p.kernel_id == K_IGEMM_128x128 ? 128 : 64;
+            const int M = p.N * p.P * p.Q;
+            const size_t tiles = (size_t)((M + bm - 1) / bm) * (p.n_pad / bn);
+            o.ws_off = off; o.ws_bytes = tiles * p.split_k * bn * bm * sizeof(float); off += align_up(o.ws_bytes);
+            o.cnt_off = off; o.cnt_bytes = tiles * sizeof(uint32_t); off += align_up(o.cnt_bytes);
+        }
+    }
+    for (size_t t = 1; t < m->tensors.size(); ++t) {
+        TensorInfo &ti = m->tensors[t];
+        if (!ti.defined) continue;
+        ti.bytes = (size_t)m->batch * ti.h * ti.w * ti.c * es;
+        ti.offset = off;
+        off += align_up(ti.bytes + 16);
+    }
+    m->tensors[0].bytes = (size_t)m->batch * m->in_h * m->in_w * m->in_c * es;
+    m->arena_bytes = off;
+    m->finalized = true;
+    return MT_OK;
+}
+
+void fill_info(const mt_model *m, const OpRec &o, mt_op_info *out) {
+    out->kind = o.d.kind;
+    out->in_h = o.in_h; out->in_w = o.in_w; out->in_c = o.in_c;
+    out->out_h = o.out_h; out->out_w = o.out_w; out->out_c = o.out_c;
+    out->kernel_id = o.plan.kernel_id;
+    out->split_k = o.plan.split_k;
+    out->grid_blocks = o.plan.grid_x ? o.plan.grid_x : 0;
+    out->flops = o.flops;
+    out->bytes = o.bytes;
+    (void)m;
+}
+
+}  // namespace
+
+// ============================================================================================
+struct Tenant {
+    mt_model model;                 // private copy (host weights dropped after upload)
+    uint8_t *arena = nullptr;
+    bool owns_arena = false;
+    std::vector<OpArgs> args;       // device pointers resolved; input/output patched per run
+    std::vector<uint8_t> reads_input, res_input, writes_output;
+};
+
+struct StreamKey {
+    int tenant, share;
+    bool operator<(const StreamKey &o) const { return tenant != o.tenant ? tenant < o.tenant : share < o.share; }
+};
+
+struct mt_ctx {
+    int device = 0;
+    hipDeviceProp_t prop{};
+    std::vector<std::unique_ptr<Tenant>> tenants;
+    hipStream_t main_stream = nullptr;
+    std::map<StreamKey, hipStream_t> streams;
+    hipEvent_t ev_start = nullptr;
+    hipEvent_t ev_stage[MT_MAX_STAGES]{};
+    hipEvent_t ev_done[MT_MAX_STAGES][MT_MAX_TENANTS]{};
+    hipEvent_t ev_prof[2]{};
+};
+
+struct StagePlan {
+    std::vector<IssueItem> items;
+    std::vector<int> streams;       // distinct streams used, ascending
+};
+
+struct mt_schedule {
+    mt_ctx *ctx = nullptr;
+    int n_tenants = 0, n_stages = 0, flags = 0;
+    std::vector<StagePlan> stages;                 // non-empty stages only keep items; empty ones stay for timing
+    hipStream_t stream_of[MT_MAX_TENANTS]{};
+    int n_launches = 0;
+    // graph replay
+    hipGraphExec_t graph_exec = nullptr;
+    std::vector<const void *> cap_in;
+    std::vector<void *> cap_out;
+};
+
+namespace {
+
+#define HIP_TRY(expr)                                                                                     \
+    do {                                                                                                  \
+        hipError_t e_ = (expr);                                                                           \
+        if (e_ != hipSuccess) return fail(MT_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+    } while (0)
+
+int32_t launch_op(const OpArgs &a, hipStream_t st) {
+    int e;
+    switch (a.kernel_id) {
+        case K_IGEMM_128x128:
+        case K_IGEMM_128x64:
+        case K_IGEMM_64x64:
+        case K_IGEMM_64x16: e = launch_igemm(a, st); break;
+        default: e = launch_direct(a, st); break;
+    }
+    if (e != 0) return fail(MT_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString((hipError_t)e));
+    return MT_OK;
+}
+
+inline OpArgs patched(const Tenant &t, int op, const void *in, void *out) {
+    OpArgs a = t.args[op];
+    if (t.reads_input[op]) a.x = in;
+    if (t.res_input[op]) a.res = in;
+    if (t.writes_output[op]) a.y = out;
+    return a;
+}
+
+// Stream of a tenant restricted to `share` compute units (0 = all).  Tenant i's units start where the
+// shares of the tenants before it end, so disjoint shares give disjoint units.
+int32_t get_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t *out) {
+    StreamKey key{tenant, share == 0 ? 0 : (first_cu << 12) | share};
+    auto it = ctx->streams.find(key);
+    if (it != ctx->streams.end()) { *out = it->second; return MT_OK; }
+    hipStream_t s = nullptr;
+    if (share == 0) {
+        HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+    } else {
+        const int cus = ctx->prop.multiProcessorCount;
+        std::vector<uint32_t> mask((cus + 31) / 32, 0u);
+        for (int j = 0; j < share; ++j) {
+            const int cu = (first_cu + j) % cus;
+            mask[cu / 32] |= 1u << (cu % 32);
+        }
+        HIP_TRY(hipExtStreamCreateWithCUMask(&s, (uint32_t)mask.size(), mask.data()));
+    }
+    ctx->streams[key] = s;
+    *out = s;
+    return MT_OK;
+}
+
+// Issues the whole schedule on the tenant streams.  Barrier between stages: every stream of the stage
+// records an event, the main stream waits for all of them and records the stage event, and every stream of
+// the next stage waits for that.
+int32_t issue_schedule(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *const *outputs, int *n_launch) {
+    HIP_TRY(hipEventRecord(ctx->ev_start, ctx->main_stream));
+    hipEvent_t gate = ctx->ev_start;
+    int launches = 0;
+    for (int st = 0; st < s->n_stages; ++st) {
+        const StagePlan &sp = s->stages[st];
+        for (int sm : sp.streams) HIP_TRY(hipStreamWaitEvent(s->stream_of[sm], gate, 0));
+        for (const IssueItem &it : sp.items) {
+            const Tenant &t = *ctx->tenants[it.tenant];
+            OpArgs a = patched(t, it.op, inputs[it.tenant], outputs[it.tenant]);
+            int32_t rc = launch_op(a, s->stream_of[it.stream]);
+            if (rc != MT_OK) return rc;
+            ++launches;
+        }
+        for (int sm : sp.streams) {
+            HIP_TRY(hipEventRecord(ctx->ev_done[st][sm], s->stream_of[sm]));
+            HIP_TRY(hipStreamWaitEvent(ctx->main_stream, ctx->ev_done[st][sm], 0));
+        }
+        HIP_TRY(hipEventRecord(ctx->ev_stage[st], ctx->main_stream));
+        gate = ctx->ev_stage[st];
+    }
+    if (n_launch) *n_launch = launches;
+    return MT_OK;
+}
+
+}  // namespace
+
+// ============================================================================================
+extern "C" {
+
+const char *mt_kernel_name(int32_t id) {
+    switch (id) {
+        case K_CONV_DIRECT: return "conv_direct";
+        case K_IGEMM_128x128: return "igemm_128x128";
+        case K_IGEMM_128x64: return "igemm_128x64";
+        case K_IGEMM_64x64: return "igemm_64x64";
+        case K_IGEMM_64x16: return "igemm_64x16";
+        case K_DWCONV: return "dwconv";
+        case K_MAXPOOL: return "maxpool";
+        case K_AVGPOOL: return "avgpool";
+        case K_GAP: return "global_avgpool";
+    }
+    return "unknown";
+}
+
+int32_t mt_create(int32_t device, mt_ctx **out) {
+    if (!out) return fail(MT_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    int count = 0;
+    HIP_TRY(hipGetDeviceCount(&count));
+    if (device < 0 || device >= count) return fail(MT_ERR_INVALID_ARG, "no such device");
+    HIP_TRY(hipSetDevice(device));
+    std::unique_ptr<mt_ctx> c(new mt_ctx);
+    c->device = device;
+    HIP_TRY(hipGetDeviceProperties(&c->prop, device));
+    HIP_TRY(hipStreamCreateWithFlags(&c->main_stream, hipStreamNonBlocking));
+    HIP_TRY(hipEventCreate(&c->ev_start));
+    for (int s = 0; s < MT_MAX_STAGES; ++s) {
+        HIP_TRY(hipEventCreate(&c->ev_stage[s]));
+        for (int t = 0; t < MT_MAX_TENANTS; ++t) HIP_TRY(hipEventCreateWithFlags(&c->ev_done[s][t], hipEventDisableTiming));
+    }
+    HIP_TRY(hipEventCreate(&c->ev_prof[0]));
+    HIP_TRY(hipEventCreate(&c->ev_prof[1]));
+    *out = c.release();
+    return MT_OK;
+}
+
+int32_t mt_destroy(mt_ctx *ctx) {
+    if (!ctx) return fail(MT_ERR_INVALID_ARG, "ctx is NULL");
+    (void)hipSetDevice(ctx->device);
+    (void)hipDeviceSynchronize();
+    for (auto &kv : ctx->streams) (void)hipStreamDestroy(kv.second);
+    if (ctx->main_stream) (void)hipStreamDestroy(ctx->main_stream);
+    if (ctx->ev_start) (void)hipEventDestroy(ctx->ev_start);
+    for (int s = 0; s < MT_MAX_STAGES; ++s) {
+        if (ctx->ev_stage[s]) (void)hipEventDestroy(ctx->ev_stage[s]);
+        for (int t = 0; t < MT_MAX_TENANTS; ++t)
+            if (ctx->ev_done[s][t]) (void)hipEventDestroy(ctx->ev_done[s][t]);
+    }
+    for (auto e : ctx->ev_prof)
+        if (e) (void)hipEventDestroy(e);
+    for (auto &t : ctx->tenants)
+        if (t->owns_arena && t->arena) (void)hipFree(t->arena);
+    delete ctx;
+    return MT_OK;
+}
+
+int32_t mt_get_device_info(const mt_ctx *ctx, mt_device_info *out) {
+    if (!ctx || !out) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    std::memset(out, 0, sizeof(*out));
+    out->cu_count = ctx->prop.multiProcessorCount;
+    out->wavefront_size = ctx->prop.warpSize;
+    out->lds_bytes_per_block = (int32_t)ctx->prop.sharedMemPerBlock;
+    out->clock_khz = ctx->prop.clockRate;
+    out->l2_bytes = ctx->prop.l2CacheSize;
+    out->hbm_bytes = (int64_t)ctx->prop.totalGlobalMem;
+    std::strncpy(out->name, ctx->prop.name, sizeof(out->name) - 1);
+    std::strncpy(out->arch, ctx->prop.gcnArchName, sizeof(out->arch) - 1);
+    return MT_OK;
+}
+
+// ---- model ---------------------------------------------------------------------------------
+int32_t mt_model_begin(int32_t dtype, int32_t batch, int32_t in_h, int32_t in_w, int32_t in_c, mt_model **out) {
+    if (!out) return fail(MT_ERR_INVALID_ARG, "out is NULL");
+    *out = nullptr;
+    if (dtype < MT_F32 || dtype > MT_BF16) return fail(MT_ERR_INVALID_ARG, "unknown storage type");
+    if (batch < 1 || in_h < 1 || in_w < 1 || in_c < 1) return fail(MT_ERR_INVALID_ARG, "batch and input dimensions must be >= 1");
+    mt_model *m = new mt_model;
+    m->dtype = dtype; m->batch = batch; m->in_h = in_h; m->in_w = in_w; m->in_c = in_c;
+    *out = m;
+    return MT_OK;
+}
+
+int32_t mt_model_add_op(mt_model *m, const mt_op_desc *desc, int32_t *out_index) {
+    if (!m || !desc) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (m->finalized) return fail(MT_ERR_INVALID_ARG, "model is already finalised");
+    if (desc->kind < MT_CONV || desc->kind > MT_FC) return fail(MT_ERR_INVALID_ARG, "unknown operator kind");
+    OpRec o;
+    o.d = *desc;
+    m->ops.push_back(std::move(o));
+    if (out_index) *out_index = (int32_t)m->ops.size() - 1;
+    return MT_OK;
+}
+
+int32_t mt_model_end(mt_model *m) {
+    if (!m) return fail(MT_ERR_INVALID_ARG, "model is NULL");
+    if (m->finalized) return MT_OK;
+    return finalize_model(m);
+}
+
+int32_t mt_model_destroy(mt_model *m) {
+    if (!m) return fail(MT_ERR_INVALID_ARG, "model is NULL");
+    delete m;
+    return MT_OK;
+}
+
+int32_t mt_model_num_ops(const mt_model *m, int32_t *out) {
+    if (!m || !out) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    *out = (int32_t)m->ops.size();
+    return MT_OK;
+}
+
+int32_t mt_model_op_info(const mt_model *m, int32_t i, mt_op_info *out) {
+    if (!m || !out) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (!m->finalized) return fail(MT_ERR_NOT_FINALIZED, "model is not finalised");
+    if (i < 0 || i >= (int)m->ops.size()) return fail(MT_ERR_INVALID_ARG, "operator index out of range");
+    fill_info(m, m->ops[i], out);
+    return MT_OK;
+}
+
+int32_t mt_model_out_features(const mt_model *m, int64_t *out) {
+    if (!m || !out) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (!m->finalized) return fail(MT_ERR_NOT_FINALIZED, "model is not finalised");
+    const TensorInfo &t = m->tensors[m->final_tensor];
+    *out = (int64_t)t.h * t.w * t.c;
+    return MT_OK;
+}
+
+int32_t mt_model_set_weights(mt_model *m, int32_t i, const void *w, size_t w_bytes, const float *bias, size_t n_bias) {
+    if (!m || !w) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (!m->finalized) return fail(MT_ERR_NOT_FINALIZED, "call mt_model_end before setting weights");
+    if (i < 0 || i >= (int)m->ops.size()) return fail(MT_ERR_INVALID_ARG, "operator index out of range");
+    OpRec &o = m->ops[i];
+    if (!needs_weights(o.d.kind)) return fail(MT_ERR_INVALID_ARG, "operator has no weights");
+    const size_t es = elt_size(m->dtype);
+    size_t count;
+    if (o.d.kind == MT_DWCONV) count = (size_t)o.in_c * o.d.r * o.d.s;
+    else if (o.d.kind == MT_FC) count = (size_t)o.out_c * o.in_h * o.in_w * o.in_c;
+    else count = (size_t)o.out_c * o.d.r * o.d.s * o.in_c;
+    if (w_bytes != count * es) return fail(MT_ERR_SHAPE_MISMATCH, "weight size does not match the operator shape");
+    if (bias && n_bias != (size_t)o.out_c) return fail(MT_ERR_SHAPE_MISMATCH, "bias length does not match the output channels");
+    o.w_host.assign((const uint8_t *)w, (const uint8_t *)w + w_bytes);
+    o.bias_host.assign(o.out_c, 0.f);
+    if (bias) std::memcpy(o.bias_host.data(), bias, sizeof(float) * o.out_c);
+    o.has_weights = true;
+    return MT_OK;
+}
+
+int32_t mt_model_arena_bytes(const mt_model *m, size_t *out) {
+    if (!m || !out) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (!m->finalized) return fail(MT_ERR_NOT_FINALIZED, "model is not finalised");
+    *out = m->arena_bytes;
+    return MT_OK;
+}
+
+int32_t mt_fold_bn(float *w, int64_t k, int64_t per_k, const float *gamma, const float *beta, const float *mean,
+                   const float *var, float eps, float *bias_out) {
+    if (!w || !gamma || !beta || !mean || !var || !bias_out || k < 1 || per_k < 1)
+        return fail(MT_ERR_INVALID_ARG, "bad argument");
+    for (int64_t i = 0; i < k; ++i) {
+        const float scale = gamma[i] / std::sqrt(var[i] + eps);
+        for (int64_t j = 0; j < per_k; ++j) w[i * per_k + j] *= scale;
+        const float ms = mean[i] * scale;
+        bias_out[i] = beta[i] - ms;
+    }
+    return MT_OK;
+}
+
+// ---- registration ----------------------------------------------------------------------------
+int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t arena_bytes, int32_t *out_tenant) {
+    if (!ctx || !m || !out_tenant) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (!m->finalized) return fail(MT_ERR_NOT_FINALIZED, "model is not finalised");
+    if ((int)ctx->tenants.size() >= MT_MAX_TENANTS) return fail(MT_ERR_INVALID_ARG, "too many tenants");
+    for (size_t i = 0; i < m->ops.size(); ++i)
+        if (needs_weights(m->ops[i].d.kind) && !m->ops[i].has_weights)
+            return fail(MT_ERR_NOT_FINALIZED, "operator " + std::to_string(i) + " has no weights");
+    if (device_arena) {
+        if (arena_bytes < m->arena_bytes) return fail(MT_ERR_OUT_OF_MEMORY, "arena is smaller than mt_model_arena_bytes");
+        if (((uintptr_t)device_arena) % ALIGN) return fail(MT_ERR_INVALID_ARG, "arena must be 256-byte aligned");
+    }
+    HIP_TRY(hipSetDevice(ctx->device));
+    std::unique_ptr<Tenant> t(new Tenant);
+    t->model = *m;
+    if (device_arena) {
+        t->arena = (uint8_t *)device_arena;
+    } else {
+        hipError_t e = hipMalloc((void **)&t->arena, std::max<size_t>(m->arena_bytes, ALIGN));
+        if (e != hipSuccess) return fail(MT_ERR_OUT_OF_MEMORY, std::string("hipMalloc: ") + hipGetErrorString(e));
+        t->owns_arena = true;
+    }
+    struct Guard {
+        Tenant *t; bool armed = true;
+        ~Guard() { if (armed && t->owns_arena && t->arena) { (void)hipFree(t->arena); t->arena = nullptr; } }
+    } guard{t.get()};
+
+    const int es = elt_size(m->dtype);
+    const size_t nops = m->ops.size();
+    t->args.resize(nops);
+    t->reads_input.assign(nops, 0); t->res_input.assign(nops, 0); t->writes_output.assign(nops, 0);
+    std::vector<uint8_t> packed;
+    for (size_t i = 0; i < nops; ++i) {
+        OpRec &o = t->model.ops[i];
+        OpArgs a = o.plan;
+        const bool igemm = a.kernel_id == K_IGEMM_128x128 || a.kernel_id == K_IGEMM_128x64 ||
+                           a.kernel_id == K_IGEMM_64x64 || a.kernel_id == K_IGEMM_64x16;
+        if (needs_weights(a.kind)) {
+            const uint8_t *src = o.w_host.data();
+            if (igemm) {
+                // [K][gemm_k] -> [n_pad][k_pad], zero padded
+                packed.assign((size_t)a.n_pad * a.k_pad * es, 0);
+                for (int k = 0; k < a.K; ++k)
+                    std::memcpy(packed.data() + (size_t)k * a.k_pad * es, src + (size_t)k * a.gemm_k * es, (size_t)a.gemm_k * es);
+                src = packed.data();
+            } else if (a.kind == MT_DWCONV) {
+                // [C][R][S] -> [R][S][C]
+                packed.assign((size_t)a.C * a.R * a.S * es, 0);
+                for (int c = 0; c < a.C; ++c)
+                    for (int rs = 0; rs < a.R * a.S; ++rs)
+                        std::memcpy(packed.data() + ((size_t)rs * a.C + c) * es, src + ((size_t)c * a.R * a.S + rs) * es, es);
+                src = packed.data();
+            }
+            HIP_TRY(hipMemcpy(t->arena + o.w_off, src, o.w_bytes, hipMemcpyHostToDevice));
+            std::vector<float> b(igemm ? a.n_pad : a.K, 0.f);
+            std::memcpy(b.data(), o.bias_host.data(), sizeof(float) * a.K);
+            HIP_TRY(hipMemcpy(t->arena + o.bias_off, b.data(), b.size() * sizeof(float), hipMemcpyHostToDevice));
+            a.w = t->arena + o.w_off;
+            a.bias = (const float *)(t->arena + o.bias_off);
+        }
+        if (a.split_k > 1) {
+            a.ws = (float *)(t->arena + o.ws_off);
+            a.counters = (uint32_t *)(t->arena + o.cnt_off);
+            HIP_TRY(hipMemset(a.counters, 0, o.cnt_bytes));
+        }
+        auto tptr = [&](int id) -> uint8_t * { return t->arena + t->model.tensors[id].offset; };
+        if (o.d.in_tensor == 0) t->reads_input[i] = 1; else a.x = tptr(o.d.in_tensor);
+        if (o.d.res_tensor == 0) t->res_input[i] = 1; else if (o.d.res_tensor > 0) a.res = tptr(o.d.res_tensor);
+        a.y = tptr(o.d.out_tensor);
+        if (o.d.out_tensor == t->model.final_tensor) t->writes_output[i] = 1;
+        t->args[i] = a;
+        o.w_host.clear(); o.w_host.shrink_to_fit();
+    }
+    HIP_TRY(hipDeviceSynchronize());
+    guard.armed = false;
+    ctx->tenants.push_back(std::move(t));
+    *out_tenant = (int32_t)ctx->tenants.size() - 1;
+    return MT_OK;
+}
+
+int32_t mt_num_tenants(const mt_ctx *ctx, int32_t *out) {
+    if (!ctx || !out) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    *out = (int32_t)ctx->tenants.size();
+    return MT_OK;
+}
+
+int32_t mt_tenant_num_ops(const mt_ctx *ctx, int32_t tenant, int32_t *out) {
+    if (!ctx || !out) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (tenant < 0 || tenant >= (int)ctx->tenants.size()) return fail(MT_ERR_INVALID_ARG, "no such tenant");
+    *out = (int32_t)ctx->tenants[tenant]->model.ops.size();
+    return MT_OK;
+}
+
+int32_t mt_tenant_op_info(const mt_ctx *ctx, int32_t tenant, int32_t i, mt_op_info *out) {
+    if (!ctx || !out) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (tenant < 0 || tenant >= (int)ctx->tenants.size()) return fail(MT_ERR_INVALID_ARG, "no such tenant");
+    return mt_model_op_info(&ctx->tenants[tenant]->model, i, out);
+}
+
+int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, void *host_dst, size_t bytes) {
+    if (!ctx || !host_dst) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (tenant < 0 || tenant >= (int)ctx->tenants.size()) return fail(MT_ERR_INVALID_ARG, "no such tenant");
+    Tenant &t = *ctx->tenants[tenant];
+    if (tensor_id < 1 || tensor_id >= (int)t.model.tensors.size() || !t.model.tensors[tensor_id].defined)
+        return fail(MT_ERR_INVALID_ARG, "no such tensor (tensor 0 and the final tensor live in caller memory)");
+    if (tensor_id == t.model.final_tensor) return fail(MT_ERR_INVALID_ARG, "the final tensor is written to the caller's output buffer");
+    if (bytes != t.model.tensors[tensor_id].bytes) return fail(MT_ERR_SHAPE_MISMATCH, "byte count does not match the tensor");
+    HIP_TRY(hipSetDevice(ctx->device));
+    HIP_TRY(hipDeviceSynchronize());
+    HIP_TRY(hipMemcpy(host_dst, t.arena + t.model.tensors[tensor_id].offset, bytes, hipMemcpyDeviceToHost));
+    return MT_OK;
+}
+
+// ---- schedule --------------------------------------------------------------------------------
+int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, const int32_t *pointers,
+                           const int32_t *stage_concurrency, const int32_t *cu_share, int32_t order, int32_t flags,
+                           mt_schedule **out) {
+    if (!ctx || !out) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    *out = nullptr;
+    if (n_tenants != (int)ctx->tenants.size() || n_tenants < 1)
+        return fail(MT_ERR_INVALID_SCHEDULE, "schedule must cover exactly the registered tenants");
+    if (order != MT_ISSUE_BFS && order != MT_ISSUE_DFS) return fail(MT_ERR_INVALID_ARG, "unknown issue order");
+    int32_t lens[MT_MAX_TENANTS];
+    for (int i = 0; i < n_tenants; ++i) lens[i] = (int32_t)ctx->tenants[i]->model.ops.size();
+    int32_t rc = validate_pointers(n_tenants, lens, n_stages, pointers);
+    if (rc != MT_OK) return rc;
+    const int cus = ctx->prop.multiProcessorCount;
+    for (int s = 0; s < n_stages; ++s)
+        if (stage_concurrency && stage_concurrency[s] < 1) return fail(MT_ERR_INVALID_SCHEDULE, "stage concurrency must be >= 1");
+    for (int i = 0; i < n_tenants; ++i)
+        if (cu_share && (cu_share[i] < 0 || cu_share[i] > cus)) return fail(MT_ERR_INVALID_SCHEDULE, "CU share out of range");
+    HIP_TRY(hipSetDevice(ctx->device));
+    std::unique_ptr<mt_schedule> s(new mt_schedule);
+    s->ctx = ctx; s->n_tenants = n_tenants; s->n_stages = n_stages; s->flags = flags;
+    int first_cu = 0;
+    for (int i = 0; i < n_tenants; ++i) {
+        const int share = (cu_share && !(flags & MT_SCHED_GRAPH)) ? cu_share[i] : 0;
+        rc = get_stream(ctx, i, share, first_cu, &s->stream_of[i]);
+        if (rc != MT_OK) return rc;
+        first_cu = (first_cu + share) % cus;
+    }
+    std::vector<int32_t> slices((size_t)n_stages * n_tenants * 2);
+    expand_pointers(n_tenants, lens, n_stages, pointers, slices.data());
+    s->stages.resize(n_stages);
+    for (int st = 0; st < n_stages; ++st) {
+        const int conc = stage_concurrency ? stage_concurrency[st] : n_tenants;
+        StagePlan &sp = s->stages[st];
+        sp.items = issue_order(n_tenants, &slices[(size_t)st * n_tenants * 2], conc, order);
+        for (const IssueItem &it : sp.items)
+            if (std::find(sp.streams.begin(), sp.streams.end(), it.stream) == sp.streams.end()) sp.streams.push_back(it.stream);
+        std::sort(sp.streams.begin(), sp.streams.end());
+        s->n_launches += (int)sp.items.size();
+    }
+    *out = s.release();
+    return MT_OK;
+}
+
+int32_t mt_schedule_destroy(mt_schedule *s) {
+    if (!s) return fail(MT_ERR_INVALID_ARG, "schedule is NULL");
+    if (s->graph_exec) (void)hipGraphExecDestroy(s->graph_exec);
+    delete s;
+    return MT_OK;
+}
+
+// ---- run -------------------------------------------------------------------------------------
+int32_t mt_run(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *const *outputs, mt_timings *tm) {
+    if (!ctx || !s || !inputs || !outputs) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (s->ctx != ctx) return fail(MT_ERR_INVALID_ARG, "schedule belongs to another context");
+    for (int i = 0; i < s->n_tenants; ++i) {
+        if (!inputs[i] || !outputs[i]) return fail(MT_ERR_INVALID_ARG, "NULL input or output buffer");
+        if (((uintptr_t)inputs[i] % 16) || ((uintptr_t)outputs[i] % 16)) return fail(MT_ERR_INVALID_ARG, "buffers must be 16-byte aligned");
+    }
+    HIP_TRY(hipSetDevice(ctx->device));
+    const auto t0 = std::chrono::steady_clock::now();
+    int launches = 0;
+    if (s->flags & MT_SCHED_GRAPH) {
+        bool same = s->graph_exec && (int)s->cap_in.size() == s->n_tenants;
+        for (int i = 0; same && i < s->n_tenants; ++i) same = s->cap_in[i] == inputs[i] && s->cap_out[i] == outputs[i];
+        if (!same) {
+            if (s->graph_exec) { (void)hipGraphExecDestroy(s->graph_exec); s->graph_exec = nullptr; }
+            hipGraph_t graph = nullptr;
+            HIP_TRY(hipStreamBeginCapture(ctx->main_stream, hipStreamCaptureModeRelaxed));
+            int32_t rc = issue_schedule(ctx, s, inputs, outputs, &launches);
+            hipError_t e = hipStreamEndCapture(ctx->main_stream, &graph);
+            if (rc != MT_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+            if (e != hipSuccess) return fail(MT_ERR_HIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
+            e = hipGraphInstantiate(&s->graph_exec, graph, nullptr, nullptr, 0);
+            (void)hipGraphDestroy(graph);
+            if (e != hipSuccess) return fail(MT_ERR_HIP, std::string("hipGraphInstantiate: ") + hipGetErrorString(e));
+            s->cap_in.assign(inputs, inputs + s->n_tenants);
+            s->cap_out.assign(outputs, outputs + s->n_tenants);
+        }
+        launches = s->n_launches;
+        HIP_TRY(hipEventRecord(ctx->ev_prof[0], ctx->main_stream));
+        HIP_TRY(hipGraphLaunch(s->graph_exec, ctx->main_stream));
+        HIP_TRY(hipEventRecord(ctx->ev_prof[1], ctx->main_stream));
+    } else {
+        int32_t rc = issue_schedule(ctx, s, inputs, outputs, &launches);
+        if (rc != MT_OK) return rc;
+    }
+    const auto t1 = std::chrono::steady_clock::now();
+    if (s->flags & MT_SCHED_GRAPH) {
+        HIP_TRY(hipEventSynchronize(ctx->ev_prof[1]));
+    } else {
+        HIP_TRY(hipEventSynchronize(ctx->ev_stage[s->n_stages - 1]));
+    }
+    if (tm) {
+        std::memset(tm, 0, sizeof(*tm));
+        tm->n_launches = launches;
+        tm->n_stages = s->n_stages;
+        tm->host_issue_ms = std::chrono::duration<float, std::milli>(t1 - t0).count();
+        if (s->flags & MT_SCHED_GRAPH) {
+            // events recorded inside a captured graph cannot be queried: only the end-to-end time is available
+            HIP_TRY(hipEventElapsedTime(&tm->makespan_ms, ctx->ev_prof[0], ctx->ev_prof[1]));
+        } else {
+            HIP_TRY(hipEventElapsedTime(&tm->makespan_ms, ctx->ev_start, ctx->ev_stage[s->n_stages - 1]));
+            hipEvent_t prev = ctx->ev_start;
+            for (int st = 0; st < s->n_stages; ++st) {
+                HIP_TRY(hipEventElapsedTime(&tm->stage_ms[st], prev, ctx->ev_stage[st]));
+                prev = ctx->ev_stage[st];
+            }
+        }
+    }
+    return MT_OK;
+}
+
+int32_t mt_profile_ops(mt_ctx *ctx, int32_t tenant, const void *input, void *output, int32_t repeats, float *op_ms) {
+    if (!ctx || !input || !output || !op_ms) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (tenant < 0 || tenant >= (int)ctx->tenants.size()) return fail(MT_ERR_INVALID_ARG, "no such tenant");
+    if (repeats < 1) return fail(MT_ERR_INVALID_ARG, "repeats must be >= 1");
+    HIP_TRY(hipSetDevice(ctx->device));
+    const Tenant &t = *ctx->tenants[tenant];
+    for (size_t i = 0; i < t.args.size(); ++i) {
+        OpArgs a = patched(t, (int)i, input, output);
+        int32_t rc = launch_op(a, ctx->main_stream);          // warm-up, also produces the next operator's input
+        if (rc != MT_OK) return rc;
+        HIP_TRY(hipEventRecord(ctx->ev_prof[0], ctx->main_stream));
+        for (int r = 0; r < repeats; ++r) {
+            rc = launch_op(a, ctx->main_stream);
+            if (rc != MT_OK) return rc;
+        }
+        HIP_TRY(hipEventRecord(ctx->ev_prof[1], ctx->main_stream));
+        HIP_TRY(hipEventSynchronize(ctx->ev_prof[1]));
+        float ms = 0;
+        HIP_TRY(hipEventElapsedTime(&ms, ctx->ev_prof[0], ctx->ev_prof[1]));
+        op_ms[i] = ms / repeats;
+    }
+    return MT_OK;
+}
+
+// ---- search ----------------------------------------------------------------------------------
+namespace {
+struct ProfileCost {
+    mt_ctx *ctx;
+    const mt_search_opts *o;
+    const void *const *inputs;
+    void *const *outputs;
+    int n_tenants;
+    int32_t rc = MT_OK;
+};
+
+double profile_cost(const int32_t *pointers, void *user) {
+    ProfileCost *pc = (ProfileCost *)user;
+    if (pc->rc != MT_OK) return 1e30;
+    mt_schedule *s = nullptr;
+    pc->rc = mt_schedule_create(pc->ctx, pc->n_tenants, pc->o->n_stages, pointers, nullptr, nullptr, pc->o->issue_order,
+                                pc->o->flags, &s);
+    if (pc->rc != MT_OK) return 1e30;
+    double sum = 0;
+    for (int r = 0; r < pc->o->warmup + pc->o->runs && pc->rc == MT_OK; ++r) {
+        mt_timings tm;
+        pc->rc = mt_run(pc->ctx, s, pc->inputs, pc->outputs, &tm);
+        if (r >= pc->o->warmup) sum += tm.makespan_ms;
+    }
+    mt_schedule_destroy(s);
+    return pc->rc == MT_OK ? sum / pc->o->runs : 1e30;
+}
+}  // namespace
+
+int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *inputs, void *const *outputs,
+                  int32_t *best_pointers, double *best_cost, int32_t *rec_pointers, double *rec_cost,
+                  int32_t max_records, int32_t *n_records) {
+    if (!ctx || !opts || !inputs || !outputs || !best_pointers) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (opts->runs < 1 || opts->warmup < 0) return fail(MT_ERR_INVALID_ARG, "runs must be >= 1 and warmup >= 0");
+    const int n = (int)ctx->tenants.size();
+    if (n < 1) return fail(MT_ERR_INVALID_ARG, "no tenants registered");
+    int32_t lens[MT_MAX_TENANTS];
+    for (int i = 0; i < n; ++i) lens[i] = (int32_t)ctx->tenants[i]->model.ops.size();
+    ProfileCost pc{ctx, opts, inputs, outputs, n};
+    int32_t rc = search_pointers(n, lens, opts, profile_cost, &pc, best_pointers, best_cost, rec_pointers, rec_cost,
+                                 max_records, n_records);
+    if (pc.rc != MT_OK) return pc.rc;
+    return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,160 @@
+"""Per-kernel parity on the GPU: small graphs chosen to hit every kernel family, tile shape, split-K path,
+vector / scalar path and ragged tail, each compared element by element with the CPU oracle."""
+import numpy as np
+import pytest
+
+from synth import GraphBuilder
+from gpu_harness import Mix, assert_close
+
+pytestmark = pytest.mark.gpu
+
+# kernel ids as reported by mt_op_info
+DIRECT, IG128, IG64, IG16, DW, MAXP, AVGP, GAP, IG128x64 = range(9)
+
+
+def g_conv(dtype, n, h, w, c, k, r, stride=1, pad=0, act="relu", bn=True, res=False, coff=0, ctot=0):
+    g = GraphBuilder("t", dtype, n, h, w, c)
+    short = -1
+    t = 0
+    if res:
+        # residual operand: another convolution with the same output geometry
+        short = g.conv(0, k, r, stride=stride, pad=pad, act="none", bn=False)
+    g.conv(t, k, r, stride=stride, pad=pad, act=act, bn=bn, res=short, c_off=coff, c_tot=ctot)
+    if ctot:
+        # fill the remaining channels so that the whole output tensor is defined
+        d = g.m.ops[-1].out_tensor
+        if coff:
+            g.conv(t, coff, r, stride=stride, pad=pad, act="none", dst=d, c_off=0, c_tot=ctot)
+        if coff + k < ctot:
+            g.conv(t, ctot - coff - k, r, stride=stride, pad=pad, act="none", dst=d, c_off=coff + k, c_tot=ctot)
+    return g.done()
+
+
+CONV_CASES = [
+    # name, builder args, expected kernel of the main conv (None = don't care)
+    ("ig64_ragged", dict(n=1, h=13, w=13, c=16, k=40, r=3, pad=1), IG64),
+    ("ig64_stride2_res", dict(n=2, h=15, w=15, c=24, k=72, r=3, stride=2, pad=1, res=True), IG64),
+    ("ig64_1x1_relu6", dict(n=1, h=14, w=14, c=96, k=24, r=1, act="relu6"), IG64),
+    ("ig64_1x7", dict(n=1, h=17, w=17, c=32, k=48, r=(1, 7), pad=(0, 3)), IG64),
+    ("ig64_7x1", dict(n=1, h=17, w=17, c=32, k=48, r=(7, 1), pad=(3, 0)), IG64),
+    ("ig64_5x5", dict(n=1, h=12, w=12, c=8, k=64, r=5, pad=2), IG64),
+    ("ig64_splitk", dict(n=1, h=7, w=7, c=256, k=128, r=3, pad=1, res=True), IG64),
+    ("ig64_first_layer_7x7s2", dict(n=1, h=40, w=40, c=3, k=64, r=7, stride=2, pad=3), IG64),
+    ("ig64_first_layer_11x11s4", dict(n=1, h=67, w=67, c=3, k=96, r=11, stride=4), IG64),
+    ("ig64_c12_scalar", dict(n=1, h=9, w=9, c=12, k=20, r=3, pad=1, act="none"), IG64),
+    ("ig64_concat_unaligned", dict(n=1, h=8, w=8, c=16, k=10, r=3, pad=1, coff=3, ctot=18), IG64),
+    ("ig64_concat_aligned", dict(n=1, h=8, w=8, c=16, k=32, r=1, coff=64, ctot=128), IG64),
+    ("ig16_conv_tiny_map", dict(n=2, h=4, w=4, c=64, k=70, r=3, pad=1), IG16),
+    ("ig16_1x1_m1", dict(n=1, h=1, w=1, c=1280, k=1000, r=1, act="none"), IG16),
+    ("ig128x64", dict(n=1, h=128, w=128, c=8, k=100, r=3, pad=1), IG128x64),
+    ("ig128", dict(n=2, h=182, w=182, c=8, k=128, r=3, pad=1, res=True), IG128),
+    ("ig128_first_layer", dict(n=2, h=200, w=200, c=3, k=120, r=3, pad=1), IG128),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("name,kw,kid", CONV_CASES, ids=[c[0] for c in CONV_CASES])
+def test_conv_igemm(name, kw, kid, dtype):
+    spec = g_conv(dtype, **kw)
+    print("case", name, dtype, flush=True)
+    mix = Mix([spec], seed=11)
+    try:
+        main = 1 if kw.get("res") else 0
+        info = mix.ctx.op_info(0, main)
+        if kid is not None:
+            assert info.kernel_id == kid, (info.kernel_id, info.split_k)
+        if "splitk" in name:
+            assert info.split_k > 1
+        got, _ = mix.run(mix.ctx.sequential())
+        assert_close(got[0], mix.oracle()[0], dtype, name)
+    finally:
+        mix.close()
+
+
+def g_fc(dtype, n, h, w, c, k, act="none"):
+    g = GraphBuilder("t", dtype, n, h, w, c)
+    g.fc(0, k, act=act)
+    return g.done()
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("n,h,w,c,k", [(1, 7, 7, 32, 100), (3, 1, 1, 1000, 70), (8, 2, 2, 64, 10), (40, 1, 1, 256, 130), (1, 5, 5, 3, 10)])
+def test_fc(dtype, n, h, w, c, k):
+    spec = g_fc(dtype, n, h, w, c, k, act="relu")
+    print("case fc", dtype, n, h, w, c, k, flush=True)
+    mix = Mix([spec], seed=12)
+    try:
+        got, _ = mix.run(mix.ctx.sequential())
+        assert_close(got[0], mix.oracle()[0], dtype)
+    finally:
+        mix.close()
+
+
+@pytest.mark.parametrize("n,h,w,c,k,r,stride,pad", [(2, 9, 9, 3, 16, 3, 1, 1), (1, 12, 12, 5, 7, 5, 2, 0), (1, 6, 6, 16, 32, 1, 1, 0)])
+def test_conv_fp32_direct(n, h, w, c, k, r, stride, pad):
+    spec = g_conv("f32", n, h, w, c, k, r, stride, pad, res=True)
+    mix = Mix([spec], seed=13, input_dist="uniform")
+    try:
+        assert mix.ctx.op_info(0, 1).kernel_id == DIRECT
+        got, _ = mix.run(mix.ctx.sequential())
+        assert_close(got[0], mix.oracle()[0], "f32")
+    finally:
+        mix.close()
+
+
+def g_chain(dtype, n, h, w, c, build):
+    g = GraphBuilder("t", dtype, n, h, w, c)
+    build(g)
+    return g.done()
+
+
+CHANNELWISE = [
+    ("dw_shuffle_c32", 1, 20, 20, 32, lambda g: g.dwconv(0, 3, 1, 1, act="relu6", bn=True)),
+    ("dw_shuffle_c64_ragged", 2, 7, 9, 64, lambda g: g.dwconv(0, 3, 1, 1, act="relu", bn=True)),
+    ("dw_shuffle_c8", 1, 5, 37, 8, lambda g: g.dwconv(0, 3, 1, 1, act="none", bn=True)),
+    ("dw_stride2", 1, 15, 15, 96, lambda g: g.dwconv(0, 3, 2, 1, act="relu6", bn=True)),
+    ("dw_c96_stride1", 1, 14, 14, 96, lambda g: g.dwconv(0, 3, 1, 1, act="relu6", bn=True)),
+    ("dw_c960", 1, 7, 7, 960, lambda g: g.dwconv(0, 3, 1, 1, act="relu6", bn=True)),
+    ("dw_scalar_c20", 1, 9, 9, 20, lambda g: g.dwconv(0, 3, 1, 1, act="relu", bn=False)),
+    ("dw_5x5", 1, 11, 11, 16, lambda g: g.dwconv(0, 5, 1, 2, act="relu", bn=False)),
+    ("maxpool_2x2", 2, 14, 14, 64, lambda g: g.maxpool(0, 2, 2)),
+    ("maxpool_3x3s2p1", 1, 17, 17, 64, lambda g: g.maxpool(0, 3, 2, 1)),
+    ("maxpool_3x3s2_scalar", 1, 13, 13, 12, lambda g: g.maxpool(0, 3, 2)),
+    ("avgpool_3x3s1p1", 1, 8, 8, 40, lambda g: g.avgpool(0, 3, 1, 1)),
+    ("avgpool_scalar", 1, 6, 7, 5, lambda g: g.avgpool(0, 3, 1, 1)),
+    ("gap_7x7", 2, 7, 7, 512, lambda g: g.gap(0)),
+    ("gap_8x8_c2048", 1, 8, 8, 2048, lambda g: g.gap(0)),
+    ("gap_16x16_c24", 3, 16, 16, 24, lambda g: g.gap(0)),
+    ("gap_scalar_c10", 1, 5, 5, 10, lambda g: g.gap(0)),
+    ("maxpool_into_concat", 1, 9, 9, 16, lambda g: (lambda d: (g.maxpool(0, 3, 2, dst=d, c_off=8, c_tot=24),
+                                                               g.conv(0, 8, 3, stride=2, dst=d, c_off=0, c_tot=24)))(g.new_tensor())),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("name,n,h,w,c,build", CHANNELWISE, ids=[c[0] for c in CHANNELWISE])
+def test_channelwise(name, n, h, w, c, build, dtype):
+    spec = g_chain(dtype, n, h, w, c, build)
+    print("case", name, dtype, flush=True)
+    mix = Mix([spec], seed=14)
+    try:
+        got, _ = mix.run(mix.ctx.sequential())
+        assert_close(got[0], mix.oracle()[0], dtype, name)
+    finally:
+        mix.close()
+
+
+def test_empty_slices_and_single_op_tenant():
+    """Degenerate schedules: a tenant with one operator, stages in which some or all tenants have no work."""
+    a = g_fc("f16", 1, 1, 1, 64, 16)
+    b = g_conv("f16", 1, 8, 8, 8, 16, 3, pad=1)
+    mix = Mix([a, b], seed=15)
+    try:
+        ref = mix.oracle()
+        for rho in ([[0, 0, 1], [0, 0, 0]], [[1, 1, 1], [1, 1, 1]], [[0, 0, 0], [1, 1, 1]], [[0, 1, 1], [0, 0, 1]]):
+            got, tm = mix.run(mix.ctx.schedule(rho, 4))
+            assert tm["n_launches"] == 2
+            for t in range(2):
+                assert_close(got[t], ref[t], "f16")
+    finally:
+        mix.close()
