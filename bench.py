@@ -1,3 +1,182 @@
-"""placeholder; replaced below"""
+"""Benchmark of the staged multi-tenant forward pass on one MI355X.
+
+One step = one pass of the whole hot path: every operator of every tenant of the workload, issued according
+to a schedule (sequential, all-concurrent, or the searched pointer matrix), inputs resident in HBM.
+Prints one JSON line; `value` is aggregate images per second under the searched schedule.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f16": 2500.0, "bf16": 2500.0, "f32": 157.3}
+PEAK_HBM_GBS = 8000.0
+
+
 def speedup(sequential_ms, ours_ms):
+    """Speed-up as the paper's tables print it: sequential latency divided by ours (Tables I-II)."""
     return sequential_ms / ours_ms
+
+
+def time_schedule(ctx, torch, sched, inputs, outputs, warmup, steps):
+    for _ in range(warmup):
+        ctx.run(sched, inputs, outputs)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    mk, issue = [], []
+    for _ in range(steps):
+        tm = ctx.run(sched, inputs, outputs)
+        mk.append(tm["makespan_ms"])
+        issue.append(tm["host_issue_ms"])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    mk.sort()
+    return {"wall_ms_per_step": wall_ms, "makespan_ms_mean": sum(mk) / len(mk), "makespan_ms_min": mk[0],
+            "makespan_ms_median": mk[len(mk) // 2], "host_issue_ms_mean": sum(issue) / len(issue)}
+
+
+def kernel_rooflines(ctx, inputs, outputs, dtype, repeats):
+    """Per kernel family: launches, total time, algorithmic flops and bytes, from back-to-back timed launches."""
+    from paper_2111_14255_amd import binding as B
+    fam = {}
+    for t in range(ctx.num_tenants()):
+        ms = ctx.profile_ops(t, inputs[t], outputs[t], repeats)
+        for i, d in enumerate(ms):
+            info = ctx.op_info(t, i)
+            name = B.load().mt_kernel_name(info.kernel_id).decode()
+            f = fam.setdefault(name, {"launches": 0, "ms": 0.0, "flops": 0.0, "bytes": 0.0})
+            f["launches"] += 1
+            f["ms"] += d
+            f["flops"] += info.flops
+            f["bytes"] += info.bytes
+    return fam
+
+
+def cpu_baseline(specs, raws, xs):
+    """The CPU oracle, as it stands, timed on this host: one forward pass of every tenant of the workload."""
+    from oracle import forward as OF, ops as oops
+    params = [OF.prepare_params(m, raw) for m, raw in zip(specs, raws)]
+    t0 = time.perf_counter()
+    for m, p, x in zip(specs, params, xs):
+        OF.forward(m, p, x)
+    dt = time.perf_counter() - t0
+    images = sum(m.batch for m in specs)
+    return {"value": images / dt, "unit": "img/s", "cores": oops.num_threads(), "kind": "oracle",
+            "sample": "one forward pass of all %d tenants (%d images, %.1f GMAC) in %.2f s" %
+                      (len(specs), images, sum(m.macs() for m in specs) / 1e9, dt)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", default="cfg2")
+    ap.add_argument("--search-rounds", type=int, default=2)
+    ap.add_argument("--search-candidates", type=int, default=6)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-graph", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); tenants would be sharded across GPUs "
+              "by bin-packing, see DESIGN.md", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from synth import configs, weights
+    from paper_2111_14255_amd import api, binding as B
+
+    cfg = configs.CONFIGS[args.config]
+    specs = cfg.models()
+    raws = [weights.make_params(m, cfg.seed, t) for t, m in enumerate(specs)]
+    xs = [weights.make_input(m, cfg.seed, t, cfg.input_dist) for t, m in enumerate(specs)]
+    ctx = api.Context(0)
+    for m, raw in zip(specs, raws):
+        model = api.Model(m, raw)
+        ctx.register(model)
+        model.close()
+    inputs = [ctx.make_input(t, x) for t, x in enumerate(xs)]
+    outputs = [ctx.make_output(t) for t in range(len(specs))]
+    images = sum(m.batch for m in specs)
+    lens = ctx.lens()
+
+    # ---- the three schedules --------------------------------------------------------------
+    results = {}
+    for flags, suffix in ((0, ""),) + (() if args.no_graph else ((B.MT_SCHED_GRAPH, "+graph"),)):
+        seq = ctx.sequential(flags=flags)
+        allc = ctx.all_concurrent(flags=flags)
+        t0 = time.perf_counter()
+        rho, cost, records = ctx.search(inputs, outputs, cfg.n_stages, rounds=args.search_rounds,
+                                        candidates=args.search_candidates, runs=5, warmup=1, seed=cfg.seed, flags=flags)
+        search_s = time.perf_counter() - t0
+        searched = ctx.schedule(rho, cfg.n_stages, flags=flags)
+        for name, s in (("sequential", seq), ("all_concurrent", allc), ("searched", searched)):
+            results[name + suffix] = time_schedule(ctx, torch, s, inputs, outputs, args.warmup, args.steps)
+        results["searched" + suffix]["pointers"] = rho
+        results["searched" + suffix]["search_seconds"] = search_s
+        results["searched" + suffix]["search_evaluations"] = len(records)
+    for k, r in results.items():
+        base = results["sequential" + ("+graph" if k.endswith("+graph") else "")]
+        r["img_per_s"] = images / (r["wall_ms_per_step"] * 1e-3)
+        r["speedup_vs_sequential"] = speedup(base["makespan_ms_mean"], r["makespan_ms_mean"])
+
+    best_key = min((k for k in results if k.startswith("searched")), key=lambda k: results[k]["wall_ms_per_step"])
+    head = results[best_key]
+
+    # ---- roofline of the dominant kernel ----------------------------------------------------
+    fam = kernel_rooflines(ctx, inputs, outputs, cfg.dtype, repeats=10)
+    dom = max(fam, key=lambda k: fam[k]["ms"])
+    f = fam[dom]
+    if dom.startswith("igemm") or dom == "conv_direct":
+        achieved = f["flops"] / (f["ms"] * 1e-3) / 1e12
+        roof = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS[cfg.dtype], "unit": "TFLOP/s",
+                "frac": achieved / PEAK_TFLOPS[cfg.dtype]}
+    else:
+        achieved = f["bytes"] / (f["ms"] * 1e-3) / 1e9
+        roof = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": achieved / PEAK_HBM_GBS}
+    roof["launches_per_step"] = f["launches"]
+    roof["avg_launch_us"] = f["ms"] * 1e3 / f["launches"]
+    roof["traffic"] = None
+    roof["families"] = {k: {"launches": v["launches"], "us": round(v["ms"] * 1e3, 2),
+                            "TFLOP/s": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] > 0 else 0.0,
+                            "GB/s": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] > 0 else 0.0}
+                        for k, v in fam.items()}
+    total_flops = sum(v["flops"] for v in fam.values())
+    total_bytes = sum(v["bytes"] for v in fam.values())
+
+    out = {
+        "metric": "aggregate images/s of the multi-tenant forward pass under the searched schedule (makespan in ms_per_step)",
+        "value": head["img_per_s"],
+        "unit": "img/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head["wall_ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": cfg.dtype,
+        "data": "synthetic",
+        "config": {"workload": "%s: %s, batch %d, %s storage, fp32 accumulate" % (cfg.name, "+".join(cfg.tenants), cfg.batch, cfg.dtype),
+                   "images_per_step": images, "launches_per_step": sum(lens), "headline_schedule": best_key,
+                   "n_stages": cfg.n_stages},
+        "schedules": results,
+        "bounds": {"flops_bound_us": total_flops / (PEAK_TFLOPS[cfg.dtype] * 1e12) * 1e6,
+                   "bytes_bound_us": total_bytes / (PEAK_HBM_GBS * 1e9) * 1e6,
+                   "makespan_frac_of_bound": max(total_flops / (PEAK_TFLOPS[cfg.dtype] * 1e12), total_bytes / (PEAK_HBM_GBS * 1e9)) * 1e3 / head["makespan_ms_mean"]},
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(specs, raws, xs)
+    ctx.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
