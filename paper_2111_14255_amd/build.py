@@ -11,7 +11,7 @@ LIB = os.path.join(HERE, "libmtsched.so")
 
 DEVICE_SOURCES = ["kernels_direct.hip", "kernels_igemm.hip"]
 HOST_SOURCES = ["sched_core.cpp", "runtime.cpp"]
-COMMON = ["-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function"]
+COMMON = ["-O3", "-fPIC", "-std=c++20", "-Wall", "-Wno-unused-function"]
 # packed-fp32 code generation is switched off for all device code
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -24,6 +24,10 @@ int32_t search_pointers(int32_t n_tenants, const int32_t *lens, const mt_search_
                         int32_t *best_pointers, double *best_cost, int32_t *rec_pointers, double *rec_cost,
                         int32_t max_records, int32_t *n_records);
 
+constexpr int IGEMM_BK = 64;   // reduction elements per implicit-GEMM tile; packed filter rows are padded to it
+
+inline bool is_gemm_kernel(int32_t id);
+
 // ---- kernel families -------------------------------------------------------------------
 // The kernel and tile of an operator are a pure function of its shape and storage type, never of the
 // stream, CU share or stage it runs in; that is what makes outputs bit-identical across schedules.
@@ -37,8 +41,13 @@ enum KernelId : int32_t {
     K_AVGPOOL = 6,
     K_GAP = 7,
     K_IGEMM_128x64 = 8,     // 128 output channels x 64 pixels
+    K_GEMV = 9,             // 1x1 / fully connected layers with at most 8 output pixels: weight streaming
     K_COUNT
 };
+
+inline bool is_gemm_kernel(int32_t id) {
+    return id == K_IGEMM_128x128 || id == K_IGEMM_128x64 || id == K_IGEMM_64x64 || id == K_IGEMM_64x16 || id == K_GEMV;
+}
 
 // Everything a launcher needs for one operator.  Pointers are resolved per run (the first operator may
 // read the caller's input buffer, the last one writes the caller's output buffer).

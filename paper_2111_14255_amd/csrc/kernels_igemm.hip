@@ -10,9 +10,13 @@
 // 8 consecutive j of one row).  The filter bank is the MFMA "A" operand, so a lane's accumulator registers
 // hold four consecutive output channels of one pixel: the NHWC store is an 8-byte access per group.
 //
-// fp16 / bf16 inputs, fp32 accumulation; bias, residual, activation in fp32; one rounding on store.
-// Tiny-M layers are split along j across workgroups; partial sums go to a workspace and the workgroup that
-// arrives last adds them in split order, so the result does not depend on arrival order.
+// Pipeline: global loads run STAGES reduction tiles ahead in registers, LDS is double buffered, one
+// workgroup barrier per tile.  fp16 / bf16 inputs, fp32 accumulation; bias, residual, activation in fp32;
+// one rounding on store.
+//
+// Tiny-M layers are split along j across workgroups.  Partial sums go to a workspace with device-coherent
+// (write-through) stores, and the workgroup that arrives last at the tile's counter adds them in split
+// order, so the result does not depend on arrival order.
 #include <hip/hip_runtime.h>
 
 #include "internal.h"
@@ -24,9 +28,10 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16-byte register chunk
 
-constexpr int BK = 32;           // reduction elements per LDS tile
-constexpr int LDK = BK + 8;      // padded LDS row (80 bytes: 16-byte reads of a wave fall in distinct banks)
+constexpr int BK = IGEMM_BK;     // reduction elements per LDS tile
+constexpr int LDK = BK + 8;      // padded LDS row (144 bytes: 16-byte reads of a wave fall in distinct banks)
 constexpr int NXCD = 8;
 
 template <typename T, int MF>
@@ -34,36 +39,38 @@ struct Mma;
 template <>
 struct Mma<f16, 32> {
     typedef f32x16 Acc;
-    static __device__ __forceinline__ Acc run(uint4 a, uint4 b, Acc c) {
+    static __device__ __forceinline__ Acc run(u32x4 a, u32x4 b, Acc c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
     }
 };
 template <>
 struct Mma<bf16, 32> {
     typedef f32x16 Acc;
-    static __device__ __forceinline__ Acc run(uint4 a, uint4 b, Acc c) {
+    static __device__ __forceinline__ Acc run(u32x4 a, u32x4 b, Acc c) {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
     }
 };
 template <>
 struct Mma<f16, 16> {
     typedef f32x4 Acc;
-    static __device__ __forceinline__ Acc run(uint4 a, uint4 b, Acc c) {
+    static __device__ __forceinline__ Acc run(u32x4 a, u32x4 b, Acc c) {
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
     }
 };
 template <>
 struct Mma<bf16, 16> {
     typedef f32x4 Acc;
-    static __device__ __forceinline__ Acc run(uint4 a, uint4 b, Acc c) {
+    static __device__ __forceinline__ Acc run(u32x4 a, u32x4 b, Acc c) {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
     }
 };
 
-// BN: output channels per workgroup, BM: pixels per workgroup, WN x WM: wave grid (4 waves), MF: MFMA edge.
-template <typename T, int BN, int BM, int WN, int WM, int MF, bool VEC_A>
+// BN: output channels per workgroup, BM: pixels per workgroup, WN x WM: wave grid (4 waves), MF: MFMA edge,
+// STAGES: reduction tiles whose global loads are in flight (register sets), even.
+template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES, bool VEC_A>
 __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     static_assert(WN * WM == 4, "four waves per workgroup");
+    static_assert(STAGES == 2 || STAGES == 4, "register sets rotate with the two LDS buffers");
     constexpr int SUBN = BN / WN, SUBM = BM / WM;          // wave tile
     constexpr int TN = SUBN / MF, TM = SUBM / MF;          // MFMA tiles per wave
     static_assert(TN >= 1 && TM >= 1, "wave tile smaller than one MFMA");
@@ -71,12 +78,13 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     constexpr int KLANES = 64 / MF;                        // lane groups along the reduction index
     constexpr int ACC_REGS = (MF == 32) ? 16 : 4;
     constexpr int CH_ROW = BK / 8;                         // 16-byte chunks per tile row
-    constexpr int W_CHUNKS = (BN * CH_ROW + 255) / 256;    // chunks per thread, filter tile
-    constexpr int X_CHUNKS = (BM * CH_ROW + 255) / 256;    // chunks per thread, pixel tile
+    constexpr int ROW_STEP = 256 / CH_ROW;                 // tile rows covered by one pass of the workgroup
+    constexpr int W_CHUNKS = (BN + ROW_STEP - 1) / ROW_STEP;
+    constexpr int X_CHUNKS = (BM + ROW_STEP - 1) / ROW_STEP;
     typedef typename Mma<T, MF>::Acc Acc;
 
-    __shared__ __attribute__((aligned(16))) uint16_t Ws[BN * LDK];
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[BM * LDK];
+    __shared__ __attribute__((aligned(16))) uint16_t Ws[2][BN * LDK];
+    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][BM * LDK];
     __shared__ int s_last;
 
     const int tid = threadIdx.x;
@@ -103,15 +111,14 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     const int nkt = a.k_pad / BK;
     const int kt_per = (nkt + a.split_k - 1) / a.split_k;
     const int kt_begin = z * kt_per;
-    const int kt_end = min(nkt, kt_begin + kt_per);
+    const int nk = min(nkt, kt_begin + kt_per) - kt_begin;     // tiles of this workgroup (>= 1 by construction)
 
     const T *x = (const T *)a.x;
     const uint16_t *wp = (const uint16_t *)a.w;
 
     // ---- per-thread load coordinates -------------------------------------------------------
     const int kc = tid % CH_ROW;          // chunk column (same for every chunk of this thread)
-    const int row0 = tid / CH_ROW;        // first tile row; further chunks are 256/CH_ROW rows apart
-    constexpr int ROW_STEP = 256 / CH_ROW;
+    const int row0 = tid / CH_ROW;        // first tile row; further chunks are ROW_STEP rows apart
 
     int64_t xbase[X_CHUNKS];              // element offset of (n, 0, 0, 0)
     int ih0[X_CHUNKS], iw0[X_CHUNKS];
@@ -129,7 +136,13 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
         ih0[i] = p * a.sh - a.ph;
         iw0[i] = q * a.sw - a.pw;
     }
-    // position of this thread's chunk inside the (r, s, c) reduction index
+    const uint16_t *wrow[W_CHUNKS];
+#pragma unroll
+    for (int i = 0; i < W_CHUNKS; ++i) {
+        const int row = min(row0 + i * ROW_STEP, BN - 1);
+        wrow[i] = wp + (int64_t)(n0 + row) * a.k_pad + (int64_t)kt_begin * BK + kc * 8;
+    }
+    // position of this thread's chunk inside the (r, s, c) reduction index, advanced by one tile per load
     int kr, ks, kcx;
     {
         const int j0 = kt_begin * BK + kc * 8;
@@ -138,26 +151,25 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
         ks = rs % a.S;
         kr = rs / a.S;
     }
+    int jbase = kt_begin * BK + kc * 8;   // scalar-gather path
 
-    uint4 wreg[W_CHUNKS], xreg[X_CHUNKS];
+    u32x4 wreg[STAGES][W_CHUNKS], xreg[STAGES][X_CHUNKS];
 
-    auto load_tiles = [&](int kt) {
+    auto load_tiles = [&](u32x4 (&wr)[W_CHUNKS], u32x4 (&xr)[X_CHUNKS]) {
 #pragma unroll
         for (int i = 0; i < W_CHUNKS; ++i) {
-            const int row = row0 + i * ROW_STEP;
-            if (row < BN)
-                wreg[i] = *reinterpret_cast<const uint4 *>(wp + (int64_t)(n0 + row) * a.k_pad + kt * BK + kc * 8);
+            wr[i] = *reinterpret_cast<const u32x4 *>(wrow[i]);
+            wrow[i] += BK;
         }
         if constexpr (VEC_A) {
 #pragma unroll
             for (int i = 0; i < X_CHUNKS; ++i) {
                 const int ih = ih0[i] + kr, iw = iw0[i] + ks;
-                uint4 v = make_uint4(0, 0, 0, 0);
+                u32x4 v = u32x4{0u, 0u, 0u, 0u};
                 if (xrow_ok[i] && kr < a.R && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W)
-                    v = *reinterpret_cast<const uint4 *>(x + xbase[i] + ((int64_t)ih * a.W + iw) * a.C + kcx);
-                xreg[i] = v;
+                    v = *reinterpret_cast<const u32x4 *>(x + xbase[i] + ((int64_t)ih * a.W + iw) * a.C + kcx);
+                xr[i] = v;
             }
-            // advance the chunk by one tile along the reduction index
             kcx += BK;
             while (kcx >= a.C) {
                 kcx -= a.C;
@@ -168,7 +180,6 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
             }
         } else {
             // input channels not a multiple of 8 (first layers, C = 3): gather element by element
-            const int jbase = kt * BK + kc * 8;
 #pragma unroll
             for (int i = 0; i < X_CHUNKS; ++i) {
                 uint16_t e[8];
@@ -185,22 +196,23 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
                         v = reinterpret_cast<const uint16_t *>(x)[xbase[i] + ((int64_t)ih * a.W + iw) * a.C + c];
                     e[t] = v;
                 }
-                xreg[i] = make_uint4(e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16),
-                                     e[4] | ((uint32_t)e[5] << 16), e[6] | ((uint32_t)e[7] << 16));
+                xr[i] = u32x4{e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16),
+                              e[4] | ((uint32_t)e[5] << 16), e[6] | ((uint32_t)e[7] << 16)};
             }
+            jbase += BK;
         }
     };
 
-    auto store_tiles = [&]() {
+    auto store_tiles = [&](int buf, const u32x4 (&wr)[W_CHUNKS], const u32x4 (&xr)[X_CHUNKS]) {
 #pragma unroll
         for (int i = 0; i < W_CHUNKS; ++i) {
             const int row = row0 + i * ROW_STEP;
-            if (row < BN) *reinterpret_cast<uint4 *>(&Ws[row * LDK + kc * 8]) = wreg[i];
+            if (row < BN) *reinterpret_cast<u32x4 *>(&Ws[buf][row * LDK + kc * 8]) = wr[i];
         }
 #pragma unroll
         for (int i = 0; i < X_CHUNKS; ++i) {
             const int row = row0 + i * ROW_STEP;
-            if (row < BM) *reinterpret_cast<uint4 *>(&Xs[row * LDK + kc * 8]) = xreg[i];
+            if (row < BM) *reinterpret_cast<u32x4 *>(&Xs[buf][row * LDK + kc * 8]) = xr[i];
         }
     };
 
@@ -215,27 +227,58 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     const int frag_row = lane % MF;
     const int frag_k = (lane / MF) * 8;
 
-    if (kt_begin < kt_end) load_tiles(kt_begin);
-    for (int kt = kt_begin; kt < kt_end; ++kt) {
-        store_tiles();
-        __syncthreads();
-        if (kt + 1 < kt_end) load_tiles(kt + 1);     // next tile's global loads overlap the MFMAs below
+    auto compute = [&](int buf) {
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk) {
             const int koff = kk * (KLANES * 8) + frag_k;
-            uint4 af[TN], bf[TM];
+            u32x4 af[TN], bf[TM];
 #pragma unroll
             for (int i = 0; i < TN; ++i)
-                af[i] = *reinterpret_cast<const uint4 *>(&Ws[(wn * SUBN + i * MF + frag_row) * LDK + koff]);
+                af[i] = *reinterpret_cast<const u32x4 *>(&Ws[buf][(wn * SUBN + i * MF + frag_row) * LDK + koff]);
 #pragma unroll
             for (int j = 0; j < TM; ++j)
-                bf[j] = *reinterpret_cast<const uint4 *>(&Xs[(wm * SUBM + j * MF + frag_row) * LDK + koff]);
+                bf[j] = *reinterpret_cast<const u32x4 *>(&Xs[buf][(wm * SUBM + j * MF + frag_row) * LDK + koff]);
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
                 for (int j = 0; j < TM; ++j) acc[i][j] = Mma<T, MF>::run(af[i], bf[j], acc[i][j]);
         }
-        __syncthreads();
+    };
+
+    // ---- software pipeline ---------------------------------------------------------------------
+    // Tile t lives in register set t % STAGES until it is copied to LDS buffer t % 2.
+    // Iteration t: copy tile t+1 to LDS, reuse its register set for tile t+1+STAGES, multiply tile t.
+    // One pipeline step with the register-set index as a compile-time constant (keeps the sets in registers).
+    auto prologue_load = [&]<int S>() {
+        if (S < nk) load_tiles(wreg[S], xreg[S]);
+    };
+    auto step = [&]<int S>(int t) {
+        constexpr int nxt = (S + 1) % STAGES;
+        if (t < nk) {
+            if (t + 1 < nk) {
+                store_tiles((S + 1) & 1, wreg[nxt], xreg[nxt]);
+                if (t + 1 + STAGES < nk) load_tiles(wreg[nxt], xreg[nxt]);
+            }
+            compute(S & 1);
+            __syncthreads();
+        }
+    };
+    prologue_load.template operator()<0>();
+    prologue_load.template operator()<1>();
+    if constexpr (STAGES > 2) {
+        prologue_load.template operator()<2>();
+        prologue_load.template operator()<3>();
+    }
+    store_tiles(0, wreg[0], xreg[0]);
+    if (STAGES < nk) load_tiles(wreg[0], xreg[0]);
+    __syncthreads();
+    for (int t0 = 0; t0 < nk; t0 += STAGES) {
+        step.template operator()<0>(t0);
+        step.template operator()<1>(t0 + 1);
+        if constexpr (STAGES > 2) {
+            step.template operator()<2>(t0 + 2);
+            step.template operator()<3>(t0 + 3);
+        }
     }
 
     // ---- split-K: publish partial sums; the last workgroup of the tile reduces in split order ----
@@ -247,16 +290,19 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
 #pragma unroll
             for (int j = 0; j < TM; ++j)
 #pragma unroll
-                for (int v = 0; v < ACC_REGS; ++v) wsp[((i * TM + j) * ACC_REGS + v) * 256 + tid] = acc[i][j][v];
-        __threadfence();
+                for (int v = 0; v < ACC_REGS; ++v)
+                    __hip_atomic_store(&wsp[((i * TM + j) * ACC_REGS + v) * 256 + tid], acc[i][j][v], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+        // The partial sums are written through to device-coherent memory; wait until every store of every wave
+        // has completed before the arrival counter is bumped.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (tid == 0) {
-            const unsigned old = atomicAdd(&a.counters[tile], 1u);
+            const unsigned old = __hip_atomic_fetch_add(&a.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             s_last = (old == (unsigned)a.split_k - 1u);
         }
         __syncthreads();
         if (!s_last) return;
-        __threadfence();
         const float *wsr = a.ws + (int64_t)tile * a.split_k * NACC * 256;
 #pragma unroll
         for (int i = 0; i < TN; ++i)
@@ -272,9 +318,10 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
                 for (int j = 0; j < TM; ++j)
 #pragma unroll
                     for (int v = 0; v < ACC_REGS; ++v)
-                        acc[i][j][v] += __builtin_nontemporal_load(&p[((i * TM + j) * ACC_REGS + v) * 256 + tid]);
+                        acc[i][j][v] += __hip_atomic_load(&p[((i * TM + j) * ACC_REGS + v) * 256 + tid], __ATOMIC_RELAXED,
+                                                          __HIP_MEMORY_SCOPE_AGENT);
         }
-        if (tid == 0) a.counters[tile] = 0;      // ready for the next launch of this operator
+        if (tid == 0) __hip_atomic_store(&a.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
 
     // ---- epilogue: bias, residual, activation, one rounding, NHWC store -------------------------
@@ -321,22 +368,120 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
         }
 }
 
-template <typename T, int BN, int BM, int WN, int WM, int MF>
+// ---------------------------------------------------------------------------------------------
+// Matrix-vector form for 1x1 / fully connected layers with at most 8 output pixels (batch <= 8): the filter
+// bank is streamed once with 16-byte loads, ROWS output channels per wavefront, the lanes stride along the
+// reduction index and combine through a fixed butterfly of wavefront shuffles.  Bandwidth bound.
+template <typename T>
+__device__ __forceinline__ void unpack8(u32x4 v, float (&f)[8]) {
+    const T *e = reinterpret_cast<const T *>(&v);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f[i] = to_f32(e[i]);
+}
+
+template <typename T, int MB, int ROWS>
+__global__ void __launch_bounds__(256) gemv_kernel(OpArgs a) {
+    const int wave = (int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
+    const int lane = threadIdx.x & 63;
+    const int k0 = wave * ROWS;
+    if (k0 >= a.K) return;                           // whole wave
+    const int J = a.gemm_k;                          // multiple of 8
+    const T *x = (const T *)a.x;
+    const uint16_t *wp = (const uint16_t *)a.w;
+    float acc[ROWS][MB];
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r)
+#pragma unroll
+        for (int m = 0; m < MB; ++m) acc[r][m] = 0.f;
+    constexpr int UNROLL = 4;
+    for (int j0 = lane * 8; j0 < J; j0 += 64 * 8 * UNROLL) {
+        u32x4 wv[UNROLL][ROWS], xv[UNROLL][MB];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int j = j0 + u * 64 * 8;
+            const bool ok = j < J;
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r)      // rows beyond K exist in the padded bank (zeros)
+                wv[u][r] = ok ? *reinterpret_cast<const u32x4 *>(wp + (int64_t)(k0 + r) * a.k_pad + j) : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int m = 0; m < MB; ++m)
+                xv[u][m] = (ok && m < a.N) ? *reinterpret_cast<const u32x4 *>(x + (int64_t)m * J + j) : u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            float xf[MB][8];
+#pragma unroll
+            for (int m = 0; m < MB; ++m) unpack8<T>(xv[u][m], xf[m]);
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) {
+                float wf[8];
+                unpack8<T>(wv[u][r], wf);
+#pragma unroll
+                for (int m = 0; m < MB; ++m)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[r][m] = fmaf(wf[e], xf[m][e], acc[r][m]);
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r)
+#pragma unroll
+        for (int m = 0; m < MB; ++m) {
+            float v = acc[r][m];
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off);
+            acc[r][m] = v;
+        }
+    if (lane == 0) {
+        T *y = (T *)a.y;
+        const T *res = (const T *)a.res;
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            const int k = k0 + r;
+            if (k >= a.K) continue;
+#pragma unroll
+            for (int m = 0; m < MB; ++m) {
+                if (m >= a.N) continue;
+                float f = acc[r][m] + a.bias[k];
+                if (res) f += to_f32(res[(int64_t)m * a.res_ct + k]);
+                f = apply_act(f, a.act);
+                T o;
+                from_f32(f, o);
+                y[(int64_t)m * a.y_ct + a.y_coff + k] = o;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES>
 static void launch_cfg(const OpArgs &a, hipStream_t st) {
     const dim3 grid(a.grid_x), block(256);
     if (a.vec_a)
-        hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, true>), grid, block, 0, st, a);
+        hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, STAGES, true>), grid, block, 0, st, a);
     else
-        hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, false>), grid, block, 0, st, a);
+        hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, 2, false>), grid, block, 0, st, a);
 }
 
 template <typename T>
 static int launch_igemm_typed(const OpArgs &a, hipStream_t st) {
     switch (a.kernel_id) {
-        case K_IGEMM_128x128: launch_cfg<T, 128, 128, 2, 2, 32>(a, st); break;
-        case K_IGEMM_128x64: launch_cfg<T, 128, 64, 2, 2, 32>(a, st); break;
-        case K_IGEMM_64x64: launch_cfg<T, 64, 64, 2, 2, 32>(a, st); break;
-        case K_IGEMM_64x16: launch_cfg<T, 64, 16, 4, 1, 16>(a, st); break;
+        case K_IGEMM_128x128: launch_cfg<T, 128, 128, 2, 2, 32, 2>(a, st); break;
+        case K_IGEMM_128x64: launch_cfg<T, 128, 64, 2, 2, 32, 2>(a, st); break;
+        case K_IGEMM_64x64: launch_cfg<T, 64, 64, 2, 2, 32, 4>(a, st); break;
+        case K_IGEMM_64x16: launch_cfg<T, 64, 16, 4, 1, 16, 4>(a, st); break;
+        case K_GEMV: {
+            const dim3 grid(a.grid_x), block(256);
+            if (a.N <= 1)
+                hipLaunchKernelGGL((gemv_kernel<T, 1, 2>), grid, block, 0, st, a);
+            else if (a.N <= 2)
+                hipLaunchKernelGGL((gemv_kernel<T, 2, 2>), grid, block, 0, st, a);
+            else if (a.N <= 4)
+                hipLaunchKernelGGL((gemv_kernel<T, 4, 2>), grid, block, 0, st, a);
+            else
+                hipLaunchKernelGGL((gemv_kernel<T, 8, 2>), grid, block, 0, st, a);
+            break;
+        }
         default: return (int)hipErrorInvalidValue;
     }
     return (int)hipGetLastError();

@@ -53,9 +53,19 @@ namespace {
 
 bool needs_weights(int kind) { return kind == MT_CONV || kind == MT_DWCONV || kind == MT_FC; }
 
-// Tile and split choice of the implicit GEMM: a pure function of the GEMM shape.
+// Kernel, tile and split choice of a convolution / fully connected layer: a pure function of the GEMM shape.
 void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
     auto cdiv = [](int a, int b) { return (a + b - 1) / b; };
+    p.k_pad = cdiv(gemm_k, IGEMM_BK) * IGEMM_BK;
+    p.grid_y = p.grid_z = 1;
+    p.block = 256;
+    p.split_k = 1;
+    if (M <= 8 && p.H == 1 && p.W == 1 && p.R == 1 && p.S == 1 && p.vec_a) {
+        p.kernel_id = K_GEMV;
+        p.n_pad = cdiv(Kc, 64) * 64;
+        p.grid_x = cdiv(cdiv(Kc, 2), 4);          // two output channels per wavefront, four wavefronts per workgroup
+        return;
+    }
     int bn, bm, kid;
     if (M <= 32) {
         kid = K_IGEMM_64x16; bn = 64; bm = 16;
@@ -67,22 +77,19 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
         kid = K_IGEMM_64x64; bn = 64; bm = 64;
     }
     p.kernel_id = kid;
-    p.k_pad = cdiv(gemm_k, 32) * 32;
     p.n_pad = cdiv(Kc, bn) * bn;
     const int tiles = cdiv(M, bm) * (p.n_pad / bn);
-    const int nkt = p.k_pad / 32;
+    const int nkt = p.k_pad / IGEMM_BK;
     const int target = (kid == K_IGEMM_64x16) ? 2048 : 768;
     int split = 1;
     if (tiles < target / 2) {
-        split = std::min({cdiv(target, tiles), std::max(1, nkt / 4), 64});
+        split = std::min({cdiv(target, tiles), std::max(1, nkt / 2), 64});
         const int per = cdiv(nkt, split);
         split = cdiv(nkt, per);            // no empty split
     }
     p.split_k = std::max(1, split);
     const int total = tiles * p.split_k;
     p.grid_x = cdiv(total, 8) * 8;
-    p.grid_y = p.grid_z = 1;
-    p.block = 256;
 }
 
 int32_t finalize_model(mt_model *m) {
@@ -182,7 +189,7 @@ int32_t finalize_model(mt_model *m) {
     for (OpRec &o : m->ops) {
         const OpArgs &p = o.plan;
         if (needs_weights(p.kind)) {
-            bool igemm = p.kernel_id != K_CONV_DIRECT && (p.kind == MT_CONV || p.kind == MT_FC);
+            bool igemm = is_gemm_kernel(p.kernel_id);
             size_t wcount = igemm ? (size_t)p.n_pad * p.k_pad
                                   : (p.kind == MT_DWCONV ? (size_t)p.C * p.R * p.S : (size_t)p.K * o.plan.R * o.plan.S * p.C);
             if (p.kind == MT_FC && !igemm) wcount = (size_t)p.K * o.in_h * o.in_w * o.in_c;
@@ -283,7 +290,8 @@ int32_t launch_op(const OpArgs &a, hipStream_t st) {
         case K_IGEMM_128x128:
         case K_IGEMM_128x64:
         case K_IGEMM_64x64:
-        case K_IGEMM_64x16: e = launch_igemm(a, st); break;
+        case K_IGEMM_64x16:
+        case K_GEMV: e = launch_igemm(a, st); break;
         default: e = launch_direct(a, st); break;
     }
     if (e != 0) return fail(MT_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString((hipError_t)e));
@@ -365,6 +373,7 @@ const char *mt_kernel_name(int32_t id) {
         case K_MAXPOOL: return "maxpool";
         case K_AVGPOOL: return "avgpool";
         case K_GAP: return "global_avgpool";
+        case K_GEMV: return "gemv";
     }
     return "unknown";
 }
@@ -557,8 +566,7 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
     for (size_t i = 0; i < nops; ++i) {
         OpRec &o = t->model.ops[i];
         OpArgs a = o.plan;
-        const bool igemm = a.kernel_id == K_IGEMM_128x128 || a.kernel_id == K_IGEMM_128x64 ||
-                           a.kernel_id == K_IGEMM_64x64 || a.kernel_id == K_IGEMM_64x16;
+        const bool igemm = is_gemm_kernel(a.kernel_id);
         if (needs_weights(a.kind)) {
             const uint8_t *src = o.w_host.data();
             if (igemm) {

@@ -9,7 +9,7 @@ from gpu_harness import Mix, assert_close
 pytestmark = pytest.mark.gpu
 
 # kernel ids as reported by mt_op_info
-DIRECT, IG128, IG64, IG16, DW, MAXP, AVGP, GAP, IG128x64 = range(9)
+DIRECT, IG128, IG64, IG16, DW, MAXP, AVGP, GAP, IG128x64, GEMV = range(10)
 
 
 def g_conv(dtype, n, h, w, c, k, r, stride=1, pad=0, act="relu", bn=True, res=False, coff=0, ctot=0):
@@ -45,7 +45,9 @@ CONV_CASES = [
     ("ig64_concat_unaligned", dict(n=1, h=8, w=8, c=16, k=10, r=3, pad=1, coff=3, ctot=18), IG64),
     ("ig64_concat_aligned", dict(n=1, h=8, w=8, c=16, k=32, r=1, coff=64, ctot=128), IG64),
     ("ig16_conv_tiny_map", dict(n=2, h=4, w=4, c=64, k=70, r=3, pad=1), IG16),
-    ("ig16_1x1_m1", dict(n=1, h=1, w=1, c=1280, k=1000, r=1, act="none"), IG16),
+    ("gemv_1x1_m1", dict(n=1, h=1, w=1, c=1280, k=1000, r=1, act="none"), GEMV),
+    ("gemv_1x1_m5_res", dict(n=5, h=1, w=1, c=520, k=77, r=1, res=True), GEMV),
+    ("ig16_1x1_m12", dict(n=12, h=1, w=1, c=512, k=100, r=1), IG16),
     ("ig128x64", dict(n=1, h=128, w=128, c=8, k=100, r=3, pad=1), IG128x64),
     ("ig128", dict(n=2, h=182, w=182, c=8, k=128, r=3, pad=1, res=True), IG128),
     ("ig128_first_layer", dict(n=2, h=200, w=200, c=3, k=120, r=3, pad=1), IG128),
@@ -156,5 +158,26 @@ def test_empty_slices_and_single_op_tenant():
             assert tm["n_launches"] == 2
             for t in range(2):
                 assert_close(got[t], ref[t], "f16")
+    finally:
+        mix.close()
+
+
+def test_split_k_is_deterministic_and_counters_reset():
+    """The split-K reduction adds partial sums in split order whatever the arrival order: repeated runs of
+    the same operator, alone and next to a busy neighbour stream, give identical bits."""
+    a = g_conv("f16", 1, 7, 7, 512, 512, 3, pad=1, res=True)
+    b = g_conv("f16", 2, 56, 56, 64, 64, 3, pad=1)
+    mix = Mix([a, b], seed=16)
+    try:
+        assert mix.ctx.op_info(0, 1).split_k > 8
+        ref = mix.oracle()
+        first = None
+        for rep in range(25):
+            sched = mix.ctx.sequential() if rep % 2 else mix.ctx.all_concurrent()
+            got, _ = mix.run(sched)
+            assert_close(got[0], ref[0], "f16")
+            if first is None:
+                first = got
+            assert np.array_equal(first[0], got[0]) and np.array_equal(first[1], got[1])
     finally:
         mix.close()
