@@ -7,6 +7,8 @@
 #include <algorithm>
 #include <chrono>
 #include <cmath>
+#include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <memory>
@@ -257,6 +259,9 @@ struct mt_ctx {
     hipEvent_t ev_stage[MT_MAX_STAGES]{};
     hipEvent_t ev_done[MT_MAX_STAGES][MT_MAX_TENANTS]{};
     hipEvent_t ev_prof[2]{};
+    // Graph executables of destroyed schedules.  They are released only at mt_destroy, after a device-wide
+    // synchronisation: destroying one right after its last launch has crashed inside the HIP runtime.
+    std::vector<hipGraphExec_t> retired_graphs;
 };
 
 struct StagePlan {
@@ -404,6 +409,7 @@ int32_t mt_destroy(mt_ctx *ctx) {
     if (!ctx) return fail(MT_ERR_INVALID_ARG, "ctx is NULL");
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
+    for (hipGraphExec_t g : ctx->retired_graphs) (void)hipGraphExecDestroy(g);
     for (auto &kv : ctx->streams) (void)hipStreamDestroy(kv.second);
     if (ctx->main_stream) (void)hipStreamDestroy(ctx->main_stream);
     if (ctx->ev_start) (void)hipEventDestroy(ctx->ev_start);
@@ -689,7 +695,7 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
 
 int32_t mt_schedule_destroy(mt_schedule *s) {
     if (!s) return fail(MT_ERR_INVALID_ARG, "schedule is NULL");
-    if (s->graph_exec) (void)hipGraphExecDestroy(s->graph_exec);
+    if (s->graph_exec && s->ctx) s->ctx->retired_graphs.push_back(s->graph_exec);
     delete s;
     return MT_OK;
 }
@@ -709,7 +715,7 @@ int32_t mt_run(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *con
         bool same = s->graph_exec && (int)s->cap_in.size() == s->n_tenants;
         for (int i = 0; same && i < s->n_tenants; ++i) same = s->cap_in[i] == inputs[i] && s->cap_out[i] == outputs[i];
         if (!same) {
-            if (s->graph_exec) { (void)hipGraphExecDestroy(s->graph_exec); s->graph_exec = nullptr; }
+            if (s->graph_exec) { ctx->retired_graphs.push_back(s->graph_exec); s->graph_exec = nullptr; }
             hipGraph_t graph = nullptr;
             HIP_TRY(hipStreamBeginCapture(ctx->main_stream, hipStreamCaptureModeRelaxed));
             int32_t rc = issue_schedule(ctx, s, inputs, outputs, &launches);
@@ -795,6 +801,13 @@ double profile_cost(const int32_t *pointers, void *user) {
     ProfileCost *pc = (ProfileCost *)user;
     if (pc->rc != MT_OK) return 1e30;
     mt_schedule *s = nullptr;
+    static const bool trace = std::getenv("MTSCHED_TRACE") != nullptr;
+    if (trace) {
+        std::fprintf(stderr, "[mtsched] profile rho =");
+        for (int i = 0; i < pc->n_tenants * (pc->o->n_stages - 1); ++i) std::fprintf(stderr, " %d", pointers[i]);
+        std::fprintf(stderr, "\n");
+        std::fflush(stderr);
+    }
     pc->rc = mt_schedule_create(pc->ctx, pc->n_tenants, pc->o->n_stages, pointers, nullptr, nullptr, pc->o->issue_order,
                                 pc->o->flags, &s);
     if (pc->rc != MT_OK) return 1e30;
@@ -803,8 +816,10 @@ double profile_cost(const int32_t *pointers, void *user) {
         mt_timings tm;
         pc->rc = mt_run(pc->ctx, s, pc->inputs, pc->outputs, &tm);
         if (r >= pc->o->warmup) sum += tm.makespan_ms;
+        if (trace) { std::fprintf(stderr, "[mtsched]   run %d rc %d %.4f ms\n", r, pc->rc, tm.makespan_ms); std::fflush(stderr); }
     }
     mt_schedule_destroy(s);
+    if (trace) { std::fprintf(stderr, "[mtsched]   destroyed\n"); std::fflush(stderr); }
     return pc->rc == MT_OK ? sum / pc->o->runs : 1e30;
 }
 }  // namespace
