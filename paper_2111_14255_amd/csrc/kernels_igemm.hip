@@ -83,8 +83,8 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     constexpr int X_CHUNKS = (BM + ROW_STEP - 1) / ROW_STEP;
     typedef typename Mma<T, MF>::Acc Acc;
 
-    __shared__ __attribute__((aligned(16))) uint16_t Ws[2][BN * LDK];
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][BM * LDK];
+    __shared__ __attribute__((aligned(16))) uint16_t Ws[2][W_CHUNKS * ROW_STEP * LDK];
+    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][X_CHUNKS * ROW_STEP * LDK];
     __shared__ int s_last;
 
     const int tid = threadIdx.x;
@@ -120,19 +120,19 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     const int kc = tid % CH_ROW;          // chunk column (same for every chunk of this thread)
     const int row0 = tid / CH_ROW;        // first tile row; further chunks are ROW_STEP rows apart
 
-    int64_t xbase[X_CHUNKS];              // element offset of (n, 0, 0, 0)
+    const T *xptr[X_CHUNKS];              // address of input pixel (n, 0, 0, 0) of the chunk's tile row
     int ih0[X_CHUNKS], iw0[X_CHUNKS];
     bool xrow_ok[X_CHUNKS];
 #pragma unroll
     for (int i = 0; i < X_CHUNKS; ++i) {
         const int row = row0 + i * ROW_STEP;
         const int m = m0 + row;
-        xrow_ok[i] = row < BM && m < M;
+        xrow_ok[i] = (row < BM) & (m < M);
         const int mm = xrow_ok[i] ? m : 0;
         const int q = mm % a.Q;
         const int p = (mm / a.Q) % a.P;
         const int n = mm / (a.Q * a.P);
-        xbase[i] = (int64_t)n * a.H * a.W * a.C;
+        xptr[i] = x + (int64_t)n * a.H * a.W * a.C;
         ih0[i] = p * a.sh - a.ph;
         iw0[i] = q * a.sw - a.pw;
     }
@@ -142,77 +142,87 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
         const int row = min(row0 + i * ROW_STEP, BN - 1);
         wrow[i] = wp + (int64_t)(n0 + row) * a.k_pad + (int64_t)kt_begin * BK + kc * 8;
     }
-    // position of this thread's chunk inside the (r, s, c) reduction index, advanced by one tile per load
-    int kr, ks, kcx;
+    // Position of this thread's chunk inside the (r, s, c) reduction index: channel kcx of filter tap krs
+    // (= r * S + s).  One tile further is adv_c channels and adv_rs taps further (plus a carry).  r and s are
+    // recovered with a multiply-high by ceil(2^32 / S), exact for every tap index that can occur.
+    const int adv_c = BK % a.C, adv_rs = BK / a.C;
+    const uint32_t inv_s = (uint32_t)((0x100000000ull + (uint32_t)a.S - 1) / (uint32_t)a.S);   // wraps to 0 for S == 1
+    auto tap_row = [&](int rs) { return a.S == 1 ? rs : (int)__umulhi((uint32_t)rs, inv_s); };
+    int kcx, krs;
     {
         const int j0 = kt_begin * BK + kc * 8;
         kcx = j0 % a.C;
-        const int rs = j0 / a.C;
-        ks = rs % a.S;
-        kr = rs / a.S;
+        krs = j0 / a.C;
     }
     int jbase = kt_begin * BK + kc * 8;   // scalar-gather path
 
     u32x4 wreg[STAGES][W_CHUNKS], xreg[STAGES][X_CHUNKS];
+    uint32_t xok[STAGES];                 // bit i: chunk i of the set holds real data (else padding halo / tail)
 
-    auto load_tiles = [&](u32x4 (&wr)[W_CHUNKS], u32x4 (&xr)[X_CHUNKS]) {
+    // Loads are straight-line code: a chunk in the padding halo reads a valid dummy address and is zeroed when
+    // it is copied to LDS.  With no control flow around the loads the compiler counts them exactly and lets the
+    // newer register sets stay in flight while the oldest one is consumed.
+    auto load_tiles = [&](u32x4 (&wr)[W_CHUNKS], u32x4 (&xr)[X_CHUNKS], uint32_t &ok) {
 #pragma unroll
         for (int i = 0; i < W_CHUNKS; ++i) {
             wr[i] = *reinterpret_cast<const u32x4 *>(wrow[i]);
             wrow[i] += BK;
         }
+        ok = 0;
         if constexpr (VEC_A) {
+            const int kr = tap_row(krs);
+            const int ks = krs - kr * a.S;
 #pragma unroll
             for (int i = 0; i < X_CHUNKS; ++i) {
                 const int ih = ih0[i] + kr, iw = iw0[i] + ks;
-                u32x4 v = u32x4{0u, 0u, 0u, 0u};
-                if (xrow_ok[i] && kr < a.R && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W)
-                    v = *reinterpret_cast<const u32x4 *>(x + xbase[i] + ((int64_t)ih * a.W + iw) * a.C + kcx);
-                xr[i] = v;
+                const bool v = xrow_ok[i] & (kr < a.R) & ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
+                const int ihc = v ? ih : 0, iwc = v ? iw : 0;
+                const int off = (ihc * a.W + iwc) * a.C + kcx;      // inside one image: fits 32 bits
+                xr[i] = *reinterpret_cast<const u32x4 *>(xptr[i] + off);
+                ok |= (v ? 1u : 0u) << i;
             }
-            kcx += BK;
-            while (kcx >= a.C) {
-                kcx -= a.C;
-                if (++ks == a.S) {
-                    ks = 0;
-                    ++kr;
-                }
-            }
+            kcx += adv_c;
+            krs += adv_rs;
+            const bool carry = kcx >= a.C;
+            kcx -= carry ? a.C : 0;
+            krs += carry ? 1 : 0;
         } else {
             // input channels not a multiple of 8 (first layers, C = 3): gather element by element
 #pragma unroll
             for (int i = 0; i < X_CHUNKS; ++i) {
-                uint16_t e[8];
+                uint32_t e[8];
 #pragma unroll
                 for (int t = 0; t < 8; ++t) {
                     const int j = jbase + t;
-                    const int c = j % a.C;
                     const int rs = j / a.C;
-                    const int s = rs % a.S;
-                    const int r = rs / a.S;
-                    const int ih = ih0[i] + r, iw = iw0[i] + s;
-                    uint16_t v = 0;
-                    if (xrow_ok[i] && j < a.gemm_k && ih >= 0 && ih < a.H && iw >= 0 && iw < a.W)
-                        v = reinterpret_cast<const uint16_t *>(x)[xbase[i] + ((int64_t)ih * a.W + iw) * a.C + c];
-                    e[t] = v;
+                    const int c = j - rs * a.C;
+                    const int r = tap_row(rs);
+                    const int sx = rs - r * a.S;
+                    const int ih = ih0[i] + r, iw = iw0[i] + sx;
+                    const bool v = xrow_ok[i] & (j < a.gemm_k) & ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
+                    const int off = v ? (ih * a.W + iw) * a.C + c : 0;
+                    const uint32_t h = reinterpret_cast<const uint16_t *>(xptr[i])[off];
+                    e[t] = v ? h : 0u;
                 }
-                xr[i] = u32x4{e[0] | ((uint32_t)e[1] << 16), e[2] | ((uint32_t)e[3] << 16),
-                              e[4] | ((uint32_t)e[5] << 16), e[6] | ((uint32_t)e[7] << 16)};
+                xr[i] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+                ok |= 1u << i;
             }
             jbase += BK;
         }
     };
 
-    auto store_tiles = [&](int buf, const u32x4 (&wr)[W_CHUNKS], const u32x4 (&xr)[X_CHUNKS]) {
+    // Every thread writes its chunks: tile rows beyond BN / BM land in spare LDS rows that nobody reads.
+    auto store_tiles = [&](int buf, const u32x4 (&wr)[W_CHUNKS], const u32x4 (&xr)[X_CHUNKS], uint32_t ok) {
 #pragma unroll
         for (int i = 0; i < W_CHUNKS; ++i) {
             const int row = row0 + i * ROW_STEP;
-            if (row < BN) *reinterpret_cast<u32x4 *>(&Ws[buf][row * LDK + kc * 8]) = wr[i];
+            *reinterpret_cast<u32x4 *>(&Ws[buf][row * LDK + kc * 8]) = wr[i];
         }
 #pragma unroll
         for (int i = 0; i < X_CHUNKS; ++i) {
             const int row = row0 + i * ROW_STEP;
-            if (row < BM) *reinterpret_cast<u32x4 *>(&Xs[buf][row * LDK + kc * 8]) = xr[i];
+            const u32x4 v = ((ok >> i) & 1u) ? xr[i] : u32x4{0u, 0u, 0u, 0u};
+            *reinterpret_cast<u32x4 *>(&Xs[buf][row * LDK + kc * 8]) = v;
         }
     };
 
@@ -249,18 +259,26 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     // Tile t lives in register set t % STAGES until it is copied to LDS buffer t % 2.
     // Iteration t: copy tile t+1 to LDS, reuse its register set for tile t+1+STAGES, multiply tile t.
     // One pipeline step with the register-set index as a compile-time constant (keeps the sets in registers).
+    // FULL steps run while a further tile is still to be fetched and contain no branch at all.
     auto prologue_load = [&]<int S>() {
-        if (S < nk) load_tiles(wreg[S], xreg[S]);
+        if (S < nk) load_tiles(wreg[S], xreg[S], xok[S]);
     };
-    auto step = [&]<int S>(int t) {
+    auto step = [&]<int S, bool FULL>(int t) {
         constexpr int nxt = (S + 1) % STAGES;
-        if (t < nk) {
-            if (t + 1 < nk) {
-                store_tiles((S + 1) & 1, wreg[nxt], xreg[nxt]);
-                if (t + 1 + STAGES < nk) load_tiles(wreg[nxt], xreg[nxt]);
-            }
+        if constexpr (FULL) {
+            store_tiles((S + 1) & 1, wreg[nxt], xreg[nxt], xok[nxt]);
+            load_tiles(wreg[nxt], xreg[nxt], xok[nxt]);
             compute(S & 1);
             __syncthreads();
+        } else {
+            if (t < nk) {
+                if (t + 1 < nk) {
+                    store_tiles((S + 1) & 1, wreg[nxt], xreg[nxt], xok[nxt]);
+                    if (t + 1 + STAGES < nk) load_tiles(wreg[nxt], xreg[nxt], xok[nxt]);
+                }
+                compute(S & 1);
+                __syncthreads();
+            }
         }
     };
     prologue_load.template operator()<0>();
@@ -269,15 +287,24 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
         prologue_load.template operator()<2>();
         prologue_load.template operator()<3>();
     }
-    store_tiles(0, wreg[0], xreg[0]);
-    if (STAGES < nk) load_tiles(wreg[0], xreg[0]);
+    store_tiles(0, wreg[0], xreg[0], xok[0]);
+    if (STAGES < nk) load_tiles(wreg[0], xreg[0], xok[0]);
     __syncthreads();
-    for (int t0 = 0; t0 < nk; t0 += STAGES) {
-        step.template operator()<0>(t0);
-        step.template operator()<1>(t0 + 1);
+    int t0 = 0;
+    for (; t0 + 2 * STAGES < nk; t0 += STAGES) {       // every step of the group fetches tile t + 1 + STAGES < nk
+        step.template operator()<0, true>(t0);
+        step.template operator()<1, true>(t0 + 1);
         if constexpr (STAGES > 2) {
-            step.template operator()<2>(t0 + 2);
-            step.template operator()<3>(t0 + 3);
+            step.template operator()<2, true>(t0 + 2);
+            step.template operator()<3, true>(t0 + 3);
+        }
+    }
+    for (; t0 < nk; t0 += STAGES) {
+        step.template operator()<0, false>(t0);
+        step.template operator()<1, false>(t0 + 1);
+        if constexpr (STAGES > 2) {
+            step.template operator()<2, false>(t0 + 2);
+            step.template operator()<3, false>(t0 + 3);
         }
     }
 
@@ -310,16 +337,28 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
             for (int j = 0; j < TM; ++j)
 #pragma unroll
                 for (int v = 0; v < ACC_REGS; ++v) acc[i][j][v] = 0.f;
-        for (int zz = 0; zz < a.split_k; ++zz) {
-            const float *p = wsr + (int64_t)zz * NACC * 256;
+        // Loads of RB splits are issued together (they are independent), then added in split order.
+        constexpr int RB = (NACC <= 16) ? 4 : 1;
+        for (int zz0 = 0; zz0 < a.split_k; zz0 += RB) {
+            float part[RB][NACC];
 #pragma unroll
-            for (int i = 0; i < TN; ++i)
+            for (int b = 0; b < RB; ++b) {
+                const float *p = wsr + (int64_t)min(zz0 + b, a.split_k - 1) * NACC * 256;
 #pragma unroll
-                for (int j = 0; j < TM; ++j)
+                for (int e = 0; e < NACC; ++e)
+                    part[b][e] = __hip_atomic_load(&p[e * 256 + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
 #pragma unroll
-                    for (int v = 0; v < ACC_REGS; ++v)
-                        acc[i][j][v] += __hip_atomic_load(&p[((i * TM + j) * ACC_REGS + v) * 256 + tid], __ATOMIC_RELAXED,
-                                                          __HIP_MEMORY_SCOPE_AGENT);
+            for (int b = 0; b < RB; ++b) {
+                if (zz0 + b < a.split_k) {
+#pragma unroll
+                    for (int i = 0; i < TN; ++i)
+#pragma unroll
+                        for (int j = 0; j < TM; ++j)
+#pragma unroll
+                            for (int v = 0; v < ACC_REGS; ++v) acc[i][j][v] += part[b][(i * TM + j) * ACC_REGS + v];
+                }
+            }
         }
         if (tid == 0) __hip_atomic_store(&a.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }

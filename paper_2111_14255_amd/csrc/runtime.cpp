@@ -78,14 +78,25 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
     } else {
         kid = K_IGEMM_64x64; bn = 64; bm = 64;
     }
+    if (const char *e = std::getenv("MTSCHED_TUNE_TILE")) {
+        if (M > 32 && Kc >= 96) {
+            kid = std::atoi(e);
+            bn = kid == K_IGEMM_64x64 ? 64 : 128;
+            bm = kid == K_IGEMM_128x128 ? 128 : 64;
+        }
+    }
     p.kernel_id = kid;
     p.n_pad = cdiv(Kc, bn) * bn;
     const int tiles = cdiv(M, bm) * (p.n_pad / bn);
     const int nkt = p.k_pad / IGEMM_BK;
-    const int target = (kid == K_IGEMM_64x16) ? 2048 : 768;
+    int target = (kid == K_IGEMM_64x16) ? 2048 : 768;
+    int max_split = 8, min_kt = 2;
+    if (const char *e = std::getenv("MTSCHED_TUNE_TARGET")) target = std::atoi(e);
+    if (const char *e = std::getenv("MTSCHED_TUNE_MAXSPLIT")) max_split = std::atoi(e);
+    if (const char *e = std::getenv("MTSCHED_TUNE_MINKT")) min_kt = std::atoi(e);
     int split = 1;
     if (tiles < target / 2) {
-        split = std::min({cdiv(target, tiles), std::max(1, nkt / 2), 64});
+        split = std::min({cdiv(target, tiles), std::max(1, nkt / min_kt), max_split});
         const int per = cdiv(nkt, split);
         split = cdiv(nkt, per);            // no empty split
     }
