@@ -57,6 +57,17 @@ def kernel_rooflines(ctx, inputs, outputs, dtype, repeats):
     return fam
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of the dominant kernel, from the rocprofv3 counter runs summarised under profiles/
+    (FETCH_SIZE and WRITE_SIZE, scaled by what the same counters read for a copy of known size)."""
+    path = os.path.join(ROOT, "profiles", "traffic_%s.json" % workload)
+    if not os.path.exists(path):
+        return None
+    with open(path) as f:
+        rec = json.load(f)
+    return rec.get(kernel, {}).get("hbm_bytes_per_launch")
+
+
 def cpu_baseline(specs, raws, xs):
     """The CPU oracle, as it stands, timed on this host: one forward pass of every tenant of the workload."""
     from oracle import forward as OF, ops as oops
@@ -81,6 +92,9 @@ def main():
     ap.add_argument("--search-candidates", type=int, default=6)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--roofline-only", action="store_true",
+                    help="only the per-kernel timing pass (back-to-back launches of every operator) preceded by a "
+                         "64 MiB elementwise copy that calibrates byte counters; this is the command profiled under rocprofv3")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); tenants would be sharded across GPUs "
@@ -104,6 +118,16 @@ def main():
     outputs = [ctx.make_output(t) for t in range(len(specs))]
     images = sum(m.batch for m in specs)
     lens = ctx.lens()
+
+    if args.roofline_only:
+        cal = torch.ones(32 * 1024 * 1024, dtype=torch.float16, device="cuda")   # 64 MiB read + 64 MiB written
+        cal2 = cal * 1
+        torch.cuda.synchronize()
+        fam = kernel_rooflines(ctx, inputs, outputs, cfg.dtype, repeats=10)
+        print(json.dumps({"workload": cfg.name, "calibration_copy_bytes": int(cal.numel() * 2), "families": fam}))
+        del cal2
+        ctx.close()
+        return
 
     # ---- the three schedules --------------------------------------------------------------
     results = {}
@@ -142,7 +166,7 @@ def main():
                 "frac": achieved / PEAK_HBM_GBS}
     roof["launches_per_step"] = f["launches"]
     roof["avg_launch_us"] = f["ms"] * 1e3 / f["launches"]
-    roof["traffic"] = None
+    roof["traffic"] = measured_traffic(cfg.name, dom)
     roof["families"] = {k: {"launches": v["launches"], "us": round(v["ms"] * 1e3, 2),
                             "TFLOP/s": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] > 0 else 0.0,
                             "GB/s": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] > 0 else 0.0}
