@@ -220,6 +220,11 @@ typedef struct mt_search_opts {
     int32_t warmup;        /* untimed runs per candidate */
     int32_t issue_order;   /* mt_issue_order */
     int32_t flags;         /* schedule flags used while profiling */
+    int32_t seed_baselines; /* non-zero: before Alg. 1 starts, also profile and record (a) the matrix whose pointers all equal
+                              len_i (every operator in stage 1: the stream-parallel baseline) and (b) the even split
+                              (Alg. 1's start point).  An addition to the printed algorithm; with it the returned schedule is
+                              never worse than stream-parallel under the same profiler. */
+    int32_t reserved;
     uint64_t seed;
 } mt_search_opts;
 

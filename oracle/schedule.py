@@ -109,12 +109,21 @@ def sample_row(seed, rnd, model, cand, n_pointers, length):
     return sorted(draw(seed, rnd, model, cand, j) % (length + 1) for j in range(n_pointers))
 
 
-def coordinate_descent(lens, n_pointers, rounds, n_cand, cost, seed, init=None):
+def baseline_seeds(lens, n_pointers):
+    """Extension to Alg. 1: matrices profiled and recorded before the search starts: everything in
+    stage 1 (the stream-parallel baseline written as a pointer matrix) and the even split."""
+    return [[[n] * n_pointers for n in lens], even_split(lens, n_pointers)]
+
+
+def coordinate_descent(lens, n_pointers, rounds, n_cand, cost, seed, init=None, seed_baselines=False):
     """Alg. 1.  `cost(rho)` stands for "profile the latency by multiple runs".
     Returns (best_rho, best_cost, records); records lists every evaluated
     (rho, cost) in evaluation order; the best is the earliest minimum."""
     rho = [list(r) for r in (init if init is not None else even_split(lens, n_pointers))]
     records = []
+    if seed_baselines and n_pointers > 0:
+        for m in baseline_seeds(lens, n_pointers):
+            records.append((m, cost(m)))
     for r in range(rounds):
         for i in range(len(lens)):
             best_row, best_lat = None, None
@@ -131,10 +140,13 @@ def coordinate_descent(lens, n_pointers, rounds, n_cand, cost, seed, init=None):
     return records[best][0], records[best][1], records
 
 
-def random_search(lens, n_pointers, evaluations, cost, seed):
+def random_search(lens, n_pointers, evaluations, cost, seed, seed_baselines=False):
     """Random search: whole matrices, independent unsorted draws, infeasible ones skipped."""
     records = []
     skipped = 0
+    if seed_baselines and n_pointers > 0:
+        for m in baseline_seeds(lens, n_pointers):
+            records.append((m, cost(m)))
     for e in range(evaluations):
         rho = [[draw(seed, e, i, 0x52, j) % (lens[i] + 1) for j in range(n_pointers)]
                for i in range(len(lens))]

@@ -242,11 +242,11 @@ class Context:
         return [ms[i] for i in range(n)]
 
     def search(self, inputs, outputs, n_stages, rounds=2, candidates=6, runs=5, warmup=1, seed=1,
-               algo=B.MT_SEARCH_COORDINATE, order=B.MT_ISSUE_BFS, flags=0):
+               algo=B.MT_SEARCH_COORDINATE, order=B.MT_ISSUE_BFS, flags=0, seed_baselines=True):
         n = self.num_tenants()
         P = n_stages - 1
-        opts = B.mt_search_opts(algo, n_stages, rounds, candidates, runs, warmup, order, flags, seed)
-        cap = rounds * n * candidates
+        opts = B.mt_search_opts(algo, n_stages, rounds, candidates, runs, warmup, order, flags, 1 if seed_baselines else 0, 0, seed)
+        cap = rounds * n * candidates + 2
         best = (C.c_int32 * max(1, n * P))()
         best_cost = C.c_double()
         recp = (C.c_int32 * max(1, cap * n * P))()

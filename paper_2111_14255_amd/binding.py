@@ -53,7 +53,7 @@ class mt_timings(C.Structure):
 class mt_search_opts(C.Structure):
     _fields_ = [("algo", C.c_int32), ("n_stages", C.c_int32), ("rounds", C.c_int32), ("candidates", C.c_int32),
                 ("runs", C.c_int32), ("warmup", C.c_int32), ("issue_order", C.c_int32), ("flags", C.c_int32),
-                ("seed", C.c_uint64)]
+                ("seed_baselines", C.c_int32), ("reserved", C.c_int32), ("seed", C.c_uint64)]
 
 
 mt_cost_fn = C.CFUNCTYPE(C.c_double, C.POINTER(C.c_int32), C.c_void_p)

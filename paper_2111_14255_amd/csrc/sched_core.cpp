@@ -139,6 +139,13 @@ int32_t search_pointers(int32_t n_tenants, const int32_t *lens, const mt_search_
     Recorder rec{rec_pointers, rec_cost, max_records, 0, n_tenants * P, {}, 0.0, false};
     std::vector<int32_t> rho(width, 0), cand(width, 0), row(std::max(1, P));
 
+    if (o->seed_baselines && P > 0) {
+        for (int i = 0; i < n_tenants; ++i)
+            for (int j = 0; j < P; ++j) cand[i * P + j] = lens[i];     // everything in stage 1
+        rec.add(cand.data(), cost(cand.data(), user));
+        even_split(n_tenants, lens, P, cand.data());
+        rec.add(cand.data(), cost(cand.data(), user));
+    }
     if (o->algo == MT_SEARCH_COORDINATE) {
         even_split(n_tenants, lens, P, rho.data());
         for (int r = 0; r < o->rounds; ++r)

@@ -67,3 +67,14 @@ def test_cfg2_r18_vgg16_mbv2_fp16():
 def test_cfg4_unbalanced_bf16():
     mix = check_config("cfg4")
     mix.close()
+
+
+def test_cfg3_batch8_fp16():
+    mix = check_config("cfg3")
+    mix.close()
+
+
+def test_cfg5_eight_resnet50_batch16_bf16_cu_masks():
+    # 8 tenants on 8 disjoint 32-CU shares, 8 stages
+    mix = check_config("cfg5", [lambda ctx, lens: ctx.schedule(even_split(lens, 8), 8, cu_share=[32] * 8, label="cu-shares-8x32")])
+    mix.close()

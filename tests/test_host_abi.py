@@ -89,10 +89,10 @@ def test_issue_order_examples_and_oracle():
             assert lib_issue(stage, conc, order) == S.issue_order(stage, conc, name)
 
 
-def lib_search(lens, n_stages, rounds, cands, seed, algo, cost):
+def lib_search(lens, n_stages, rounds, cands, seed, algo, cost, seed_baselines=0):
     n, P = len(lens), n_stages - 1
-    opts = B.mt_search_opts(algo, n_stages, rounds, cands, 1, 0, 0, 0, seed)
-    cap = rounds * n * cands
+    opts = B.mt_search_opts(algo, n_stages, rounds, cands, 1, 0, 0, 0, seed_baselines, 0, seed)
+    cap = rounds * n * cands + 2
     best = (I32 * max(1, n * P))()
     bc = C.c_double()
     recp = (I32 * max(1, cap * n * P))()
@@ -123,6 +123,17 @@ def test_coordinate_descent_matches_oracle():
         assert recs == [(r, c2) for r, c2 in orecs]
         assert rho == orho and c == oc
         assert len(recs) == 3 * 3 * 4
+
+
+def test_search_with_baseline_seeds_matches_oracle():
+    lens = [23, 21, 54]
+    target = [[23, 23, 23], [21, 21, 21], [50, 52, 54]]       # close to "everything in stage 1"
+    for algo, fn in ((B.MT_SEARCH_COORDINATE, lambda: S.coordinate_descent(lens, 3, 2, 3, _cost(target), 5, seed_baselines=True)[:3]),
+                     (B.MT_SEARCH_RANDOM, lambda: S.random_search(lens, 3, 2 * 3 * 3, _cost(target), 5, seed_baselines=True)[:3])):
+        rho, c, recs = lib_search(lens, 4, 2, 3, 5, algo, _cost(target), seed_baselines=1)
+        orho, oc, orecs = fn()
+        assert recs == orecs and rho == orho and c == oc
+        assert recs[0][0] == [[23] * 3, [21] * 3, [54] * 3] and recs[1][0] == S.even_split(lens, 3)
 
 
 def test_random_search_matches_oracle():
