@@ -144,6 +144,16 @@ def main():
         results["searched" + suffix]["pointers"] = rho
         results["searched" + suffix]["search_seconds"] = search_s
         results["searched" + suffix]["search_evaluations"] = len(records)
+    # searched pointers plus searched per-tenant CU shares (stream CU masks; not available under graph replay)
+    t0 = time.perf_counter()
+    rho, cost, records, shares = ctx.search(inputs, outputs, cfg.n_stages, rounds=args.search_rounds,
+                                            candidates=args.search_candidates, runs=5, warmup=1, seed=cfg.seed,
+                                            cu_share_rounds=1)
+    search_s = time.perf_counter() - t0
+    sched = ctx.schedule(rho, cfg.n_stages, cu_share=shares)
+    results["searched+cu_share"] = time_schedule(ctx, torch, sched, inputs, outputs, args.warmup, args.steps)
+    results["searched+cu_share"].update({"pointers": rho, "cu_share": shares, "search_seconds": search_s,
+                                         "search_evaluations": len(records)})
     for k, r in results.items():
         base = results["sequential" + ("+graph" if k.endswith("+graph") else "")]
         r["img_per_s"] = images / (r["wall_ms_per_step"] * 1e-3)

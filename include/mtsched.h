@@ -224,7 +224,7 @@ typedef struct mt_search_opts {
                               len_i (every operator in stage 1: the stream-parallel baseline) and (b) the even split
                               (Alg. 1's start point).  An addition to the printed algorithm; with it the returned schedule is
                               never worse than stream-parallel under the same profiler. */
-    int32_t reserved;
+    int32_t cu_share_rounds; /* mt_search only: > 0 runs that many rounds of the CU-share descent (below) after the pointer search */
     uint64_t seed;
 } mt_search_opts;
 
@@ -239,9 +239,20 @@ int32_t mt_search_pointers(int32_t n_tenants, const int32_t *lens, const mt_sear
                            mt_cost_fn cost, void *user, int32_t *best_pointers, double *best_cost,
                            int32_t *rec_pointers, double *rec_cost, int32_t max_records, int32_t *n_records);
 
-/* The same search with the profiled makespan of mt_run as cost, all tenants on their own stream. */
+/* Per-tenant CU share as one more coordinate per tenant (an extension; the paper leaves resource sharing to the
+ * hardware, Sec. III-A(b)).  Host only, any cost function.  Start: every share 0 (= all units).  Each round visits the
+ * tenants in order; for a tenant the candidates k * cu_count / 8, k = 1..7, are evaluated with the other shares fixed,
+ * and the candidate replaces the tenant's share if its cost is lower than the best cost so far.
+ * share_cost: cost of a share vector (host [n_tenants]).  best_share: host [n_tenants]; *best_cost: in = cost of
+ * all-zero shares, out = best cost found. */
+typedef double (*mt_share_cost_fn)(const int32_t *cu_share, void *user);
+int32_t mt_search_cu_share(int32_t n_tenants, int32_t cu_count, int32_t rounds, mt_share_cost_fn share_cost, void *user,
+                           int32_t *best_share, double *best_cost);
+
+/* The same searches with the profiled makespan of mt_run as cost, all tenants on their own stream.
+ * best_cu_share: host [n_tenants] or NULL; filled with zeros unless opts->cu_share_rounds > 0. */
 int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *inputs, void *const *outputs,
-                  int32_t *best_pointers, double *best_cost,
+                  int32_t *best_pointers, int32_t *best_cu_share, double *best_cost,
                   int32_t *rec_pointers, double *rec_cost, int32_t max_records, int32_t *n_records);
 
 #ifdef __cplusplus

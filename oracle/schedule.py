@@ -158,3 +158,22 @@ def random_search(lens, n_pointers, evaluations, cost, seed, seed_baselines=Fals
         return None, None, records, skipped
     best = min(range(len(records)), key=lambda j: (records[j][1], j))
     return records[best][0], records[best][1], records, skipped
+
+
+def cu_share_descent(n_tenants, cu_count, rounds, cost, start_cost):
+    """Extension: per-tenant CU share as one more coordinate.  Start with all shares 0 (= every unit); per
+    round and tenant, try k * cu_count // 8 for k = 1..7 with the other shares fixed; a candidate replaces
+    the tenant's share when its cost is lower than the best so far."""
+    cur = [0] * n_tenants
+    best = start_cost
+    for _ in range(rounds):
+        for i in range(n_tenants):
+            for k in range(1, 8):
+                cand = list(cur)
+                cand[i] = k * cu_count // 8
+                if cand[i] == cur[i]:
+                    continue
+                c = cost(cand)
+                if c < best:
+                    best, cur = c, cand
+    return cur, best

@@ -4,7 +4,13 @@ Every computation on the forward path happens inside libmtsched.so; this module 
 PyTorch owns the device memory (arenas, inputs, outputs) and hands raw pointers to the library.
 """
 import ctypes as C
+import os
+
 import numpy as np
+
+# One hardware queue per tenant stream plus the main stream (the HIP default of 4 would make 8 tenants share
+# queues).  Must be in the environment before the HIP runtime initialises.
+os.environ.setdefault("GPU_MAX_HW_QUEUES", "16")
 
 from . import binding as B
 
@@ -242,21 +248,25 @@ class Context:
         return [ms[i] for i in range(n)]
 
     def search(self, inputs, outputs, n_stages, rounds=2, candidates=6, runs=5, warmup=1, seed=1,
-               algo=B.MT_SEARCH_COORDINATE, order=B.MT_ISSUE_BFS, flags=0, seed_baselines=True):
+               algo=B.MT_SEARCH_COORDINATE, order=B.MT_ISSUE_BFS, flags=0, seed_baselines=True, cu_share_rounds=0):
+        """Returns (pointer matrix, best cost, records) and, with cu_share_rounds > 0, also the CU shares."""
         n = self.num_tenants()
         P = n_stages - 1
-        opts = B.mt_search_opts(algo, n_stages, rounds, candidates, runs, warmup, order, flags, 1 if seed_baselines else 0, 0, seed)
+        opts = B.mt_search_opts(algo, n_stages, rounds, candidates, runs, warmup, order, flags, 1 if seed_baselines else 0, cu_share_rounds, seed)
         cap = rounds * n * candidates + 2
         best = (C.c_int32 * max(1, n * P))()
         best_cost = C.c_double()
+        shares = (C.c_int32 * n)()
         recp = (C.c_int32 * max(1, cap * n * P))()
         recc = (C.c_double * cap)()
         nrec = C.c_int32()
         ins = (C.c_void_p * n)(*[t.data_ptr() for t in inputs])
         outs = (C.c_void_p * n)(*[t.data_ptr() for t in outputs])
-        B.check(self.lib.mt_search(self.h, C.byref(opts), ins, outs, best, C.byref(best_cost), recp, recc, cap, C.byref(nrec)))
+        B.check(self.lib.mt_search(self.h, C.byref(opts), ins, outs, best, shares, C.byref(best_cost), recp, recc, cap, C.byref(nrec)))
         rho = [[best[i * P + j] for j in range(P)] for i in range(n)]
         records = [([[recp[(k * n + i) * P + j] for j in range(P)] for i in range(n)], recc[k]) for k in range(min(nrec.value, cap))]
+        if cu_share_rounds > 0:
+            return rho, best_cost.value, records, [shares[i] for i in range(n)]
         return rho, best_cost.value, records
 
     def close(self):

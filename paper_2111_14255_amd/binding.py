@@ -53,10 +53,11 @@ class mt_timings(C.Structure):
 class mt_search_opts(C.Structure):
     _fields_ = [("algo", C.c_int32), ("n_stages", C.c_int32), ("rounds", C.c_int32), ("candidates", C.c_int32),
                 ("runs", C.c_int32), ("warmup", C.c_int32), ("issue_order", C.c_int32), ("flags", C.c_int32),
-                ("seed_baselines", C.c_int32), ("reserved", C.c_int32), ("seed", C.c_uint64)]
+                ("seed_baselines", C.c_int32), ("cu_share_rounds", C.c_int32), ("seed", C.c_uint64)]
 
 
 mt_cost_fn = C.CFUNCTYPE(C.c_double, C.POINTER(C.c_int32), C.c_void_p)
+mt_share_cost_fn = C.CFUNCTYPE(C.c_double, C.POINTER(C.c_int32), C.c_void_p)
 
 _vp, _i32, _i64, _sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
 _pi32, _pf, _pd = C.POINTER(C.c_int32), C.POINTER(C.c_float), C.POINTER(C.c_double)
@@ -90,7 +91,8 @@ SIGNATURES = {
     "mt_run": (_i32, [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(mt_timings)]),
     "mt_profile_ops": (_i32, [_vp, _i32, _vp, _vp, _i32, _pf]),
     "mt_search_pointers": (_i32, [_i32, _pi32, C.POINTER(mt_search_opts), mt_cost_fn, _vp, _pi32, _pd, _pi32, _pd, _i32, _pi32]),
-    "mt_search": (_i32, [_vp, C.POINTER(mt_search_opts), C.POINTER(_vp), C.POINTER(_vp), _pi32, _pd, _pi32, _pd, _i32, _pi32]),
+    "mt_search_cu_share": (_i32, [_i32, _i32, _i32, mt_share_cost_fn, _vp, _pi32, _pd]),
+    "mt_search": (_i32, [_vp, C.POINTER(mt_search_opts), C.POINTER(_vp), C.POINTER(_vp), _pi32, _pi32, _pd, _pi32, _pd, _i32, _pi32]),
 }
 
 _lib = None

@@ -24,6 +24,9 @@ int32_t search_pointers(int32_t n_tenants, const int32_t *lens, const mt_search_
                         int32_t *best_pointers, double *best_cost, int32_t *rec_pointers, double *rec_cost,
                         int32_t max_records, int32_t *n_records);
 
+int32_t search_cu_share(int32_t n_tenants, int32_t cu_count, int32_t rounds, mt_share_cost_fn cost, void *user,
+                        int32_t *best_share, double *best_cost);
+
 constexpr int IGEMM_BK = 64;   // reduction elements per implicit-GEMM tile; packed filter rows are padded to it
 
 inline bool is_gemm_kernel(int32_t id);
@@ -66,7 +69,7 @@ struct OpArgs {
     int32_t k_pad;               // packed weight row length (multiple of the k tile)
     int32_t n_pad;               // packed weight rows (multiple of the channel tile)
     int32_t split_k;
-    int32_t vec_a;               // 1: input channels are a multiple of 8 (16-byte im2col loads)
+    int32_t vec_a;               // im2col gather mode: 0 element-wise, 1 16-byte chunks (C % 8 == 0), 2 tile inside one tap (C % 64 == 0)
     int32_t grid_x, grid_y, grid_z, block;
     const void *x;
     const void *w;

@@ -33,6 +33,8 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16-byte registe
 constexpr int BK = IGEMM_BK;     // reduction elements per LDS tile
 constexpr int LDK = BK + 8;      // padded LDS row (144 bytes: 16-byte reads of a wave fall in distinct banks)
 constexpr int NXCD = 8;
+constexpr int A_SCALAR = 0, A_VEC8 = 1, A_UNIFORM = 2;
+constexpr uint32_t OOB_OFFSET = 0x80000000u;   // beyond any tensor: buffer loads return zeros
 
 template <typename T, int MF>
 struct Mma;
@@ -67,7 +69,15 @@ struct Mma<bf16, 16> {
 
 // BN: output channels per workgroup, BM: pixels per workgroup, WN x WM: wave grid (4 waves), MF: MFMA edge,
 // STAGES: reduction tiles whose global loads are in flight (register sets), even.
-template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES, bool VEC_A>
+// AMODE: how a tile row of the im2col matrix is gathered:
+//   A_UNIFORM  C % 64 == 0 and R*S <= 64: a 64-deep tile lies inside one filter tap, so the tap walks in
+//              scalar registers and a lane only selects between its pixel's offset and "out of range"
+//   A_VEC8     C % 8 == 0: every lane tracks the tap of its own 8-channel chunk
+//   A_SCALAR   any C (first layers, C = 3): element-wise gather
+// Filter tiles and (except A_SCALAR) im2col chunks are fetched with buffer loads: offsets are 32 bit, the
+// tile walk is a scalar offset, and a chunk in the padding halo is given an out-of-range offset, for which
+// the hardware returns zeros: no select and no 64-bit address arithmetic in the loop.
+template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES, int AMODE>
 __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     static_assert(WN * WM == 4, "four waves per workgroup");
     static_assert(STAGES == 2 || STAGES == 4, "register sets rotate with the two LDS buffers");
@@ -81,6 +91,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     constexpr int ROW_STEP = 256 / CH_ROW;                 // tile rows covered by one pass of the workgroup
     constexpr int W_CHUNKS = (BN + ROW_STEP - 1) / ROW_STEP;
     constexpr int X_CHUNKS = (BM + ROW_STEP - 1) / ROW_STEP;
+    constexpr bool FRAG_PREFETCH = KSTEPS * (TN + TM) <= 8;   // two fragment sets fit the register budget
     typedef typename Mma<T, MF>::Acc Acc;
 
     __shared__ __attribute__((aligned(16))) uint16_t Ws[2][W_CHUNKS * ROW_STEP * LDK];
@@ -120,7 +131,12 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     const int kc = tid % CH_ROW;          // chunk column (same for every chunk of this thread)
     const int row0 = tid / CH_ROW;        // first tile row; further chunks are ROW_STEP rows apart
 
-    const T *xptr[X_CHUNKS];              // address of input pixel (n, 0, 0, 0) of the chunk's tile row
+    const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<T *>(x), 0, (int)((int64_t)a.N * a.H * a.W * a.C * (int)sizeof(T)), 0x00027000);
+    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t *>(wp), 0, (int)((int64_t)a.n_pad * a.k_pad * 2), 0x00027000);
+
+    int img_off[X_CHUNKS];                // element offset of input pixel (n, 0, 0, 0) of the chunk's tile row
     int ih0[X_CHUNKS], iw0[X_CHUNKS];
     bool xrow_ok[X_CHUNKS];
 #pragma unroll
@@ -132,54 +148,89 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
         const int q = mm % a.Q;
         const int p = (mm / a.Q) % a.P;
         const int n = mm / (a.Q * a.P);
-        xptr[i] = x + (int64_t)n * a.H * a.W * a.C;
+        img_off[i] = n * a.H * a.W * a.C;
         ih0[i] = p * a.sh - a.ph;
         iw0[i] = q * a.sw - a.pw;
     }
-    const uint16_t *wrow[W_CHUNKS];
+    uint32_t wvoff[W_CHUNKS];             // byte offset of the chunk inside the packed filter bank, tile 0
 #pragma unroll
     for (int i = 0; i < W_CHUNKS; ++i) {
         const int row = min(row0 + i * ROW_STEP, BN - 1);
-        wrow[i] = wp + (int64_t)(n0 + row) * a.k_pad + (int64_t)kt_begin * BK + kc * 8;
+        wvoff[i] = (uint32_t)(((n0 + row) * a.k_pad + kc * 8) * 2);
     }
-    // Position of this thread's chunk inside the (r, s, c) reduction index: channel kcx of filter tap krs
-    // (= r * S + s).  One tile further is adv_c channels and adv_rs taps further (plus a carry).  r and s are
-    // recovered with a multiply-high by ceil(2^32 / S), exact for every tap index that can occur.
+    uint32_t wsoff = (uint32_t)(kt_begin * BK * 2);     // scalar: byte offset of the current tile in a filter row
+
+    // A_UNIFORM: the tap (r, s) and the channel base of the current tile are wave-uniform.
+    int u_r = 0, u_s = 0, u_tap = 0, u_cb = 0;
+    uint64_t tapmask[X_CHUNKS];           // bit r*S+s: the tap reads inside the image for this chunk's pixel
+    int rowoff[X_CHUNKS];                 // byte offset of (n, ih0, iw0, kc*8)
+    // A_VEC8 / A_SCALAR: position of this thread's chunk inside the (r, s, c) reduction index.
     const int adv_c = BK % a.C, adv_rs = BK / a.C;
     const uint32_t inv_s = (uint32_t)((0x100000000ull + (uint32_t)a.S - 1) / (uint32_t)a.S);   // wraps to 0 for S == 1
     auto tap_row = [&](int rs) { return a.S == 1 ? rs : (int)__umulhi((uint32_t)rs, inv_s); };
-    int kcx, krs;
-    {
+    int kcx = 0, krs = 0;
+    int jbase = kt_begin * BK + kc * 8;
+    if constexpr (AMODE == A_UNIFORM) {
+        const int j0 = kt_begin * BK;
+        u_cb = j0 % a.C;
+        u_tap = j0 / a.C;
+        u_r = u_tap / a.S;
+        u_s = u_tap - u_r * a.S;
+#pragma unroll
+        for (int i = 0; i < X_CHUNKS; ++i) {
+            uint64_t mask = 0;
+            for (int r = 0; r < a.R; ++r)
+                for (int sx = 0; sx < a.S; ++sx) {
+                    const bool v = xrow_ok[i] & ((uint32_t)(ih0[i] + r) < (uint32_t)a.H) & ((uint32_t)(iw0[i] + sx) < (uint32_t)a.W);
+                    mask |= (uint64_t)(v ? 1u : 0u) << (r * a.S + sx);
+                }
+            tapmask[i] = mask;
+            rowoff[i] = (img_off[i] + (ih0[i] * a.W + iw0[i]) * a.C + kc * 8) * 2;
+        }
+    } else {
         const int j0 = kt_begin * BK + kc * 8;
         kcx = j0 % a.C;
         krs = j0 / a.C;
     }
-    int jbase = kt_begin * BK + kc * 8;   // scalar-gather path
 
     u32x4 wreg[STAGES][W_CHUNKS], xreg[STAGES][X_CHUNKS];
-    uint32_t xok[STAGES];                 // bit i: chunk i of the set holds real data (else padding halo / tail)
 
-    // Loads are straight-line code: a chunk in the padding halo reads a valid dummy address and is zeroed when
-    // it is copied to LDS.  With no control flow around the loads the compiler counts them exactly and lets the
-    // newer register sets stay in flight while the oldest one is consumed.
-    auto load_tiles = [&](u32x4 (&wr)[W_CHUNKS], u32x4 (&xr)[X_CHUNKS], uint32_t &ok) {
+    // Straight-line loads (no control flow), so the compiler counts them exactly and lets the newer register
+    // sets stay in flight while the oldest one is consumed.
+    auto load_tiles = [&](u32x4 (&wr)[W_CHUNKS], u32x4 (&xr)[X_CHUNKS]) {
 #pragma unroll
-        for (int i = 0; i < W_CHUNKS; ++i) {
-            wr[i] = *reinterpret_cast<const u32x4 *>(wrow[i]);
-            wrow[i] += BK;
-        }
-        ok = 0;
-        if constexpr (VEC_A) {
+        for (int i = 0; i < W_CHUNKS; ++i)
+            wr[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, wvoff[i], wsoff, 0);
+        wsoff += BK * 2;
+        if constexpr (AMODE == A_UNIFORM) {
+            const int tapoff = ((u_r * a.W + u_s) * a.C + u_cb) * 2;        // scalar
+            const bool tap_ok = u_tap < a.R * a.S;
+            const int sh = tap_ok ? u_tap : 0;
+#pragma unroll
+            for (int i = 0; i < X_CHUNKS; ++i) {
+                const bool v = tap_ok & (((tapmask[i] >> sh) & 1ull) != 0);
+                const uint32_t voff = v ? (uint32_t)(rowoff[i] + tapoff) : OOB_OFFSET;
+                xr[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, voff, 0, 0);
+            }
+            u_cb += BK;
+            if (u_cb >= a.C) {              // scalar branch-free updates (uniform values)
+                u_cb = 0;
+                ++u_tap;
+                ++u_s;
+                if (u_s == a.S) {
+                    u_s = 0;
+                    ++u_r;
+                }
+            }
+        } else if constexpr (AMODE == A_VEC8) {
             const int kr = tap_row(krs);
             const int ks = krs - kr * a.S;
 #pragma unroll
             for (int i = 0; i < X_CHUNKS; ++i) {
                 const int ih = ih0[i] + kr, iw = iw0[i] + ks;
                 const bool v = xrow_ok[i] & (kr < a.R) & ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
-                const int ihc = v ? ih : 0, iwc = v ? iw : 0;
-                const int off = (ihc * a.W + iwc) * a.C + kcx;      // inside one image: fits 32 bits
-                xr[i] = *reinterpret_cast<const u32x4 *>(xptr[i] + off);
-                ok |= (v ? 1u : 0u) << i;
+                const uint32_t voff = v ? (uint32_t)((img_off[i] + (ih * a.W + iw) * a.C + kcx) * 2) : OOB_OFFSET;
+                xr[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, voff, 0, 0);
             }
             kcx += adv_c;
             krs += adv_rs;
@@ -188,6 +239,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
             krs += carry ? 1 : 0;
         } else {
             // input channels not a multiple of 8 (first layers, C = 3): gather element by element
+            const uint16_t *xs = reinterpret_cast<const uint16_t *>(x);
 #pragma unroll
             for (int i = 0; i < X_CHUNKS; ++i) {
                 uint32_t e[8];
@@ -200,19 +252,18 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
                     const int sx = rs - r * a.S;
                     const int ih = ih0[i] + r, iw = iw0[i] + sx;
                     const bool v = xrow_ok[i] & (j < a.gemm_k) & ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
-                    const int off = v ? (ih * a.W + iw) * a.C + c : 0;
-                    const uint32_t h = reinterpret_cast<const uint16_t *>(xptr[i])[off];
+                    const int off = v ? img_off[i] + (ih * a.W + iw) * a.C + c : 0;
+                    const uint32_t h = xs[off];
                     e[t] = v ? h : 0u;
                 }
                 xr[i] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
-                ok |= 1u << i;
             }
             jbase += BK;
         }
     };
 
     // Every thread writes its chunks: tile rows beyond BN / BM land in spare LDS rows that nobody reads.
-    auto store_tiles = [&](int buf, const u32x4 (&wr)[W_CHUNKS], const u32x4 (&xr)[X_CHUNKS], uint32_t ok) {
+    auto store_tiles = [&](int buf, const u32x4 (&wr)[W_CHUNKS], const u32x4 (&xr)[X_CHUNKS]) {
 #pragma unroll
         for (int i = 0; i < W_CHUNKS; ++i) {
             const int row = row0 + i * ROW_STEP;
@@ -221,8 +272,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
 #pragma unroll
         for (int i = 0; i < X_CHUNKS; ++i) {
             const int row = row0 + i * ROW_STEP;
-            const u32x4 v = ((ok >> i) & 1u) ? xr[i] : u32x4{0u, 0u, 0u, 0u};
-            *reinterpret_cast<u32x4 *>(&Xs[buf][row * LDK + kc * 8]) = v;
+            *reinterpret_cast<u32x4 *>(&Xs[buf][row * LDK + kc * 8]) = xr[i];
         }
     };
 
@@ -237,49 +287,44 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     const int frag_row = lane % MF;
     const int frag_k = (lane / MF) * 8;
 
-    auto compute = [&](int buf) {
+    // MFMA operand fragments of one LDS tile.
+    struct Frags {
+        u32x4 a[KSTEPS][TN], b[KSTEPS][TM];
+    };
+    auto load_frags = [&](int buf, Frags &f) {
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk) {
             const int koff = kk * (KLANES * 8) + frag_k;
-            u32x4 af[TN], bf[TM];
 #pragma unroll
             for (int i = 0; i < TN; ++i)
-                af[i] = *reinterpret_cast<const u32x4 *>(&Ws[buf][(wn * SUBN + i * MF + frag_row) * LDK + koff]);
+                f.a[kk][i] = *reinterpret_cast<const u32x4 *>(&Ws[buf][(wn * SUBN + i * MF + frag_row) * LDK + koff]);
 #pragma unroll
             for (int j = 0; j < TM; ++j)
-                bf[j] = *reinterpret_cast<const u32x4 *>(&Xs[buf][(wm * SUBM + j * MF + frag_row) * LDK + koff]);
+                f.b[kk][j] = *reinterpret_cast<const u32x4 *>(&Xs[buf][(wm * SUBM + j * MF + frag_row) * LDK + koff]);
+        }
+    };
+    // Small wave tiles alternate between two accumulators so that consecutive MFMAs do not wait for each
+    // other; the two are added once at the end (fixed order).
+    constexpr bool TWO_ACC = (TN * TM == 1) && (KSTEPS % 2 == 0);
+    Acc acc2;
+#pragma unroll
+    for (int v = 0; v < ACC_REGS; ++v) acc2[v] = 0.f;
+    auto mma = [&](const Frags &f) {
+#pragma unroll
+        for (int kk = 0; kk < KSTEPS; ++kk)
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
-                for (int j = 0; j < TM; ++j) acc[i][j] = Mma<T, MF>::run(af[i], bf[j], acc[i][j]);
-        }
+                for (int j = 0; j < TM; ++j) {
+                    if (TWO_ACC && (kk & 1))
+                        acc2 = Mma<T, MF>::run(f.a[kk][i], f.b[kk][j], acc2);
+                    else
+                        acc[i][j] = Mma<T, MF>::run(f.a[kk][i], f.b[kk][j], acc[i][j]);
+                }
     };
 
-    // ---- software pipeline ---------------------------------------------------------------------
-    // Tile t lives in register set t % STAGES until it is copied to LDS buffer t % 2.
-    // Iteration t: copy tile t+1 to LDS, reuse its register set for tile t+1+STAGES, multiply tile t.
-    // One pipeline step with the register-set index as a compile-time constant (keeps the sets in registers).
-    // FULL steps run while a further tile is still to be fetched and contain no branch at all.
     auto prologue_load = [&]<int S>() {
-        if (S < nk) load_tiles(wreg[S], xreg[S], xok[S]);
-    };
-    auto step = [&]<int S, bool FULL>(int t) {
-        constexpr int nxt = (S + 1) % STAGES;
-        if constexpr (FULL) {
-            store_tiles((S + 1) & 1, wreg[nxt], xreg[nxt], xok[nxt]);
-            load_tiles(wreg[nxt], xreg[nxt], xok[nxt]);
-            compute(S & 1);
-            __syncthreads();
-        } else {
-            if (t < nk) {
-                if (t + 1 < nk) {
-                    store_tiles((S + 1) & 1, wreg[nxt], xreg[nxt], xok[nxt]);
-                    if (t + 1 + STAGES < nk) load_tiles(wreg[nxt], xreg[nxt], xok[nxt]);
-                }
-                compute(S & 1);
-                __syncthreads();
-            }
-        }
+        if (S < nk) load_tiles(wreg[S], xreg[S]);
     };
     prologue_load.template operator()<0>();
     prologue_load.template operator()<1>();
@@ -287,25 +332,88 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
         prologue_load.template operator()<2>();
         prologue_load.template operator()<3>();
     }
-    store_tiles(0, wreg[0], xreg[0], xok[0]);
-    if (STAGES < nk) load_tiles(wreg[0], xreg[0], xok[0]);
-    __syncthreads();
-    int t0 = 0;
-    for (; t0 + 2 * STAGES < nk; t0 += STAGES) {       // every step of the group fetches tile t + 1 + STAGES < nk
-        step.template operator()<0, true>(t0);
-        step.template operator()<1, true>(t0 + 1);
-        if constexpr (STAGES > 2) {
-            step.template operator()<2, true>(t0 + 2);
-            step.template operator()<3, true>(t0 + 3);
+
+    // Tile t waits in register set t % STAGES until it is copied to LDS buffer t % 2.  FULL steps are the
+    // steady state (every tile they touch exists) and contain no branch.
+    if constexpr (FRAG_PREFETCH) {
+        // Fragments of tile t+1 are read from LDS while the MFMAs of tile t run (two fragment register sets).
+        Frags fr[2];
+        auto step = [&]<int S, bool FULL>(int t) {
+            constexpr int set = (S + 2) % STAGES;
+            if (FULL || t < nk) {
+                if (FULL || t + 2 < nk) {
+                    store_tiles(S & 1, wreg[set], xreg[set]);                    // tile t+2 replaces tile t
+                    if (FULL || t + 2 + STAGES < nk) load_tiles(wreg[set], xreg[set]);
+                }
+                if (FULL || t + 1 < nk) load_frags((S + 1) & 1, fr[(S + 1) & 1]);
+                mma(fr[S & 1]);
+                __syncthreads();
+            }
+        };
+        store_tiles(0, wreg[0], xreg[0]);
+        if (STAGES < nk) load_tiles(wreg[0], xreg[0]);
+        __syncthreads();
+        if (1 < nk) {
+            store_tiles(1, wreg[1], xreg[1]);
+            if (STAGES + 1 < nk) load_tiles(wreg[1], xreg[1]);
+        }
+        load_frags(0, fr[0]);
+        __syncthreads();
+        int t0 = 0;
+        for (; t0 + 2 * STAGES + 1 < nk; t0 += STAGES) {
+            step.template operator()<0, true>(t0);
+            step.template operator()<1, true>(t0 + 1);
+            if constexpr (STAGES > 2) {
+                step.template operator()<2, true>(t0 + 2);
+                step.template operator()<3, true>(t0 + 3);
+            }
+        }
+        for (; t0 < nk; t0 += STAGES) {
+            step.template operator()<0, false>(t0);
+            step.template operator()<1, false>(t0 + 1);
+            if constexpr (STAGES > 2) {
+                step.template operator()<2, false>(t0 + 2);
+                step.template operator()<3, false>(t0 + 3);
+            }
+        }
+    } else {
+        auto step = [&]<int S, bool FULL>(int t) {
+            constexpr int nxt = (S + 1) % STAGES;
+            if (FULL || t < nk) {
+                if (FULL || t + 1 < nk) {
+                    store_tiles((S + 1) & 1, wreg[nxt], xreg[nxt]);
+                    if (FULL || t + 1 + STAGES < nk) load_tiles(wreg[nxt], xreg[nxt]);
+                }
+                Frags f;
+                load_frags(S & 1, f);
+                mma(f);
+                __syncthreads();
+            }
+        };
+        store_tiles(0, wreg[0], xreg[0]);
+        if (STAGES < nk) load_tiles(wreg[0], xreg[0]);
+        __syncthreads();
+        int t0 = 0;
+        for (; t0 + 2 * STAGES < nk; t0 += STAGES) {
+            step.template operator()<0, true>(t0);
+            step.template operator()<1, true>(t0 + 1);
+            if constexpr (STAGES > 2) {
+                step.template operator()<2, true>(t0 + 2);
+                step.template operator()<3, true>(t0 + 3);
+            }
+        }
+        for (; t0 < nk; t0 += STAGES) {
+            step.template operator()<0, false>(t0);
+            step.template operator()<1, false>(t0 + 1);
+            if constexpr (STAGES > 2) {
+                step.template operator()<2, false>(t0 + 2);
+                step.template operator()<3, false>(t0 + 3);
+            }
         }
     }
-    for (; t0 < nk; t0 += STAGES) {
-        step.template operator()<0, false>(t0);
-        step.template operator()<1, false>(t0 + 1);
-        if constexpr (STAGES > 2) {
-            step.template operator()<2, false>(t0 + 2);
-            step.template operator()<3, false>(t0 + 3);
-        }
+    if constexpr (TWO_ACC) {
+#pragma unroll
+        for (int v = 0; v < ACC_REGS; ++v) acc[0][0][v] += acc2[v];
     }
 
     // ---- split-K: publish partial sums; the last workgroup of the tile reduces in split order ----
@@ -496,10 +604,12 @@ __global__ void __launch_bounds__(256) gemv_kernel(OpArgs a) {
 template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES>
 static void launch_cfg(const OpArgs &a, hipStream_t st) {
     const dim3 grid(a.grid_x), block(256);
-    if (a.vec_a)
-        hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, STAGES, true>), grid, block, 0, st, a);
+    if (a.vec_a == A_UNIFORM)
+        hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, STAGES, A_UNIFORM>), grid, block, 0, st, a);
+    else if (a.vec_a == A_VEC8)
+        hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, STAGES, A_VEC8>), grid, block, 0, st, a);
     else
-        hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, 2, false>), grid, block, 0, st, a);
+        hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, 2, A_SCALAR>), grid, block, 0, st, a);
 }
 
 template <typename T>

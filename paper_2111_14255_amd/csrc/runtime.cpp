@@ -171,7 +171,8 @@ int32_t finalize_model(mt_model *m) {
                 } else {
                     // a fully connected layer is a 1x1 convolution over a 1x1 map with H*W*C channels
                     if (d.kind == MT_FC) { p.H = p.W = 1; p.C = gemm_k; p.R = p.S = 1; }
-                    p.vec_a = (p.C % 8 == 0) ? 1 : 0;
+                    // im2col gather mode: 2 = tile inside one tap (C % 64 == 0, at most 64 taps), 1 = 16-byte chunks, 0 = element-wise
+                    p.vec_a = (p.C % IGEMM_BK == 0 && p.R * p.S <= 64) ? 2 : (p.C % 8 == 0) ? 1 : 0;
                     plan_igemm(p, m->batch * o.out_h * o.out_w, o.out_c, gemm_k);
                 }
                 break;
@@ -265,7 +266,8 @@ struct mt_ctx {
     hipDeviceProp_t prop{};
     std::vector<std::unique_ptr<Tenant>> tenants;
     hipStream_t main_stream = nullptr;
-    std::map<StreamKey, hipStream_t> streams;
+    struct StreamEntry { hipStream_t stream = nullptr; int refs = 0; };
+    std::map<StreamKey, StreamEntry> streams;   // tenant streams, shared by schedules (reference counted)
     hipEvent_t ev_start = nullptr;
     hipEvent_t ev_stage[MT_MAX_STAGES]{};
     hipEvent_t ev_done[MT_MAX_STAGES][MT_MAX_TENANTS]{};
@@ -285,6 +287,8 @@ struct mt_schedule {
     int n_tenants = 0, n_stages = 0, flags = 0;
     std::vector<StagePlan> stages;                 // non-empty stages only keep items; empty ones stay for timing
     hipStream_t stream_of[MT_MAX_TENANTS]{};
+    StreamKey stream_key[MT_MAX_TENANTS]{};
+    int n_keys = 0;
     int n_launches = 0;
     // graph replay
     hipGraphExec_t graph_exec = nullptr;
@@ -324,10 +328,23 @@ inline OpArgs patched(const Tenant &t, int op, const void *in, void *out) {
 
 // Stream of a tenant restricted to `share` compute units (0 = all).  Tenant i's units start where the
 // shares of the tenants before it end, so disjoint shares give disjoint units.
-int32_t get_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t *out) {
+int32_t get_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t *out, StreamKey *out_key) {
     StreamKey key{tenant, share == 0 ? 0 : (first_cu << 12) | share};
+    *out_key = key;
     auto it = ctx->streams.find(key);
-    if (it != ctx->streams.end()) { *out = it->second; return MT_OK; }
+    if (it != ctx->streams.end()) { it->second.refs++; *out = it->second.stream; return MT_OK; }
+    // A search over CU shares creates many masked streams: drop the unreferenced ones before they pile up.
+    if (share != 0 && ctx->streams.size() > 40) {
+        HIP_TRY(hipDeviceSynchronize());
+        for (auto e = ctx->streams.begin(); e != ctx->streams.end();) {
+            if (e->second.refs == 0 && e->first.share != 0) {
+                (void)hipStreamDestroy(e->second.stream);
+                e = ctx->streams.erase(e);
+            } else {
+                ++e;
+            }
+        }
+    }
     hipStream_t s = nullptr;
     if (share == 0) {
         HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
@@ -340,9 +357,17 @@ int32_t get_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t
         }
         HIP_TRY(hipExtStreamCreateWithCUMask(&s, (uint32_t)mask.size(), mask.data()));
     }
-    ctx->streams[key] = s;
+    ctx->streams[key] = mt_ctx::StreamEntry{s, 1};
     *out = s;
     return MT_OK;
+}
+
+void release_streams(mt_schedule *s) {
+    for (int i = 0; i < s->n_keys; ++i) {
+        auto it = s->ctx->streams.find(s->stream_key[i]);
+        if (it != s->ctx->streams.end() && it->second.refs > 0) it->second.refs--;
+    }
+    s->n_keys = 0;
 }
 
 // Issues the whole schedule on the tenant streams.  Barrier between stages: every stream of the stage
@@ -421,7 +446,7 @@ int32_t mt_destroy(mt_ctx *ctx) {
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
     for (hipGraphExec_t g : ctx->retired_graphs) (void)hipGraphExecDestroy(g);
-    for (auto &kv : ctx->streams) (void)hipStreamDestroy(kv.second);
+    for (auto &kv : ctx->streams) (void)hipStreamDestroy(kv.second.stream);
     if (ctx->main_stream) (void)hipStreamDestroy(ctx->main_stream);
     if (ctx->ev_start) (void)hipEventDestroy(ctx->ev_start);
     for (int s = 0; s < MT_MAX_STAGES; ++s) {
@@ -684,8 +709,9 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
     int first_cu = 0;
     for (int i = 0; i < n_tenants; ++i) {
         const int share = (cu_share && !(flags & MT_SCHED_GRAPH)) ? cu_share[i] : 0;
-        rc = get_stream(ctx, i, share, first_cu, &s->stream_of[i]);
-        if (rc != MT_OK) return rc;
+        rc = get_stream(ctx, i, share, first_cu, &s->stream_of[i], &s->stream_key[i]);
+        if (rc != MT_OK) { release_streams(s.get()); return rc; }
+        s->n_keys = i + 1;
         first_cu = (first_cu + share) % cus;
     }
     std::vector<int32_t> slices((size_t)n_stages * n_tenants * 2);
@@ -707,6 +733,7 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
 int32_t mt_schedule_destroy(mt_schedule *s) {
     if (!s) return fail(MT_ERR_INVALID_ARG, "schedule is NULL");
     if (s->graph_exec && s->ctx) s->ctx->retired_graphs.push_back(s->graph_exec);
+    release_streams(s);
     delete s;
     return MT_OK;
 }
@@ -805,21 +832,26 @@ struct ProfileCost {
     const void *const *inputs;
     void *const *outputs;
     int n_tenants;
+    const int32_t *pointers = nullptr;     // fixed while shares are searched
+    const int32_t *cu_share = nullptr;     // fixed while pointers are searched
     int32_t rc = MT_OK;
 };
 
-double profile_cost(const int32_t *pointers, void *user) {
-    ProfileCost *pc = (ProfileCost *)user;
+double profile_schedule(ProfileCost *pc, const int32_t *pointers, const int32_t *cu_share) {
     if (pc->rc != MT_OK) return 1e30;
     mt_schedule *s = nullptr;
     static const bool trace = std::getenv("MTSCHED_TRACE") != nullptr;
     if (trace) {
         std::fprintf(stderr, "[mtsched] profile rho =");
         for (int i = 0; i < pc->n_tenants * (pc->o->n_stages - 1); ++i) std::fprintf(stderr, " %d", pointers[i]);
+        if (cu_share) {
+            std::fprintf(stderr, "  shares =");
+            for (int i = 0; i < pc->n_tenants; ++i) std::fprintf(stderr, " %d", cu_share[i]);
+        }
         std::fprintf(stderr, "\n");
         std::fflush(stderr);
     }
-    pc->rc = mt_schedule_create(pc->ctx, pc->n_tenants, pc->o->n_stages, pointers, nullptr, nullptr, pc->o->issue_order,
+    pc->rc = mt_schedule_create(pc->ctx, pc->n_tenants, pc->o->n_stages, pointers, nullptr, cu_share, pc->o->issue_order,
                                 pc->o->flags, &s);
     if (pc->rc != MT_OK) return 1e30;
     double sum = 0;
@@ -827,28 +859,51 @@ double profile_cost(const int32_t *pointers, void *user) {
         mt_timings tm;
         pc->rc = mt_run(pc->ctx, s, pc->inputs, pc->outputs, &tm);
         if (r >= pc->o->warmup) sum += tm.makespan_ms;
-        if (trace) { std::fprintf(stderr, "[mtsched]   run %d rc %d %.4f ms\n", r, pc->rc, tm.makespan_ms); std::fflush(stderr); }
     }
     mt_schedule_destroy(s);
-    if (trace) { std::fprintf(stderr, "[mtsched]   destroyed\n"); std::fflush(stderr); }
-    return pc->rc == MT_OK ? sum / pc->o->runs : 1e30;
+    const double c = pc->rc == MT_OK ? sum / pc->o->runs : 1e30;
+    if (trace) { std::fprintf(stderr, "[mtsched]   cost %.4f ms rc %d\n", c, pc->rc); std::fflush(stderr); }
+    return c;
+}
+
+double profile_cost(const int32_t *pointers, void *user) {
+    ProfileCost *pc = (ProfileCost *)user;
+    return profile_schedule(pc, pointers, pc->cu_share);
+}
+
+double profile_share_cost(const int32_t *cu_share, void *user) {
+    ProfileCost *pc = (ProfileCost *)user;
+    return profile_schedule(pc, pc->pointers, cu_share);
 }
 }  // namespace
 
 int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *inputs, void *const *outputs,
-                  int32_t *best_pointers, double *best_cost, int32_t *rec_pointers, double *rec_cost,
-                  int32_t max_records, int32_t *n_records) {
+                  int32_t *best_pointers, int32_t *best_cu_share, double *best_cost, int32_t *rec_pointers,
+                  double *rec_cost, int32_t max_records, int32_t *n_records) {
     if (!ctx || !opts || !inputs || !outputs || !best_pointers) return fail(MT_ERR_INVALID_ARG, "NULL argument");
     if (opts->runs < 1 || opts->warmup < 0) return fail(MT_ERR_INVALID_ARG, "runs must be >= 1 and warmup >= 0");
     const int n = (int)ctx->tenants.size();
     if (n < 1) return fail(MT_ERR_INVALID_ARG, "no tenants registered");
+    if (opts->cu_share_rounds > 0 && (opts->flags & MT_SCHED_GRAPH))
+        return fail(MT_ERR_INVALID_ARG, "CU shares have no effect under graph replay");
     int32_t lens[MT_MAX_TENANTS];
     for (int i = 0; i < n; ++i) lens[i] = (int32_t)ctx->tenants[i]->model.ops.size();
     ProfileCost pc{ctx, opts, inputs, outputs, n};
-    int32_t rc = search_pointers(n, lens, opts, profile_cost, &pc, best_pointers, best_cost, rec_pointers, rec_cost,
+    double cost = 0;
+    int32_t rc = search_pointers(n, lens, opts, profile_cost, &pc, best_pointers, &cost, rec_pointers, rec_cost,
                                  max_records, n_records);
     if (pc.rc != MT_OK) return pc.rc;
-    return rc;
+    if (rc != MT_OK) return rc;
+    int32_t shares[MT_MAX_TENANTS] = {0};
+    if (opts->cu_share_rounds > 0) {
+        pc.pointers = best_pointers;
+        rc = search_cu_share(n, ctx->prop.multiProcessorCount, opts->cu_share_rounds, profile_share_cost, &pc, shares, &cost);
+        if (pc.rc != MT_OK) return pc.rc;
+        if (rc != MT_OK) return rc;
+    }
+    if (best_cu_share) std::memcpy(best_cu_share, shares, sizeof(int32_t) * n);
+    if (best_cost) *best_cost = cost;
+    return MT_OK;
 }
 
 }  // extern "C"

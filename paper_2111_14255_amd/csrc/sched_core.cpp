@@ -193,9 +193,38 @@ int32_t search_pointers(int32_t n_tenants, const int32_t *lens, const mt_search_
     return MT_OK;
 }
 
+int32_t search_cu_share(int32_t n_tenants, int32_t cu_count, int32_t rounds, mt_share_cost_fn cost, void *user,
+                        int32_t *best_share, double *best_cost) {
+    if (!cost || !best_share || !best_cost) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (n_tenants < 1 || n_tenants > MT_MAX_TENANTS || cu_count < 8 || rounds < 1)
+        return fail(MT_ERR_INVALID_ARG, "bad tenant count, CU count or rounds");
+    std::vector<int32_t> cur(n_tenants, 0), cand(n_tenants, 0);
+    double best = *best_cost;
+    for (int r = 0; r < rounds; ++r)
+        for (int i = 0; i < n_tenants; ++i)
+            for (int k = 1; k <= 7; ++k) {
+                cand = cur;
+                cand[i] = k * cu_count / 8;
+                if (cand[i] == cur[i]) continue;
+                const double c = cost(cand.data(), user);
+                if (c < best) {
+                    best = c;
+                    cur = cand;
+                }
+            }
+    std::memcpy(best_share, cur.data(), sizeof(int32_t) * n_tenants);
+    *best_cost = best;
+    return MT_OK;
+}
+
 }  // namespace mt
 
 extern "C" {
+
+int32_t mt_search_cu_share(int32_t n_tenants, int32_t cu_count, int32_t rounds, mt_share_cost_fn share_cost, void *user,
+                           int32_t *best_share, double *best_cost) {
+    return mt::search_cu_share(n_tenants, cu_count, rounds, share_cost, user, best_share, best_cost);
+}
 
 const char *mt_last_error(void) { return mt::g_last_error.c_str(); }
 

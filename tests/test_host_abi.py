@@ -23,6 +23,7 @@ def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "mtsched.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     declared = set(re.findall(r"\b(mt_[a-z0-9_]+)\s*\(", hdr)) - {"mt_cost_fn"}
+    declared -= {"mt_share_cost_fn"}
     assert declared == set(B.SIGNATURES), declared ^ set(B.SIGNATURES)
     lib = B.load()
     for name in declared:
@@ -244,3 +245,25 @@ def test_speedup_definition_matches_printed_tables():
     assert len(rows) == 12
     for seq, ours, printed in rows:
         assert abs(speedup(float(seq), float(ours)) - float(printed)) < 0.01   # printed to two decimals, some rounded, some truncated
+
+
+def test_cu_share_descent_matches_oracle():
+    target = [64, 160, 32]
+    calls = []
+
+    def cost(sh):
+        return float(sum(abs((a or 256) - b) for a, b in zip(sh, target))) + 1.0
+
+    def cb(ptr, _u):
+        v = [ptr[i] for i in range(3)]
+        calls.append(v)
+        return cost(v)
+
+    best = (I32 * 3)()
+    bc = C.c_double(cost([0, 0, 0]))
+    fn = B.mt_share_cost_fn(cb)
+    assert B.load().mt_search_cu_share(3, 256, 2, fn, None, best, C.byref(bc)) == 0
+    ocalls = []
+    oshare, ocost = S.cu_share_descent(3, 256, 2, lambda sh: (ocalls.append(list(sh)) or cost(sh)), cost([0, 0, 0]))
+    assert [best[i] for i in range(3)] == oshare == [64, 160, 32]
+    assert bc.value == ocost and calls == ocalls
