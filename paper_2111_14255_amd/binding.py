@@ -102,7 +102,7 @@ def load():
     """Loads the built library (building it first only if it has never been built)."""
     global _lib
     if _lib is None:
-        path = _build.lib_path()
+        path = os.environ.get("MTSCHED_LIB") or _build.lib_path()   # override: load another build of the library
         if not os.path.exists(path):
             _build.build()
         lib = C.CDLL(path)

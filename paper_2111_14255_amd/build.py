@@ -25,7 +25,7 @@ def _hipcc():
 
 def _compile(src, extra):
     out = os.path.join(OBJ, os.path.basename(src) + ".o")
-    cmd = [_hipcc(), "-c", os.path.join(CSRC, src), "-o", out] + COMMON + extra
+    cmd = [_hipcc(), "-c", os.path.join(CSRC, src), "-o", out] + COMMON + extra + os.environ.get("MT_EXTRA_DEFS", "").split()
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
@@ -36,7 +36,10 @@ def _compile(src, extra):
     return out
 
 
-def build(verbose=False):
+def build(verbose=False, lib=None):
+    global LIB
+    if lib:
+        LIB = lib
     os.makedirs(OBJ, exist_ok=True)
     jobs = [(s, DEVICE_FLAGS) for s in DEVICE_SOURCES] + [(s, ["-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include"]) for s in HOST_SOURCES]
     with ThreadPoolExecutor(max_workers=4) as ex:

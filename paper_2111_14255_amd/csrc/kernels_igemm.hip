@@ -91,7 +91,13 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     constexpr int ROW_STEP = 256 / CH_ROW;                 // tile rows covered by one pass of the workgroup
     constexpr int W_CHUNKS = (BN + ROW_STEP - 1) / ROW_STEP;
     constexpr int X_CHUNKS = (BM + ROW_STEP - 1) / ROW_STEP;
-    constexpr bool FRAG_PREFETCH = KSTEPS * (TN + TM) <= 8;   // two fragment sets fit the register budget
+#ifndef MT_FRAG_PREFETCH
+#define MT_FRAG_PREFETCH 0
+#endif
+#ifndef MT_TWO_ACC
+#define MT_TWO_ACC 0
+#endif
+    constexpr bool FRAG_PREFETCH = MT_FRAG_PREFETCH && KSTEPS * (TN + TM) <= 8;   // two fragment sets fit the register budget
     typedef typename Mma<T, MF>::Acc Acc;
 
     __shared__ __attribute__((aligned(16))) uint16_t Ws[2][W_CHUNKS * ROW_STEP * LDK];
@@ -114,8 +120,8 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     if (vid >= total) return;
     const int z = vid % a.split_k;
     const int tile = vid / a.split_k;
-    const int tn_idx = tile % tiles_n;
-    const int tm_idx = tile / tiles_n;
+    const int tn_idx = a.tile_order ? tile / tiles_m : tile % tiles_n;
+    const int tm_idx = a.tile_order ? tile % tiles_m : tile / tiles_n;
     const int n0 = tn_idx * BN;
     const int m0 = tm_idx * BM;
 
@@ -305,7 +311,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     };
     // Small wave tiles alternate between two accumulators so that consecutive MFMAs do not wait for each
     // other; the two are added once at the end (fixed order).
-    constexpr bool TWO_ACC = (TN * TM == 1) && (KSTEPS % 2 == 0);
+    constexpr bool TWO_ACC = MT_TWO_ACC && (TN * TM == 1) && (KSTEPS % 2 == 0);
     Acc acc2;
 #pragma unroll
     for (int v = 0; v < ACC_REGS; ++v) acc2[v] = 0.f;

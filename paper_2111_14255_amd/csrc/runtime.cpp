@@ -11,6 +11,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <map>
+#include <set>
 #include <memory>
 
 #include "internal.h"
@@ -69,7 +70,10 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
         return;
     }
     int bn, bm, kid;
-    if (M <= 32) {
+    // Small problems (few multiply-accumulates on a small map) are latency bound: narrow pixel tiles give more,
+    // shorter workgroups.  Measured on MI355X: ResNet-18 3x3 layers (115 M MACs) 9-11 us -> 7.3-8.6 us.
+    const double macs = (double)M * Kc * gemm_k;
+    if (M <= 32 || (M <= 4096 && macs <= 3.0e8)) {
         kid = K_IGEMM_64x16; bn = 64; bm = 16;
     } else if (Kc >= 96 && cdiv(M, 128) * cdiv(Kc, 128) >= 512) {
         kid = K_IGEMM_128x128; bn = 128; bm = 128;
@@ -77,13 +81,6 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
         kid = K_IGEMM_128x64; bn = 128; bm = 64;
     } else {
         kid = K_IGEMM_64x64; bn = 64; bm = 64;
-    }
-    if (const char *e = std::getenv("MTSCHED_TUNE_TILE")) {
-        if (M > 32 && Kc >= 96) {
-            kid = std::atoi(e);
-            bn = kid == K_IGEMM_64x64 ? 64 : 128;
-            bm = kid == K_IGEMM_128x128 ? 128 : 64;
-        }
     }
     p.kernel_id = kid;
     p.n_pad = cdiv(Kc, bn) * bn;
@@ -101,6 +98,9 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
         split = cdiv(nkt, per);            // no empty split
     }
     p.split_k = std::max(1, split);
+    // Which operand each XCD's L2 keeps to itself: consecutive tiles (one XCD) walk the channel tiles of one pixel
+    // tile (0) when the activations are the larger operand, the pixel tiles of one channel tile (1) otherwise.
+    p.tile_order = ((double)Kc * gemm_k > (double)p.N * p.H * p.W * p.C) ? 1 : 0;
     const int total = tiles * p.split_k;
     p.grid_x = cdiv(total, 8) * 8;
 }
@@ -275,6 +275,9 @@ struct mt_ctx {
     // Graph executables of destroyed schedules.  They are released only at mt_destroy, after a device-wide
     // synchronisation: destroying one right after its last launch has crashed inside the HIP runtime.
     std::vector<hipGraphExec_t> retired_graphs;
+    // Schedules created from this context and not destroyed yet; mt_destroy detaches them so that a later
+    // mt_schedule_destroy does not touch the freed context.
+    std::set<mt_schedule *> live_schedules;
 };
 
 struct StagePlan {
@@ -333,15 +336,22 @@ int32_t get_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t
     *out_key = key;
     auto it = ctx->streams.find(key);
     if (it != ctx->streams.end()) { it->second.refs++; *out = it->second.stream; return MT_OK; }
-    // A search over CU shares creates many masked streams: drop the unreferenced ones before they pile up.
-    if (share != 0 && ctx->streams.size() > 40) {
-        HIP_TRY(hipDeviceSynchronize());
-        for (auto e = ctx->streams.begin(); e != ctx->streams.end();) {
-            if (e->second.refs == 0 && e->first.share != 0) {
-                (void)hipStreamDestroy(e->second.stream);
-                e = ctx->streams.erase(e);
-            } else {
-                ++e;
+    // A search over CU shares creates many masked streams, each with a hardware queue of its own.  Too many
+    // queues make the hardware scheduler time-slice them, which slows every stream of the process: release
+    // the unreferenced masked streams before they pile up.
+    if (share != 0) {
+        int idle = 0;
+        for (auto &e : ctx->streams)
+            if (e.second.refs == 0 && e.first.share != 0) ++idle;
+        if (idle >= 6) {
+            HIP_TRY(hipDeviceSynchronize());
+            for (auto e = ctx->streams.begin(); e != ctx->streams.end();) {
+                if (e->second.refs == 0 && e->first.share != 0) {
+                    (void)hipStreamDestroy(e->second.stream);
+                    e = ctx->streams.erase(e);
+                } else {
+                    ++e;
+                }
             }
         }
     }
@@ -363,6 +373,7 @@ int32_t get_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t
 }
 
 void release_streams(mt_schedule *s) {
+    if (!s->ctx) { s->n_keys = 0; return; }
     for (int i = 0; i < s->n_keys; ++i) {
         auto it = s->ctx->streams.find(s->stream_key[i]);
         if (it != s->ctx->streams.end() && it->second.refs > 0) it->second.refs--;
@@ -445,6 +456,11 @@ int32_t mt_destroy(mt_ctx *ctx) {
     if (!ctx) return fail(MT_ERR_INVALID_ARG, "ctx is NULL");
     (void)hipSetDevice(ctx->device);
     (void)hipDeviceSynchronize();
+    for (mt_schedule *ls : ctx->live_schedules) {
+        if (ls->graph_exec) ctx->retired_graphs.push_back(ls->graph_exec);
+        ls->graph_exec = nullptr;
+        ls->ctx = nullptr;
+    }
     for (hipGraphExec_t g : ctx->retired_graphs) (void)hipGraphExecDestroy(g);
     for (auto &kv : ctx->streams) (void)hipStreamDestroy(kv.second.stream);
     if (ctx->main_stream) (void)hipStreamDestroy(ctx->main_stream);
@@ -726,14 +742,18 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
         std::sort(sp.streams.begin(), sp.streams.end());
         s->n_launches += (int)sp.items.size();
     }
+    ctx->live_schedules.insert(s.get());
     *out = s.release();
     return MT_OK;
 }
 
 int32_t mt_schedule_destroy(mt_schedule *s) {
     if (!s) return fail(MT_ERR_INVALID_ARG, "schedule is NULL");
-    if (s->graph_exec && s->ctx) s->ctx->retired_graphs.push_back(s->graph_exec);
-    release_streams(s);
+    if (s->ctx) {
+        if (s->graph_exec) s->ctx->retired_graphs.push_back(s->graph_exec);
+        release_streams(s);
+        s->ctx->live_schedules.erase(s);
+    }
     delete s;
     return MT_OK;
 }
@@ -741,7 +761,7 @@ int32_t mt_schedule_destroy(mt_schedule *s) {
 // ---- run -------------------------------------------------------------------------------------
 int32_t mt_run(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *const *outputs, mt_timings *tm) {
     if (!ctx || !s || !inputs || !outputs) return fail(MT_ERR_INVALID_ARG, "NULL argument");
-    if (s->ctx != ctx) return fail(MT_ERR_INVALID_ARG, "schedule belongs to another context");
+    if (s->ctx != ctx) return fail(MT_ERR_INVALID_ARG, "schedule belongs to another (or a destroyed) context");
     for (int i = 0; i < s->n_tenants; ++i) {
         if (!inputs[i] || !outputs[i]) return fail(MT_ERR_INVALID_ARG, "NULL input or output buffer");
         if (((uintptr_t)inputs[i] % 16) || ((uintptr_t)outputs[i] % 16)) return fail(MT_ERR_INVALID_ARG, "buffers must be 16-byte aligned");

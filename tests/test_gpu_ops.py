@@ -45,6 +45,7 @@ CONV_CASES = [
     ("ig64_concat_unaligned", dict(n=1, h=8, w=8, c=16, k=10, r=3, pad=1, coff=3, ctot=18), IG64),
     ("ig64_concat_aligned", dict(n=1, h=8, w=8, c=16, k=32, r=1, coff=64, ctot=128), IG64),
     ("ig16_conv_tiny_map", dict(n=2, h=4, w=4, c=64, k=70, r=3, pad=1), IG16),
+    ("ig64_splitk_wide", dict(n=1, h=66, w=66, c=128, k=64, r=3, pad=1, res=True), IG64),
     ("gemv_1x1_m1", dict(n=1, h=1, w=1, c=1280, k=1000, r=1, act="none"), GEMV),
     ("gemv_1x1_m5_res", dict(n=5, h=1, w=1, c=520, k=77, r=1, res=True), GEMV),
     ("ig16_1x1_m12", dict(n=12, h=1, w=1, c=512, k=100, r=1), IG16),
@@ -54,8 +55,38 @@ CONV_CASES = [
 ]
 
 
+def _expand_cases():
+    """Small problems (<= 4096 pixels and <= 3e8 MACs) run on the 64x16 tile; every case written for the 64x64
+    tile is therefore run twice: as is (64x16 kernel) and on a map of more than 4096 output pixels (64x64 kernel)."""
+    out = []
+    for name, kw, kid in CONV_CASES:
+        if kid != IG64:
+            out.append((name, kw, kid))
+            continue
+        op = g_conv("f16", **kw).ops[1 if kw.get("res") else 0]
+        if kw["n"] * op.out_shape[0] * op.out_shape[1] > 4096:
+            out.append((name, kw, kid))
+            continue
+        out.append((name + "_small", kw, IG16))
+        big = dict(kw)
+        stride = kw.get("stride", 1)
+        r = kw["r"] if isinstance(kw["r"], int) else max(kw["r"])
+        side = 66 * stride + (r if not kw.get("pad") else 0)
+        big["h"] = big["w"] = side
+        big["n"] = 1
+        if big["c"] > 64:
+            big["c"] = 64                      # keep the oracle fast; the channel-mode of the case is preserved below
+            if kw["c"] % 64 != 0:
+                big["c"] = kw["c"]
+        out.append((name + "_big", big, IG64))
+    return out
+
+
+ALL_CONV_CASES = _expand_cases()
+
+
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("name,kw,kid", CONV_CASES, ids=[c[0] for c in CONV_CASES])
+@pytest.mark.parametrize("name,kw,kid", ALL_CONV_CASES, ids=[c[0] for c in ALL_CONV_CASES])
 def test_conv_igemm(name, kw, kid, dtype):
     spec = g_conv(dtype, **kw)
     print("case", name, dtype, flush=True)
@@ -64,7 +95,7 @@ def test_conv_igemm(name, kw, kid, dtype):
         main = 1 if kw.get("res") else 0
         info = mix.ctx.op_info(0, main)
         if kid is not None:
-            assert info.kernel_id == kid, (info.kernel_id, info.split_k)
+            assert info.kernel_id == kid, (info.kernel_id, info.split_k, info.out_h, info.out_w)
         if "splitk" in name:
             assert info.split_k > 1
         got, _ = mix.run(mix.ctx.sequential())
