@@ -136,6 +136,93 @@ __global__ void __launch_bounds__(256) dwconv_kernel(OpArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Fixed-window variants (KS x KS known at compile time, 16-byte channel vectors).  All taps are loaded first,
+// from clamped addresses and without branches, so the loads of a thread overlap instead of each waiting for the
+// one before it; taps in the padding halo are masked afterwards.  Tap order of the sums is the same (r, s).
+template <typename T, int V, int KS>
+__global__ void __launch_bounds__(256) dwconv_fixed_kernel(OpArgs a) {
+    const int CV = a.C / V;
+    const int64_t total = (int64_t)a.N * a.P * a.Q * CV;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= total) return;
+    const int cv = (int)(gid % CV);
+    int64_t m = gid / CV;
+    const int q = (int)(m % a.Q);
+    const int p = (int)((m / a.Q) % a.P);
+    const int n = (int)(m / ((int64_t)a.Q * a.P));
+    const int c0 = cv * V;
+    const T *x = (const T *)a.x + (int64_t)n * a.H * a.W * a.C + c0;
+    const T *w = (const T *)a.w + c0;
+    float xv[KS * KS][V], wv[KS * KS][V];
+    bool ok[KS * KS];
+#pragma unroll
+    for (int r = 0; r < KS; ++r)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const int ih = p * a.sh - a.ph + r, iw = q * a.sw - a.pw + s;
+            ok[r * KS + s] = ((unsigned)ih < (unsigned)a.H) & ((unsigned)iw < (unsigned)a.W);
+            const int ihc = min(max(ih, 0), a.H - 1), iwc = min(max(iw, 0), a.W - 1);
+            load_pack<T, V>(x + ((int64_t)ihc * a.W + iwc) * a.C, xv[r * KS + s]);
+            load_pack<T, V>(w + (int64_t)(r * KS + s) * a.C, wv[r * KS + s]);
+        }
+    float acc[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int t = 0; t < KS * KS; ++t)
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] = ok[t] ? fmaf(xv[t][i], wv[t][i], acc[i]) : acc[i];
+#pragma unroll
+    for (int i = 0; i < V; ++i) {
+        if (a.bias) acc[i] += a.bias[c0 + i];
+        acc[i] = apply_act(acc[i], a.act);
+    }
+    store_pack<T, V>((T *)a.y + m * a.y_ct + a.y_coff + c0, acc);
+}
+
+template <typename T, int V, bool IS_MAX, int KS>
+__global__ void __launch_bounds__(256) pool_fixed_kernel(OpArgs a) {
+    const int CV = a.C / V;
+    const int64_t total = (int64_t)a.N * a.P * a.Q * CV;
+    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= total) return;
+    const int cv = (int)(gid % CV);
+    int64_t m = gid / CV;
+    const int q = (int)(m % a.Q);
+    const int p = (int)((m / a.Q) % a.P);
+    const int n = (int)(m / ((int64_t)a.Q * a.P));
+    const int c0 = cv * V;
+    const T *x = (const T *)a.x + (int64_t)n * a.H * a.W * a.C + c0;
+    float xv[KS * KS][V];
+    bool ok[KS * KS];
+#pragma unroll
+    for (int r = 0; r < KS; ++r)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const int ih = p * a.sh - a.ph + r, iw = q * a.sw - a.pw + s;
+            ok[r * KS + s] = ((unsigned)ih < (unsigned)a.H) & ((unsigned)iw < (unsigned)a.W);
+            const int ihc = min(max(ih, 0), a.H - 1), iwc = min(max(iw, 0), a.W - 1);
+            load_pack<T, V>(x + ((int64_t)ihc * a.W + iwc) * a.C, xv[r * KS + s]);
+        }
+    float acc[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) acc[i] = IS_MAX ? -INFINITY : 0.f;
+    int cnt = 0;
+#pragma unroll
+    for (int t = 0; t < KS * KS; ++t) {
+        cnt += ok[t] ? 1 : 0;
+#pragma unroll
+        for (int i = 0; i < V; ++i)
+            acc[i] = ok[t] ? (IS_MAX ? fmaxf(acc[i], xv[t][i]) : acc[i] + xv[t][i]) : acc[i];
+    }
+    if (!IS_MAX) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] = acc[i] / (float)cnt;
+    }
+    store_pack<T, V>((T *)a.y + m * a.y_ct + a.y_coff + c0, acc);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Window pooling: one thread per (output pixel, V-channel vector).
 template <typename T, int V, bool IS_MAX>
 __global__ void __launch_bounds__(256) pool_kernel(OpArgs a) {
@@ -234,6 +321,8 @@ static int launch_typed(const OpArgs &a, hipStream_t st) {
                 const int64_t th = (int64_t)a.N * a.P * a.Q * (a.C / VMAX);
                 if (shuffle)
                     hipLaunchKernelGGL((dwconv_kernel<T, VMAX, true>), blocks(th), block, 0, st, a);
+                else if (a.R == 3 && a.S == 3)
+                    hipLaunchKernelGGL((dwconv_fixed_kernel<T, VMAX, 3>), blocks(th), block, 0, st, a);
                 else
                     hipLaunchKernelGGL((dwconv_kernel<T, VMAX, false>), blocks(th), block, 0, st, a);
             } else {
@@ -246,7 +335,13 @@ static int launch_typed(const OpArgs &a, hipStream_t st) {
             const bool mx = a.kernel_id == K_MAXPOOL;
             if (a.vec == VMAX) {
                 const int64_t th = (int64_t)a.N * a.P * a.Q * (a.C / VMAX);
-                if (mx)
+                if (mx && a.R == 2 && a.S == 2)
+                    hipLaunchKernelGGL((pool_fixed_kernel<T, VMAX, true, 2>), blocks(th), block, 0, st, a);
+                else if (mx && a.R == 3 && a.S == 3)
+                    hipLaunchKernelGGL((pool_fixed_kernel<T, VMAX, true, 3>), blocks(th), block, 0, st, a);
+                else if (!mx && a.R == 3 && a.S == 3)
+                    hipLaunchKernelGGL((pool_fixed_kernel<T, VMAX, false, 3>), blocks(th), block, 0, st, a);
+                else if (mx)
                     hipLaunchKernelGGL((pool_kernel<T, VMAX, true>), blocks(th), block, 0, st, a);
                 else
                     hipLaunchKernelGGL((pool_kernel<T, VMAX, false>), blocks(th), block, 0, st, a);
