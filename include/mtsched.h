@@ -138,6 +138,17 @@ int32_t mt_create(int32_t device, mt_ctx **out);
 int32_t mt_destroy(mt_ctx *ctx);
 int32_t mt_get_device_info(const mt_ctx *ctx, mt_device_info *out);
 
+/* Diagnostic: which compute units a stream restricted to `share` units starting at unit `first_cu` (same rule as
+ * mt_schedule_create's cu_share; share 0 = unmasked) really runs on.  Launches n_groups one-wavefront workgroups that
+ * each record the hardware id registers of the unit they run on.  hw_ids: host [n_groups][2] = (HW_ID, XCC_ID) raw
+ * register values (CU_ID = bits 8-11, SH_ID = bit 12, SE_ID = bits 13-15 of HW_ID; XCC_ID = low 4 bits). */
+int32_t mt_probe_cu_mask(mt_ctx *ctx, int32_t share, int32_t first_cu, int32_t n_groups, uint32_t *hw_ids);
+
+/* Diagnostic: creates n_streams streams (each restricted to `share` units, 0 = unmasked), keeps them all alive, and
+ * measures on each the mean time of `n_launches` dependent one-workgroup kernels issued while the context's main
+ * stream waits for the stream's completion event (the pattern of a stage).  us_per_launch: host [n_streams]. */
+int32_t mt_probe_dispatch_latency(mt_ctx *ctx, int32_t n_streams, int32_t share, int32_t n_launches, float *us_per_launch);
+
 /* ---- model construction (host only; no GPU needed) ----------------------------------- */
 /* Operators are added in the serial order that becomes the model's sequence M_i (Eq. 1). */
 int32_t mt_model_begin(int32_t dtype, int32_t batch, int32_t in_h, int32_t in_w, int32_t in_c, mt_model **out);
@@ -185,6 +196,10 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
  * flags: MT_SCHED_GRAPH captures the whole schedule into a HIP graph on the first run and replays it
  * afterwards (CU shares are ignored in that mode: graph nodes do not inherit stream CU masks). */
 #define MT_SCHED_GRAPH 1
+/* MT_SCHED_PARALLEL_ISSUE: one issuing host thread per tenant stream instead of the paper's single main thread
+ * (Sec. III-D); the operators of a stage are launched by the threads of its streams concurrently, stage barriers and
+ * results are unchanged.  Not combinable with MT_SCHED_GRAPH. */
+#define MT_SCHED_PARALLEL_ISSUE 2
 int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, const int32_t *pointers,
                            const int32_t *stage_concurrency, const int32_t *cu_share,
                            int32_t issue_order, int32_t flags, mt_schedule **out);

@@ -24,6 +24,7 @@ MT_CONV, MT_DWCONV, MT_MAXPOOL, MT_AVGPOOL, MT_GLOBAL_AVGPOOL, MT_FC = range(6)
 MT_ACT_NONE, MT_ACT_RELU, MT_ACT_RELU6 = 0, 1, 2
 MT_ISSUE_BFS, MT_ISSUE_DFS = 0, 1
 MT_SCHED_GRAPH = 1
+MT_SCHED_PARALLEL_ISSUE = 2
 MT_SEARCH_COORDINATE, MT_SEARCH_RANDOM = 0, 1
 
 
@@ -69,6 +70,8 @@ SIGNATURES = {
     "mt_create": (_i32, [_i32, C.POINTER(_vp)]),
     "mt_destroy": (_i32, [_vp]),
     "mt_get_device_info": (_i32, [_vp, C.POINTER(mt_device_info)]),
+    "mt_probe_dispatch_latency": (_i32, [_vp, _i32, _i32, _i32, _pf]),
+    "mt_probe_cu_mask": (_i32, [_vp, _i32, _i32, _i32, C.POINTER(C.c_uint32)]),
     "mt_model_begin": (_i32, [_i32, _i32, _i32, _i32, _i32, C.POINTER(_vp)]),
     "mt_model_add_op": (_i32, [_vp, C.POINTER(mt_op_desc), _pi32]),
     "mt_model_end": (_i32, [_vp]),

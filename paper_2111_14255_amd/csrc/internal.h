@@ -85,5 +85,6 @@ struct OpArgs {
 int launch_direct(const OpArgs &a, void *stream);
 int launch_igemm(const OpArgs &a, void *stream);
 int launch_fill_u32(uint32_t *p, size_t n, uint32_t v, void *stream);
+int launch_probe(uint32_t *out, int n_groups, void *stream);
 
 }  // namespace mt

@@ -299,6 +299,19 @@ __global__ void __launch_bounds__(256) gap_kernel(OpArgs a, int lanes_c) {
     }
 }
 
+// Records the hardware id registers of the compute unit each one-wavefront workgroup runs on, then keeps the unit
+// busy for a few microseconds so that later workgroups spread over every unit the queue may use.
+__global__ void __launch_bounds__(64) probe_kernel(uint32_t *out) {
+    const uint32_t hw_id = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 4);     // HW_REG_HW_ID, 32 bits
+    const uint32_t xcc_id = __builtin_amdgcn_s_getreg((31 << 11) | (0 << 6) | 20);   // HW_REG_XCC_ID, 32 bits
+    float v = (float)threadIdx.x;
+    for (int i = 0; i < 4000; ++i) v = fmaf(v, 1.0000001f, 1e-7f);
+    if (threadIdx.x == 0) {
+        out[2 * blockIdx.x + 0] = hw_id;
+        out[2 * blockIdx.x + 1] = xcc_id | (v == 12345.f ? 0x80000000u : 0u);   // keeps the loop alive
+    }
+}
+
 __global__ void fill_u32_kernel(uint32_t *p, size_t n, uint32_t v) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
@@ -381,6 +394,11 @@ int launch_direct(const OpArgs &a, void *stream) {
         case MT_BF16: return launch_typed<bf16>(a, st);
     }
     return (int)hipErrorInvalidValue;
+}
+
+int launch_probe(uint32_t *out, int n_groups, void *stream) {
+    hipLaunchKernelGGL(probe_kernel, dim3((unsigned)n_groups), dim3(64), 0, (hipStream_t)stream, out);
+    return (int)hipGetLastError();
 }
 
 int launch_fill_u32(uint32_t *p, size_t n, uint32_t v, void *stream) {

@@ -293,6 +293,21 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     const int frag_row = lane % MF;
     const int frag_k = (lane / MF) * 8;
 
+    // Bias of this lane's output channels, fetched before the main loop so that the epilogue of a short,
+    // latency-bound workgroup does not start with another round trip to memory (the bank is padded to n_pad).
+    constexpr int GROUPS = ACC_REGS / 4;
+    constexpr bool BIAS_EARLY = TN * GROUPS <= 4;
+    float4 bias_pre[BIAS_EARLY ? TN * GROUPS : 1];
+    if constexpr (BIAS_EARLY) {
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int g = 0; g < GROUPS; ++g) {
+                const int k = n0 + wn * SUBN + i * MF + ((MF == 32) ? (8 * g + 4 * (lane / 32)) : (4 * (lane / 16)));
+                bias_pre[i * GROUPS + g] = *reinterpret_cast<const float4 *>(a.bias + k);
+            }
+    }
+
     // MFMA operand fragments of one LDS tile.
     struct Frags {
         u32x4 a[KSTEPS][TN], b[KSTEPS][TM];
@@ -481,7 +496,6 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     T *y = (T *)a.y;
     const T *res = (const T *)a.res;
     const bool vec_ok = (a.y_ct % 4 == 0) && (a.y_coff % 4 == 0) && (a.res_ct % 4 == 0);
-    constexpr int GROUPS = ACC_REGS / 4;
 #pragma unroll
     for (int i = 0; i < TN; ++i)
 #pragma unroll
@@ -495,7 +509,9 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
                 float v[4];
 #pragma unroll
                 for (int t = 0; t < 4; ++t) v[t] = acc[i][j][g * 4 + t];
-                const float4 b = *reinterpret_cast<const float4 *>(a.bias + k);    // bias is padded to n_pad
+                float4 b;
+                if constexpr (BIAS_EARLY) b = bias_pre[i * GROUPS + g];
+                else b = *reinterpret_cast<const float4 *>(a.bias + k);    // bias is padded to n_pad
                 v[0] += b.x; v[1] += b.y; v[2] += b.z; v[3] += b.w;
                 if (vec_ok && k + 4 <= a.K) {
                     if (res) {

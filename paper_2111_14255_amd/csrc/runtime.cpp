@@ -12,6 +12,10 @@
 #include <cstring>
 #include <map>
 #include <set>
+#include <atomic>
+#include <condition_variable>
+#include <mutex>
+#include <thread>
 #include <memory>
 
 #include "internal.h"
@@ -87,7 +91,7 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
     const int tiles = cdiv(M, bm) * (p.n_pad / bn);
     const int nkt = p.k_pad / IGEMM_BK;
     int target = (kid == K_IGEMM_64x16) ? 2048 : 768;
-    int max_split = 8, min_kt = 2;
+    int max_split = 8, min_kt = 6;    // a split below 6 reduction tiles costs more in the partial-sum exchange than it saves
     if (const char *e = std::getenv("MTSCHED_TUNE_TARGET")) target = std::atoi(e);
     if (const char *e = std::getenv("MTSCHED_TUNE_MAXSPLIT")) max_split = std::atoi(e);
     if (const char *e = std::getenv("MTSCHED_TUNE_MINKT")) min_kt = std::atoi(e);
@@ -261,6 +265,25 @@ struct StreamKey {
     bool operator<(const StreamKey &o) const { return tenant != o.tenant ? tenant < o.tenant : share < o.share; }
 };
 
+struct mt_schedule;
+
+// Issuing threads of MT_SCHED_PARALLEL_ISSUE: worker w launches everything that goes to tenant w's stream.
+struct IssuePool {
+    std::vector<std::thread> threads;
+    std::mutex mu;
+    std::condition_variable cv;
+    uint64_t run_seq = 0;           // guarded by mu
+    bool quit = false;              // guarded by mu
+    mt_schedule *sched = nullptr;   // the run being issued
+    const void *const *inputs = nullptr;
+    void *const *outputs = nullptr;
+    std::atomic<int> stage_posted{-1};            // stages up to this one may be issued (their gate event is recorded)
+    std::atomic<int> stage_done[MT_MAX_STAGES];   // workers that finished issuing the stage
+    std::atomic<int> finished{0};                 // workers that left the run
+    std::atomic<int> error{0};
+    std::string error_msg;                        // guarded by mu
+};
+
 struct mt_ctx {
     int device = 0;
     hipDeviceProp_t prop{};
@@ -278,11 +301,17 @@ struct mt_ctx {
     // Schedules created from this context and not destroyed yet; mt_destroy detaches them so that a later
     // mt_schedule_destroy does not touch the freed context.
     std::set<mt_schedule *> live_schedules;
+    IssuePool pool;
+    // Masked streams whose hardware queue dispatches slowly (see get_stream) are parked: kept alive, never used.
+    std::vector<hipStream_t> parked_streams;
+    uint32_t *probe_buf = nullptr;
+    float best_dispatch_us = 0.f;
 };
 
 struct StagePlan {
     std::vector<IssueItem> items;
     std::vector<int> streams;       // distinct streams used, ascending
+    std::vector<std::vector<IssueItem>> by_stream;   // items of each stream (index = tenant that owns the stream), in issue order
 };
 
 struct mt_schedule {
@@ -329,6 +358,8 @@ inline OpArgs patched(const Tenant &t, int op, const void *in, void *out) {
     return a;
 }
 
+int32_t dispatch_latency_us(mt_ctx *ctx, hipStream_t st, uint32_t *scratch, int n, float *us);
+
 // Stream of a tenant restricted to `share` compute units (0 = all).  Tenant i's units start where the
 // shares of the tenants before it end, so disjoint shares give disjoint units.
 int32_t get_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t *out, StreamKey *out_key) {
@@ -365,7 +396,20 @@ int32_t get_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t
             const int cu = (first_cu + j) % cus;
             mask[cu / 32] |= 1u << (cu % 32);
         }
-        HIP_TRY(hipExtStreamCreateWithCUMask(&s, (uint32_t)mask.size(), mask.data()));
+        // On MI355X roughly one in four CU-masked queues dispatches dependent kernels about 1.5x slower than the
+        // others (measured: 16 us against 11 us per launch of a fixed probe kernel, in creation order 1, 5, 9, ...;
+        // whole tenants then run 2x slower).  A new queue is therefore timed, and a slow one is parked (kept alive so
+        // that its hardware slot stays taken) and replaced by the next one.
+        if (!ctx->probe_buf) HIP_TRY(hipMalloc((void **)&ctx->probe_buf, 256));
+        for (int attempt = 0;; ++attempt) {
+            HIP_TRY(hipExtStreamCreateWithCUMask(&s, (uint32_t)mask.size(), mask.data()));
+            float us = 0.f;
+            int32_t rc = dispatch_latency_us(ctx, s, ctx->probe_buf, 12, &us);
+            if (rc != MT_OK) { (void)hipStreamDestroy(s); return rc; }
+            if (ctx->best_dispatch_us == 0.f || us < ctx->best_dispatch_us) ctx->best_dispatch_us = us;
+            if (us <= 1.2f * ctx->best_dispatch_us || attempt == 3) break;
+            ctx->parked_streams.push_back(s);
+        }
     }
     ctx->streams[key] = mt_ctx::StreamEntry{s, 1};
     *out = s;
@@ -406,6 +450,107 @@ int32_t issue_schedule(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, v
         gate = ctx->ev_stage[st];
     }
     if (n_launch) *n_launch = launches;
+    return MT_OK;
+}
+
+inline void spin_pause() {
+#if defined(__x86_64__)
+    __builtin_ia32_pause();
+#endif
+}
+
+void issue_worker(mt_ctx *ctx, int w) {
+    IssuePool &pool = ctx->pool;
+    (void)hipSetDevice(ctx->device);
+    uint64_t seen = 0;
+    for (;;) {
+        {
+            std::unique_lock<std::mutex> lk(pool.mu);
+            pool.cv.wait(lk, [&] { return pool.quit || pool.run_seq != seen; });
+            if (pool.quit) return;
+            seen = pool.run_seq;
+        }
+        mt_schedule *s = pool.sched;
+        if (w < s->n_tenants) {
+            for (int st = 0; st < s->n_stages; ++st) {
+                const StagePlan &sp = s->stages[st];
+                if (sp.by_stream[w].empty()) continue;
+                while (pool.stage_posted.load(std::memory_order_acquire) < st) spin_pause();
+                hipEvent_t gate = st == 0 ? ctx->ev_start : ctx->ev_stage[st - 1];
+                hipError_t e = hipStreamWaitEvent(s->stream_of[w], gate, 0);
+                for (const IssueItem &it : sp.by_stream[w]) {
+                    if (e != hipSuccess) break;
+                    const Tenant &t = *ctx->tenants[it.tenant];
+                    OpArgs a = patched(t, it.op, pool.inputs[it.tenant], pool.outputs[it.tenant]);
+                    int rc = is_gemm_kernel(a.kernel_id) ? launch_igemm(a, s->stream_of[w]) : launch_direct(a, s->stream_of[w]);
+                    if (rc != 0) e = (hipError_t)rc;
+                }
+                if (e == hipSuccess) e = hipEventRecord(ctx->ev_done[st][w], s->stream_of[w]);
+                if (e != hipSuccess) {
+                    std::lock_guard<std::mutex> lk(pool.mu);
+                    pool.error_msg = std::string("issuing thread: ") + hipGetErrorString(e);
+                    pool.error.store(1);
+                }
+                pool.stage_done[st].fetch_add(1, std::memory_order_release);
+            }
+        }
+        pool.finished.fetch_add(1, std::memory_order_release);
+    }
+}
+
+int32_t ensure_pool(mt_ctx *ctx, int n) {
+    while ((int)ctx->pool.threads.size() < n) {
+        const int w = (int)ctx->pool.threads.size();
+        ctx->pool.threads.emplace_back(issue_worker, ctx, w);
+    }
+    return MT_OK;
+}
+
+void stop_pool(mt_ctx *ctx) {
+    {
+        std::lock_guard<std::mutex> lk(ctx->pool.mu);
+        ctx->pool.quit = true;
+    }
+    ctx->pool.cv.notify_all();
+    for (auto &t : ctx->pool.threads) t.join();
+    ctx->pool.threads.clear();
+}
+
+// Same event structure as issue_schedule, with the launches of a stage spread over one host thread per stream.
+int32_t issue_schedule_parallel(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *const *outputs, int *n_launch) {
+    IssuePool &pool = ctx->pool;
+    int32_t rc = ensure_pool(ctx, s->n_tenants);
+    if (rc != MT_OK) return rc;
+    const int n_workers = (int)pool.threads.size();
+    pool.sched = s;
+    pool.inputs = inputs;
+    pool.outputs = outputs;
+    pool.stage_posted.store(-1);
+    for (int st = 0; st < MT_MAX_STAGES; ++st) pool.stage_done[st].store(0);
+    pool.finished.store(0);
+    pool.error.store(0);
+    HIP_TRY(hipEventRecord(ctx->ev_start, ctx->main_stream));
+    {
+        std::lock_guard<std::mutex> lk(pool.mu);
+        ++pool.run_seq;
+    }
+    pool.cv.notify_all();
+    hipError_t err = hipSuccess;
+    for (int st = 0; st < s->n_stages; ++st) {
+        const StagePlan &sp = s->stages[st];
+        pool.stage_posted.store(st, std::memory_order_release);
+        while (pool.stage_done[st].load(std::memory_order_acquire) < (int)sp.streams.size()) spin_pause();
+        for (int sm : sp.streams)
+            if (err == hipSuccess) err = hipStreamWaitEvent(ctx->main_stream, ctx->ev_done[st][sm], 0);
+        if (err == hipSuccess) err = hipEventRecord(ctx->ev_stage[st], ctx->main_stream);
+    }
+    while (pool.finished.load(std::memory_order_acquire) < n_workers) spin_pause();
+    if (pool.error.load()) {
+        std::lock_guard<std::mutex> lk(pool.mu);
+        return fail(MT_ERR_HIP, pool.error_msg);
+    }
+    if (err != hipSuccess) return fail(MT_ERR_HIP, std::string("parallel issue: ") + hipGetErrorString(err));
+    if (n_launch) *n_launch = s->n_launches;
     return MT_OK;
 }
 
@@ -455,6 +600,7 @@ int32_t mt_create(int32_t device, mt_ctx **out) {
 int32_t mt_destroy(mt_ctx *ctx) {
     if (!ctx) return fail(MT_ERR_INVALID_ARG, "ctx is NULL");
     (void)hipSetDevice(ctx->device);
+    stop_pool(ctx);
     (void)hipDeviceSynchronize();
     for (mt_schedule *ls : ctx->live_schedules) {
         if (ls->graph_exec) ctx->retired_graphs.push_back(ls->graph_exec);
@@ -463,6 +609,8 @@ int32_t mt_destroy(mt_ctx *ctx) {
     }
     for (hipGraphExec_t g : ctx->retired_graphs) (void)hipGraphExecDestroy(g);
     for (auto &kv : ctx->streams) (void)hipStreamDestroy(kv.second.stream);
+    for (hipStream_t ps : ctx->parked_streams) (void)hipStreamDestroy(ps);
+    if (ctx->probe_buf) (void)hipFree(ctx->probe_buf);
     if (ctx->main_stream) (void)hipStreamDestroy(ctx->main_stream);
     if (ctx->ev_start) (void)hipEventDestroy(ctx->ev_start);
     for (int s = 0; s < MT_MAX_STAGES; ++s) {
@@ -490,6 +638,88 @@ int32_t mt_get_device_info(const mt_ctx *ctx, mt_device_info *out) {
     std::strncpy(out->name, ctx->prop.name, sizeof(out->name) - 1);
     std::strncpy(out->arch, ctx->prop.gcnArchName, sizeof(out->arch) - 1);
     return MT_OK;
+}
+
+int32_t mt_probe_cu_mask(mt_ctx *ctx, int32_t share, int32_t first_cu, int32_t n_groups, uint32_t *hw_ids) {
+    if (!ctx || !hw_ids) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    const int cus = ctx->prop.multiProcessorCount;
+    if (share < 0 || share > cus || first_cu < 0 || first_cu >= cus || n_groups < 1 || n_groups > (1 << 20))
+        return fail(MT_ERR_INVALID_ARG, "share, first_cu or n_groups out of range");
+    HIP_TRY(hipSetDevice(ctx->device));
+    hipStream_t st = nullptr;
+    if (share == 0) {
+        HIP_TRY(hipStreamCreateWithFlags(&st, hipStreamNonBlocking));
+    } else {
+        std::vector<uint32_t> mask((cus + 31) / 32, 0u);
+        for (int j = 0; j < share; ++j) {
+            const int cu = (first_cu + j) % cus;
+            mask[cu / 32] |= 1u << (cu % 32);
+        }
+        HIP_TRY(hipExtStreamCreateWithCUMask(&st, (uint32_t)mask.size(), mask.data()));
+    }
+    uint32_t *dev = nullptr;
+    hipError_t e = hipMalloc((void **)&dev, sizeof(uint32_t) * 2 * n_groups);
+    if (e == hipSuccess) {
+        int rc = launch_probe(dev, n_groups, st);
+        e = rc ? (hipError_t)rc : hipStreamSynchronize(st);
+        if (e == hipSuccess) e = hipMemcpy(hw_ids, dev, sizeof(uint32_t) * 2 * n_groups, hipMemcpyDeviceToHost);
+        (void)hipFree(dev);
+    }
+    (void)hipStreamDestroy(st);
+    if (e != hipSuccess) return fail(MT_ERR_HIP, std::string("probe: ") + hipGetErrorString(e));
+    return MT_OK;
+}
+
+namespace {
+// Mean time per launch of n dependent one-workgroup kernels on `st`, measured the way a stage runs: the main stream
+// records a start event, the stream waits for it, runs, records its done event, the main stream waits for that.
+int32_t dispatch_latency_us(mt_ctx *ctx, hipStream_t st, uint32_t *scratch, int n, float *us) {
+    for (int rep = 0; rep < 2; ++rep) {          // first pass warms up
+        HIP_TRY(hipEventRecord(ctx->ev_prof[0], ctx->main_stream));
+        HIP_TRY(hipStreamWaitEvent(st, ctx->ev_prof[0], 0));
+        for (int i = 0; i < n; ++i) {
+            int rc = launch_probe(scratch, 1, st);
+            if (rc) return fail(MT_ERR_HIP, std::string("probe launch: ") + hipGetErrorString((hipError_t)rc));
+        }
+        HIP_TRY(hipEventRecord(ctx->ev_done[0][0], st));
+        HIP_TRY(hipStreamWaitEvent(ctx->main_stream, ctx->ev_done[0][0], 0));
+        HIP_TRY(hipEventRecord(ctx->ev_prof[1], ctx->main_stream));
+        HIP_TRY(hipEventSynchronize(ctx->ev_prof[1]));
+    }
+    float ms = 0;
+    HIP_TRY(hipEventElapsedTime(&ms, ctx->ev_prof[0], ctx->ev_prof[1]));
+    *us = ms * 1e3f / n;
+    return MT_OK;
+}
+}  // namespace
+
+int32_t mt_probe_dispatch_latency(mt_ctx *ctx, int32_t n_streams, int32_t share, int32_t n_launches, float *us_per_launch) {
+    if (!ctx || !us_per_launch) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    const int cus = ctx->prop.multiProcessorCount;
+    if (n_streams < 1 || n_streams > 64 || n_launches < 1 || share < 0 || share > cus) return fail(MT_ERR_INVALID_ARG, "argument out of range");
+    HIP_TRY(hipSetDevice(ctx->device));
+    std::vector<hipStream_t> streams;
+    uint32_t *dev = nullptr;
+    HIP_TRY(hipMalloc((void **)&dev, 64));
+    int32_t rc = MT_OK;
+    for (int i = 0; i < n_streams && rc == MT_OK; ++i) {
+        hipStream_t st = nullptr;
+        hipError_t e;
+        if (share == 0) {
+            e = hipStreamCreateWithFlags(&st, hipStreamNonBlocking);
+        } else {
+            std::vector<uint32_t> mask((cus + 31) / 32, 0u);
+            for (int j = 0; j < share; ++j) mask[j / 32] |= 1u << (j % 32);
+            e = hipExtStreamCreateWithCUMask(&st, (uint32_t)mask.size(), mask.data());
+        }
+        if (e != hipSuccess) { rc = fail(MT_ERR_HIP, std::string("stream create: ") + hipGetErrorString(e)); break; }
+        streams.push_back(st);
+        rc = dispatch_latency_us(ctx, st, dev, n_launches, &us_per_launch[i]);
+    }
+    (void)hipDeviceSynchronize();
+    for (hipStream_t st : streams) (void)hipStreamDestroy(st);
+    (void)hipFree(dev);
+    return rc;
 }
 
 // ---- model ---------------------------------------------------------------------------------
@@ -710,6 +940,8 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
     if (n_tenants != (int)ctx->tenants.size() || n_tenants < 1)
         return fail(MT_ERR_INVALID_SCHEDULE, "schedule must cover exactly the registered tenants");
     if (order != MT_ISSUE_BFS && order != MT_ISSUE_DFS) return fail(MT_ERR_INVALID_ARG, "unknown issue order");
+    if ((flags & MT_SCHED_GRAPH) && (flags & MT_SCHED_PARALLEL_ISSUE))
+        return fail(MT_ERR_INVALID_ARG, "graph replay and parallel issue cannot be combined");
     int32_t lens[MT_MAX_TENANTS];
     for (int i = 0; i < n_tenants; ++i) lens[i] = (int32_t)ctx->tenants[i]->model.ops.size();
     int32_t rc = validate_pointers(n_tenants, lens, n_stages, pointers);
@@ -740,6 +972,8 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
         for (const IssueItem &it : sp.items)
             if (std::find(sp.streams.begin(), sp.streams.end(), it.stream) == sp.streams.end()) sp.streams.push_back(it.stream);
         std::sort(sp.streams.begin(), sp.streams.end());
+        sp.by_stream.assign(n_tenants, {});
+        for (const IssueItem &it : sp.items) sp.by_stream[it.stream].push_back(it);
         s->n_launches += (int)sp.items.size();
     }
     ctx->live_schedules.insert(s.get());
@@ -791,7 +1025,8 @@ int32_t mt_run(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *con
         HIP_TRY(hipGraphLaunch(s->graph_exec, ctx->main_stream));
         HIP_TRY(hipEventRecord(ctx->ev_prof[1], ctx->main_stream));
     } else {
-        int32_t rc = issue_schedule(ctx, s, inputs, outputs, &launches);
+        int32_t rc = (s->flags & MT_SCHED_PARALLEL_ISSUE) ? issue_schedule_parallel(ctx, s, inputs, outputs, &launches)
+                                                          : issue_schedule(ctx, s, inputs, outputs, &launches);
         if (rc != MT_OK) return rc;
     }
     const auto t1 = std::chrono::steady_clock::now();

@@ -25,13 +25,15 @@ def check_config(name, extra_schedules=()):
         scheds = [ctx.sequential(), ctx.all_concurrent(),
                   ctx.schedule(even_split(lens, cfg.n_stages), cfg.n_stages, label="even-split"),
                   ctx.schedule(even_split(lens, cfg.n_stages), cfg.n_stages, order=B.MT_ISSUE_DFS, label="even-split-dfs"),
-                  ctx.schedule(even_split(lens, 2), 2, flags=B.MT_SCHED_GRAPH, label="graph")]
+                  ctx.schedule(even_split(lens, 2), 2, flags=B.MT_SCHED_GRAPH, label="graph"),
+                  ctx.schedule(even_split(lens, cfg.n_stages), cfg.n_stages, flags=B.MT_SCHED_PARALLEL_ISSUE, label="parallel-issue"),
+                  ctx.all_concurrent(flags=B.MT_SCHED_PARALLEL_ISSUE)]
         scheds += [f(ctx, lens) for f in extra_schedules]
         ref = mix.oracle()
         first = None
         for s in scheds:
             print("  schedule", s.label, flush=True)
-            reps = 3 if s.label == "graph" else 1
+            reps = 3 if s.label in ("graph", "parallel-issue") else 1
             for _ in range(reps):                      # a graph is replayed several times, each replay checked
                 got, tm = mix.run(s)
                 assert tm["n_launches"] == sum(lens)
