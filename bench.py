@@ -148,7 +148,7 @@ def main():
     t0 = time.perf_counter()
     rho, cost, records, shares = ctx.search(inputs, outputs, cfg.n_stages, rounds=args.search_rounds,
                                             candidates=args.search_candidates, runs=5, warmup=1, seed=cfg.seed,
-                                            cu_share_rounds=1)
+                                            cu_share_rounds=2)
     search_s = time.perf_counter() - t0
     sched = ctx.schedule(rho, cfg.n_stages, cu_share=shares)
     results["searched+cu_share"] = time_schedule(ctx, torch, sched, inputs, outputs, args.warmup, args.steps)
@@ -166,7 +166,10 @@ def main():
     fam = kernel_rooflines(ctx, inputs, outputs, cfg.dtype, repeats=10)
     dom = max(fam, key=lambda k: fam[k]["ms"])
     f = fam[dom]
-    if dom.startswith("igemm") or dom == "conv_direct":
+    # The family is priced against the MFMA peak when its arithmetic intensity (algorithmic flops per algorithmic
+    # byte over its launches) is above the ridge of the chip, against the HBM peak otherwise.
+    ridge = PEAK_TFLOPS[cfg.dtype] * 1e12 / (PEAK_HBM_GBS * 1e9)
+    if f["bytes"] > 0 and f["flops"] / f["bytes"] >= ridge:
         achieved = f["flops"] / (f["ms"] * 1e-3) / 1e12
         roof = {"kernel": dom, "bound": "mfma", "achieved": achieved, "peak": PEAK_TFLOPS[cfg.dtype], "unit": "TFLOP/s",
                 "frac": achieved / PEAK_TFLOPS[cfg.dtype]}
@@ -174,6 +177,7 @@ def main():
         achieved = f["bytes"] / (f["ms"] * 1e-3) / 1e9
         roof = {"kernel": dom, "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": achieved / PEAK_HBM_GBS}
+    roof["arithmetic_intensity_flop_per_byte"] = f["flops"] / f["bytes"] if f["bytes"] else None
     roof["launches_per_step"] = f["launches"]
     roof["avg_launch_us"] = f["ms"] * 1e3 / f["launches"]
     roof["traffic"] = measured_traffic(cfg.name, dom)
