@@ -96,7 +96,7 @@ def test_conv_igemm(name, kw, kid, dtype):
         info = mix.ctx.op_info(0, main)
         if kid is not None:
             assert info.kernel_id == kid, (info.kernel_id, info.split_k, info.out_h, info.out_w)
-        if "splitk" in name:
+        if "splitk" in name and not name.endswith("_big"):   # the enlarged copy has enough tiles without a split
             assert info.split_k > 1
         got, _ = mix.run(mix.ctx.sequential())
         assert_close(got[0], mix.oracle()[0], dtype, name)
