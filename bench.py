@@ -37,7 +37,8 @@ def time_schedule(ctx, torch, sched, inputs, outputs, warmup, steps):
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
     mk.sort()
     return {"wall_ms_per_step": wall_ms, "makespan_ms_mean": sum(mk) / len(mk), "makespan_ms_min": mk[0],
-            "makespan_ms_median": mk[len(mk) // 2], "host_issue_ms_mean": sum(issue) / len(issue)}
+            "makespan_ms_median": mk[len(mk) // 2], "makespan_ms_p90": mk[(len(mk) * 9) // 10 if len(mk) > 1 else 0],
+            "host_issue_ms_mean": sum(issue) / len(issue)}
 
 
 def kernel_rooflines(ctx, inputs, outputs, dtype, repeats):
@@ -88,8 +89,8 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", default="cfg2")
-    ap.add_argument("--search-rounds", type=int, default=2)
-    ap.add_argument("--search-candidates", type=int, default=6)
+    ap.add_argument("--search-rounds", type=int, default=3)
+    ap.add_argument("--search-candidates", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--roofline-only", action="store_true",
@@ -136,7 +137,7 @@ def main():
         allc = ctx.all_concurrent(flags=flags)
         t0 = time.perf_counter()
         rho, cost, records = ctx.search(inputs, outputs, cfg.n_stages, rounds=args.search_rounds,
-                                        candidates=args.search_candidates, runs=5, warmup=1, seed=cfg.seed, flags=flags)
+                                        candidates=args.search_candidates, runs=7, warmup=1, seed=cfg.seed, flags=flags)
         search_s = time.perf_counter() - t0
         searched = ctx.schedule(rho, cfg.n_stages, flags=flags)
         for name, s in (("sequential", seq), ("all_concurrent", allc), ("searched", searched)):
@@ -147,7 +148,7 @@ def main():
     # searched pointers plus searched per-tenant CU shares (stream CU masks; not available under graph replay)
     t0 = time.perf_counter()
     rho, cost, records, shares = ctx.search(inputs, outputs, cfg.n_stages, rounds=args.search_rounds,
-                                            candidates=args.search_candidates, runs=5, warmup=1, seed=cfg.seed,
+                                            candidates=args.search_candidates, runs=7, warmup=1, seed=cfg.seed,
                                             cu_share_rounds=2)
     search_s = time.perf_counter() - t0
     sched = ctx.schedule(rho, cfg.n_stages, cu_share=shares)

@@ -191,7 +191,10 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
  * that have work are ranked in tenant order and rank j is issued on the stream of rank j mod c; c = 1 runs
  * them one after another on one stream (the sequential baseline), c >= active tenants is the paper's
  * one-stream-per-model.
- * cu_share: host [n_tenants] or NULL.  Number of compute units tenant i's stream may use; 0 = all.
+ * cu_share: host [n_tenants] or NULL.  Number of compute units tenant i's stream may use; 0 = all.  The ranges are
+ * laid out one after another (tenant i starts where tenant i-1 ended, modulo the unit count), so shares that sum to
+ * at most the unit count are disjoint.  A share between 1 and 7 is rejected with MT_ERR_INVALID_SCHEDULE: consecutive
+ * mask bits fall on the 8 XCDs in turn and the runtime refuses a mask that leaves an XCD without a unit.
  * issue_order: MT_ISSUE_BFS issues one operator per stream round-robin (Sec. III-D), MT_ISSUE_DFS stream by stream.
  * flags: MT_SCHED_GRAPH captures the whole schedule into a HIP graph on the first run and replays it
  * afterwards (CU shares are ignored in that mode: graph nodes do not inherit stream CU masks). */
@@ -255,17 +258,29 @@ int32_t mt_search_pointers(int32_t n_tenants, const int32_t *lens, const mt_sear
                            int32_t *rec_pointers, double *rec_cost, int32_t max_records, int32_t *n_records);
 
 /* Per-tenant CU share as one more coordinate per tenant (an extension; the paper leaves resource sharing to the
- * hardware, Sec. III-A(b)).  Host only, any cost function.  Start: every share 0 (= all units).  Each round visits the
- * tenants in order; for a tenant the candidates k * cu_count / 8, k = 1..7, are evaluated with the other shares fixed,
- * and the candidate replaces the tenant's share if its cost is lower than the best cost so far.
- * share_cost: cost of a share vector (host [n_tenants]).  best_share: host [n_tenants]; *best_cost: in = cost of
- * all-zero shares, out = best cost found. */
+ * hardware, Sec. III-A(b)).  Host only, any cost function.  Start: the share vector passed in best_share (all zeros =
+ * every tenant on all units).  Each round visits the tenants in order; for a tenant the candidates k * cu_count / 8,
+ * k = 1..7, are evaluated with the other shares fixed, and the candidate replaces the tenant's share if its cost is
+ * lower than the best cost so far.
+ * share_cost: cost of a share vector (host [n_tenants]).  best_share: host [n_tenants], in = start, out = best found;
+ * *best_cost: in = cost of the start vector, out = best cost found. */
 typedef double (*mt_share_cost_fn)(const int32_t *cu_share, void *user);
 int32_t mt_search_cu_share(int32_t n_tenants, int32_t cu_count, int32_t rounds, mt_share_cost_fn share_cost, void *user,
                            int32_t *best_share, double *best_cost);
 
-/* The same searches with the profiled makespan of mt_run as cost, all tenants on their own stream.
- * best_cu_share: host [n_tenants] or NULL; filled with zeros unless opts->cu_share_rounds > 0. */
+/* A disjoint start vector for that search: the units are dealt out in eighths of cu_count; every tenant owns one eighth,
+ * the 8 - n_tenants spare eighths go to the tenants in proportion to weight[] (host [n_tenants], >= 0, e.g. the serial
+ * latency of each tenant) by largest remainder, lower index first on ties; with more than 8 tenants every share is one
+ * eighth (the ranges then overlap).  share: host [n_tenants]. */
+int32_t mt_proportional_cu_share(int32_t n_tenants, int32_t cu_count, const double *weight, int32_t *share);
+
+/* The same searches with the profiled makespan of mt_run as cost (median of opts->runs timed runs after opts->warmup
+ * untimed ones), all tenants on their own stream.
+ * best_cu_share: host [n_tenants] or NULL; filled with zeros unless opts->cu_share_rounds > 0.  With
+ * opts->cu_share_rounds > 0 three phases run: the pointer search on unmasked streams (the only phase written to the
+ * records); the share descent under those pointers, started from the better of all-zero shares and
+ * mt_proportional_cu_share of the tenants' serial latencies; and, if a share came out non-zero and n_stages > 1, the
+ * pointer search once more under those shares, kept only when its best cost is lower. */
 int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *inputs, void *const *outputs,
                   int32_t *best_pointers, int32_t *best_cu_share, double *best_cost,
                   int32_t *rec_pointers, double *rec_cost, int32_t max_records, int32_t *n_records);

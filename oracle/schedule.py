@@ -18,6 +18,7 @@ Readings where the paper is silent:
   * Random draws come from a counter-based generator so that an independent
     implementation can reproduce them: draw(seed, a, b, c, d) below.
 """
+import math
 
 M64 = (1 << 64) - 1
 
@@ -160,11 +161,41 @@ def random_search(lens, n_pointers, evaluations, cost, seed, seed_baselines=Fals
     return records[best][0], records[best][1], records, skipped
 
 
-def cu_share_descent(n_tenants, cu_count, rounds, cost, start_cost):
-    """Extension: per-tenant CU share as one more coordinate.  Start with all shares 0 (= every unit); per
-    round and tenant, try k * cu_count // 8 for k = 1..7 with the other shares fixed; a candidate replaces
-    the tenant's share when its cost is lower than the best so far."""
-    cur = [0] * n_tenants
+def proportional_shares(weights, cu_count):
+    """Extension: a disjoint start vector for the share descent.  Units are dealt out in eighths of cu_count;
+    every tenant owns one eighth, the spare eighths follow the weights by largest remainder (lower index first
+    on ties); with more than 8 tenants every share is one eighth."""
+    n = len(weights)
+    units = [1] * n
+    spare = 8 - n
+    total = 0.0
+    for w in weights:
+        total += float(w)
+    if spare > 0 and total > 0:
+        frac = []
+        given = 0
+        for i, w in enumerate(weights):
+            quota = float(spare) * float(w) / total
+            whole = int(math.floor(quota))
+            units[i] += whole
+            given += whole
+            frac.append(quota - whole)
+        while given < spare:
+            pick = max(range(n), key=lambda i: (frac[i], -i))
+            units[pick] += 1
+            frac[pick] = -1.0
+            given += 1
+    elif spare > 0:
+        for k in range(spare):
+            units[k % n] += 1
+    return [u * (cu_count // 8) for u in units]
+
+
+def cu_share_descent(n_tenants, cu_count, rounds, cost, start_cost, start=None):
+    """Extension: per-tenant CU share as one more coordinate.  Start with the given vector (default: all
+    shares 0 = every unit); per round and tenant, try k * cu_count // 8 for k = 1..7 with the other shares
+    fixed; a candidate replaces the tenant's share when its cost is lower than the best so far."""
+    cur = list(start) if start is not None else [0] * n_tenants
     best = start_cost
     for _ in range(rounds):
         for i in range(n_tenants):

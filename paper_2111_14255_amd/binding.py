@@ -95,6 +95,7 @@ SIGNATURES = {
     "mt_profile_ops": (_i32, [_vp, _i32, _vp, _vp, _i32, _pf]),
     "mt_search_pointers": (_i32, [_i32, _pi32, C.POINTER(mt_search_opts), mt_cost_fn, _vp, _pi32, _pd, _pi32, _pd, _i32, _pi32]),
     "mt_search_cu_share": (_i32, [_i32, _i32, _i32, mt_share_cost_fn, _vp, _pi32, _pd]),
+    "mt_proportional_cu_share": (_i32, [_i32, _i32, _pd, _pi32]),
     "mt_search": (_i32, [_vp, C.POINTER(mt_search_opts), C.POINTER(_vp), C.POINTER(_vp), _pi32, _pi32, _pd, _pi32, _pd, _i32, _pi32]),
 }
 

@@ -360,6 +360,23 @@ inline OpArgs patched(const Tenant &t, int op, const void *in, void *out) {
 
 int32_t dispatch_latency_us(mt_ctx *ctx, hipStream_t st, uint32_t *scratch, int n, float *us);
 
+// Destroys every masked stream no schedule refers to, and the parked ones with them (the next masked streams are
+// timed again, so a slow queue slot that becomes free is parked again when it comes up).
+int32_t purge_idle_streams(mt_ctx *ctx) {
+    HIP_TRY(hipDeviceSynchronize());
+    for (auto e = ctx->streams.begin(); e != ctx->streams.end();) {
+        if (e->second.refs == 0 && e->first.share != 0) {
+            (void)hipStreamDestroy(e->second.stream);
+            e = ctx->streams.erase(e);
+        } else {
+            ++e;
+        }
+    }
+    for (hipStream_t p : ctx->parked_streams) (void)hipStreamDestroy(p);
+    ctx->parked_streams.clear();
+    return MT_OK;
+}
+
 // Stream of a tenant restricted to `share` compute units (0 = all).  Tenant i's units start where the
 // shares of the tenants before it end, so disjoint shares give disjoint units.
 int32_t get_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t *out, StreamKey *out_key) {
@@ -368,22 +385,15 @@ int32_t get_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t
     auto it = ctx->streams.find(key);
     if (it != ctx->streams.end()) { it->second.refs++; *out = it->second.stream; return MT_OK; }
     // A search over CU shares creates many masked streams, each with a hardware queue of its own.  Too many
-    // queues make the hardware scheduler time-slice them, which slows every stream of the process: release
-    // the unreferenced masked streams before they pile up.
+    // queues make the hardware scheduler time-slice them, which slows every stream of the process and adds
+    // stalls of 10-20 ms every few dozen runs: release the unreferenced masked streams before they pile up.
     if (share != 0) {
-        int idle = 0;
+        int idle = (int)ctx->parked_streams.size();
         for (auto &e : ctx->streams)
             if (e.second.refs == 0 && e.first.share != 0) ++idle;
         if (idle >= 6) {
-            HIP_TRY(hipDeviceSynchronize());
-            for (auto e = ctx->streams.begin(); e != ctx->streams.end();) {
-                if (e->second.refs == 0 && e->first.share != 0) {
-                    (void)hipStreamDestroy(e->second.stream);
-                    e = ctx->streams.erase(e);
-                } else {
-                    ++e;
-                }
-            }
+            int32_t rc = purge_idle_streams(ctx);
+            if (rc != MT_OK) return rc;
         }
     }
     hipStream_t s = nullptr;
@@ -951,6 +961,9 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
         if (stage_concurrency && stage_concurrency[s] < 1) return fail(MT_ERR_INVALID_SCHEDULE, "stage concurrency must be >= 1");
     for (int i = 0; i < n_tenants; ++i)
         if (cu_share && (cu_share[i] < 0 || cu_share[i] > cus)) return fail(MT_ERR_INVALID_SCHEDULE, "CU share out of range");
+    for (int i = 0; i < n_tenants; ++i)
+        if (cu_share && cu_share[i] > 0 && cu_share[i] < 8)
+            return fail(MT_ERR_INVALID_SCHEDULE, "a CU share must be 0 (all units) or at least 8: a mask has to leave every one of the 8 XCDs a unit");
     HIP_TRY(hipSetDevice(ctx->device));
     std::unique_ptr<mt_schedule> s(new mt_schedule);
     s->ctx = ctx; s->n_tenants = n_tenants; s->n_stages = n_stages; s->flags = flags;
@@ -1109,14 +1122,21 @@ double profile_schedule(ProfileCost *pc, const int32_t *pointers, const int32_t 
     pc->rc = mt_schedule_create(pc->ctx, pc->n_tenants, pc->o->n_stages, pointers, nullptr, cu_share, pc->o->issue_order,
                                 pc->o->flags, &s);
     if (pc->rc != MT_OK) return 1e30;
-    double sum = 0;
+    // The profiled latency of a candidate is the median of its timed runs: one preempted run must not decide
+    // a comparison between two schedules that differ by a few percent.
+    std::vector<double> samples;
     for (int r = 0; r < pc->o->warmup + pc->o->runs && pc->rc == MT_OK; ++r) {
         mt_timings tm;
         pc->rc = mt_run(pc->ctx, s, pc->inputs, pc->outputs, &tm);
-        if (r >= pc->o->warmup) sum += tm.makespan_ms;
+        if (r >= pc->o->warmup) samples.push_back(tm.makespan_ms);
     }
     mt_schedule_destroy(s);
-    const double c = pc->rc == MT_OK ? sum / pc->o->runs : 1e30;
+    double c = 1e30;
+    if (pc->rc == MT_OK && !samples.empty()) {
+        std::sort(samples.begin(), samples.end());
+        const size_t h = samples.size() / 2;
+        c = samples.size() % 2 ? samples[h] : 0.5 * (samples[h - 1] + samples[h]);
+    }
     if (trace) { std::fprintf(stderr, "[mtsched]   cost %.4f ms rc %d\n", c, pc->rc); std::fflush(stderr); }
     return c;
 }
@@ -1151,9 +1171,53 @@ int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *in
     if (rc != MT_OK) return rc;
     int32_t shares[MT_MAX_TENANTS] = {0};
     if (opts->cu_share_rounds > 0) {
+        // Shares are searched under the pointers just found.  The descent starts from the better of two vectors:
+        // all zeros (every tenant on every unit, whose cost is known) and a disjoint split in proportion to the serial
+        // latency of each tenant; a descent from all zeros alone rarely leaves it, because one masked tenant
+        // among unmasked ones gains nothing.
         pc.pointers = best_pointers;
-        rc = search_cu_share(n, ctx->prop.multiProcessorCount, opts->cu_share_rounds, profile_share_cost, &pc, shares, &cost);
+        const int cus = ctx->prop.multiProcessorCount;
+        double weight[MT_MAX_TENANTS];
+        std::vector<float> op_ms;
+        for (int i = 0; i < n; ++i) {
+            op_ms.assign((size_t)lens[i], 0.f);
+            rc = mt_profile_ops(ctx, i, inputs[i], outputs[i], 3, op_ms.data());
+            if (rc != MT_OK) return rc;
+            weight[i] = 0;
+            for (float v : op_ms) weight[i] += v;
+        }
+        int32_t start[MT_MAX_TENANTS];
+        rc = proportional_cu_share(n, cus, weight, start);
+        if (rc != MT_OK) return rc;
+        const double start_cost = profile_share_cost(start, &pc);
         if (pc.rc != MT_OK) return pc.rc;
+        if (start_cost < cost) {
+            std::memcpy(shares, start, sizeof(int32_t) * n);
+            cost = start_cost;
+        }
+        rc = search_cu_share(n, cus, opts->cu_share_rounds, profile_share_cost, &pc, shares, &cost);
+        if (pc.rc != MT_OK) return pc.rc;
+        if (rc != MT_OK) return rc;
+        bool masked = false;
+        for (int i = 0; i < n; ++i) masked = masked || shares[i] != 0;
+        if (masked && opts->n_stages > 1) {
+            // The stage boundaries were chosen while the tenants competed for every unit; search them once more under
+            // the shares found and keep the result only if it is better.
+            pc.cu_share = shares;
+            std::vector<int32_t> rho2((size_t)n * (opts->n_stages - 1));
+            double cost2 = 0;
+            int32_t n2 = 0;
+            rc = search_pointers(n, lens, opts, profile_cost, &pc, rho2.data(), &cost2, nullptr, nullptr, 0, &n2);
+            if (pc.rc != MT_OK) return pc.rc;
+            if (rc != MT_OK) return rc;
+            if (cost2 < cost) {
+                std::memcpy(best_pointers, rho2.data(), sizeof(int32_t) * rho2.size());
+                cost = cost2;
+            }
+        }
+    }
+    if (opts->cu_share_rounds > 0) {
+        rc = purge_idle_streams(ctx);     // leave the caller a process with few hardware queues
         if (rc != MT_OK) return rc;
     }
     if (best_cu_share) std::memcpy(best_cu_share, shares, sizeof(int32_t) * n);

@@ -3,6 +3,7 @@
 #include "internal.h"
 
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 
 namespace mt {
@@ -193,12 +194,50 @@ int32_t search_pointers(int32_t n_tenants, const int32_t *lens, const mt_search_
     return MT_OK;
 }
 
+int32_t proportional_cu_share(int32_t n_tenants, int32_t cu_count, const double *weight, int32_t *share) {
+    if (!weight || !share) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (n_tenants < 1 || n_tenants > MT_MAX_TENANTS || cu_count < 8)
+        return fail(MT_ERR_INVALID_ARG, "bad tenant count or CU count");
+    double total = 0;
+    for (int i = 0; i < n_tenants; ++i) {
+        if (!(weight[i] >= 0)) return fail(MT_ERR_INVALID_ARG, "weights must be non-negative");
+        total += weight[i];
+    }
+    const int unit = cu_count / 8;
+    std::vector<int32_t> units(n_tenants, 1);            // every tenant owns at least one eighth
+    const int spare = 8 - n_tenants;
+    if (spare > 0 && total > 0) {
+        std::vector<double> frac(n_tenants);
+        int given = 0;
+        for (int i = 0; i < n_tenants; ++i) {
+            const double quota = (double)spare * weight[i] / total;
+            const int whole = (int)std::floor(quota);
+            units[i] += whole;
+            given += whole;
+            frac[i] = quota - (double)whole;
+        }
+        for (; given < spare; ++given) {                 // largest remainder first, lower index on ties
+            int pick = 0;
+            for (int i = 1; i < n_tenants; ++i)
+                if (frac[i] > frac[pick]) pick = i;
+            units[pick] += 1;
+            frac[pick] = -1.0;
+        }
+    } else if (spare > 0) {
+        for (int k = 0; k < spare; ++k) units[k % n_tenants] += 1;
+    }
+    for (int i = 0; i < n_tenants; ++i) share[i] = units[i] * unit;
+    return MT_OK;
+}
+
 int32_t search_cu_share(int32_t n_tenants, int32_t cu_count, int32_t rounds, mt_share_cost_fn cost, void *user,
                         int32_t *best_share, double *best_cost) {
     if (!cost || !best_share || !best_cost) return fail(MT_ERR_INVALID_ARG, "NULL argument");
     if (n_tenants < 1 || n_tenants > MT_MAX_TENANTS || cu_count < 8 || rounds < 1)
         return fail(MT_ERR_INVALID_ARG, "bad tenant count, CU count or rounds");
-    std::vector<int32_t> cur(n_tenants, 0), cand(n_tenants, 0);
+    std::vector<int32_t> cur(best_share, best_share + n_tenants), cand(n_tenants, 0);
+    for (int i = 0; i < n_tenants; ++i)
+        if (cur[i] < 0 || cur[i] > cu_count) return fail(MT_ERR_INVALID_ARG, "start share out of range");
     double best = *best_cost;
     for (int r = 0; r < rounds; ++r)
         for (int i = 0; i < n_tenants; ++i)
@@ -220,6 +259,10 @@ int32_t search_cu_share(int32_t n_tenants, int32_t cu_count, int32_t rounds, mt_
 }  // namespace mt
 
 extern "C" {
+
+int32_t mt_proportional_cu_share(int32_t n_tenants, int32_t cu_count, const double *weight, int32_t *share) {
+    return mt::proportional_cu_share(n_tenants, cu_count, weight, share);
+}
 
 int32_t mt_search_cu_share(int32_t n_tenants, int32_t cu_count, int32_t rounds, mt_share_cost_fn share_cost, void *user,
                            int32_t *best_share, double *best_cost) {

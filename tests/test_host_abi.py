@@ -267,3 +267,51 @@ def test_cu_share_descent_matches_oracle():
     oshare, ocost = S.cu_share_descent(3, 256, 2, lambda sh: (ocalls.append(list(sh)) or cost(sh)), cost([0, 0, 0]))
     assert [best[i] for i in range(3)] == oshare == [64, 160, 32]
     assert bc.value == ocost and calls == ocalls
+
+
+def test_cu_share_descent_from_a_start_vector():
+    target = [32, 160, 64]
+
+    def cost(sh):
+        return float(sum(abs((a or 256) - b) for a, b in zip(sh, target))) + 1.0
+
+    start = [64, 96, 96]
+    best = (I32 * 3)(*start)
+    bc = C.c_double(cost(start))
+    calls, ocalls = [], []
+    fn = B.mt_share_cost_fn(lambda ptr, _u: (calls.append([ptr[i] for i in range(3)]) or cost(calls[-1])))
+    assert B.load().mt_search_cu_share(3, 256, 1, fn, None, best, C.byref(bc)) == 0
+    oshare, ocost = S.cu_share_descent(3, 256, 1, lambda sh: (ocalls.append(list(sh)) or cost(sh)), cost(start), start)
+    assert [best[i] for i in range(3)] == oshare == target
+    assert bc.value == ocost == 1.0 and calls == ocalls
+    bad = (I32 * 3)(64, 300, 0)
+    assert B.load().mt_search_cu_share(3, 256, 1, fn, None, bad, C.byref(bc)) != 0
+
+
+def test_proportional_cu_share():
+    lib = B.load()
+
+    def host(w, cus=256):
+        out = (I32 * len(w))()
+        assert lib.mt_proportional_cu_share(len(w), cus, (C.c_double * len(w))(*w), out) == 0
+        return [out[i] for i in range(len(w))]
+
+    # hand-worked: 5 spare eighths, quotas 1.163 / 1.954 / 1.883 -> floors 1,1,1, the two left go to tenants 1 and 2
+    assert host([147.0, 247.0, 238.0]) == [64, 96, 96] == S.proportional_shares([147.0, 247.0, 238.0], 256)
+    assert host([1.0, 1.0]) == [128, 128]
+    assert host([3.0, 1.0]) == [192, 64]     # 6 spare eighths, quotas 4.5 / 1.5: tie on the remainder, lower index first
+    assert host([0.0, 0.0, 0.0]) == [96, 96, 64] == S.proportional_shares([0.0, 0.0, 0.0], 256)
+    assert host([1.0] * 8) == [32] * 8
+    assert host([5.0] * 12) == [32] * 12 == S.proportional_shares([5.0] * 12, 256)
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        n = int(rng.integers(1, 9))
+        w = [float(x) for x in rng.uniform(0.0, 10.0, n)]
+        sh = host(w)
+        assert sh == S.proportional_shares(w, 256)
+        assert sum(sh) == 256 and min(sh) >= 32 and all(v % 32 == 0 for v in sh)
+        for i in range(n):                                       # monotone: a heavier tenant never gets less
+            for j in range(n):
+                if w[i] > w[j]:
+                    assert sh[i] >= sh[j]
+    assert lib.mt_proportional_cu_share(3, 256, (C.c_double * 3)(1.0, -1.0, 1.0), (I32 * 3)()) != 0
