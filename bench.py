@@ -155,6 +155,10 @@ def main():
     results["searched+cu_share"] = time_schedule(ctx, torch, sched, inputs, outputs, args.warmup, args.steps)
     results["searched+cu_share"].update({"pointers": rho, "cu_share": shares, "search_seconds": search_s,
                                          "search_evaluations": len(records)})
+    # the same schedule issued by one host thread per tenant stream instead of the single main thread
+    sched_pi = ctx.schedule(rho, cfg.n_stages, cu_share=shares, flags=B.MT_SCHED_PARALLEL_ISSUE)
+    results["searched+cu_share+parallel_issue"] = time_schedule(ctx, torch, sched_pi, inputs, outputs, args.warmup, args.steps)
+    results["searched+cu_share+parallel_issue"].update({"pointers": rho, "cu_share": shares})
     for k, r in results.items():
         base = results["sequential" + ("+graph" if k.endswith("+graph") else "")]
         r["img_per_s"] = images / (r["wall_ms_per_step"] * 1e-3)

@@ -119,13 +119,16 @@ typedef struct mt_device_info {
  * makespan_ms: from the event recorded before the first operator of any tenant may start to the
  * event recorded after the last operator of every tenant has finished (Sec. III-A objective).
  * stage_ms[s]: from the previous barrier (or the start) to the barrier that ends stage s.
- * host_issue_ms: wall time the issuing thread spent launching (Sec. III-D "invoking overhead"). */
+ * host_issue_ms: wall time the issuing thread spent launching (Sec. III-D "invoking overhead").
+ * first_op_done_ms[i]: only with MT_SCHED_TIME_FIRST_OP, else 0: from the start to the end of tenant i's first
+ * operator, i.e. how long stream i was held back by the issue of the streams before it (Sec. III-D, Fig. 5). */
 typedef struct mt_timings {
     float makespan_ms;
     float host_issue_ms;
     int32_t n_launches;
     int32_t n_stages;
     float stage_ms[MT_MAX_STAGES];
+    float first_op_done_ms[MT_MAX_TENANTS];
 } mt_timings;
 
 /* ---- error reporting ---------------------------------------------------------------- */
@@ -203,6 +206,9 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
  * (Sec. III-D); the operators of a stage are launched by the threads of its streams concurrently, stage barriers and
  * results are unchanged.  Not combinable with MT_SCHED_GRAPH. */
 #define MT_SCHED_PARALLEL_ISSUE 2
+/* MT_SCHED_TIME_FIRST_OP: records one more event per tenant, after its first operator, and reports it in
+ * mt_timings.first_op_done_ms.  Only with the single issuing thread on plain streams (neither flag above). */
+#define MT_SCHED_TIME_FIRST_OP 4
 int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, const int32_t *pointers,
                            const int32_t *stage_concurrency, const int32_t *cu_share,
                            int32_t issue_order, int32_t flags, mt_schedule **out);

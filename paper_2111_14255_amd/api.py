@@ -239,7 +239,8 @@ class Context:
         tm = B.mt_timings()
         B.check(self.lib.mt_run(self.h, sched.h, ins, outs, C.byref(tm)))
         return {"makespan_ms": tm.makespan_ms, "host_issue_ms": tm.host_issue_ms, "n_launches": tm.n_launches,
-                "stage_ms": [tm.stage_ms[i] for i in range(tm.n_stages)]}
+                "stage_ms": [tm.stage_ms[i] for i in range(tm.n_stages)],
+                "first_op_done_ms": [tm.first_op_done_ms[i] for i in range(n)]}
 
     def profile_ops(self, tenant, inp, out, repeats=5):
         n = self.lens()[tenant]

@@ -25,6 +25,7 @@ MT_ACT_NONE, MT_ACT_RELU, MT_ACT_RELU6 = 0, 1, 2
 MT_ISSUE_BFS, MT_ISSUE_DFS = 0, 1
 MT_SCHED_GRAPH = 1
 MT_SCHED_PARALLEL_ISSUE = 2
+MT_SCHED_TIME_FIRST_OP = 4
 MT_SEARCH_COORDINATE, MT_SEARCH_RANDOM = 0, 1
 
 
@@ -48,7 +49,8 @@ class mt_device_info(C.Structure):
 
 class mt_timings(C.Structure):
     _fields_ = [("makespan_ms", C.c_float), ("host_issue_ms", C.c_float), ("n_launches", C.c_int32),
-                ("n_stages", C.c_int32), ("stage_ms", C.c_float * MT_MAX_STAGES)]
+                ("n_stages", C.c_int32), ("stage_ms", C.c_float * MT_MAX_STAGES),
+                ("first_op_done_ms", C.c_float * MT_MAX_TENANTS)]
 
 
 class mt_search_opts(C.Structure):

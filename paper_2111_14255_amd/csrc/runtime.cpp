@@ -295,6 +295,7 @@ struct mt_ctx {
     hipEvent_t ev_stage[MT_MAX_STAGES]{};
     hipEvent_t ev_done[MT_MAX_STAGES][MT_MAX_TENANTS]{};
     hipEvent_t ev_prof[2]{};
+    hipEvent_t ev_first[MT_MAX_TENANTS]{};   // after the first operator of each tenant (MT_SCHED_TIME_FIRST_OP)
     // Graph executables of destroyed schedules.  They are released only at mt_destroy, after a device-wide
     // synchronisation: destroying one right after its last launch has crashed inside the HIP runtime.
     std::vector<hipGraphExec_t> retired_graphs;
@@ -312,6 +313,7 @@ struct StagePlan {
     std::vector<IssueItem> items;
     std::vector<int> streams;       // distinct streams used, ascending
     std::vector<std::vector<IssueItem>> by_stream;   // items of each stream (index = tenant that owns the stream), in issue order
+    int prev_stage = -1;            // latest earlier stage that launched anything (-1: none)
 };
 
 struct mt_schedule {
@@ -435,29 +437,45 @@ void release_streams(mt_schedule *s) {
     s->n_keys = 0;
 }
 
-// Issues the whole schedule on the tenant streams.  Barrier between stages: every stream of the stage
-// records an event, the main stream waits for all of them and records the stage event, and every stream of
-// the next stage waits for that.
+// A stream about to run stage st waits for the start event (no earlier work) or, directly, for the end of every other
+// stream of the latest earlier stage with work; those streams waited the same way, so all earlier stages are complete.
+// One cross-queue hop per barrier instead of two through the main stream.
+// Under graph capture the barrier goes through the main stream as before (every stream waits for the stage event the
+// main stream recorded): capturing the direct form ended in a host crash of the capture/instantiate path whose cause
+// is not known, so that combination is switched off.
+hipError_t wait_for_previous_stage(mt_ctx *ctx, const mt_schedule *s, int st, int stream) {
+    if (s->flags & MT_SCHED_GRAPH)
+        return hipStreamWaitEvent(s->stream_of[stream], st == 0 ? ctx->ev_start : ctx->ev_stage[st - 1], 0);
+    const int prev = s->stages[st].prev_stage;
+    if (prev < 0) return hipStreamWaitEvent(s->stream_of[stream], ctx->ev_start, 0);
+    hipError_t e = hipSuccess;
+    for (int pm : s->stages[prev].streams)
+        if (pm != stream && e == hipSuccess) e = hipStreamWaitEvent(s->stream_of[stream], ctx->ev_done[prev][pm], 0);
+    return e;
+}
+
+// Issues the whole schedule on the tenant streams.  Barrier between stages: every stream of the stage records an
+// event and the streams of the next stage wait for all of them; the main stream waits for them too and records the
+// stage event, which only the timings and the final synchronisation use.
 int32_t issue_schedule(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *const *outputs, int *n_launch) {
     HIP_TRY(hipEventRecord(ctx->ev_start, ctx->main_stream));
-    hipEvent_t gate = ctx->ev_start;
     int launches = 0;
     for (int st = 0; st < s->n_stages; ++st) {
         const StagePlan &sp = s->stages[st];
-        for (int sm : sp.streams) HIP_TRY(hipStreamWaitEvent(s->stream_of[sm], gate, 0));
+        for (int sm : sp.streams) HIP_TRY(wait_for_previous_stage(ctx, s, st, sm));
         for (const IssueItem &it : sp.items) {
             const Tenant &t = *ctx->tenants[it.tenant];
             OpArgs a = patched(t, it.op, inputs[it.tenant], outputs[it.tenant]);
             int32_t rc = launch_op(a, s->stream_of[it.stream]);
             if (rc != MT_OK) return rc;
             ++launches;
+            if ((s->flags & MT_SCHED_TIME_FIRST_OP) && it.op == 0) HIP_TRY(hipEventRecord(ctx->ev_first[it.tenant], s->stream_of[it.stream]));
         }
         for (int sm : sp.streams) {
             HIP_TRY(hipEventRecord(ctx->ev_done[st][sm], s->stream_of[sm]));
             HIP_TRY(hipStreamWaitEvent(ctx->main_stream, ctx->ev_done[st][sm], 0));
         }
         HIP_TRY(hipEventRecord(ctx->ev_stage[st], ctx->main_stream));
-        gate = ctx->ev_stage[st];
     }
     if (n_launch) *n_launch = launches;
     return MT_OK;
@@ -486,8 +504,7 @@ void issue_worker(mt_ctx *ctx, int w) {
                 const StagePlan &sp = s->stages[st];
                 if (sp.by_stream[w].empty()) continue;
                 while (pool.stage_posted.load(std::memory_order_acquire) < st) spin_pause();
-                hipEvent_t gate = st == 0 ? ctx->ev_start : ctx->ev_stage[st - 1];
-                hipError_t e = hipStreamWaitEvent(s->stream_of[w], gate, 0);
+                hipError_t e = wait_for_previous_stage(ctx, s, st, w);
                 for (const IssueItem &it : sp.by_stream[w]) {
                     if (e != hipSuccess) break;
                     const Tenant &t = *ctx->tenants[it.tenant];
@@ -601,6 +618,7 @@ int32_t mt_create(int32_t device, mt_ctx **out) {
         HIP_TRY(hipEventCreate(&c->ev_stage[s]));
         for (int t = 0; t < MT_MAX_TENANTS; ++t) HIP_TRY(hipEventCreateWithFlags(&c->ev_done[s][t], hipEventDisableTiming));
     }
+    for (int t = 0; t < MT_MAX_TENANTS; ++t) HIP_TRY(hipEventCreate(&c->ev_first[t]));
     HIP_TRY(hipEventCreate(&c->ev_prof[0]));
     HIP_TRY(hipEventCreate(&c->ev_prof[1]));
     *out = c.release();
@@ -628,6 +646,8 @@ int32_t mt_destroy(mt_ctx *ctx) {
         for (int t = 0; t < MT_MAX_TENANTS; ++t)
             if (ctx->ev_done[s][t]) (void)hipEventDestroy(ctx->ev_done[s][t]);
     }
+    for (auto e : ctx->ev_first)
+        if (e) (void)hipEventDestroy(e);
     for (auto e : ctx->ev_prof)
         if (e) (void)hipEventDestroy(e);
     for (auto &t : ctx->tenants)
@@ -952,6 +972,8 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
     if (order != MT_ISSUE_BFS && order != MT_ISSUE_DFS) return fail(MT_ERR_INVALID_ARG, "unknown issue order");
     if ((flags & MT_SCHED_GRAPH) && (flags & MT_SCHED_PARALLEL_ISSUE))
         return fail(MT_ERR_INVALID_ARG, "graph replay and parallel issue cannot be combined");
+    if ((flags & MT_SCHED_TIME_FIRST_OP) && (flags & (MT_SCHED_GRAPH | MT_SCHED_PARALLEL_ISSUE)))
+        return fail(MT_ERR_INVALID_ARG, "first-operator timing needs the single issuing thread and plain streams");
     int32_t lens[MT_MAX_TENANTS];
     for (int i = 0; i < n_tenants; ++i) lens[i] = (int32_t)ctx->tenants[i]->model.ops.size();
     int32_t rc = validate_pointers(n_tenants, lens, n_stages, pointers);
@@ -988,6 +1010,10 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
         sp.by_stream.assign(n_tenants, {});
         for (const IssueItem &it : sp.items) sp.by_stream[it.stream].push_back(it);
         s->n_launches += (int)sp.items.size();
+    }
+    for (int st = 0, last = -1; st < n_stages; ++st) {
+        s->stages[st].prev_stage = last;
+        if (!s->stages[st].items.empty()) last = st;
     }
     ctx->live_schedules.insert(s.get());
     *out = s.release();
@@ -1058,6 +1084,10 @@ int32_t mt_run(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *con
             HIP_TRY(hipEventElapsedTime(&tm->makespan_ms, ctx->ev_prof[0], ctx->ev_prof[1]));
         } else {
             HIP_TRY(hipEventElapsedTime(&tm->makespan_ms, ctx->ev_start, ctx->ev_stage[s->n_stages - 1]));
+            if (s->flags & MT_SCHED_TIME_FIRST_OP)
+                for (int i = 0; i < s->n_tenants; ++i)
+                    if (!ctx->tenants[i]->model.ops.empty())
+                        HIP_TRY(hipEventElapsedTime(&tm->first_op_done_ms[i], ctx->ev_start, ctx->ev_first[i]));
             hipEvent_t prev = ctx->ev_start;
             for (int st = 0; st < s->n_stages; ++st) {
                 HIP_TRY(hipEventElapsedTime(&tm->stage_ms[st], prev, ctx->ev_stage[st]));
