@@ -286,7 +286,10 @@ int32_t mt_proportional_cu_share(int32_t n_tenants, int32_t cu_count, const doub
  * opts->cu_share_rounds > 0 three phases run: the pointer search on unmasked streams (the only phase written to the
  * records); the share descent under those pointers, started from the better of all-zero shares and
  * mt_proportional_cu_share of the tenants' serial latencies; and, if a share came out non-zero and n_stages > 1, the
- * pointer search once more under those shares, kept only when its best cost is lower. */
+ * pointer search once more under those shares, kept only when its best cost is lower.  A masked result is measured
+ * again on fresh streams before it is returned (they stay in the context's pool, so a schedule created next with the
+ * same shares runs on exactly those streams); if it does not beat the unmasked result there, the unmasked pointers and
+ * all-zero shares are returned. */
 int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *inputs, void *const *outputs,
                   int32_t *best_pointers, int32_t *best_cu_share, double *best_cost,
                   int32_t *rec_pointers, double *rec_cost, int32_t max_records, int32_t *n_records);
