@@ -16,7 +16,7 @@ def even_split(lens, n_stages):
 
 
 def check_config(name, extra_schedules=()):
-    cfg = configs.CONFIGS[name]
+    cfg = configs.ALL[name]
     print("config", name, flush=True)
     mix = Mix(cfg.models(), cfg.seed, cfg.input_dist)
     try:
@@ -80,3 +80,33 @@ def test_cfg5_eight_resnet50_batch16_bf16_cu_masks():
     # 8 tenants on 8 disjoint 32-CU shares, 8 stages
     mix = check_config("cfg5", [lambda ctx, lens: ctx.schedule(even_split(lens, 8), 8, cu_share=[32] * 8, label="cu-shares-8x32")])
     mix.close()
+
+
+def test_paper_mix_r18_r34_fp16_with_share_search_and_first_op_timing():
+    # a tenant combination of the paper's tables (adds ResNet-34), plus the flags no other test covers
+    mix = check_config("mix_r18_r34", [
+        lambda ctx, lens: ctx.schedule(even_split(lens, 3), 3, flags=B.MT_SCHED_TIME_FIRST_OP, label="first-op-timing"),
+        lambda ctx, lens: ctx.schedule(even_split(lens, 2), 2, cu_share=[96, 160], flags=B.MT_SCHED_PARALLEL_ISSUE, label="shares-parallel"),
+    ])
+    try:
+        ctx = mix.ctx
+        lens = ctx.lens()
+        s = ctx.schedule([[], []], 1, order=B.MT_ISSUE_DFS, flags=B.MT_SCHED_TIME_FIRST_OP)
+        _, tm = mix.run(s)
+        first = tm["first_op_done_ms"]
+        assert 0 < first[0] < first[1] < tm["makespan_ms"]       # DFS: the second stream starts after the first is issued
+        ref = mix.oracle()
+        outs = [ctx.make_output(t) for t in range(2)]
+        rho, cost, rec, shares = ctx.search(mix.inputs, outs, 3, rounds=1, candidates=3, runs=3, warmup=1, seed=9,
+                                            cu_share_rounds=1)
+        assert len(shares) == 2 and all(v == 0 or (v % 32 == 0 and 32 <= v <= 224) for v in shares)
+        assert cost <= min(c for _, c in rec) * 1.15      # a masked winner is re-measured, the unmasked one is in the records
+        got, _ = mix.run(ctx.schedule(rho, 3, cu_share=shares))
+        for t in range(2):
+            assert_close(got[t], ref[t], "f16", "searched schedule tenant %d" % t)
+        with pytest.raises(B.MtError):
+            ctx.schedule([[], []], 1, cu_share=[4, 0])             # a share that cannot cover the 8 XCDs
+        with pytest.raises(B.MtError):
+            ctx.schedule([[], []], 1, flags=B.MT_SCHED_TIME_FIRST_OP | B.MT_SCHED_GRAPH)
+    finally:
+        mix.close()
