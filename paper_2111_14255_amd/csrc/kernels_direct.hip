@@ -8,19 +8,36 @@
 
 namespace mt {
 
+// Linear element index -> (channel vector, column, row, image).  Tensors stay below 2^31 elements (checked when a
+// model is finalised), so the index arithmetic is 32-bit: a 64-bit division costs several hundred instructions,
+// which is a large part of a kernel that otherwise makes one memory round trip.
+struct ElemIdx {
+    int cv, q, p, n;
+    uint32_t m;       // pixel index (n * P + p) * Q + q
+};
+__device__ inline ElemIdx split_index(uint32_t g, int CV, int Q, int P) {
+    ElemIdx e;
+    e.m = g / (uint32_t)CV;
+    e.cv = (int)(g - e.m * (uint32_t)CV);
+    const uint32_t t = e.m / (uint32_t)Q;
+    e.q = (int)(e.m - t * (uint32_t)Q);
+    const uint32_t n = t / (uint32_t)P;
+    e.p = (int)(t - n * (uint32_t)P);
+    e.n = (int)n;
+    return e;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Direct convolution / fully connected: one thread per output element, output channel fastest.
 // Sum order is fixed (r, s, c), so the result does not depend on the launch environment.
 template <typename T>
 __global__ void __launch_bounds__(256) conv_direct_kernel(OpArgs a) {
-    const int64_t total = (int64_t)a.N * a.P * a.Q * a.K;
-    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t total = (uint32_t)a.N * a.P * a.Q * a.K;
+    const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= total) return;
-    const int k = (int)(gid % a.K);
-    int64_t m = gid / a.K;
-    const int q = (int)(m % a.Q);
-    const int p = (int)((m / a.Q) % a.P);
-    const int n = (int)(m / ((int64_t)a.Q * a.P));
+    const ElemIdx e = split_index(gid, a.K, a.Q, a.P);
+    const int k = e.cv, q = e.q, p = e.p, n = e.n;
+    const int64_t m = e.m;
     const T *x = (const T *)a.x;
     const T *w = (const T *)a.w + (int64_t)k * a.R * a.S * a.C;
     float acc = 0.f;
@@ -44,24 +61,17 @@ __global__ void __launch_bounds__(256) conv_direct_kernel(OpArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Depthwise convolution.  One thread per (pixel, V-channel vector); weights repacked as [R][S][C] so
+// Depthwise convolution, any window.  One thread per (pixel, V-channel vector); weights repacked as [R][S][C] so
 // that the weight vector of a tap is one contiguous load, shared by every pixel through the caches.
-// For stride 1 the lanes that hold the left and right neighbour pixels of the same channel vector sit
-// CV lanes away in the wave: the three taps of a filter row are obtained by loading only the centre
-// column and exchanging it with the neighbours through wavefront shuffles; lanes at a wave or image-row
-// edge fall back to a load.
-template <typename T, int V, bool SHUFFLE>
+template <typename T, int V>
 __global__ void __launch_bounds__(256) dwconv_kernel(OpArgs a) {
     const int CV = a.C / V;
-    const int64_t total = (int64_t)a.N * a.P * a.Q * CV;
-    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const bool live = gid < total;
-    const int64_t g = live ? gid : total - 1;   // dead lanes shadow a real element so shuffles stay defined
-    const int cv = (int)(g % CV);
-    int64_t m = g / CV;
-    const int q = (int)(m % a.Q);
-    const int p = (int)((m / a.Q) % a.P);
-    const int n = (int)(m / ((int64_t)a.Q * a.P));
+    const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
+    const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= total) return;
+    const ElemIdx e = split_index(gid, CV, a.Q, a.P);
+    const int cv = e.cv, q = e.q, p = e.p, n = e.n;
+    const int64_t m = e.m;
     const int c0 = cv * V;
     const T *x = (const T *)a.x;
     const T *w = (const T *)a.w;
@@ -69,64 +79,19 @@ __global__ void __launch_bounds__(256) dwconv_kernel(OpArgs a) {
 #pragma unroll
     for (int i = 0; i < V; ++i) acc[i] = 0.f;
 
-    if constexpr (SHUFFLE) {
-        // stride 1, S == 3, pad_w == 1: column of tap s is q - 1 + s.
-        const int lane = threadIdx.x & 63;
-        const int src_l = lane - CV, src_r = lane + CV;
-        // The neighbour lane holds pixel q-1 / q+1 of the same image row iff it is inside the wave and this
-        // pixel is not at the row edge (gid is linear in (n,p,q,cv), so +-CV lanes is +-1 pixel).
-        const bool l_ok = src_l >= 0 && q > 0;
-        const bool r_ok = src_r < 64 && q + 1 < a.Q && (gid + CV) < total;
-        for (int r = 0; r < a.R; ++r) {
-            const int ih = p - a.ph + r;
-            const bool row_ok = ih >= 0 && ih < a.H;
-            const T *xrow = x + (((int64_t)n * a.H + (row_ok ? ih : 0)) * a.W) * a.C + c0;
-            float ctr[V], lft[V], rgt[V];
+    for (int r = 0; r < a.R; ++r) {
+        const int ih = p * a.sh - a.ph + r;
+        if (ih < 0 || ih >= a.H) continue;
+        for (int s = 0; s < a.S; ++s) {
+            const int iw = q * a.sw - a.pw + s;
+            if (iw < 0 || iw >= a.W) continue;
+            float xv[V], wv[V];
+            load_pack<T, V>(x + (((int64_t)n * a.H + ih) * a.W + iw) * a.C + c0, xv);
+            load_pack<T, V>(w + ((int64_t)r * a.S + s) * a.C + c0, wv);
 #pragma unroll
-            for (int i = 0; i < V; ++i) ctr[i] = 0.f;
-            if (row_ok) load_pack<T, V>(xrow + (int64_t)q * a.C, ctr);
-#pragma unroll
-            for (int i = 0; i < V; ++i) {
-                lft[i] = __shfl(ctr[i], src_l & 63);
-                rgt[i] = __shfl(ctr[i], src_r & 63);
-            }
-            if (!l_ok) {
-#pragma unroll
-                for (int i = 0; i < V; ++i) lft[i] = 0.f;
-                if (row_ok && q > 0) load_pack<T, V>(xrow + (int64_t)(q - 1) * a.C, lft);
-            }
-            if (!r_ok) {
-#pragma unroll
-                for (int i = 0; i < V; ++i) rgt[i] = 0.f;
-                if (row_ok && q + 1 < a.W) load_pack<T, V>(xrow + (int64_t)(q + 1) * a.C, rgt);
-            }
-            float w0[V], w1[V], w2[V];
-            load_pack<T, V>(w + ((int64_t)r * 3 + 0) * a.C + c0, w0);
-            load_pack<T, V>(w + ((int64_t)r * 3 + 1) * a.C + c0, w1);
-            load_pack<T, V>(w + ((int64_t)r * 3 + 2) * a.C + c0, w2);
-#pragma unroll
-            for (int i = 0; i < V; ++i) {
-                acc[i] = fmaf(lft[i], w0[i], acc[i]);
-                acc[i] = fmaf(ctr[i], w1[i], acc[i]);
-                acc[i] = fmaf(rgt[i], w2[i], acc[i]);
-            }
-        }
-    } else {
-        for (int r = 0; r < a.R; ++r) {
-            const int ih = p * a.sh - a.ph + r;
-            if (ih < 0 || ih >= a.H) continue;
-            for (int s = 0; s < a.S; ++s) {
-                const int iw = q * a.sw - a.pw + s;
-                if (iw < 0 || iw >= a.W) continue;
-                float xv[V], wv[V];
-                load_pack<T, V>(x + (((int64_t)n * a.H + ih) * a.W + iw) * a.C + c0, xv);
-                load_pack<T, V>(w + ((int64_t)r * a.S + s) * a.C + c0, wv);
-#pragma unroll
-                for (int i = 0; i < V; ++i) acc[i] = fmaf(xv[i], wv[i], acc[i]);
-            }
+            for (int i = 0; i < V; ++i) acc[i] = fmaf(xv[i], wv[i], acc[i]);
         }
     }
-    if (!live) return;
 #pragma unroll
     for (int i = 0; i < V; ++i) {
         if (a.bias) acc[i] += a.bias[c0 + i];
@@ -142,18 +107,16 @@ __global__ void __launch_bounds__(256) dwconv_kernel(OpArgs a) {
 template <typename T, int V, int KS>
 __global__ void __launch_bounds__(256) dwconv_fixed_kernel(OpArgs a) {
     const int CV = a.C / V;
-    const int64_t total = (int64_t)a.N * a.P * a.Q * CV;
-    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
+    const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= total) return;
-    const int cv = (int)(gid % CV);
-    int64_t m = gid / CV;
-    const int q = (int)(m % a.Q);
-    const int p = (int)((m / a.Q) % a.P);
-    const int n = (int)(m / ((int64_t)a.Q * a.P));
+    const ElemIdx e = split_index(gid, CV, a.Q, a.P);
+    const int cv = e.cv, q = e.q, p = e.p, n = e.n;
+    const int64_t m = e.m;
     const int c0 = cv * V;
     const T *x = (const T *)a.x + (int64_t)n * a.H * a.W * a.C + c0;
     const T *w = (const T *)a.w + c0;
-    float xv[KS * KS][V], wv[KS * KS][V];
+    float xv[KS * KS][V], wv[KS * KS][V], bv[V];
     bool ok[KS * KS];
 #pragma unroll
     for (int r = 0; r < KS; ++r)
@@ -165,6 +128,12 @@ __global__ void __launch_bounds__(256) dwconv_fixed_kernel(OpArgs a) {
             load_pack<T, V>(x + ((int64_t)ihc * a.W + iwc) * a.C, xv[r * KS + s]);
             load_pack<T, V>(w + (int64_t)(r * KS + s) * a.C, wv[r * KS + s]);
         }
+    // the bias vector always exists (zeros when the layer has none): loaded with the taps, not after the sum
+#pragma unroll
+    for (int i = 0; i < V; i += 4) {
+        const float4 b4 = *reinterpret_cast<const float4 *>(a.bias + c0 + i);
+        bv[i] = b4.x; bv[i + 1] = b4.y; bv[i + 2] = b4.z; bv[i + 3] = b4.w;
+    }
     float acc[V];
 #pragma unroll
     for (int i = 0; i < V; ++i) acc[i] = 0.f;
@@ -173,24 +142,19 @@ __global__ void __launch_bounds__(256) dwconv_fixed_kernel(OpArgs a) {
 #pragma unroll
         for (int i = 0; i < V; ++i) acc[i] = ok[t] ? fmaf(xv[t][i], wv[t][i], acc[i]) : acc[i];
 #pragma unroll
-    for (int i = 0; i < V; ++i) {
-        if (a.bias) acc[i] += a.bias[c0 + i];
-        acc[i] = apply_act(acc[i], a.act);
-    }
+    for (int i = 0; i < V; ++i) acc[i] = apply_act(acc[i] + bv[i], a.act);
     store_pack<T, V>((T *)a.y + m * a.y_ct + a.y_coff + c0, acc);
 }
 
 template <typename T, int V, bool IS_MAX, int KS>
 __global__ void __launch_bounds__(256) pool_fixed_kernel(OpArgs a) {
     const int CV = a.C / V;
-    const int64_t total = (int64_t)a.N * a.P * a.Q * CV;
-    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
+    const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= total) return;
-    const int cv = (int)(gid % CV);
-    int64_t m = gid / CV;
-    const int q = (int)(m % a.Q);
-    const int p = (int)((m / a.Q) % a.P);
-    const int n = (int)(m / ((int64_t)a.Q * a.P));
+    const ElemIdx e = split_index(gid, CV, a.Q, a.P);
+    const int cv = e.cv, q = e.q, p = e.p, n = e.n;
+    const int64_t m = e.m;
     const int c0 = cv * V;
     const T *x = (const T *)a.x + (int64_t)n * a.H * a.W * a.C + c0;
     float xv[KS * KS][V];
@@ -227,14 +191,12 @@ __global__ void __launch_bounds__(256) pool_fixed_kernel(OpArgs a) {
 template <typename T, int V, bool IS_MAX>
 __global__ void __launch_bounds__(256) pool_kernel(OpArgs a) {
     const int CV = a.C / V;
-    const int64_t total = (int64_t)a.N * a.P * a.Q * CV;
-    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
+    const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= total) return;
-    const int cv = (int)(gid % CV);
-    int64_t m = gid / CV;
-    const int q = (int)(m % a.Q);
-    const int p = (int)((m / a.Q) % a.P);
-    const int n = (int)(m / ((int64_t)a.Q * a.P));
+    const ElemIdx e = split_index(gid, CV, a.Q, a.P);
+    const int cv = e.cv, q = e.q, p = e.p, n = e.n;
+    const int64_t m = e.m;
     const int c0 = cv * V;
     const T *x = (const T *)a.x;
     float acc[V];
@@ -282,11 +244,20 @@ __global__ void __launch_bounds__(256) gap_kernel(OpArgs a, int lanes_c) {
     float acc[V];
 #pragma unroll
     for (int i = 0; i < V; ++i) acc[i] = 0.f;
-    for (int i = slice; i < HW; i += lanes_hw) {
-        float xv[V];
-        load_pack<T, V>(x + (int64_t)i * a.C, xv);
+    // four pixels of the slice per round, loaded before any is added (clamped address + select, no branch)
+    for (int base = slice; base < HW; base += 4 * lanes_hw) {
+        float xv[4][V];
+        bool ok[4];
 #pragma unroll
-        for (int j = 0; j < V; ++j) acc[j] += xv[j];
+        for (int u = 0; u < 4; ++u) {
+            const int i = base + u * lanes_hw;
+            ok[u] = i < HW;
+            load_pack<T, V>(x + (int64_t)(ok[u] ? i : slice) * a.C, xv[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int j = 0; j < V; ++j) acc[j] = ok[u] ? acc[j] + xv[u][j] : acc[j];
     }
     for (int off = 32; off >= lanes_c; off >>= 1) {
 #pragma unroll
@@ -328,18 +299,14 @@ static int launch_typed(const OpArgs &a, hipStream_t st) {
             hipLaunchKernelGGL(conv_direct_kernel<T>, blocks((int64_t)a.N * a.P * a.Q * a.K), block, 0, st, a);
             break;
         case K_DWCONV: {
-            const bool shuffle = a.sh == 1 && a.sw == 1 && a.S == 3 && a.pw == 1 && a.vec == VMAX &&
-                                 (a.C / VMAX) < 64 && 64 % (a.C / VMAX) == 0;
             if (a.vec == VMAX) {
                 const int64_t th = (int64_t)a.N * a.P * a.Q * (a.C / VMAX);
-                if (shuffle)
-                    hipLaunchKernelGGL((dwconv_kernel<T, VMAX, true>), blocks(th), block, 0, st, a);
-                else if (a.R == 3 && a.S == 3)
+                if (a.R == 3 && a.S == 3)
                     hipLaunchKernelGGL((dwconv_fixed_kernel<T, VMAX, 3>), blocks(th), block, 0, st, a);
                 else
-                    hipLaunchKernelGGL((dwconv_kernel<T, VMAX, false>), blocks(th), block, 0, st, a);
+                    hipLaunchKernelGGL((dwconv_kernel<T, VMAX>), blocks(th), block, 0, st, a);
             } else {
-                hipLaunchKernelGGL((dwconv_kernel<T, 1, false>), blocks((int64_t)a.N * a.P * a.Q * a.C), block, 0, st, a);
+                hipLaunchKernelGGL((dwconv_kernel<T, 1>), blocks((int64_t)a.N * a.P * a.Q * a.C), block, 0, st, a);
             }
             break;
         }
@@ -371,7 +338,7 @@ static int launch_typed(const OpArgs &a, hipStream_t st) {
             const int V = a.vec == VMAX ? VMAX : 1;
             const int CV = a.C / V;
             int lanes_c = 1;
-            while (lanes_c < 16 && lanes_c < CV) lanes_c <<= 1;    // at least 4 spatial slices per wave
+            while (lanes_c < 4 && lanes_c < CV) lanes_c <<= 1;     // at least 16 spatial slices per wave
             const int groups = (CV + lanes_c - 1) / lanes_c;
             const int64_t th = (int64_t)a.N * groups * 64;
             if (V == VMAX)

@@ -562,6 +562,9 @@ __global__ void __launch_bounds__(256) gemv_kernel(OpArgs a) {
     for (int r = 0; r < ROWS; ++r)
 #pragma unroll
         for (int m = 0; m < MB; ++m) acc[r][m] = 0.f;
+    float bias_k[ROWS];                              // fetched before the dot product, not after it (the bank is padded)
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) bias_k[r] = a.bias[k0 + r];
     constexpr int UNROLL = 4;
     for (int j0 = lane * 8; j0 < J; j0 += 64 * 8 * UNROLL) {
         u32x4 wv[UNROLL][ROWS], xv[UNROLL][MB];
@@ -611,7 +614,7 @@ __global__ void __launch_bounds__(256) gemv_kernel(OpArgs a) {
 #pragma unroll
             for (int m = 0; m < MB; ++m) {
                 if (m >= a.N) continue;
-                float f = acc[r][m] + a.bias[k];
+                float f = acc[r][m] + bias_k[r];
                 if (res) f += to_f32(res[(int64_t)m * a.res_ct + k]);
                 f = apply_act(f, a.act);
                 T o;

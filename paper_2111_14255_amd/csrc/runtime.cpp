@@ -232,6 +232,14 @@ int32_t finalize_model(mt_model *m) {
         off += align_up(ti.bytes + 16);
     }
     m->tensors[0].bytes = (size_t)m->batch * m->in_h * m->in_w * m->in_c * es;
+    // The kernels index tensors and packed filters with 32-bit offsets.
+    const size_t limit = (size_t)1 << 31;
+    for (size_t t = 0; t < m->tensors.size(); ++t)
+        if (m->tensors[t].defined && m->tensors[t].bytes >= limit)
+            return fail(MT_ERR_SHAPE_MISMATCH, "tensor " + std::to_string(t) + " is 2 GiB or larger: not supported");
+    for (size_t i = 0; i < m->ops.size(); ++i)
+        if (m->ops[i].w_bytes >= limit || m->ops[i].ws_bytes >= limit)
+            return fail(MT_ERR_SHAPE_MISMATCH, "op " + std::to_string(i) + ": packed filters or split workspace of 2 GiB or more: not supported");
     m->arena_bytes = off;
     m->finalized = true;
     return MT_OK;

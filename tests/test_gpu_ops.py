@@ -142,14 +142,15 @@ def g_chain(dtype, n, h, w, c, build):
 
 
 CHANNELWISE = [
-    ("dw_shuffle_c32", 1, 20, 20, 32, lambda g: g.dwconv(0, 3, 1, 1, act="relu6", bn=True)),
-    ("dw_shuffle_c64_ragged", 2, 7, 9, 64, lambda g: g.dwconv(0, 3, 1, 1, act="relu", bn=True)),
-    ("dw_shuffle_c8", 1, 5, 37, 8, lambda g: g.dwconv(0, 3, 1, 1, act="none", bn=True)),
+    ("dw_c32", 1, 20, 20, 32, lambda g: g.dwconv(0, 3, 1, 1, act="relu6", bn=True)),
+    ("dw_c64_ragged", 2, 7, 9, 64, lambda g: g.dwconv(0, 3, 1, 1, act="relu", bn=True)),
+    ("dw_c8", 1, 5, 37, 8, lambda g: g.dwconv(0, 3, 1, 1, act="none", bn=True)),
     ("dw_stride2", 1, 15, 15, 96, lambda g: g.dwconv(0, 3, 2, 1, act="relu6", bn=True)),
     ("dw_c96_stride1", 1, 14, 14, 96, lambda g: g.dwconv(0, 3, 1, 1, act="relu6", bn=True)),
     ("dw_c960", 1, 7, 7, 960, lambda g: g.dwconv(0, 3, 1, 1, act="relu6", bn=True)),
     ("dw_scalar_c20", 1, 9, 9, 20, lambda g: g.dwconv(0, 3, 1, 1, act="relu", bn=False)),
     ("dw_5x5", 1, 11, 11, 16, lambda g: g.dwconv(0, 5, 1, 2, act="relu", bn=False)),
+    ("dw_7x7_generic", 1, 9, 10, 24, lambda g: g.dwconv(0, 7, 1, 3, act="relu", bn=True)),
     ("maxpool_2x2", 2, 14, 14, 64, lambda g: g.maxpool(0, 2, 2)),
     ("maxpool_3x3s2p1", 1, 17, 17, 64, lambda g: g.maxpool(0, 3, 2, 1)),
     ("maxpool_3x3s2_scalar", 1, 13, 13, 12, lambda g: g.maxpool(0, 3, 2)),

@@ -215,6 +215,10 @@ def test_model_validation_errors():
     assert _model([_op(dst=1, ctot=16), _op(dst=1, coff=8, ctot=16, sh=2, sw=2)]) == B.MT_ERR_SHAPE_MISMATCH
     assert _model([_op(kind=B.MT_MAXPOOL, res=0)]) == B.MT_ERR_SHAPE_MISMATCH
     assert _model([]) == B.MT_ERR_SHAPE_MISMATCH
+    # 32-bit offsets inside the kernels: a tensor of 2 GiB or more is refused when the model is finalised
+    assert _model([_op(oc=64)], dims=(64, 512, 512, 64)) == B.MT_ERR_SHAPE_MISMATCH        # 2 GiB fp16 input and output
+    assert "2 GiB" in lib.mt_last_error().decode()
+    assert _model([_op(oc=64)], dims=(32, 512, 512, 63)) == 0                              # just below
     h = C.c_void_p()
     assert lib.mt_model_begin(7, 1, 8, 8, 8, C.byref(h)) == B.MT_ERR_INVALID_ARG
     assert lib.mt_model_begin(B.MT_F16, 0, 8, 8, 8, C.byref(h)) == B.MT_ERR_INVALID_ARG
