@@ -36,7 +36,7 @@ def forward(model, params, x, keep=False):
         co, ct = op.out_c_offset, op.out_c_total
         if op.kind == "conv":
             res = t[op.res_tensor] if op.res_tensor >= 0 else None
-            y = ops.conv(xin, p[0], p[1], st, pd, op.act, res, dt, y, co, ct)
+            y = ops.conv(xin, p[0], p[1], st, pd, op.act, res, dt, y, co, ct, op.groups)
         elif op.kind == "dwconv":
             y = ops.dwconv(xin, p[0], p[1], st, pd, op.act, dt, y, co, ct)
         elif op.kind == "maxpool":
@@ -47,6 +47,10 @@ def forward(model, params, x, keep=False):
             y = ops.global_avgpool(xin, dt, y, co, ct)
         elif op.kind == "fc":
             y = ops.fc(xin, p[0], p[1], op.act, dt)
+        elif op.kind == "lrn":
+            y = ops.lrn(xin, op.r, op.lrn_alpha, op.lrn_beta, op.lrn_k, dt)
+        elif op.kind == "add":
+            y = ops.add(xin, t[op.res_tensor], op.act, dt)
         else:
             raise ValueError(op.kind)
         t[op.out_tensor] = y

@@ -243,6 +243,12 @@ void orc_round_array(float *a, size_t n, int dtype)
     for (size_t i = 0; i < n; ++i) a[i] = (float)orc_round_store((double)a[i], dtype);
 }
 
+/* Round a double array to the storage type, into a float array (results computed in numpy in double). */
+void orc_round_array_f64(const double *in, float *out, size_t n, int dtype)
+{
+    for (size_t i = 0; i < n; ++i) out[i] = (float)orc_round_store(in[i], dtype);
+}
+
 /* One output element of a convolution, for spot checks of large tensors. */
 double orc_conv_point(const float *x, int H, int W, int C,
                       const float *w, int R, int S,

@@ -58,9 +58,23 @@ def _out(y, n, p, q, k, c_off, c_tot):
 
 
 def conv(x, w, bias=None, stride=(1, 1), pad=(0, 0), act="none", res=None, dtype="f32",
-         y=None, c_off=0, c_tot=0):
+         y=None, c_off=0, c_tot=0, groups=1):
     n, h, wd, c = x.shape
     k, r, s, c2 = w.shape
+    if groups > 1:
+        # Grouped convolution, by its definition: group g maps input channels [g*C/G, (g+1)*C/G) to output
+        # channels [g*K/G, (g+1)*K/G) with its own filters; the groups do not interact.
+        assert c % groups == 0 and k % groups == 0 and c2 == c // groups
+        cg, kg = c // groups, k // groups
+        p, q = out_dim(h, pad[0], r, stride[0]), out_dim(wd, pad[1], s, stride[1])
+        y, c_tot = _out(y, n, p, q, k, c_off, c_tot)
+        for g in range(groups):
+            xg = np.ascontiguousarray(x[..., g * cg:(g + 1) * cg])
+            wg = np.ascontiguousarray(w[g * kg:(g + 1) * kg])
+            bg = None if bias is None else np.ascontiguousarray(bias[g * kg:(g + 1) * kg])
+            rg = None if res is None else np.ascontiguousarray(res[..., g * kg:(g + 1) * kg])
+            conv(xg, wg, bg, stride, pad, act, rg, dtype, y, c_off + g * kg, c_tot)
+        return y
     assert c == c2
     p, q = out_dim(h, pad[0], r, stride[0]), out_dim(wd, pad[1], s, stride[1])
     y, c_tot = _out(y, n, p, q, k, c_off, c_tot)
@@ -115,6 +129,43 @@ def fc(x, w, bias=None, act="none", dtype="f32"):
     y = np.zeros((n, 1, 1, k), dtype=np.float32)
     lib().orc_fc(_p(np.ascontiguousarray(x.reshape(n, j))), n, j, _p(w), k, _p(bias), _ACT[act], _DT[dtype], _p(y))
     return y
+
+
+def lrn(x, size, alpha, beta, k, dtype="f32"):
+    """Local response normalisation across channels, as the AlexNet paper defines it (its Sec. 3.3):
+    b[c] = a[c] / (k + alpha * sum_{j = max(0, c - size/2)}^{min(C-1, c + size/2)} a[j]^2) ** beta,
+    alpha NOT divided by the window size.  Double precision, one rounding to the storage type."""
+    n, h, wd, c = x.shape
+    a = x.astype(np.float64)
+    sq = a * a
+    half = size // 2
+    den = np.zeros_like(a)
+    for ch in range(c):
+        lo, hi = max(0, ch - half), min(c - 1, ch + half)
+        den[..., ch] = sq[..., lo:hi + 1].sum(axis=-1)
+    out = a / np.power(float(k) + float(alpha) * den, float(beta))
+    return round_array_f64(out, dtype)
+
+
+def add(x, other, act="none", dtype="f32"):
+    """Element-wise sum of two tensors of the same shape, then the activation, one rounding."""
+    assert x.shape == other.shape
+    v = x.astype(np.float64) + other.astype(np.float64)
+    if act == "relu":
+        v = np.maximum(v, 0.0)
+    elif act == "relu6":
+        v = np.minimum(np.maximum(v, 0.0), 6.0)
+    else:
+        assert act == "none"
+    return round_array_f64(v, dtype)
+
+
+def round_array_f64(a, dtype):
+    """Rounds a float64 array to the storage type."""
+    flat = np.ascontiguousarray(a, dtype=np.float64).ravel()
+    out = np.empty(flat.shape, dtype=np.float32)
+    lib().orc_round_array_f64(flat.ctypes.data_as(C.POINTER(C.c_double)), _p(out), C.c_size_t(flat.size), _DT[dtype])
+    return out.reshape(a.shape)
 
 
 def conv_point(x, w, stride, pad, n, p, q, k):

@@ -86,6 +86,13 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
     } else {
         kid = K_IGEMM_64x64; bn = 64; bm = 64;
     }
+    if (const char *e = std::getenv("MTSCHED_TUNE_TILE")) {
+        const int t = std::atoi(e);
+        if (t == 1) { kid = K_IGEMM_128x128; bn = 128; bm = 128; }
+        if (t == 8) { kid = K_IGEMM_128x64; bn = 128; bm = 64; }
+        if (t == 2) { kid = K_IGEMM_64x64; bn = 64; bm = 64; }
+        if (t == 3) { kid = K_IGEMM_64x16; bn = 64; bm = 16; }
+    }
     p.kernel_id = kid;
     p.n_pad = cdiv(Kc, bn) * bn;
     const int tiles = cdiv(M, bm) * (p.n_pad / bn);

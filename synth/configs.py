@@ -39,5 +39,13 @@ PAPER_MIXES = {
     "mix_5": Config("mix_5", "f16", 1, ("vgg16", "resnet18", "resnet34", "resnet50", "resnet101"), "normal", 617, 4),
 }
 
+# Operator-set completion: grouped convolution, local response normalisation and a stand-alone add.
+EXTRA = {
+    "ops_f32": Config("ops_f32", "f32", 2, ("tinyD", "tinyA"), "uniform", 701, 2),
+    "ops_f16": Config("ops_f16", "f16", 2, ("tinyD", "tinyC"), "uniform", 702, 2),
+    "alexnet_published": Config("alexnet_published", "bf16", 1, ("alexnet_published", "resnet18"), "normal", 703, 3),
+}
+
 ALL = dict(CONFIGS)
+ALL.update(EXTRA)
 ALL.update(PAPER_MIXES)

@@ -9,7 +9,7 @@ is how channel concatenation is expressed without a copy.
 from dataclasses import dataclass, field
 from typing import List, Dict, Tuple
 
-KINDS = ("conv", "dwconv", "maxpool", "avgpool", "gap", "fc")
+KINDS = ("conv", "dwconv", "maxpool", "avgpool", "gap", "fc", "lrn", "add")
 ACTS = ("none", "relu", "relu6")
 DTYPES = ("f32", "f16", "bf16")
 
@@ -32,6 +32,10 @@ class OpSpec:
     out_c_total: int = 0      # channel count of the output tensor (0 = out_c)
     bn: bool = False          # synthetic batch-norm follows (to be folded)
     bn_gain: float = 1.0      # multiplier on the synthetic BN gamma
+    groups: int = 1           # conv: independent channel groups
+    lrn_alpha: float = 0.0    # lrn: b = a / (lrn_k + lrn_alpha * sum of squares over r neighbouring channels) ** lrn_beta
+    lrn_beta: float = 0.0
+    lrn_k: float = 0.0
     # filled by the builder, for generators and reports (not consumed by either implementation)
     in_shape: Tuple[int, int, int] = (0, 0, 0)    # H, W, C of the input tensor
     out_shape: Tuple[int, int, int] = (0, 0, 0)   # P, Q, channels written
@@ -59,7 +63,7 @@ class ModelSpec:
             h, w, c = op.in_shape
             p, q, k = op.out_shape
             if op.kind == "conv":
-                total += p * q * k * op.r * op.s * c
+                total += p * q * k * op.r * op.s * (c // op.groups)
             elif op.kind == "dwconv":
                 total += p * q * k * op.r * op.s
             elif op.kind == "fc":
@@ -110,8 +114,22 @@ class GraphBuilder:
         return self._emit(op, p, q, oc)
 
     def conv(self, src, out_c, k, stride=1, pad=0, act="relu", bn=False, gain=1.0,
-             res=-1, dst=None, c_off=0, c_tot=0):
-        return self._window("conv", src, out_c, k, stride, pad, act, res, dst, c_off, c_tot, bn, gain)
+             res=-1, dst=None, c_off=0, c_tot=0, groups=1):
+        t = self._window("conv", src, out_c, k, stride, pad, act, res, dst, c_off, c_tot, bn, gain)
+        assert self.shapes[src][2] % groups == 0 and out_c % groups == 0
+        self.m.ops[-1].groups = groups
+        return t
+
+    def lrn(self, src, size=5, alpha=1e-4, beta=0.75, k=2.0):
+        h, w, c = self.shapes[src]
+        op = OpSpec("lrn", src, self.new_tensor(), c, size, 1, lrn_alpha=alpha, lrn_beta=beta, lrn_k=k)
+        return self._emit(op, h, w, c)
+
+    def add(self, src, other, act="none"):
+        assert self.shapes[src] == self.shapes[other]
+        h, w, c = self.shapes[src]
+        op = OpSpec("add", src, self.new_tensor(), c, act=act, res_tensor=other)
+        return self._emit(op, h, w, c)
 
     def dwconv(self, src, k=3, stride=1, pad=1, act="relu", bn=False, gain=1.0):
         return self._window("dwconv", src, 0, k, stride, pad, act, -1, None, 0, 0, bn, gain)

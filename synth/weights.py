@@ -29,7 +29,8 @@ def make_params(model: ModelSpec, seed: int, tenant: int):
         h, w, c = op.in_shape
         g = _rng(seed, tenant, i, 0)
         if op.kind == "conv":
-            shape, fan_in = (op.out_c, op.r, op.s, c), op.r * op.s * c
+            cg = c // op.groups
+            shape, fan_in = (op.out_c, op.r, op.s, cg), op.r * op.s * cg
         elif op.kind == "dwconv":
             shape, fan_in = (c, op.r, op.s), op.r * op.s
         else:

@@ -135,6 +135,41 @@ def alexnet(dtype="bf16", batch=1):
     return g.done()
 
 
+def alexnet_published(dtype="bf16", batch=1):
+    """AlexNet as its paper prints it: two filter groups in conv2, conv4 and conv5, local response
+    normalisation (5 channels, k = 2, alpha = 1e-4, beta = 0.75) after conv1 and conv2; no dropout / softmax."""
+    g = GraphBuilder("alexnet_published", dtype, batch, 227, 227, 3)
+    t = g.conv(0, 96, 11, stride=4)
+    t = g.lrn(t)
+    t = g.maxpool(t, 3, 2)
+    t = g.conv(t, 256, 5, pad=2, groups=2)
+    t = g.lrn(t)
+    t = g.maxpool(t, 3, 2)
+    t = g.conv(t, 384, 3, pad=1)
+    t = g.conv(t, 384, 3, pad=1, groups=2)
+    t = g.conv(t, 256, 3, pad=1, groups=2)
+    t = g.maxpool(t, 3, 2)
+    t = g.fc(t, 4096, act="relu")
+    t = g.fc(t, 4096, act="relu")
+    g.fc(t, 1000)
+    return g.done()
+
+
+def tiny_d(dtype="f32", batch=1):
+    """A small residual net whose shortcut sum is an operator of its own (not fused into a convolution),
+    with a grouped convolution and a local response normalisation."""
+    g = GraphBuilder("tinyD", dtype, batch, 24, 24, 8)
+    t = g.conv(0, 32, 3, pad=1)
+    u = g.conv(t, 32, 3, pad=1, groups=4)
+    u = g.conv(u, 32, 1, act="none")
+    t = g.add(u, t, act="relu")
+    t = g.lrn(t, size=3, alpha=2e-2, beta=0.75, k=1.0)
+    t = g.maxpool(t, 2, 2)
+    t = g.gap(t)
+    g.fc(t, 10)
+    return g.done()
+
+
 # --------------------------------------------------------------- MobileNetV2
 def mobilenet_v2(dtype="f16", batch=1):
     g = GraphBuilder("mobilenetv2", dtype, batch, 224, 224, 3)
@@ -263,4 +298,5 @@ BUILDERS = {
     "tinyA": tiny_a, "tinyB": tiny_b, "tinyC": tiny_c,
     "resnet18": resnet18, "resnet34": resnet34, "resnet50": resnet50, "resnet101": resnet101,
     "vgg16": vgg16, "alexnet": alexnet, "mobilenetv2": mobilenet_v2, "inceptionv3": inception_v3,
+    "alexnet_published": alexnet_published, "tinyD": tiny_d,
 }

@@ -8,9 +8,9 @@ from synth import zoo, weights, GraphBuilder
 from oracle import forward as F, ops
 
 GMAC = {"resnet18": 1.814, "resnet34": 3.664, "resnet50": 4.089, "resnet101": 7.801, "vgg16": 15.470,
-        "mobilenetv2": 0.301, "alexnet": 1.135, "inceptionv3": 5.713}
+        "mobilenetv2": 0.301, "alexnet": 1.135, "inceptionv3": 5.713, "alexnet_published": 0.724}
 NOPS = {"tinyA": 8, "tinyB": 5, "tinyC": 9, "resnet18": 23, "resnet50": 56, "resnet101": 107, "vgg16": 21,
-        "mobilenetv2": 54, "alexnet": 11, "inceptionv3": 109}
+        "mobilenetv2": 54, "alexnet": 11, "inceptionv3": 109, "alexnet_published": 13, "tinyD": 8, "resnet34": 39}
 
 
 @pytest.mark.parametrize("name", sorted(GMAC))
@@ -81,7 +81,7 @@ def _torch_forward(model, params, x):
         st, pd, kk = (op.stride_h, op.stride_w), (op.pad_h, op.pad_w), (op.r, op.s)
         if op.kind == "conv":
             y = TF.conv2d(xin, torch.from_numpy(p[0]).double().permute(0, 3, 1, 2),
-                          None if p[1] is None else torch.from_numpy(p[1]).double(), st, pd)
+                          None if p[1] is None else torch.from_numpy(p[1]).double(), st, pd, 1, op.groups)
             if op.res_tensor >= 0:
                 y = y + t[op.res_tensor][:, : y.shape[1]]
         elif op.kind == "dwconv":
@@ -98,6 +98,10 @@ def _torch_forward(model, params, x):
             flat = xin.permute(0, 2, 3, 1).reshape(xin.shape[0], -1)
             y = TF.linear(flat, torch.from_numpy(p[0]).double(), None if p[1] is None else torch.from_numpy(p[1]).double())
             y = y.reshape(y.shape[0], -1, 1, 1)
+        elif op.kind == "lrn":
+            y = TF.local_response_norm(xin, op.r, op.lrn_alpha * op.r, op.lrn_beta, op.lrn_k)   # torch divides alpha by the size
+        elif op.kind == "add":
+            y = xin + t[op.res_tensor]
         if op.act == "relu":
             y = y.clamp(min=0)
         elif op.act == "relu6":
@@ -135,7 +139,7 @@ def _mini_graph():
     return g.done()
 
 
-@pytest.mark.parametrize("builder", [zoo.tiny_a, zoo.tiny_b, zoo.tiny_c, _mini_graph])
+@pytest.mark.parametrize("builder", [zoo.tiny_a, zoo.tiny_b, zoo.tiny_c, zoo.tiny_d, _mini_graph])
 def test_forward_matches_torch_composition(builder):
     m = builder() if builder is _mini_graph else builder("f32", 1)
     raw = weights.make_params(m, 7, 0)

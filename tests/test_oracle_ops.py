@@ -245,3 +245,66 @@ def test_conv_point_matches_full():
     y = ops.conv(x, w, stride=(2, 2), pad=(1, 1))
     for (n, p, q, k) in [(0, 0, 0, 0), (1, 4, 4, 2), (1, 2, 3, 1)]:
         assert abs(ops.conv_point(x, w, (2, 2), (1, 1), n, p, q, k) - y[n, p, q, k]) < 1e-6
+
+
+# ---- grouped convolution, local response normalisation, stand-alone add ------------------------------------------
+@pytest.mark.parametrize("groups,c,k,r,st,pd", [(2, 6, 4, 3, (1, 1), (1, 1)), (4, 8, 8, 3, (2, 2), (1, 1)), (2, 4, 6, 5, (1, 1), (2, 2)),
+                                                 (3, 6, 3, 1, (1, 1), (0, 0))])
+def test_grouped_conv_matches_brute_force_and_torch(groups, c, k, r, st, pd):
+    x = rnd((2, 7, 6, c), 31)
+    w = rnd((k, r, r, c // groups), 32, 0.3)
+    b = rnd((k,), 33, 0.1)
+    got = ops.conv(x, w, b, st, pd, "none", None, "f32", groups=groups).astype(np.float64)
+    want = brute_conv(x, w, st, pd, groups) + b.astype(np.float64)
+    assert np.abs(got - want).max() < 1e-5
+    tx = torch.from_numpy(x).double().permute(0, 3, 1, 2)
+    tw = torch.from_numpy(w).double().permute(0, 3, 1, 2)
+    ty = TF.conv2d(tx, tw, torch.from_numpy(b).double(), st, pd, 1, groups).permute(0, 2, 3, 1).numpy()
+    assert np.abs(got - ty).max() < 1e-5
+    # a group must not see the other groups' channels: changing group 1's input leaves group 0's output alone
+    x2 = x.copy()
+    x2[..., c // groups:] += 1.0
+    got2 = ops.conv(x2, w, b, st, pd, "none", None, "f32", groups=groups)
+    assert np.array_equal(got2[..., :k // groups], got[..., :k // groups].astype(np.float32))
+    assert not np.array_equal(got2[..., k // groups:], got[..., k // groups:].astype(np.float32))
+
+
+def test_lrn_closed_forms_and_torch():
+    # constant input a over 7 channels, window 5: interior channels see 5 squares, the edge channels 3 and 4
+    a, k, alpha, beta = 2.0, 2.0, 1e-1, 0.75
+    x = np.full((1, 2, 2, 7), a, dtype=np.float32)
+    y = ops.lrn(x, 5, alpha, beta, k).astype(np.float64)
+    counts = [3, 4, 5, 5, 5, 4, 3]
+    for ch, cnt in enumerate(counts):
+        assert abs(y[0, 0, 0, ch] - a / (k + alpha * cnt * a * a) ** beta) < 1e-6
+    # a single non-zero channel: only channels within two of it are damped, and they are zero anyway
+    x = np.zeros((1, 1, 1, 9), dtype=np.float32)
+    x[0, 0, 0, 4] = 3.0
+    y = ops.lrn(x, 5, 1e-4, 0.75, 2.0)
+    assert abs(float(y[0, 0, 0, 4]) - 3.0 / (2.0 + 1e-4 * 9.0) ** 0.75) < 1e-6 and np.count_nonzero(y) == 1
+    # torch divides alpha by the window size: alpha_torch = alpha * size gives the AlexNet-paper form
+    rng = np.random.default_rng(3)
+    for size in (3, 5):
+        x = rng.standard_normal((2, 3, 4, 11)).astype(np.float32)
+        got = ops.lrn(x, size, 2e-2, 0.75, 1.5).astype(np.float64)
+        tx = torch.from_numpy(x).double().permute(0, 3, 1, 2)
+        want = TF.local_response_norm(tx, size, 2e-2 * size, 0.75, 1.5).permute(0, 2, 3, 1).numpy()
+        assert np.abs(got - want).max() < 1e-6
+    # storage rounding happens once, at the end
+    x = rng.standard_normal((1, 2, 2, 8)).astype(np.float32)
+    xh = ops.round_array(x, "f16")
+    exact = xh.astype(np.float64) / (2.0 + 1e-4 * np.stack([
+        (xh.astype(np.float64) ** 2)[..., max(0, c - 2):min(7, c + 2) + 1].sum(-1) for c in range(8)], -1)) ** 0.75
+    assert np.array_equal(ops.lrn(xh, 5, 1e-4, 0.75, 2.0, "f16"), exact.astype(np.float16).astype(np.float32))
+
+
+def test_add_pins():
+    x = np.array([[[[1.5, -2.0, 7.0, 0.25]]]], dtype=np.float32)
+    o = np.array([[[[0.5, 1.0, 1.0, -0.25]]]], dtype=np.float32)
+    assert ops.add(x, o).ravel().tolist() == [2.0, -1.0, 8.0, 0.0]
+    assert ops.add(x, o, "relu").ravel().tolist() == [2.0, 0.0, 8.0, 0.0]
+    assert ops.add(x, o, "relu6").ravel().tolist() == [2.0, 0.0, 6.0, 0.0]
+    # one rounding of the exact sum: 2048 + 1 is a tie in fp16 (spacing 2) and goes to the even neighbour
+    a = np.array([[[[2048.0, 2050.0]]]], dtype=np.float32)
+    b = np.array([[[[1.0, 1.0]]]], dtype=np.float32)
+    assert ops.add(a, b, "none", "f16").ravel().tolist() == [2048.0, 2052.0]
