@@ -68,7 +68,9 @@ typedef enum mt_op_kind {
     MT_MAXPOOL = 2,
     MT_AVGPOOL = 3,          /* divisor = number of in-bounds taps */
     MT_GLOBAL_AVGPOOL = 4,
-    MT_FC = 5
+    MT_FC = 5,
+    MT_LRN = 6,              /* across-channel local response normalisation (the AlexNet paper's form, its Sec. 3.3) */
+    MT_ADD = 7               /* out = act(in + res): a shortcut sum that is an operator of its own */
 } mt_op_kind;
 
 typedef enum mt_act { MT_ACT_NONE = 0, MT_ACT_RELU = 1, MT_ACT_RELU6 = 2 } mt_act;
@@ -80,15 +82,21 @@ typedef enum mt_issue_order { MT_ISSUE_BFS = 0, MT_ISSUE_DFS = 1 } mt_issue_orde
 typedef struct mt_op_desc {
     int32_t kind;          /* mt_op_kind */
     int32_t in_tensor;     /* must have been written by an earlier operator (or be 0) */
-    int32_t res_tensor;    /* CONV only: tensor added before the activation, -1 = none */
+    int32_t res_tensor;    /* CONV: tensor added before the activation, -1 = none; ADD: the second summand (required) */
     int32_t out_tensor;    /* >= 1 */
     int32_t out_c;         /* CONV / FC: output channels; ignored otherwise */
     int32_t out_c_offset;  /* first channel written inside out_tensor (channel concatenation without a copy) */
     int32_t out_c_total;   /* channel count of out_tensor; 0 = exactly the channels written */
-    int32_t r, s;          /* window (CONV, DWCONV, pools); ignored for GLOBAL_AVGPOOL and FC */
+    int32_t r, s;          /* window (CONV, DWCONV, pools); ignored for GLOBAL_AVGPOOL, FC, ADD; LRN: r = channels in the window (odd) */
     int32_t stride_h, stride_w;
     int32_t pad_h, pad_w;  /* symmetric per axis; max-pool padding is never selected */
-    int32_t act;           /* mt_act; CONV, DWCONV, FC */
+    int32_t act;           /* mt_act; CONV, DWCONV, FC, ADD */
+    int32_t groups;        /* CONV: independent channel groups (0 or 1 = ordinary convolution); group g maps input
+                              channels [g*C/G, (g+1)*C/G) to output channels [g*K/G, (g+1)*K/G); weights are
+                              [out_c][r][s][C/G].  One operator of the sequence, issued as G launches */
+    float lrn_alpha;       /* LRN: out[c] = in[c] / (lrn_k + lrn_alpha * sum_{|j-c| <= r/2} in[j]^2) ^ lrn_beta; */
+    float lrn_beta;        /*      lrn_alpha is not divided by the window size */
+    float lrn_k;
 } mt_op_desc;
 
 /* What the library derived for one operator; lets a harness compute roofline figures

@@ -16,7 +16,7 @@ from . import binding as B
 
 _DT = {"f32": B.MT_F32, "f16": B.MT_F16, "bf16": B.MT_BF16}
 _KIND = {"conv": B.MT_CONV, "dwconv": B.MT_DWCONV, "maxpool": B.MT_MAXPOOL, "avgpool": B.MT_AVGPOOL,
-         "gap": B.MT_GLOBAL_AVGPOOL, "fc": B.MT_FC}
+         "gap": B.MT_GLOBAL_AVGPOOL, "fc": B.MT_FC, "lrn": B.MT_LRN, "add": B.MT_ADD}
 _ACT = {"none": B.MT_ACT_NONE, "relu": B.MT_ACT_RELU, "relu6": B.MT_ACT_RELU6}
 
 
@@ -71,7 +71,9 @@ class Model:
         B.check(lib.mt_model_begin(_DT[spec.dtype], spec.batch, spec.in_h, spec.in_w, spec.in_c, C.byref(self.h)))
         for op in spec.ops:
             d = B.mt_op_desc(_KIND[op.kind], op.in_tensor, op.res_tensor, op.out_tensor, op.out_c, op.out_c_offset,
-                             op.out_c_total, op.r, op.s, op.stride_h, op.stride_w, op.pad_h, op.pad_w, _ACT[op.act])
+                             op.out_c_total, op.r, op.s, op.stride_h, op.stride_w, op.pad_h, op.pad_w, _ACT[op.act],
+                             getattr(op, "groups", 1), getattr(op, "lrn_alpha", 0.0), getattr(op, "lrn_beta", 0.0),
+                             getattr(op, "lrn_k", 0.0))
             B.check(lib.mt_model_add_op(self.h, C.byref(d), None))
         B.check(lib.mt_model_end(self.h))
         if raw_params is not None:

@@ -20,7 +20,7 @@ MT_ERR_HIP = -5
 MT_ERR_NOT_FINALIZED = -6
 
 MT_F32, MT_F16, MT_BF16 = 0, 1, 2
-MT_CONV, MT_DWCONV, MT_MAXPOOL, MT_AVGPOOL, MT_GLOBAL_AVGPOOL, MT_FC = range(6)
+MT_CONV, MT_DWCONV, MT_MAXPOOL, MT_AVGPOOL, MT_GLOBAL_AVGPOOL, MT_FC, MT_LRN, MT_ADD = range(8)
 MT_ACT_NONE, MT_ACT_RELU, MT_ACT_RELU6 = 0, 1, 2
 MT_ISSUE_BFS, MT_ISSUE_DFS = 0, 1
 MT_SCHED_GRAPH = 1
@@ -32,7 +32,8 @@ MT_SEARCH_COORDINATE, MT_SEARCH_RANDOM = 0, 1
 class mt_op_desc(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "kind", "in_tensor", "res_tensor", "out_tensor", "out_c", "out_c_offset", "out_c_total",
-        "r", "s", "stride_h", "stride_w", "pad_h", "pad_w", "act")]
+        "r", "s", "stride_h", "stride_w", "pad_h", "pad_w", "act", "groups")] + [
+        ("lrn_alpha", C.c_float), ("lrn_beta", C.c_float), ("lrn_k", C.c_float)]
 
 
 class mt_op_info(C.Structure):

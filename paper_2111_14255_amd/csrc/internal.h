@@ -46,6 +46,8 @@ enum KernelId : int32_t {
     K_GAP = 7,
     K_IGEMM_128x64 = 8,     // 128 output channels x 64 pixels
     K_GEMV = 9,             // 1x1 / fully connected layers with at most 8 output pixels: weight streaming
+    K_LRN = 10,             // local response normalisation across channels
+    K_ADD = 11,             // element-wise sum of two tensors, activation
     K_COUNT
 };
 
@@ -57,7 +59,10 @@ inline bool is_gemm_kernel(int32_t id) {
 // read the caller's input buffer, the last one writes the caller's output buffer).
 struct OpArgs {
     int32_t kind, kernel_id, dtype;
-    int32_t N, H, W, C;          // input tensor
+    int32_t N, H, W, C;          // input tensor; for a grouped convolution C is the channel count of one group
+    int32_t x_ct, x_coff;        // channels per pixel of the input buffer and first channel read (x_ct == C, 0 unless grouped)
+    int32_t groups;              // launches of this operator (grouped convolution), 1 otherwise
+    float lrn_alpha, lrn_beta, lrn_k;
     int32_t K, R, S;             // output channels written, window
     int32_t P, Q;                // output spatial size
     int32_t sh, sw, ph, pw;

@@ -47,7 +47,7 @@ __global__ void __launch_bounds__(256) conv_direct_kernel(OpArgs a) {
         for (int s = 0; s < a.S; ++s) {
             const int iw = q * a.sw - a.pw + s;
             if (iw < 0 || iw >= a.W) continue;
-            const T *xp = x + (((int64_t)n * a.H + ih) * a.W + iw) * a.C;
+            const T *xp = x + (((int64_t)n * a.H + ih) * a.W + iw) * a.x_ct + a.x_coff;
             const T *wp = w + ((int64_t)r * a.S + s) * a.C;
             for (int c = 0; c < a.C; ++c) acc = fmaf(to_f32(xp[c]), to_f32(wp[c]), acc);
         }
@@ -270,6 +270,81 @@ __global__ void __launch_bounds__(256) gap_kernel(OpArgs a, int lanes_c) {
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Local response normalisation across channels: out[c] = in[c] / (k + alpha * sum_{|j-c| <= size/2} in[j]^2)^beta.
+// One thread per (pixel, V-channel vector); it loads its own vector and the two neighbouring vectors (the window
+// reaches at most 7 channels to either side, V >= 8 for the vector form), all before any arithmetic.
+template <typename T, int V>
+__global__ void __launch_bounds__(256) lrn_kernel(OpArgs a) {
+    const int CV = a.C / V;
+    const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
+    const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= total) return;
+    const uint32_t m = gid / (uint32_t)CV;
+    const int cv = (int)(gid - m * (uint32_t)CV);
+    const int c0 = cv * V;
+    const int half = a.R / 2;
+    const T *x = (const T *)a.x + (int64_t)m * a.C;
+    float win[3 * V];                        // channels c0 - V .. c0 + 2V - 1, zero outside the tensor
+    if constexpr (V > 1) {
+        float lo[V], mid[V], hi[V];
+        const bool has_lo = cv > 0, has_hi = cv + 1 < CV;
+        load_pack<T, V>(x + (has_lo ? c0 - V : c0), lo);
+        load_pack<T, V>(x + c0, mid);
+        load_pack<T, V>(x + (has_hi ? c0 + V : c0), hi);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            win[i] = has_lo ? lo[i] : 0.f;
+            win[V + i] = mid[i];
+            win[2 * V + i] = has_hi ? hi[i] : 0.f;
+        }
+    } else {
+        for (int i = 0; i < 3; ++i) win[i] = 0.f;
+        win[1] = to_f32(x[c0]);
+    }
+    float out[V];
+    if constexpr (V > 1) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+            float ssq = 0.f;
+#pragma unroll
+            for (int d = -7; d <= 7; ++d) {
+                const float v = win[V + i + d];
+                ssq = (d >= -half && d <= half) ? fmaf(v, v, ssq) : ssq;
+            }
+            out[i] = win[V + i] / powf(a.lrn_k + a.lrn_alpha * ssq, a.lrn_beta);
+        }
+    } else {
+        float ssq = 0.f;
+        for (int d = -half; d <= half; ++d) {
+            const int c = c0 + d;
+            if (c >= 0 && c < a.C) {
+                const float v = to_f32(x[c]);
+                ssq = fmaf(v, v, ssq);
+            }
+        }
+        out[0] = win[1] / powf(a.lrn_k + a.lrn_alpha * ssq, a.lrn_beta);
+    }
+    store_pack<T, V>((T *)a.y + (int64_t)m * a.y_ct + a.y_coff + c0, out);
+}
+
+// Element-wise sum of two tensors of the same shape, activation, one rounding.
+template <typename T, int V>
+__global__ void __launch_bounds__(256) add_kernel(OpArgs a) {
+    const int CV = a.C / V;
+    const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
+    const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= total) return;
+    const uint32_t m = gid / (uint32_t)CV;
+    const int c0 = (int)(gid - m * (uint32_t)CV) * V;
+    float u[V], v[V];
+    load_pack<T, V>((const T *)a.x + (int64_t)m * a.C + c0, u);
+    load_pack<T, V>((const T *)a.res + (int64_t)m * a.res_ct + c0, v);
+#pragma unroll
+    for (int i = 0; i < V; ++i) u[i] = apply_act(u[i] + v[i], a.act);
+    store_pack<T, V>((T *)a.y + (int64_t)m * a.y_ct + a.y_coff + c0, u);
+}
+
 // Records the hardware id registers of the compute unit each one-wavefront workgroup runs on, then keeps the unit
 // busy for a few microseconds so that later workgroups spread over every unit the queue may use.
 __global__ void __launch_bounds__(64) probe_kernel(uint32_t *out) {
@@ -345,6 +420,25 @@ static int launch_typed(const OpArgs &a, hipStream_t st) {
                 hipLaunchKernelGGL((gap_kernel<T, VMAX>), blocks(th), block, 0, st, a, lanes_c);
             else
                 hipLaunchKernelGGL((gap_kernel<T, 1>), blocks(th), block, 0, st, a, lanes_c);
+            break;
+        }
+        case K_LRN:
+        case K_ADD: {
+            const bool lrn = a.kernel_id == K_LRN;
+            bool done = false;
+            if constexpr (VMAX >= 8) {          // the vector form of the normalisation needs the window inside one neighbour vector
+                if (a.vec == VMAX) {
+                    const int64_t th = (int64_t)a.N * a.P * a.Q * (a.C / VMAX);
+                    if (lrn) hipLaunchKernelGGL((lrn_kernel<T, VMAX>), blocks(th), block, 0, st, a);
+                    else hipLaunchKernelGGL((add_kernel<T, VMAX>), blocks(th), block, 0, st, a);
+                    done = true;
+                }
+            }
+            if (!done) {
+                const int64_t th = (int64_t)a.N * a.P * a.Q * a.C;
+                if (lrn) hipLaunchKernelGGL((lrn_kernel<T, 1>), blocks(th), block, 0, st, a);
+                else hipLaunchKernelGGL((add_kernel<T, 1>), blocks(th), block, 0, st, a);
+            }
             break;
         }
         default:

@@ -130,7 +130,8 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     const int kt_begin = z * kt_per;
     const int nk = min(nkt, kt_begin + kt_per) - kt_begin;     // tiles of this workgroup (>= 1 by construction)
 
-    const T *x = (const T *)a.x;
+    const int XS = a.x_ct;                 // channels per pixel of the input buffer (> C for a grouped convolution)
+    const T *x = (const T *)a.x + a.x_coff;
     const uint16_t *wp = (const uint16_t *)a.w;
 
     // ---- per-thread load coordinates -------------------------------------------------------
@@ -138,7 +139,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     const int row0 = tid / CH_ROW;        // first tile row; further chunks are ROW_STEP rows apart
 
     const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<T *>(x), 0, (int)((int64_t)a.N * a.H * a.W * a.C * (int)sizeof(T)), 0x00027000);
+        const_cast<T *>(x), 0, (int)(((int64_t)a.N * a.H * a.W * XS - a.x_coff) * (int)sizeof(T)), 0x00027000);
     const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint16_t *>(wp), 0, (int)((int64_t)a.n_pad * a.k_pad * 2), 0x00027000);
 
@@ -154,7 +155,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
         const int q = mm % a.Q;
         const int p = (mm / a.Q) % a.P;
         const int n = mm / (a.Q * a.P);
-        img_off[i] = n * a.H * a.W * a.C;
+        img_off[i] = n * a.H * a.W * XS;
         ih0[i] = p * a.sh - a.ph;
         iw0[i] = q * a.sw - a.pw;
     }
@@ -191,7 +192,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
                     mask |= (uint64_t)(v ? 1u : 0u) << (r * a.S + sx);
                 }
             tapmask[i] = mask;
-            rowoff[i] = (img_off[i] + (ih0[i] * a.W + iw0[i]) * a.C + kc * 8) * 2;
+            rowoff[i] = (img_off[i] + (ih0[i] * a.W + iw0[i]) * XS + kc * 8) * 2;
         }
     } else {
         const int j0 = kt_begin * BK + kc * 8;
@@ -209,7 +210,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
             wr[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, wvoff[i], wsoff, 0);
         wsoff += BK * 2;
         if constexpr (AMODE == A_UNIFORM) {
-            const int tapoff = ((u_r * a.W + u_s) * a.C + u_cb) * 2;        // scalar
+            const int tapoff = ((u_r * a.W + u_s) * XS + u_cb) * 2;        // scalar
             const bool tap_ok = u_tap < a.R * a.S;
             const int sh = tap_ok ? u_tap : 0;
 #pragma unroll
@@ -235,7 +236,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
             for (int i = 0; i < X_CHUNKS; ++i) {
                 const int ih = ih0[i] + kr, iw = iw0[i] + ks;
                 const bool v = xrow_ok[i] & (kr < a.R) & ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
-                const uint32_t voff = v ? (uint32_t)((img_off[i] + (ih * a.W + iw) * a.C + kcx) * 2) : OOB_OFFSET;
+                const uint32_t voff = v ? (uint32_t)((img_off[i] + (ih * a.W + iw) * XS + kcx) * 2) : OOB_OFFSET;
                 xr[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, voff, 0, 0);
             }
             kcx += adv_c;
@@ -258,7 +259,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
                     const int sx = rs - r * a.S;
                     const int ih = ih0[i] + r, iw = iw0[i] + sx;
                     const bool v = xrow_ok[i] & (j < a.gemm_k) & ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
-                    const int off = v ? img_off[i] + (ih * a.W + iw) * a.C + c : 0;
+                    const int off = v ? img_off[i] + (ih * a.W + iw) * XS + c : 0;
                     const uint32_t h = xs[off];
                     e[t] = v ? h : 0u;
                 }

@@ -67,7 +67,7 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
     p.grid_y = p.grid_z = 1;
     p.block = 256;
     p.split_k = 1;
-    if (M <= 8 && p.H == 1 && p.W == 1 && p.R == 1 && p.S == 1 && p.vec_a) {
+    if (M <= 8 && p.H == 1 && p.W == 1 && p.R == 1 && p.S == 1 && p.vec_a && p.groups <= 1) {
         p.kernel_id = K_GEMV;
         p.n_pad = cdiv(Kc, 64) * 64;
         p.grid_x = cdiv(cdiv(Kc, 2), 4);          // two output channels per wavefront, four wavefronts per workgroup
@@ -133,6 +133,10 @@ int32_t finalize_model(mt_model *m) {
         o.in_h = in.h; o.in_w = in.w; o.in_c = in.c;
         int R = d.r, S = d.s, sh = d.stride_h, sw = d.stride_w, ph = d.pad_h, pw = d.pad_w;
         if (d.kind == MT_GLOBAL_AVGPOOL || d.kind == MT_FC) { R = in.h; S = in.w; sh = sw = 1; ph = pw = 0; }
+        const int lrn_size = d.r;
+        if (d.kind == MT_LRN || d.kind == MT_ADD) { R = S = 1; sh = sw = 1; ph = pw = 0; }
+        const int groups = (d.kind == MT_CONV && d.groups > 1) ? d.groups : 1;
+        if (d.kind != MT_CONV && d.groups > 1) return bad("groups are supported on CONV only");
         if (R < 1 || S < 1 || sh < 1 || sw < 1 || ph < 0 || pw < 0) return bad("bad window / stride / padding");
         if (ph >= R || pw >= S) return bad("padding must be smaller than the window");
         if (in.h + 2 * ph < R || in.w + 2 * pw < S) return bad("window larger than the padded input");
@@ -152,18 +156,24 @@ int32_t finalize_model(mt_model *m) {
         }
         int res_ct = 0;
         if (d.res_tensor >= 0) {
-            if (d.kind != MT_CONV) return bad("residual is supported on CONV only");
+            if (d.kind != MT_CONV && d.kind != MT_ADD) return bad("a second input is supported on CONV (residual) and ADD only");
             if (d.res_tensor >= (int)m->tensors.size() || !m->tensors[d.res_tensor].defined || d.res_tensor == d.out_tensor)
                 return bad("residual tensor is not produced by an earlier operator");
             const TensorInfo &rt = m->tensors[d.res_tensor];
             if (rt.h != o.out_h || rt.w != o.out_w || rt.c < o.out_c) return bad("residual tensor shape mismatch");
             res_ct = rt.c;
         }
+        if (d.kind == MT_ADD && (d.res_tensor < 0 || res_ct != in.c)) return bad("ADD needs a second tensor of the input's shape");
+        if (d.kind == MT_ADD && (d.act < MT_ACT_NONE || d.act > MT_ACT_RELU6)) return bad("unknown activation");
+        if (d.kind == MT_LRN && (lrn_size < 1 || lrn_size % 2 == 0 || lrn_size > 15)) return bad("LRN window must be odd and at most 15");
+        if (groups > 1 && (in.c % groups || o.out_c % groups)) return bad("channel counts must be multiples of the group count");
         OpArgs &p = o.plan;
         p = OpArgs{};
         p.kind = d.kind; p.dtype = m->dtype;
-        p.N = m->batch; p.H = in.h; p.W = in.w; p.C = in.c;
-        p.K = o.out_c; p.R = R; p.S = S; p.P = o.out_h; p.Q = o.out_w;
+        p.N = m->batch; p.H = in.h; p.W = in.w; p.C = in.c / groups;
+        p.x_ct = in.c; p.x_coff = 0; p.groups = groups;
+        p.lrn_alpha = d.lrn_alpha; p.lrn_beta = d.lrn_beta; p.lrn_k = d.lrn_k;
+        p.K = o.out_c / groups; p.R = d.kind == MT_LRN ? lrn_size : R; p.S = S; p.P = o.out_h; p.Q = o.out_w;
         p.sh = sh; p.sw = sw; p.ph = ph; p.pw = pw; p.act = d.act;
         p.res_ct = res_ct; p.y_coff = d.out_c_offset; p.y_ct = ctot;
         p.split_k = 1; p.block = 256; p.vec = 1;
@@ -173,7 +183,7 @@ int32_t finalize_model(mt_model *m) {
         switch (d.kind) {
             case MT_CONV:
             case MT_FC: {
-                const int gemm_k = R * S * in.c;
+                const int gemm_k = R * S * (in.c / groups);
                 p.gemm_k = gemm_k;
                 o.flops = 2.0 * out_elems * gemm_k;
                 o.bytes = (in_elems + out_elems + (double)o.out_c * gemm_k + (res_ct ? out_elems : 0)) * es + 4.0 * o.out_c;
@@ -181,10 +191,10 @@ int32_t finalize_model(mt_model *m) {
                     p.kernel_id = K_CONV_DIRECT;
                 } else {
                     // a fully connected layer is a 1x1 convolution over a 1x1 map with H*W*C channels
-                    if (d.kind == MT_FC) { p.H = p.W = 1; p.C = gemm_k; p.R = p.S = 1; }
+                    if (d.kind == MT_FC) { p.H = p.W = 1; p.C = gemm_k; p.x_ct = gemm_k; p.R = p.S = 1; }
                     // im2col gather mode: 2 = tile inside one tap (C % 64 == 0, at most 64 taps), 1 = 16-byte chunks, 0 = element-wise
                     p.vec_a = (p.C % IGEMM_BK == 0 && p.R * p.S <= 64) ? 2 : (p.C % 8 == 0) ? 1 : 0;
-                    plan_igemm(p, m->batch * o.out_h * o.out_w, o.out_c, gemm_k);
+                    plan_igemm(p, m->batch * o.out_h * o.out_w, o.out_c / groups, gemm_k);
                 }
                 break;
             }
@@ -202,6 +212,18 @@ int32_t finalize_model(mt_model *m) {
                 o.flops = 0;
                 o.bytes = (in_elems + out_elems) * es;
                 break;
+            case MT_LRN:
+                p.kernel_id = K_LRN;
+                p.vec = (in.c % vmax == 0) ? vmax : 1;
+                o.flops = out_elems * (2.0 * lrn_size + 3);
+                o.bytes = (in_elems + out_elems) * es;
+                break;
+            case MT_ADD:
+                p.kernel_id = K_ADD;
+                p.vec = (in.c % vmax == 0) ? vmax : 1;
+                o.flops = out_elems;
+                o.bytes = (2 * in_elems + out_elems) * es;
+                break;
             default:
                 return bad("unknown operator kind");
         }
@@ -215,11 +237,11 @@ int32_t finalize_model(mt_model *m) {
         const OpArgs &p = o.plan;
         if (needs_weights(p.kind)) {
             bool igemm = is_gemm_kernel(p.kernel_id);
-            size_t wcount = igemm ? (size_t)p.n_pad * p.k_pad
-                                  : (p.kind == MT_DWCONV ? (size_t)p.C * p.R * p.S : (size_t)p.K * o.plan.R * o.plan.S * p.C);
+            size_t wcount = igemm ? (size_t)p.groups * p.n_pad * p.k_pad
+                                  : (p.kind == MT_DWCONV ? (size_t)p.C * p.R * p.S : (size_t)p.groups * p.K * o.plan.R * o.plan.S * p.C);
             if (p.kind == MT_FC && !igemm) wcount = (size_t)p.K * o.in_h * o.in_w * o.in_c;
             o.w_off = off; o.w_bytes = wcount * es; off += align_up(o.w_bytes);
-            const size_t nb = igemm ? p.n_pad : p.K;
+            const size_t nb = (size_t)p.groups * (igemm ? p.n_pad : p.K);
             o.bias_off = off; off += align_up(nb * sizeof(float));
         }
         if (p.split_k > 1) {
@@ -353,16 +375,34 @@ namespace {
         if (e_ != hipSuccess) return fail(MT_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
     } while (0)
 
-int32_t launch_op(const OpArgs &a, hipStream_t st) {
-    int e;
-    switch (a.kernel_id) {
-        case K_IGEMM_128x128:
-        case K_IGEMM_128x64:
-        case K_IGEMM_64x64:
-        case K_IGEMM_64x16:
-        case K_GEMV: e = launch_igemm(a, st); break;
-        default: e = launch_direct(a, st); break;
+// One kernel launch; returns a hipError_t as int.
+int launch_kernel(const OpArgs &a, hipStream_t st) {
+    return is_gemm_kernel(a.kernel_id) ? launch_igemm(a, st) : launch_direct(a, st);
+}
+
+// One operator; returns a hipError_t as int.  A grouped convolution is one operator of the sequence issued as one
+// launch per group: each launch reads its slice of the input channels and its own filter bank and writes its slice of
+// the output channels.
+int launch_raw(const OpArgs &a, hipStream_t st) {
+    if (a.groups <= 1) return launch_kernel(a, st);
+    const size_t es = a.dtype == MT_F32 ? 4 : 2;
+    const bool igemm = is_gemm_kernel(a.kernel_id);
+    for (int g = 0; g < a.groups; ++g) {
+        OpArgs b = a;
+        b.groups = 1;
+        b.x_coff = a.x_coff + g * a.C;
+        b.y_coff = a.y_coff + g * a.K;
+        b.w = (const uint8_t *)a.w + (size_t)g * (igemm ? (size_t)a.n_pad * a.k_pad : (size_t)a.K * a.R * a.S * a.C) * es;
+        b.bias = a.bias + (size_t)g * (igemm ? a.n_pad : a.K);
+        if (a.res) b.res = (const uint8_t *)a.res + (size_t)g * a.K * es;
+        const int e = launch_kernel(b, st);
+        if (e != 0) return e;
     }
+    return 0;
+}
+
+int32_t launch_op(const OpArgs &a, hipStream_t st) {
+    const int e = launch_raw(a, st);
     if (e != 0) return fail(MT_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString((hipError_t)e));
     return MT_OK;
 }
@@ -524,7 +564,7 @@ void issue_worker(mt_ctx *ctx, int w) {
                     if (e != hipSuccess) break;
                     const Tenant &t = *ctx->tenants[it.tenant];
                     OpArgs a = patched(t, it.op, pool.inputs[it.tenant], pool.outputs[it.tenant]);
-                    int rc = is_gemm_kernel(a.kernel_id) ? launch_igemm(a, s->stream_of[w]) : launch_direct(a, s->stream_of[w]);
+                    int rc = launch_raw(a, s->stream_of[w]);
                     if (rc != 0) e = (hipError_t)rc;
                 }
                 if (e == hipSuccess) e = hipEventRecord(ctx->ev_done[st][w], s->stream_of[w]);
@@ -613,6 +653,8 @@ const char *mt_kernel_name(int32_t id) {
         case K_AVGPOOL: return "avgpool";
         case K_GAP: return "global_avgpool";
         case K_GEMV: return "gemv";
+        case K_LRN: return "lrn";
+        case K_ADD: return "add";
     }
     return "unknown";
 }
@@ -782,7 +824,7 @@ int32_t mt_model_begin(int32_t dtype, int32_t batch, int32_t in_h, int32_t in_w,
 int32_t mt_model_add_op(mt_model *m, const mt_op_desc *desc, int32_t *out_index) {
     if (!m || !desc) return fail(MT_ERR_INVALID_ARG, "NULL argument");
     if (m->finalized) return fail(MT_ERR_INVALID_ARG, "model is already finalised");
-    if (desc->kind < MT_CONV || desc->kind > MT_FC) return fail(MT_ERR_INVALID_ARG, "unknown operator kind");
+    if (desc->kind < MT_CONV || desc->kind > MT_ADD) return fail(MT_ERR_INVALID_ARG, "unknown operator kind");
     OpRec o;
     o.d = *desc;
     m->ops.push_back(std::move(o));
@@ -834,7 +876,7 @@ int32_t mt_model_set_weights(mt_model *m, int32_t i, const void *w, size_t w_byt
     size_t count;
     if (o.d.kind == MT_DWCONV) count = (size_t)o.in_c * o.d.r * o.d.s;
     else if (o.d.kind == MT_FC) count = (size_t)o.out_c * o.in_h * o.in_w * o.in_c;
-    else count = (size_t)o.out_c * o.d.r * o.d.s * o.in_c;
+    else count = (size_t)o.out_c * o.d.r * o.d.s * (o.in_c / std::max(1, o.plan.groups));
     if (w_bytes != count * es) return fail(MT_ERR_SHAPE_MISMATCH, "weight size does not match the operator shape");
     if (bias && n_bias != (size_t)o.out_c) return fail(MT_ERR_SHAPE_MISMATCH, "bias length does not match the output channels");
     o.w_host.assign((const uint8_t *)w, (const uint8_t *)w + w_bytes);
@@ -903,10 +945,12 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
         if (needs_weights(a.kind)) {
             const uint8_t *src = o.w_host.data();
             if (igemm) {
-                // [K][gemm_k] -> [n_pad][k_pad], zero padded
-                packed.assign((size_t)a.n_pad * a.k_pad * es, 0);
-                for (int k = 0; k < a.K; ++k)
-                    std::memcpy(packed.data() + (size_t)k * a.k_pad * es, src + (size_t)k * a.gemm_k * es, (size_t)a.gemm_k * es);
+                // [groups][K][gemm_k] -> [groups][n_pad][k_pad], zero padded
+                packed.assign((size_t)a.groups * a.n_pad * a.k_pad * es, 0);
+                for (int g = 0; g < a.groups; ++g)
+                    for (int k = 0; k < a.K; ++k)
+                        std::memcpy(packed.data() + ((size_t)g * a.n_pad + k) * a.k_pad * es,
+                                    src + ((size_t)g * a.K + k) * a.gemm_k * es, (size_t)a.gemm_k * es);
                 src = packed.data();
             } else if (a.kind == MT_DWCONV) {
                 // [C][R][S] -> [R][S][C]
@@ -917,8 +961,10 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
                 src = packed.data();
             }
             HIP_TRY(hipMemcpy(t->arena + o.w_off, src, o.w_bytes, hipMemcpyHostToDevice));
-            std::vector<float> b(igemm ? a.n_pad : a.K, 0.f);
-            std::memcpy(b.data(), o.bias_host.data(), sizeof(float) * a.K);
+            const size_t bstride = igemm ? a.n_pad : a.K;
+            std::vector<float> b(bstride * a.groups, 0.f);
+            for (int g = 0; g < a.groups; ++g)
+                std::memcpy(b.data() + g * bstride, o.bias_host.data() + (size_t)g * a.K, sizeof(float) * a.K);
             HIP_TRY(hipMemcpy(t->arena + o.bias_off, b.data(), b.size() * sizeof(float), hipMemcpyHostToDevice));
             a.w = t->arena + o.w_off;
             a.bias = (const float *)(t->arena + o.bias_off);

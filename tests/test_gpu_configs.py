@@ -110,3 +110,10 @@ def test_paper_mix_r18_r34_fp16_with_share_search_and_first_op_timing():
             ctx.schedule([[], []], 1, flags=B.MT_SCHED_TIME_FIRST_OP | B.MT_SCHED_GRAPH)
     finally:
         mix.close()
+
+
+@pytest.mark.parametrize("name", ["ops_f32", "ops_f16", "alexnet_published"])
+def test_operator_set_completion_workloads(name):
+    # grouped convolution, local response normalisation and a stand-alone add inside whole tenants
+    mix = check_config(name)
+    mix.close()

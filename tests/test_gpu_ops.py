@@ -160,6 +160,17 @@ CHANNELWISE = [
     ("gap_8x8_c2048", 1, 8, 8, 2048, lambda g: g.gap(0)),
     ("gap_16x16_c24", 3, 16, 16, 24, lambda g: g.gap(0)),
     ("gap_scalar_c10", 1, 5, 5, 10, lambda g: g.gap(0)),
+    ("lrn_5_c96", 1, 9, 9, 96, lambda g: g.lrn(0, 5, 1e-2, 0.75, 2.0)),
+    ("lrn_3_c8_single_vector", 2, 5, 6, 8, lambda g: g.lrn(0, 3, 5e-2, 0.5, 1.0)),
+    ("lrn_15_c32_widest_window", 1, 4, 4, 32, lambda g: g.lrn(0, 15, 1e-2, 0.75, 1.0)),
+    ("lrn_5_scalar_c11", 1, 6, 5, 11, lambda g: g.lrn(0, 5, 1e-2, 0.75, 2.0)),
+    ("add_relu_c64", 2, 7, 9, 64, lambda g: g.add(g.maxpool(0, 3, 1, 1), 0, act="relu")),
+    ("add_none_scalar_c5", 1, 6, 7, 5, lambda g: g.add(g.avgpool(0, 3, 1, 1), 0)),
+    ("conv_groups2_c96_5x5", 1, 13, 13, 96, lambda g: g.conv(0, 256, 5, pad=2, groups=2)),
+    ("conv_groups2_c384_3x3", 1, 13, 13, 384, lambda g: g.conv(0, 256, 3, pad=1, groups=2)),
+    ("conv_groups4_scalar_gather", 2, 9, 8, 12, lambda g: g.conv(0, 20, 3, pad=1, groups=4, act="none")),
+    ("conv_groups2_residual", 1, 8, 8, 32, lambda g: g.conv(g.conv(0, 32, 1), 32, 3, pad=1, groups=2, res=0)),
+    ("conv_groups3_1x1_on_1x1_map", 4, 1, 1, 48, lambda g: g.conv(0, 24, 1, groups=3)),
     ("maxpool_into_concat", 1, 9, 9, 16, lambda g: (lambda d: (g.maxpool(0, 3, 2, dst=d, c_off=8, c_tot=24),
                                                                g.conv(0, 8, 3, stride=2, dst=d, c_off=0, c_tot=24)))(g.new_tensor())),
 ]

@@ -170,7 +170,8 @@ def test_storage_casts_match_oracle_rounding():
         np.testing.assert_array_equal(mine, oops.round_array(v, dt))
 
 
-@pytest.mark.parametrize("name", ["tinyA", "tinyB", "tinyC", "resnet18", "resnet50", "vgg16", "mobilenetv2", "alexnet", "inceptionv3"])
+@pytest.mark.parametrize("name", ["tinyA", "tinyB", "tinyC", "tinyD", "resnet18", "resnet50", "vgg16", "mobilenetv2", "alexnet",
+                                  "alexnet_published", "inceptionv3"])
 def test_shape_inference_matches_model_tables(name):
     spec = zoo.BUILDERS[name]("f16", 2)
     m = api.Model(spec)
@@ -180,7 +181,8 @@ def test_shape_inference_matches_model_tables(name):
         info = m.op_info(i)
         assert (info.in_h, info.in_w, info.in_c) == tuple(op.in_shape)
         assert (info.out_h, info.out_w, info.out_c) == tuple(op.out_shape)
-        flops += info.flops
+        if op.kind in ("conv", "dwconv", "fc"):        # the MAC-counting kinds; normalisation and add report their own count
+            flops += info.flops
         assert info.bytes > 0
     assert flops == 2 * spec.macs()
     assert m.out_features() == spec.out_features
@@ -198,8 +200,8 @@ def _model(ops, dtype=B.MT_F16, dims=(1, 8, 8, 8)):
     return rc
 
 
-def _op(kind=B.MT_CONV, src=0, res=-1, dst=1, oc=8, coff=0, ctot=0, r=3, s=3, sh=1, sw=1, ph=1, pw=1, act=0):
-    return B.mt_op_desc(kind, src, res, dst, oc, coff, ctot, r, s, sh, sw, ph, pw, act)
+def _op(kind=B.MT_CONV, src=0, res=-1, dst=1, oc=8, coff=0, ctot=0, r=3, s=3, sh=1, sw=1, ph=1, pw=1, act=0, groups=1):
+    return B.mt_op_desc(kind, src, res, dst, oc, coff, ctot, r, s, sh, sw, ph, pw, act, groups, 1e-4, 0.75, 2.0)
 
 
 def test_model_validation_errors():
@@ -215,6 +217,14 @@ def test_model_validation_errors():
     assert _model([_op(dst=1, ctot=16), _op(dst=1, coff=8, ctot=16, sh=2, sw=2)]) == B.MT_ERR_SHAPE_MISMATCH
     assert _model([_op(kind=B.MT_MAXPOOL, res=0)]) == B.MT_ERR_SHAPE_MISMATCH
     assert _model([]) == B.MT_ERR_SHAPE_MISMATCH
+    assert _model([_op(groups=3)]) == B.MT_ERR_SHAPE_MISMATCH                      # 8 channels do not split into 3 groups
+    assert _model([_op(groups=2)]) == 0
+    assert _model([_op(kind=B.MT_MAXPOOL, groups=2)]) == B.MT_ERR_SHAPE_MISMATCH   # groups on a pool
+    assert _model([_op(kind=B.MT_LRN, r=4)]) == B.MT_ERR_SHAPE_MISMATCH            # even window
+    assert _model([_op(kind=B.MT_LRN, r=5)]) == 0
+    assert _model([_op(kind=B.MT_ADD)]) == B.MT_ERR_SHAPE_MISMATCH                 # no second summand
+    assert _model([_op(oc=8), _op(kind=B.MT_ADD, src=1, res=0, dst=2)]) == 0
+    assert _model([_op(oc=16), _op(kind=B.MT_ADD, src=1, res=0, dst=2)]) == B.MT_ERR_SHAPE_MISMATCH   # 16 + 8 channels
     # 32-bit offsets inside the kernels: a tensor of 2 GiB or more is refused when the model is finalised
     assert _model([_op(oc=64)], dims=(64, 512, 512, 64)) == B.MT_ERR_SHAPE_MISMATCH        # 2 GiB fp16 input and output
     assert "2 GiB" in lib.mt_last_error().decode()
