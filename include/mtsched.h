@@ -217,6 +217,10 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
 /* MT_SCHED_TIME_FIRST_OP: records one more event per tenant, after its first operator, and reports it in
  * mt_timings.first_op_done_ms.  Only with the single issuing thread on plain streams (neither flag above). */
 #define MT_SCHED_TIME_FIRST_OP 4
+/* MT_SCHED_SHARE_PER_STAGE: cu_share holds n_stages * n_tenants entries, row s = the shares of stage s; a tenant then
+ * runs each stage on the pooled stream of that stage's share (the stage barrier orders them).  Without the flag
+ * cu_share holds n_tenants entries used in every stage. */
+#define MT_SCHED_SHARE_PER_STAGE 8
 int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, const int32_t *pointers,
                            const int32_t *stage_concurrency, const int32_t *cu_share,
                            int32_t issue_order, int32_t flags, mt_schedule **out);

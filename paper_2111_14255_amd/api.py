@@ -221,7 +221,11 @@ class Context:
         assert len(flat) == n * P
         arr = (C.c_int32 * max(1, len(flat)))(*flat)
         conc = None if concurrency is None else (C.c_int32 * n_stages)(*concurrency)
-        share = None if cu_share is None else (C.c_int32 * n)(*cu_share)
+        if cu_share is not None and len(cu_share) and isinstance(cu_share[0], (list, tuple)):    # one row of shares per stage
+            assert len(cu_share) == n_stages and all(len(r) == n for r in cu_share)
+            cu_share = [int(v) for r in cu_share for v in r]
+            flags |= B.MT_SCHED_SHARE_PER_STAGE
+        share = None if cu_share is None else (C.c_int32 * len(cu_share))(*cu_share)
         h = C.c_void_p()
         B.check(self.lib.mt_schedule_create(self.h, n, n_stages, arr, conc, share, order, flags, C.byref(h)))
         return Schedule(self, h, [list(r) for r in pointers], n_stages, label)

@@ -26,6 +26,7 @@ MT_ISSUE_BFS, MT_ISSUE_DFS = 0, 1
 MT_SCHED_GRAPH = 1
 MT_SCHED_PARALLEL_ISSUE = 2
 MT_SCHED_TIME_FIRST_OP = 4
+MT_SCHED_SHARE_PER_STAGE = 8
 MT_SEARCH_COORDINATE, MT_SEARCH_RANDOM = 0, 1
 
 

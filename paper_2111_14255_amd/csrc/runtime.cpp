@@ -5,6 +5,7 @@
 #include <hip/hip_ext.h>
 
 #include <algorithm>
+#include <array>
 #include <chrono>
 #include <cmath>
 #include <cstdio>
@@ -86,6 +87,7 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
     } else {
         kid = K_IGEMM_64x64; bn = 64; bm = 64;
     }
+#ifdef MT_TUNE_ENV      // tile and split overrides for tuning sweeps; never compiled into the product library
     if (const char *e = std::getenv("MTSCHED_TUNE_TILE")) {
         const int t = std::atoi(e);
         if (t == 1) { kid = K_IGEMM_128x128; bn = 128; bm = 128; }
@@ -93,15 +95,18 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
         if (t == 2) { kid = K_IGEMM_64x64; bn = 64; bm = 64; }
         if (t == 3) { kid = K_IGEMM_64x16; bn = 64; bm = 16; }
     }
+#endif
     p.kernel_id = kid;
     p.n_pad = cdiv(Kc, bn) * bn;
     const int tiles = cdiv(M, bm) * (p.n_pad / bn);
     const int nkt = p.k_pad / IGEMM_BK;
     int target = (kid == K_IGEMM_64x16) ? 2048 : 768;
     int max_split = 8, min_kt = 6;    // a split below 6 reduction tiles costs more in the partial-sum exchange than it saves
+#ifdef MT_TUNE_ENV
     if (const char *e = std::getenv("MTSCHED_TUNE_TARGET")) target = std::atoi(e);
     if (const char *e = std::getenv("MTSCHED_TUNE_MAXSPLIT")) max_split = std::atoi(e);
     if (const char *e = std::getenv("MTSCHED_TUNE_MINKT")) min_kt = std::atoi(e);
+#endif
     int split = 1;
     if (tiles < target / 2) {
         split = std::min({cdiv(target, tiles), std::max(1, nkt / min_kt), max_split});
@@ -357,9 +362,9 @@ struct mt_schedule {
     mt_ctx *ctx = nullptr;
     int n_tenants = 0, n_stages = 0, flags = 0;
     std::vector<StagePlan> stages;                 // non-empty stages only keep items; empty ones stay for timing
-    hipStream_t stream_of[MT_MAX_TENANTS]{};
-    StreamKey stream_key[MT_MAX_TENANTS]{};
-    int n_keys = 0;
+    // stream of (stage, stream owner); the same for every stage unless the shares are given per stage
+    std::vector<std::array<hipStream_t, MT_MAX_TENANTS>> stream_at;
+    std::vector<StreamKey> stream_keys;     // one reference in the context's pool per entry
     int n_launches = 0;
     // graph replay
     hipGraphExec_t graph_exec = nullptr;
@@ -484,12 +489,12 @@ int32_t get_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t
 }
 
 void release_streams(mt_schedule *s) {
-    if (!s->ctx) { s->n_keys = 0; return; }
-    for (int i = 0; i < s->n_keys; ++i) {
-        auto it = s->ctx->streams.find(s->stream_key[i]);
+    if (!s->ctx) { s->stream_keys.clear(); return; }
+    for (const StreamKey &k : s->stream_keys) {
+        auto it = s->ctx->streams.find(k);
         if (it != s->ctx->streams.end() && it->second.refs > 0) it->second.refs--;
     }
-    s->n_keys = 0;
+    s->stream_keys.clear();
 }
 
 // A stream about to run stage st waits for the start event (no earlier work) or, directly, for the end of every other
@@ -500,12 +505,13 @@ void release_streams(mt_schedule *s) {
 // is not known, so that combination is switched off.
 hipError_t wait_for_previous_stage(mt_ctx *ctx, const mt_schedule *s, int st, int stream) {
     if (s->flags & MT_SCHED_GRAPH)
-        return hipStreamWaitEvent(s->stream_of[stream], st == 0 ? ctx->ev_start : ctx->ev_stage[st - 1], 0);
+        return hipStreamWaitEvent(s->stream_at[st][stream], st == 0 ? ctx->ev_start : ctx->ev_stage[st - 1], 0);
     const int prev = s->stages[st].prev_stage;
-    if (prev < 0) return hipStreamWaitEvent(s->stream_of[stream], ctx->ev_start, 0);
+    if (prev < 0) return hipStreamWaitEvent(s->stream_at[st][stream], ctx->ev_start, 0);
     hipError_t e = hipSuccess;
     for (int pm : s->stages[prev].streams)
-        if (pm != stream && e == hipSuccess) e = hipStreamWaitEvent(s->stream_of[stream], ctx->ev_done[prev][pm], 0);
+        if (s->stream_at[prev][pm] != s->stream_at[st][stream] && e == hipSuccess)     // the same stream is in order by itself
+            e = hipStreamWaitEvent(s->stream_at[st][stream], ctx->ev_done[prev][pm], 0);
     return e;
 }
 
@@ -521,13 +527,13 @@ int32_t issue_schedule(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, v
         for (const IssueItem &it : sp.items) {
             const Tenant &t = *ctx->tenants[it.tenant];
             OpArgs a = patched(t, it.op, inputs[it.tenant], outputs[it.tenant]);
-            int32_t rc = launch_op(a, s->stream_of[it.stream]);
+            int32_t rc = launch_op(a, s->stream_at[st][it.stream]);
             if (rc != MT_OK) return rc;
             ++launches;
-            if ((s->flags & MT_SCHED_TIME_FIRST_OP) && it.op == 0) HIP_TRY(hipEventRecord(ctx->ev_first[it.tenant], s->stream_of[it.stream]));
+            if ((s->flags & MT_SCHED_TIME_FIRST_OP) && it.op == 0) HIP_TRY(hipEventRecord(ctx->ev_first[it.tenant], s->stream_at[st][it.stream]));
         }
         for (int sm : sp.streams) {
-            HIP_TRY(hipEventRecord(ctx->ev_done[st][sm], s->stream_of[sm]));
+            HIP_TRY(hipEventRecord(ctx->ev_done[st][sm], s->stream_at[st][sm]));
             HIP_TRY(hipStreamWaitEvent(ctx->main_stream, ctx->ev_done[st][sm], 0));
         }
         HIP_TRY(hipEventRecord(ctx->ev_stage[st], ctx->main_stream));
@@ -564,10 +570,10 @@ void issue_worker(mt_ctx *ctx, int w) {
                     if (e != hipSuccess) break;
                     const Tenant &t = *ctx->tenants[it.tenant];
                     OpArgs a = patched(t, it.op, pool.inputs[it.tenant], pool.outputs[it.tenant]);
-                    int rc = launch_raw(a, s->stream_of[w]);
+                    int rc = launch_raw(a, s->stream_at[st][w]);
                     if (rc != 0) e = (hipError_t)rc;
                 }
-                if (e == hipSuccess) e = hipEventRecord(ctx->ev_done[st][w], s->stream_of[w]);
+                if (e == hipSuccess) e = hipEventRecord(ctx->ev_done[st][w], s->stream_at[st][w]);
                 if (e != hipSuccess) {
                     std::lock_guard<std::mutex> lk(pool.mu);
                     pool.error_msg = std::string("issuing thread: ") + hipGetErrorString(e);
@@ -1042,22 +1048,31 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
     const int cus = ctx->prop.multiProcessorCount;
     for (int s = 0; s < n_stages; ++s)
         if (stage_concurrency && stage_concurrency[s] < 1) return fail(MT_ERR_INVALID_SCHEDULE, "stage concurrency must be >= 1");
-    for (int i = 0; i < n_tenants; ++i)
+    const int n_shares = (flags & MT_SCHED_SHARE_PER_STAGE) ? n_stages * n_tenants : n_tenants;
+    if ((flags & MT_SCHED_SHARE_PER_STAGE) && !cu_share) return fail(MT_ERR_INVALID_ARG, "per-stage shares asked for but cu_share is NULL");
+    for (int i = 0; i < n_shares; ++i)
         if (cu_share && (cu_share[i] < 0 || cu_share[i] > cus)) return fail(MT_ERR_INVALID_SCHEDULE, "CU share out of range");
-    for (int i = 0; i < n_tenants; ++i)
+    for (int i = 0; i < n_shares; ++i)
         if (cu_share && cu_share[i] > 0 && cu_share[i] < 8)
             return fail(MT_ERR_INVALID_SCHEDULE, "a CU share must be 0 (all units) or at least 8: a mask has to leave every one of the 8 XCDs a unit");
     HIP_TRY(hipSetDevice(ctx->device));
     std::unique_ptr<mt_schedule> s(new mt_schedule);
     s->ctx = ctx; s->n_tenants = n_tenants; s->n_stages = n_stages; s->flags = flags;
-    int first_cu = 0;
-    for (int i = 0; i < n_tenants; ++i) {
-        const int share = (cu_share && !(flags & MT_SCHED_GRAPH)) ? cu_share[i] : 0;
-        rc = get_stream(ctx, i, share, first_cu, &s->stream_of[i], &s->stream_key[i]);
-        if (rc != MT_OK) { release_streams(s.get()); return rc; }
-        s->n_keys = i + 1;
-        first_cu = (first_cu + share) % cus;
+    const bool per_stage = (flags & MT_SCHED_SHARE_PER_STAGE) != 0;
+    s->stream_at.assign(n_stages, {});
+    for (int st = 0; st < (per_stage ? n_stages : 1); ++st) {
+        int first_cu = 0;
+        for (int i = 0; i < n_tenants; ++i) {
+            const int share = (cu_share && !(flags & MT_SCHED_GRAPH)) ? cu_share[(per_stage ? st * n_tenants : 0) + i] : 0;
+            StreamKey key;
+            rc = get_stream(ctx, i, share, first_cu, &s->stream_at[st][i], &key);
+            if (rc != MT_OK) { release_streams(s.get()); return rc; }
+            s->stream_keys.push_back(key);
+            first_cu = (first_cu + share) % cus;
+        }
     }
+    if (!per_stage)
+        for (int st = 1; st < n_stages; ++st) s->stream_at[st] = s->stream_at[0];
     std::vector<int32_t> slices((size_t)n_stages * n_tenants * 2);
     expand_pointers(n_tenants, lens, n_stages, pointers, slices.data());
     s->stages.resize(n_stages);
