@@ -19,6 +19,8 @@
 // order, so the result does not depend on arrival order.
 #include <hip/hip_runtime.h>
 
+#include <utility>
+
 #include "internal.h"
 #include "device_types.h"
 
@@ -80,7 +82,7 @@ struct Mma<bf16, 16> {
 template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES, int AMODE>
 __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     static_assert(WN * WM == 4, "four waves per workgroup");
-    static_assert(STAGES == 2 || STAGES == 4, "register sets rotate with the two LDS buffers");
+    static_assert(STAGES >= 2 && STAGES % 2 == 0, "register sets rotate with the two LDS buffers");
     constexpr int SUBN = BN / WN, SUBM = BM / WM;          // wave tile
     constexpr int TN = SUBN / MF, TM = SUBM / MF;          // MFMA tiles per wave
     static_assert(TN >= 1 && TM >= 1, "wave tile smaller than one MFMA");
@@ -348,16 +350,14 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     auto prologue_load = [&]<int S>() {
         if (S < nk) load_tiles(wreg[S], xreg[S]);
     };
-    prologue_load.template operator()<0>();
-    prologue_load.template operator()<1>();
-    if constexpr (STAGES > 2) {
-        prologue_load.template operator()<2>();
-        prologue_load.template operator()<3>();
-    }
+    [&]<int... S>(std::integer_sequence<int, S...>) {
+        (prologue_load.template operator()<S>(), ...);
+    }(std::make_integer_sequence<int, STAGES>{});
 
     // Tile t waits in register set t % STAGES until it is copied to LDS buffer t % 2.  FULL steps are the
     // steady state (every tile they touch exists) and contain no branch.
     if constexpr (FRAG_PREFETCH) {
+        static_assert(!FRAG_PREFETCH || STAGES <= 4, "the fragment-prefetch loop is written for 2 or 4 stages");
         // Fragments of tile t+1 are read from LDS while the MFMAs of tile t run (two fragment register sets).
         Frags fr[2];
         auto step = [&]<int S, bool FULL>(int t) {
@@ -415,23 +415,12 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
         store_tiles(0, wreg[0], xreg[0]);
         if (STAGES < nk) load_tiles(wreg[0], xreg[0]);
         __syncthreads();
+        auto round = [&]<bool FULL, int... S>(int t0, std::integer_sequence<int, S...>) {
+            (step.template operator()<S, FULL>(t0 + S), ...);
+        };
         int t0 = 0;
-        for (; t0 + 2 * STAGES < nk; t0 += STAGES) {
-            step.template operator()<0, true>(t0);
-            step.template operator()<1, true>(t0 + 1);
-            if constexpr (STAGES > 2) {
-                step.template operator()<2, true>(t0 + 2);
-                step.template operator()<3, true>(t0 + 3);
-            }
-        }
-        for (; t0 < nk; t0 += STAGES) {
-            step.template operator()<0, false>(t0);
-            step.template operator()<1, false>(t0 + 1);
-            if constexpr (STAGES > 2) {
-                step.template operator()<2, false>(t0 + 2);
-                step.template operator()<3, false>(t0 + 3);
-            }
-        }
+        for (; t0 + 2 * STAGES < nk; t0 += STAGES) round.template operator()<true>(t0, std::make_integer_sequence<int, STAGES>{});
+        for (; t0 < nk; t0 += STAGES) round.template operator()<false>(t0, std::make_integer_sequence<int, STAGES>{});
     }
     if constexpr (TWO_ACC) {
 #pragma unroll
@@ -643,7 +632,10 @@ static int launch_igemm_typed(const OpArgs &a, hipStream_t st) {
     switch (a.kernel_id) {
         case K_IGEMM_128x128: launch_cfg<T, 128, 128, 2, 2, 32, 2>(a, st); break;
         case K_IGEMM_128x64: launch_cfg<T, 128, 64, 2, 2, 32, 2>(a, st); break;
-        case K_IGEMM_64x64: launch_cfg<T, 64, 64, 2, 2, 32, 4>(a, st); break;
+#ifndef MT_STAGES_64
+#define MT_STAGES_64 4
+#endif
+        case K_IGEMM_64x64: launch_cfg<T, 64, 64, 2, 2, 32, MT_STAGES_64>(a, st); break;
         case K_IGEMM_64x16: launch_cfg<T, 64, 16, 4, 1, 16, 4>(a, st); break;
         case K_GEMV: {
             const dim3 grid(a.grid_x), block(256);
