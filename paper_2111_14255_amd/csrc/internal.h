@@ -75,6 +75,7 @@ struct OpArgs {
     int32_t k_pad;               // packed weight row length (multiple of the k tile)
     int32_t n_pad;               // packed weight rows (multiple of the channel tile)
     int32_t split_k;
+    int32_t wk;                  // wave groups that share an output tile (64x64 tile only): 1 or 2
     int32_t tile_order;          // 0: channel tile fastest (an XCD shares activation tiles), 1: pixel tile fastest (shares filter tiles)
     int32_t vec_a;               // im2col gather mode: 0 element-wise, 1 16-byte chunks (C % 8 == 0), 2 tile inside one tap (C % 64 == 0)
     int32_t grid_x, grid_y, grid_z, block;

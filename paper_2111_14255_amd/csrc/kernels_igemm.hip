@@ -79,18 +79,24 @@ struct Mma<bf16, 16> {
 // Filter tiles and (except A_SCALAR) im2col chunks are fetched with buffer loads: offsets are 32 bit, the
 // tile walk is a scalar offset, and a chunk in the padding halo is given an out-of-range offset, for which
 // the hardware returns zeros: no select and no 64-bit address arithmetic in the loop.
-template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES, int AMODE>
-__global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
-    static_assert(WN * WM == 4, "four waves per workgroup");
+template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES, int AMODE, int WK = 1>
+__global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
+    static_assert(WN * WM == 4, "four waves per output tile");
+    // WK > 1: WK groups of four waves share the output tile and split the MFMA steps of every LDS tile between them
+    // (a second wave per SIMD to overlap with when the grid gives a compute unit a single workgroup); their
+    // accumulators are added through LDS after the main loop, in group order.
+    constexpr int NT = 256 * WK;
     static_assert(STAGES >= 2 && STAGES % 2 == 0, "register sets rotate with the two LDS buffers");
     constexpr int SUBN = BN / WN, SUBM = BM / WM;          // wave tile
     constexpr int TN = SUBN / MF, TM = SUBM / MF;          // MFMA tiles per wave
     static_assert(TN >= 1 && TM >= 1, "wave tile smaller than one MFMA");
-    constexpr int KSTEPS = (MF == 32) ? BK / 16 : BK / 32; // MFMA issues per LDS tile
+    constexpr int KSTEPS_TILE = (MF == 32) ? BK / 16 : BK / 32;   // MFMA steps per LDS tile
+    static_assert(KSTEPS_TILE % WK == 0, "the wave groups split the MFMA steps evenly");
+    constexpr int KSTEPS = KSTEPS_TILE / WK;               // MFMA issues per LDS tile and wave
     constexpr int KLANES = 64 / MF;                        // lane groups along the reduction index
     constexpr int ACC_REGS = (MF == 32) ? 16 : 4;
     constexpr int CH_ROW = BK / 8;                         // 16-byte chunks per tile row
-    constexpr int ROW_STEP = 256 / CH_ROW;                 // tile rows covered by one pass of the workgroup
+    constexpr int ROW_STEP = NT / CH_ROW;                  // tile rows covered by one pass of the workgroup
     constexpr int W_CHUNKS = (BN + ROW_STEP - 1) / ROW_STEP;
     constexpr int X_CHUNKS = (BM + ROW_STEP - 1) / ROW_STEP;
 #ifndef MT_FRAG_PREFETCH
@@ -99,17 +105,21 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
 #ifndef MT_TWO_ACC
 #define MT_TWO_ACC 0
 #endif
-    constexpr bool FRAG_PREFETCH = MT_FRAG_PREFETCH && KSTEPS * (TN + TM) <= 8;   // two fragment sets fit the register budget
+    constexpr bool FRAG_PREFETCH = MT_FRAG_PREFETCH && WK == 1 && KSTEPS * (TN + TM) <= 8;   // two fragment sets fit the register budget
     typedef typename Mma<T, MF>::Acc Acc;
 
-    __shared__ __attribute__((aligned(16))) uint16_t Ws[2][W_CHUNKS * ROW_STEP * LDK];
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[2][X_CHUNKS * ROW_STEP * LDK];
+    // One LDS block: two filter tile buffers, then two im2col tile buffers; reused for the accumulator exchange.
+    constexpr int W_TILE = W_CHUNKS * ROW_STEP * LDK, X_TILE = X_CHUNKS * ROW_STEP * LDK;
+    __shared__ __attribute__((aligned(16))) uint16_t smem[2 * (W_TILE + X_TILE)];
+    uint16_t(*Ws)[W_TILE] = reinterpret_cast<uint16_t(*)[W_TILE]>(&smem[0]);
+    uint16_t(*Xs)[X_TILE] = reinterpret_cast<uint16_t(*)[X_TILE]>(&smem[2 * W_TILE]);
     __shared__ int s_last;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int wn = wave % WN, wm = wave / WN;
+    const int wk = wave / 4;                               // wave group along the reduction index
+    const int wn = (wave % 4) % WN, wm = (wave % 4) / WN;
 
     // Workgroup ids are dealt round-robin to the 8 XCDs; remap so that each XCD (one L2) works on a
     // contiguous range of tiles and the tiles sharing an activation tile share an L2.
@@ -318,7 +328,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     auto load_frags = [&](int buf, Frags &f) {
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk) {
-            const int koff = kk * (KLANES * 8) + frag_k;
+            const int koff = (wk * KSTEPS + kk) * (KLANES * 8) + frag_k;
 #pragma unroll
             for (int i = 0; i < TN; ++i)
                 f.a[kk][i] = *reinterpret_cast<const u32x4 *>(&Ws[buf][(wn * SUBN + i * MF + frag_row) * LDK + koff]);
@@ -427,6 +437,35 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
         for (int v = 0; v < ACC_REGS; ++v) acc[0][0][v] += acc2[v];
     }
 
+    // ---- wave groups: groups 1 .. WK-1 hand their accumulators to group 0 through LDS (the tile buffers are free:
+    // the main loop ends with a barrier), which adds them in group order and alone runs the rest of the kernel.
+    const bool owner = wk == 0;
+    if constexpr (WK > 1) {
+        constexpr int NACC_W = TN * TM * ACC_REGS;
+        static_assert((size_t)(WK - 1) * NACC_W * 256 * sizeof(float) <= sizeof(smem), "accumulator exchange must fit the tile buffers");
+        float *red = reinterpret_cast<float *>(&smem[0]);
+        if (!owner) {
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int j = 0; j < TM; ++j)
+#pragma unroll
+                    for (int v = 0; v < ACC_REGS; ++v)
+                        red[(((wk - 1) * NACC_W) + (i * TM + j) * ACC_REGS + v) * 256 + (tid & 255)] = acc[i][j][v];
+        }
+        __syncthreads();
+        if (owner) {
+            for (int g = 1; g < WK; ++g)
+#pragma unroll
+                for (int i = 0; i < TN; ++i)
+#pragma unroll
+                    for (int j = 0; j < TM; ++j)
+#pragma unroll
+                        for (int v = 0; v < ACC_REGS; ++v)
+                            acc[i][j][v] += red[(((g - 1) * NACC_W) + (i * TM + j) * ACC_REGS + v) * 256 + tid];
+        }
+    }
+
     // ---- split-K: publish partial sums; the last workgroup of the tile reduces in split order ----
     if (a.split_k > 1) {
         constexpr int NACC = TN * TM * ACC_REGS;
@@ -437,8 +476,9 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
             for (int j = 0; j < TM; ++j)
 #pragma unroll
                 for (int v = 0; v < ACC_REGS; ++v)
-                    __hip_atomic_store(&wsp[((i * TM + j) * ACC_REGS + v) * 256 + tid], acc[i][j][v], __ATOMIC_RELAXED,
-                                       __HIP_MEMORY_SCOPE_AGENT);
+                    if (owner)
+                        __hip_atomic_store(&wsp[((i * TM + j) * ACC_REGS + v) * 256 + tid], acc[i][j][v], __ATOMIC_RELAXED,
+                                           __HIP_MEMORY_SCOPE_AGENT);
         // The partial sums are written through to device-coherent memory; wait until every store of every wave
         // has completed before the arrival counter is bumped.
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -448,7 +488,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
             s_last = (old == (unsigned)a.split_k - 1u);
         }
         __syncthreads();
-        if (!s_last) return;
+        if (!s_last || !owner) return;      // no barrier follows: the other wave groups are done
         const float *wsr = a.ws + (int64_t)tile * a.split_k * NACC * 256;
 #pragma unroll
         for (int i = 0; i < TN; ++i)
@@ -483,6 +523,7 @@ __global__ void __launch_bounds__(256) igemm_kernel(OpArgs a) {
     }
 
     // ---- epilogue: bias, residual, activation, one rounding, NHWC store -------------------------
+    if (!owner) return;
     T *y = (T *)a.y;
     const T *res = (const T *)a.res;
     const bool vec_ok = (a.y_ct % 4 == 0) && (a.y_coff % 4 == 0) && (a.res_ct % 4 == 0);
@@ -616,15 +657,15 @@ __global__ void __launch_bounds__(256) gemv_kernel(OpArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES>
+template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES, int WK = 1>
 static void launch_cfg(const OpArgs &a, hipStream_t st) {
-    const dim3 grid(a.grid_x), block(256);
+    const dim3 grid(a.grid_x);
     if (a.vec_a == A_UNIFORM)
-        hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, STAGES, A_UNIFORM>), grid, block, 0, st, a);
+        hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, STAGES, A_UNIFORM, WK>), grid, dim3(256 * WK), 0, st, a);
     else if (a.vec_a == A_VEC8)
-        hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, STAGES, A_VEC8>), grid, block, 0, st, a);
+        hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, STAGES, A_VEC8, WK>), grid, dim3(256 * WK), 0, st, a);
     else
-        hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, 2, A_SCALAR>), grid, block, 0, st, a);
+        hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, 2, A_SCALAR>), grid, dim3(256), 0, st, a);
 }
 
 template <typename T>
@@ -635,7 +676,10 @@ static int launch_igemm_typed(const OpArgs &a, hipStream_t st) {
 #ifndef MT_STAGES_64
 #define MT_STAGES_64 4
 #endif
-        case K_IGEMM_64x64: launch_cfg<T, 64, 64, 2, 2, 32, MT_STAGES_64>(a, st); break;
+        case K_IGEMM_64x64:
+            if (a.wk == 2) launch_cfg<T, 64, 64, 2, 2, 32, MT_STAGES_64, 2>(a, st);
+            else launch_cfg<T, 64, 64, 2, 2, 32, MT_STAGES_64, 1>(a, st);
+            break;
         case K_IGEMM_64x16: launch_cfg<T, 64, 16, 4, 1, 16, 4>(a, st); break;
         case K_GEMV: {
             const dim3 grid(a.grid_x), block(256);

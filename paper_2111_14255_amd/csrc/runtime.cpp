@@ -108,11 +108,27 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
     if (const char *e = std::getenv("MTSCHED_TUNE_MINKT")) min_kt = std::atoi(e);
 #endif
     int split = 1;
-    if (tiles < target / 2) {
+    p.wk = 1;
+    if (kid == K_IGEMM_64x64 && p.vec_a != 0 && tiles <= 512) {
+        // Few workgroups per compute unit: eight waves per tile (two per SIMD, the MFMA steps of every LDS tile split
+        // between two wave groups) and only as many splits as keep about one workgroup per unit.  Measured on MI355X,
+        // VGG-16 at batch 1: conv3_2 18.9 -> 13.9 us, conv4_1 15.2 -> 11.8 us, conv4_2 19.7 -> 16.1 us.
+        p.wk = 2;
+        split = std::max(1, std::min({256 / tiles, std::max(1, nkt / 4), max_split}));
+        const int per = cdiv(nkt, split);
+        split = cdiv(nkt, per);
+    } else if (tiles < target / 2) {
         split = std::min({cdiv(target, tiles), std::max(1, nkt / min_kt), max_split});
         const int per = cdiv(nkt, split);
         split = cdiv(nkt, per);            // no empty split
     }
+#ifdef MT_TUNE_ENV
+    if (const char *e = std::getenv("MTSCHED_TUNE_SPLIT")) {
+        split = std::max(1, std::min(std::atoi(e), nkt));
+        const int per = cdiv(nkt, split);
+        split = cdiv(nkt, per);
+    }
+#endif
     p.split_k = std::max(1, split);
     // Which operand each XCD's L2 keeps to itself: consecutive tiles (one XCD) walk the channel tiles of one pixel
     // tile (0) when the activations are the larger operand, the pixel tiles of one channel tile (1) otherwise.
