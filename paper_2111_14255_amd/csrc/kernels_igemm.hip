@@ -488,7 +488,7 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
             s_last = (old == (unsigned)a.split_k - 1u);
         }
         __syncthreads();
-        if (!s_last || !owner) return;      // no barrier follows: the other wave groups are done
+        if (!s_last) return;                // the whole workgroup
         const float *wsr = a.ws + (int64_t)tile * a.split_k * NACC * 256;
 #pragma unroll
         for (int i = 0; i < TN; ++i)
@@ -498,7 +498,7 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
                 for (int v = 0; v < ACC_REGS; ++v) acc[i][j][v] = 0.f;
         // Loads of RB splits are issued together (they are independent), then added in split order.
         constexpr int RB = (NACC <= 16) ? 4 : 1;
-        for (int zz0 = 0; zz0 < a.split_k; zz0 += RB) {
+        for (int zz0 = 0; owner && zz0 < a.split_k; zz0 += RB) {
             float part[RB][NACC];
 #pragma unroll
             for (int b = 0; b < RB; ++b) {
@@ -523,9 +523,61 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
     }
 
     // ---- epilogue: bias, residual, activation, one rounding, NHWC store -------------------------
-    if (!owner) return;
     T *y = (T *)a.y;
     const T *res = (const T *)a.res;
+    // Coalesced form (channel counts and offsets multiples of 8): the accumulators plus bias go through LDS as an
+    // fp32 [pixel][channel] tile, then every thread finishes 8 consecutive channels of one pixel: one 16-byte residual
+    // load and one 16-byte store, a pixel's channels forming whole cache lines.  Same operations in the same order
+    // as the direct form below, so the results are identical.
+    const bool vec8_ok = (a.K % 8 == 0) && (a.y_ct % 8 == 0) && (a.y_coff % 8 == 0) && (a.res_ct % 8 == 0);
+    if (vec8_ok) {
+        constexpr int ELD = BN + 4;                       // row stride in floats: 4 lanes apart land 16 banks apart
+        static_assert((size_t)BM * ELD * sizeof(float) <= sizeof(smem), "epilogue tile must fit the tile buffers");
+        float *et = reinterpret_cast<float *>(&smem[0]);
+        __syncthreads();                                  // the accumulator exchange above may still be read
+        if (owner) {
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int j = 0; j < TM; ++j)
+#pragma unroll
+                    for (int g = 0; g < GROUPS; ++g) {
+                        const int ml = wm * SUBM + j * MF + frag_row;
+                        const int kl = wn * SUBN + i * MF + ((MF == 32) ? (8 * g + 4 * (lane / 32)) : (4 * (lane / 16)));
+                        float4 b;
+                        if constexpr (BIAS_EARLY) b = bias_pre[i * GROUPS + g];
+                        else b = *reinterpret_cast<const float4 *>(a.bias + n0 + kl);
+                        float4 v;
+                        v.x = acc[i][j][g * 4 + 0] + b.x;
+                        v.y = acc[i][j][g * 4 + 1] + b.y;
+                        v.z = acc[i][j][g * 4 + 2] + b.z;
+                        v.w = acc[i][j][g * 4 + 3] + b.w;
+                        *reinterpret_cast<float4 *>(&et[ml * ELD + kl]) = v;
+                    }
+        }
+        __syncthreads();
+        constexpr int CPR = BN / 8;                       // 8-channel chunks per pixel row of the tile
+        for (int c = tid; c < BM * CPR; c += NT) {
+            const int row = c / CPR, col = (c % CPR) * 8;
+            const int m = m0 + row, k = n0 + col;
+            if (m >= M || k >= a.K) continue;
+            float v[8];
+            const float4 lo = *reinterpret_cast<const float4 *>(&et[row * ELD + col]);
+            const float4 hi = *reinterpret_cast<const float4 *>(&et[row * ELD + col + 4]);
+            v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
+            if (res) {
+                float rv[8];
+                load_pack<T, 8>(res + (int64_t)m * a.res_ct + k, rv);
+#pragma unroll
+                for (int t = 0; t < 8; ++t) v[t] += rv[t];
+            }
+#pragma unroll
+            for (int t = 0; t < 8; ++t) v[t] = apply_act(v[t], a.act);
+            store_pack<T, 8>(y + (int64_t)m * a.y_ct + a.y_coff + k, v);
+        }
+        return;
+    }
+    if (!owner) return;
     const bool vec_ok = (a.y_ct % 4 == 0) && (a.y_coff % 4 == 0) && (a.res_ct % 4 == 0);
 #pragma unroll
     for (int i = 0; i < TN; ++i)
