@@ -17,19 +17,15 @@ __device__ __forceinline__ float to_f32(bf16 v) { return __uint_as_float(((uint3
 __device__ __forceinline__ void from_f32(float f, float &o) { o = f; }
 __device__ __forceinline__ void from_f32(float f, f16 &o) { o = (f16)f; }   // v_cvt_f16_f32: nearest even
 __device__ __forceinline__ void from_f32(float f, bf16 &o) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) {
-        o.v = (uint16_t)((u >> 16) | 0x0040u);   // quiet NaN
-    } else {
-        u += 0x7fffu + ((u >> 16) & 1u);          // nearest even; carries into the exponent, up to infinity
-        o.v = (uint16_t)(u >> 16);
-    }
+    o.v = __builtin_bit_cast(uint16_t, (__bf16)f);      // v_cvt_pk_bf16_f32: nearest even, NaN stays NaN
 }
 
+// Activation as a clamp to [lo, hi]: none = [-inf, inf], ReLU = [0, inf], ReLU6 = [0, 6]; the bounds depend only on
+// the kernel argument, so the per-value cost is one v_med3_f32.
 __device__ __forceinline__ float apply_act(float v, int act) {
-    if (act == MT_ACT_RELU) return v > 0.f ? v : 0.f;
-    if (act == MT_ACT_RELU6) return v < 0.f ? 0.f : (v > 6.f ? 6.f : v);
-    return v;
+    const float lo = act == MT_ACT_NONE ? -__builtin_inff() : 0.f;
+    const float hi = act == MT_ACT_RELU6 ? 6.f : __builtin_inff();
+    return __builtin_amdgcn_fmed3f(v, lo, hi);
 }
 
 // V consecutive elements of T moved as one access when V*sizeof(T) is 4, 8 or 16 bytes.

@@ -76,6 +76,9 @@ struct OpArgs {
     int32_t n_pad;               // packed weight rows (multiple of the channel tile)
     int32_t split_k;
     int32_t wk;                  // wave groups that share an output tile (64x64 tile only): 1 or 2
+    // Exact unsigned division by Q and by P*Q without a divide (multiply-high, two shifts): n / d =
+    // (t + ((n - t) >> s1)) >> s2 with t = mulhi(m, n); filled by make_divisor().
+    uint32_t divq_m, divq_s1, divq_s2, divpq_m, divpq_s1, divpq_s2;
     int32_t tile_order;          // 0: channel tile fastest (an XCD shares activation tiles), 1: pixel tile fastest (shares filter tiles)
     int32_t vec_a;               // im2col gather mode: 0 element-wise, 1 16-byte chunks (C % 8 == 0), 2 tile inside one tap (C % 64 == 0)
     int32_t grid_x, grid_y, grid_z, block;
@@ -87,6 +90,15 @@ struct OpArgs {
     float *ws;                   // split-K partial sums
     uint32_t *counters;          // split-K arrival counters, one per output tile, zero between launches
 };
+
+// Magic numbers of the division above: l = ceil(log2 d), m = floor(2^32 (2^l - d) / d) + 1, s1 = min(l, 1), s2 = max(l - 1, 0).
+inline void make_divisor(uint32_t d, uint32_t &m, uint32_t &s1, uint32_t &s2) {
+    uint32_t l = 0;
+    while (l < 32 && ((uint64_t)1 << l) < d) ++l;
+    m = (uint32_t)((((uint64_t)1 << 32) * (((uint64_t)1 << l) - d)) / d + 1);
+    s1 = l < 1 ? l : 1;
+    s2 = l > 1 ? l - 1 : 0;
+}
 
 // Launchers (defined in the .hip files).  Return a hipError_t as int.
 int launch_direct(const OpArgs &a, void *stream);

@@ -163,10 +163,15 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
         const int row = row0 + i * ROW_STEP;
         const int m = m0 + row;
         xrow_ok[i] = (row < BM) & (m < M);
-        const int mm = xrow_ok[i] ? m : 0;
-        const int q = mm % a.Q;
-        const int p = (mm / a.Q) % a.P;
-        const int n = mm / (a.Q * a.P);
+        const uint32_t mm = xrow_ok[i] ? (uint32_t)m : 0u;
+        // pixel index -> (image, row, column) by multiply-high divisions: a divide instruction sequence per row is a
+        // large part of the prologue of a short, latency-bound launch
+        const uint32_t t1 = __umulhi(a.divpq_m, mm);
+        const int n = (int)((t1 + ((mm - t1) >> a.divpq_s1)) >> a.divpq_s2);
+        const uint32_t rem = mm - (uint32_t)n * (uint32_t)(a.P * a.Q);
+        const uint32_t t2 = __umulhi(a.divq_m, rem);
+        const int p = (int)((t2 + ((rem - t2) >> a.divq_s1)) >> a.divq_s2);
+        const int q = (int)(rem - (uint32_t)p * (uint32_t)a.Q);
         img_off[i] = n * a.H * a.W * XS;
         ih0[i] = p * a.sh - a.ph;
         iw0[i] = q * a.sw - a.pw;
@@ -573,6 +578,9 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
             }
 #pragma unroll
             for (int t = 0; t < 8; ++t) v[t] = apply_act(v[t], a.act);
+#ifdef MT_EXP_NOSTORE
+            if (v[0] == 123456.f)
+#endif
             store_pack<T, 8>(y + (int64_t)m * a.y_ct + a.y_coff + k, v);
         }
         return;

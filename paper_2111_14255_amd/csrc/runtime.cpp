@@ -133,6 +133,8 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
     // Which operand each XCD's L2 keeps to itself: consecutive tiles (one XCD) walk the channel tiles of one pixel
     // tile (0) when the activations are the larger operand, the pixel tiles of one channel tile (1) otherwise.
     p.tile_order = ((double)Kc * gemm_k > (double)p.N * p.H * p.W * p.C) ? 1 : 0;
+    make_divisor((uint32_t)p.Q, p.divq_m, p.divq_s1, p.divq_s2);
+    make_divisor((uint32_t)p.P * (uint32_t)p.Q, p.divpq_m, p.divpq_s1, p.divpq_s2);
     const int total = tiles * p.split_k;
     p.grid_x = cdiv(total, 8) * 8;
 }
