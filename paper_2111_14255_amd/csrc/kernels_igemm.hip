@@ -639,7 +639,7 @@ __device__ __forceinline__ void unpack8(u32x4 v, float (&f)[8]) {
     for (int i = 0; i < 8; ++i) f[i] = to_f32(e[i]);
 }
 
-template <typename T, int MB, int ROWS>
+template <typename T, int MB, int ROWS, bool STREAM_W>
 __global__ void __launch_bounds__(256) gemv_kernel(OpArgs a) {
     const int wave = (int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
     const int lane = threadIdx.x & 63;
@@ -665,7 +665,13 @@ __global__ void __launch_bounds__(256) gemv_kernel(OpArgs a) {
             const bool ok = j < J;
 #pragma unroll
             for (int r = 0; r < ROWS; ++r)      // rows beyond K exist in the padded bank (zeros)
-                wv[u][r] = ok ? *reinterpret_cast<const u32x4 *>(wp + (int64_t)(k0 + r) * a.k_pad + j) : u32x4{0u, 0u, 0u, 0u};
+                // STREAM_W: a bank of 16 MB or more is read with non-temporal loads, so that it (VGG-16 FC1: 205 MB) does
+                // not evict every other tenant's weights from the memory-side cache on its way through
+                if (STREAM_W)
+                    wv[u][r] = ok ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(wp + (int64_t)(k0 + r) * a.k_pad + j))
+                                  : u32x4{0u, 0u, 0u, 0u};
+                else
+                    wv[u][r] = ok ? *reinterpret_cast<const u32x4 *>(wp + (int64_t)(k0 + r) * a.k_pad + j) : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
             for (int m = 0; m < MB; ++m)
                 xv[u][m] = (ok && m < a.N) ? *reinterpret_cast<const u32x4 *>(x + (int64_t)m * J + j) : u32x4{0u, 0u, 0u, 0u};
@@ -743,14 +749,15 @@ static int launch_igemm_typed(const OpArgs &a, hipStream_t st) {
         case K_IGEMM_64x16: launch_cfg<T, 64, 16, 4, 1, 16, 4>(a, st); break;
         case K_GEMV: {
             const dim3 grid(a.grid_x), block(256);
-            if (a.N <= 1)
-                hipLaunchKernelGGL((gemv_kernel<T, 1, 2>), grid, block, 0, st, a);
-            else if (a.N <= 2)
-                hipLaunchKernelGGL((gemv_kernel<T, 2, 2>), grid, block, 0, st, a);
-            else if (a.N <= 4)
-                hipLaunchKernelGGL((gemv_kernel<T, 4, 2>), grid, block, 0, st, a);
-            else
-                hipLaunchKernelGGL((gemv_kernel<T, 8, 2>), grid, block, 0, st, a);
+            const bool stream_w = (int64_t)a.n_pad * a.k_pad * 2 >= (16ll << 20);
+            auto go = [&]<int MB>() {
+                if (stream_w) hipLaunchKernelGGL((gemv_kernel<T, MB, 2, true>), grid, block, 0, st, a);
+                else hipLaunchKernelGGL((gemv_kernel<T, MB, 2, false>), grid, block, 0, st, a);
+            };
+            if (a.N <= 1) go.template operator()<1>();
+            else if (a.N <= 2) go.template operator()<2>();
+            else if (a.N <= 4) go.template operator()<4>();
+            else go.template operator()<8>();
             break;
         }
         default: return (int)hipErrorInvalidValue;
