@@ -250,7 +250,7 @@ class Context:
         B.check(self.lib.mt_run(self.h, sched.h, ins, outs, C.byref(tm)))
         return {"makespan_ms": tm.makespan_ms, "host_issue_ms": tm.host_issue_ms, "n_launches": tm.n_launches,
                 "stage_ms": [tm.stage_ms[i] for i in range(tm.n_stages)],
-                "first_op_done_ms": [tm.first_op_done_ms[i] for i in range(n)]}
+                "first_op_done_ms": [tm.first_op_done_ms[i] for i in range(n)], "n_fused": tm.n_fused}
 
     def profile_ops(self, tenant, inp, out, repeats=5):
         n = self.lens()[tenant]

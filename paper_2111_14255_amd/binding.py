@@ -27,6 +27,7 @@ MT_SCHED_GRAPH = 1
 MT_SCHED_PARALLEL_ISSUE = 2
 MT_SCHED_TIME_FIRST_OP = 4
 MT_SCHED_SHARE_PER_STAGE = 8
+MT_SCHED_FUSE_DEPTHWISE = 16
 MT_SEARCH_COORDINATE, MT_SEARCH_RANDOM = 0, 1
 
 
@@ -52,7 +53,7 @@ class mt_device_info(C.Structure):
 class mt_timings(C.Structure):
     _fields_ = [("makespan_ms", C.c_float), ("host_issue_ms", C.c_float), ("n_launches", C.c_int32),
                 ("n_stages", C.c_int32), ("stage_ms", C.c_float * MT_MAX_STAGES),
-                ("first_op_done_ms", C.c_float * MT_MAX_TENANTS)]
+                ("first_op_done_ms", C.c_float * MT_MAX_TENANTS), ("n_fused", C.c_int32)]
 
 
 class mt_search_opts(C.Structure):

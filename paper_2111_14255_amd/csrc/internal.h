@@ -15,6 +15,7 @@ int32_t fail(int32_t code, const std::string &msg);
 // ---- scheduling layer (host only) ------------------------------------------------------
 struct IssueItem {
     int32_t stream, tenant, op;
+    int32_t fuse = 0;      // runtime only: 1 = issued as part of the next operator's launch, 2 = launches the pair (op - 1, op)
 };
 int32_t validate_pointers(int32_t n_tenants, const int32_t *lens, int32_t n_stages, const int32_t *pointers);
 void expand_pointers(int32_t n_tenants, const int32_t *lens, int32_t n_stages, const int32_t *pointers, int32_t *slices);
@@ -103,6 +104,8 @@ inline void make_divisor(uint32_t d, uint32_t &m, uint32_t &s1, uint32_t &s2) {
 // Launchers (defined in the .hip files).  Return a hipError_t as int.
 int launch_direct(const OpArgs &a, void *stream);
 int launch_igemm(const OpArgs &a, void *stream);
+bool dwpw_fusable(const OpArgs &dw, const OpArgs &pw);
+int launch_dwpw(const OpArgs &dw, const OpArgs &pw, void *stream);   // depthwise 3x3 + the 1x1 convolution that reads it, one launch
 int launch_fill_u32(uint32_t *p, size_t n, uint32_t v, void *stream);
 int launch_probe(uint32_t *out, int n_groups, void *stream);
 

@@ -765,6 +765,214 @@ static int launch_igemm_typed(const OpArgs &a, hipStream_t st) {
     return (int)hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// Depthwise 3x3 convolution fused into the 1x1 convolution that consumes it (the second half of an inverted
+// residual block), for the case where the 1x1 layer runs on the 64x16 tile without a split: one launch instead of
+// two on a latency-bound chain.  The im2col tile of the 1x1 layer is not read from memory but computed: for its
+// (pixel, 8 channels) chunk a thread loads the nine taps, multiplies them with the depthwise filters (kept in LDS),
+// adds bias, applies the activation and rounds to the storage type, exactly the operation sequence of the stand-alone
+// depthwise kernel, and writes the chunk to the LDS tile (and, from the first channel tile, to the intermediate
+// tensor, which stays valid).  The MFMA sequence, tile and reduction order are those of the 64x16 implicit-GEMM
+// instantiation, so the output bits equal those of the two separate launches.
+template <typename T>
+__global__ void __launch_bounds__(256) dwpw_kernel(OpArgs a, OpArgs d) {
+    constexpr int BN = 64, BM = 16;
+    constexpr int G = 3;                                 // channel chunks of a thread whose tap loads are in flight together
+    typedef typename Mma<T, 16>::Acc Acc;
+    __shared__ __attribute__((aligned(16))) uint16_t Ws[2][BN * LDK];
+    // depthwise filters [9][k_pad] of T, bias [k_pad] floats, depthwise output of the 16 pixels [16][k_pad + 8] of T
+    extern __shared__ __attribute__((aligned(16))) unsigned char dyn[];
+    const int tid = threadIdx.x, lane = tid & 63, wn = tid >> 6;
+    const int M = a.N * a.P * a.Q;
+    const int tiles_n = a.n_pad / BN;
+    const int tn = blockIdx.x % tiles_n, tm = blockIdx.x / tiles_n;
+    const int n0 = tn * BN, m0 = tm * BM;
+    const int nk = a.k_pad / BK;
+    const int C = d.C;                                   // channels of the depthwise layer = reduction length of the 1x1 layer
+    const int CP8 = a.k_pad / 8;                         // 8-channel chunks per padded row
+    const int XLD = a.k_pad + 8;                         // row stride of the depthwise output tile (16-byte reads fall in distinct banks)
+    u32x4 *dww = reinterpret_cast<u32x4 *>(dyn);
+    float *dwb = reinterpret_cast<float *>(dyn + (size_t)9 * a.k_pad * 2);
+    uint16_t *Xf = reinterpret_cast<uint16_t *>(dyn + (size_t)9 * a.k_pad * 2 + (size_t)a.k_pad * 4);
+
+    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void *>(a.w), 0, (int)((int64_t)a.n_pad * a.k_pad * 2), 0x00027000);
+    const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void *>(d.x), 0, (int)((int64_t)d.N * d.H * d.W * C * 2), 0x00027000);
+    const __amdgpu_buffer_rsrc_t rsrc_dw = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void *>(d.w), 0, (int)((int64_t)9 * C * 2), 0x00027000);
+
+    // filter tile of the 1x1 layer: 512 chunks, two per thread; tile 0 is requested before anything else
+    uint32_t wvoff[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int c = tid + i * 256;
+        wvoff[i] = (uint32_t)(((n0 + c / 8) * a.k_pad + (c % 8) * 8) * 2);
+    }
+    u32x4 wr[2][2];
+    auto load_w = [&](int t, u32x4 (&r)[2]) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) r[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, wvoff[i], (uint32_t)(t * BK * 2), 0);
+    };
+    auto store_w = [&](int buf, const u32x4 (&r)[2]) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int c = tid + i * 256;
+            *reinterpret_cast<u32x4 *>(&Ws[buf][(c / 8) * LDK + (c % 8) * 8]) = r[i];
+        }
+    };
+    load_w(0, wr[0]);
+    if (1 < nk) load_w(1, wr[1]);
+
+    // depthwise filters and bias of every channel into LDS (zeros beyond C)
+    for (int i = tid; i < 9 * CP8; i += 256) {
+        const int tap = i / CP8, c8 = i - tap * CP8;
+        const uint32_t off = c8 * 8 < C ? (uint32_t)((tap * C + c8 * 8) * 2) : OOB_OFFSET;
+        dww[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_dw, off, 0, 0);
+    }
+    for (int i = tid; i < a.k_pad; i += 256) dwb[i] = i < C ? d.bias[i] : 0.f;
+
+    // ---- phase 1: the depthwise output of this tile's 16 pixels, every channel, into LDS -----------------------
+    // 16 threads per pixel; a thread walks the 8-channel chunks (tid % 16) + 16 j of its pixel.
+    const int px = tid >> 4, cl = tid & 15;
+    const int m = m0 + px;
+    const bool row_ok = m < M;
+    const uint32_t mm = row_ok ? (uint32_t)m : 0u;
+    const uint32_t t1 = __umulhi(a.divpq_m, mm);
+    const int img = (int)((t1 + ((mm - t1) >> a.divpq_s1)) >> a.divpq_s2);
+    const uint32_t rem = mm - (uint32_t)img * (uint32_t)(a.P * a.Q);
+    const uint32_t t2 = __umulhi(a.divq_m, rem);
+    const int pp = (int)((t2 + ((rem - t2) >> a.divq_s1)) >> a.divq_s2);
+    const int qq = (int)(rem - (uint32_t)pp * (uint32_t)a.Q);
+    const int ih0 = pp * d.sh - d.ph, iw0 = qq * d.sw - d.pw;
+    bool tap_ok[9];
+    uint32_t tapoff[9];
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+        for (int sx = 0; sx < 3; ++sx) {
+            const int ih = ih0 + r, iw = iw0 + sx;
+            tap_ok[r * 3 + sx] = row_ok & ((uint32_t)ih < (uint32_t)d.H) & ((uint32_t)iw < (uint32_t)d.W);
+            tapoff[r * 3 + sx] = (uint32_t)((((img * d.H + ih) * d.W + iw) * C) * 2);
+        }
+    __syncthreads();                                     // depthwise filters and bias are in LDS
+    for (int c8b = cl; c8b < CP8; c8b += 16 * G) {
+        u32x4 xt[G][9];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const int c0 = (c8b + 16 * g) * 8;
+            const bool ch_ok = c0 < C;
+#pragma unroll
+            for (int k = 0; k < 9; ++k) {
+                const uint32_t off = (tap_ok[k] & ch_ok) ? tapoff[k] + (uint32_t)(c0 * 2) : OOB_OFFSET;
+                xt[g][k] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, off, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const int c8 = c8b + 16 * g;
+            if (c8 >= CP8) continue;
+            const int c0 = c8 * 8;
+            const bool ch_ok = row_ok && c0 < C;
+            float acc[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+#pragma unroll
+            for (int k = 0; k < 9; ++k) {
+                const Pack<T, 8> xv = __builtin_bit_cast(Pack<T, 8>, xt[g][k]);
+                const Pack<T, 8> wv = __builtin_bit_cast(Pack<T, 8>, dww[k * CP8 + c8]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[i] = tap_ok[k] ? fmaf(to_f32(xv.e[i]), to_f32(wv.e[i]), acc[i]) : acc[i];
+            }
+            Pack<T, 8> o;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float v = apply_act(acc[i] + dwb[c0 + i], d.act);
+                from_f32(ch_ok ? v : 0.f, o.e[i]);
+            }
+            *reinterpret_cast<Pack<T, 8> *>(&Xf[px * XLD + c0]) = o;
+            if (tn == 0 && ch_ok) *reinterpret_cast<Pack<T, 8> *>((T *)d.y + (int64_t)m * d.y_ct + d.y_coff + c0) = o;
+        }
+    }
+
+    // ---- phase 2: the 1x1 layer, im2col rows read from the LDS tile above --------------------------------------
+    Acc acc;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[v] = 0.f;
+    const int frag_row = lane & 15, frag_k = (lane >> 4) * 8;
+    const float4 bias4 = *reinterpret_cast<const float4 *>(a.bias + n0 + wn * 16 + 4 * (lane >> 4));   // padded to n_pad
+    auto step = [&](int t, u32x4 (&r)[2]) {
+        const int buf = t & 1;
+        store_w(buf, r);
+        if (t + 2 < nk) load_w(t + 2, r);
+        __syncthreads();                   // filter tile t (and, at t = 0, the depthwise tile) complete; tile t - 1 was consumed
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const int koff = kk * 32 + frag_k;
+            const u32x4 fa = *reinterpret_cast<const u32x4 *>(&Ws[buf][(wn * 16 + frag_row) * LDK + koff]);
+            const u32x4 fb = *reinterpret_cast<const u32x4 *>(&Xf[frag_row * XLD + t * BK + koff]);
+            acc = Mma<T, 16>::run(fa, fb, acc);
+        }
+    };
+    for (int t = 0; t < nk; t += 2) {
+        step(t, wr[0]);
+        if (t + 1 < nk) step(t + 1, wr[1]);
+    }
+
+    // epilogue of the 1x1 layer: bias, residual, activation, one rounding
+    T *y = (T *)a.y;
+    const T *res = (const T *)a.res;
+    const int mo = m0 + frag_row, k = n0 + wn * 16 + 4 * (lane >> 4);
+    if (mo >= M || k >= a.K) return;
+    float v[4] = {acc[0] + bias4.x, acc[1] + bias4.y, acc[2] + bias4.z, acc[3] + bias4.w};
+    const bool vec_ok = (a.y_ct % 4 == 0) && (a.y_coff % 4 == 0) && (a.res_ct % 4 == 0);
+    if (vec_ok && k + 4 <= a.K) {
+        if (res) {
+            float rv[4];
+            load_pack<T, 4>(res + (int64_t)mo * a.res_ct + k, rv);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) v[t] += rv[t];
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) v[t] = apply_act(v[t], a.act);
+        store_pack<T, 4>(y + (int64_t)mo * a.y_ct + a.y_coff + k, v);
+    } else {
+        for (int t = 0; t < 4 && k + t < a.K; ++t) {
+            float f = v[t];
+            if (res) f += to_f32(res[(int64_t)mo * a.res_ct + k + t]);
+            f = apply_act(f, a.act);
+            T o;
+            from_f32(f, o);
+            y[(int64_t)mo * a.y_ct + a.y_coff + k + t] = o;
+        }
+    }
+}
+
+static size_t dwpw_lds_bytes(int k_pad) { return (size_t)k_pad * (18 + 4) + (size_t)16 * (k_pad + 8) * 2; }
+
+// Host check of what the fused kernel assumes; the runtime pairs two operators only when this holds.
+bool dwpw_fusable(const OpArgs &dw, const OpArgs &pw) {
+    if (dw.kernel_id != K_DWCONV || pw.kernel_id != K_IGEMM_64x16) return false;
+    if (dw.dtype != pw.dtype || (dw.dtype != MT_F16 && dw.dtype != MT_BF16)) return false;
+    if (dw.R != 3 || dw.S != 3 || dw.vec != 8 || dw.C % 8 != 0 || dw.y_coff != 0 || dw.y_ct != dw.C) return false;
+    if (pw.R != 1 || pw.S != 1 || pw.sh != 1 || pw.sw != 1 || pw.ph != 0 || pw.pw != 0 || pw.groups > 1) return false;
+    if (pw.split_k != 1 || pw.vec_a == 0 || pw.C != dw.C || pw.x_ct != dw.C || pw.x_coff != 0) return false;
+    if (pw.N != dw.N || pw.H != dw.P || pw.W != dw.Q || pw.P != dw.P || pw.Q != dw.Q) return false;
+    if (dwpw_lds_bytes(pw.k_pad) > 44 * 1024) return false;          // filters, bias and the depthwise tile must fit beside the filter tiles in 64 KB of LDS
+    return true;
+}
+
+int launch_dwpw(const OpArgs &dw, const OpArgs &pw, void *stream) {
+    hipStream_t st = (hipStream_t)stream;
+    if (!dwpw_fusable(dw, pw)) return (int)hipErrorInvalidValue;
+    const int M = pw.N * pw.P * pw.Q;
+    const dim3 grid(((M + 15) / 16) * (pw.n_pad / 64)), block(256);
+    const size_t dyn = dwpw_lds_bytes(pw.k_pad);
+    if (pw.dtype == MT_F16) hipLaunchKernelGGL(dwpw_kernel<f16>, grid, block, dyn, st, pw, dw);
+    else hipLaunchKernelGGL(dwpw_kernel<bf16>, grid, block, dyn, st, pw, dw);
+    return (int)hipGetLastError();
+}
+
 int launch_igemm(const OpArgs &a, void *stream) {
     hipStream_t st = (hipStream_t)stream;
     if (a.dtype == MT_F16) return launch_igemm_typed<f16>(a, st);

@@ -318,6 +318,7 @@ struct Tenant {
     bool owns_arena = false;
     std::vector<OpArgs> args;       // device pointers resolved; input/output patched per run
     std::vector<uint8_t> reads_input, res_input, writes_output;
+    std::vector<uint8_t> fuse_next;  // operator i is a depthwise convolution that can run inside the launch of operator i + 1
 };
 
 struct StreamKey {
@@ -384,6 +385,7 @@ struct mt_schedule {
     std::vector<std::array<hipStream_t, MT_MAX_TENANTS>> stream_at;
     std::vector<StreamKey> stream_keys;     // one reference in the context's pool per entry
     int n_launches = 0;
+    int n_fused = 0;                // operators that run inside the next operator's launch
     // graph replay
     hipGraphExec_t graph_exec = nullptr;
     std::vector<const void *> cap_in;
@@ -544,10 +546,18 @@ int32_t issue_schedule(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, v
         for (int sm : sp.streams) HIP_TRY(wait_for_previous_stage(ctx, s, st, sm));
         for (const IssueItem &it : sp.items) {
             const Tenant &t = *ctx->tenants[it.tenant];
+            ++launches;                              // counts operators issued, fused or not
+            if (it.fuse == 1) continue;              // runs inside the next operator's launch
             OpArgs a = patched(t, it.op, inputs[it.tenant], outputs[it.tenant]);
-            int32_t rc = launch_op(a, s->stream_at[st][it.stream]);
+            int32_t rc = MT_OK;
+            if (it.fuse == 2) {
+                const OpArgs dw = patched(t, it.op - 1, inputs[it.tenant], outputs[it.tenant]);
+                const int e = launch_dwpw(dw, a, s->stream_at[st][it.stream]);
+                if (e != 0) rc = fail(MT_ERR_HIP, std::string("fused launch: ") + hipGetErrorString((hipError_t)e));
+            } else {
+                rc = launch_op(a, s->stream_at[st][it.stream]);
+            }
             if (rc != MT_OK) return rc;
-            ++launches;
             if ((s->flags & MT_SCHED_TIME_FIRST_OP) && it.op == 0) HIP_TRY(hipEventRecord(ctx->ev_first[it.tenant], s->stream_at[st][it.stream]));
         }
         for (int sm : sp.streams) {
@@ -588,7 +598,9 @@ void issue_worker(mt_ctx *ctx, int w) {
                     if (e != hipSuccess) break;
                     const Tenant &t = *ctx->tenants[it.tenant];
                     OpArgs a = patched(t, it.op, pool.inputs[it.tenant], pool.outputs[it.tenant]);
-                    int rc = launch_raw(a, s->stream_at[st][w]);
+                    if (it.fuse == 1) continue;
+                    int rc = it.fuse == 2 ? launch_dwpw(patched(t, it.op - 1, pool.inputs[it.tenant], pool.outputs[it.tenant]), a, s->stream_at[st][w])
+                                          : launch_raw(a, s->stream_at[st][w]);
                     if (rc != 0) e = (hipError_t)rc;
                 }
                 if (e == hipSuccess) e = hipEventRecord(ctx->ev_done[st][w], s->stream_at[st][w]);
@@ -1006,6 +1018,14 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
         t->args[i] = a;
         o.w_host.clear(); o.w_host.shrink_to_fit();
     }
+    // depthwise convolution followed by the 1x1 convolution that reads it: candidates for one fused launch
+    t->fuse_next.assign(nops, 0);
+    for (size_t i = 0; i + 1 < nops; ++i) {
+        const mt_op_desc &d0 = t->model.ops[i].d, &d1 = t->model.ops[i + 1].d;
+        if (d0.kind == MT_DWCONV && d1.kind == MT_CONV && d1.in_tensor == d0.out_tensor && !t->writes_output[i] &&
+            dwpw_fusable(t->args[i], t->args[i + 1]))
+            t->fuse_next[i] = 1;
+    }
     HIP_TRY(hipDeviceSynchronize());
     guard.armed = false;
     ctx->tenants.push_back(std::move(t));
@@ -1098,6 +1118,19 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
         const int conc = stage_concurrency ? stage_concurrency[st] : n_tenants;
         StagePlan &sp = s->stages[st];
         sp.items = issue_order(n_tenants, &slices[(size_t)st * n_tenants * 2], conc, order);
+        // On request, a depthwise convolution whose consumer is issued in the same stage runs inside the consumer's launch.
+        if (flags & MT_SCHED_FUSE_DEPTHWISE)
+            for (size_t k = 0; k < sp.items.size(); ++k) {
+                IssueItem &it = sp.items[k];
+                const Tenant &tt = *ctx->tenants[it.tenant];
+                const int end = slices[((size_t)st * n_tenants + it.tenant) * 2 + 1];
+                if (it.op + 1 < end && tt.fuse_next[it.op]) {
+                    it.fuse = 1;
+                    ++s->n_fused;
+                    for (size_t k2 = k + 1; k2 < sp.items.size(); ++k2)
+                        if (sp.items[k2].tenant == it.tenant && sp.items[k2].op == it.op + 1) { sp.items[k2].fuse = 2; break; }
+                }
+            }
         for (const IssueItem &it : sp.items)
             if (std::find(sp.streams.begin(), sp.streams.end(), it.stream) == sp.streams.end()) sp.streams.push_back(it.stream);
         std::sort(sp.streams.begin(), sp.streams.end());
@@ -1171,6 +1204,7 @@ int32_t mt_run(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *con
     if (tm) {
         std::memset(tm, 0, sizeof(*tm));
         tm->n_launches = launches;
+        tm->n_fused = s->n_fused;
         tm->n_stages = s->n_stages;
         tm->host_issue_ms = std::chrono::duration<float, std::milli>(t1 - t0).count();
         if (s->flags & MT_SCHED_GRAPH) {

@@ -4,6 +4,8 @@ import numpy as np
 import pytest
 
 from synth import GraphBuilder
+from oracle import forward as OF
+from paper_2111_14255_amd import binding as B
 from gpu_harness import Mix, assert_close
 
 pytestmark = pytest.mark.gpu
@@ -222,5 +224,48 @@ def test_split_k_is_deterministic_and_counters_reset():
             if first is None:
                 first = got
             assert np.array_equal(first[0], got[0]) and np.array_equal(first[1], got[1])
+    finally:
+        mix.close()
+
+
+# ---- depthwise convolution fused into the 1x1 convolution that reads it --------------------------------------------
+FUSED_BLOCKS = [
+    # name, n, h, w, c_in, hidden, c_out, stride, residual
+    ("c96_s1_res", 1, 14, 14, 16, 96, 16, 1, True),
+    ("c144_s2", 1, 15, 15, 24, 144, 32, 2, False),
+    ("c192_s1_ragged_pixels", 2, 7, 9, 32, 192, 32, 1, True),
+    ("c384_s1_n96", 1, 14, 14, 64, 384, 96, 1, False),
+    ("c960_s1_n160_two_channel_tiles", 1, 7, 7, 160, 960, 160, 1, True),
+    ("c32_single_tile_padded", 1, 10, 10, 8, 32, 16, 1, False),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("name,n,h,w,cin,hid,cout,stride,resid", FUSED_BLOCKS, ids=[c[0] for c in FUSED_BLOCKS])
+def test_fused_depthwise_pointwise_equals_separate_launches(name, n, h, w, cin, hid, cout, stride, resid, dtype):
+    g = GraphBuilder("blk", dtype, n, h, w, cin)
+    e = g.conv(0, hid, 1, act="relu6", bn=True)
+    d = g.dwconv(e, 3, stride, 1, act="relu6", bn=True)
+    g.conv(d, cout, 1, act="none", bn=True, res=0 if resid else -1)
+    spec = g.done()
+    print("case", name, dtype, flush=True)
+    mix = Mix([spec], seed=21)
+    try:
+        ctx = mix.ctx
+        fused, tm = mix.run(ctx.sequential(flags=B.MT_SCHED_FUSE_DEPTHWISE))
+        assert tm["n_fused"] == (0 if "two_channel_tiles" in name else 1), tm     # the 960-channel case is split along K: not fused
+        dshape = (n,) + tuple(spec.ops[1].out_shape)
+        dw_fused = ctx.read_tensor(0, d, dshape)
+        plain, tm = mix.run(ctx.sequential())
+        assert tm["n_fused"] == 0
+        dw_plain = ctx.read_tensor(0, d, dshape)
+        split, tm = mix.run(ctx.schedule([[2]], 2, flags=B.MT_SCHED_FUSE_DEPTHWISE))   # a stage boundary between the two operators: no fusion either
+        assert tm["n_fused"] == 0
+        assert np.array_equal(fused[0].view(np.uint32), plain[0].view(np.uint32))
+        assert np.array_equal(fused[0].view(np.uint32), split[0].view(np.uint32))
+        assert np.array_equal(dw_fused.view(np.uint32), dw_plain.view(np.uint32))      # the intermediate tensor stays valid
+        ref, tensors = OF.forward(spec, OF.prepare_params(spec, mix.raw[0]), mix.x[0], keep=True)
+        assert_close(fused[0], ref, dtype, name)
+        assert_close(dw_fused.reshape(n, -1), tensors[d].reshape(n, -1), dtype, name + " depthwise output")
     finally:
         mix.close()
