@@ -159,6 +159,10 @@ def main():
     sched_pi = ctx.schedule(rho, cfg.n_stages, cu_share=shares, flags=B.MT_SCHED_PARALLEL_ISSUE)
     results["searched+cu_share+parallel_issue"] = time_schedule(ctx, torch, sched_pi, inputs, outputs, args.warmup, args.steps)
     results["searched+cu_share+parallel_issue"].update({"pointers": rho, "cu_share": shares})
+    # and replayed from one captured graph per stream (CU shares stay in force)
+    sched_sg = ctx.schedule(rho, cfg.n_stages, cu_share=shares, flags=B.MT_SCHED_STREAM_GRAPHS)
+    results["searched+cu_share+stream_graphs"] = time_schedule(ctx, torch, sched_sg, inputs, outputs, args.warmup, args.steps)
+    results["searched+cu_share+stream_graphs"].update({"pointers": rho, "cu_share": shares})
     for k, r in results.items():
         base = results["sequential" + ("+graph" if k.endswith("+graph") else "")]
         r["img_per_s"] = images / (r["wall_ms_per_step"] * 1e-3)

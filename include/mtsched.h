@@ -228,6 +228,12 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
  * MobileNetV2 at batch 1 the fused launch takes as long as the two it replaces (10.3 us against 4.0 + 4.9 us plus
  * the gap between them), because one workgroup then computes the depthwise output of its 16 pixels alone. */
 #define MT_SCHED_FUSE_DEPTHWISE 16
+/* MT_SCHED_STREAM_GRAPHS: the launches of one stream in one stage are captured (on that stream, on the first run
+ * and again when a buffer pointer changes) into a graph of their own and replayed on that stream: the short gaps
+ * between kernels of a replayed graph, with CU shares still in force (the replay runs on the masked stream) and with
+ * per-stage timings (the stage barriers stay ordinary events).  Not combinable with MT_SCHED_GRAPH,
+ * MT_SCHED_PARALLEL_ISSUE or MT_SCHED_TIME_FIRST_OP. */
+#define MT_SCHED_STREAM_GRAPHS 32
 int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, const int32_t *pointers,
                            const int32_t *stage_concurrency, const int32_t *cu_share,
                            int32_t issue_order, int32_t flags, mt_schedule **out);

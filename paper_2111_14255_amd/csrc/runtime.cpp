@@ -390,7 +390,12 @@ struct mt_schedule {
     hipGraphExec_t graph_exec = nullptr;
     std::vector<const void *> cap_in;
     std::vector<void *> cap_out;
+    // MT_SCHED_STREAM_GRAPHS: one graph per (stage, stream) with the launches of that stream in that stage
+    std::vector<std::array<hipGraphExec_t, MT_MAX_TENANTS>> slice_exec;
 };
+
+// Hands every graph of a schedule to the context for release at mt_destroy.
+static void retire_graphs(mt_ctx *ctx, mt_schedule *s);
 
 namespace {
 
@@ -425,6 +430,19 @@ int launch_raw(const OpArgs &a, hipStream_t st) {
     }
     return 0;
 }
+
+}  // namespace
+
+static void retire_graphs(mt_ctx *ctx, mt_schedule *s) {
+    if (s->graph_exec) ctx->retired_graphs.push_back(s->graph_exec);
+    s->graph_exec = nullptr;
+    for (auto &row : s->slice_exec)
+        for (hipGraphExec_t g : row)
+            if (g) ctx->retired_graphs.push_back(g);
+    s->slice_exec.clear();
+}
+
+namespace {
 
 int32_t launch_op(const OpArgs &a, hipStream_t st) {
     const int e = launch_raw(a, st);
@@ -535,6 +553,43 @@ hipError_t wait_for_previous_stage(mt_ctx *ctx, const mt_schedule *s, int st, in
     return e;
 }
 
+// MT_SCHED_STREAM_GRAPHS: the launches of one stream in one stage, captured on that stream (so that a CU mask of the
+// stream applies at replay) into a graph of their own.  The barriers between stages stay ordinary events.
+int32_t capture_slice_graphs(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *const *outputs) {
+    retire_graphs(ctx, s);
+    s->slice_exec.assign(s->n_stages, {});
+    for (int st = 0; st < s->n_stages; ++st) {
+        const StagePlan &sp = s->stages[st];
+        for (int sm : sp.streams) {
+            hipStream_t stream = s->stream_at[st][sm];
+            hipGraph_t graph = nullptr;
+            HIP_TRY(hipStreamBeginCapture(stream, hipStreamCaptureModeRelaxed));
+            int32_t rc = MT_OK;
+            for (const IssueItem &it : sp.by_stream[sm]) {
+                if (it.fuse == 1) continue;
+                const Tenant &t = *ctx->tenants[it.tenant];
+                const OpArgs a = patched(t, it.op, inputs[it.tenant], outputs[it.tenant]);
+                if (it.fuse == 2) {
+                    const int e = launch_dwpw(patched(t, it.op - 1, inputs[it.tenant], outputs[it.tenant]), a, stream);
+                    if (e != 0) rc = fail(MT_ERR_HIP, std::string("fused launch: ") + hipGetErrorString((hipError_t)e));
+                } else {
+                    rc = launch_op(a, stream);
+                }
+                if (rc != MT_OK) break;
+            }
+            hipError_t e = hipStreamEndCapture(stream, &graph);
+            if (rc != MT_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+            if (e != hipSuccess) return fail(MT_ERR_HIP, std::string("hipStreamEndCapture: ") + hipGetErrorString(e));
+            e = hipGraphInstantiate(&s->slice_exec[st][sm], graph, nullptr, nullptr, 0);
+            (void)hipGraphDestroy(graph);
+            if (e != hipSuccess) return fail(MT_ERR_HIP, std::string("hipGraphInstantiate: ") + hipGetErrorString(e));
+        }
+    }
+    s->cap_in.assign(inputs, inputs + s->n_tenants);
+    s->cap_out.assign(outputs, outputs + s->n_tenants);
+    return MT_OK;
+}
+
 // Issues the whole schedule on the tenant streams.  Barrier between stages: every stream of the stage records an
 // event and the streams of the next stage wait for all of them; the main stream waits for them too and records the
 // stage event, which only the timings and the final synchronisation use.
@@ -544,6 +599,10 @@ int32_t issue_schedule(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, v
     for (int st = 0; st < s->n_stages; ++st) {
         const StagePlan &sp = s->stages[st];
         for (int sm : sp.streams) HIP_TRY(wait_for_previous_stage(ctx, s, st, sm));
+        if (s->flags & MT_SCHED_STREAM_GRAPHS) {
+            for (int sm : sp.streams) HIP_TRY(hipGraphLaunch(s->slice_exec[st][sm], s->stream_at[st][sm]));
+            launches += (int)sp.items.size();
+        } else
         for (const IssueItem &it : sp.items) {
             const Tenant &t = *ctx->tenants[it.tenant];
             ++launches;                              // counts operators issued, fused or not
@@ -724,8 +783,7 @@ int32_t mt_destroy(mt_ctx *ctx) {
     stop_pool(ctx);
     (void)hipDeviceSynchronize();
     for (mt_schedule *ls : ctx->live_schedules) {
-        if (ls->graph_exec) ctx->retired_graphs.push_back(ls->graph_exec);
-        ls->graph_exec = nullptr;
+        retire_graphs(ctx, ls);
         ls->ctx = nullptr;
     }
     for (hipGraphExec_t g : ctx->retired_graphs) (void)hipGraphExecDestroy(g);
@@ -1077,6 +1135,8 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
     if (order != MT_ISSUE_BFS && order != MT_ISSUE_DFS) return fail(MT_ERR_INVALID_ARG, "unknown issue order");
     if ((flags & MT_SCHED_GRAPH) && (flags & MT_SCHED_PARALLEL_ISSUE))
         return fail(MT_ERR_INVALID_ARG, "graph replay and parallel issue cannot be combined");
+    if ((flags & MT_SCHED_STREAM_GRAPHS) && (flags & (MT_SCHED_GRAPH | MT_SCHED_PARALLEL_ISSUE | MT_SCHED_TIME_FIRST_OP)))
+        return fail(MT_ERR_INVALID_ARG, "per-stream graphs cannot be combined with whole-schedule replay, parallel issue or first-operator timing");
     if ((flags & MT_SCHED_TIME_FIRST_OP) && (flags & (MT_SCHED_GRAPH | MT_SCHED_PARALLEL_ISSUE)))
         return fail(MT_ERR_INVALID_ARG, "first-operator timing needs the single issuing thread and plain streams");
     int32_t lens[MT_MAX_TENANTS];
@@ -1150,7 +1210,7 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
 int32_t mt_schedule_destroy(mt_schedule *s) {
     if (!s) return fail(MT_ERR_INVALID_ARG, "schedule is NULL");
     if (s->ctx) {
-        if (s->graph_exec) s->ctx->retired_graphs.push_back(s->graph_exec);
+        retire_graphs(s->ctx, s);
         release_streams(s);
         s->ctx->live_schedules.erase(s);
     }
@@ -1173,7 +1233,7 @@ int32_t mt_run(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *con
         bool same = s->graph_exec && (int)s->cap_in.size() == s->n_tenants;
         for (int i = 0; same && i < s->n_tenants; ++i) same = s->cap_in[i] == inputs[i] && s->cap_out[i] == outputs[i];
         if (!same) {
-            if (s->graph_exec) { ctx->retired_graphs.push_back(s->graph_exec); s->graph_exec = nullptr; }
+            retire_graphs(ctx, s);
             hipGraph_t graph = nullptr;
             HIP_TRY(hipStreamBeginCapture(ctx->main_stream, hipStreamCaptureModeRelaxed));
             int32_t rc = issue_schedule(ctx, s, inputs, outputs, &launches);
@@ -1191,6 +1251,14 @@ int32_t mt_run(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *con
         HIP_TRY(hipGraphLaunch(s->graph_exec, ctx->main_stream));
         HIP_TRY(hipEventRecord(ctx->ev_prof[1], ctx->main_stream));
     } else {
+        if (s->flags & MT_SCHED_STREAM_GRAPHS) {
+            bool same = !s->slice_exec.empty() && (int)s->cap_in.size() == s->n_tenants;
+            for (int i = 0; same && i < s->n_tenants; ++i) same = s->cap_in[i] == inputs[i] && s->cap_out[i] == outputs[i];
+            if (!same) {
+                int32_t rc = capture_slice_graphs(ctx, s, inputs, outputs);
+                if (rc != MT_OK) return rc;
+            }
+        }
         int32_t rc = (s->flags & MT_SCHED_PARALLEL_ISSUE) ? issue_schedule_parallel(ctx, s, inputs, outputs, &launches)
                                                           : issue_schedule(ctx, s, inputs, outputs, &launches);
         if (rc != MT_OK) return rc;
