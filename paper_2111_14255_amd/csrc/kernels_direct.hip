@@ -40,6 +40,7 @@ __global__ void __launch_bounds__(256) conv_direct_kernel(OpArgs a) {
     const int64_t m = e.m;
     const T *x = (const T *)a.x;
     const T *w = (const T *)a.w + (int64_t)k * a.R * a.S * a.C;
+    const bool vec4 = (a.C % 4 == 0) && (a.x_ct % 4 == 0) && (a.x_coff % 4 == 0) && (((uintptr_t)a.x | (uintptr_t)a.w) % 16 == 0);
     float acc = 0.f;
     for (int r = 0; r < a.R; ++r) {
         const int ih = p * a.sh - a.ph + r;
@@ -49,7 +50,22 @@ __global__ void __launch_bounds__(256) conv_direct_kernel(OpArgs a) {
             if (iw < 0 || iw >= a.W) continue;
             const T *xp = x + (((int64_t)n * a.H + ih) * a.W + iw) * a.x_ct + a.x_coff;
             const T *wp = w + ((int64_t)r * a.S + s) * a.C;
-            for (int c = 0; c < a.C; ++c) acc = fmaf(to_f32(xp[c]), to_f32(wp[c]), acc);
+            int c = 0;
+            if constexpr (sizeof(T) == 4) {
+                // four channels per step when both rows are 16-byte aligned: the same products added in the same
+                // order, with a quarter of the loads
+                if (vec4) {
+                    for (; c + 4 <= a.C; c += 4) {
+                        const float4 xv = *reinterpret_cast<const float4 *>(xp + c);
+                        const float4 wv = *reinterpret_cast<const float4 *>(wp + c);
+                        acc = fmaf(xv.x, wv.x, acc);
+                        acc = fmaf(xv.y, wv.y, acc);
+                        acc = fmaf(xv.z, wv.z, acc);
+                        acc = fmaf(xv.w, wv.w, acc);
+                    }
+                }
+            }
+            for (; c < a.C; ++c) acc = fmaf(to_f32(xp[c]), to_f32(wp[c]), acc);
         }
     }
     if (a.bias) acc += a.bias[k];
