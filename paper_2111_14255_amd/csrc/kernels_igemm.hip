@@ -99,13 +99,6 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
     constexpr int ROW_STEP = NT / CH_ROW;                  // tile rows covered by one pass of the workgroup
     constexpr int W_CHUNKS = (BN + ROW_STEP - 1) / ROW_STEP;
     constexpr int X_CHUNKS = (BM + ROW_STEP - 1) / ROW_STEP;
-#ifndef MT_FRAG_PREFETCH
-#define MT_FRAG_PREFETCH 0
-#endif
-#ifndef MT_TWO_ACC
-#define MT_TWO_ACC 0
-#endif
-    constexpr bool FRAG_PREFETCH = MT_FRAG_PREFETCH && WK == 1 && KSTEPS * (TN + TM) <= 8;   // two fragment sets fit the register budget
     typedef typename Mma<T, MF>::Acc Acc;
 
     // One LDS block: two filter tile buffers, then two im2col tile buffers; reused for the accumulator exchange.
@@ -342,12 +335,6 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
                 f.b[kk][j] = *reinterpret_cast<const u32x4 *>(&Xs[buf][(wm * SUBM + j * MF + frag_row) * LDK + koff]);
         }
     };
-    // Small wave tiles alternate between two accumulators so that consecutive MFMAs do not wait for each
-    // other; the two are added once at the end (fixed order).
-    constexpr bool TWO_ACC = MT_TWO_ACC && (TN * TM == 1) && (KSTEPS % 2 == 0);
-    Acc acc2;
-#pragma unroll
-    for (int v = 0; v < ACC_REGS; ++v) acc2[v] = 0.f;
     auto mma = [&](const Frags &f) {
 #pragma unroll
         for (int kk = 0; kk < KSTEPS; ++kk)
@@ -355,10 +342,7 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
             for (int i = 0; i < TN; ++i)
 #pragma unroll
                 for (int j = 0; j < TM; ++j) {
-                    if (TWO_ACC && (kk & 1))
-                        acc2 = Mma<T, MF>::run(f.a[kk][i], f.b[kk][j], acc2);
-                    else
-                        acc[i][j] = Mma<T, MF>::run(f.a[kk][i], f.b[kk][j], acc[i][j]);
+                    acc[i][j] = Mma<T, MF>::run(f.a[kk][i], f.b[kk][j], acc[i][j]);
                 }
     };
 
@@ -371,49 +355,7 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
 
     // Tile t waits in register set t % STAGES until it is copied to LDS buffer t % 2.  FULL steps are the
     // steady state (every tile they touch exists) and contain no branch.
-    if constexpr (FRAG_PREFETCH) {
-        static_assert(!FRAG_PREFETCH || STAGES <= 4, "the fragment-prefetch loop is written for 2 or 4 stages");
-        // Fragments of tile t+1 are read from LDS while the MFMAs of tile t run (two fragment register sets).
-        Frags fr[2];
-        auto step = [&]<int S, bool FULL>(int t) {
-            constexpr int set = (S + 2) % STAGES;
-            if (FULL || t < nk) {
-                if (FULL || t + 2 < nk) {
-                    store_tiles(S & 1, wreg[set], xreg[set]);                    // tile t+2 replaces tile t
-                    if (FULL || t + 2 + STAGES < nk) load_tiles(wreg[set], xreg[set]);
-                }
-                if (FULL || t + 1 < nk) load_frags((S + 1) & 1, fr[(S + 1) & 1]);
-                mma(fr[S & 1]);
-                __syncthreads();
-            }
-        };
-        store_tiles(0, wreg[0], xreg[0]);
-        if (STAGES < nk) load_tiles(wreg[0], xreg[0]);
-        __syncthreads();
-        if (1 < nk) {
-            store_tiles(1, wreg[1], xreg[1]);
-            if (STAGES + 1 < nk) load_tiles(wreg[1], xreg[1]);
-        }
-        load_frags(0, fr[0]);
-        __syncthreads();
-        int t0 = 0;
-        for (; t0 + 2 * STAGES + 1 < nk; t0 += STAGES) {
-            step.template operator()<0, true>(t0);
-            step.template operator()<1, true>(t0 + 1);
-            if constexpr (STAGES > 2) {
-                step.template operator()<2, true>(t0 + 2);
-                step.template operator()<3, true>(t0 + 3);
-            }
-        }
-        for (; t0 < nk; t0 += STAGES) {
-            step.template operator()<0, false>(t0);
-            step.template operator()<1, false>(t0 + 1);
-            if constexpr (STAGES > 2) {
-                step.template operator()<2, false>(t0 + 2);
-                step.template operator()<3, false>(t0 + 3);
-            }
-        }
-    } else {
+    {
         auto step = [&]<int S, bool FULL>(int t) {
             constexpr int nxt = (S + 1) % STAGES;
             if (FULL || t < nk) {
@@ -437,11 +379,6 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
         for (; t0 + 2 * STAGES < nk; t0 += STAGES) round.template operator()<true>(t0, std::make_integer_sequence<int, STAGES>{});
         for (; t0 < nk; t0 += STAGES) round.template operator()<false>(t0, std::make_integer_sequence<int, STAGES>{});
     }
-    if constexpr (TWO_ACC) {
-#pragma unroll
-        for (int v = 0; v < ACC_REGS; ++v) acc[0][0][v] += acc2[v];
-    }
-
     // ---- wave groups: groups 1 .. WK-1 hand their accumulators to group 0 through LDS (the tile buffers are free:
     // the main loop ends with a barrier), which adds them in group order and alone runs the rest of the kernel.
     const bool owner = wk == 0;
