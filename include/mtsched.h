@@ -83,7 +83,7 @@ typedef struct mt_op_desc {
     int32_t kind;          /* mt_op_kind */
     int32_t in_tensor;     /* must have been written by an earlier operator (or be 0) */
     int32_t res_tensor;    /* CONV: tensor added before the activation, -1 = none; ADD: the second summand (required) */
-    int32_t out_tensor;    /* >= 1 */
+    int32_t out_tensor;    /* >= 1 and at most 2 * (operators of the model) + 16 */
     int32_t out_c;         /* CONV / FC: output channels; ignored otherwise */
     int32_t out_c_offset;  /* first channel written inside out_tensor (channel concatenation without a copy) */
     int32_t out_c_total;   /* channel count of out_tensor; 0 = exactly the channels written */

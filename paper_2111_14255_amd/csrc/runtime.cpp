@@ -151,6 +151,7 @@ int32_t finalize_model(mt_model *m) {
         if (d.in_tensor < 0 || d.in_tensor >= (int)m->tensors.size() || !m->tensors[d.in_tensor].defined)
             return bad("input tensor is not produced by an earlier operator");
         if (d.out_tensor < 1) return bad("output tensor id must be >= 1");
+        if (d.out_tensor > 2 * (int)m->ops.size() + 16) return bad("output tensor id is too large for a model of this many operators");
         if (d.out_tensor == d.in_tensor) return bad("in-place operators are not supported");
         const TensorInfo in = m->tensors[d.in_tensor];
         o.in_h = in.h; o.in_w = in.w; o.in_c = in.c;
@@ -1352,7 +1353,7 @@ double profile_schedule(ProfileCost *pc, const int32_t *pointers, const int32_t 
     // a comparison between two schedules that differ by a few percent.
     std::vector<double> samples;
     for (int r = 0; r < pc->o->warmup + pc->o->runs && pc->rc == MT_OK; ++r) {
-        mt_timings tm;
+        mt_timings tm{};
         pc->rc = mt_run(pc->ctx, s, pc->inputs, pc->outputs, &tm);
         if (r >= pc->o->warmup) samples.push_back(tm.makespan_ms);
     }

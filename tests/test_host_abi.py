@@ -217,6 +217,7 @@ def test_model_validation_errors():
     assert _model([_op(dst=1, ctot=16), _op(dst=1, coff=8, ctot=16, sh=2, sw=2)]) == B.MT_ERR_SHAPE_MISMATCH
     assert _model([_op(kind=B.MT_MAXPOOL, res=0)]) == B.MT_ERR_SHAPE_MISMATCH
     assert _model([]) == B.MT_ERR_SHAPE_MISMATCH
+    assert _model([_op(dst=1 << 30)]) == B.MT_ERR_SHAPE_MISMATCH       # tensor id far beyond what one operator can define
     assert _model([_op(groups=3)]) == B.MT_ERR_SHAPE_MISMATCH                      # 8 channels do not split into 3 groups
     assert _model([_op(groups=2)]) == 0
     assert _model([_op(kind=B.MT_MAXPOOL, groups=2)]) == B.MT_ERR_SHAPE_MISMATCH   # groups on a pool
