@@ -167,8 +167,22 @@ def main():
     sched_sg = ctx.schedule(rho, cfg.n_stages, cu_share=shares, flags=B.MT_SCHED_STREAM_GRAPHS)
     results["searched+cu_share+stream_graphs"] = time_schedule(ctx, torch, sched_sg, inputs, outputs, args.warmup, args.steps)
     results["searched+cu_share+stream_graphs"].update({"pointers": rho, "cu_share": shares})
+    # the same with neighbouring 1x1 + depthwise operators of a stage issued as one launch (identical output bits)
+    FE = B.MT_SCHED_FUSE_EXPAND
+    seq_f = ctx.sequential(flags=FE)
+    results["sequential+fused_pairs"] = time_schedule(ctx, torch, seq_f, inputs, outputs, args.warmup, args.steps)
+    t0 = time.perf_counter()
+    rho_f, cost, records, shares_f = ctx.search(inputs, outputs, cfg.n_stages, rounds=args.search_rounds,
+                                                candidates=args.search_candidates, runs=7, warmup=1, seed=cfg.seed,
+                                                cu_share_rounds=2, flags=FE)
+    search_s = time.perf_counter() - t0
+    for extra, suffix in ((0, ""), (B.MT_SCHED_PARALLEL_ISSUE, "+parallel_issue")):
+        sf = ctx.schedule(rho_f, cfg.n_stages, cu_share=shares_f, flags=FE | extra)
+        key = "searched+cu_share+fused_pairs" + suffix
+        results[key] = time_schedule(ctx, torch, sf, inputs, outputs, args.warmup, args.steps)
+        results[key].update({"pointers": rho_f, "cu_share": shares_f, "search_seconds": search_s, "search_evaluations": len(records)})
     for k, r in results.items():
-        base = results["sequential" + ("+graph" if k.endswith("+graph") else "")]
+        base = results["sequential" + ("+graph" if k.endswith("+graph") else "+fused_pairs" if "+fused_pairs" in k else "")]
         r["img_per_s"] = images / (r["wall_ms_per_step"] * 1e-3)
         r["speedup_vs_sequential"] = speedup(base["makespan_ms_mean"], r["makespan_ms_mean"])
 

@@ -15,7 +15,7 @@ int32_t fail(int32_t code, const std::string &msg);
 // ---- scheduling layer (host only) ------------------------------------------------------
 struct IssueItem {
     int32_t stream, tenant, op;
-    int32_t fuse = 0;      // runtime only: 1 = issued as part of the next operator's launch, 2 = launches the pair (op - 1, op)
+    int32_t fuse = 0;      // runtime only: 1 = issued as part of the next operator's launch, 2 / 3 = launches the pair (op - 1, op): depthwise + 1x1 / 1x1 + depthwise
 };
 int32_t validate_pointers(int32_t n_tenants, const int32_t *lens, int32_t n_stages, const int32_t *pointers);
 void expand_pointers(int32_t n_tenants, const int32_t *lens, int32_t n_stages, const int32_t *pointers, int32_t *slices);
@@ -106,6 +106,8 @@ int launch_direct(const OpArgs &a, void *stream);
 int launch_igemm(const OpArgs &a, void *stream);
 bool dwpw_fusable(const OpArgs &dw, const OpArgs &pw);
 int launch_dwpw(const OpArgs &dw, const OpArgs &pw, void *stream);   // depthwise 3x3 + the 1x1 convolution that reads it, one launch
+bool pwdw_fusable(const OpArgs &pw, const OpArgs &dw);
+int launch_pwdw(const OpArgs &pw, const OpArgs &dw, void *stream);   // 1x1 convolution + the depthwise 3x3 that reads it on a small map, one launch
 int launch_fill_u32(uint32_t *p, size_t n, uint32_t v, void *stream);
 int launch_probe(uint32_t *out, int n_groups, void *stream);
 

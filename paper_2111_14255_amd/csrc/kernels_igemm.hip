@@ -19,6 +19,7 @@
 // order, so the result does not depend on arrival order.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <utility>
 
 #include "internal.h"
@@ -37,6 +38,10 @@ constexpr int LDK = BK + 8;      // padded LDS row (144 bytes: 16-byte reads of 
 constexpr int NXCD = 8;
 constexpr int A_SCALAR = 0, A_VEC8 = 1, A_UNIFORM = 2;
 constexpr uint32_t OOB_OFFSET = 0x80000000u;   // beyond any tensor: buffer loads return zeros
+// Fused 1x1 + depthwise kernel: channels of the widened tensor per workgroup, workgroups wanted at least, and 8-channel
+// chunks of depthwise output a workgroup takes at most (measured on MobileNetV2 at batch 1: 32 channels per workgroup
+// are 7 % slower, 256 to 1024 chunks 1 to 4 % slower).
+constexpr int PWDW_HC = 16, PWDW_WGS = 64, PWDW_ITEMS = 128;
 
 template <typename T, int MF>
 struct Mma;
@@ -515,9 +520,6 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
             }
 #pragma unroll
             for (int t = 0; t < 8; ++t) v[t] = apply_act(v[t], a.act);
-#ifdef MT_EXP_NOSTORE
-            if (v[0] == 123456.f)
-#endif
             store_pack<T, 8>(y + (int64_t)m * a.y_ct + a.y_coff + k, v);
         }
         return;
@@ -907,6 +909,187 @@ int launch_dwpw(const OpArgs &dw, const OpArgs &pw, void *stream) {
     const size_t dyn = dwpw_lds_bytes(pw.k_pad);
     if (pw.dtype == MT_F16) hipLaunchKernelGGL(dwpw_kernel<f16>, grid, block, dyn, st, pw, dw);
     else hipLaunchKernelGGL(dwpw_kernel<bf16>, grid, block, dyn, st, pw, dw);
+    return (int)hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// 1x1 convolution fused with the depthwise 3x3 convolution that consumes it (the first two operators of an inverted
+// residual block): one launch instead of two on a latency-bound chain.  A workgroup owns HC channels of the widened
+// tensor and a band of output rows of one image.  It computes the widened tensor on the input rows the band needs
+// (one row of overlap on each side) with the MFMA sequence of the 64x16 implicit-GEMM instantiation (operands straight
+// from memory into registers: filter rows and pixel rows are contiguous along the reduction index), rounds it to the
+// storage type into LDS (and, for the rows the band owns, to the intermediate tensor, which stays valid), and then
+// runs the depthwise filter over the LDS copy with the operation sequence of the stand-alone depthwise kernel.  Both
+// halves therefore produce the bits of the two separate launches.
+// MT: 16-pixel tiles per wave (a band reads at most 64 * MT pixels), KS: 32-deep reduction steps (k_pad <= 32 * KS).
+template <typename T, int MT, int KS, int HC>
+__global__ void __launch_bounds__(256) pwdw_kernel(OpArgs e, OpArgs d, int bands) {
+    constexpr int NI = HC / 16;                          // MFMA tiles along the channels
+    constexpr int CPP = HC / 8;                          // 8-channel chunks per pixel
+    constexpr int ELD = HC + 8;                          // LDS row stride
+    typedef typename Mma<T, 16>::Acc Acc;
+    __shared__ __attribute__((aligned(16))) uint16_t Es[MT * 64 * ELD];
+    __shared__ __attribute__((aligned(16))) uint16_t Wd[9 * HC];
+    __shared__ float Bd[HC];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int chunks = (e.K + HC - 1) / HC;
+    const int c0 = (blockIdx.x % chunks) * HC;
+    const int band = (blockIdx.x / chunks) % bands;
+    const int img = blockIdx.x / (chunks * bands);
+    const int W = d.W, Min = d.H * d.W;                  // the widened map has the pixels of the input map (1x1, stride 1)
+    const int PB = (d.P + bands - 1) / bands;
+    const int p_lo = band * PB, p_hi = min(d.P, p_lo + PB);               // output rows of this band
+    const int r_lo = max(0, p_lo * d.sh - 1), r_hi = min(d.H - 1, (p_hi - 1) * d.sh + 1);   // widened rows it reads
+    const int px0 = r_lo * W, Mb = (r_hi - r_lo + 1) * W;
+    const int own_lo = p_lo * d.sh, own_hi = band == bands - 1 ? d.H : min(d.H, p_hi * d.sh);   // widened rows it stores
+    const int nsteps = e.k_pad / 32;
+    const int frag_row = lane & 15, frag_k = (lane >> 4) * 8;
+
+    const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void *>(e.x), 0, (int)((int64_t)e.N * Min * e.C * 2), 0x00027000);
+    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void *>(e.w), 0, (int)((int64_t)e.n_pad * e.k_pad * 2), 0x00027000);
+    const __amdgpu_buffer_rsrc_t rsrc_dw = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void *>(d.w), 0, (int)((int64_t)9 * d.C * 2), 0x00027000);
+
+    u32x4 wf[NI][KS], xf[MT][KS];
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const uint32_t off = s < nsteps ? (uint32_t)(((c0 + i * 16 + frag_row) * e.k_pad + s * 32 + frag_k) * 2) : OOB_OFFSET;
+            wf[i][s] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, off, 0, 0);
+        }
+#pragma unroll
+    for (int j = 0; j < MT; ++j) {
+        const int px = (wave + 4 * j) * 16 + frag_row;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            const int k = s * 32 + frag_k;
+            const bool v = (px < Mb) & (k < e.C);
+            const uint32_t off = v ? (uint32_t)((((img * Min + px0 + px) * e.C) + k) * 2) : OOB_OFFSET;
+            xf[j][s] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, off, 0, 0);
+        }
+    }
+    float4 bias4[NI];
+#pragma unroll
+    for (int i = 0; i < NI; ++i) bias4[i] = *reinterpret_cast<const float4 *>(e.bias + c0 + i * 16 + 4 * (lane >> 4));   // padded to n_pad
+    // depthwise filters [9][HC] and bias of this workgroup's channels (zeros beyond the last channel)
+    if (tid < 9 * CPP) {
+        const int tap = tid / CPP, c8 = tid - tap * CPP;
+        const int c = c0 + c8 * 8;
+        const uint32_t off = c < d.C ? (uint32_t)((tap * d.C + c) * 2) : OOB_OFFSET;
+        *reinterpret_cast<u32x4 *>(&Wd[tap * HC + c8 * 8]) = __builtin_amdgcn_raw_buffer_load_b128(rsrc_dw, off, 0, 0);
+    }
+    if (tid < HC) Bd[tid] = c0 + tid < d.C ? d.bias[c0 + tid] : 0.f;
+
+    // ---- the 1x1 layer: reduction steps in ascending order into one accumulator per tile ---------------------
+#pragma unroll
+    for (int j = 0; j < MT; ++j) {
+        if ((wave + 4 * j) * 16 >= Mb) continue;         // wave-uniform
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            Acc acc;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[v] = 0.f;
+#pragma unroll
+            for (int s = 0; s < KS; ++s)
+                if (s < nsteps) acc = Mma<T, 16>::run(wf[i][s], xf[j][s], acc);
+            float v[4] = {acc[0] + bias4[i].x, acc[1] + bias4[i].y, acc[2] + bias4[i].z, acc[3] + bias4[i].w};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) v[t] = apply_act(v[t], e.act);
+            Pack<T, 4> o;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) from_f32(v[t], o.e[t]);
+            *reinterpret_cast<Pack<T, 4> *>(&Es[((wave + 4 * j) * 16 + frag_row) * ELD + i * 16 + 4 * (lane >> 4)]) = o;
+        }
+    }
+    __syncthreads();
+
+    // ---- the rows of the widened tensor this band owns, to memory, 16 bytes per thread ------------------------
+    T *ey = (T *)e.y;
+    for (int it = (own_lo - r_lo) * W * CPP + tid; it < (own_hi - r_lo) * W * CPP; it += 256) {
+        const int px = it / CPP, c8 = it - px * CPP;
+        const int c = c0 + c8 * 8;
+        if (c < e.K)
+            *reinterpret_cast<u32x4 *>(ey + (int64_t)(img * Min + px0 + px) * e.y_ct + e.y_coff + c) = *reinterpret_cast<const u32x4 *>(&Es[px * ELD + c8 * 8]);
+    }
+    // ---- the depthwise layer over the LDS copy ---------------------------------------------------------------
+    T *dy = (T *)d.y;
+    const int Mout = d.P * d.Q;
+    for (int it = tid; it < (p_hi - p_lo) * d.Q * CPP; it += 256) {
+        const int ol = it / CPP, c8 = it - ol * CPP;
+        const int c = c0 + c8 * 8;
+        const int pl = ol / d.Q;
+        const int p = p_lo + pl, q = ol - pl * d.Q;
+        float acc[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+#pragma unroll
+            for (int sx = 0; sx < 3; ++sx) {
+                const int ih = p * d.sh - 1 + r, iw = q * d.sw - 1 + sx;
+                const bool ok = ((uint32_t)ih < (uint32_t)d.H) & ((uint32_t)iw < (uint32_t)W);
+                const int ihc = min(max(ih, r_lo), r_hi), iwc = min(max(iw, 0), W - 1);
+                const Pack<T, 8> xv = *reinterpret_cast<const Pack<T, 8> *>(&Es[((ihc - r_lo) * W + iwc) * ELD + c8 * 8]);
+                const Pack<T, 8> wv = *reinterpret_cast<const Pack<T, 8> *>(&Wd[(r * 3 + sx) * HC + c8 * 8]);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[i] = ok ? fmaf(to_f32(xv.e[i]), to_f32(wv.e[i]), acc[i]) : acc[i];
+            }
+        if (c < d.C) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] = apply_act(acc[i] + Bd[c8 * 8 + i], d.act);
+            store_pack<T, 8>(dy + (int64_t)(img * Mout + p * d.Q + q) * d.y_ct + d.y_coff + c, acc);
+        }
+    }
+}
+
+// Launch shape of the fused pair: the kernel variant (pixels a band may read, by reduction depth) and the number of
+// row bands, chosen so that enough workgroups exist and a band's input rows fit the variant.  False: not fusable.
+static bool pwdw_plan(const OpArgs &pw, const OpArgs &dw, int *variant, int *bands) {
+    if (pw.kernel_id != K_IGEMM_64x16 || dw.kernel_id != K_DWCONV) return false;
+    if (dw.dtype != pw.dtype || (dw.dtype != MT_F16 && dw.dtype != MT_BF16)) return false;
+    if (pw.R != 1 || pw.S != 1 || pw.sh != 1 || pw.sw != 1 || pw.ph != 0 || pw.pw != 0 || pw.groups > 1) return false;
+    if (pw.split_k != 1 || pw.vec_a == 0 || pw.C % 8 != 0 || pw.x_ct != pw.C || pw.x_coff != 0 || pw.res_ct != 0) return false;
+    if (pw.K % 8 != 0 || pw.y_coff != 0 || pw.y_ct != pw.K) return false;
+    if (dw.R != 3 || dw.S != 3 || dw.ph != 1 || dw.pw != 1 || dw.sh < 1 || dw.sh > 2 || dw.vec != 8 || dw.C != pw.K) return false;
+    if (dw.N != pw.N || dw.H != pw.P || dw.W != pw.Q) return false;
+    const int steps = pw.k_pad / 32;
+    const int limit = steps <= 2 ? 512 : steps <= 4 ? 256 : steps <= 8 ? 64 : 0;     // pixels a band may read
+    *variant = steps <= 2 ? 0 : steps <= 4 ? 1 : 2;
+    if (limit == 0 || 3 * dw.W > limit) return false;
+    const int chunks = (pw.K + PWDW_HC - 1) / PWDW_HC;
+    const int by_count = (PWDW_WGS + pw.N * chunks - 1) / (pw.N * chunks);
+    const int by_work = (dw.P * dw.Q * (PWDW_HC / 8) + PWDW_ITEMS - 1) / PWDW_ITEMS;
+    int b = std::max(1, std::min(dw.P, std::max(by_count, by_work)));
+    for (;; ++b) {
+        const int PB = (dw.P + b - 1) / b;
+        if (std::min(dw.H, (PB - 1) * dw.sh + 3) * dw.W <= limit) {        // b <= P here: one output row per band always fits
+            *bands = (dw.P + PB - 1) / PB;                                  // no empty band
+            return true;
+        }
+    }
+}
+
+bool pwdw_fusable(const OpArgs &pw, const OpArgs &dw) {
+    int variant = 0, bands = 0;
+    return pwdw_plan(pw, dw, &variant, &bands);
+}
+
+int launch_pwdw(const OpArgs &pw, const OpArgs &dw, void *stream) {
+    hipStream_t st = (hipStream_t)stream;
+    int variant = 0, bands = 0;
+    if (!pwdw_plan(pw, dw, &variant, &bands)) return (int)hipErrorInvalidValue;
+    constexpr int HC = PWDW_HC;
+    const dim3 grid(pw.N * bands * ((pw.K + HC - 1) / HC)), block(256);
+    auto go = [&]<typename T>() {
+        if (variant == 0) hipLaunchKernelGGL((pwdw_kernel<T, 8, 2, HC>), grid, block, 0, st, pw, dw, bands);
+        else if (variant == 1) hipLaunchKernelGGL((pwdw_kernel<T, 4, 4, HC>), grid, block, 0, st, pw, dw, bands);
+        else hipLaunchKernelGGL((pwdw_kernel<T, 1, 8, HC>), grid, block, 0, st, pw, dw, bands);
+    };
+    if (pw.dtype == MT_F16) go.template operator()<f16>();
+    else go.template operator()<bf16>();
     return (int)hipGetLastError();
 }
 

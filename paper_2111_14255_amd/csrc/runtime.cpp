@@ -320,6 +320,7 @@ struct Tenant {
     std::vector<OpArgs> args;       // device pointers resolved; input/output patched per run
     std::vector<uint8_t> reads_input, res_input, writes_output;
     std::vector<uint8_t> fuse_next;  // operator i is a depthwise convolution that can run inside the launch of operator i + 1
+    std::vector<uint8_t> fuse_pwdw;  // operator i is a 1x1 convolution that can run inside the launch of the depthwise operator i + 1
 };
 
 struct StreamKey {
@@ -461,6 +462,17 @@ inline OpArgs patched(const Tenant &t, int op, const void *in, void *out) {
 
 int32_t dispatch_latency_us(mt_ctx *ctx, hipStream_t st, uint32_t *scratch, int n, float *us);
 
+// One issue item on its stream; returns a hipError_t as int.  An operator that runs inside its successor's launch
+// (fuse 1) is skipped here; the successor launches the pair (fuse 2: depthwise + 1x1, fuse 3: 1x1 + depthwise).
+int launch_item(const mt_ctx *ctx, const IssueItem &it, const void *const *inputs, void *const *outputs, hipStream_t st) {
+    if (it.fuse == 1) return 0;
+    const Tenant &t = *ctx->tenants[it.tenant];
+    const OpArgs a = patched(t, it.op, inputs[it.tenant], outputs[it.tenant]);
+    if (it.fuse == 2) return launch_dwpw(patched(t, it.op - 1, inputs[it.tenant], outputs[it.tenant]), a, st);
+    if (it.fuse == 3) return launch_pwdw(patched(t, it.op - 1, inputs[it.tenant], outputs[it.tenant]), a, st);
+    return launch_raw(a, st);
+}
+
 // Destroys every masked stream no schedule refers to, and the parked ones with them (the next masked streams are
 // timed again, so a slow queue slot that becomes free is parked again when it comes up).
 int32_t purge_idle_streams(mt_ctx *ctx) {
@@ -567,16 +579,8 @@ int32_t capture_slice_graphs(mt_ctx *ctx, mt_schedule *s, const void *const *inp
             HIP_TRY(hipStreamBeginCapture(stream, hipStreamCaptureModeRelaxed));
             int32_t rc = MT_OK;
             for (const IssueItem &it : sp.by_stream[sm]) {
-                if (it.fuse == 1) continue;
-                const Tenant &t = *ctx->tenants[it.tenant];
-                const OpArgs a = patched(t, it.op, inputs[it.tenant], outputs[it.tenant]);
-                if (it.fuse == 2) {
-                    const int e = launch_dwpw(patched(t, it.op - 1, inputs[it.tenant], outputs[it.tenant]), a, stream);
-                    if (e != 0) rc = fail(MT_ERR_HIP, std::string("fused launch: ") + hipGetErrorString((hipError_t)e));
-                } else {
-                    rc = launch_op(a, stream);
-                }
-                if (rc != MT_OK) break;
+                const int e = launch_item(ctx, it, inputs, outputs, stream);
+                if (e != 0) { rc = fail(MT_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString((hipError_t)e)); break; }
             }
             hipError_t e = hipStreamEndCapture(stream, &graph);
             if (rc != MT_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
@@ -605,19 +609,9 @@ int32_t issue_schedule(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, v
             launches += (int)sp.items.size();
         } else
         for (const IssueItem &it : sp.items) {
-            const Tenant &t = *ctx->tenants[it.tenant];
             ++launches;                              // counts operators issued, fused or not
-            if (it.fuse == 1) continue;              // runs inside the next operator's launch
-            OpArgs a = patched(t, it.op, inputs[it.tenant], outputs[it.tenant]);
-            int32_t rc = MT_OK;
-            if (it.fuse == 2) {
-                const OpArgs dw = patched(t, it.op - 1, inputs[it.tenant], outputs[it.tenant]);
-                const int e = launch_dwpw(dw, a, s->stream_at[st][it.stream]);
-                if (e != 0) rc = fail(MT_ERR_HIP, std::string("fused launch: ") + hipGetErrorString((hipError_t)e));
-            } else {
-                rc = launch_op(a, s->stream_at[st][it.stream]);
-            }
-            if (rc != MT_OK) return rc;
+            const int e = launch_item(ctx, it, inputs, outputs, s->stream_at[st][it.stream]);
+            if (e != 0) return fail(MT_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString((hipError_t)e));
             if ((s->flags & MT_SCHED_TIME_FIRST_OP) && it.op == 0) HIP_TRY(hipEventRecord(ctx->ev_first[it.tenant], s->stream_at[st][it.stream]));
         }
         for (int sm : sp.streams) {
@@ -656,11 +650,7 @@ void issue_worker(mt_ctx *ctx, int w) {
                 hipError_t e = wait_for_previous_stage(ctx, s, st, w);
                 for (const IssueItem &it : sp.by_stream[w]) {
                     if (e != hipSuccess) break;
-                    const Tenant &t = *ctx->tenants[it.tenant];
-                    OpArgs a = patched(t, it.op, pool.inputs[it.tenant], pool.outputs[it.tenant]);
-                    if (it.fuse == 1) continue;
-                    int rc = it.fuse == 2 ? launch_dwpw(patched(t, it.op - 1, pool.inputs[it.tenant], pool.outputs[it.tenant]), a, s->stream_at[st][w])
-                                          : launch_raw(a, s->stream_at[st][w]);
+                    const int rc = launch_item(ctx, it, pool.inputs, pool.outputs, s->stream_at[st][w]);
                     if (rc != 0) e = (hipError_t)rc;
                 }
                 if (e == hipSuccess) e = hipEventRecord(ctx->ev_done[st][w], s->stream_at[st][w]);
@@ -1085,6 +1075,18 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
             dwpw_fusable(t->args[i], t->args[i + 1]))
             t->fuse_next[i] = 1;
     }
+    // 1x1 convolution followed by the depthwise convolution that alone reads it, on a small map
+    t->fuse_pwdw.assign(nops, 0);
+    for (size_t i = 0; i + 1 < nops; ++i) {
+        const mt_op_desc &d0 = t->model.ops[i].d, &d1 = t->model.ops[i + 1].d;
+        if (d0.kind != MT_CONV || d1.kind != MT_DWCONV || d1.in_tensor != d0.out_tensor || t->writes_output[i] ||
+            !pwdw_fusable(t->args[i], t->args[i + 1]))
+            continue;
+        bool sole_writer = true;                     // no other operator writes channels of the widened tensor
+        for (size_t j = 0; j < nops; ++j)
+            if (j != i && t->model.ops[j].d.out_tensor == d0.out_tensor) sole_writer = false;
+        if (sole_writer) t->fuse_pwdw[i] = 1;
+    }
     HIP_TRY(hipDeviceSynchronize());
     guard.armed = false;
     ctx->tenants.push_back(std::move(t));
@@ -1179,19 +1181,27 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
         const int conc = stage_concurrency ? stage_concurrency[st] : n_tenants;
         StagePlan &sp = s->stages[st];
         sp.items = issue_order(n_tenants, &slices[(size_t)st * n_tenants * 2], conc, order);
-        // On request, a depthwise convolution whose consumer is issued in the same stage runs inside the consumer's launch.
-        if (flags & MT_SCHED_FUSE_DEPTHWISE)
+        // On request, two neighbouring operators issued in the same stage run as one launch.
+        for (int pass = 0; pass < 2; ++pass) {       // 1x1 + depthwise pairs first: a depthwise operator joins one neighbour only
+            const int want = pass == 0 ? MT_SCHED_FUSE_EXPAND : MT_SCHED_FUSE_DEPTHWISE;
+            if (!(flags & want)) continue;
             for (size_t k = 0; k < sp.items.size(); ++k) {
                 IssueItem &it = sp.items[k];
                 const Tenant &tt = *ctx->tenants[it.tenant];
                 const int end = slices[((size_t)st * n_tenants + it.tenant) * 2 + 1];
-                if (it.op + 1 < end && tt.fuse_next[it.op]) {
-                    it.fuse = 1;
-                    ++s->n_fused;
-                    for (size_t k2 = k + 1; k2 < sp.items.size(); ++k2)
-                        if (sp.items[k2].tenant == it.tenant && sp.items[k2].op == it.op + 1) { sp.items[k2].fuse = 2; break; }
-                }
+                const bool can = pass == 0 ? tt.fuse_pwdw[it.op] != 0 : tt.fuse_next[it.op] != 0;
+                if (it.fuse != 0 || it.op + 1 >= end || !can) continue;
+                for (size_t k2 = k + 1; k2 < sp.items.size(); ++k2)
+                    if (sp.items[k2].tenant == it.tenant && sp.items[k2].op == it.op + 1) {
+                        if (sp.items[k2].fuse == 0) {
+                            sp.items[k2].fuse = pass == 0 ? 3 : 2;
+                            it.fuse = 1;
+                            ++s->n_fused;
+                        }
+                        break;
+                    }
             }
+        }
         for (const IssueItem &it : sp.items)
             if (std::find(sp.streams.begin(), sp.streams.end(), it.stream) == sp.streams.end()) sp.streams.push_back(it.stream);
         std::sort(sp.streams.begin(), sp.streams.end());

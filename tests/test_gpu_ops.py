@@ -269,3 +269,63 @@ def test_fused_depthwise_pointwise_equals_separate_launches(name, n, h, w, cin, 
         assert_close(dw_fused.reshape(n, -1), tensors[d].reshape(n, -1), dtype, name + " depthwise output")
     finally:
         mix.close()
+
+
+# ---- 1x1 convolution fused with the depthwise convolution that reads it (small maps) ---------------------------------
+EXPAND_BLOCKS = [
+    # name, n, h, w, c_in, hidden, c_out, stride, residual, fused
+    ("c64_h384_14x14", 1, 14, 14, 64, 384, 64, 1, True, True),
+    ("c96_h576_14x14_s2", 1, 14, 14, 96, 576, 160, 2, False, True),
+    ("c160_h960_7x7", 1, 7, 7, 160, 960, 320, 1, False, True),
+    ("c32_h192_7x9_two_images", 2, 7, 9, 32, 192, 32, 1, True, True),
+    ("c24_h144_13x13_partial_chunk", 1, 13, 13, 24, 144, 24, 1, True, True),
+    ("c128_h64_16x16_largest_map", 1, 16, 16, 128, 64, 32, 1, False, True),
+    ("c8_h8_2x2_map", 3, 2, 2, 8, 8, 8, 1, True, True),
+    ("c8_h8_1x1_map_matrix_vector_form", 3, 1, 1, 8, 8, 8, 1, True, False),
+    ("c256_h64_8x8_deep_reduction", 1, 8, 8, 256, 64, 16, 2, False, True),
+    ("c32_h192_28x28_four_bands", 1, 28, 28, 32, 192, 32, 1, True, True),
+    ("c32_h192_28x28_s2", 1, 28, 28, 32, 192, 64, 2, False, True),
+    ("c24_h144_56x56_wide_rows", 1, 56, 56, 24, 144, 24, 1, True, True),
+    ("c24_h144_57x55_s2_odd", 1, 57, 55, 24, 144, 32, 2, False, True),
+    ("c136_h64_12x12_deep_reduction_many_bands", 1, 12, 12, 136, 64, 16, 1, False, True),
+    ("c160_h64_8x32_rows_too_wide", 1, 8, 32, 160, 64, 16, 1, False, False),
+    ("c264_h64_6x6_reduction_too_deep", 1, 6, 6, 264, 64, 16, 1, False, False),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("name,n,h,w,cin,hid,cout,stride,resid,fusable", EXPAND_BLOCKS, ids=[c[0] for c in EXPAND_BLOCKS])
+def test_fused_pointwise_depthwise_equals_separate_launches(name, n, h, w, cin, hid, cout, stride, resid, fusable, dtype):
+    g = GraphBuilder("blk", dtype, n, h, w, cin)
+    pre = g.conv(0, cin, 1, act="none", bn=True)          # the block input is an arena tensor, as inside a network
+    e = g.conv(pre, hid, 1, act="relu6", bn=True)
+    d = g.dwconv(e, 3, stride, 1, act="relu6", bn=True)
+    g.conv(d, cout, 1, act="none", bn=True, res=pre if resid and stride == 1 and cout == cin else -1)
+    spec = g.done()
+    print("case", name, dtype, flush=True)
+    mix = Mix([spec], seed=23)
+    try:
+        ctx = mix.ctx
+        eshape = (n,) + tuple(spec.ops[1].out_shape)
+        dshape = (n,) + tuple(spec.ops[2].out_shape)
+        fused, tm = mix.run(ctx.sequential(flags=B.MT_SCHED_FUSE_EXPAND))
+        assert tm["n_fused"] == (1 if fusable else 0), tm
+        assert tm["n_launches"] == 4
+        e_fused, d_fused = ctx.read_tensor(0, e, eshape), ctx.read_tensor(0, d, dshape)
+        plain, tm = mix.run(ctx.sequential())
+        assert tm["n_fused"] == 0
+        e_plain, d_plain = ctx.read_tensor(0, e, eshape), ctx.read_tensor(0, d, dshape)
+        both, tm = mix.run(ctx.sequential(flags=B.MT_SCHED_FUSE_EXPAND | B.MT_SCHED_FUSE_DEPTHWISE))
+        assert tm["n_fused"] >= (1 if fusable else 0)
+        split, tm = mix.run(ctx.schedule([[2]], 2, flags=B.MT_SCHED_FUSE_EXPAND))   # a stage boundary inside the pair: no fusion
+        assert tm["n_fused"] == 0
+        for other in (plain, both, split):
+            assert np.array_equal(fused[0].view(np.uint32), other[0].view(np.uint32))
+        assert np.array_equal(e_fused.view(np.uint32), e_plain.view(np.uint32))        # both intermediate tensors stay valid
+        assert np.array_equal(d_fused.view(np.uint32), d_plain.view(np.uint32))
+        ref, tensors = OF.forward(spec, OF.prepare_params(spec, mix.raw[0]), mix.x[0], keep=True)
+        assert_close(fused[0], ref, dtype, name)
+        assert_close(e_fused.reshape(n, -1), tensors[e].reshape(n, -1), dtype, name + " widened tensor")
+        assert_close(d_fused.reshape(n, -1), tensors[d].reshape(n, -1), dtype, name + " depthwise output")
+    finally:
+        mix.close()
