@@ -167,8 +167,9 @@ def main():
     sched_sg = ctx.schedule(rho, cfg.n_stages, cu_share=shares, flags=B.MT_SCHED_STREAM_GRAPHS)
     results["searched+cu_share+stream_graphs"] = time_schedule(ctx, torch, sched_sg, inputs, outputs, args.warmup, args.steps)
     results["searched+cu_share+stream_graphs"].update({"pointers": rho, "cu_share": shares})
-    # the same with neighbouring 1x1 + depthwise operators of a stage issued as one launch (identical output bits)
-    FE = B.MT_SCHED_FUSE_EXPAND
+    # the same with the 1x1 + depthwise and convolution + 2x2 max pooling pairs of a stage issued as one launch each
+    # (identical output bits)
+    FE = B.MT_SCHED_FUSE_EXPAND | B.MT_SCHED_FUSE_POOL
     seq_f = ctx.sequential(flags=FE)
     results["sequential+fused_pairs"] = time_schedule(ctx, torch, seq_f, inputs, outputs, args.warmup, args.steps)
     t0 = time.perf_counter()

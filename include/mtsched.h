@@ -137,7 +137,7 @@ typedef struct mt_timings {
     int32_t n_stages;
     float stage_ms[MT_MAX_STAGES];
     float first_op_done_ms[MT_MAX_TENANTS];
-    int32_t n_fused;       /* operators (of the n_launches issued) that ran inside the next operator's launch */
+    int32_t n_fused;       /* operators (of the n_launches issued) that ran inside a neighbouring operator's launch */
 } mt_timings;
 
 /* ---- error reporting ---------------------------------------------------------------- */
@@ -237,6 +237,12 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
  * the GPU: 15 pairs fused, 0.28 -> 0.25 ms per pass.  With MT_SCHED_FUSE_DEPTHWISE also set, a depthwise operator
  * joins its producer when it can and its consumer otherwise. */
 #define MT_SCHED_FUSE_EXPAND 64
+/* MT_SCHED_FUSE_POOL: a convolution on the matrix cores (fp16 / bf16, no residual, output channels a multiple of 8, even
+ * output height and width) whose output only the next operator reads, a 2x2 max pooling with stride 2 issued in the
+ * same stage, applies the pooling in its epilogue: the convolution walks its output pixels window by window and
+ * writes the pooled tensor only.  The pooled tensor keeps its bits (activation and rounding are monotonic, so the
+ * maximum commutes with them); the convolution's own output tensor is NOT written by such a launch. */
+#define MT_SCHED_FUSE_POOL 128
 /* MT_SCHED_STREAM_GRAPHS: the launches of one stream in one stage are captured (on that stream, on the first run
  * and again when a buffer pointer changes) into a graph of their own and replayed on that stream: the short gaps
  * between kernels of a replayed graph, with CU shares still in force (the replay runs on the masked stream) and with

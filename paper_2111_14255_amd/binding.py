@@ -29,6 +29,7 @@ MT_SCHED_TIME_FIRST_OP = 4
 MT_SCHED_SHARE_PER_STAGE = 8
 MT_SCHED_FUSE_DEPTHWISE = 16
 MT_SCHED_FUSE_EXPAND = 64
+MT_SCHED_FUSE_POOL = 128
 MT_SCHED_STREAM_GRAPHS = 32
 MT_SEARCH_COORDINATE, MT_SEARCH_RANDOM = 0, 1
 

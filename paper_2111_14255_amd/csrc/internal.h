@@ -15,7 +15,7 @@ int32_t fail(int32_t code, const std::string &msg);
 // ---- scheduling layer (host only) ------------------------------------------------------
 struct IssueItem {
     int32_t stream, tenant, op;
-    int32_t fuse = 0;      // runtime only: 1 = issued as part of the next operator's launch, 2 / 3 = launches the pair (op - 1, op): depthwise + 1x1 / 1x1 + depthwise
+    int32_t fuse = 0;      // runtime only: 1 = issued as part of a neighbour's launch, 2 / 3 = launches the pair (op - 1, op): depthwise + 1x1 / 1x1 + depthwise, 4 = convolution launched with the pooling operator op + 1 in its epilogue (that operator then carries 1)
 };
 int32_t validate_pointers(int32_t n_tenants, const int32_t *lens, int32_t n_stages, const int32_t *pointers);
 void expand_pointers(int32_t n_tenants, const int32_t *lens, int32_t n_stages, const int32_t *pointers, int32_t *slices);
@@ -77,6 +77,7 @@ struct OpArgs {
     int32_t n_pad;               // packed weight rows (multiple of the channel tile)
     int32_t split_k;
     int32_t wk;                  // wave groups that share an output tile (64x64 tile only): 1 or 2
+    int32_t pool2;               // 1: the epilogue applies a 2x2 / stride-2 max pooling; pixels are then walked quad by quad and y is the pooled tensor
     // Exact unsigned division by Q and by P*Q without a divide (multiply-high, two shifts): n / d =
     // (t + ((n - t) >> s1)) >> s2 with t = mulhi(m, n); filled by make_divisor().
     uint32_t divq_m, divq_s1, divq_s2, divpq_m, divpq_s1, divpq_s2;

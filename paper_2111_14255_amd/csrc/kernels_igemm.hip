@@ -164,12 +164,21 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
         const uint32_t mm = xrow_ok[i] ? (uint32_t)m : 0u;
         // pixel index -> (image, row, column) by multiply-high divisions: a divide instruction sequence per row is a
         // large part of the prologue of a short, latency-bound launch
-        const uint32_t t1 = __umulhi(a.divpq_m, mm);
-        const int n = (int)((t1 + ((mm - t1) >> a.divpq_s1)) >> a.divpq_s2);
-        const uint32_t rem = mm - (uint32_t)n * (uint32_t)(a.P * a.Q);
+        // With the pooled epilogue the pixel index walks 2x2 quads (quad index * 4 + position inside the quad) and the
+        // divisors are those of the pooled map, so four consecutive tile rows are one pooling window.
+        const uint32_t mq = a.pool2 ? mm >> 2 : mm;
+        const uint32_t pqd = a.pool2 ? (uint32_t)((a.P >> 1) * (a.Q >> 1)) : (uint32_t)(a.P * a.Q);
+        const uint32_t qd = a.pool2 ? (uint32_t)(a.Q >> 1) : (uint32_t)a.Q;
+        const uint32_t t1 = __umulhi(a.divpq_m, mq);
+        const int n = (int)((t1 + ((mq - t1) >> a.divpq_s1)) >> a.divpq_s2);
+        const uint32_t rem = mq - (uint32_t)n * pqd;
         const uint32_t t2 = __umulhi(a.divq_m, rem);
-        const int p = (int)((t2 + ((rem - t2) >> a.divq_s1)) >> a.divq_s2);
-        const int q = (int)(rem - (uint32_t)p * (uint32_t)a.Q);
+        int p = (int)((t2 + ((rem - t2) >> a.divq_s1)) >> a.divq_s2);
+        int q = (int)(rem - (uint32_t)p * qd);
+        if (a.pool2) {
+            p = 2 * p + (int)((mm >> 1) & 1u);
+            q = 2 * q + (int)(mm & 1u);
+        }
         img_off[i] = n * a.H * a.W * XS;
         ih0[i] = p * a.sh - a.ph;
         iw0[i] = q * a.sw - a.pw;
@@ -504,6 +513,29 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
         }
         __syncthreads();
         constexpr int CPR = BN / 8;                       // 8-channel chunks per pixel row of the tile
+        if (a.pool2) {
+            // Four consecutive tile rows are one 2x2 window (see the pixel walk above) and the pooled pixel index is the
+            // quad index.  Activation and rounding are monotonic, so the maximum is taken before them on fp32 values.
+            for (int c = tid; c < (BM / 4) * CPR; c += NT) {
+                const int r4 = c / CPR, col = (c % CPR) * 8;
+                const int m = m0 + r4 * 4, k = n0 + col;
+                if (m >= M || k >= a.K) continue;
+                float v[8];
+#pragma unroll
+                for (int t = 0; t < 8; ++t) v[t] = -INFINITY;
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const float4 lo = *reinterpret_cast<const float4 *>(&et[(r4 * 4 + rr) * ELD + col]);
+                    const float4 hi = *reinterpret_cast<const float4 *>(&et[(r4 * 4 + rr) * ELD + col + 4]);
+                    v[0] = fmaxf(v[0], lo.x); v[1] = fmaxf(v[1], lo.y); v[2] = fmaxf(v[2], lo.z); v[3] = fmaxf(v[3], lo.w);
+                    v[4] = fmaxf(v[4], hi.x); v[5] = fmaxf(v[5], hi.y); v[6] = fmaxf(v[6], hi.z); v[7] = fmaxf(v[7], hi.w);
+                }
+#pragma unroll
+                for (int t = 0; t < 8; ++t) v[t] = apply_act(v[t], a.act);
+                store_pack<T, 8>(y + (int64_t)(m >> 2) * a.y_ct + a.y_coff + k, v);
+            }
+            return;
+        }
         for (int c = tid; c < BM * CPR; c += NT) {
             const int row = c / CPR, col = (c % CPR) * 8;
             const int m = m0 + row, k = n0 + col;

@@ -321,6 +321,8 @@ struct Tenant {
     std::vector<uint8_t> reads_input, res_input, writes_output;
     std::vector<uint8_t> fuse_next;  // operator i is a depthwise convolution that can run inside the launch of operator i + 1
     std::vector<uint8_t> fuse_pwdw;  // operator i is a 1x1 convolution that can run inside the launch of the depthwise operator i + 1
+    std::vector<uint8_t> fuse_pool;  // operator i is a convolution whose epilogue can apply the 2x2 max pooling operator i + 1
+    std::vector<OpArgs> pool_args;   // its arguments for that form (pooled output tensor, quad pixel walk)
 };
 
 struct StreamKey {
@@ -463,13 +465,20 @@ inline OpArgs patched(const Tenant &t, int op, const void *in, void *out) {
 int32_t dispatch_latency_us(mt_ctx *ctx, hipStream_t st, uint32_t *scratch, int n, float *us);
 
 // One issue item on its stream; returns a hipError_t as int.  An operator that runs inside its successor's launch
-// (fuse 1) is skipped here; the successor launches the pair (fuse 2: depthwise + 1x1, fuse 3: 1x1 + depthwise).
+// (fuse 1) is skipped here; its neighbour launches the pair (fuse 2: depthwise + 1x1, fuse 3: 1x1 + depthwise, both from
+// the second operator; fuse 4: convolution with the next operator, a 2x2 max pooling, in its epilogue).
 int launch_item(const mt_ctx *ctx, const IssueItem &it, const void *const *inputs, void *const *outputs, hipStream_t st) {
     if (it.fuse == 1) return 0;
     const Tenant &t = *ctx->tenants[it.tenant];
     const OpArgs a = patched(t, it.op, inputs[it.tenant], outputs[it.tenant]);
     if (it.fuse == 2) return launch_dwpw(patched(t, it.op - 1, inputs[it.tenant], outputs[it.tenant]), a, st);
     if (it.fuse == 3) return launch_pwdw(patched(t, it.op - 1, inputs[it.tenant], outputs[it.tenant]), a, st);
+    if (it.fuse == 4) {
+        OpArgs b = t.pool_args[it.op];
+        if (t.reads_input[it.op]) b.x = inputs[it.tenant];
+        if (t.writes_output[it.op + 1]) b.y = outputs[it.tenant];
+        return launch_raw(b, st);
+    }
     return launch_raw(a, st);
 }
 
@@ -1087,6 +1096,31 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
             if (j != i && t->model.ops[j].d.out_tensor == d0.out_tensor) sole_writer = false;
         if (sole_writer) t->fuse_pwdw[i] = 1;
     }
+    // convolution followed by the 2x2 / stride-2 max pooling that alone reads it: candidates for the pooled epilogue
+    t->fuse_pool.assign(nops, 0);
+    t->pool_args.assign(nops, OpArgs{});
+    for (size_t i = 0; i + 1 < nops; ++i) {
+        const mt_op_desc &d0 = t->model.ops[i].d, &d1 = t->model.ops[i + 1].d;
+        const OpArgs &a0 = t->args[i], &a1 = t->args[i + 1];
+        if (d0.kind != MT_CONV || d1.kind != MT_MAXPOOL || d1.in_tensor != d0.out_tensor || t->writes_output[i]) continue;
+        if (!is_gemm_kernel(a0.kernel_id) || a0.kernel_id == K_GEMV || a0.groups > 1 || a0.res_ct != 0 || d0.res_tensor >= 0) continue;
+        if (a0.K % 8 != 0 || a0.y_coff != 0 || a0.y_ct != a0.K || a0.P % 2 != 0 || a0.Q % 2 != 0) continue;
+        if (a1.R != 2 || a1.S != 2 || a1.sh != 2 || a1.sw != 2 || a1.ph != 0 || a1.pw != 0 || a1.vec != 8) continue;
+        bool only = true;                            // nothing else reads or writes the convolution's output tensor
+        for (size_t j = 0; j < nops; ++j) {
+            const mt_op_desc &dj = t->model.ops[j].d;
+            if (j != i && dj.out_tensor == d0.out_tensor) only = false;
+            if (j != i + 1 && (dj.in_tensor == d0.out_tensor || dj.res_tensor == d0.out_tensor)) only = false;
+        }
+        if (!only) continue;
+        OpArgs b = a0;
+        b.pool2 = 1;
+        b.y = a1.y; b.y_ct = a1.y_ct; b.y_coff = a1.y_coff;
+        make_divisor((uint32_t)(b.Q / 2), b.divq_m, b.divq_s1, b.divq_s2);
+        make_divisor((uint32_t)(b.P / 2) * (uint32_t)(b.Q / 2), b.divpq_m, b.divpq_s1, b.divpq_s2);
+        t->pool_args[i] = b;
+        t->fuse_pool[i] = 1;
+    }
     HIP_TRY(hipDeviceSynchronize());
     guard.armed = false;
     ctx->tenants.push_back(std::move(t));
@@ -1182,20 +1216,21 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
         StagePlan &sp = s->stages[st];
         sp.items = issue_order(n_tenants, &slices[(size_t)st * n_tenants * 2], conc, order);
         // On request, two neighbouring operators issued in the same stage run as one launch.
-        for (int pass = 0; pass < 2; ++pass) {       // 1x1 + depthwise pairs first: a depthwise operator joins one neighbour only
-            const int want = pass == 0 ? MT_SCHED_FUSE_EXPAND : MT_SCHED_FUSE_DEPTHWISE;
+        for (int pass = 0; pass < 3; ++pass) {       // 1x1 + depthwise pairs before depthwise + 1x1: a depthwise operator joins one neighbour only
+            const int want = pass == 0 ? MT_SCHED_FUSE_EXPAND : pass == 1 ? MT_SCHED_FUSE_DEPTHWISE : MT_SCHED_FUSE_POOL;
             if (!(flags & want)) continue;
             for (size_t k = 0; k < sp.items.size(); ++k) {
                 IssueItem &it = sp.items[k];
                 const Tenant &tt = *ctx->tenants[it.tenant];
                 const int end = slices[((size_t)st * n_tenants + it.tenant) * 2 + 1];
-                const bool can = pass == 0 ? tt.fuse_pwdw[it.op] != 0 : tt.fuse_next[it.op] != 0;
+                const bool can = pass == 0 ? tt.fuse_pwdw[it.op] != 0 : pass == 1 ? tt.fuse_next[it.op] != 0 : tt.fuse_pool[it.op] != 0;
                 if (it.fuse != 0 || it.op + 1 >= end || !can) continue;
                 for (size_t k2 = k + 1; k2 < sp.items.size(); ++k2)
                     if (sp.items[k2].tenant == it.tenant && sp.items[k2].op == it.op + 1) {
                         if (sp.items[k2].fuse == 0) {
-                            sp.items[k2].fuse = pass == 0 ? 3 : 2;
-                            it.fuse = 1;
+                            // the absorbed operator is skipped; the other one launches the pair
+                            sp.items[k2].fuse = pass == 0 ? 3 : pass == 1 ? 2 : 1;
+                            it.fuse = pass == 2 ? 4 : 1;
                             ++s->n_fused;
                         }
                         break;

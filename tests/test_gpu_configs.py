@@ -63,9 +63,9 @@ def test_cfg2_r18_vgg16_mbv2_fp16():
         lambda ctx, lens: ctx.schedule(even_split(lens, 4), 4, concurrency=[2, 1, 3, 2], label="mixed-concurrency"),
         lambda ctx, lens: ctx.schedule(even_split(lens, 3), 3, cu_share=[64, 128, 64], label="cu-shares"),
         lambda ctx, lens: ctx.all_concurrent(flags=B.MT_SCHED_FUSE_DEPTHWISE),
-        lambda ctx, lens: ctx.all_concurrent(flags=B.MT_SCHED_FUSE_EXPAND | B.MT_SCHED_PARALLEL_ISSUE),
+        lambda ctx, lens: ctx.all_concurrent(flags=B.MT_SCHED_FUSE_EXPAND | B.MT_SCHED_FUSE_POOL | B.MT_SCHED_PARALLEL_ISSUE),
         lambda ctx, lens: ctx.schedule(even_split(lens, 4), 4, cu_share=[64, 64, 128], flags=B.MT_SCHED_FUSE_EXPAND | B.MT_SCHED_FUSE_DEPTHWISE, label="fused-pairs"),
-        lambda ctx, lens: ctx.schedule(even_split(lens, 2), 2, flags=B.MT_SCHED_FUSE_EXPAND | B.MT_SCHED_STREAM_GRAPHS, label="graph"),
+        lambda ctx, lens: ctx.schedule(even_split(lens, 2), 2, flags=B.MT_SCHED_FUSE_EXPAND | B.MT_SCHED_FUSE_POOL | B.MT_SCHED_STREAM_GRAPHS, label="graph"),
         lambda ctx, lens: ctx.schedule(even_split(lens, 3), 3, cu_share=[64, 128, 64], flags=B.MT_SCHED_STREAM_GRAPHS, label="graph"),
         lambda ctx, lens: ctx.schedule([[] for _ in lens], 1, flags=B.MT_SCHED_STREAM_GRAPHS | B.MT_SCHED_FUSE_DEPTHWISE, label="graph"),
         lambda ctx, lens: ctx.schedule(even_split(lens, 3), 3, cu_share=[[64, 128, 64], [0, 0, 0], [128, 64, 64]], label="per-stage-shares"),
@@ -81,7 +81,7 @@ def test_cfg4_unbalanced_bf16():
 
 
 def test_cfg3_batch8_fp16():
-    mix = check_config("cfg3", [lambda ctx, lens: ctx.all_concurrent(flags=B.MT_SCHED_FUSE_EXPAND)])     # fused pairs at batch 8
+    mix = check_config("cfg3", [lambda ctx, lens: ctx.all_concurrent(flags=B.MT_SCHED_FUSE_EXPAND | B.MT_SCHED_FUSE_POOL)])     # fused pairs at batch 8
     mix.close()
 
 

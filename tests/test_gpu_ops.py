@@ -329,3 +329,56 @@ def test_fused_pointwise_depthwise_equals_separate_launches(name, n, h, w, cin, 
         assert_close(d_fused.reshape(n, -1), tensors[d].reshape(n, -1), dtype, name + " depthwise output")
     finally:
         mix.close()
+
+
+# ---- 2x2 max pooling applied in the epilogue of the convolution that feeds it ---------------------------------------
+POOL_BLOCKS = [
+    # name (starts with the kernel expected), n, h, w, c_in, c_out, window, stride, pad, act, fusable
+    ("igemm_64x16_16x16", 1, 16, 16, 64, 64, 3, 1, 1, "relu", True),
+    ("igemm_64x64_two_wave_groups_56x56", 1, 56, 56, 128, 128, 3, 1, 1, "relu", True),
+    ("igemm_64x64_split_14x14_c512", 1, 14, 14, 512, 512, 3, 1, 1, "relu", True),
+    ("igemm_128x64_batch4_56x56", 4, 56, 56, 128, 256, 3, 1, 1, "relu6", True),
+    ("igemm_128x128_batch8_112x112", 8, 112, 112, 64, 128, 3, 1, 1, "relu", True),
+    ("ragged_6x10_c24_k40", 3, 6, 10, 24, 40, 3, 1, 1, "none", True),
+    ("pointwise_stride2_conv", 2, 20, 12, 32, 72, 1, 2, 0, "relu", True),
+    ("first_layer_c3_element_gather", 1, 32, 32, 3, 64, 3, 1, 1, "relu", True),
+    ("odd_map_15x15_not_fused", 1, 15, 15, 64, 64, 3, 1, 1, "relu", False),
+    ("k_not_multiple_of_8_not_fused", 1, 16, 16, 64, 36, 3, 1, 1, "relu", False),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("name,n,h,w,cin,cout,win,stride,pad,act,fusable", POOL_BLOCKS, ids=[c[0] for c in POOL_BLOCKS])
+def test_pooling_in_the_convolution_epilogue_equals_separate_launches(name, n, h, w, cin, cout, win, stride, pad, act, fusable, dtype):
+    g = GraphBuilder("blk", dtype, n, h, w, cin)
+    c = g.conv(0, cout, win, stride, pad, act=act, bn=True)
+    pl = g.maxpool(c, 2, 2, 0)
+    g.conv(pl, 16, 1, act="none", bn=True)
+    spec = g.done()
+    print("case", name, dtype, flush=True)
+    mix = Mix([spec], seed=29)
+    try:
+        ctx = mix.ctx
+        if name.startswith("igemm_"):
+            kname = B.load().mt_kernel_name(ctx.op_info(0, 0).kernel_id).decode()
+            assert name.startswith(kname), kname
+        if "split" in name:
+            assert ctx.op_info(0, 0).split_k > 1
+        pshape = (n,) + tuple(spec.ops[1].out_shape)
+        fused, tm = mix.run(ctx.sequential(flags=B.MT_SCHED_FUSE_POOL))
+        assert tm["n_fused"] == (1 if fusable else 0), tm
+        assert tm["n_launches"] == 3
+        p_fused = ctx.read_tensor(0, pl, pshape)
+        plain, tm = mix.run(ctx.sequential())
+        assert tm["n_fused"] == 0
+        p_plain = ctx.read_tensor(0, pl, pshape)
+        split, tm = mix.run(ctx.schedule([[1]], 2, flags=B.MT_SCHED_FUSE_POOL))     # a stage boundary inside the pair: no fusion
+        assert tm["n_fused"] == 0
+        assert np.array_equal(fused[0].view(np.uint32), plain[0].view(np.uint32))
+        assert np.array_equal(fused[0].view(np.uint32), split[0].view(np.uint32))
+        assert np.array_equal(p_fused.view(np.uint32), p_plain.view(np.uint32))
+        ref, tensors = OF.forward(spec, OF.prepare_params(spec, mix.raw[0]), mix.x[0], keep=True)
+        assert_close(fused[0], ref, dtype, name)
+        assert_close(p_fused.reshape(n, -1), tensors[pl].reshape(n, -1), dtype, name + " pooled tensor")
+    finally:
+        mix.close()
