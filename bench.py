@@ -106,9 +106,9 @@ def main():
               "by bin-packing, see DESIGN.md", file=sys.stderr)
         sys.exit(2)
 
+    from paper_2111_14255_amd import api, binding as B     # first: sets the runtime's environment before HIP initialises
     import torch
     from synth import configs, weights
-    from paper_2111_14255_amd import api, binding as B
 
     cfg = configs.CONFIGS[args.config]
     specs = cfg.models()
@@ -172,16 +172,19 @@ def main():
     FE = B.MT_SCHED_FUSE_EXPAND | B.MT_SCHED_FUSE_POOL
     seq_f = ctx.sequential(flags=FE)
     results["sequential+fused_pairs"] = time_schedule(ctx, torch, seq_f, inputs, outputs, args.warmup, args.steps)
+    # searched in the mode it is deployed in (one issuing thread per stream), wave priorities as the last coordinates
     t0 = time.perf_counter()
-    rho_f, cost, records, shares_f = ctx.search(inputs, outputs, cfg.n_stages, rounds=args.search_rounds,
-                                                candidates=args.search_candidates, runs=7, warmup=1, seed=cfg.seed,
-                                                cu_share_rounds=2, flags=FE)
+    rho_f, cost, records, shares_f, prio_f = ctx.search(inputs, outputs, cfg.n_stages, rounds=args.search_rounds,
+                                                        candidates=args.search_candidates, runs=7, warmup=1, seed=cfg.seed,
+                                                        cu_share_rounds=2, wave_priority_rounds=2,
+                                                        flags=FE | B.MT_SCHED_PARALLEL_ISSUE)
     search_s = time.perf_counter() - t0
     for extra, suffix in ((0, ""), (B.MT_SCHED_PARALLEL_ISSUE, "+parallel_issue")):
-        sf = ctx.schedule(rho_f, cfg.n_stages, cu_share=shares_f, flags=FE | extra)
-        key = "searched+cu_share+fused_pairs" + suffix
+        sf = ctx.schedule(rho_f, cfg.n_stages, cu_share=shares_f, flags=FE | extra, wave_priority=prio_f)
+        key = "searched+cu_share+priority+fused_pairs" + suffix
         results[key] = time_schedule(ctx, torch, sf, inputs, outputs, args.warmup, args.steps)
-        results[key].update({"pointers": rho_f, "cu_share": shares_f, "search_seconds": search_s, "search_evaluations": len(records)})
+        results[key].update({"pointers": rho_f, "cu_share": shares_f, "wave_priority": prio_f, "search_seconds": search_s,
+                             "search_evaluations": len(records)})
     for k, r in results.items():
         base = results["sequential" + ("+graph" if k.endswith("+graph") else "+fused_pairs" if "+fused_pairs" in k else "")]
         r["img_per_s"] = images / (r["wall_ms_per_step"] * 1e-3)

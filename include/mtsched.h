@@ -243,6 +243,12 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
  * writes the pooled tensor only.  The pooled tensor keeps its bits (activation and rounding are monotonic, so the
  * maximum commutes with them); the convolution's own output tensor is NOT written by such a launch. */
 #define MT_SCHED_FUSE_POOL 128
+/* MT_SCHED_PRIORITIZE_SHORT: the waves of short, latency-bound kernels (64x16-tile convolutions, depthwise, pooling,
+ * normalisation, add, small matrix-vector layers, fused pairs of them) raise their issue priority on the SIMD to the
+ * maximum; long kernels keep the default.  A short kernel of one tenant that shares a compute unit with a long kernel
+ * of another then issues first.  Timing only, results unchanged.  (This is the priority of a wave among the waves of
+ * its SIMD, set by the kernel itself; stream and queue priorities are never used.) */
+#define MT_SCHED_PRIORITIZE_SHORT 256
 /* MT_SCHED_STREAM_GRAPHS: the launches of one stream in one stage are captured (on that stream, on the first run
  * and again when a buffer pointer changes) into a graph of their own and replayed on that stream: the short gaps
  * between kernels of a replayed graph, with CU shares still in force (the replay runs on the masked stream) and with
@@ -252,6 +258,10 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
 int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, const int32_t *pointers,
                            const int32_t *stage_concurrency, const int32_t *cu_share,
                            int32_t issue_order, int32_t flags, mt_schedule **out);
+/* Wave priority per tenant (host array of n_tenants entries): 0..3 = every kernel of that tenant raises its waves to
+ * that issue priority, -1 = the rule of MT_SCHED_PRIORITIZE_SHORT for that tenant.  Replaces what the flags set;
+ * graphs captured so far are dropped and captured again on the next run.  Timing only. */
+int32_t mt_schedule_set_wave_priority(mt_schedule *s, const int32_t *prio);
 int32_t mt_schedule_destroy(mt_schedule *s);
 
 /* Host-only views of the schedule generation function T(G, rho) (Eq. 8) and of the launch order (Sec. III-D).
@@ -289,6 +299,7 @@ typedef struct mt_search_opts {
                               (Alg. 1's start point).  An addition to the printed algorithm; with it the returned schedule is
                               never worse than stream-parallel under the same profiler. */
     int32_t cu_share_rounds; /* mt_search only: > 0 runs that many rounds of the CU-share descent (below) after the pointer search */
+    int32_t wave_priority_rounds; /* mt_search only: > 0 runs that many rounds of the wave-priority descent (below) last */
     uint64_t seed;
 } mt_search_opts;
 
@@ -314,7 +325,16 @@ typedef double (*mt_share_cost_fn)(const int32_t *cu_share, void *user);
 int32_t mt_search_cu_share(int32_t n_tenants, int32_t cu_count, int32_t rounds, mt_share_cost_fn share_cost, void *user,
                            int32_t *best_share, double *best_cost);
 
-/* A disjoint start vector for that search: the units are dealt out in eighths of cu_count; every tenant owns one eighth,
+/* Wave priority per tenant as one more coordinate per tenant (an extension, see mt_schedule_set_wave_priority).  Host
+ * only, any cost function of the same shape as for the shares.  Start: the vector passed in best_prio.  Each round
+ * visits the tenants in order; for a tenant the values -1, 0, 1, 2, 3 other than its current one are evaluated with the
+ * other entries fixed, and a value replaces the tenant's entry if its cost is lower than the best cost so far; the
+ * search stops after a round that changed nothing.  best_prio: host [n_tenants], in = start, out = best found;
+ * *best_cost: in = cost of the start vector, out = best cost found. */
+int32_t mt_search_wave_priority(int32_t n_tenants, int32_t rounds, mt_share_cost_fn prio_cost, void *user,
+                                int32_t *best_prio, double *best_cost);
+
+/* A disjoint start vector for the share search: the units are dealt out in eighths of cu_count; every tenant owns one eighth,
  * the 8 - n_tenants spare eighths go to the tenants in proportion to weight[] (host [n_tenants], >= 0, e.g. the serial
  * latency of each tenant) by largest remainder, lower index first on ties; with more than 8 tenants every share is one
  * eighth (the ranges then overlap).  share: host [n_tenants]. */
@@ -324,14 +344,20 @@ int32_t mt_proportional_cu_share(int32_t n_tenants, int32_t cu_count, const doub
  * untimed ones), all tenants on their own stream.
  * best_cu_share: host [n_tenants] or NULL; filled with zeros unless opts->cu_share_rounds > 0.  With
  * opts->cu_share_rounds > 0 three phases run: the pointer search on unmasked streams (the only phase written to the
- * records); the share descent under those pointers, started from the better of all-zero shares and
- * mt_proportional_cu_share of the tenants' serial latencies; and, if a share came out non-zero and n_stages > 1, the
+ * records); the share descent under those pointers, started from the best of all-zero shares,
+ * mt_proportional_cu_share of the tenants' serial latencies and two uniform vectors (every tenant one half, or three
+ * quarters, of the units: overlapping shares); and, if a share came out non-zero and n_stages > 1, the
  * pointer search once more under those shares, kept only when its best cost is lower.  A masked result is measured
  * again on fresh streams before it is returned (they stay in the context's pool, so a schedule created next with the
  * same shares runs on exactly those streams); if it does not beat the unmasked result there, the unmasked pointers and
- * all-zero shares are returned. */
+ * all-zero shares are returned.
+ * best_wave_priority: host [n_tenants] or NULL; with opts->wave_priority_rounds > 0 the priority descent runs last,
+ * under the pointers and shares found, from the vector the flags give (all 0, or all -1 with
+ * MT_SCHED_PRIORITIZE_SHORT); if shares were found, a second descent runs under the unmasked result of the pointer
+ * search, and that result (all-zero shares) is returned when it ends lower.  Without the descent the vector the flags
+ * give is returned as it is. */
 int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *inputs, void *const *outputs,
-                  int32_t *best_pointers, int32_t *best_cu_share, double *best_cost,
+                  int32_t *best_pointers, int32_t *best_cu_share, int32_t *best_wave_priority, double *best_cost,
                   int32_t *rec_pointers, double *rec_cost, int32_t max_records, int32_t *n_records);
 
 #ifdef __cplusplus

@@ -208,3 +208,26 @@ def cu_share_descent(n_tenants, cu_count, rounds, cost, start_cost, start=None):
                 if c < best:
                     best, cur = c, cand
     return cur, best
+
+
+def wave_priority_descent(n_tenants, rounds, cost, start_cost, start=None):
+    """Extension: per-tenant wave priority as one more coordinate.  Start with the given vector (default: all 0);
+    per round and tenant, try the values -1, 0, 1, 2, 3 other than the current one with the other entries fixed; a
+    value replaces the tenant's entry when its cost is lower than the best so far; a round that changes nothing
+    ends the search."""
+    cur = list(start) if start is not None else [0] * n_tenants
+    best = start_cost
+    for _ in range(rounds):
+        changed = False
+        for i in range(n_tenants):
+            for v in (-1, 0, 1, 2, 3):
+                if v == cur[i]:
+                    continue
+                cand = list(cur)
+                cand[i] = v
+                c = cost(cand)
+                if c < best:
+                    best, cur, changed = c, cand, True
+        if not changed:
+            break
+    return cur, best

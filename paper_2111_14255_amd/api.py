@@ -8,14 +8,6 @@ import os
 
 import numpy as np
 
-# One hardware queue per tenant stream plus the main stream (the HIP default of 4 would make 8 tenants share
-# queues).  Must be in the environment before the HIP runtime initialises.
-os.environ.setdefault("GPU_MAX_HW_QUEUES", "16")
-# Kernel arguments in device memory: with them in host memory every launch starts with a read over the host link
-# (measured on MI355X: 848 against 578 us for the 98 launches of the ResNet-18 + VGG-16 + MobileNetV2 pass).
-# The runtime of this image already defaults to it; set here so that another default does not change the numbers.
-os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
-
 from . import binding as B
 
 _DT = {"f32": B.MT_F32, "f16": B.MT_F16, "bf16": B.MT_BF16}
@@ -133,6 +125,11 @@ class Schedule:
     def __init__(self, ctx, handle, pointers, n_stages, label=""):
         self.ctx, self.h, self.pointers, self.n_stages, self.label = ctx, handle, pointers, n_stages, label
 
+    def set_wave_priority(self, prio):
+        """prio: one entry per tenant, 0..3 or -1 (short kernels 3, others 0)."""
+        arr = (C.c_int32 * len(prio))(*prio)
+        B.check(B.load().mt_schedule_set_wave_priority(self.h, arr))
+
     def close(self):
         if self.h:
             B.load().mt_schedule_destroy(self.h)
@@ -218,7 +215,8 @@ class Context:
         return out.detach().float().cpu().numpy()
 
     # -- schedules -------------------------------------------------------------------------
-    def schedule(self, pointers, n_stages, concurrency=None, cu_share=None, order=B.MT_ISSUE_BFS, flags=0, label=""):
+    def schedule(self, pointers, n_stages, concurrency=None, cu_share=None, order=B.MT_ISSUE_BFS, flags=0, label="",
+                 wave_priority=None):
         n = self.num_tenants()
         P = n_stages - 1
         flat = [int(v) for row in pointers for v in row] if P > 0 else []
@@ -232,7 +230,10 @@ class Context:
         share = None if cu_share is None else (C.c_int32 * len(cu_share))(*cu_share)
         h = C.c_void_p()
         B.check(self.lib.mt_schedule_create(self.h, n, n_stages, arr, conc, share, order, flags, C.byref(h)))
-        return Schedule(self, h, [list(r) for r in pointers], n_stages, label)
+        sched = Schedule(self, h, [list(r) for r in pointers], n_stages, label)
+        if wave_priority is not None:
+            sched.set_wave_priority(wave_priority)
+        return sched
 
     def sequential(self, **kw):
         """One stage, concurrency 1: tenants one after another on one stream."""
@@ -259,26 +260,34 @@ class Context:
         return [ms[i] for i in range(n)]
 
     def search(self, inputs, outputs, n_stages, rounds=2, candidates=6, runs=5, warmup=1, seed=1,
-               algo=B.MT_SEARCH_COORDINATE, order=B.MT_ISSUE_BFS, flags=0, seed_baselines=True, cu_share_rounds=0):
-        """Returns (pointer matrix, best cost, records) and, with cu_share_rounds > 0, also the CU shares."""
+               algo=B.MT_SEARCH_COORDINATE, order=B.MT_ISSUE_BFS, flags=0, seed_baselines=True, cu_share_rounds=0,
+               wave_priority_rounds=0):
+        """Returns (pointer matrix, best cost, records), then the CU shares if cu_share_rounds > 0, then the wave
+        priorities if wave_priority_rounds > 0."""
         n = self.num_tenants()
         P = n_stages - 1
-        opts = B.mt_search_opts(algo, n_stages, rounds, candidates, runs, warmup, order, flags, 1 if seed_baselines else 0, cu_share_rounds, seed)
+        opts = B.mt_search_opts(algo, n_stages, rounds, candidates, runs, warmup, order, flags, 1 if seed_baselines else 0, cu_share_rounds,
+                                wave_priority_rounds, seed)
         cap = rounds * n * candidates + 2
         best = (C.c_int32 * max(1, n * P))()
         best_cost = C.c_double()
         shares = (C.c_int32 * n)()
+        prio = (C.c_int32 * n)()
         recp = (C.c_int32 * max(1, cap * n * P))()
         recc = (C.c_double * cap)()
         nrec = C.c_int32()
         ins = (C.c_void_p * n)(*[t.data_ptr() for t in inputs])
         outs = (C.c_void_p * n)(*[t.data_ptr() for t in outputs])
-        B.check(self.lib.mt_search(self.h, C.byref(opts), ins, outs, best, shares, C.byref(best_cost), recp, recc, cap, C.byref(nrec)))
+        B.check(self.lib.mt_search(self.h, C.byref(opts), ins, outs, best, shares, prio, C.byref(best_cost), recp, recc, cap,
+                                  C.byref(nrec)))
         rho = [[best[i * P + j] for j in range(P)] for i in range(n)]
         records = [([[recp[(k * n + i) * P + j] for j in range(P)] for i in range(n)], recc[k]) for k in range(min(nrec.value, cap))]
+        out = (rho, best_cost.value, records)
         if cu_share_rounds > 0:
-            return rho, best_cost.value, records, [shares[i] for i in range(n)]
-        return rho, best_cost.value, records
+            out += ([shares[i] for i in range(n)],)
+        if wave_priority_rounds > 0:
+            out += ([prio[i] for i in range(n)],)
+        return out
 
     def close(self):
         if self.h:

@@ -30,6 +30,7 @@ MT_SCHED_SHARE_PER_STAGE = 8
 MT_SCHED_FUSE_DEPTHWISE = 16
 MT_SCHED_FUSE_EXPAND = 64
 MT_SCHED_FUSE_POOL = 128
+MT_SCHED_PRIORITIZE_SHORT = 256
 MT_SCHED_STREAM_GRAPHS = 32
 MT_SEARCH_COORDINATE, MT_SEARCH_RANDOM = 0, 1
 
@@ -62,7 +63,8 @@ class mt_timings(C.Structure):
 class mt_search_opts(C.Structure):
     _fields_ = [("algo", C.c_int32), ("n_stages", C.c_int32), ("rounds", C.c_int32), ("candidates", C.c_int32),
                 ("runs", C.c_int32), ("warmup", C.c_int32), ("issue_order", C.c_int32), ("flags", C.c_int32),
-                ("seed_baselines", C.c_int32), ("cu_share_rounds", C.c_int32), ("seed", C.c_uint64)]
+                ("seed_baselines", C.c_int32), ("cu_share_rounds", C.c_int32), ("wave_priority_rounds", C.c_int32),
+                ("seed", C.c_uint64)]
 
 
 mt_cost_fn = C.CFUNCTYPE(C.c_double, C.POINTER(C.c_int32), C.c_void_p)
@@ -96,6 +98,7 @@ SIGNATURES = {
     "mt_tenant_op_info": (_i32, [_vp, _i32, _i32, C.POINTER(mt_op_info)]),
     "mt_tenant_read_tensor": (_i32, [_vp, _i32, _i32, _vp, _sz]),
     "mt_schedule_create": (_i32, [_vp, _i32, _i32, _pi32, _pi32, _pi32, _i32, _i32, C.POINTER(_vp)]),
+    "mt_schedule_set_wave_priority": (_i32, [_vp, C.POINTER(C.c_int32)]),
     "mt_schedule_destroy": (_i32, [_vp]),
     "mt_expand_pointers": (_i32, [_i32, _pi32, _i32, _pi32, _pi32]),
     "mt_issue_order_of_stage": (_i32, [_i32, _pi32, _i32, _i32, _pi32, _pi32]),
@@ -104,7 +107,8 @@ SIGNATURES = {
     "mt_search_pointers": (_i32, [_i32, _pi32, C.POINTER(mt_search_opts), mt_cost_fn, _vp, _pi32, _pd, _pi32, _pd, _i32, _pi32]),
     "mt_search_cu_share": (_i32, [_i32, _i32, _i32, mt_share_cost_fn, _vp, _pi32, _pd]),
     "mt_proportional_cu_share": (_i32, [_i32, _i32, _pd, _pi32]),
-    "mt_search": (_i32, [_vp, C.POINTER(mt_search_opts), C.POINTER(_vp), C.POINTER(_vp), _pi32, _pi32, _pd, _pi32, _pd, _i32, _pi32]),
+    "mt_search": (_i32, [_vp, C.POINTER(mt_search_opts), C.POINTER(_vp), C.POINTER(_vp), _pi32, _pi32, _pi32, _pd, _pi32, _pd, _i32, _pi32]),
+    "mt_search_wave_priority": (_i32, [_i32, _i32, mt_share_cost_fn, _vp, _pi32, _pd]),
 }
 
 _lib = None

@@ -28,6 +28,14 @@ __device__ __forceinline__ float apply_act(float v, int act) {
     return __builtin_amdgcn_fmed3f(v, lo, hi);
 }
 
+// Issue priority of the calling wave among the waves of its SIMD (0 lowest, 3 highest); the instruction takes an
+// immediate, hence the ladder.  Changes timing only, never results.
+__device__ __forceinline__ void set_wave_priority(int p) {
+    if (p == 1) __builtin_amdgcn_s_setprio(1);
+    else if (p == 2) __builtin_amdgcn_s_setprio(2);
+    else if (p == 3) __builtin_amdgcn_s_setprio(3);
+}
+
 // V consecutive elements of T moved as one access when V*sizeof(T) is 4, 8 or 16 bytes.
 template <typename T, int V>
 struct alignas(sizeof(T) * V) Pack {

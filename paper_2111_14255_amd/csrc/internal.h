@@ -29,6 +29,9 @@ int32_t proportional_cu_share(int32_t n_tenants, int32_t cu_count, const double 
 int32_t search_cu_share(int32_t n_tenants, int32_t cu_count, int32_t rounds, mt_share_cost_fn cost, void *user,
                         int32_t *best_share, double *best_cost);
 
+int32_t search_wave_priority(int32_t n_tenants, int32_t rounds, mt_share_cost_fn cost, void *user, int32_t *best_prio,
+                             double *best_cost);
+
 constexpr int IGEMM_BK = 64;   // reduction elements per implicit-GEMM tile; packed filter rows are padded to it
 
 inline bool is_gemm_kernel(int32_t id);
@@ -77,6 +80,7 @@ struct OpArgs {
     int32_t n_pad;               // packed weight rows (multiple of the channel tile)
     int32_t split_k;
     int32_t wk;                  // wave groups that share an output tile (64x64 tile only): 1 or 2
+    int32_t prio;                // issue priority of the kernel's waves, 0 (default) .. 3; set per launch from the schedule
     int32_t pool2;               // 1: the epilogue applies a 2x2 / stride-2 max pooling; pixels are then walked quad by quad and y is the pooled tensor
     // Exact unsigned division by Q and by P*Q without a divide (multiply-high, two shifts): n / d =
     // (t + ((n - t) >> s1)) >> s2 with t = mulhi(m, n); filled by make_divisor().

@@ -32,6 +32,7 @@ __device__ inline ElemIdx split_index(uint32_t g, int CV, int Q, int P) {
 // Sum order is fixed (r, s, c), so the result does not depend on the launch environment.
 template <typename T>
 __global__ void __launch_bounds__(256) conv_direct_kernel(OpArgs a) {
+    set_wave_priority(a.prio);
     const uint32_t total = (uint32_t)a.N * a.P * a.Q * a.K;
     const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= total) return;
@@ -81,6 +82,7 @@ __global__ void __launch_bounds__(256) conv_direct_kernel(OpArgs a) {
 // that the weight vector of a tap is one contiguous load, shared by every pixel through the caches.
 template <typename T, int V>
 __global__ void __launch_bounds__(256) dwconv_kernel(OpArgs a) {
+    set_wave_priority(a.prio);
     const int CV = a.C / V;
     const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
     const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
@@ -122,6 +124,7 @@ __global__ void __launch_bounds__(256) dwconv_kernel(OpArgs a) {
 // one before it; taps in the padding halo are masked afterwards.  Tap order of the sums is the same (r, s).
 template <typename T, int V, int KS>
 __global__ void __launch_bounds__(256) dwconv_fixed_kernel(OpArgs a) {
+    set_wave_priority(a.prio);
     const int CV = a.C / V;
     const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
     const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
@@ -164,6 +167,7 @@ __global__ void __launch_bounds__(256) dwconv_fixed_kernel(OpArgs a) {
 
 template <typename T, int V, bool IS_MAX, int KS>
 __global__ void __launch_bounds__(256) pool_fixed_kernel(OpArgs a) {
+    set_wave_priority(a.prio);
     const int CV = a.C / V;
     const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
     const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
@@ -206,6 +210,7 @@ __global__ void __launch_bounds__(256) pool_fixed_kernel(OpArgs a) {
 // Window pooling: one thread per (output pixel, V-channel vector).
 template <typename T, int V, bool IS_MAX>
 __global__ void __launch_bounds__(256) pool_kernel(OpArgs a) {
+    set_wave_priority(a.prio);
     const int CV = a.C / V;
     const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
     const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
@@ -245,6 +250,7 @@ __global__ void __launch_bounds__(256) pool_kernel(OpArgs a) {
 // the slices are combined by a fixed butterfly of wavefront shuffles, so the sum order is fixed.
 template <typename T, int V>
 __global__ void __launch_bounds__(256) gap_kernel(OpArgs a, int lanes_c) {
+    set_wave_priority(a.prio);
     const int CV = a.C / V;
     const int lanes_hw = 64 / lanes_c;
     const int groups = (CV + lanes_c - 1) / lanes_c;            // wave tasks per image
@@ -292,6 +298,7 @@ __global__ void __launch_bounds__(256) gap_kernel(OpArgs a, int lanes_c) {
 // reaches at most 7 channels to either side, V >= 8 for the vector form), all before any arithmetic.
 template <typename T, int V>
 __global__ void __launch_bounds__(256) lrn_kernel(OpArgs a) {
+    set_wave_priority(a.prio);
     const int CV = a.C / V;
     const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
     const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
@@ -347,6 +354,7 @@ __global__ void __launch_bounds__(256) lrn_kernel(OpArgs a) {
 // Element-wise sum of two tensors of the same shape, activation, one rounding.
 template <typename T, int V>
 __global__ void __launch_bounds__(256) add_kernel(OpArgs a) {
+    set_wave_priority(a.prio);
     const int CV = a.C / V;
     const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
     const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;

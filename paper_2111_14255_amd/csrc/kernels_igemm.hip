@@ -86,6 +86,7 @@ struct Mma<bf16, 16> {
 // the hardware returns zeros: no select and no 64-bit address arithmetic in the loop.
 template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES, int AMODE, int WK = 1>
 __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
+    set_wave_priority(a.prio);
     static_assert(WN * WM == 4, "four waves per output tile");
     // WK > 1: WK groups of four waves share the output tile and split the MFMA steps of every LDS tile between them
     // (a second wave per SIMD to overlap with when the grid gives a compute unit a single workgroup); their
@@ -612,6 +613,7 @@ __device__ __forceinline__ void unpack8(u32x4 v, float (&f)[8]) {
 
 template <typename T, int MB, int ROWS, bool STREAM_W>
 __global__ void __launch_bounds__(256) gemv_kernel(OpArgs a) {
+    set_wave_priority(a.prio);
     const int wave = (int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
     const int lane = threadIdx.x & 63;
     const int k0 = wave * ROWS;
@@ -747,6 +749,7 @@ static int launch_igemm_typed(const OpArgs &a, hipStream_t st) {
 // instantiation, so the output bits equal those of the two separate launches.
 template <typename T>
 __global__ void __launch_bounds__(256) dwpw_kernel(OpArgs a, OpArgs d) {
+    set_wave_priority(a.prio);
     constexpr int BN = 64, BM = 16;
     constexpr int G = 3;                                 // channel chunks of a thread whose tap loads are in flight together
     typedef typename Mma<T, 16>::Acc Acc;
@@ -956,6 +959,7 @@ int launch_dwpw(const OpArgs &dw, const OpArgs &pw, void *stream) {
 // MT: 16-pixel tiles per wave (a band reads at most 64 * MT pixels), KS: 32-deep reduction steps (k_pad <= 32 * KS).
 template <typename T, int MT, int KS, int HC>
 __global__ void __launch_bounds__(256) pwdw_kernel(OpArgs e, OpArgs d, int bands) {
+    set_wave_priority(d.prio);
     constexpr int NI = HC / 16;                          // MFMA tiles along the channels
     constexpr int CPP = HC / 8;                          // 8-channel chunks per pixel
     constexpr int ELD = HC + 8;                          // LDS row stride

@@ -323,6 +323,7 @@ struct Tenant {
     std::vector<uint8_t> fuse_pwdw;  // operator i is a 1x1 convolution that can run inside the launch of the depthwise operator i + 1
     std::vector<uint8_t> fuse_pool;  // operator i is a convolution whose epilogue can apply the 2x2 max pooling operator i + 1
     std::vector<OpArgs> pool_args;   // its arguments for that form (pooled output tensor, quad pixel walk)
+    std::vector<uint8_t> short_kernel;   // operator runs on a short, latency-bound kernel (see MT_SCHED_PRIORITIZE_SHORT)
 };
 
 struct StreamKey {
@@ -390,6 +391,7 @@ struct mt_schedule {
     std::vector<StreamKey> stream_keys;     // one reference in the context's pool per entry
     int n_launches = 0;
     int n_fused = 0;                // operators that run inside the next operator's launch
+    int32_t prio[MT_MAX_TENANTS] = {0};   // wave priority of a tenant's kernels, 0..3; -1: 3 for its short kernels, 0 for the others
     // graph replay
     hipGraphExec_t graph_exec = nullptr;
     std::vector<const void *> cap_in;
@@ -467,14 +469,20 @@ int32_t dispatch_latency_us(mt_ctx *ctx, hipStream_t st, uint32_t *scratch, int 
 // One issue item on its stream; returns a hipError_t as int.  An operator that runs inside its successor's launch
 // (fuse 1) is skipped here; its neighbour launches the pair (fuse 2: depthwise + 1x1, fuse 3: 1x1 + depthwise, both from
 // the second operator; fuse 4: convolution with the next operator, a 2x2 max pooling, in its epilogue).
-int launch_item(const mt_ctx *ctx, const IssueItem &it, const void *const *inputs, void *const *outputs, hipStream_t st) {
+int launch_item(const mt_ctx *ctx, const mt_schedule *s, const IssueItem &it, const void *const *inputs, void *const *outputs, hipStream_t st) {
     if (it.fuse == 1) return 0;
     const Tenant &t = *ctx->tenants[it.tenant];
-    const OpArgs a = patched(t, it.op, inputs[it.tenant], outputs[it.tenant]);
-    if (it.fuse == 2) return launch_dwpw(patched(t, it.op - 1, inputs[it.tenant], outputs[it.tenant]), a, st);
-    if (it.fuse == 3) return launch_pwdw(patched(t, it.op - 1, inputs[it.tenant], outputs[it.tenant]), a, st);
+    const int tp = s->prio[it.tenant];
+    OpArgs a = patched(t, it.op, inputs[it.tenant], outputs[it.tenant]);
+    a.prio = tp >= 0 ? tp : (t.short_kernel[it.op] || it.fuse == 2 || it.fuse == 3) ? 3 : 0;
+    if (it.fuse == 2 || it.fuse == 3) {
+        OpArgs prev = patched(t, it.op - 1, inputs[it.tenant], outputs[it.tenant]);
+        prev.prio = a.prio;
+        return it.fuse == 2 ? launch_dwpw(prev, a, st) : launch_pwdw(prev, a, st);
+    }
     if (it.fuse == 4) {
         OpArgs b = t.pool_args[it.op];
+        b.prio = a.prio;
         if (t.reads_input[it.op]) b.x = inputs[it.tenant];
         if (t.writes_output[it.op + 1]) b.y = outputs[it.tenant];
         return launch_raw(b, st);
@@ -519,29 +527,28 @@ int32_t get_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t
         }
     }
     hipStream_t s = nullptr;
-    if (share == 0) {
-        HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
-    } else {
-        const int cus = ctx->prop.multiProcessorCount;
-        std::vector<uint32_t> mask((cus + 31) / 32, 0u);
-        for (int j = 0; j < share; ++j) {
-            const int cu = (first_cu + j) % cus;
-            mask[cu / 32] |= 1u << (cu % 32);
-        }
-        // On MI355X roughly one in four CU-masked queues dispatches dependent kernels about 1.5x slower than the
-        // others (measured: 16 us against 11 us per launch of a fixed probe kernel, in creation order 1, 5, 9, ...;
-        // whole tenants then run 2x slower).  A new queue is therefore timed, and a slow one is parked (kept alive so
-        // that its hardware slot stays taken) and replaced by the next one.
-        if (!ctx->probe_buf) HIP_TRY(hipMalloc((void **)&ctx->probe_buf, 256));
-        for (int attempt = 0;; ++attempt) {
-            HIP_TRY(hipExtStreamCreateWithCUMask(&s, (uint32_t)mask.size(), mask.data()));
-            float us = 0.f;
-            int32_t rc = dispatch_latency_us(ctx, s, ctx->probe_buf, 12, &us);
-            if (rc != MT_OK) { (void)hipStreamDestroy(s); return rc; }
-            if (ctx->best_dispatch_us == 0.f || us < ctx->best_dispatch_us) ctx->best_dispatch_us = us;
-            if (us <= 1.2f * ctx->best_dispatch_us || attempt == 3) break;
-            ctx->parked_streams.push_back(s);
-        }
+    const int cus = ctx->prop.multiProcessorCount;
+    std::vector<uint32_t> mask((cus + 31) / 32, 0u);
+    for (int j = 0; j < share; ++j) {
+        const int cu = (first_cu + j) % cus;
+        mask[cu / 32] |= 1u << (cu % 32);
+    }
+    // On MI355X roughly one in four hardware queues dispatches dependent kernels about 1.5x slower than the others
+    // (measured: 16 us against 11 us per launch of a fixed probe kernel, in creation order 1, 5, 9, ...; whole tenants
+    // then run up to 2x slower).  A new stream is therefore timed, and a slow one is parked (kept alive so that its
+    // hardware slot stays taken) and replaced by the next one.
+    if (!ctx->probe_buf) HIP_TRY(hipMalloc((void **)&ctx->probe_buf, 256));
+    for (int attempt = 0;; ++attempt) {
+        if (share == 0) HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+        else HIP_TRY(hipExtStreamCreateWithCUMask(&s, (uint32_t)mask.size(), mask.data()));
+        float us = 0.f;
+        int32_t rc = dispatch_latency_us(ctx, s, ctx->probe_buf, 12, &us);
+        if (rc != MT_OK) { (void)hipStreamDestroy(s); return rc; }
+        static const bool trace = std::getenv("MTSCHED_TRACE") != nullptr;
+        if (trace) std::fprintf(stderr, "[mtsched] stream tenant %d share %d attempt %d: %.2f us per dependent launch (best %.2f)\n", tenant, share, attempt, us, ctx->best_dispatch_us);
+        if (ctx->best_dispatch_us == 0.f || us < ctx->best_dispatch_us) ctx->best_dispatch_us = us;
+        if (us <= 1.2f * ctx->best_dispatch_us || attempt == 3) break;
+        ctx->parked_streams.push_back(s);
     }
     ctx->streams[key] = mt_ctx::StreamEntry{s, 1};
     *out = s;
@@ -588,7 +595,7 @@ int32_t capture_slice_graphs(mt_ctx *ctx, mt_schedule *s, const void *const *inp
             HIP_TRY(hipStreamBeginCapture(stream, hipStreamCaptureModeRelaxed));
             int32_t rc = MT_OK;
             for (const IssueItem &it : sp.by_stream[sm]) {
-                const int e = launch_item(ctx, it, inputs, outputs, stream);
+                const int e = launch_item(ctx, s, it, inputs, outputs, stream);
                 if (e != 0) { rc = fail(MT_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString((hipError_t)e)); break; }
             }
             hipError_t e = hipStreamEndCapture(stream, &graph);
@@ -619,7 +626,7 @@ int32_t issue_schedule(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, v
         } else
         for (const IssueItem &it : sp.items) {
             ++launches;                              // counts operators issued, fused or not
-            const int e = launch_item(ctx, it, inputs, outputs, s->stream_at[st][it.stream]);
+            const int e = launch_item(ctx, s, it, inputs, outputs, s->stream_at[st][it.stream]);
             if (e != 0) return fail(MT_ERR_HIP, std::string("kernel launch: ") + hipGetErrorString((hipError_t)e));
             if ((s->flags & MT_SCHED_TIME_FIRST_OP) && it.op == 0) HIP_TRY(hipEventRecord(ctx->ev_first[it.tenant], s->stream_at[st][it.stream]));
         }
@@ -659,7 +666,7 @@ void issue_worker(mt_ctx *ctx, int w) {
                 hipError_t e = wait_for_previous_stage(ctx, s, st, w);
                 for (const IssueItem &it : sp.by_stream[w]) {
                     if (e != hipSuccess) break;
-                    const int rc = launch_item(ctx, it, pool.inputs, pool.outputs, s->stream_at[st][w]);
+                    const int rc = launch_item(ctx, s, it, pool.inputs, pool.outputs, s->stream_at[st][w]);
                     if (rc != 0) e = (hipError_t)rc;
                 }
                 if (e == hipSuccess) e = hipEventRecord(ctx->ev_done[st][w], s->stream_at[st][w]);
@@ -1076,6 +1083,14 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
         t->args[i] = a;
         o.w_host.clear(); o.w_host.shrink_to_fit();
     }
+    // short kernels: few workgroups of little work each, bound by launch and memory latency
+    t->short_kernel.assign(nops, 0);
+    for (size_t i = 0; i < nops; ++i) {
+        const OpArgs &a = t->args[i];
+        const int k = a.kernel_id;
+        t->short_kernel[i] = k == K_IGEMM_64x16 || k == K_DWCONV || k == K_MAXPOOL || k == K_AVGPOOL || k == K_GAP || k == K_LRN ||
+                             k == K_ADD || (k == K_GEMV && (size_t)a.n_pad * a.k_pad * 2 < ((size_t)16 << 20));
+    }
     // depthwise convolution followed by the 1x1 convolution that reads it: candidates for one fused launch
     t->fuse_next.assign(nops, 0);
     for (size_t i = 0; i + 1 < nops; ++i) {
@@ -1193,6 +1208,7 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
     HIP_TRY(hipSetDevice(ctx->device));
     std::unique_ptr<mt_schedule> s(new mt_schedule);
     s->ctx = ctx; s->n_tenants = n_tenants; s->n_stages = n_stages; s->flags = flags;
+    for (int i = 0; i < n_tenants; ++i) s->prio[i] = (flags & MT_SCHED_PRIORITIZE_SHORT) ? -1 : 0;
     const bool per_stage = (flags & MT_SCHED_SHARE_PER_STAGE) != 0;
     s->stream_at.assign(n_stages, {});
     for (int st = 0; st < (per_stage ? n_stages : 1); ++st) {
@@ -1250,6 +1266,17 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
     }
     ctx->live_schedules.insert(s.get());
     *out = s.release();
+    return MT_OK;
+}
+
+int32_t mt_schedule_set_wave_priority(mt_schedule *s, const int32_t *prio) {
+    if (!s || !prio) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    for (int i = 0; i < s->n_tenants; ++i)
+        if (prio[i] < -1 || prio[i] > 3) return fail(MT_ERR_INVALID_ARG, "wave priority must be -1 (by kernel size) or 0..3");
+    for (int i = 0; i < s->n_tenants; ++i) s->prio[i] = prio[i];
+    if (s->ctx) retire_graphs(s->ctx, s);            // captured launches carry the old value
+    s->cap_in.clear();
+    s->cap_out.clear();
     return MT_OK;
 }
 
@@ -1374,6 +1401,7 @@ struct ProfileCost {
     int n_tenants;
     const int32_t *pointers = nullptr;     // fixed while shares are searched
     const int32_t *cu_share = nullptr;     // fixed while pointers are searched
+    const int32_t *prio = nullptr;         // wave priorities applied to every candidate (NULL: what the flags give)
     int32_t rc = MT_OK;
 };
 
@@ -1393,7 +1421,8 @@ double profile_schedule(ProfileCost *pc, const int32_t *pointers, const int32_t 
     }
     pc->rc = mt_schedule_create(pc->ctx, pc->n_tenants, pc->o->n_stages, pointers, nullptr, cu_share, pc->o->issue_order,
                                 pc->o->flags, &s);
-    if (pc->rc != MT_OK) return 1e30;
+    if (pc->rc == MT_OK && pc->prio) pc->rc = mt_schedule_set_wave_priority(s, pc->prio);
+    if (pc->rc != MT_OK) { if (s) mt_schedule_destroy(s); return 1e30; }
     // The profiled latency of a candidate is the median of its timed runs: one preempted run must not decide
     // a comparison between two schedules that differ by a few percent.
     std::vector<double> samples;
@@ -1422,11 +1451,20 @@ double profile_share_cost(const int32_t *cu_share, void *user) {
     ProfileCost *pc = (ProfileCost *)user;
     return profile_schedule(pc, pc->pointers, cu_share);
 }
+
+double profile_prio_cost(const int32_t *prio, void *user) {
+    ProfileCost *pc = (ProfileCost *)user;
+    const int32_t *keep = pc->prio;
+    pc->prio = prio;
+    const double c = profile_schedule(pc, pc->pointers, pc->cu_share);
+    pc->prio = keep;
+    return c;
+}
 }  // namespace
 
 int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *inputs, void *const *outputs,
-                  int32_t *best_pointers, int32_t *best_cu_share, double *best_cost, int32_t *rec_pointers,
-                  double *rec_cost, int32_t max_records, int32_t *n_records) {
+                  int32_t *best_pointers, int32_t *best_cu_share, int32_t *best_wave_priority, double *best_cost,
+                  int32_t *rec_pointers, double *rec_cost, int32_t max_records, int32_t *n_records) {
     if (!ctx || !opts || !inputs || !outputs || !best_pointers) return fail(MT_ERR_INVALID_ARG, "NULL argument");
     if (opts->runs < 1 || opts->warmup < 0) return fail(MT_ERR_INVALID_ARG, "runs must be >= 1 and warmup >= 0");
     const int n = (int)ctx->tenants.size();
@@ -1445,9 +1483,9 @@ int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *in
     const double unmasked_cost = cost;
     std::vector<int32_t> unmasked_pointers(best_pointers, best_pointers + (size_t)n * (opts->n_stages - 1));
     if (opts->cu_share_rounds > 0) {
-        // Shares are searched under the pointers just found.  The descent starts from the better of two vectors:
-        // all zeros (every tenant on every unit, whose cost is known) and a disjoint split in proportion to the serial
-        // latency of each tenant; a descent from all zeros alone rarely leaves it, because one masked tenant
+        // Shares are searched under the pointers just found.  The descent starts from the best of four vectors:
+        // all zeros (every tenant on every unit, whose cost is known), a disjoint split in proportion to the serial
+        // latency of each tenant, and two uniform overlapping ones (below); a descent from all zeros alone rarely leaves it, because one masked tenant
         // among unmasked ones gains nothing.
         pc.pointers = best_pointers;
         const int cus = ctx->prop.multiProcessorCount;
@@ -1463,11 +1501,18 @@ int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *in
         int32_t start[MT_MAX_TENANTS];
         rc = proportional_cu_share(n, cus, weight, start);
         if (rc != MT_OK) return rc;
-        const double start_cost = profile_share_cost(start, &pc);
-        if (pc.rc != MT_OK) return pc.rc;
-        if (start_cost < cost) {
-            std::memcpy(shares, start, sizeof(int32_t) * n);
-            cost = start_cost;
+        // Two more start vectors give every tenant the same share, one half and three quarters of the units: the
+        // shares then overlap (tenant i's units follow those of tenant i - 1, modulo the unit count), which keeps a
+        // heavy tenant apart from some of the others without starving it.
+        for (int cand = 0; cand < 3; ++cand) {
+            if (cand > 0)
+                for (int i = 0; i < n; ++i) start[i] = std::max(8, (cand == 1 ? cus / 2 : 3 * cus / 4) / 8 * 8);
+            const double start_cost = profile_share_cost(start, &pc);
+            if (pc.rc != MT_OK) return pc.rc;
+            if (start_cost < cost) {
+                std::memcpy(shares, start, sizeof(int32_t) * n);
+                cost = start_cost;
+            }
         }
         rc = search_cu_share(n, cus, opts->cu_share_rounds, profile_share_cost, &pc, shares, &cost);
         if (pc.rc != MT_OK) return pc.rc;
@@ -1519,6 +1564,39 @@ int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *in
             }
         }
     }
+    int32_t prio[MT_MAX_TENANTS];
+    for (int i = 0; i < n; ++i) prio[i] = (opts->flags & MT_SCHED_PRIORITIZE_SHORT) ? -1 : 0;
+    if (opts->wave_priority_rounds > 0) {
+        // Last coordinate set: the wave priority of each tenant's kernels, under the pointers and shares found.
+        bool masked = false;
+        for (int i = 0; i < n; ++i) masked = masked || shares[i] != 0;
+        pc.pointers = best_pointers;
+        pc.cu_share = masked ? shares : nullptr;
+        rc = search_wave_priority(n, opts->wave_priority_rounds, profile_prio_cost, &pc, prio, &cost);
+        if (pc.rc != MT_OK) return pc.rc;
+        if (rc != MT_OK) return rc;
+        if (masked) {
+            // Priorities matter most where tenants share units, which masks prevent: the unmasked result of the pointer
+            // search gets its own descent and wins if it ends lower.
+            int32_t prio_u[MT_MAX_TENANTS];
+            for (int i = 0; i < n; ++i) prio_u[i] = (opts->flags & MT_SCHED_PRIORITIZE_SHORT) ? -1 : 0;
+            double cost_u = unmasked_cost;
+            pc.pointers = unmasked_pointers.data();
+            pc.cu_share = nullptr;
+            rc = search_wave_priority(n, opts->wave_priority_rounds, profile_prio_cost, &pc, prio_u, &cost_u);
+            if (pc.rc != MT_OK) return pc.rc;
+            if (rc != MT_OK) return rc;
+            if (cost_u < cost) {
+                cost = cost_u;
+                std::memcpy(prio, prio_u, sizeof(int32_t) * n);
+                std::memcpy(best_pointers, unmasked_pointers.data(), sizeof(int32_t) * unmasked_pointers.size());
+                std::memset(shares, 0, sizeof(shares));
+                rc = purge_idle_streams(ctx);
+                if (rc != MT_OK) return rc;
+            }
+        }
+    }
+    if (best_wave_priority) std::memcpy(best_wave_priority, prio, sizeof(int32_t) * n);
     if (best_cu_share) std::memcpy(best_cu_share, shares, sizeof(int32_t) * n);
     if (best_cost) *best_cost = cost;
     return MT_OK;

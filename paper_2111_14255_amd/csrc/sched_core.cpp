@@ -256,9 +256,43 @@ int32_t search_cu_share(int32_t n_tenants, int32_t cu_count, int32_t rounds, mt_
     return MT_OK;
 }
 
+int32_t search_wave_priority(int32_t n_tenants, int32_t rounds, mt_share_cost_fn cost, void *user, int32_t *best_prio,
+                             double *best_cost) {
+    if (!cost || !best_prio || !best_cost) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (n_tenants < 1 || n_tenants > MT_MAX_TENANTS || rounds < 1) return fail(MT_ERR_INVALID_ARG, "bad tenant count or rounds");
+    std::vector<int32_t> cur(best_prio, best_prio + n_tenants), cand(n_tenants, 0);
+    for (int i = 0; i < n_tenants; ++i)
+        if (cur[i] < -1 || cur[i] > 3) return fail(MT_ERR_INVALID_ARG, "start priority out of range");
+    double best = *best_cost;
+    for (int r = 0; r < rounds; ++r) {
+        bool changed = false;
+        for (int i = 0; i < n_tenants; ++i)
+            for (int v = -1; v <= 3; ++v) {
+                cand = cur;
+                cand[i] = v;
+                if (v == cur[i]) continue;
+                const double c = cost(cand.data(), user);
+                if (c < best) {
+                    best = c;
+                    cur = cand;
+                    changed = true;
+                }
+            }
+        if (!changed) break;
+    }
+    std::memcpy(best_prio, cur.data(), sizeof(int32_t) * n_tenants);
+    *best_cost = best;
+    return MT_OK;
+}
+
 }  // namespace mt
 
 extern "C" {
+
+int32_t mt_search_wave_priority(int32_t n_tenants, int32_t rounds, mt_share_cost_fn prio_cost, void *user, int32_t *best_prio,
+                                double *best_cost) {
+    return mt::search_wave_priority(n_tenants, rounds, prio_cost, user, best_prio, best_cost);
+}
 
 int32_t mt_proportional_cu_share(int32_t n_tenants, int32_t cu_count, const double *weight, int32_t *share) {
     return mt::proportional_cu_share(n_tenants, cu_count, weight, share);

@@ -63,7 +63,7 @@ def test_cfg2_r18_vgg16_mbv2_fp16():
         lambda ctx, lens: ctx.schedule(even_split(lens, 4), 4, concurrency=[2, 1, 3, 2], label="mixed-concurrency"),
         lambda ctx, lens: ctx.schedule(even_split(lens, 3), 3, cu_share=[64, 128, 64], label="cu-shares"),
         lambda ctx, lens: ctx.all_concurrent(flags=B.MT_SCHED_FUSE_DEPTHWISE),
-        lambda ctx, lens: ctx.all_concurrent(flags=B.MT_SCHED_FUSE_EXPAND | B.MT_SCHED_FUSE_POOL | B.MT_SCHED_PARALLEL_ISSUE),
+        lambda ctx, lens: ctx.all_concurrent(flags=B.MT_SCHED_FUSE_EXPAND | B.MT_SCHED_FUSE_POOL | B.MT_SCHED_PARALLEL_ISSUE | B.MT_SCHED_PRIORITIZE_SHORT),
         lambda ctx, lens: ctx.schedule(even_split(lens, 4), 4, cu_share=[64, 64, 128], flags=B.MT_SCHED_FUSE_EXPAND | B.MT_SCHED_FUSE_DEPTHWISE, label="fused-pairs"),
         lambda ctx, lens: ctx.schedule(even_split(lens, 2), 2, flags=B.MT_SCHED_FUSE_EXPAND | B.MT_SCHED_FUSE_POOL | B.MT_SCHED_STREAM_GRAPHS, label="graph"),
         lambda ctx, lens: ctx.schedule(even_split(lens, 3), 3, cu_share=[64, 128, 64], flags=B.MT_SCHED_STREAM_GRAPHS, label="graph"),
@@ -113,6 +113,21 @@ def test_paper_mix_r18_r34_fp16_with_share_search_and_first_op_timing():
         got, _ = mix.run(ctx.schedule(rho, 3, cu_share=shares))
         for t in range(2):
             assert_close(got[t], ref[t], "f16", "searched schedule tenant %d" % t)
+        # wave priorities: searched as the last coordinate set, and never change a bit
+        rho2, cost2, rec2, prio = ctx.search(mix.inputs, outs, 2, rounds=1, candidates=2, runs=3, warmup=1, seed=9,
+                                             flags=B.MT_SCHED_PARALLEL_ISSUE | B.MT_SCHED_FUSE_POOL, wave_priority_rounds=1)
+        assert len(prio) == 2 and all(-1 <= v <= 3 for v in prio)
+        base, _ = mix.run(ctx.sequential())
+        for pr, fl in ((prio, B.MT_SCHED_PARALLEL_ISSUE), ([3, 0], 0), ([-1, 2], B.MT_SCHED_GRAPH), ([1, -1], B.MT_SCHED_STREAM_GRAPHS)):
+            sp = ctx.schedule(rho2, 2, flags=fl, wave_priority=pr)
+            for rep in range(2):
+                got, _ = mix.run(sp)
+                if rep == 0:
+                    sp.set_wave_priority([2, 3])          # captured graphs are dropped and captured again
+            for t in range(2):
+                assert np.array_equal(got[t].view(np.uint32), base[t].view(np.uint32)), (pr, fl, t)
+        with pytest.raises(B.MtError):
+            ctx.schedule([[], []], 1, wave_priority=[4, 0])
         with pytest.raises(B.MtError):
             ctx.schedule([[], []], 1, cu_share=[4, 0])             # a share that cannot cover the 8 XCDs
         with pytest.raises(B.MtError):

@@ -92,7 +92,7 @@ def test_issue_order_examples_and_oracle():
 
 def lib_search(lens, n_stages, rounds, cands, seed, algo, cost, seed_baselines=0):
     n, P = len(lens), n_stages - 1
-    opts = B.mt_search_opts(algo, n_stages, rounds, cands, 1, 0, 0, 0, seed_baselines, 0, seed)
+    opts = B.mt_search_opts(algo, n_stages, rounds, cands, 1, 0, 0, 0, seed_baselines, 0, 0, seed)
     cap = rounds * n * cands + 2
     best = (I32 * max(1, n * P))()
     bc = C.c_double()
@@ -330,3 +330,31 @@ def test_proportional_cu_share():
                 if w[i] > w[j]:
                     assert sh[i] >= sh[j]
     assert lib.mt_proportional_cu_share(3, 256, (C.c_double * 3)(1.0, -1.0, 1.0), (I32 * 3)()) != 0
+
+
+def test_wave_priority_descent_matches_oracle_and_finds_a_separable_optimum():
+    # a separable cost with a known minimum: the descent must land on it in one round and stop after the next one
+    target = [3, 0, -1, 2]
+
+    def cost(pr):
+        return float(sum((a - b) ** 2 for a, b in zip(pr, target))) + 0.5
+
+    for start in ([0, 0, 0, 0], [-1, 3, 2, 1]):
+        best = (I32 * 4)(*start)
+        bc = C.c_double(cost(start))
+        calls, ocalls = [], []
+        fn = B.mt_share_cost_fn(lambda ptr, _u: (calls.append([ptr[i] for i in range(4)]) or cost(calls[-1])))
+        assert B.load().mt_search_wave_priority(4, 5, fn, None, best, C.byref(bc)) == 0
+        oprio, ocost = S.wave_priority_descent(4, 5, lambda pr: (ocalls.append(list(pr)) or cost(pr)), cost(start), start)
+        assert [best[i] for i in range(4)] == oprio == target
+        assert bc.value == ocost == 0.5 and calls == ocalls
+        assert len(calls) <= 2 * 4 * 5                      # one improving round, one round without change, then stop
+    # a cost that never improves keeps the start vector and evaluates one round only
+    best = (I32 * 2)(1, 2)
+    bc = C.c_double(1.0)
+    n = []
+    fn = B.mt_share_cost_fn(lambda ptr, _u: (n.append(1) or 2.0))
+    assert B.load().mt_search_wave_priority(2, 3, fn, None, best, C.byref(bc)) == 0
+    assert [best[0], best[1]] == [1, 2] and bc.value == 1.0 and len(n) == 8
+    bad = (I32 * 2)(0, 4)
+    assert B.load().mt_search_wave_priority(2, 1, fn, None, bad, C.byref(bc)) != 0
