@@ -6,24 +6,17 @@ def _runtime_environment():
     """Settings the HIP runtime reads when it initialises (the first HIP call of the process), so they are made on
     import of the package, before anything touches the GPU.
 
-    GPU_MAX_HW_QUEUES: one hardware queue per tenant stream plus the main stream.  With the HIP default of 4 the
-    streams of three tenants and the main stream already share queues with the framework's own streams, and
-    concurrent tenants then serialise (measured on MI355X, ResNet-18 + VGG-16 + MobileNetV2 all concurrent on plain
-    streams: 0.54 ms with 4 queues, 0.42 ms with 8 or 16; with one issuing thread per stream 0.56 against 0.36 ms).
-    8 rather than 16 because replaying a captured 4-stage schedule took 0.90 ms with 16 queues against 0.43 ms with
-    8.  A larger value already set is kept; MTSCHED_HW_QUEUES=<n> forces a value (for measurements).
     HIP_FORCE_DEV_KERNARG: kernel arguments in device memory; in host memory every launch starts with a read over
-    the host link (848 against 578 us for the 98 launches of that pass).  The runtime of this image already defaults
-    to it; set here so that another default does not change the numbers."""
-    want = _os.environ.get("MTSCHED_HW_QUEUES")          # explicit request (for measurements); otherwise at least 8
-    try:
-        have = int(_os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0)
-    except ValueError:
-        have = 0
+    the host link (measured on MI355X: 848 against 578 us for the 98 launches of the ResNet-18 + VGG-16 +
+    MobileNetV2 pass).  The runtime of this image already defaults to it; set here so that another default does not
+    change the numbers.
+    GPU_MAX_HW_QUEUES is left as the environment has it (the HIP default is 4): every tenant stream is created with a
+    CU mask and therefore owns a hardware queue whatever that number is.  MTSCHED_HW_QUEUES=<n> (1..32) sets it, for
+    measurements only: with more than 4 queues the replay of some captured multi-stage schedules took 1 to 2.7 ms
+    instead of 0.4 to 0.6 ms."""
+    want = _os.environ.get("MTSCHED_HW_QUEUES")
     if want:
         _os.environ["GPU_MAX_HW_QUEUES"] = str(max(1, min(32, int(want))))
-    elif have < 8:
-        _os.environ["GPU_MAX_HW_QUEUES"] = "8"
     _os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
 
 

@@ -529,7 +529,12 @@ int32_t get_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t
     hipStream_t s = nullptr;
     const int cus = ctx->prop.multiProcessorCount;
     std::vector<uint32_t> mask((cus + 31) / 32, 0u);
-    for (int j = 0; j < share; ++j) {
+    // A stream over all units is created with a full mask as well: a stream made with a CU mask owns a hardware queue,
+    // while plain streams share the few queues the runtime allots to a process (GPU_MAX_HW_QUEUES, 4 by default)
+    // with each other and with the framework's streams, and concurrent tenants on a shared queue serialise (measured:
+    // ResNet-18 + VGG-16 + MobileNetV2 all concurrent, one issuing thread per stream, 0.49 ms on plain streams with
+    // 4 queues against 0.34 ms on streams with queues of their own).
+    for (int j = 0; j < (share == 0 ? cus : share); ++j) {
         const int cu = (first_cu + j) % cus;
         mask[cu / 32] |= 1u << (cu % 32);
     }
@@ -539,8 +544,7 @@ int32_t get_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t
     // hardware slot stays taken) and replaced by the next one.
     if (!ctx->probe_buf) HIP_TRY(hipMalloc((void **)&ctx->probe_buf, 256));
     for (int attempt = 0;; ++attempt) {
-        if (share == 0) HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
-        else HIP_TRY(hipExtStreamCreateWithCUMask(&s, (uint32_t)mask.size(), mask.data()));
+        HIP_TRY(hipExtStreamCreateWithCUMask(&s, (uint32_t)mask.size(), mask.data()));
         float us = 0.f;
         int32_t rc = dispatch_latency_us(ctx, s, ctx->probe_buf, 12, &us);
         if (rc != MT_OK) { (void)hipStreamDestroy(s); return rc; }
