@@ -1362,7 +1362,8 @@ int32_t mt_run(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *con
                     if (!ctx->tenants[i]->model.ops.empty())
                         HIP_TRY(hipEventElapsedTime(&tm->first_op_done_ms[i], ctx->ev_start, ctx->ev_first[i]));
             hipEvent_t prev = ctx->ev_start;
-            for (int st = 0; st < s->n_stages; ++st) {
+            if (s->n_stages == 1) tm->stage_ms[0] = tm->makespan_ms;      // the same pair of events
+            for (int st = 0; st < s->n_stages && s->n_stages > 1; ++st) {
                 HIP_TRY(hipEventElapsedTime(&tm->stage_ms[st], prev, ctx->ev_stage[st]));
                 prev = ctx->ev_stage[st];
             }
