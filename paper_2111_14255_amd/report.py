@@ -5,10 +5,13 @@
   issue    breadth-first against depth-first issue of the same schedules, with the host issue time and the stall of
            every stream behind the main thread (Sec. III-D), and the same schedules replayed as a device graph
   mixes    sequential, all-concurrent and searched latency of the paper's tenant combinations (Tables I-II)
+  fusion   every tenant alone and all tenants together, with and without the fused launches of neighbouring operators
+           and with wave priorities (the runtime's additions to the paper's method)
 
     python -m paper_2111_14255_amd.report search --config cfg2
     python -m paper_2111_14255_amd.report issue --config cfg2
     python -m paper_2111_14255_amd.report mixes
+    python -m paper_2111_14255_amd.report fusion --config cfg2
 """
 import argparse
 import sys
@@ -193,9 +196,63 @@ def report_mixes(args):
         ctx.close()
 
 
+def report_fusion(args):
+    from synth import configs, weights
+    from . import api, binding as B
+    cfg = configs.ALL[args.config]
+    FE, FD, FP = B.MT_SCHED_FUSE_EXPAND, B.MT_SCHED_FUSE_DEPTHWISE, B.MT_SCHED_FUSE_POOL
+    print("# Fused launches and wave priorities, workload %s (%s)" % (cfg.name, " + ".join(cfg.tenants)))
+    print()
+    print("Command: `python -m paper_2111_14255_amd.report fusion --config %s`" % args.config)
+    print()
+    print("Median makespan of 60 runs, ms.  Every output is bit-identical in all columns (tests/test_gpu_ops.py, "
+          "tests/test_gpu_configs.py).  `1x1+dw`: MT_SCHED_FUSE_EXPAND, `dw+1x1`: MT_SCHED_FUSE_DEPTHWISE, `conv+pool`: "
+          "MT_SCHED_FUSE_POOL; `fused` = operators that ran inside a neighbour's launch.")
+    print()
+    print("## Every tenant alone (sequential schedule of one tenant)")
+    print()
+    print("| tenant | operators | plain | 1x1+dw | fused | dw+1x1 | fused | conv+pool | fused | 1x1+dw and conv+pool |")
+    print("|---|---|---|---|---|---|---|---|---|---|")
+    all_specs = cfg.models()
+    for which, spec in enumerate(all_specs):
+        ctx = api.Context(0)
+        model = api.Model(spec, weights.make_params(spec, cfg.seed, which))
+        ctx.register(model)
+        model.close()
+        inputs = [ctx.make_input(0, weights.make_input(spec, cfg.seed, which, cfg.input_dist))]
+        outputs = [ctx.make_output(0)]
+        row = []
+        for fl in (0, FE, FD, FP, FE | FP):
+            sched = ctx.sequential(flags=fl)
+            r = _time(ctx, sched, inputs, outputs, steps=60, warmup=8)
+            row.append((r["median"], ctx.run(sched, inputs, outputs)["n_fused"]))
+        print("| %s | %d | %.4f | %.4f | %d | %.4f | %d | %.4f | %d | %.4f |" % (
+            spec.name, ctx.lens()[0], row[0][0], row[1][0], row[1][1], row[2][0], row[2][1], row[3][0], row[3][1], row[4][0]))
+        sys.stdout.flush()
+        ctx.close()
+    print()
+    print("## All tenants concurrent (one stage, one issuing thread per stream, no CU masks)")
+    print()
+    ctx, specs, inputs, outputs = _setup(cfg)
+    n = len(specs)
+    PI = B.MT_SCHED_PARALLEL_ISSUE
+    print("| launches | wave priority per tenant | makespan | min | p90 |")
+    print("|---|---|---|---|---|")
+    rows = [("plain", 0, [0] * n), ("fused", FE | FP, [0] * n), ("fused", FE | FP, [-1] * n)]
+    rows += [("fused", FE | FP, [3 if j == i else 0 for j in range(n)]) for i in range(n)]
+    for label, fl, pr in rows:
+        sched = ctx.schedule([[] for _ in specs], 1, flags=fl | PI, wave_priority=pr)
+        r = _time(ctx, sched, inputs, outputs, steps=60, warmup=8)
+        print("| %s | %s | %.4f | %.4f | %.4f |" % (label, "/".join(str(v) for v in pr), r["median"], r["min"], r["p90"]))
+        sys.stdout.flush()
+    print()
+    print("Priority -1 = 3 for the tenant's short kernels and 0 for the others; tenants in the order %s." % ", ".join(s.name for s in specs))
+    ctx.close()
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=["search", "issue", "mixes"])
+    ap.add_argument("what", choices=["search", "issue", "mixes", "fusion"])
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--rounds", type=int, default=3)
     ap.add_argument("--candidates", type=int, default=8)
@@ -203,7 +260,7 @@ def main():
     ap.add_argument("--seeds", type=int, default=5)
     ap.add_argument("--only", default="", help="mixes: comma-separated subset of the mix names")
     args = ap.parse_args()
-    {"search": report_search, "issue": report_issue, "mixes": report_mixes}[args.what](args)
+    {"search": report_search, "issue": report_issue, "mixes": report_mixes, "fusion": report_fusion}[args.what](args)
 
 
 if __name__ == "__main__":
