@@ -52,11 +52,13 @@ enum KernelId : int32_t {
     K_GEMV = 9,             // 1x1 / fully connected layers with at most 8 output pixels: weight streaming
     K_LRN = 10,             // local response normalisation across channels
     K_ADD = 11,             // element-wise sum of two tensors, activation
+    K_IGEMM_PW = 12,        // 1x1 convolution on a small map: MFMA operands straight from memory, no LDS tiles
     K_COUNT
 };
 
 inline bool is_gemm_kernel(int32_t id) {
-    return id == K_IGEMM_128x128 || id == K_IGEMM_128x64 || id == K_IGEMM_64x64 || id == K_IGEMM_64x16 || id == K_GEMV;
+    return id == K_IGEMM_128x128 || id == K_IGEMM_128x64 || id == K_IGEMM_64x64 || id == K_IGEMM_64x16 || id == K_GEMV ||
+           id == K_IGEMM_PW;
 }
 
 // Everything a launcher needs for one operator.  Pointers are resolved per run (the first operator may

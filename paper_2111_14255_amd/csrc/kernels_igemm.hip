@@ -696,6 +696,107 @@ __global__ void __launch_bounds__(256) gemv_kernel(OpArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// ---------------------------------------------------------------------------------------------
+// 1x1 convolution on a small map (a few hundred pixels): latency bound, so no LDS tiles and no workgroup barrier in the
+// reduction.  A wave owns 16 output channels x 16 pixels; filter rows and pixel rows are contiguous along the
+// reduction index, so the 16x16x32 MFMA operands are 16-byte loads straight from memory, issued eight reduction steps
+// at a time.  SLICES = 1: the four waves of a workgroup take four channel tiles of one pixel tile and each walks the
+// whole reduction in ascending order into one accumulator (the arithmetic of the 64x16 tile kernel, bit for bit).
+// SLICES = 4 (long reductions): the four waves split the reduction of one tile into four contiguous ranges and wave 0
+// adds the partial sums in range order through LDS.
+template <typename T, int SLICES>
+__global__ void __launch_bounds__(256) pw_direct_kernel(OpArgs a) {
+    set_wave_priority(a.prio);
+    typedef typename Mma<T, 16>::Acc Acc;
+    constexpr int CH = 8;                                // reduction steps whose loads are in flight together
+    __shared__ float red[SLICES > 1 ? (SLICES - 1) * 256 : 1];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int M = a.N * a.P * a.Q;
+    const int tiles_m = (M + 15) / 16, tiles_n = (a.K + 15) / 16;
+    const int tile = SLICES == 1 ? (int)blockIdx.x * 4 + wave : (int)blockIdx.x;
+    if (tile >= tiles_m * tiles_n) return;               // SLICES = 1: a whole wave, and no barrier follows; SLICES = 4: the whole workgroup
+    const int tn = tile % tiles_n, tm = tile / tiles_n;  // neighbouring waves share the pixel tile
+    const int nsteps = a.k_pad / 32;
+    const int per = (nsteps + SLICES - 1) / SLICES;
+    const int s_begin = SLICES == 1 ? 0 : wave * per, s_end = SLICES == 1 ? nsteps : min(nsteps, s_begin + per);
+    const int frag_row = lane & 15, frag_k = (lane >> 4) * 8;
+
+    const __amdgpu_buffer_rsrc_t rsrc_x = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void *>(a.x), 0, (int)((int64_t)a.N * a.H * a.W * a.x_ct * 2), 0x00027000);
+    const __amdgpu_buffer_rsrc_t rsrc_w = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void *>(a.w), 0, (int)((int64_t)a.n_pad * a.k_pad * 2), 0x00027000);
+
+    // this lane's pixel row (operand B) and filter row (operand A)
+    const int m = tm * 16 + frag_row;
+    const uint32_t mm = m < M ? (uint32_t)m : 0u;
+    const uint32_t t1 = __umulhi(a.divpq_m, mm);
+    const int img = (int)((t1 + ((mm - t1) >> a.divpq_s1)) >> a.divpq_s2);
+    const uint32_t rem = mm - (uint32_t)img * (uint32_t)(a.P * a.Q);
+    const uint32_t t2 = __umulhi(a.divq_m, rem);
+    const int pp = (int)((t2 + ((rem - t2) >> a.divq_s1)) >> a.divq_s2);
+    const int qq = (int)(rem - (uint32_t)pp * (uint32_t)a.Q);
+    const uint32_t xrow = (uint32_t)(((((img * a.H + pp * a.sh) * a.W) + qq * a.sw) * a.x_ct + a.x_coff + frag_k) * 2);
+    const uint32_t wrow = (uint32_t)(((tn * 16 + frag_row) * a.k_pad + frag_k) * 2);
+    const float4 bias4 = *reinterpret_cast<const float4 *>(a.bias + tn * 16 + 4 * (lane >> 4));       // padded to n_pad
+
+    Acc acc;
+#pragma unroll
+    for (int v = 0; v < 4; ++v) acc[v] = 0.f;
+    for (int s0 = s_begin; s0 < s_end; s0 += CH) {
+        u32x4 wf[CH], xf[CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int s = s0 + i;
+            const bool live = s < s_end;
+            wf[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, live ? wrow + (uint32_t)(s * 64) : OOB_OFFSET, 0, 0);
+            const bool xv = live & (m < M) & (s * 32 + frag_k < a.C);
+            xf[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, xv ? xrow + (uint32_t)(s * 64) : OOB_OFFSET, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+            if (s0 + i < s_end) acc = Mma<T, 16>::run(wf[i], xf[i], acc);
+    }
+    if constexpr (SLICES > 1) {
+        if (wave > 0) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[((wave - 1) * 4 + v) * 64 + lane] = acc[v];
+        }
+        __syncthreads();
+        if (wave > 0) return;
+        for (int w = 1; w < SLICES; ++w)
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[v] += red[((w - 1) * 4 + v) * 64 + lane];
+    }
+
+    // epilogue: bias, residual, activation, one rounding
+    T *y = (T *)a.y;
+    const T *res = (const T *)a.res;
+    const int k = tn * 16 + 4 * (lane >> 4);
+    if (m >= M || k >= a.K) return;
+    float v[4] = {acc[0] + bias4.x, acc[1] + bias4.y, acc[2] + bias4.z, acc[3] + bias4.w};
+    const bool vec_ok = (a.y_ct % 4 == 0) && (a.y_coff % 4 == 0) && (a.res_ct % 4 == 0);
+    if (vec_ok && k + 4 <= a.K) {
+        if (res) {
+            float rv[4];
+            load_pack<T, 4>(res + (int64_t)m * a.res_ct + k, rv);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) v[t] += rv[t];
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) v[t] = apply_act(v[t], a.act);
+        store_pack<T, 4>(y + (int64_t)m * a.y_ct + a.y_coff + k, v);
+    } else {
+        for (int t = 0; t < 4 && k + t < a.K; ++t) {
+            float f = v[t];
+            if (res) f += to_f32(res[(int64_t)m * a.res_ct + k + t]);
+            f = apply_act(f, a.act);
+            T o;
+            from_f32(f, o);
+            y[(int64_t)m * a.y_ct + a.y_coff + k + t] = o;
+        }
+    }
+}
+
 template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES, int WK = 1>
 static void launch_cfg(const OpArgs &a, hipStream_t st) {
     const dim3 grid(a.grid_x);
@@ -720,6 +821,12 @@ static int launch_igemm_typed(const OpArgs &a, hipStream_t st) {
             else launch_cfg<T, 64, 64, 2, 2, 32, MT_STAGES_64, 1>(a, st);
             break;
         case K_IGEMM_64x16: launch_cfg<T, 64, 16, 4, 1, 16, 4>(a, st); break;
+        case K_IGEMM_PW: {
+            const dim3 grid(a.grid_x), block(256);
+            if (a.split_k > 1) hipLaunchKernelGGL((pw_direct_kernel<T, 4>), grid, block, 0, st, a);
+            else hipLaunchKernelGGL((pw_direct_kernel<T, 1>), grid, block, 0, st, a);
+            break;
+        }
         case K_GEMV: {
             const dim3 grid(a.grid_x), block(256);
             const bool stream_w = (int64_t)a.n_pad * a.k_pad * 2 >= (16ll << 20);
@@ -926,7 +1033,8 @@ static size_t dwpw_lds_bytes(int k_pad) { return (size_t)k_pad * (18 + 4) + (siz
 
 // Host check of what the fused kernel assumes; the runtime pairs two operators only when this holds.
 bool dwpw_fusable(const OpArgs &dw, const OpArgs &pw) {
-    if (dw.kernel_id != K_DWCONV || pw.kernel_id != K_IGEMM_64x16) return false;
+    // the 1x1 layer must be one whose stand-alone kernel walks the reduction in one ascending pass, as the fused kernel does
+    if (dw.kernel_id != K_DWCONV || !(pw.kernel_id == K_IGEMM_64x16 || pw.kernel_id == K_IGEMM_PW)) return false;
     if (dw.dtype != pw.dtype || (dw.dtype != MT_F16 && dw.dtype != MT_BF16)) return false;
     if (dw.R != 3 || dw.S != 3 || dw.vec != 8 || dw.C % 8 != 0 || dw.y_coff != 0 || dw.y_ct != dw.C) return false;
     if (pw.R != 1 || pw.S != 1 || pw.sh != 1 || pw.sw != 1 || pw.ph != 0 || pw.pw != 0 || pw.groups > 1) return false;
@@ -1084,7 +1192,8 @@ __global__ void __launch_bounds__(256) pwdw_kernel(OpArgs e, OpArgs d, int bands
 // Launch shape of the fused pair: the kernel variant (pixels a band may read, by reduction depth) and the number of
 // row bands, chosen so that enough workgroups exist and a band's input rows fit the variant.  False: not fusable.
 static bool pwdw_plan(const OpArgs &pw, const OpArgs &dw, int *variant, int *bands) {
-    if (pw.kernel_id != K_IGEMM_64x16 || dw.kernel_id != K_DWCONV) return false;
+    // the 1x1 layer must be one whose stand-alone kernel walks the reduction in one ascending pass, as the fused kernel does
+    if (!(pw.kernel_id == K_IGEMM_64x16 || pw.kernel_id == K_IGEMM_PW) || dw.kernel_id != K_DWCONV) return false;
     if (dw.dtype != pw.dtype || (dw.dtype != MT_F16 && dw.dtype != MT_BF16)) return false;
     if (pw.R != 1 || pw.S != 1 || pw.sh != 1 || pw.sw != 1 || pw.ph != 0 || pw.pw != 0 || pw.groups > 1) return false;
     if (pw.split_k != 1 || pw.vec_a == 0 || pw.C % 8 != 0 || pw.x_ct != pw.C || pw.x_coff != 0 || pw.res_ct != 0) return false;

@@ -74,6 +74,21 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
         p.grid_x = cdiv(cdiv(Kc, 2), 4);          // two output channels per wavefront, four wavefronts per workgroup
         return;
     }
+    const double macs_pw = (double)M * Kc * gemm_k;
+    if (p.kind == MT_CONV && p.R == 1 && p.S == 1 && p.ph == 0 && p.pw == 0 && p.vec_a != 0 && M <= 4096 && macs_pw <= 3.0e8) {
+        // 1x1 convolution on a small map: operands straight from memory, one wave per 16 x 16 output tile.  Up to eight
+        // 32-deep reduction steps a wave walks alone (split_k 1); longer reductions are cut into four ranges, one per
+        // wave of the workgroup (recorded as split_k 4; no workspace: the partial sums meet in LDS).
+        // Measured on MI355X (MobileNetV2 at batch 1, in the chain): 5.4-7.8 us per layer on the 64x16 tile.
+        p.kernel_id = K_IGEMM_PW;
+        p.n_pad = cdiv(Kc, 64) * 64;
+        const int tiles = cdiv(M, 16) * cdiv(Kc, 16);
+        p.split_k = (p.k_pad / 32 > 8) ? 4 : 1;
+        p.grid_x = p.split_k == 1 ? cdiv(tiles, 4) : tiles;
+        make_divisor((uint32_t)p.Q, p.divq_m, p.divq_s1, p.divq_s2);
+        make_divisor((uint32_t)p.P * (uint32_t)p.Q, p.divpq_m, p.divpq_s1, p.divpq_s2);
+        return;
+    }
     int bn, bm, kid;
     // Small problems (few multiply-accumulates on a small map) are latency bound: narrow pixel tiles give more,
     // shorter workgroups.  Measured on MI355X: ResNet-18 3x3 layers (115 M MACs) 9-11 us -> 7.3-8.6 us.
@@ -268,7 +283,7 @@ int32_t finalize_model(mt_model *m) {
             const size_t nb = (size_t)p.groups * (igemm ? p.n_pad : p.K);
             o.bias_off = off; off += align_up(nb * sizeof(float));
         }
-        if (p.split_k > 1) {
+        if (p.split_k > 1 && p.kernel_id != K_IGEMM_PW) {
             const int bn = p.kernel_id == K_IGEMM_64x16 || p.kernel_id == K_IGEMM_64x64 ? 64 : 128;
             const int bm = p.kernel_id == K_IGEMM_64x16 ? 16 : p.kernel_id == K_IGEMM_128x128 ? 128 : 64;
             const int M = p.N * p.P * p.Q;
@@ -754,6 +769,7 @@ const char *mt_kernel_name(int32_t id) {
         case K_IGEMM_128x64: return "igemm_128x64";
         case K_IGEMM_64x64: return "igemm_64x64";
         case K_IGEMM_64x16: return "igemm_64x16";
+        case K_IGEMM_PW: return "igemm_pointwise";
         case K_DWCONV: return "dwconv";
         case K_MAXPOOL: return "maxpool";
         case K_AVGPOOL: return "avgpool";
@@ -1074,7 +1090,7 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
             a.w = t->arena + o.w_off;
             a.bias = (const float *)(t->arena + o.bias_off);
         }
-        if (a.split_k > 1) {
+        if (a.split_k > 1 && a.kernel_id != K_IGEMM_PW) {
             a.ws = (float *)(t->arena + o.ws_off);
             a.counters = (uint32_t *)(t->arena + o.cnt_off);
             HIP_TRY(hipMemset(a.counters, 0, o.cnt_bytes));
@@ -1092,7 +1108,7 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
     for (size_t i = 0; i < nops; ++i) {
         const OpArgs &a = t->args[i];
         const int k = a.kernel_id;
-        t->short_kernel[i] = k == K_IGEMM_64x16 || k == K_DWCONV || k == K_MAXPOOL || k == K_AVGPOOL || k == K_GAP || k == K_LRN ||
+        t->short_kernel[i] = k == K_IGEMM_64x16 || k == K_IGEMM_PW || k == K_DWCONV || k == K_MAXPOOL || k == K_AVGPOOL || k == K_GAP || k == K_LRN ||
                              k == K_ADD || (k == K_GEMV && (size_t)a.n_pad * a.k_pad * 2 < ((size_t)16 << 20));
     }
     // depthwise convolution followed by the 1x1 convolution that reads it: candidates for one fused launch
@@ -1122,7 +1138,7 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
         const mt_op_desc &d0 = t->model.ops[i].d, &d1 = t->model.ops[i + 1].d;
         const OpArgs &a0 = t->args[i], &a1 = t->args[i + 1];
         if (d0.kind != MT_CONV || d1.kind != MT_MAXPOOL || d1.in_tensor != d0.out_tensor || t->writes_output[i]) continue;
-        if (!is_gemm_kernel(a0.kernel_id) || a0.kernel_id == K_GEMV || a0.groups > 1 || a0.res_ct != 0 || d0.res_tensor >= 0) continue;
+        if (!is_gemm_kernel(a0.kernel_id) || a0.kernel_id == K_GEMV || a0.kernel_id == K_IGEMM_PW || a0.groups > 1 || a0.res_ct != 0 || d0.res_tensor >= 0) continue;
         if (a0.K % 8 != 0 || a0.y_coff != 0 || a0.y_ct != a0.K || a0.P % 2 != 0 || a0.Q % 2 != 0) continue;
         if (a1.R != 2 || a1.S != 2 || a1.sh != 2 || a1.sw != 2 || a1.ph != 0 || a1.pw != 0 || a1.vec != 8) continue;
         bool only = true;                            // nothing else reads or writes the convolution's output tensor

@@ -12,6 +12,7 @@ pytestmark = pytest.mark.gpu
 
 # kernel ids as reported by mt_op_info
 DIRECT, IG128, IG64, IG16, DW, MAXP, AVGP, GAP, IG128x64, GEMV = range(10)
+PW = 12
 
 
 def g_conv(dtype, n, h, w, c, k, r, stride=1, pad=0, act="relu", bn=True, res=False, coff=0, ctot=0):
@@ -50,7 +51,14 @@ CONV_CASES = [
     ("ig64_splitk_wide", dict(n=1, h=66, w=66, c=128, k=64, r=3, pad=1, res=True), IG64),
     ("gemv_1x1_m1", dict(n=1, h=1, w=1, c=1280, k=1000, r=1, act="none"), GEMV),
     ("gemv_1x1_m5_res", dict(n=5, h=1, w=1, c=520, k=77, r=1, res=True), GEMV),
-    ("ig16_1x1_m12", dict(n=12, h=1, w=1, c=512, k=100, r=1), IG16),
+    ("pw_1x1_m12", dict(n=12, h=1, w=1, c=512, k=100, r=1), PW),
+    ("pw_stride2_res", dict(n=2, h=15, w=15, c=64, k=128, r=1, stride=2, res=True), PW),
+    ("pw_four_slices_res", dict(n=1, h=7, w=7, c=960, k=160, r=1, act="none", res=True), PW),
+    ("pw_four_slices_two_chunks_per_wave", dict(n=1, h=7, w=7, c=2048, k=72, r=1), PW),
+    ("pw_c24_partial_step_scalar_store", dict(n=1, h=9, w=9, c=24, k=18, r=1, act="none"), PW),
+    ("pw_concat_unaligned", dict(n=1, h=8, w=8, c=16, k=10, r=1, coff=3, ctot=18), PW),
+    ("pw_largest_map_64x64", dict(n=1, h=64, w=64, c=32, k=48, r=1, act="relu6"), PW),
+    ("ig64_1x1_c12_element_gather", dict(n=1, h=10, w=10, c=12, k=32, r=1), IG64),
     ("ig128x64", dict(n=1, h=128, w=128, c=8, k=100, r=3, pad=1), IG128x64),
     ("ig128", dict(n=2, h=182, w=182, c=8, k=128, r=3, pad=1, res=True), IG128),
     ("ig128_first_layer", dict(n=2, h=200, w=200, c=3, k=120, r=3, pad=1), IG128),
@@ -69,7 +77,8 @@ def _expand_cases():
         if kw["n"] * op.out_shape[0] * op.out_shape[1] > 4096:
             out.append((name, kw, kid))
             continue
-        out.append((name + "_small", kw, IG16))
+        pointwise = kw["r"] == 1 and not kw.get("pad") and kw["c"] % 8 == 0
+        out.append((name + "_small", kw, PW if pointwise else IG16))
         big = dict(kw)
         stride = kw.get("stride", 1)
         r = kw["r"] if isinstance(kw["r"], int) else max(kw["r"])
@@ -100,6 +109,8 @@ def test_conv_igemm(name, kw, kid, dtype):
             assert info.kernel_id == kid, (info.kernel_id, info.split_k, info.out_h, info.out_w)
         if "splitk" in name and not name.endswith("_big"):   # the enlarged copy has enough tiles without a split
             assert info.split_k > 1
+        if "four_slices" in name:
+            assert info.split_k == 4
         got, _ = mix.run(mix.ctx.sequential())
         assert_close(got[0], mix.oracle()[0], dtype, name)
     finally:
@@ -173,6 +184,7 @@ CHANNELWISE = [
     ("conv_groups4_scalar_gather", 2, 9, 8, 12, lambda g: g.conv(0, 20, 3, pad=1, groups=4, act="none")),
     ("conv_groups2_residual", 1, 8, 8, 32, lambda g: g.conv(g.conv(0, 32, 1), 32, 3, pad=1, groups=2, res=0)),
     ("conv_groups3_1x1_on_1x1_map", 4, 1, 1, 48, lambda g: g.conv(0, 24, 1, groups=3)),
+    ("conv_groups2_1x1_pointwise_kernel", 2, 6, 6, 64, lambda g: g.conv(0, 48, 1, groups=2)),
     ("maxpool_into_concat", 1, 9, 9, 16, lambda g: (lambda d: (g.maxpool(0, 3, 2, dst=d, c_off=8, c_tot=24),
                                                                g.conv(0, 8, 3, stride=2, dst=d, c_off=0, c_tot=24)))(g.new_tensor())),
 ]
@@ -253,7 +265,7 @@ def test_fused_depthwise_pointwise_equals_separate_launches(name, n, h, w, cin, 
     try:
         ctx = mix.ctx
         fused, tm = mix.run(ctx.sequential(flags=B.MT_SCHED_FUSE_DEPTHWISE))
-        assert tm["n_fused"] == (0 if "two_channel_tiles" in name else 1), tm     # the 960-channel case is split along K: not fused
+        assert tm["n_fused"] == (1 if hid <= 256 else 0), tm     # longer reductions are cut into four ranges: not fused
         dshape = (n,) + tuple(spec.ops[1].out_shape)
         dw_fused = ctx.read_tensor(0, d, dshape)
         plain, tm = mix.run(ctx.sequential())
@@ -340,7 +352,8 @@ POOL_BLOCKS = [
     ("igemm_128x64_batch4_56x56", 4, 56, 56, 128, 256, 3, 1, 1, "relu6", True),
     ("igemm_128x128_batch8_112x112", 8, 112, 112, 64, 128, 3, 1, 1, "relu", True),
     ("ragged_6x10_c24_k40", 3, 6, 10, 24, 40, 3, 1, 1, "none", True),
-    ("pointwise_stride2_conv", 2, 20, 12, 32, 72, 1, 2, 0, "relu", True),
+    ("pointwise_stride2_conv_large_map", 2, 140, 100, 32, 72, 1, 2, 0, "relu", True),
+    ("pointwise_small_map_direct_operand_kernel_not_fused", 2, 20, 12, 32, 72, 1, 2, 0, "relu", False),
     ("first_layer_c3_element_gather", 1, 32, 32, 3, 64, 3, 1, 1, "relu", True),
     ("odd_map_15x15_not_fused", 1, 15, 15, 64, 64, 3, 1, 1, "relu", False),
     ("k_not_multiple_of_8_not_fused", 1, 16, 16, 64, 36, 3, 1, 1, "relu", False),
