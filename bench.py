@@ -173,6 +173,8 @@ def main():
     FE = B.MT_SCHED_FUSE_EXPAND | B.MT_SCHED_FUSE_POOL
     seq_f = ctx.sequential(flags=FE)
     results["sequential+fused_pairs"] = time_schedule(ctx, torch, seq_f, inputs, outputs, args.warmup, args.steps)
+    allc_f = ctx.all_concurrent(flags=FE | B.MT_SCHED_PARALLEL_ISSUE)
+    results["all_concurrent+fused_pairs+parallel_issue"] = time_schedule(ctx, torch, allc_f, inputs, outputs, args.warmup, args.steps)
     # searched in the mode it is deployed in (one issuing thread per stream), wave priorities as the last coordinates
     t0 = time.perf_counter()
     rho_f, cost, records, shares_f, prio_f = ctx.search(inputs, outputs, cfg.n_stages, rounds=args.search_rounds,
