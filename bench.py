@@ -215,9 +215,12 @@ def main():
     roof["launches_per_step"] = f["launches"]
     roof["avg_launch_us"] = f["ms"] * 1e3 / f["launches"]
     roof["traffic"] = measured_traffic(cfg.name, dom)
+    # every family against both peaks: MFMA utilisation for the conv / FC families, achieved HBM rate for the rest
     roof["families"] = {k: {"launches": v["launches"], "us": round(v["ms"] * 1e3, 2),
                             "TFLOP/s": round(v["flops"] / (v["ms"] * 1e-3) / 1e12, 2) if v["ms"] > 0 else 0.0,
-                            "GB/s": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] > 0 else 0.0}
+                            "GB/s": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9, 1) if v["ms"] > 0 else 0.0,
+                            "frac_of_mfma_peak": round(v["flops"] / (v["ms"] * 1e-3) / 1e12 / PEAK_TFLOPS[cfg.dtype], 4) if v["ms"] > 0 else 0.0,
+                            "frac_of_hbm_peak": round(v["bytes"] / (v["ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4) if v["ms"] > 0 else 0.0}
                         for k, v in fam.items()}
     total_flops = sum(v["flops"] for v in fam.values())
     total_bytes = sum(v["bytes"] for v in fam.values())

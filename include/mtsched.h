@@ -148,6 +148,9 @@ const char *mt_kernel_name(int32_t kernel_id);
 /* Binds to HIP device `device`, creates the main stream and timing events. */
 int32_t mt_create(int32_t device, mt_ctx **out);
 int32_t mt_destroy(mt_ctx *ctx);
+/* Destroys the pooled CU-masked streams that no schedule refers to (a share search leaves its winner's streams in the
+ * pool for the schedule created next).  Synchronises the device. */
+int32_t mt_release_idle_streams(mt_ctx *ctx);
 int32_t mt_get_device_info(const mt_ctx *ctx, mt_device_info *out);
 
 /* Diagnostic: which compute units a stream restricted to `share` units starting at unit `first_cu` (same rule as
@@ -209,7 +212,10 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
  * mask bits fall on the 8 XCDs in turn and the runtime refuses a mask that leaves an XCD without a unit.
  * issue_order: MT_ISSUE_BFS issues one operator per stream round-robin (Sec. III-D), MT_ISSUE_DFS stream by stream.
  * flags: MT_SCHED_GRAPH captures the whole schedule into a HIP graph on the first run and replays it
- * afterwards (CU shares are ignored in that mode: graph nodes do not inherit stream CU masks). */
+ * afterwards (CU shares are ignored in that mode: graph nodes do not inherit stream CU masks).  A replay has no issue
+ * order, only the capture has one; a schedule of several tenants is captured in both orders on that first run, each
+ * graph is replayed three times and the faster one is kept (on this runtime one of the two is sometimes several times
+ * slower), so that run takes about ten passes. */
 #define MT_SCHED_GRAPH 1
 /* MT_SCHED_PARALLEL_ISSUE: one issuing host thread per tenant stream instead of the paper's single main thread
  * (Sec. III-D); the operators of a stage are launched by the threads of its streams concurrently, stage barriers and

@@ -182,6 +182,9 @@ class Context:
         B.check(self.lib.mt_tenant_op_info(self.h, tenant, i, C.byref(info)))
         return info
 
+    def release_idle_streams(self):
+        B.check(self.lib.mt_release_idle_streams(self.h))
+
     def device_info(self):
         d = B.mt_device_info()
         B.check(self.lib.mt_get_device_info(self.h, C.byref(d)))

@@ -98,6 +98,7 @@ SIGNATURES = {
     "mt_tenant_op_info": (_i32, [_vp, _i32, _i32, C.POINTER(mt_op_info)]),
     "mt_tenant_read_tensor": (_i32, [_vp, _i32, _i32, _vp, _sz]),
     "mt_schedule_create": (_i32, [_vp, _i32, _i32, _pi32, _pi32, _pi32, _i32, _i32, C.POINTER(_vp)]),
+    "mt_release_idle_streams": (_i32, [_vp]),
     "mt_schedule_set_wave_priority": (_i32, [_vp, C.POINTER(C.c_int32)]),
     "mt_schedule_destroy": (_i32, [_vp]),
     "mt_expand_pointers": (_i32, [_i32, _pi32, _i32, _pi32, _pi32]),
