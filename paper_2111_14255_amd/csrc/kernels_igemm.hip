@@ -812,7 +812,10 @@ template <typename T>
 static int launch_igemm_typed(const OpArgs &a, hipStream_t st) {
     switch (a.kernel_id) {
         case K_IGEMM_128x128: launch_cfg<T, 128, 128, 2, 2, 32, 2>(a, st); break;
-        case K_IGEMM_128x64: launch_cfg<T, 128, 64, 2, 2, 32, 2>(a, st); break;
+        case K_IGEMM_128x64:
+            if (a.wk == 2) launch_cfg<T, 128, 64, 2, 2, 32, 2, 2>(a, st);
+            else launch_cfg<T, 128, 64, 2, 2, 32, 2>(a, st);
+            break;
 #ifndef MT_STAGES_64
 #define MT_STAGES_64 4
 #endif

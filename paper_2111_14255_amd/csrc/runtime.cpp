@@ -124,6 +124,11 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
 #endif
     int split = 1;
     p.wk = 1;
+    // Long reductions on the 128x64 tile are bound by the matrix cores: eight waves per tile (two per SIMD) overlap LDS
+    // reads with MFMA better than four.  Measured on MI355X at batch 8: 3x3 layers of 128 / 256 / 512 channels on
+    // 112^2 / 56^2 / 28^2 maps 62.9 -> 56.5, 62.2 -> 54.9, 59.5 -> 52.1 us; the short reductions of 1x1 layers lose
+    // (17.3 -> 19.3 us) and keep four waves.  The same change on the 128x128 tile loses everywhere.
+    if (kid == K_IGEMM_128x64 && p.vec_a != 0 && nkt >= 18) p.wk = 2;
     if (kid == K_IGEMM_64x64 && p.vec_a != 0 && tiles <= 512) {
         // Few workgroups per compute unit: eight waves per tile (two per SIMD, the MFMA steps of every LDS tile split
         // between two wave groups) and only as many splits as keep about one workgroup per unit.  Measured on MI355X,

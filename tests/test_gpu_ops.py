@@ -60,6 +60,7 @@ CONV_CASES = [
     ("pw_largest_map_64x64", dict(n=1, h=64, w=64, c=32, k=48, r=1, act="relu6"), PW),
     ("ig64_1x1_c12_element_gather", dict(n=1, h=10, w=10, c=12, k=32, r=1), IG64),
     ("ig128x64", dict(n=1, h=128, w=128, c=8, k=100, r=3, pad=1), IG128x64),
+    ("ig128x64_long_reduction_eight_waves", dict(n=1, h=128, w=128, c=128, k=128, r=3, pad=1, res=True), IG128x64),
     ("ig128", dict(n=2, h=182, w=182, c=8, k=128, r=3, pad=1, res=True), IG128),
     ("ig128_first_layer", dict(n=2, h=200, w=200, c=3, k=120, r=3, pad=1), IG128),
 ]
