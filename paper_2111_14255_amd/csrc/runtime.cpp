@@ -129,7 +129,11 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
     // 112^2 / 56^2 / 28^2 maps 62.9 -> 56.5, 62.2 -> 54.9, 59.5 -> 52.1 us; the short reductions of 1x1 layers lose
     // (17.3 -> 19.3 us) and keep four waves.  The same change on the 128x128 tile loses everywhere.
     if (kid == K_IGEMM_128x64 && p.vec_a != 0 && nkt >= 18) p.wk = 2;
-    if (kid == K_IGEMM_64x64 && p.vec_a != 0 && tiles <= 512) {
+    int wk_tiles = 512;
+#ifdef MT_TUNE_ENV
+    if (const char *e = std::getenv("MTSCHED_TUNE_WK_TILES")) wk_tiles = std::atoi(e);
+#endif
+    if (kid == K_IGEMM_64x64 && p.vec_a != 0 && tiles <= wk_tiles) {
         // Few workgroups per compute unit: eight waves per tile (two per SIMD, the MFMA steps of every LDS tile split
         // between two wave groups) and only as many splits as keep about one workgroup per unit.  Measured on MI355X,
         // VGG-16 at batch 1: conv3_2 18.9 -> 13.9 us, conv4_1 15.2 -> 11.8 us, conv4_2 19.7 -> 16.1 us.
