@@ -932,18 +932,19 @@ int32_t dispatch_latency_us(mt_ctx *ctx, hipStream_t st, uint32_t *scratch, int 
 // Time per round of n rounds in which every stream of the list launches one probe kernel, all chains running at once.
 int32_t concurrent_latency_us(mt_ctx *ctx, const std::vector<hipStream_t> &streams, int n, float *us) {
     const int m = (int)streams.size();
+    if (m < 1 || m > MT_MAX_TENANTS) return fail(MT_ERR_INVALID_ARG, "stream count out of range");
     if (!ctx->probe_buf) HIP_TRY(hipMalloc((void **)&ctx->probe_buf, 256));
     for (int rep = 0; rep < 2; ++rep) {
         HIP_TRY(hipEventRecord(ctx->ev_prof[0], ctx->main_stream));
         for (int j = 0; j < m; ++j) HIP_TRY(hipStreamWaitEvent(streams[j], ctx->ev_prof[0], 0));
         for (int i = 0; i < n; ++i)
             for (int j = 0; j < m; ++j) {
-                int rc = launch_probe(ctx->probe_buf + 2 * (j % 16), 1, streams[j]);
+                int rc = launch_probe(ctx->probe_buf + 2 * j, 1, streams[j]);
                 if (rc) return fail(MT_ERR_HIP, std::string("probe launch: ") + hipGetErrorString((hipError_t)rc));
             }
         for (int j = 0; j < m; ++j) {
-            HIP_TRY(hipEventRecord(ctx->ev_done[0][j % MT_MAX_TENANTS], streams[j]));
-            HIP_TRY(hipStreamWaitEvent(ctx->main_stream, ctx->ev_done[0][j % MT_MAX_TENANTS], 0));
+            HIP_TRY(hipEventRecord(ctx->ev_done[0][j], streams[j]));
+            HIP_TRY(hipStreamWaitEvent(ctx->main_stream, ctx->ev_done[0][j], 0));
         }
         HIP_TRY(hipEventRecord(ctx->ev_prof[1], ctx->main_stream));
         HIP_TRY(hipEventSynchronize(ctx->ev_prof[1]));
@@ -1312,7 +1313,7 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
             all.clear();
             for (int st = 0; st < (per_stage ? n_stages : 1); ++st)
                 for (int i = 0; i < n_tenants; ++i)
-                    if (std::find(all.begin(), all.end(), s->stream_at[st][i]) == all.end() && all.size() < 16) all.push_back(s->stream_at[st][i]);
+                    if (std::find(all.begin(), all.end(), s->stream_at[st][i]) == all.end() && (int)all.size() < MT_MAX_TENANTS) all.push_back(s->stream_at[st][i]);
         };
         collect();
         for (int attempt = 0; attempt < 3 && all.size() > 1; ++attempt) {
