@@ -553,6 +553,45 @@ PlainPool &plain_pool(int device) {
     return pools[device];
 }
 
+// A new stream for `share` units starting at first_cu (0 = all units: a plain stream), timed; slow ones are parked.
+int32_t make_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t *out) {
+    hipStream_t s = nullptr;
+    const int cus = ctx->prop.multiProcessorCount;
+    std::vector<uint32_t> mask((cus + 31) / 32, 0u);
+    // A stream over all units is a plain stream on one of the runtime's own hardware queues (GPU_MAX_HW_QUEUES of them,
+    // dealt to the plain streams of the process in turn).  Giving it a full CU mask, and with it a queue of its own,
+    // was measured and dropped: after the queue creations and destructions of a share search such streams sometimes
+    // ran three tenants in 0.9 ms instead of 0.32 ms, the timing below not showing it.
+    for (int j = 0; j < share; ++j) {
+        const int cu = (first_cu + j) % cus;
+        mask[cu / 32] |= 1u << (cu % 32);
+    }
+    // On MI355X roughly one in four hardware queues dispatches dependent kernels about 1.5x slower than the others
+    // (measured: 16-19 us against 12 us per launch of a fixed probe kernel, in creation order 1, 5, 9, ... for masked
+    // streams; a tenant on such a queue slows the whole pass: three tenants on plain streams took 0.89 ms with one of
+    // them on the slow queue against 0.33 ms without).  A new stream is therefore timed, and a slow one is parked
+    // (kept alive so that its queue, or its turn among the runtime's queues, stays taken) and replaced by the next one.
+    if (!ctx->probe_buf) HIP_TRY(hipMalloc((void **)&ctx->probe_buf, 256));
+    PlainPool &pool = plain_pool(ctx->device);
+    for (int attempt = 0;; ++attempt) {
+        if (share == 0) HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+        else HIP_TRY(hipExtStreamCreateWithCUMask(&s, (uint32_t)mask.size(), mask.data()));
+        float us = 0.f;
+        int32_t rc = dispatch_latency_us(ctx, s, ctx->probe_buf, 12, &us);
+        if (rc != MT_OK) { (void)hipStreamDestroy(s); return rc; }
+        static const bool trace = std::getenv("MTSCHED_TRACE") != nullptr;
+        if (trace) std::fprintf(stderr, "[mtsched] stream tenant %d share %d attempt %d: %.2f us per dependent launch (best %.2f)\n", tenant, share, attempt, us, ctx->best_dispatch_us);
+        if (ctx->best_dispatch_us == 0.f || us < ctx->best_dispatch_us) ctx->best_dispatch_us = us;
+        if (us <= 1.2f * ctx->best_dispatch_us || attempt == 3) break;
+        // A parked plain stream is never released: after one was destroyed, schedules that mixed plain and masked
+        // streams ran in 0.95 ms instead of 0.35 ms.
+        if (share == 0) pool.parked.push_back(s);
+        else ctx->parked_streams.push_back(s);
+    }
+    *out = s;
+    return MT_OK;
+}
+
 // Stream of a tenant restricted to `share` compute units (0 = all).  Tenant i's units start where the
 // shares of the tenants before it end, so disjoint shares give disjoint units.
 int32_t get_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t *out, StreamKey *out_key, bool *created = nullptr) {
@@ -575,49 +614,18 @@ int32_t get_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t
             if (rc != MT_OK) return rc;
         }
     }
-    hipStream_t s = nullptr;
-    const int cus = ctx->prop.multiProcessorCount;
-    std::vector<uint32_t> mask((cus + 31) / 32, 0u);
-    // A stream over all units is a plain stream on one of the runtime's own hardware queues (GPU_MAX_HW_QUEUES of them,
-    // dealt to the plain streams of the process in turn).  Giving it a full CU mask, and with it a queue of its own,
-    // was measured and dropped: after the queue creations and destructions of a share search such streams sometimes
-    // ran three tenants in 0.9 ms instead of 0.32 ms, the timing below not showing it.
-    for (int j = 0; j < share; ++j) {
-        const int cu = (first_cu + j) % cus;
-        mask[cu / 32] |= 1u << (cu % 32);
-    }
-    // On MI355X roughly one in four hardware queues dispatches dependent kernels about 1.5x slower than the others
-    // (measured: 16-19 us against 12 us per launch of a fixed probe kernel, in creation order 1, 5, 9, ... for masked
-    // streams; a tenant on such a queue slows the whole pass: three tenants on plain streams took 0.89 ms with one of
-    // them on the slow queue against 0.33 ms without).  A new stream is therefore timed, and a slow one is parked
-    // (kept alive so that its queue, or its turn among the runtime's queues, stays taken) and replaced by the next one.
-    if (!ctx->probe_buf) HIP_TRY(hipMalloc((void **)&ctx->probe_buf, 256));
     PlainPool &pool = plain_pool(ctx->device);
-    if (share == 0 && tenant < MT_MAX_TENANTS && pool.tenant[tenant]) {
-        ctx->streams[key] = mt_ctx::StreamEntry{pool.tenant[tenant], 1};
-        *out = pool.tenant[tenant];
-        if (created) *created = false;
-        return MT_OK;
+    hipStream_t s = nullptr;
+    if (share == 0 && pool.tenant[tenant]) {
+        s = pool.tenant[tenant];                    // created by an earlier context of the process
+    } else {
+        int32_t rc = make_stream(ctx, tenant, share, first_cu, &s);
+        if (rc != MT_OK) return rc;
+        if (share == 0) pool.tenant[tenant] = s;
+        if (created) *created = true;
     }
-    for (int attempt = 0;; ++attempt) {
-        if (share == 0) HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
-        else HIP_TRY(hipExtStreamCreateWithCUMask(&s, (uint32_t)mask.size(), mask.data()));
-        float us = 0.f;
-        int32_t rc = dispatch_latency_us(ctx, s, ctx->probe_buf, 12, &us);
-        if (rc != MT_OK) { (void)hipStreamDestroy(s); return rc; }
-        static const bool trace = std::getenv("MTSCHED_TRACE") != nullptr;
-        if (trace) std::fprintf(stderr, "[mtsched] stream tenant %d share %d attempt %d: %.2f us per dependent launch (best %.2f)\n", tenant, share, attempt, us, ctx->best_dispatch_us);
-        if (ctx->best_dispatch_us == 0.f || us < ctx->best_dispatch_us) ctx->best_dispatch_us = us;
-        if (us <= 1.2f * ctx->best_dispatch_us || attempt == 3) break;
-        // A parked plain stream is never released: after one was destroyed, schedules that mixed plain and masked
-        // streams ran in 0.95 ms instead of 0.35 ms.
-        if (share == 0) pool.parked.push_back(s);
-        else ctx->parked_streams.push_back(s);
-    }
-    if (share == 0) pool.tenant[tenant] = s;
     ctx->streams[key] = mt_ctx::StreamEntry{s, 1};
     *out = s;
-    if (created) *created = true;
     return MT_OK;
 }
 
@@ -1318,69 +1326,18 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
     for (int i = 0; i < n_tenants; ++i) s->prio[i] = (flags & MT_SCHED_PRIORITIZE_SHORT) ? -1 : 0;
     const bool per_stage = (flags & MT_SCHED_SHARE_PER_STAGE) != 0;
     s->stream_at.assign(n_stages, {});
-    struct Fresh { StreamKey key; int tenant, share, first_cu, stage; };
-    std::vector<Fresh> fresh;                      // streams this call created
+    struct Acquired { StreamKey key; int share, first_cu; };
+    std::vector<std::array<Acquired, MT_MAX_TENANTS>> acq(per_stage ? n_stages : 1);
     for (int st = 0; st < (per_stage ? n_stages : 1); ++st) {
         int first_cu = 0;
         for (int i = 0; i < n_tenants; ++i) {
             const int share = (cu_share && !(flags & MT_SCHED_GRAPH)) ? cu_share[(per_stage ? st * n_tenants : 0) + i] : 0;
             StreamKey key;
-            bool created = false;
-            rc = get_stream(ctx, i, share, first_cu, &s->stream_at[st][i], &key, &created);
+            rc = get_stream(ctx, i, share, first_cu, &s->stream_at[st][i], &key);
             if (rc != MT_OK) { release_streams(s.get()); return rc; }
             s->stream_keys.push_back(key);
-            if (created) fresh.push_back(Fresh{key, i, share, first_cu, st});
+            acq[st][i] = Acquired{key, share, first_cu};
             first_cu = (first_cu + share) % cus;
-        }
-    }
-    // Streams that were just created are checked together with the other streams of the schedule: now and then a new
-    // queue (masked, or the runtime's own for a plain stream) passes the timing of get_stream alone but cannot run beside
-    // the others (measured: every stream
-    // launching one probe kernel per round takes 15-16.5 us per round on a good set and 27-30 us on a bad one, and a
-    // ResNet-18 + VGG-16 + MobileNetV2 pass then takes 1.0-1.6 ms instead of 0.4 ms).  Such a stream is parked and
-    // replaced, up to three times.
-    if (!fresh.empty()) {
-        static const bool trace = std::getenv("MTSCHED_TRACE") != nullptr;
-        std::vector<hipStream_t> all;
-        auto collect = [&]() {
-            all.clear();
-            for (int st = 0; st < (per_stage ? n_stages : 1); ++st)
-                for (int i = 0; i < n_tenants; ++i)
-                    if (std::find(all.begin(), all.end(), s->stream_at[st][i]) == all.end() && (int)all.size() < MT_MAX_TENANTS) all.push_back(s->stream_at[st][i]);
-        };
-        collect();
-        for (int attempt = 0; attempt < 3 && all.size() > 1; ++attempt) {
-            // Up to four streams run their probe kernels side by side (a round takes 14-16 us, one kernel 11-12 us); a
-            // fifth always waits for one of the others (26-30 us per round with five streams, good or not), as if four
-            // queues at most were served at a time.  Bad: a round takes more than 1.8 single-stream launches per
-            // started group of four streams, and the issuing thread itself does not explain it.
-            float us = 0.f, host_us = 0.f;
-            bool bad = false;
-            const float limit = 1.8f * ctx->best_dispatch_us * (float)((all.size() + 3) / 4);
-            for (int rep = 0; rep < 2; ++rep) {          // a single high reading is measured again before it counts
-                rc = concurrent_latency_us(ctx, all, 8, &us, &host_us);
-                if (rc != MT_OK) { release_streams(s.get()); return rc; }
-                bad = us > limit && us > 1.3f * host_us;
-                if (!bad) break;
-            }
-            if (trace) std::fprintf(stderr, "[mtsched] schedule streams: %.2f us per concurrent round (host %.2f, best single %.2f)%s\n", us, host_us, ctx->best_dispatch_us, bad ? " -> replaced" : "");
-            if (!bad) break;
-            for (const Fresh &f : fresh) {
-                auto it = ctx->streams.find(f.key);
-                if (it == ctx->streams.end() || it->second.refs != 1) continue;
-                if (f.share == 0) {
-                    PlainPool &pool = plain_pool(ctx->device);
-                    pool.parked.push_back(it->second.stream);
-                    pool.tenant[f.tenant] = nullptr;
-                } else {
-                    ctx->parked_streams.push_back(it->second.stream);
-                }
-                ctx->streams.erase(it);
-                StreamKey key;
-                rc = get_stream(ctx, f.tenant, f.share, f.first_cu, &s->stream_at[f.stage][f.tenant], &key);
-                if (rc != MT_OK) { release_streams(s.get()); return rc; }
-            }
-            collect();
         }
     }
     if (!per_stage)
@@ -1432,6 +1389,91 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
     for (int st = 0, last = -1; st < n_stages; ++st) {
         s->stages[st].prev_stage = last;
         if (!s->stages[st].items.empty()) last = st;
+    }
+    // The streams this schedule launches on are checked together: now and then a queue (masked, or the runtime's own
+    // for a plain stream) passes the timing of make_stream alone but cannot run beside the others, and a
+    // ResNet-18 + VGG-16 + MobileNetV2 pass then takes 1.0-1.6 ms instead of 0.4 ms.  Every stream launches one probe
+    // kernel per round: up to four streams run side by side (14-16.5 us per round, one kernel taking 11-12 us), a bad
+    // set of three takes 27-30 us, and five streams always take 26-30 us, as if four queues at most were served at a
+    // time.  Bad: a round takes more than 1.8 single-stream launches per started group of four streams, twice in a row,
+    // and the issuing thread's own launch time does not explain it.  The stream whose removal helps most is then parked
+    // and replaced (a masked one only if no other schedule holds it), up to three times.
+    if (!(flags & MT_SCHED_GRAPH)) {
+        static const bool trace = std::getenv("MTSCHED_TRACE") != nullptr;
+        struct Used { int row, idx; };
+        std::vector<Used> used;
+        std::vector<hipStream_t> all;
+        auto collect = [&]() {
+            used.clear();
+            all.clear();
+            for (int st = 0; st < n_stages; ++st)
+                for (int sm : s->stages[st].streams) {
+                    hipStream_t h = s->stream_at[st][sm];
+                    if (std::find(all.begin(), all.end(), h) == all.end() && (int)all.size() < MT_MAX_TENANTS) {
+                        all.push_back(h);
+                        used.push_back(Used{per_stage ? st : 0, sm});
+                    }
+                }
+        };
+        auto measure = [&](const std::vector<hipStream_t> &set, float *us, bool *bad) -> int32_t {
+            float host_us = 0.f;
+            const float limit = 1.8f * ctx->best_dispatch_us * (float)((set.size() + 3) / 4);
+            for (int rep = 0; rep < 2; ++rep) {          // a single high reading is measured again before it counts
+                int32_t r = concurrent_latency_us(ctx, set, 8, us, &host_us);
+                if (r != MT_OK) return r;
+                *bad = ctx->best_dispatch_us > 0.f && *us > limit && *us > 1.3f * host_us;
+                if (!*bad) break;
+            }
+            return MT_OK;
+        };
+        collect();
+        for (int attempt = 0; attempt < 3 && all.size() > 1; ++attempt) {
+            if (ctx->best_dispatch_us == 0.f) {         // a context that only met pooled streams so far has no reference yet
+                float us1 = 0.f;
+                if (!ctx->probe_buf) HIP_TRY(hipMalloc((void **)&ctx->probe_buf, 256));
+                rc = dispatch_latency_us(ctx, all[0], ctx->probe_buf, 12, &us1);
+                if (rc != MT_OK) { release_streams(s.get()); return rc; }
+                ctx->best_dispatch_us = us1;
+            }
+            float us = 0.f;
+            bool bad = false;
+            rc = measure(all, &us, &bad);
+            if (rc != MT_OK) { release_streams(s.get()); return rc; }
+            if (trace) std::fprintf(stderr, "[mtsched] schedule streams (%zu): %.2f us per concurrent round (best single %.2f)%s\n", all.size(), us, ctx->best_dispatch_us, bad ? " -> bad" : "");
+            if (!bad) break;
+            // leave one out: the stream without which the rest runs fastest is the one to replace
+            int culprit = (int)all.size() - 1;
+            float best_rest = 1e30f;
+            for (size_t j = 0; j < all.size() && all.size() > 2; ++j) {
+                std::vector<hipStream_t> rest;
+                for (size_t k = 0; k < all.size(); ++k)
+                    if (k != j) rest.push_back(all[k]);
+                float host_us = 0.f, r_us = 0.f;
+                rc = concurrent_latency_us(ctx, rest, 8, &r_us, &host_us);
+                if (rc != MT_OK) { release_streams(s.get()); return rc; }
+                if (r_us < best_rest) { best_rest = r_us; culprit = (int)j; }
+            }
+            const Used u = used[culprit];
+            const Acquired &aq = acq[u.row][u.idx];
+            auto it = ctx->streams.find(aq.key);
+            if (it == ctx->streams.end()) break;
+            if (aq.share != 0 && it->second.refs != 1) break;          // another schedule launches on this masked stream
+            hipStream_t fresh = nullptr;
+            rc = make_stream(ctx, u.idx, aq.share, aq.first_cu, &fresh);
+            if (rc != MT_OK) { release_streams(s.get()); return rc; }
+            if (aq.share == 0) {
+                PlainPool &pool = plain_pool(ctx->device);
+                pool.parked.push_back(it->second.stream);           // never destroyed: other schedules may hold it
+                pool.tenant[u.idx] = fresh;
+            } else {
+                ctx->parked_streams.push_back(it->second.stream);
+            }
+            if (trace) std::fprintf(stderr, "[mtsched]   stream of tenant %d (share %d) replaced\n", u.idx, aq.share);
+            it->second.stream = fresh;
+            for (int st = 0; st < n_stages; ++st)
+                if (!per_stage || st == u.row) s->stream_at[st][u.idx] = fresh;
+            collect();
+        }
     }
     ctx->live_schedules.insert(s.get());
     *out = s.release();
