@@ -306,6 +306,8 @@ typedef struct mt_search_opts {
                               never worse than stream-parallel under the same profiler. */
     int32_t cu_share_rounds; /* mt_search only: > 0 runs that many rounds of the CU-share descent (below) after the pointer search */
     int32_t wave_priority_rounds; /* mt_search only: > 0 runs that many rounds of the wave-priority descent (below) last */
+    int32_t search_concurrency; /* mt_search only: non-zero also tries 2 .. n_tenants - 1 streams per stage (the same in every
+                                   stage) under the pointers found, before shares and priorities */
     uint64_t seed;
 } mt_search_opts;
 
@@ -361,9 +363,11 @@ int32_t mt_proportional_cu_share(int32_t n_tenants, int32_t cu_count, const doub
  * under the pointers and shares found, from the vector the flags give (all 0, or all -1 with
  * MT_SCHED_PRIORITIZE_SHORT); if shares were found, a second descent runs under the unmasked result of the pointer
  * search, and that result (all-zero shares) is returned when it ends lower.  Without the descent the vector the flags
- * give is returned as it is. */
+ * give is returned as it is.
+ * best_concurrency: host [n_stages] or NULL; the stage concurrency the result was measured with (n_tenants in every
+ * stage unless opts->search_concurrency found fewer streams faster); pass it to mt_schedule_create. */
 int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *inputs, void *const *outputs,
-                  int32_t *best_pointers, int32_t *best_cu_share, int32_t *best_wave_priority, double *best_cost,
+                  int32_t *best_pointers, int32_t *best_concurrency, int32_t *best_cu_share, int32_t *best_wave_priority, double *best_cost,
                   int32_t *rec_pointers, double *rec_cost, int32_t max_records, int32_t *n_records);
 
 #ifdef __cplusplus

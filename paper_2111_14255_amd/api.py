@@ -275,24 +275,25 @@ class Context:
 
     def search(self, inputs, outputs, n_stages, rounds=2, candidates=6, runs=5, warmup=1, seed=1,
                algo=B.MT_SEARCH_COORDINATE, order=B.MT_ISSUE_BFS, flags=0, seed_baselines=True, cu_share_rounds=0,
-               wave_priority_rounds=0):
+               wave_priority_rounds=0, search_concurrency=False):
         """Returns (pointer matrix, best cost, records), then the CU shares if cu_share_rounds > 0, then the wave
-        priorities if wave_priority_rounds > 0."""
+        priorities if wave_priority_rounds > 0, then the per-stage concurrency if search_concurrency."""
         n = self.num_tenants()
         P = n_stages - 1
         opts = B.mt_search_opts(algo, n_stages, rounds, candidates, runs, warmup, order, flags, 1 if seed_baselines else 0, cu_share_rounds,
-                                wave_priority_rounds, seed)
+                                wave_priority_rounds, 1 if search_concurrency else 0, seed)
         cap = rounds * n * candidates + 2
         best = (C.c_int32 * max(1, n * P))()
         best_cost = C.c_double()
         shares = (C.c_int32 * n)()
         prio = (C.c_int32 * n)()
+        conc = (C.c_int32 * n_stages)()
         recp = (C.c_int32 * max(1, cap * n * P))()
         recc = (C.c_double * cap)()
         nrec = C.c_int32()
         ins = (C.c_void_p * n)(*[t.data_ptr() for t in inputs])
         outs = (C.c_void_p * n)(*[t.data_ptr() for t in outputs])
-        B.check(self.lib.mt_search(self.h, C.byref(opts), ins, outs, best, shares, prio, C.byref(best_cost), recp, recc, cap,
+        B.check(self.lib.mt_search(self.h, C.byref(opts), ins, outs, best, conc, shares, prio, C.byref(best_cost), recp, recc, cap,
                                   C.byref(nrec)))
         rho = [[best[i * P + j] for j in range(P)] for i in range(n)]
         records = [([[recp[(k * n + i) * P + j] for j in range(P)] for i in range(n)], recc[k]) for k in range(min(nrec.value, cap))]
@@ -301,6 +302,8 @@ class Context:
             out += ([shares[i] for i in range(n)],)
         if wave_priority_rounds > 0:
             out += ([prio[i] for i in range(n)],)
+        if search_concurrency:
+            out += ([conc[i] for i in range(n_stages)],)
         return out
 
     def close(self):

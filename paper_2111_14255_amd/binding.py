@@ -64,7 +64,7 @@ class mt_search_opts(C.Structure):
     _fields_ = [("algo", C.c_int32), ("n_stages", C.c_int32), ("rounds", C.c_int32), ("candidates", C.c_int32),
                 ("runs", C.c_int32), ("warmup", C.c_int32), ("issue_order", C.c_int32), ("flags", C.c_int32),
                 ("seed_baselines", C.c_int32), ("cu_share_rounds", C.c_int32), ("wave_priority_rounds", C.c_int32),
-                ("seed", C.c_uint64)]
+                ("search_concurrency", C.c_int32), ("seed", C.c_uint64)]
 
 
 mt_cost_fn = C.CFUNCTYPE(C.c_double, C.POINTER(C.c_int32), C.c_void_p)
@@ -108,7 +108,7 @@ SIGNATURES = {
     "mt_search_pointers": (_i32, [_i32, _pi32, C.POINTER(mt_search_opts), mt_cost_fn, _vp, _pi32, _pd, _pi32, _pd, _i32, _pi32]),
     "mt_search_cu_share": (_i32, [_i32, _i32, _i32, mt_share_cost_fn, _vp, _pi32, _pd]),
     "mt_proportional_cu_share": (_i32, [_i32, _i32, _pd, _pi32]),
-    "mt_search": (_i32, [_vp, C.POINTER(mt_search_opts), C.POINTER(_vp), C.POINTER(_vp), _pi32, _pi32, _pi32, _pd, _pi32, _pd, _i32, _pi32]),
+    "mt_search": (_i32, [_vp, C.POINTER(mt_search_opts), C.POINTER(_vp), C.POINTER(_vp), _pi32, _pi32, _pi32, _pi32, _pd, _pi32, _pd, _i32, _pi32]),
     "mt_search_wave_priority": (_i32, [_i32, _i32, mt_share_cost_fn, _vp, _pi32, _pd]),
 }
 

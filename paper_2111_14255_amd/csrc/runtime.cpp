@@ -1645,6 +1645,7 @@ struct ProfileCost {
     const int32_t *pointers = nullptr;     // fixed while shares are searched
     const int32_t *cu_share = nullptr;     // fixed while pointers are searched
     const int32_t *prio = nullptr;         // wave priorities applied to every candidate (NULL: what the flags give)
+    const int32_t *conc = nullptr;         // per-stage concurrency applied to every candidate (NULL: one stream per tenant)
     int32_t rc = MT_OK;
 };
 
@@ -1662,7 +1663,7 @@ double profile_schedule(ProfileCost *pc, const int32_t *pointers, const int32_t 
         std::fprintf(stderr, "\n");
         std::fflush(stderr);
     }
-    pc->rc = mt_schedule_create(pc->ctx, pc->n_tenants, pc->o->n_stages, pointers, nullptr, cu_share, pc->o->issue_order,
+    pc->rc = mt_schedule_create(pc->ctx, pc->n_tenants, pc->o->n_stages, pointers, pc->conc, cu_share, pc->o->issue_order,
                                 pc->o->flags, &s);
     if (pc->rc == MT_OK && pc->prio) pc->rc = mt_schedule_set_wave_priority(s, pc->prio);
     if (pc->rc != MT_OK) { if (s) mt_schedule_destroy(s); return 1e30; }
@@ -1706,7 +1707,7 @@ double profile_prio_cost(const int32_t *prio, void *user) {
 }  // namespace
 
 int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *inputs, void *const *outputs,
-                  int32_t *best_pointers, int32_t *best_cu_share, int32_t *best_wave_priority, double *best_cost,
+                  int32_t *best_pointers, int32_t *best_concurrency, int32_t *best_cu_share, int32_t *best_wave_priority, double *best_cost,
                   int32_t *rec_pointers, double *rec_cost, int32_t max_records, int32_t *n_records) {
     if (!ctx || !opts || !inputs || !outputs || !best_pointers) return fail(MT_ERR_INVALID_ARG, "NULL argument");
     if (opts->runs < 1 || opts->warmup < 0) return fail(MT_ERR_INVALID_ARG, "runs must be >= 1 and warmup >= 0");
@@ -1722,6 +1723,23 @@ int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *in
                                  max_records, n_records);
     if (pc.rc != MT_OK) return pc.rc;
     if (rc != MT_OK) return rc;
+    // Streams in use at a time, the same number in every stage: on this machine about four queues are served at once
+    // (the main stream is one of them), so with five tenants or more fewer streams than tenants can be faster.
+    int32_t conc[MT_MAX_STAGES];
+    for (int st = 0; st < opts->n_stages; ++st) conc[st] = n;
+    if (opts->search_concurrency && n > 2) {
+        int32_t trial[MT_MAX_STAGES];
+        int best_c = n;
+        pc.conc = trial;
+        for (int c = 2; c < n; ++c) {
+            for (int st = 0; st < opts->n_stages; ++st) trial[st] = c;
+            const double cc = profile_schedule(&pc, best_pointers, nullptr);
+            if (pc.rc != MT_OK) return pc.rc;
+            if (cc < cost) { cost = cc; best_c = c; }
+        }
+        for (int st = 0; st < opts->n_stages; ++st) conc[st] = best_c;
+        pc.conc = best_c == n ? nullptr : conc;
+    }
     int32_t shares[MT_MAX_TENANTS] = {0};
     const double unmasked_cost = cost;
     std::vector<int32_t> unmasked_pointers(best_pointers, best_pointers + (size_t)n * (opts->n_stages - 1));
@@ -1840,6 +1858,7 @@ int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *in
         }
     }
     if (best_wave_priority) std::memcpy(best_wave_priority, prio, sizeof(int32_t) * n);
+    if (best_concurrency) std::memcpy(best_concurrency, conc, sizeof(int32_t) * opts->n_stages);
     if (best_cu_share) std::memcpy(best_cu_share, shares, sizeof(int32_t) * n);
     if (best_cost) *best_cost = cost;
     return MT_OK;

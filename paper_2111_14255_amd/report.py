@@ -165,12 +165,12 @@ def report_mixes(args):
     print("Command: `python -m paper_2111_14255_amd.report mixes --rounds %d --candidates %d --runs %d`" % (args.rounds, args.candidates, args.runs))
     print()
     print("Median makespan of 40 runs, ms; speed-up = sequential / schedule, as the paper's tables print it.  "
-          "`searched` = coordinate descent over the pointer matrix (4 stages); `+shares` adds the per-tenant CU-share "
-          "descent and issues with one host thread per stream.  The paper's own numbers (other GPUs, other kernels) are "
+          "`searched` = coordinate descent over the pointer matrix (4 stages); `+shares` searches the number of streams in "
+          "use per stage and the per-tenant CU shares as well, in the mode it is then run in: one issuing host thread per stream.  The paper's own numbers (other GPUs, other kernels) are "
           "context only: its coordinate-descent speed-ups for these rows are 1.37, 1.49, 1.49, 1.31, 1.37, 1.63, 1.72 on Titan V.")
     print()
-    print("| tenants | launches | sequential | all-concurrent | searched | searched+graph | searched+shares | shares | best speed-up | search s |")
-    print("|---|---|---|---|---|---|---|---|---|---|")
+    print("| tenants | launches | sequential | all-concurrent | searched | searched+graph | searched+shares | streams | shares | best speed-up | search s |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|")
     names = args.only.split(",") if args.only else list(configs.PAPER_MIXES)
     for name in names:
         cfg = configs.ALL[name]
@@ -184,14 +184,16 @@ def report_mixes(args):
         rho_g, _, _ = ctx.search(inputs, outputs, cfg.n_stages, rounds=args.rounds, candidates=args.candidates, runs=args.runs,
                                  warmup=1, seed=cfg.seed, flags=B.MT_SCHED_GRAPH)
         s2 = _time(ctx, ctx.schedule(rho_g, cfg.n_stages, flags=B.MT_SCHED_GRAPH), inputs, outputs)
-        rho_s, _, _, shares = ctx.search(inputs, outputs, cfg.n_stages, rounds=args.rounds, candidates=args.candidates,
-                                         runs=args.runs, warmup=1, seed=cfg.seed, cu_share_rounds=2)
+        rho_s, _, _, shares, conc = ctx.search(inputs, outputs, cfg.n_stages, rounds=args.rounds, candidates=args.candidates,
+                                               runs=args.runs, warmup=1, seed=cfg.seed, cu_share_rounds=2,
+                                               search_concurrency=True, flags=B.MT_SCHED_PARALLEL_ISSUE)
         dt = time.perf_counter() - t0
-        s3 = _time(ctx, ctx.schedule(rho_s, cfg.n_stages, cu_share=shares, flags=B.MT_SCHED_PARALLEL_ISSUE), inputs, outputs)
+        s3 = _time(ctx, ctx.schedule(rho_s, cfg.n_stages, concurrency=conc, cu_share=shares, flags=B.MT_SCHED_PARALLEL_ISSUE),
+                   inputs, outputs)
         best = min(s1["median"], s2["median"], s3["median"])
-        print("| %s | %d | %.4f | %.4f | %.4f | %.4f | %.4f | %s | %.2f | %.1f |" % (
+        print("| %s | %d | %.4f | %.4f | %.4f | %.4f | %.4f | %d | %s | %.2f | %.1f |" % (
             " + ".join(cfg.tenants), sum(ctx.lens()), seq["median"], allc["median"], s1["median"], s2["median"], s3["median"],
-            "/".join(str(v) for v in shares), seq["median"] / best, dt))
+            conc[0], "/".join(str(v) for v in shares), seq["median"] / best, dt))
         sys.stdout.flush()
         ctx.close()
 

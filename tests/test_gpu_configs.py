@@ -54,7 +54,18 @@ def check_config(name, extra_schedules=()):
 def test_cfg1_tiny_fp32():
     # the 2-stage interleave: stage 1 = A ops 1-4 + all of B, stage 2 = A ops 5-8 + all of C
     mix = check_config("cfg1", [lambda ctx, lens: ctx.schedule([[4], [5], [0]], 2, label="interleave")])
-    mix.close()
+    try:
+        # the number of streams in use per stage as a searched coordinate
+        ctx = mix.ctx
+        outs = [ctx.make_output(t) for t in range(3)]
+        rho, cost, rec, conc = ctx.search(mix.inputs, outs, 2, rounds=1, candidates=2, runs=3, warmup=1, seed=5, search_concurrency=True)
+        assert len(conc) == 2 and conc[0] == conc[1] and 2 <= conc[0] <= 3
+        base, _ = mix.run(ctx.sequential())
+        got, _ = mix.run(ctx.schedule(rho, 2, concurrency=conc))
+        for t in range(3):
+            assert np.array_equal(got[t].view(np.uint32), base[t].view(np.uint32))
+    finally:
+        mix.close()
 
 
 def test_cfg2_r18_vgg16_mbv2_fp16():

@@ -92,7 +92,7 @@ def test_issue_order_examples_and_oracle():
 
 def lib_search(lens, n_stages, rounds, cands, seed, algo, cost, seed_baselines=0):
     n, P = len(lens), n_stages - 1
-    opts = B.mt_search_opts(algo, n_stages, rounds, cands, 1, 0, 0, 0, seed_baselines, 0, 0, seed)
+    opts = B.mt_search_opts(algo, n_stages, rounds, cands, 1, 0, 0, 0, seed_baselines, 0, 0, 0, seed)
     cap = rounds * n * cands + 2
     best = (I32 * max(1, n * P))()
     bc = C.c_double()
