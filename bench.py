@@ -103,8 +103,8 @@ def main():
                          "64 MiB elementwise copy that calibrates byte counters; this is the command profiled under rocprofv3")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (--gpus 1); tenants would be sharded across GPUs "
-              "by bin-packing, see DESIGN.md", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (--gpus 1); with more, independent tenants would be "
+              "bin-packed across GPUs by their profiled latency, each GPU running its own schedule", file=sys.stderr)
         sys.exit(2)
 
     from paper_2111_14255_amd import api, binding as B     # first: sets the runtime's environment before HIP initialises
