@@ -37,7 +37,9 @@ def time_schedule(ctx, torch, sched, inputs, outputs, warmup, steps):
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
     mk.sort()
-    return {"wall_ms_per_step": wall_ms, "makespan_ms_mean": sum(mk) / len(mk), "makespan_ms_min": mk[0],
+    mean = sum(mk) / len(mk)
+    return {"wall_ms_per_step": wall_ms, "makespan_ms_mean": mean, "makespan_ms_min": mk[0],
+            "makespan_ms_stdev": (sum((v - mean) ** 2 for v in mk) / max(1, len(mk) - 1)) ** 0.5,
             "makespan_ms_median": mk[len(mk) // 2], "makespan_ms_p90": mk[(len(mk) * 9) // 10 if len(mk) > 1 else 0],
             "host_issue_ms_mean": sum(issue) / len(issue)}
 
@@ -225,6 +227,13 @@ def main():
                         for k, v in fam.items()}
     total_flops = sum(v["flops"] for v in fam.values())
     total_bytes = sum(v["bytes"] for v in fam.values())
+    # what this chip sustains on the simplest possible kernels, next to the published peaks the fractions above use
+    measured = {"mfma_%s_TFLOP/s" % cfg.dtype: round(ctx.peak_mfma(cfg.dtype), 1) if cfg.dtype != "f32" else None,
+                "hbm_copy_GB/s": round(ctx.peak_stream("copy"), 1),
+                "hbm_read_GB/s": round(ctx.peak_stream("read"), 1)}
+    roof["measured_peaks"] = measured
+    m_peak = measured["mfma_%s_TFLOP/s" % cfg.dtype] if roof["bound"] == "mfma" else measured["hbm_read_GB/s"]
+    roof["frac_of_measured_peak"] = achieved / m_peak if m_peak else None
 
     out = {
         "metric": "aggregate images/s of the multi-tenant forward pass under the searched schedule (makespan in ms_per_step)",

@@ -164,6 +164,19 @@ int32_t mt_probe_cu_mask(mt_ctx *ctx, int32_t share, int32_t first_cu, int32_t n
  * stream waits for the stream's completion event (the pattern of a stage).  us_per_launch: host [n_streams]. */
 int32_t mt_probe_dispatch_latency(mt_ctx *ctx, int32_t n_streams, int32_t share, int32_t n_launches, float *us_per_launch);
 
+/* Diagnostic: what the chip sustains on a register-only loop of 32x32x16 matrix instructions (dtype MT_F16 or MT_BF16;
+ * two workgroups of four waves per compute unit, four independent accumulators per wave, 4 * iters instructions per
+ * wave; iters 1 .. 2^20).  tflops: host scalar, 2 * 32 * 32 * 16 flops per instruction over the kernel's event time.
+ * Allocates and frees a small device buffer.  The figure to hold next to the published peak when a kernel's fraction
+ * of the matrix-core roofline is read. */
+int32_t mt_probe_peak_mfma(mt_ctx *ctx, int32_t dtype, int32_t iters, float *tflops);
+/* Diagnostic: sustained device-memory rate of a plain kernel.  mode 0 copies `bytes` bytes (16-byte pieces, grid-stride,
+ * eight pieces in flight per thread, groups_per_unit workgroups of 256 threads per compute unit, 1 .. 256) and counts
+ * 2 * bytes per launch, mode 1 only reads them and counts bytes.  bytes: multiple of 16 between 1 MiB and 8 GiB (choose
+ * it well above the last-level cache); reps launches (1 .. 1000) are timed after as many warm-up launches.
+ * gbytes_per_s: host scalar.  Allocates and frees its buffers (MT_ERR_OUT_OF_MEMORY if it cannot). */
+int32_t mt_probe_peak_stream(mt_ctx *ctx, int32_t mode, size_t bytes, int32_t groups_per_unit, int32_t reps, float *gbytes_per_s);
+
 /* ---- model construction (host only; no GPU needed) ----------------------------------- */
 /* Operators are added in the serial order that becomes the model's sequence M_i (Eq. 1). */
 int32_t mt_model_begin(int32_t dtype, int32_t batch, int32_t in_h, int32_t in_w, int32_t in_c, mt_model **out);

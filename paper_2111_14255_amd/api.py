@@ -185,6 +185,18 @@ class Context:
     def release_idle_streams(self):
         B.check(self.lib.mt_release_idle_streams(self.h))
 
+    def peak_mfma(self, dtype="f16", iters=100000):
+        """TFLOP/s of a register-only loop of 32x32x16 matrix instructions on every unit (mt_probe_peak_mfma)."""
+        v = C.c_float()
+        B.check(self.lib.mt_probe_peak_mfma(self.h, _DT[dtype], iters, C.byref(v)))
+        return v.value
+
+    def peak_stream(self, mode="copy", nbytes=1 << 32, reps=10, groups_per_unit=2):
+        """GB/s of a plain copy (read + written bytes) or read kernel over `nbytes` bytes (mt_probe_peak_stream)."""
+        v = C.c_float()
+        B.check(self.lib.mt_probe_peak_stream(self.h, {"copy": 0, "read": 1}[mode], nbytes, groups_per_unit, reps, C.byref(v)))
+        return v.value
+
     def device_info(self):
         d = B.mt_device_info()
         B.check(self.lib.mt_get_device_info(self.h, C.byref(d)))

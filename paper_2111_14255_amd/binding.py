@@ -82,6 +82,8 @@ SIGNATURES = {
     "mt_get_device_info": (_i32, [_vp, C.POINTER(mt_device_info)]),
     "mt_probe_dispatch_latency": (_i32, [_vp, _i32, _i32, _i32, _pf]),
     "mt_probe_cu_mask": (_i32, [_vp, _i32, _i32, _i32, C.POINTER(C.c_uint32)]),
+    "mt_probe_peak_mfma": (_i32, [_vp, _i32, _i32, _pf]),
+    "mt_probe_peak_stream": (_i32, [_vp, _i32, C.c_size_t, _i32, _i32, _pf]),
     "mt_model_begin": (_i32, [_i32, _i32, _i32, _i32, _i32, C.POINTER(_vp)]),
     "mt_model_add_op": (_i32, [_vp, C.POINTER(mt_op_desc), _pi32]),
     "mt_model_end": (_i32, [_vp]),

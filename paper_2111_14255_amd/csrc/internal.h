@@ -117,5 +117,9 @@ bool pwdw_fusable(const OpArgs &pw, const OpArgs &dw);
 int launch_pwdw(const OpArgs &pw, const OpArgs &dw, void *stream);   // 1x1 convolution + the depthwise 3x3 that reads it on a small map, one launch
 int launch_fill_u32(uint32_t *p, size_t n, uint32_t v, void *stream);
 int launch_probe(uint32_t *out, int n_groups, void *stream);
+// Diagnostics: a register-only loop of 4 * iters 32x32x16 matrix instructions per wave (sink: n_groups * 256 floats), and
+// a 16-byte grid-stride copy (mode 0) or read (mode 1; dst then holds n_groups * 256 words) of `bytes` bytes.
+int launch_peak_mfma(int dtype, float *sink, int n_groups, int iters, void *stream);
+int launch_peak_stream(int mode, const void *src, void *dst, size_t bytes, int n_groups, void *stream);
 
 }  // namespace mt

@@ -20,6 +20,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <type_traits>
 #include <utility>
 
 #include "internal.h"
@@ -1238,6 +1239,77 @@ int launch_pwdw(const OpArgs &pw, const OpArgs &dw, void *stream) {
     };
     if (pw.dtype == MT_F16) go.template operator()<f16>();
     else go.template operator()<bf16>();
+    return (int)hipGetLastError();
+}
+
+// ---- what the chip sustains (diagnostics) -----------------------------------------------------------------------
+// A loop of 32x32x16 matrix instructions on registers alone: four independent accumulators per wave, so that the
+// issue of one never waits for the result of the one before.  Operands are small non-trivial values (all-zero inputs
+// would draw less power than real work and let the clock run higher); every lane folds its accumulators into one
+// word at the end, which keeps the loop alive.
+template <typename T>
+__global__ void __launch_bounds__(256) peak_mfma_kernel(float *sink, int iters) {
+    const uint32_t lane = threadIdx.x;
+    u32x4 a, b;
+    const uint32_t expo = std::is_same<T, f16>::value ? 0x2000u : 0x3c00u;    // 2^-7 in either format, mantissa below
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t h0 = ((lane * 2654435761u + i * 40503u) >> 20) & 0x7fu, h1 = ((lane * 2246822519u + i * 9973u) >> 21) & 0x7fu;
+        a[i] = (expo | h0) | ((expo | h1) << 16);
+        b[i] = (expo | h1) | ((expo | h0) << 16);
+    }
+    typename Mma<T, 32>::Acc acc0 = {}, acc1 = {}, acc2 = {}, acc3 = {};
+    for (int it = 0; it < iters; ++it) {
+        acc0 = Mma<T, 32>::run(a, b, acc0);
+        acc1 = Mma<T, 32>::run(b, a, acc1);
+        acc2 = Mma<T, 32>::run(a, a, acc2);
+        acc3 = Mma<T, 32>::run(b, b, acc3);
+    }
+    float v = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v += acc0[i] + acc1[i] + acc2[i] + acc3[i];
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = v;
+}
+
+// mode 0: dst[i] = src[i] in 16-byte pieces, grid-stride, eight pieces in flight per thread; mode 1: reads only and
+// folds what it read into one word per thread (written to dst, which then needs gridDim.x * 256 words).
+template <int MODE>
+__global__ void __launch_bounds__(256) peak_stream_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, size_t n16) {
+    constexpr int U = 8;
+    const size_t stride = (size_t)gridDim.x * 256;
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    u32x4 s = {0u, 0u, 0u, 0u};
+    for (; i + (U - 1) * stride < n16; i += U * stride) {
+        u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(src + i + u * stride);
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (MODE == 0) __builtin_nontemporal_store(v[u], dst + i + u * stride);
+            else s ^= v[u];
+        }
+    }
+    for (; i < n16; i += stride) {
+        const u32x4 v = __builtin_nontemporal_load(src + i);
+        if (MODE == 0) __builtin_nontemporal_store(v, dst + i);
+        else s ^= v;
+    }
+    if (MODE == 1) ((uint32_t *)dst)[(size_t)blockIdx.x * 256 + threadIdx.x] = s[0] ^ s[1] ^ s[2] ^ s[3];
+}
+
+int launch_peak_mfma(int dtype, float *sink, int n_groups, int iters, void *stream) {
+    hipStream_t st = (hipStream_t)stream;
+    if (dtype == MT_F16) hipLaunchKernelGGL(peak_mfma_kernel<f16>, dim3((unsigned)n_groups), dim3(256), 0, st, sink, iters);
+    else if (dtype == MT_BF16) hipLaunchKernelGGL(peak_mfma_kernel<bf16>, dim3((unsigned)n_groups), dim3(256), 0, st, sink, iters);
+    else return (int)hipErrorInvalidValue;
+    return (int)hipGetLastError();
+}
+
+int launch_peak_stream(int mode, const void *src, void *dst, size_t bytes, int n_groups, void *stream) {
+    hipStream_t st = (hipStream_t)stream;
+    if (bytes % 16 != 0 || n_groups < 1) return (int)hipErrorInvalidValue;
+    if (mode == 0) hipLaunchKernelGGL(peak_stream_kernel<0>, dim3((unsigned)n_groups), dim3(256), 0, st, (const u32x4 *)src, (u32x4 *)dst, bytes / 16);
+    else hipLaunchKernelGGL(peak_stream_kernel<1>, dim3((unsigned)n_groups), dim3(256), 0, st, (const u32x4 *)src, (u32x4 *)dst, bytes / 16);
     return (int)hipGetLastError();
 }
 

@@ -1025,6 +1025,62 @@ int32_t mt_probe_dispatch_latency(mt_ctx *ctx, int32_t n_streams, int32_t share,
     return rc;
 }
 
+int32_t mt_probe_peak_mfma(mt_ctx *ctx, int32_t dtype, int32_t iters, float *tflops) {
+    if (!ctx || !tflops) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (dtype != MT_F16 && dtype != MT_BF16) return fail(MT_ERR_INVALID_ARG, "the matrix-instruction loop exists for fp16 and bf16");
+    if (iters < 1 || iters > (1 << 20)) return fail(MT_ERR_INVALID_ARG, "iters out of range (1 .. 2^20)");
+    HIP_TRY(hipSetDevice(ctx->device));
+    const int n_groups = ctx->prop.multiProcessorCount * 2;        // two workgroups of four waves per unit: two waves per SIMD
+    float *sink = nullptr;
+    HIP_TRY(hipMalloc((void **)&sink, (size_t)n_groups * 256 * sizeof(float)));
+    int32_t rc = MT_OK;
+    float ms = 0;
+    for (int rep = 0; rep < 2 && rc == MT_OK; ++rep) {             // first pass warms up
+        hipError_t e = hipEventRecord(ctx->ev_prof[0], ctx->main_stream);
+        if (e == hipSuccess) e = (hipError_t)launch_peak_mfma(dtype, sink, n_groups, iters, ctx->main_stream);
+        if (e == hipSuccess) e = hipEventRecord(ctx->ev_prof[1], ctx->main_stream);
+        if (e == hipSuccess) e = hipEventSynchronize(ctx->ev_prof[1]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ctx->ev_prof[0], ctx->ev_prof[1]);
+        if (e != hipSuccess) rc = fail(MT_ERR_HIP, std::string("peak probe: ") + hipGetErrorString(e));
+    }
+    (void)hipFree(sink);
+    if (rc != MT_OK) return rc;
+    const double flops = (double)n_groups * 4 /*waves*/ * 4 /*accumulators*/ * (double)iters * 2.0 * 32 * 32 * 16;
+    *tflops = (float)(flops / (ms * 1e-3) / 1e12);
+    return MT_OK;
+}
+
+int32_t mt_probe_peak_stream(mt_ctx *ctx, int32_t mode, size_t bytes, int32_t groups_per_unit, int32_t reps, float *gbytes_per_s) {
+    if (!ctx || !gbytes_per_s) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (mode != 0 && mode != 1) return fail(MT_ERR_INVALID_ARG, "mode is 0 (copy) or 1 (read)");
+    if (bytes < ((size_t)1 << 20) || bytes > ((size_t)8 << 30) || bytes % 16 != 0)
+        return fail(MT_ERR_INVALID_ARG, "bytes must be a multiple of 16 between 1 MiB and 8 GiB");
+    if (reps < 1 || reps > 1000) return fail(MT_ERR_INVALID_ARG, "reps out of range (1 .. 1000)");
+    if (groups_per_unit < 1 || groups_per_unit > 256) return fail(MT_ERR_INVALID_ARG, "groups_per_unit out of range (1 .. 256)");
+    HIP_TRY(hipSetDevice(ctx->device));
+    const int n_groups = ctx->prop.multiProcessorCount * groups_per_unit;
+    const size_t dst_bytes = mode == 0 ? bytes : (size_t)n_groups * 256 * sizeof(uint32_t);
+    void *src = nullptr, *dst = nullptr;
+    HIP_TRY(hipMalloc(&src, bytes));
+    if (hipMalloc(&dst, dst_bytes) != hipSuccess) { (void)hipFree(src); return fail(MT_ERR_OUT_OF_MEMORY, "peak probe: destination buffer"); }
+    hipError_t e = (hipError_t)launch_fill_u32((uint32_t *)src, bytes / 4, 0x3c003c00u, ctx->main_stream);
+    float ms = 0;
+    for (int rep = 0; rep < 2 && e == hipSuccess; ++rep) {         // first pass warms up
+        e = hipEventRecord(ctx->ev_prof[0], ctx->main_stream);
+        for (int i = 0; i < reps && e == hipSuccess; ++i) e = (hipError_t)launch_peak_stream(mode, src, dst, bytes, n_groups, ctx->main_stream);
+        if (e == hipSuccess) e = hipEventRecord(ctx->ev_prof[1], ctx->main_stream);
+        if (e == hipSuccess) e = hipEventSynchronize(ctx->ev_prof[1]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ctx->ev_prof[0], ctx->ev_prof[1]);
+    }
+    (void)hipDeviceSynchronize();
+    (void)hipFree(src);
+    (void)hipFree(dst);
+    if (e != hipSuccess) return fail(MT_ERR_HIP, std::string("peak probe: ") + hipGetErrorString(e));
+    const double moved = (double)bytes * (mode == 0 ? 2.0 : 1.0) * reps;
+    *gbytes_per_s = (float)(moved / (ms * 1e-3) / 1e9);
+    return MT_OK;
+}
+
 // ---- model ---------------------------------------------------------------------------------
 int32_t mt_model_begin(int32_t dtype, int32_t batch, int32_t in_h, int32_t in_w, int32_t in_c, mt_model **out) {
     if (!out) return fail(MT_ERR_INVALID_ARG, "out is NULL");

@@ -1,0 +1,58 @@
+"""The machine probes of the library on the GPU: sustained matrix-instruction and memory rates (the measured figures
+that stand next to the published peaks in a roofline), compute-unit masks and dispatch latency."""
+import ctypes as C
+
+import pytest
+
+from paper_2111_14255_amd import api, binding as B
+
+pytestmark = pytest.mark.gpu
+
+
+def test_peak_probes_are_sane_and_reject_bad_arguments():
+    ctx = api.Context(0)
+    try:
+        for dt in ("f16", "bf16"):
+            print("peak mfma", dt, flush=True)
+            tf = ctx.peak_mfma(dt, 20000)
+            print("  %.0f TFLOP/s" % tf, flush=True)
+            assert 300.0 < tf < 2500.0 * 1.05       # a register-only loop cannot beat the published dense peak
+        for mode in ("copy", "read"):
+            print("peak stream", mode, flush=True)
+            gb = ctx.peak_stream(mode, 1 << 30, reps=4)
+            print("  %.0f GB/s" % gb, flush=True)
+            assert 1500.0 < gb < 8000.0 * 1.05       # 1 GiB per launch is four times the last-level cache
+        with pytest.raises(B.MtError):
+            ctx.peak_mfma("f32", 10)
+        with pytest.raises(B.MtError):
+            ctx.peak_mfma("f16", 0)
+        with pytest.raises(B.MtError):
+            ctx.peak_stream("copy", 1000, reps=1)
+        with pytest.raises(B.MtError):
+            ctx.peak_stream("read", (1 << 20) + 8, reps=1)
+        with pytest.raises(B.MtError):
+            ctx.peak_stream("read", 1 << 20, reps=1, groups_per_unit=0)
+    finally:
+        ctx.close()
+
+
+def test_cu_mask_probe_and_dispatch_latency():
+    ctx = api.Context(0)
+    try:
+        cus = ctx.device_info().cu_count
+        n = 512
+        ids = (C.c_uint32 * (2 * n))()
+        print("cu mask probe, share 32", flush=True)
+        B.check(ctx.lib.mt_probe_cu_mask(ctx.h, 32, 0, n, ids))
+        units = {(ids[2 * i] & 0xff00, ids[2 * i + 1] & 0xf) for i in range(n)}
+        assert 1 <= len(units) <= 32                  # never more distinct units than the share
+        B.check(ctx.lib.mt_probe_cu_mask(ctx.h, 0, 0, n, ids))
+        assert len({(ids[2 * i] & 0xff00, ids[2 * i + 1] & 0xf) for i in range(n)}) > 32
+        with pytest.raises(B.MtError):
+            B.check(ctx.lib.mt_probe_cu_mask(ctx.h, cus + 1, 0, n, ids))
+        us = (C.c_float * 2)()
+        print("dispatch latency probe", flush=True)
+        B.check(ctx.lib.mt_probe_dispatch_latency(ctx.h, 2, 0, 16, us))
+        assert all(1.0 < v < 200.0 for v in us)
+    finally:
+        ctx.close()
