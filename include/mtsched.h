@@ -124,12 +124,15 @@ typedef struct mt_device_info {
 } mt_device_info;
 
 /* Timings of one mt_run, from HIP events recorded on the device.
- * makespan_ms: from the event recorded before the first operator of any tenant may start to the
- * event recorded after the last operator of every tenant has finished (Sec. III-A objective).
+ * makespan_ms: from the event recorded before the first operator of any tenant may start to the latest of the
+ * events that the streams of the last stage record after their last operator (Sec. III-A objective: earliest start to
+ * latest end); under MT_SCHED_GRAPH, the events around the graph launch.
  * stage_ms[s]: from the previous barrier (or the start) to the barrier that ends stage s.
  * host_issue_ms: wall time the issuing thread spent launching (Sec. III-D "invoking overhead").
  * first_op_done_ms[i]: only with MT_SCHED_TIME_FIRST_OP, else 0: from the start to the end of tenant i's first
- * operator, i.e. how long stream i was held back by the issue of the streams before it (Sec. III-D, Fig. 5). */
+ * operator, i.e. how long stream i was held back by the issue of the streams before it (Sec. III-D, Fig. 5).
+ * tenant_done_ms[i]: only with MT_SCHED_TIME_TENANTS, else 0: from the start to the end of tenant i's last operator,
+ * the latency of model i inside the multi-tenant run (the makespan is the largest of them, up to the final barrier). */
 typedef struct mt_timings {
     float makespan_ms;
     float host_issue_ms;
@@ -138,6 +141,7 @@ typedef struct mt_timings {
     float stage_ms[MT_MAX_STAGES];
     float first_op_done_ms[MT_MAX_TENANTS];
     int32_t n_fused;       /* operators (of the n_launches issued) that ran inside a neighbouring operator's launch */
+    float tenant_done_ms[MT_MAX_TENANTS];
 } mt_timings;
 
 /* ---- error reporting ---------------------------------------------------------------- */
@@ -268,6 +272,10 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
  * of another then issues first.  Timing only, results unchanged.  (This is the priority of a wave among the waves of
  * its SIMD, set by the kernel itself; stream and queue priorities are never used.) */
 #define MT_SCHED_PRIORITIZE_SHORT 256
+/* MT_SCHED_TIME_TENANTS: records one more event per tenant, after its last operator, and reports it in
+ * mt_timings.tenant_done_ms.  Works with the single issuing thread and with MT_SCHED_PARALLEL_ISSUE, with or without CU
+ * shares; not with MT_SCHED_GRAPH or MT_SCHED_STREAM_GRAPHS (events inside a captured graph cannot be queried). */
+#define MT_SCHED_TIME_TENANTS 512
 /* MT_SCHED_STREAM_GRAPHS: the launches of one stream in one stage are captured (on that stream, on the first run
  * and again when a buffer pointer changes) into a graph of their own and replayed on that stream: the short gaps
  * between kernels of a replayed graph, with CU shares still in force (the replay runs on the masked stream) and with

@@ -271,7 +271,8 @@ class Context:
         B.check(self.lib.mt_run(self.h, sched.h, ins, outs, C.byref(tm)))
         return {"makespan_ms": tm.makespan_ms, "host_issue_ms": tm.host_issue_ms, "n_launches": tm.n_launches,
                 "stage_ms": [tm.stage_ms[i] for i in range(tm.n_stages)],
-                "first_op_done_ms": [tm.first_op_done_ms[i] for i in range(n)], "n_fused": tm.n_fused}
+                "first_op_done_ms": [tm.first_op_done_ms[i] for i in range(n)], "n_fused": tm.n_fused,
+                "tenant_done_ms": [tm.tenant_done_ms[i] for i in range(n)]}
 
     def run_makespan(self, sched, bound):
         """One pass on bound buffers; returns (makespan_ms, host_issue_ms) only: the cheap form for timing loops."""

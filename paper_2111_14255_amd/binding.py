@@ -31,6 +31,7 @@ MT_SCHED_FUSE_DEPTHWISE = 16
 MT_SCHED_FUSE_EXPAND = 64
 MT_SCHED_FUSE_POOL = 128
 MT_SCHED_PRIORITIZE_SHORT = 256
+MT_SCHED_TIME_TENANTS = 512
 MT_SCHED_STREAM_GRAPHS = 32
 MT_SEARCH_COORDINATE, MT_SEARCH_RANDOM = 0, 1
 
@@ -57,7 +58,8 @@ class mt_device_info(C.Structure):
 class mt_timings(C.Structure):
     _fields_ = [("makespan_ms", C.c_float), ("host_issue_ms", C.c_float), ("n_launches", C.c_int32),
                 ("n_stages", C.c_int32), ("stage_ms", C.c_float * MT_MAX_STAGES),
-                ("first_op_done_ms", C.c_float * MT_MAX_TENANTS), ("n_fused", C.c_int32)]
+                ("first_op_done_ms", C.c_float * MT_MAX_TENANTS), ("n_fused", C.c_int32),
+                ("tenant_done_ms", C.c_float * MT_MAX_TENANTS)]
 
 
 class mt_search_opts(C.Structure):

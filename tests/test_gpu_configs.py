@@ -115,6 +115,20 @@ def test_paper_mix_r18_r34_fp16_with_share_search_and_first_op_timing():
         _, tm = mix.run(s)
         first = tm["first_op_done_ms"]
         assert 0 < first[0] < first[1] < tm["makespan_ms"]       # DFS: the second stream starts after the first is issued
+        # per-tenant completion times: one tenant after the other when sequential, all within the makespan always
+        for sched in (ctx.sequential(flags=B.MT_SCHED_TIME_TENANTS),
+                      ctx.all_concurrent(flags=B.MT_SCHED_TIME_TENANTS | B.MT_SCHED_PARALLEL_ISSUE | B.MT_SCHED_FUSE_POOL),
+                      ctx.schedule(even_split(lens, 3), 3, cu_share=[128, 128], flags=B.MT_SCHED_TIME_TENANTS)):
+            _, tm = mix.run(sched)
+            done = tm["tenant_done_ms"]
+            assert all(0 < d <= tm["makespan_ms"] * 1.001 + 1e-3 for d in done), (sched.label, done, tm["makespan_ms"])
+            assert max(done) >= 0.8 * tm["makespan_ms"]
+            if sched.label == "sequential":
+                assert done[0] < done[1]
+        _, tm = mix.run(ctx.all_concurrent())
+        assert tm["tenant_done_ms"] == [0.0, 0.0]
+        with pytest.raises(B.MtError):
+            ctx.schedule([[], []], 1, flags=B.MT_SCHED_TIME_TENANTS | B.MT_SCHED_GRAPH)
         ref = mix.oracle()
         outs = [ctx.make_output(t) for t in range(2)]
         rho, cost, rec, shares = ctx.search(mix.inputs, outs, 3, rounds=1, candidates=3, runs=3, warmup=1, seed=9,
