@@ -212,10 +212,18 @@ def test_empty_slices_and_single_op_tenant():
     try:
         ref = mix.oracle()
         for rho in ([[0, 0, 1], [0, 0, 0]], [[1, 1, 1], [1, 1, 1]], [[0, 0, 0], [1, 1, 1]], [[0, 1, 1], [0, 0, 1]]):
-            got, tm = mix.run(mix.ctx.schedule(rho, 4))
-            assert tm["n_launches"] == 2
-            for t in range(2):
-                assert_close(got[t], ref[t], "f16")
+            for flags in (0, B.MT_SCHED_PARALLEL_ISSUE):
+                got, tm = mix.run(mix.ctx.schedule(rho, 4, flags=flags))
+                assert tm["n_launches"] == 2
+                for t in range(2):
+                    assert_close(got[t], ref[t], "f16")
+                # a stage lasts from the end of the one before to the latest end on its streams; one that launches
+                # nothing takes no time, and the stages add up to the makespan
+                work = [any((rho[t][st - 1] if st else 0) < (rho[t][st] if st < 3 else 1) for t in range(2)) for st in range(4)]
+                assert len(tm["stage_ms"]) == 4
+                for st in range(4):
+                    assert (tm["stage_ms"][st] > 0) == work[st], (rho, st, tm["stage_ms"])
+                assert abs(sum(tm["stage_ms"]) - tm["makespan_ms"]) <= 1e-3 * tm["makespan_ms"] + 1e-6
     finally:
         mix.close()
 
