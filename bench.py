@@ -177,14 +177,16 @@ def main():
     results["sequential+fused_pairs"] = time_schedule(ctx, torch, seq_f, inputs, outputs, args.warmup, args.steps)
     allc_f = ctx.all_concurrent(flags=FE | B.MT_SCHED_PARALLEL_ISSUE)
     results["all_concurrent+fused_pairs+parallel_issue"] = time_schedule(ctx, torch, allc_f, inputs, outputs, args.warmup, args.steps)
-    # searched in the mode it is deployed in (one issuing thread per stream), wave priorities as the last coordinates
+    # searched in the mode it is deployed in (one issuing thread per stream, stage barriers taken on the host), wave
+    # priorities as the last coordinates
     t0 = time.perf_counter()
     rho_f, cost, records, shares_f, prio_f, conc_f = ctx.search(inputs, outputs, cfg.n_stages, rounds=args.search_rounds,
                                                                 candidates=args.search_candidates, runs=7, warmup=1,
                                                                 seed=cfg.seed, cu_share_rounds=2, wave_priority_rounds=2,
-                                                                search_concurrency=True, flags=FE | B.MT_SCHED_PARALLEL_ISSUE)
+                                                                search_concurrency=True,
+                                                                flags=FE | B.MT_SCHED_PARALLEL_ISSUE | B.MT_SCHED_HOST_BARRIER)
     search_s = time.perf_counter() - t0
-    for extra, suffix in ((0, ""), (B.MT_SCHED_PARALLEL_ISSUE, "+parallel_issue")):
+    for extra, suffix in ((0, ""), (B.MT_SCHED_PARALLEL_ISSUE | B.MT_SCHED_HOST_BARRIER, "+parallel_issue")):
         sf = ctx.schedule(rho_f, cfg.n_stages, concurrency=conc_f, cu_share=shares_f, flags=FE | extra, wave_priority=prio_f)
         key = "searched+cu_share+priority+fused_pairs" + suffix
         results[key] = time_schedule(ctx, torch, sf, inputs, outputs, args.warmup, args.steps)

@@ -276,6 +276,12 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
  * mt_timings.tenant_done_ms.  Works with the single issuing thread and with MT_SCHED_PARALLEL_ISSUE, with or without CU
  * shares; not with MT_SCHED_GRAPH or MT_SCHED_STREAM_GRAPHS (events inside a captured graph cannot be queried). */
 #define MT_SCHED_TIME_TENANTS 512
+/* MT_SCHED_HOST_BARRIER (only with MT_SCHED_PARALLEL_ISSUE): the barrier between stages is taken on the host.  The
+ * issuing thread of a stream waits (hipEventSynchronize) for the events that the other streams recorded at the end of
+ * the stage before and launches its operators of the stage after that, instead of queueing a device-side wait in
+ * front of them.  Same ordering, same results; the launches of a stage can no longer be queued while the stage before
+ * still runs, but no queue sits in a wait, which on this machine slows the dispatch of the queues that still work. */
+#define MT_SCHED_HOST_BARRIER 1024
 /* MT_SCHED_STREAM_GRAPHS: the launches of one stream in one stage are captured (on that stream, on the first run
  * and again when a buffer pointer changes) into a graph of their own and replayed on that stream: the short gaps
  * between kernels of a replayed graph, with CU shares still in force (the replay runs on the masked stream) and with

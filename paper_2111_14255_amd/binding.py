@@ -32,6 +32,7 @@ MT_SCHED_FUSE_EXPAND = 64
 MT_SCHED_FUSE_POOL = 128
 MT_SCHED_PRIORITIZE_SHORT = 256
 MT_SCHED_TIME_TENANTS = 512
+MT_SCHED_HOST_BARRIER = 1024
 MT_SCHED_STREAM_GRAPHS = 32
 MT_SEARCH_COORDINATE, MT_SEARCH_RANDOM = 0, 1
 

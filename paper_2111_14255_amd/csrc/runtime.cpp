@@ -753,7 +753,18 @@ void issue_worker(mt_ctx *ctx, int w) {
                 const StagePlan &sp = s->stages[st];
                 if (sp.by_stream[w].empty()) continue;
                 while (pool.stage_posted.load(std::memory_order_acquire) < st) spin_pause();
-                hipError_t e = wait_for_previous_stage(ctx, s, st, w);
+                hipError_t e = hipSuccess;
+                const int prev = sp.prev_stage;
+                if ((s->flags & MT_SCHED_HOST_BARRIER) && prev >= 0) {
+                    // the barrier on the host: once every stream of the stage before has recorded its event, this
+                    // thread waits for those of the other streams and only then launches
+                    const StagePlan &pp = s->stages[prev];
+                    while (pool.stage_done[prev].load(std::memory_order_acquire) < (int)pp.streams.size()) spin_pause();
+                    for (int pm : pp.streams)
+                        if (s->stream_at[prev][pm] != s->stream_at[st][w] && e == hipSuccess) e = hipEventSynchronize(ctx->ev_done[prev][pm]);
+                } else {
+                    e = wait_for_previous_stage(ctx, s, st, w);
+                }
                 for (const IssueItem &it : sp.by_stream[w]) {
                     if (e != hipSuccess) break;
                     const int rc = launch_item(ctx, s, it, pool.inputs, pool.outputs, s->stream_at[st][w]);
@@ -1384,6 +1395,8 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
         return fail(MT_ERR_INVALID_ARG, "per-stream graphs cannot be combined with whole-schedule replay, parallel issue or first-operator timing");
     if ((flags & MT_SCHED_TIME_FIRST_OP) && (flags & (MT_SCHED_GRAPH | MT_SCHED_PARALLEL_ISSUE)))
         return fail(MT_ERR_INVALID_ARG, "first-operator timing needs the single issuing thread and plain streams");
+    if ((flags & MT_SCHED_HOST_BARRIER) && !(flags & MT_SCHED_PARALLEL_ISSUE))
+        return fail(MT_ERR_INVALID_ARG, "the host-side barrier needs one issuing thread per stream (MT_SCHED_PARALLEL_ISSUE)");
     if ((flags & MT_SCHED_TIME_TENANTS) && (flags & (MT_SCHED_GRAPH | MT_SCHED_STREAM_GRAPHS)))
         return fail(MT_ERR_INVALID_ARG, "per-tenant completion times cannot be read from captured graphs");
     int32_t lens[MT_MAX_TENANTS];

@@ -82,6 +82,10 @@ def test_cfg2_r18_vgg16_mbv2_fp16():
         lambda ctx, lens: ctx.schedule(even_split(lens, 3), 3, cu_share=[[64, 128, 64], [0, 0, 0], [128, 64, 64]], label="per-stage-shares"),
         lambda ctx, lens: ctx.schedule(even_split(lens, 3), 3, cu_share=[[96, 96, 64], [64, 64, 128], [0, 224, 32]],
                                        flags=B.MT_SCHED_PARALLEL_ISSUE, label="parallel-issue"),
+        lambda ctx, lens: ctx.schedule(even_split(lens, 5), 5, concurrency=[3, 2, 3, 1, 3],
+                                       flags=B.MT_SCHED_PARALLEL_ISSUE | B.MT_SCHED_HOST_BARRIER | B.MT_SCHED_FUSE_EXPAND, label="parallel-issue"),
+        lambda ctx, lens: ctx.schedule([[0, 0], [lens[1], lens[1]], [0, lens[2]]], 3, cu_share=[64, 128, 64],
+                                       flags=B.MT_SCHED_PARALLEL_ISSUE | B.MT_SCHED_HOST_BARRIER, label="parallel-issue"),
     ])
     mix.close()
 
@@ -129,6 +133,8 @@ def test_paper_mix_r18_r34_fp16_with_share_search_and_first_op_timing():
         assert tm["tenant_done_ms"] == [0.0, 0.0]
         with pytest.raises(B.MtError):
             ctx.schedule([[], []], 1, flags=B.MT_SCHED_TIME_TENANTS | B.MT_SCHED_GRAPH)
+        with pytest.raises(B.MtError):
+            ctx.schedule([[], []], 1, flags=B.MT_SCHED_HOST_BARRIER)              # needs one issuing thread per stream
         ref = mix.oracle()
         outs = [ctx.make_output(t) for t in range(2)]
         rho, cost, rec, shares = ctx.search(mix.inputs, outs, 3, rounds=1, candidates=3, runs=3, warmup=1, seed=9,
