@@ -16,7 +16,12 @@ def _runtime_environment():
     why the library captures a schedule in both orders and keeps the faster graph.
     HIP_FORCE_DEV_KERNARG: kernel arguments in device memory; in host memory every launch starts with a read over
     the host link (848 against 578 us for the 98 launches of that pass).  The runtime of this image already defaults
-    to it; set here so that another default does not change the numbers."""
+    to it; set here so that another default does not change the numbers.
+    HSA_ENABLE_INTERRUPT=0: host waits for device signals (hipEventSynchronize at the end of a run and in host-side
+    stage barriers) poll the signal instead of sleeping until the driver's interrupt wakes the thread.  Measured on
+    MI355X: the same three-tenant pass 0.294 -> 0.286 ms per step on the host's clock (makespan 0.279 -> 0.272 ms),
+    even two- to seven-stage schedules 4 to 8 % shorter.  The price is a busy host thread per waiting call; a value
+    already set in the environment is kept."""
     want = _os.environ.get("MTSCHED_HW_QUEUES")
     try:
         have = int(_os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0)
@@ -27,6 +32,7 @@ def _runtime_environment():
     elif have < 8:
         _os.environ["GPU_MAX_HW_QUEUES"] = "8"
     _os.environ.setdefault("HIP_FORCE_DEV_KERNARG", "1")
+    _os.environ.setdefault("HSA_ENABLE_INTERRUPT", "0")
 
 
 _runtime_environment()
