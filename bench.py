@@ -197,6 +197,12 @@ def main():
         results[key].update({"pointers": rho_f, "stage_concurrency": conc_f, "cu_share": shares_f, "wave_priority": prio_f,
                              "search_seconds": search_s,
                              "search_evaluations": len(records)})
+    # when each tenant finishes inside that schedule (one more event per tenant; not part of the timed variants)
+    st = ctx.schedule(rho_f, cfg.n_stages, concurrency=conc_f, cu_share=shares_f, wave_priority=prio_f,
+                      flags=FE | B.MT_SCHED_PARALLEL_ISSUE | B.MT_SCHED_HOST_BARRIER | B.MT_SCHED_TIME_TENANTS)
+    bound = ctx.bind(inputs, outputs)
+    done = [ctx.run(st, bound)["tenant_done_ms"] for _ in range(args.warmup + 21)][args.warmup:]
+    results[key]["tenant_done_ms_median"] = [sorted(d[t] for d in done)[len(done) // 2] for t in range(len(specs))]    # tenant order
     for k, r in results.items():
         base = results["sequential" + ("+graph" if k.endswith("+graph") else "+fused_pairs" if "+fused_pairs" in k else "")]
         r["img_per_s"] = images / (r["wall_ms_per_step"] * 1e-3)
