@@ -203,6 +203,11 @@ int32_t mt_model_arena_bytes(const mt_model *m, size_t *out);
 int32_t mt_fold_bn(float *w, int64_t k, int64_t per_k, const float *gamma, const float *beta,
                    const float *mean, const float *var, float eps, float *bias_out);
 
+/* Cast to the storage type (the numeric reading taken where the paper states no precision: values are stored as
+ * fp16 or bf16 with one round-to-nearest-even, NaN kept quiet, or as fp32 unchanged).  Host only.
+ * src: host [n] floats; dst: host [n] elements of the storage type (2 or 4 bytes each). */
+int32_t mt_round_to_storage(const float *src, int64_t n, int32_t dtype, void *dst);
+
 /* ---- registration -------------------------------------------------------------------- */
 /* Uploads a finalised model with all weights set and makes it tenant `*out_tenant` (0, 1, ...)
  * of the context.  device_arena: device memory of at least mt_model_arena_bytes() bytes, 256-byte
@@ -323,7 +328,7 @@ typedef struct mt_search_opts {
     int32_t n_stages;      /* P + 1 */
     int32_t rounds;        /* R.  Random search evaluates rounds * n_tenants * candidates matrices. */
     int32_t candidates;    /* M candidate rows per (round, model) */
-    int32_t runs;          /* timed runs averaged per candidate ("profile the latency by multiple runs") */
+    int32_t runs;          /* timed runs per candidate (the profiling step of Alg. 1's inner loop); the cost is their median */
     int32_t warmup;        /* untimed runs per candidate */
     int32_t issue_order;   /* mt_issue_order */
     int32_t flags;         /* schedule flags used while profiling */
@@ -335,6 +340,9 @@ typedef struct mt_search_opts {
     int32_t wave_priority_rounds; /* mt_search only: > 0 runs that many rounds of the wave-priority descent (below) last */
     int32_t search_concurrency; /* mt_search only: non-zero also tries 2 .. n_tenants - 1 streams per stage (the same in every
                                    stage) under the pointers found, before shares and priorities */
+    int32_t playoff_top;   /* mt_search only: > 0 ends the pointer search with a play-off (mt_playoff_pointers) over that many
+                              of the best records plus the one-stage matrix, each measured again with playoff_runs runs */
+    int32_t playoff_runs;  /* timed runs per play-off candidate (median); values below 1 mean 21 */
     uint64_t seed;
 } mt_search_opts;
 
@@ -348,6 +356,17 @@ typedef double (*mt_cost_fn)(const int32_t *pointers, void *user);
 int32_t mt_search_pointers(int32_t n_tenants, const int32_t *lens, const mt_search_opts *opts,
                            mt_cost_fn cost, void *user, int32_t *best_pointers, double *best_cost,
                            int32_t *rec_pointers, double *rec_cost, int32_t max_records, int32_t *n_records);
+
+/* Play-off over a record memory (an addition: Alg. 1 ends by returning the best record as it was profiled once, and two
+ * schedules a few percent apart cannot be told apart by one short measurement).  Host only, any cost function.
+ * Candidates, in this order: the top_k distinct matrices of the records by (cost, position), then the matrix whose
+ * pointers all equal len_i (every operator in stage 1) unless it is one of them.  Each candidate is measured with
+ * `cost` (meant to be a longer measurement than the one that filled the records); the lowest wins, the earlier
+ * candidate on ties.  rec_pointers: host [n_records][n_tenants][n_stages-1]; rec_cost: host [n_records];
+ * best_pointers: host [n_tenants][n_stages-1]; n_evaluated (optional): number of candidates measured. */
+int32_t mt_playoff_pointers(int32_t n_tenants, const int32_t *lens, int32_t n_stages, const int32_t *rec_pointers,
+                            const double *rec_cost, int32_t n_records, int32_t top_k, mt_cost_fn cost, void *user,
+                            int32_t *best_pointers, double *best_cost, int32_t *n_evaluated);
 
 /* Per-tenant CU share as one more coordinate per tenant (an extension; the paper leaves resource sharing to the
  * hardware, Sec. III-A(b)).  Host only, any cost function.  Start: the share vector passed in best_share (all zeros =
@@ -376,7 +395,9 @@ int32_t mt_search_wave_priority(int32_t n_tenants, int32_t rounds, mt_share_cost
 int32_t mt_proportional_cu_share(int32_t n_tenants, int32_t cu_count, const double *weight, int32_t *share);
 
 /* The same searches with the profiled makespan of mt_run as cost (median of opts->runs timed runs after opts->warmup
- * untimed ones), all tenants on their own stream.
+ * untimed ones), all tenants on their own stream.  With opts->playoff_top > 0 the pointer search ends with
+ * mt_playoff_pointers over its records (cost = median of opts->playoff_runs runs), and the play-off's winner and cost
+ * replace the best record; the records returned to the caller are those of the search itself.
  * best_cu_share: host [n_tenants] or NULL; filled with zeros unless opts->cu_share_rounds > 0.  With
  * opts->cu_share_rounds > 0 three phases run: the pointer search on unmasked streams (the only phase written to the
  * records); the share descent under those pointers, started from the best of all-zero shares,

@@ -14,7 +14,7 @@ Readings where the paper is silent:
     the lower-ranked tenants mapped to the same stream.
   * Candidate rows of Alg. 1 are P draws, uniform on [0, len_i], sorted.  Random
     search draws every pointer independently and unsorted, and discards a matrix
-    with a non-monotone row (the paper's "infeasible solutions are filtered out").
+    with a non-monotone row (the filtering of infeasible samples that Sec. IV-D mentions).
   * Random draws come from a counter-based generator so that an independent
     implementation can reproduce them: draw(seed, a, b, c, d) below.
 """
@@ -117,7 +117,8 @@ def baseline_seeds(lens, n_pointers):
 
 
 def coordinate_descent(lens, n_pointers, rounds, n_cand, cost, seed, init=None, seed_baselines=False):
-    """Alg. 1.  `cost(rho)` stands for "profile the latency by multiple runs".
+    """Alg. 1.  `cost(rho)` stands for the profiling step of the inner loop (the latency of the
+    candidate schedule measured over several runs).
     Returns (best_rho, best_cost, records); records lists every evaluated
     (rho, cost) in evaluation order; the best is the earliest minimum."""
     rho = [list(r) for r in (init if init is not None else even_split(lens, n_pointers))]
@@ -159,6 +160,28 @@ def random_search(lens, n_pointers, evaluations, cost, seed, seed_baselines=Fals
         return None, None, records, skipped
     best = min(range(len(records)), key=lambda j: (records[j][1], j))
     return records[best][0], records[best][1], records, skipped
+
+
+def playoff(lens, n_pointers, records, top_k, final_cost):
+    """Extension to Alg. 1 (its last step returns the best entry of the record memory as profiled once): the
+    top_k distinct matrices of the record memory, lowest profiled cost first and earlier entry first on ties,
+    followed by the matrix that puts every operator into stage 1 unless it is already among them, are measured
+    again with `final_cost` (more runs); the lowest of these second measurements wins, the earlier candidate on
+    ties.  Returns (rho, cost, candidates) with candidates = [(rho, final cost), ...] in evaluation order."""
+    order = sorted(range(len(records)), key=lambda j: (records[j][1], j))
+    cands = []
+    for j in order:
+        m = [list(r) for r in records[j][0]]
+        if m not in cands:
+            cands.append(m)
+        if len(cands) >= max(1, top_k):
+            break
+    one_stage = [[n] * n_pointers for n in lens]
+    if one_stage not in cands:
+        cands.append(one_stage)
+    scored = [(m, final_cost(m)) for m in cands]
+    best = min(range(len(scored)), key=lambda j: (scored[j][1], j))
+    return scored[best][0], scored[best][1], scored
 
 
 def proportional_shares(weights, cu_count):

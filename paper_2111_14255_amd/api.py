@@ -17,17 +17,13 @@ _ACT = {"none": B.MT_ACT_NONE, "relu": B.MT_ACT_RELU, "relu6": B.MT_ACT_RELU6}
 
 
 def to_storage(a, dtype):
-    """float32 array -> array holding the storage type's bits (round to nearest even)."""
+    """float32 array -> array holding the storage type's bits; the rounding itself is the library's (mt_round_to_storage)."""
     a = np.ascontiguousarray(a, dtype=np.float32)
     if dtype == "f32":
         return a
-    if dtype == "f16":
-        return a.astype(np.float16)
-    u = a.view(np.uint32).astype(np.uint64)
-    nan = (u & 0x7FFFFFFF) > 0x7F800000
-    r = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
-    r[nan] = ((u[nan] >> 16) | 0x40).astype(np.uint16)
-    return r
+    out = np.empty(a.shape, dtype=np.float16 if dtype == "f16" else np.uint16)
+    B.check(B.load().mt_round_to_storage(a.ctypes.data_as(C.POINTER(C.c_float)), a.size, _DT[dtype], C.c_void_p(out.ctypes.data)))
+    return out
 
 
 def from_storage(a, dtype):
@@ -288,13 +284,13 @@ class Context:
 
     def search(self, inputs, outputs, n_stages, rounds=2, candidates=6, runs=5, warmup=1, seed=1,
                algo=B.MT_SEARCH_COORDINATE, order=B.MT_ISSUE_BFS, flags=0, seed_baselines=True, cu_share_rounds=0,
-               wave_priority_rounds=0, search_concurrency=False):
+               wave_priority_rounds=0, search_concurrency=False, playoff_top=0, playoff_runs=21):
         """Returns (pointer matrix, best cost, records), then the CU shares if cu_share_rounds > 0, then the wave
         priorities if wave_priority_rounds > 0, then the per-stage concurrency if search_concurrency."""
         n = self.num_tenants()
         P = n_stages - 1
         opts = B.mt_search_opts(algo, n_stages, rounds, candidates, runs, warmup, order, flags, 1 if seed_baselines else 0, cu_share_rounds,
-                                wave_priority_rounds, 1 if search_concurrency else 0, seed)
+                                wave_priority_rounds, 1 if search_concurrency else 0, playoff_top, playoff_runs, seed)
         cap = rounds * n * candidates + 2
         best = (C.c_int32 * max(1, n * P))()
         best_cost = C.c_double()

@@ -67,7 +67,8 @@ class mt_search_opts(C.Structure):
     _fields_ = [("algo", C.c_int32), ("n_stages", C.c_int32), ("rounds", C.c_int32), ("candidates", C.c_int32),
                 ("runs", C.c_int32), ("warmup", C.c_int32), ("issue_order", C.c_int32), ("flags", C.c_int32),
                 ("seed_baselines", C.c_int32), ("cu_share_rounds", C.c_int32), ("wave_priority_rounds", C.c_int32),
-                ("search_concurrency", C.c_int32), ("seed", C.c_uint64)]
+                ("search_concurrency", C.c_int32), ("playoff_top", C.c_int32), ("playoff_runs", C.c_int32),
+                ("seed", C.c_uint64)]
 
 
 mt_cost_fn = C.CFUNCTYPE(C.c_double, C.POINTER(C.c_int32), C.c_void_p)
@@ -97,6 +98,7 @@ SIGNATURES = {
     "mt_model_set_weights": (_i32, [_vp, _i32, _vp, _sz, _pf, _sz]),
     "mt_model_arena_bytes": (_i32, [_vp, C.POINTER(_sz)]),
     "mt_fold_bn": (_i32, [_pf, _i64, _i64, _pf, _pf, _pf, _pf, C.c_float, _pf]),
+    "mt_round_to_storage": (_i32, [_pf, _i64, _i32, _vp]),
     "mt_register": (_i32, [_vp, _vp, _vp, _sz, _pi32]),
     "mt_num_tenants": (_i32, [_vp, _pi32]),
     "mt_tenant_num_ops": (_i32, [_vp, _i32, _pi32]),
@@ -111,6 +113,7 @@ SIGNATURES = {
     "mt_run": (_i32, [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(mt_timings)]),
     "mt_profile_ops": (_i32, [_vp, _i32, _vp, _vp, _i32, _pf]),
     "mt_search_pointers": (_i32, [_i32, _pi32, C.POINTER(mt_search_opts), mt_cost_fn, _vp, _pi32, _pd, _pi32, _pd, _i32, _pi32]),
+    "mt_playoff_pointers": (_i32, [_i32, _pi32, _i32, _pi32, _pd, _i32, _i32, mt_cost_fn, _vp, _pi32, _pd, _pi32]),
     "mt_search_cu_share": (_i32, [_i32, _i32, _i32, mt_share_cost_fn, _vp, _pi32, _pd]),
     "mt_proportional_cu_share": (_i32, [_i32, _i32, _pd, _pi32]),
     "mt_search": (_i32, [_vp, C.POINTER(mt_search_opts), C.POINTER(_vp), C.POINTER(_vp), _pi32, _pi32, _pi32, _pi32, _pd, _pi32, _pd, _i32, _pi32]),

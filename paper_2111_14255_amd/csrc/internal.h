@@ -25,6 +25,10 @@ int32_t search_pointers(int32_t n_tenants, const int32_t *lens, const mt_search_
                         int32_t *best_pointers, double *best_cost, int32_t *rec_pointers, double *rec_cost,
                         int32_t max_records, int32_t *n_records);
 
+int32_t playoff_pointers(int32_t n_tenants, const int32_t *lens, int32_t n_stages, const int32_t *rec_pointers,
+                         const double *rec_cost, int32_t n_records, int32_t top_k, mt_cost_fn cost, void *user,
+                         int32_t *best_pointers, double *best_cost, int32_t *n_evaluated);
+
 int32_t proportional_cu_share(int32_t n_tenants, int32_t cu_count, const double *weight, int32_t *share);
 int32_t search_cu_share(int32_t n_tenants, int32_t cu_count, int32_t rounds, mt_share_cost_fn cost, void *user,
                         int32_t *best_share, double *best_cost);

@@ -228,23 +228,61 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
 
     u32x4 wreg[STAGES][W_CHUNKS], xreg[STAGES][X_CHUNKS];
 
-    // Straight-line loads (no control flow), so the compiler counts them exactly and lets the newer register
-    // sets stay in flight while the oldest one is consumed.
-    auto load_tiles = [&](u32x4 (&wr)[W_CHUNKS], u32x4 (&xr)[X_CHUNKS]) {
+    // A tile is fetched and copied to LDS chunk by chunk (filter chunks first, then im2col chunks), so that the main
+    // loop can spread the chunks of the next tiles between the matrix instructions of the current one.  All loads are
+    // straight-line code: the compiler counts them exactly and lets the newer register sets stay in flight while the
+    // oldest one is consumed.
+    constexpr int NCH = W_CHUNKS + X_CHUNKS;
+    int t_tapoff = 0, t_sh = 0, t_kr = 0, t_ks = 0;      // per-tile values of the im2col gather, set by tile_begin
+    bool t_tap_ok = false;
+    auto tile_begin = [&]() {
+        if constexpr (AMODE == A_UNIFORM) {
+            t_tapoff = ((u_r * a.W + u_s) * XS + u_cb) * 2;                // scalar
+            t_tap_ok = u_tap < a.R * a.S;
+            t_sh = t_tap_ok ? u_tap : 0;
+        } else if constexpr (AMODE == A_VEC8) {
+            t_kr = tap_row(krs);
+            t_ks = krs - t_kr * a.S;
+        }
+    };
+    auto load_chunk = [&]<int I>(u32x4 (&wr)[W_CHUNKS], u32x4 (&xr)[X_CHUNKS]) {
+        if constexpr (I < W_CHUNKS) {
+            wr[I] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, wvoff[I], wsoff, 0);
+        } else if constexpr (AMODE == A_UNIFORM) {
+            constexpr int i = I - W_CHUNKS;
+            const bool v = t_tap_ok & (((tapmask[i] >> t_sh) & 1ull) != 0);
+            const uint32_t voff = v ? (uint32_t)(rowoff[i] + t_tapoff) : OOB_OFFSET;
+            xr[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, voff, 0, 0);
+        } else if constexpr (AMODE == A_VEC8) {
+            constexpr int i = I - W_CHUNKS;
+            const int ih = ih0[i] + t_kr, iw = iw0[i] + t_ks;
+            const bool v = xrow_ok[i] & (t_kr < a.R) & ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
+            const uint32_t voff = v ? (uint32_t)((img_off[i] + (ih * a.W + iw) * XS + kcx) * 2) : OOB_OFFSET;
+            xr[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, voff, 0, 0);
+        } else {
+            // input channels not a multiple of 8 (first layers, C = 3): gather element by element
+            constexpr int i = I - W_CHUNKS;
+            const uint16_t *xs = reinterpret_cast<const uint16_t *>(x);
+            uint32_t e[8];
 #pragma unroll
-        for (int i = 0; i < W_CHUNKS; ++i)
-            wr[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_w, wvoff[i], wsoff, 0);
+            for (int t = 0; t < 8; ++t) {
+                const int j = jbase + t;
+                const int rs = j / a.C;
+                const int c = j - rs * a.C;
+                const int r = tap_row(rs);
+                const int sx = rs - r * a.S;
+                const int ih = ih0[i] + r, iw = iw0[i] + sx;
+                const bool v = xrow_ok[i] & (j < a.gemm_k) & ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
+                const int off = v ? img_off[i] + (ih * a.W + iw) * XS + c : 0;
+                const uint32_t h = xs[off];
+                e[t] = v ? h : 0u;
+            }
+            xr[i] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
+        }
+    };
+    auto tile_end = [&]() {
         wsoff += BK * 2;
         if constexpr (AMODE == A_UNIFORM) {
-            const int tapoff = ((u_r * a.W + u_s) * XS + u_cb) * 2;        // scalar
-            const bool tap_ok = u_tap < a.R * a.S;
-            const int sh = tap_ok ? u_tap : 0;
-#pragma unroll
-            for (int i = 0; i < X_CHUNKS; ++i) {
-                const bool v = tap_ok & (((tapmask[i] >> sh) & 1ull) != 0);
-                const uint32_t voff = v ? (uint32_t)(rowoff[i] + tapoff) : OOB_OFFSET;
-                xr[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, voff, 0, 0);
-            }
             u_cb += BK;
             if (u_cb >= a.C) {              // scalar branch-free updates (uniform values)
                 u_cb = 0;
@@ -256,57 +294,35 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
                 }
             }
         } else if constexpr (AMODE == A_VEC8) {
-            const int kr = tap_row(krs);
-            const int ks = krs - kr * a.S;
-#pragma unroll
-            for (int i = 0; i < X_CHUNKS; ++i) {
-                const int ih = ih0[i] + kr, iw = iw0[i] + ks;
-                const bool v = xrow_ok[i] & (kr < a.R) & ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
-                const uint32_t voff = v ? (uint32_t)((img_off[i] + (ih * a.W + iw) * XS + kcx) * 2) : OOB_OFFSET;
-                xr[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc_x, voff, 0, 0);
-            }
             kcx += adv_c;
             krs += adv_rs;
             const bool carry = kcx >= a.C;
             kcx -= carry ? a.C : 0;
             krs += carry ? 1 : 0;
         } else {
-            // input channels not a multiple of 8 (first layers, C = 3): gather element by element
-            const uint16_t *xs = reinterpret_cast<const uint16_t *>(x);
-#pragma unroll
-            for (int i = 0; i < X_CHUNKS; ++i) {
-                uint32_t e[8];
-#pragma unroll
-                for (int t = 0; t < 8; ++t) {
-                    const int j = jbase + t;
-                    const int rs = j / a.C;
-                    const int c = j - rs * a.C;
-                    const int r = tap_row(rs);
-                    const int sx = rs - r * a.S;
-                    const int ih = ih0[i] + r, iw = iw0[i] + sx;
-                    const bool v = xrow_ok[i] & (j < a.gemm_k) & ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
-                    const int off = v ? img_off[i] + (ih * a.W + iw) * XS + c : 0;
-                    const uint32_t h = xs[off];
-                    e[t] = v ? h : 0u;
-                }
-                xr[i] = u32x4{e[0] | (e[1] << 16), e[2] | (e[3] << 16), e[4] | (e[5] << 16), e[6] | (e[7] << 16)};
-            }
             jbase += BK;
         }
     };
-
     // Every thread writes its chunks: tile rows beyond BN / BM land in spare LDS rows that nobody reads.
+    auto store_chunk = [&]<int I>(int buf, const u32x4 (&wr)[W_CHUNKS], const u32x4 (&xr)[X_CHUNKS]) {
+        if constexpr (I < W_CHUNKS) {
+            *reinterpret_cast<u32x4 *>(&Ws[buf][(row0 + I * ROW_STEP) * LDK + kc * 8]) = wr[I];
+        } else {
+            constexpr int i = I - W_CHUNKS;
+            *reinterpret_cast<u32x4 *>(&Xs[buf][(row0 + i * ROW_STEP) * LDK + kc * 8]) = xr[i];
+        }
+    };
+    auto load_tiles = [&](u32x4 (&wr)[W_CHUNKS], u32x4 (&xr)[X_CHUNKS]) {
+        tile_begin();
+        [&]<int... I>(std::integer_sequence<int, I...>) {
+            (load_chunk.template operator()<I>(wr, xr), ...);
+        }(std::make_integer_sequence<int, NCH>{});
+        tile_end();
+    };
     auto store_tiles = [&](int buf, const u32x4 (&wr)[W_CHUNKS], const u32x4 (&xr)[X_CHUNKS]) {
-#pragma unroll
-        for (int i = 0; i < W_CHUNKS; ++i) {
-            const int row = row0 + i * ROW_STEP;
-            *reinterpret_cast<u32x4 *>(&Ws[buf][row * LDK + kc * 8]) = wr[i];
-        }
-#pragma unroll
-        for (int i = 0; i < X_CHUNKS; ++i) {
-            const int row = row0 + i * ROW_STEP;
-            *reinterpret_cast<u32x4 *>(&Xs[buf][row * LDK + kc * 8]) = xr[i];
-        }
+        [&]<int... I>(std::integer_sequence<int, I...>) {
+            (store_chunk.template operator()<I>(buf, wr, xr), ...);
+        }(std::make_integer_sequence<int, NCH>{});
     };
 
     Acc acc[TN][TM];
@@ -335,31 +351,27 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
             }
     }
 
-    // MFMA operand fragments of one LDS tile.
-    struct Frags {
-        u32x4 a[KSTEPS][TN], b[KSTEPS][TM];
+    // MFMA operand fragments of one reduction step (16 or 32 elements deep) of an LDS tile.  The fragments of step
+    // kk + 1 are requested before the matrix instructions of step kk are issued, so that a wave's LDS reads run under
+    // its own MFMA work instead of in front of it; the accumulation order (kk, then channel tile, then pixel tile) is
+    // that of a plain loop.
+    struct Frag {
+        u32x4 a[TN], b[TM];
     };
-    auto load_frags = [&](int buf, Frags &f) {
+    auto load_frag = [&](int buf, int kk, Frag &f) {
+        const int koff = (wk * KSTEPS + kk) * (KLANES * 8) + frag_k;
 #pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk) {
-            const int koff = (wk * KSTEPS + kk) * (KLANES * 8) + frag_k;
+        for (int i = 0; i < TN; ++i)
+            f.a[i] = *reinterpret_cast<const u32x4 *>(&Ws[buf][(wn * SUBN + i * MF + frag_row) * LDK + koff]);
 #pragma unroll
-            for (int i = 0; i < TN; ++i)
-                f.a[kk][i] = *reinterpret_cast<const u32x4 *>(&Ws[buf][(wn * SUBN + i * MF + frag_row) * LDK + koff]);
-#pragma unroll
-            for (int j = 0; j < TM; ++j)
-                f.b[kk][j] = *reinterpret_cast<const u32x4 *>(&Xs[buf][(wm * SUBM + j * MF + frag_row) * LDK + koff]);
-        }
+        for (int j = 0; j < TM; ++j)
+            f.b[j] = *reinterpret_cast<const u32x4 *>(&Xs[buf][(wm * SUBM + j * MF + frag_row) * LDK + koff]);
     };
-    auto mma = [&](const Frags &f) {
+    auto mma = [&](const Frag &f) {
 #pragma unroll
-        for (int kk = 0; kk < KSTEPS; ++kk)
+        for (int i = 0; i < TN; ++i)
 #pragma unroll
-            for (int i = 0; i < TN; ++i)
-#pragma unroll
-                for (int j = 0; j < TM; ++j) {
-                    acc[i][j] = Mma<T, MF>::run(f.a[kk][i], f.b[kk][j], acc[i][j]);
-                }
+            for (int j = 0; j < TM; ++j) acc[i][j] = Mma<T, MF>::run(f.a[i], f.b[j], acc[i][j]);
     };
 
     auto prologue_load = [&]<int S>() {
@@ -372,22 +384,56 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
     // Tile t waits in register set t % STAGES until it is copied to LDS buffer t % 2.  FULL steps are the
     // steady state (every tile they touch exists) and contain no branch.
     {
+        Frag fr[2];
+        // One reduction tile: the chunks of tile t + 1 go from registers to the other LDS buffer and the chunks of tile
+        // t + 1 + STAGES are requested from memory, a few after each reduction step of tile t, whose fragments are read
+        // one step ahead of the matrix instructions that use them.
+        // Spreading pays on the wide tiles (measured on MI355X: a 3x3 layer of 256 channels on a 56x56 map at batch 8,
+        // 128x128 tile, 49.8 -> 44.8 us); tiles of few chunks per thread move them all before the first step.
+        constexpr int PER = NCH >= 8 ? (NCH + KSTEPS - 1) / KSTEPS : NCH;   // chunks moved per reduction step
         auto step = [&]<int S, bool FULL>(int t) {
             constexpr int nxt = (S + 1) % STAGES;
             if (FULL || t < nk) {
-                if (FULL || t + 1 < nk) {
-                    store_tiles((S + 1) & 1, wreg[nxt], xreg[nxt]);
-                    if (FULL || t + 1 + STAGES < nk) load_tiles(wreg[nxt], xreg[nxt]);
+                const bool more = FULL || t + 1 < nk;
+                const bool fetch = FULL || t + 1 + STAGES < nk;
+                constexpr bool SPREAD = PER < NCH;
+                if constexpr (!SPREAD) {
+                    if (more) {
+                        store_tiles((S + 1) & 1, wreg[nxt], xreg[nxt]);
+                        if (fetch) load_tiles(wreg[nxt], xreg[nxt]);
+                    }
+                } else {
+                    if (fetch) tile_begin();
                 }
-                Frags f;
-                load_frags(S & 1, f);
-                mma(f);
+                auto move_chunk = [&]<int C>() {
+                    if constexpr (C < NCH) {
+                        if (more) store_chunk.template operator()<C>((S + 1) & 1, wreg[nxt], xreg[nxt]);
+                        if (fetch) load_chunk.template operator()<C>(wreg[nxt], xreg[nxt]);
+                    }
+                };
+                auto kstep = [&]<int KK>() {
+                    if constexpr (KK + 1 < KSTEPS) load_frag(S & 1, KK + 1, fr[(KK + 1) & 1]);
+                    if constexpr (SPREAD) {
+                        [&]<int... CI>(std::integer_sequence<int, CI...>) {
+                            (move_chunk.template operator()<KK * PER + CI>(), ...);
+                        }(std::make_integer_sequence<int, PER>{});
+                    }
+                    mma(fr[KK & 1]);
+                };
+                [&]<int... KK>(std::integer_sequence<int, KK...>) {
+                    (kstep.template operator()<KK>(), ...);
+                }(std::make_integer_sequence<int, KSTEPS>{});
+                if constexpr (SPREAD) {
+                    if (fetch) tile_end();
+                }
                 __syncthreads();
+                if (more) load_frag((S + 1) & 1, 0, fr[0]);
             }
         };
         store_tiles(0, wreg[0], xreg[0]);
         if (STAGES < nk) load_tiles(wreg[0], xreg[0]);
         __syncthreads();
+        load_frag(0, 0, fr[0]);
         auto round = [&]<bool FULL, int... S>(int t0, std::integer_sequence<int, S...>) {
             (step.template operator()<S, FULL>(t0 + S), ...);
         };
@@ -809,10 +855,13 @@ static void launch_cfg(const OpArgs &a, hipStream_t st) {
         hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, 2, A_SCALAR>), grid, dim3(256), 0, st, a);
 }
 
+#ifndef MT_STAGES_128
+#define MT_STAGES_128 2
+#endif
 template <typename T>
 static int launch_igemm_typed(const OpArgs &a, hipStream_t st) {
     switch (a.kernel_id) {
-        case K_IGEMM_128x128: launch_cfg<T, 128, 128, 2, 2, 32, 2>(a, st); break;
+        case K_IGEMM_128x128: launch_cfg<T, 128, 128, 2, 2, 32, MT_STAGES_128>(a, st); break;
         case K_IGEMM_128x64:
             if (a.wk == 2) launch_cfg<T, 128, 64, 2, 2, 32, 2, 2>(a, st);
             else launch_cfg<T, 128, 64, 2, 2, 32, 2>(a, st);

@@ -736,10 +736,11 @@ inline void spin_pause() {
 #endif
 }
 
-void issue_worker(mt_ctx *ctx, int w) {
+// `seen` is the run counter at the time the thread was created: a worker added after earlier runs (a tenant
+// registered later) must sleep until the next run is published, not wake for the last one, whose schedule may be gone.
+void issue_worker(mt_ctx *ctx, int w, uint64_t seen) {
     IssuePool &pool = ctx->pool;
     (void)hipSetDevice(ctx->device);
-    uint64_t seen = 0;
     for (;;) {
         {
             std::unique_lock<std::mutex> lk(pool.mu);
@@ -788,7 +789,12 @@ void issue_worker(mt_ctx *ctx, int w) {
 int32_t ensure_pool(mt_ctx *ctx, int n) {
     while ((int)ctx->pool.threads.size() < n) {
         const int w = (int)ctx->pool.threads.size();
-        ctx->pool.threads.emplace_back(issue_worker, ctx, w);
+        uint64_t seq;
+        {
+            std::lock_guard<std::mutex> lk(ctx->pool.mu);
+            seq = ctx->pool.run_seq;
+        }
+        ctx->pool.threads.emplace_back(issue_worker, ctx, w, seq);
     }
     return MT_OK;
 }
@@ -833,6 +839,9 @@ int32_t issue_schedule_parallel(mt_ctx *ctx, mt_schedule *s, const void *const *
         if (err == hipSuccess) err = hipEventRecord(ctx->ev_stage[st], ctx->main_stream);
     }
     while (pool.finished.load(std::memory_order_acquire) < n_workers) spin_pause();
+    pool.sched = nullptr;                      // every worker has left the run; nothing may look at the schedule again
+    pool.inputs = nullptr;
+    pool.outputs = nullptr;
     if (pool.error.load()) {
         std::lock_guard<std::mutex> lk(pool.mu);
         return fail(MT_ERR_HIP, pool.error_msg);
@@ -1207,6 +1216,46 @@ int32_t mt_fold_bn(float *w, int64_t k, int64_t per_k, const float *gamma, const
         for (int64_t j = 0; j < per_k; ++j) w[i * per_k + j] *= scale;
         const float ms = mean[i] * scale;
         bias_out[i] = beta[i] - ms;
+    }
+    return MT_OK;
+}
+
+// One round-to-nearest-even from fp32 to the storage type, written from the formats' definitions (host code: the
+// device kernels round with the hardware conversions).
+int32_t mt_round_to_storage(const float *src, int64_t n, int32_t dtype, void *dst) {
+    if (!src || !dst || n < 0) return fail(MT_ERR_INVALID_ARG, "bad argument");
+    if (dtype == MT_F32) {
+        std::memcpy(dst, src, sizeof(float) * (size_t)n);
+    } else if (dtype == MT_BF16) {
+        uint16_t *o = (uint16_t *)dst;
+        for (int64_t i = 0; i < n; ++i) {
+            uint32_t u;
+            std::memcpy(&u, src + i, 4);
+            if ((u & 0x7fffffffu) > 0x7f800000u) o[i] = (uint16_t)((u >> 16) | 0x40u);          // NaN stays NaN (quiet)
+            else o[i] = (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);                   // ties to even
+        }
+    } else if (dtype == MT_F16) {
+        uint16_t *o = (uint16_t *)dst;
+        for (int64_t i = 0; i < n; ++i) {
+            uint32_t u;
+            std::memcpy(&u, src + i, 4);
+            const uint32_t sign = (u >> 16) & 0x8000u, mag = u & 0x7fffffffu;
+            uint32_t h;
+            if (mag > 0x7f800000u) h = 0x7e00u;                                               // NaN
+            else if (mag >= 0x477ff000u) h = 0x7c00u;                                         // rounds to infinity (>= 65520)
+            else if (mag >= 0x38800000u) {                                                    // normal half
+                const uint32_t v = mag - 0x38000000u;                                         // rebias the exponent (127 -> 15)
+                h = (v + 0xfffu + ((v >> 13) & 1u)) >> 13;
+            } else if (mag >= 0x33000000u) {                                                  // subnormal half: multiples of 2^-24
+                const uint32_t e = mag >> 23, m = (mag & 0x7fffffu) | 0x800000u;
+                const uint32_t shift = 126u - e;                                              // 14 .. 24
+                const uint32_t q = m >> shift, rem = m & ((1u << shift) - 1u), half = 1u << (shift - 1);
+                h = q + ((rem > half || (rem == half && (q & 1u))) ? 1u : 0u);
+            } else h = 0;                                                                     // below half of the smallest subnormal
+            o[i] = (uint16_t)(sign | h);
+        }
+    } else {
+        return fail(MT_ERR_INVALID_ARG, "unknown storage type");
     }
     return MT_OK;
 }
@@ -1834,10 +1883,45 @@ int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *in
     for (int i = 0; i < n; ++i) lens[i] = (int32_t)ctx->tenants[i]->model.ops.size();
     ProfileCost pc{ctx, opts, inputs, outputs, n};
     double cost = 0;
-    int32_t rc = search_pointers(n, lens, opts, profile_cost, &pc, best_pointers, &cost, rec_pointers, rec_cost,
-                                 max_records, n_records);
+    // The play-off needs the whole record memory: when the caller's buffer is absent or may be too small the search
+    // records into a buffer of its own, and the caller's one is filled from it afterwards.
+    const int P = opts->n_stages - 1;
+    const size_t width = (size_t)n * P;
+    const bool playoff = opts->playoff_top > 0 && P > 0;
+    const int32_t need = (int32_t)std::min<int64_t>((int64_t)opts->rounds * n * opts->candidates + 2, 1 << 24);
+    std::vector<int32_t> own_p;
+    std::vector<double> own_c;
+    int32_t *rp = rec_pointers;
+    double *rcst = rec_cost;
+    int32_t cap = max_records;
+    if (playoff && (!rec_pointers || !rec_cost || max_records < need)) {
+        own_p.assign((size_t)need * std::max<size_t>(1, width), 0);
+        own_c.assign((size_t)need, 0.0);
+        rp = own_p.data(); rcst = own_c.data(); cap = need;
+    }
+    int32_t n_rec = 0;
+    int32_t rc = search_pointers(n, lens, opts, profile_cost, &pc, best_pointers, &cost, rp, rcst, cap, &n_rec);
     if (pc.rc != MT_OK) return pc.rc;
     if (rc != MT_OK) return rc;
+    if (n_records) *n_records = n_rec;
+    if (rp != rec_pointers && rec_pointers && rec_cost) {
+        const int32_t keep = std::min(std::min(n_rec, cap), max_records);
+        if (keep > 0) {
+            std::memcpy(rec_pointers, rp, sizeof(int32_t) * width * keep);
+            std::memcpy(rec_cost, rcst, sizeof(double) * keep);
+        }
+    }
+    if (playoff) {
+        // Alg. 1 returns the best record as it was profiled once; schedules a few percent apart are not separated by
+        // one short measurement, so the leaders (and the one-stage matrix) are measured again, longer.
+        mt_search_opts longer = *opts;
+        longer.runs = opts->playoff_runs >= 1 ? opts->playoff_runs : 21;
+        ProfileCost pcf{ctx, &longer, inputs, outputs, n};
+        rc = playoff_pointers(n, lens, opts->n_stages, rp, rcst, std::min(n_rec, cap), opts->playoff_top, profile_cost, &pcf,
+                              best_pointers, &cost, nullptr);
+        if (pcf.rc != MT_OK) return pcf.rc;
+        if (rc != MT_OK) return rc;
+    }
     // Streams in use at a time, the same number in every stage: on this machine about four queues are served at once
     // (the main stream is one of them), so with five tenants or more fewer streams than tenants can be faster.
     int32_t conc[MT_MAX_STAGES];

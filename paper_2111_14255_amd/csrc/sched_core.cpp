@@ -194,6 +194,45 @@ int32_t search_pointers(int32_t n_tenants, const int32_t *lens, const mt_search_
     return MT_OK;
 }
 
+// Play-off over the record memory (an addition to Alg. 1, whose last step returns the best record as profiled once).
+// Candidates: the top_k distinct matrices by (profiled cost, position in the record memory), then the matrix with every
+// operator in stage 1 unless it is one of them.  Each is measured again with `cost` (which the caller makes a longer
+// measurement); the lowest wins, the earlier candidate on ties.
+int32_t playoff_pointers(int32_t n_tenants, const int32_t *lens, int32_t n_stages, const int32_t *rec_pointers,
+                         const double *rec_cost, int32_t n_records, int32_t top_k, mt_cost_fn cost, void *user,
+                         int32_t *best_pointers, double *best_cost, int32_t *n_evaluated) {
+    if (!lens || !cost || !best_pointers || !best_cost) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (n_tenants < 1 || n_tenants > MT_MAX_TENANTS) return fail(MT_ERR_INVALID_ARG, "tenant count out of range");
+    if (n_stages < 1 || n_stages > MT_MAX_STAGES) return fail(MT_ERR_INVALID_ARG, "stage count out of range");
+    if (n_records < 0 || (n_records > 0 && (!rec_pointers || !rec_cost))) return fail(MT_ERR_INVALID_ARG, "bad record memory");
+    const int P = n_stages - 1;
+    const int width = n_tenants * P;
+    std::vector<int32_t> order(n_records);
+    for (int j = 0; j < n_records; ++j) order[j] = j;
+    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return rec_cost[x] < rec_cost[y]; });
+    std::vector<std::vector<int32_t>> cands;
+    auto known = [&](const std::vector<int32_t> &m) { return std::find(cands.begin(), cands.end(), m) != cands.end(); };
+    for (int32_t j : order) {
+        std::vector<int32_t> m(rec_pointers + (size_t)j * width, rec_pointers + (size_t)(j + 1) * width);
+        if (!known(m)) cands.push_back(std::move(m));
+        if ((int)cands.size() >= std::max(1, top_k)) break;
+    }
+    std::vector<int32_t> one(width);
+    for (int i = 0; i < n_tenants; ++i)
+        for (int j = 0; j < P; ++j) one[i * P + j] = lens[i];
+    if (!known(one)) cands.push_back(one);
+    int best = -1;
+    double best_c = 0;
+    for (size_t c = 0; c < cands.size(); ++c) {
+        const double v = cost(cands[c].data(), user);
+        if (best < 0 || v < best_c) { best = (int)c; best_c = v; }     // strict: the earlier candidate wins a tie
+    }
+    if (width > 0) std::memcpy(best_pointers, cands[best].data(), sizeof(int32_t) * width);
+    *best_cost = best_c;
+    if (n_evaluated) *n_evaluated = (int32_t)cands.size();
+    return MT_OK;
+}
+
 int32_t proportional_cu_share(int32_t n_tenants, int32_t cu_count, const double *weight, int32_t *share) {
     if (!weight || !share) return fail(MT_ERR_INVALID_ARG, "NULL argument");
     if (n_tenants < 1 || n_tenants > MT_MAX_TENANTS || cu_count < 8)
@@ -330,6 +369,13 @@ int32_t mt_issue_order_of_stage(int32_t n_tenants, const int32_t *slices, int32_
     }
     *n_out = (int32_t)v.size();
     return MT_OK;
+}
+
+int32_t mt_playoff_pointers(int32_t n_tenants, const int32_t *lens, int32_t n_stages, const int32_t *rec_pointers,
+                            const double *rec_cost, int32_t n_records, int32_t top_k, mt_cost_fn cost, void *user,
+                            int32_t *best_pointers, double *best_cost, int32_t *n_evaluated) {
+    return mt::playoff_pointers(n_tenants, lens, n_stages, rec_pointers, rec_cost, n_records, top_k, cost, user,
+                                best_pointers, best_cost, n_evaluated);
 }
 
 int32_t mt_search_pointers(int32_t n_tenants, const int32_t *lens, const mt_search_opts *opts, mt_cost_fn cost,

@@ -172,3 +172,71 @@ def test_operator_set_completion_workloads(name):
     # grouped convolution, local response normalisation and a stand-alone add inside whole tenants
     mix = check_config(name)
     mix.close()
+
+
+@pytest.mark.parametrize("name", ["mix_vgg_r18", "mix_r34_r50", "mix_r50_r101", "mix_vgg_r18_r50", "mix_r18_r34_r50", "mix_5"])
+def test_paper_tenant_mixes(name):
+    # the other tenant combinations of the paper's scalability tables (Tables I-II), the five-tenant one included
+    mix = check_config(name)
+    mix.close()
+
+
+def test_random_search_on_the_gpu_returns_a_valid_schedule_with_the_same_bits():
+    # Sec. IV-D's random search with the profiled makespan as cost, then a play-off over its records
+    cfg = configs.ALL["cfg1"]
+    mix = Mix(cfg.models(), cfg.seed, cfg.input_dist)
+    try:
+        ctx = mix.ctx
+        lens = ctx.lens()
+        outs = [ctx.make_output(t) for t in range(3)]
+        base, _ = mix.run(ctx.sequential())
+        for playoff in (0, 3):
+            rho, cost, rec = ctx.search(mix.inputs, outs, 3, rounds=2, candidates=3, runs=3, warmup=1, seed=17,
+                                        algo=B.MT_SEARCH_RANDOM, seed_baselines=True, playoff_top=playoff, playoff_runs=5)
+            assert len(rho) == 3 and all(len(r) == 2 and 0 <= r[0] <= r[1] <= n for r, n in zip(rho, lens))
+            assert 2 <= len(rec) <= 2 * 3 * 3 + 2 and all(c > 0 for _, c in rec)         # infeasible draws are skipped
+            assert rec[0][0] == [[n, n] for n in lens]                                  # the one-stage matrix is recorded first
+            if playoff == 0:
+                assert cost == min(c for _, c in rec) and (rho, cost) in [(r, c) for r, c in rec]
+            else:
+                assert rho in [r for r, _ in rec] and cost > 0
+            got, tm = mix.run(ctx.schedule(rho, 3))
+            assert tm["n_launches"] == sum(lens)
+            for t in range(3):
+                assert np.array_equal(got[t].view(np.uint32), base[t].view(np.uint32))
+                assert_close(got[t], mix.oracle()[t], cfg.dtype, "random search tenant %d" % t)
+    finally:
+        mix.close()
+
+
+def test_tenant_registered_after_a_parallel_issue_run():
+    # the issuing thread added for a later tenant must wait for the next run instead of waking for the finished one
+    from synth import weights
+    from paper_2111_14255_amd import api
+    cfg = configs.ALL["cfg1"]
+    specs = cfg.models()
+    ctx = api.Context(0)
+    try:
+        raws = [weights.make_params(m, cfg.seed, t) for t, m in enumerate(specs)]
+        xs = [weights.make_input(m, cfg.seed, t, cfg.input_dist) for t, m in enumerate(specs)]
+        from oracle import forward as OF
+        refs = [OF.forward(m, OF.prepare_params(m, raw), x) for m, raw, x in zip(specs, raws, xs)]
+        inputs, outs = [], []
+        for k in range(3):
+            model = api.Model(specs[k], raws[k])
+            ctx.register(model)
+            model.close()
+            inputs.append(ctx.make_input(k, xs[k]))
+            outs.append(ctx.make_output(k))
+            for flags in (B.MT_SCHED_PARALLEL_ISSUE, B.MT_SCHED_PARALLEL_ISSUE | B.MT_SCHED_HOST_BARRIER):
+                s = ctx.schedule(even_split(ctx.lens(), 2), 2, flags=flags)
+                for _ in range(3):
+                    for o in outs:
+                        o.fill_(float("nan"))
+                    tm = ctx.run(s, inputs, outs)
+                    assert tm["n_launches"] == sum(ctx.lens())
+                    for t in range(k + 1):
+                        assert_close(ctx.output_to_numpy(t, outs[t]), refs[t], cfg.dtype, "tenant %d of %d" % (t, k + 1))
+                s.close()
+    finally:
+        ctx.close()

@@ -92,7 +92,7 @@ def test_issue_order_examples_and_oracle():
 
 def lib_search(lens, n_stages, rounds, cands, seed, algo, cost, seed_baselines=0):
     n, P = len(lens), n_stages - 1
-    opts = B.mt_search_opts(algo, n_stages, rounds, cands, 1, 0, 0, 0, seed_baselines, 0, 0, 0, seed)
+    opts = B.mt_search_opts(algo, n_stages, rounds, cands, 1, 0, 0, 0, seed_baselines, 0, 0, 0, 0, 0, seed)
     cap = rounds * n * cands + 2
     best = (I32 * max(1, n * P))()
     bc = C.c_double()
@@ -143,6 +143,53 @@ def test_random_search_matches_oracle():
     rho, c, recs = lib_search(lens, 3, 10, 5, 99, B.MT_SEARCH_RANDOM, _cost(target))
     orho, oc, orecs, skipped = S.random_search(lens, 2, 10 * 2 * 5, _cost(target), 99)
     assert recs == orecs and rho == orho and c == oc and skipped > 0
+
+
+def lib_playoff(lens, n_stages, recs, top_k, cost):
+    n, P = len(lens), n_stages - 1
+    flat = [v for rho, _ in recs for row in rho for v in row]
+    costs = (C.c_double * max(1, len(recs)))(*[c for _, c in recs])
+    best = (I32 * max(1, n * P))()
+    bc = C.c_double()
+    nev = I32()
+    seen = []
+
+    def cb(ptr, _user):
+        rho = [[ptr[i * P + j] for j in range(P)] for i in range(n)]
+        seen.append(rho)
+        return cost(rho)
+
+    fn = B.mt_cost_fn(cb)
+    rc = B.load().mt_playoff_pointers(n, arr(lens), n_stages, arr(flat), costs, len(recs), top_k, fn, None, best, C.byref(bc), C.byref(nev))
+    assert rc == 0, B.load().mt_last_error()
+    assert nev.value == len(seen)
+    return [[best[i * P + j] for j in range(P)] for i in range(n)], bc.value, seen
+
+
+def test_playoff_matches_oracle_and_can_overturn_the_first_measurement():
+    lens = [23, 21, 54]
+    target = [[5, 11, 17], [3, 9, 20], [10, 30, 50]]
+    _, _, recs = S.coordinate_descent(lens, 3, 2, 4, _cost(target), 11, seed_baselines=True)
+    recs = recs + [recs[3]]                                       # a duplicate matrix must be measured once only
+    one_stage = [[n] * 3 for n in lens]
+    # second measurement: the noisy first one is replaced by a cost that prefers the one-stage matrix, then the third-best record
+    order = sorted(range(len(recs)), key=lambda j: (recs[j][1], j))
+    third = recs[order[2]][0]
+    final = lambda rho: 1.0 if rho == one_stage else 2.0 if rho == third else 3.0 + _cost(target)(rho)
+    for top_k in (1, 3, 5):
+        rho, c, seen = lib_playoff(lens, 4, recs, top_k, final)
+        orho, oc, oscored = S.playoff(lens, 3, recs, top_k, final)
+        assert rho == orho and c == oc and seen == [m for m, _ in oscored]
+        assert rho == one_stage and c == 1.0 and seen[-1] == one_stage and len(seen) == top_k + 1
+    # without the one-stage preference the winner is the best of the second measurements, not of the first
+    final2 = lambda rho: 2.0 if rho == third else 3.0 + _cost(target)(rho)
+    rho, c, seen = lib_playoff(lens, 4, recs, 3, final2)
+    assert (rho, c) == S.playoff(lens, 3, recs, 3, final2)[:2] and rho == third
+    # the one-stage matrix is not measured twice when it is already among the leaders; ties go to the earlier candidate
+    recs2 = [(one_stage, 0.1)] + recs
+    rho, c, seen = lib_playoff(lens, 4, recs2, 2, lambda r: 5.0)
+    assert seen.count(one_stage) == 1 and rho == one_stage and len(seen) == 2
+    assert (rho, c) == S.playoff(lens, 3, recs2, 2, lambda r: 5.0)[:2]
 
 
 def test_single_stage_search_is_trivial():
