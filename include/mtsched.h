@@ -316,6 +316,22 @@ int32_t mt_issue_order_of_stage(int32_t n_tenants, const int32_t *slices, int32_
  * Blocks until every tenant has finished.  t may be NULL. */
 int32_t mt_run(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *const *outputs, mt_timings *t);
 
+/* mt_run for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): the same pass on the same streams with the same kernels, but the partial-sum workspaces and
+ * arrival counters of every operator whose reduction is split over workgroups are taken from a fixed array of
+ * MT_STATIC_SCRATCH_BYTES bytes of device memory that the library's code object holds on every GPU it is loaded on,
+ * instead of from the tenants' arenas.  The call allocates nothing on the device: no hipMalloc, no hipFree, no graph
+ * instantiation, no stream creation; the schedule must have been created without MT_SCHED_GRAPH,
+ * MT_SCHED_STREAM_GRAPHS and MT_SCHED_PARALLEL_ISSUE (their first run captures graphs or starts threads):
+ * MT_ERR_INVALID_ARG otherwise.  The counters' part of the array is cleared by a fill kernel at the start of each call
+ * (not a memset node, so that a caller may capture the call); workspaces need no clearing.  If the tenants together
+ * need more than the array holds the call fails with MT_ERR_OUT_OF_MEMORY before anything is launched, and
+ * mt_last_error states both figures.  Outputs have the bits of mt_run.  All calls on one GPU share the array, which
+ * keeps the last call's contents: two calls that overlap in time on one GPU (from two contexts or two host threads)
+ * race on it and must be serialised by the caller.  inputs / outputs / t as for mt_run. */
+#define MT_STATIC_SCRATCH_BYTES (16u << 20)
+int32_t mt_run_static_scratch(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *const *outputs, mt_timings *t);
+
 /* Measurement aid: runs each operator of one tenant `repeats` times back to back on one stream between
  * two events and reports the mean duration per launch.  op_ms: host [num ops]. */
 int32_t mt_profile_ops(mt_ctx *ctx, int32_t tenant, const void *input, void *output, int32_t repeats, float *op_ms);

@@ -270,6 +270,13 @@ class Context:
                 "first_op_done_ms": [tm.first_op_done_ms[i] for i in range(n)], "n_fused": tm.n_fused,
                 "tenant_done_ms": [tm.tenant_done_ms[i] for i in range(n)]}
 
+    def run_static_scratch(self, sched, inputs, outputs=None):
+        """One pass through mt_run_static_scratch (no device allocation; split workspaces in the library's fixed array)."""
+        ins, outs, tm, n, _ = inputs if outputs is None else self.bind(inputs, outputs)
+        B.check(self.lib.mt_run_static_scratch(self.h, sched.h, ins, outs, C.byref(tm)))
+        return {"makespan_ms": tm.makespan_ms, "host_issue_ms": tm.host_issue_ms, "n_launches": tm.n_launches,
+                "stage_ms": [tm.stage_ms[i] for i in range(tm.n_stages)], "n_fused": tm.n_fused}
+
     def run_makespan(self, sched, bound):
         """One pass on bound buffers; returns (makespan_ms, host_issue_ms) only: the cheap form for timing loops."""
         tm = bound[2]

@@ -10,6 +10,7 @@ from . import build as _build
 
 MT_MAX_TENANTS = 16
 MT_MAX_STAGES = 16
+MT_STATIC_SCRATCH_BYTES = 16 << 20
 
 MT_OK = 0
 MT_ERR_INVALID_ARG = -1
@@ -111,6 +112,7 @@ SIGNATURES = {
     "mt_expand_pointers": (_i32, [_i32, _pi32, _i32, _pi32, _pi32]),
     "mt_issue_order_of_stage": (_i32, [_i32, _pi32, _i32, _i32, _pi32, _pi32]),
     "mt_run": (_i32, [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(mt_timings)]),
+    "mt_run_static_scratch": (_i32, [_vp, _vp, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(mt_timings)]),
     "mt_profile_ops": (_i32, [_vp, _i32, _vp, _vp, _i32, _pf]),
     "mt_search_pointers": (_i32, [_i32, _pi32, C.POINTER(mt_search_opts), mt_cost_fn, _vp, _pi32, _pd, _pi32, _pd, _i32, _pi32]),
     "mt_playoff_pointers": (_i32, [_i32, _pi32, _i32, _pi32, _pd, _i32, _i32, mt_cost_fn, _vp, _pi32, _pd, _pi32]),

@@ -120,6 +120,9 @@ int launch_dwpw(const OpArgs &dw, const OpArgs &pw, void *stream);   // depthwis
 bool pwdw_fusable(const OpArgs &pw, const OpArgs &dw);
 int launch_pwdw(const OpArgs &pw, const OpArgs &dw, void *stream);   // 1x1 convolution + the depthwise 3x3 that reads it on a small map, one launch
 int launch_fill_u32(uint32_t *p, size_t n, uint32_t v, void *stream);
+// Device address of the library's fixed scratch array (MT_STATIC_SCRATCH_BYTES bytes) on `device`, which must be the
+// current device; looked up once per device.  Returns a hipError_t as int.
+int static_scratch_address(int device, void **ptr);
 int launch_probe(uint32_t *out, int n_groups, void *stream);
 // Diagnostics: a register-only loop of 4 * iters 32x32x16 matrix instructions per wave (sink: n_groups * 256 floats), and
 // a 16-byte grid-stride copy (mode 0) or read (mode 1; dst then holds n_groups * 256 words) of `bytes` bytes.

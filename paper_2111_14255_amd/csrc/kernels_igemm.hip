@@ -20,6 +20,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <mutex>
 #include <type_traits>
 #include <utility>
 
@@ -1360,6 +1361,33 @@ int launch_peak_stream(int mode, const void *src, void *dst, size_t bytes, int n
     if (mode == 0) hipLaunchKernelGGL(peak_stream_kernel<0>, dim3((unsigned)n_groups), dim3(256), 0, st, (const u32x4 *)src, (u32x4 *)dst, bytes / 16);
     else hipLaunchKernelGGL(peak_stream_kernel<1>, dim3((unsigned)n_groups), dim3(256), 0, st, (const u32x4 *)src, (u32x4 *)dst, bytes / 16);
     return (int)hipGetLastError();
+}
+
+// ---- fixed scratch for callers that cannot allocate ---------------------------------------------------------------
+// Split-K workspaces and arrival counters of mt_run_static_scratch live here.  In host code the array's name is only a
+// handle for the symbol lookup below: every use of the memory (kernel arguments, fills) goes through the address that
+// hipGetSymbolAddress returned for the device in question, because each GPU holds its own copy at its own address.
+static __device__ __align__(256) unsigned char scratch[MT_STATIC_SCRATCH_BYTES];
+
+int static_scratch_address(int device, void **ptr) {
+    constexpr int MAX_DEV = 64;
+    static std::mutex mu;
+    static void *addr[MAX_DEV] = {};
+    if (!ptr || device < 0 || device >= MAX_DEV) return (int)hipErrorInvalidValue;
+    std::lock_guard<std::mutex> lk(mu);
+    if (!addr[device]) {
+        int cur = -1;
+        hipError_t e = hipGetDevice(&cur);
+        if (e != hipSuccess) return (int)e;
+        if (cur != device) return (int)hipErrorInvalidDevice;      // the lookup answers for the current device
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return (int)e;
+        if (!p) return (int)hipErrorInvalidSymbol;
+        addr[device] = p;
+    }
+    *ptr = addr[device];
+    return 0;
 }
 
 int launch_igemm(const OpArgs &a, void *stream) {

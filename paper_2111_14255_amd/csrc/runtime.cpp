@@ -348,6 +348,10 @@ struct Tenant {
     std::vector<uint8_t> fuse_pool;  // operator i is a convolution whose epilogue can apply the 2x2 max pooling operator i + 1
     std::vector<OpArgs> pool_args;   // its arguments for that form (pooled output tensor, quad pixel walk)
     std::vector<uint8_t> short_kernel;   // operator runs on a short, latency-bound kernel (see MT_SCHED_PRIORITIZE_SHORT)
+    // mt_run_static_scratch: where each split operator's counters and workspace sit inside the tenant's two blocks of the
+    // fixed scratch array (byte offsets; blocks are laid out per call, counters of all tenants first)
+    std::vector<size_t> st_cnt_off, st_ws_off;
+    size_t st_cnt_bytes = 0, st_ws_bytes = 0;
 };
 
 struct StreamKey {
@@ -427,6 +431,9 @@ struct mt_schedule {
     std::vector<void *> cap_out;
     // MT_SCHED_STREAM_GRAPHS: one graph per (stage, stream) with the launches of that stream in that stage
     std::vector<std::array<hipGraphExec_t, MT_MAX_TENANTS>> slice_exec;
+    // set for the duration of an mt_run_static_scratch call: base of the fixed scratch array and each tenant's blocks in it
+    uint8_t *st_base = nullptr;
+    size_t st_cnt_base[MT_MAX_TENANTS] = {}, st_ws_base[MT_MAX_TENANTS] = {};
 };
 
 // Hands every graph of a schedule to the context for release at mt_destroy.
@@ -504,6 +511,13 @@ int launch_item(const mt_ctx *ctx, const mt_schedule *s, const IssueItem &it, co
     const Tenant &t = *ctx->tenants[it.tenant];
     const int tp = s->prio[it.tenant];
     OpArgs a = patched(t, it.op, inputs[it.tenant], outputs[it.tenant]);
+    // partial sums and arrival counters from the fixed scratch array instead of the arena
+    auto redirect = [&](OpArgs &o) {
+        if (!s->st_base || !o.ws) return;
+        o.ws = (float *)(s->st_base + s->st_ws_base[it.tenant] + t.st_ws_off[it.op]);
+        o.counters = (uint32_t *)(s->st_base + s->st_cnt_base[it.tenant] + t.st_cnt_off[it.op]);
+    };
+    redirect(a);
     a.prio = tp >= 0 ? tp : (t.short_kernel[it.op] || it.fuse == 2 || it.fuse == 3) ? 3 : 0;
     if (it.fuse == 2 || it.fuse == 3) {
         OpArgs prev = patched(t, it.op - 1, inputs[it.tenant], outputs[it.tenant]);
@@ -513,6 +527,7 @@ int launch_item(const mt_ctx *ctx, const mt_schedule *s, const IssueItem &it, co
     if (it.fuse == 4) {
         OpArgs b = t.pool_args[it.op];
         b.prio = a.prio;
+        redirect(b);
         if (t.reads_input[it.op]) b.x = inputs[it.tenant];
         if (t.writes_output[it.op + 1]) b.y = outputs[it.tenant];
         return launch_raw(b, st);
@@ -1336,6 +1351,14 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
         t->args[i] = a;
         o.w_host.clear(); o.w_host.shrink_to_fit();
     }
+    t->st_cnt_off.assign(nops, 0);
+    t->st_ws_off.assign(nops, 0);
+    for (size_t i = 0; i < nops; ++i) {
+        const OpRec &o = t->model.ops[i];
+        if (!t->args[i].ws) continue;
+        t->st_cnt_off[i] = t->st_cnt_bytes; t->st_cnt_bytes += align_up(o.cnt_bytes);
+        t->st_ws_off[i] = t->st_ws_bytes; t->st_ws_bytes += align_up(o.ws_bytes);
+    }
     // short kernels: few workgroups of little work each, bound by launch and memory latency
     t->short_kernel.assign(nops, 0);
     for (size_t i = 0; i < nops; ++i) {
@@ -1646,7 +1669,47 @@ int32_t mt_schedule_destroy(mt_schedule *s) {
 }
 
 // ---- run -------------------------------------------------------------------------------------
+static int32_t run_pass(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *const *outputs, mt_timings *tm);
+
 int32_t mt_run(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *const *outputs, mt_timings *tm) {
+    return run_pass(ctx, s, inputs, outputs, tm);
+}
+
+int32_t mt_run_static_scratch(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *const *outputs, mt_timings *tm) {
+    if (!ctx || !s || !inputs || !outputs) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (s->ctx != ctx) return fail(MT_ERR_INVALID_ARG, "schedule belongs to another (or a destroyed) context");
+    if (s->flags & (MT_SCHED_GRAPH | MT_SCHED_STREAM_GRAPHS | MT_SCHED_PARALLEL_ISSUE))
+        return fail(MT_ERR_INVALID_ARG, "graph replay and parallel issue allocate on their first run: not available without allocation");
+    HIP_TRY(hipSetDevice(ctx->device));
+    size_t cnt_total = 0, ws_total = 0;
+    for (int i = 0; i < s->n_tenants; ++i) {
+        cnt_total += ctx->tenants[i]->st_cnt_bytes;
+        ws_total += ctx->tenants[i]->st_ws_bytes;
+    }
+    if (cnt_total + ws_total > (size_t)MT_STATIC_SCRATCH_BYTES)
+        return fail(MT_ERR_OUT_OF_MEMORY, "the split workspaces of these tenants need " + std::to_string(cnt_total + ws_total) +
+                                              " bytes, the fixed scratch array holds " + std::to_string((size_t)MT_STATIC_SCRATCH_BYTES));
+    void *base = nullptr;
+    const int e = static_scratch_address(ctx->device, &base);
+    if (e != 0) return fail(MT_ERR_HIP, std::string("fixed scratch array: ") + hipGetErrorString((hipError_t)e));
+    size_t cnt_at = 0, ws_at = cnt_total;                  // counters of all tenants first: one fill clears them
+    for (int i = 0; i < s->n_tenants; ++i) {
+        s->st_cnt_base[i] = cnt_at; cnt_at += ctx->tenants[i]->st_cnt_bytes;
+        s->st_ws_base[i] = ws_at; ws_at += ctx->tenants[i]->st_ws_bytes;
+    }
+    if (cnt_total > 0) {
+        // The array keeps what the last call (of any context) left; counters must start at zero.  The fill runs on the
+        // main stream ahead of the start event that every tenant stream waits for.
+        const int fe = launch_fill_u32((uint32_t *)base, cnt_total / sizeof(uint32_t), 0u, ctx->main_stream);
+        if (fe != 0) return fail(MT_ERR_HIP, std::string("clearing the counters: ") + hipGetErrorString((hipError_t)fe));
+    }
+    s->st_base = (uint8_t *)base;
+    const int32_t rc = run_pass(ctx, s, inputs, outputs, tm);
+    s->st_base = nullptr;
+    return rc;
+}
+
+static int32_t run_pass(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *const *outputs, mt_timings *tm) {
     if (!ctx || !s || !inputs || !outputs) return fail(MT_ERR_INVALID_ARG, "NULL argument");
     if (s->ctx != ctx) return fail(MT_ERR_INVALID_ARG, "schedule belongs to another (or a destroyed) context");
     for (int i = 0; i < s->n_tenants; ++i) {
