@@ -163,6 +163,23 @@ int32_t mt_get_device_info(const mt_ctx *ctx, mt_device_info *out);
  * register values (CU_ID = bits 8-11, SH_ID = bit 12, SE_ID = bits 13-15 of HW_ID; XCC_ID = low 4 bits). */
 int32_t mt_probe_cu_mask(mt_ctx *ctx, int32_t share, int32_t first_cu, int32_t n_groups, uint32_t *hw_ids);
 
+/* Diagnostic: what one stage barrier (Sec. III-B "Stage") costs on the tenant streams of this context.  n_streams
+ * streams each run `rounds` rounds of one one-workgroup kernel; between rounds they are synchronised by
+ *   kind 0  nothing (the reference: n_streams independent chains),
+ *   kind 1  the barrier mt_run uses: every stream records an event and waits for the events of all others,
+ *   kind 2  stream memory operations: every stream writes the round number to a word of its own
+ *           (hipStreamWriteValue32) and waits until the words of all others have reached it (hipStreamWaitValue32, >=);
+ *           all writes of a round are queued before any wait, so streams that share a hardware queue cannot block
+ *           each other,
+ *   kind 3  a counter: every stream launches a one-thread kernel that adds 1 to a shared word, then waits once until the
+ *           word has reached round * n_streams (hipStreamWaitValue32, >=): 2 n runtime calls instead of n^2,
+ *   kind 4  events through the main stream: every stream records an event, the main stream waits for all of them and
+ *           records one, every stream waits for that: 3 n + 1 runtime calls.
+ *   Kinds 2 and 3 give MT_ERR_HIP if the device does not support stream memory operations.
+ * us_per_round: host float, the mean time of one round over all streams (the barrier's cost is the difference to
+ * kind 0).  n_streams 1 .. MT_MAX_TENANTS, rounds 1 .. 4096. */
+int32_t mt_probe_barrier_cost(mt_ctx *ctx, int32_t n_streams, int32_t kind, int32_t rounds, float *us_per_round);
+
 /* Diagnostic: creates n_streams streams (each restricted to `share` units, 0 = unmasked), keeps them all alive, and
  * measures on each the mean time of `n_launches` dependent one-workgroup kernels issued while the context's main
  * stream waits for the stream's completion event (the pattern of a stage).  us_per_launch: host [n_streams]. */
@@ -293,6 +310,15 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
  * per-stage timings (the stage barriers stay ordinary events).  Not combinable with MT_SCHED_GRAPH,
  * MT_SCHED_PARALLEL_ISSUE or MT_SCHED_TIME_FIRST_OP. */
 #define MT_SCHED_STREAM_GRAPHS 32
+/* MT_SCHED_COUNTER_BARRIER: the barrier between stages (Sec. III-B "Stage") is taken with one counter word per run instead
+ * of events: at the end of a stage every stream of the stage launches a one-thread kernel that adds 1 to the word, and a
+ * stream of a later stage waits, with one hipStreamWaitValue32 packet on its queue, until the word has reached the number
+ * of streams that ended the stages before.  2 n runtime calls per barrier instead of n + n (n - 1) event records and
+ * waits; the stage's events are still recorded for the timings.  Same ordering, same results.  Works with the single
+ * issuing thread and with MT_SCHED_PARALLEL_ISSUE (the arrivals of a stage are queued before any wait for them, so
+ * streams that share a hardware queue cannot block each other); not with MT_SCHED_GRAPH, MT_SCHED_STREAM_GRAPHS or
+ * MT_SCHED_HOST_BARRIER.  MT_ERR_HIP from mt_schedule_create if the device has no stream memory operations. */
+#define MT_SCHED_COUNTER_BARRIER 2048
 int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, const int32_t *pointers,
                            const int32_t *stage_concurrency, const int32_t *cu_share,
                            int32_t issue_order, int32_t flags, mt_schedule **out);

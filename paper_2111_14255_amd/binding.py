@@ -35,6 +35,7 @@ MT_SCHED_PRIORITIZE_SHORT = 256
 MT_SCHED_TIME_TENANTS = 512
 MT_SCHED_HOST_BARRIER = 1024
 MT_SCHED_STREAM_GRAPHS = 32
+MT_SCHED_COUNTER_BARRIER = 2048
 MT_SEARCH_COORDINATE, MT_SEARCH_RANDOM = 0, 1
 
 
@@ -86,6 +87,7 @@ SIGNATURES = {
     "mt_destroy": (_i32, [_vp]),
     "mt_get_device_info": (_i32, [_vp, C.POINTER(mt_device_info)]),
     "mt_probe_dispatch_latency": (_i32, [_vp, _i32, _i32, _i32, _pf]),
+    "mt_probe_barrier_cost": (_i32, [_vp, _i32, _i32, _i32, _pf]),
     "mt_probe_cu_mask": (_i32, [_vp, _i32, _i32, _i32, C.POINTER(C.c_uint32)]),
     "mt_probe_peak_mfma": (_i32, [_vp, _i32, _i32, _pf]),
     "mt_probe_peak_stream": (_i32, [_vp, _i32, C.c_size_t, _i32, _i32, _pf]),

@@ -124,6 +124,7 @@ int launch_fill_u32(uint32_t *p, size_t n, uint32_t v, void *stream);
 // current device; looked up once per device.  Returns a hipError_t as int.
 int static_scratch_address(int device, void **ptr);
 int launch_probe(uint32_t *out, int n_groups, void *stream);
+int launch_arrive(uint32_t *counter, void *stream);                 // one thread adds 1 to *counter (system scope, release)
 // Diagnostics: a register-only loop of 4 * iters 32x32x16 matrix instructions per wave (sink: n_groups * 256 floats), and
 // a 16-byte grid-stride copy (mode 0) or read (mode 1; dst then holds n_groups * 256 words) of `bytes` bytes.
 int launch_peak_mfma(int dtype, float *sink, int n_groups, int iters, void *stream);

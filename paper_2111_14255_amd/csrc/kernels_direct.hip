@@ -382,6 +382,12 @@ __global__ void __launch_bounds__(64) probe_kernel(uint32_t *out) {
     }
 }
 
+// Arrival at a stage barrier taken with a counter: one thread bumps the word that the queues of the next stage poll.
+// System scope, release: the word lives in host-visible signal memory and the increment must not pass the stage's stores.
+__global__ void __launch_bounds__(64) arrive_kernel(uint32_t *counter) {
+    if (threadIdx.x == 0) __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 __global__ void fill_u32_kernel(uint32_t *p, size_t n, uint32_t v) {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
@@ -483,6 +489,11 @@ int launch_direct(const OpArgs &a, void *stream) {
 
 int launch_probe(uint32_t *out, int n_groups, void *stream) {
     hipLaunchKernelGGL(probe_kernel, dim3((unsigned)n_groups), dim3(64), 0, (hipStream_t)stream, out);
+    return (int)hipGetLastError();
+}
+
+int launch_arrive(uint32_t *counter, void *stream) {
+    hipLaunchKernelGGL(arrive_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, counter);
     return (int)hipGetLastError();
 }
 

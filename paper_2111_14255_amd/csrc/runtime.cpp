@@ -402,6 +402,7 @@ struct mt_ctx {
     std::vector<hipStream_t> parked_streams;       // masked ones; released by purge_idle_streams
     uint32_t *probe_buf = nullptr;
     float best_dispatch_us = 0.f;
+    uint32_t *barrier_word = nullptr;    // MT_SCHED_COUNTER_BARRIER: arrivals of the current run (borrowed from the process's pool)
 };
 
 struct StagePlan {
@@ -424,6 +425,7 @@ struct mt_schedule {
     int n_launches = 0;
     int end_stage = -1;             // last stage that launches anything (-1: the schedule launches nothing)
     int n_fused = 0;                // operators that run inside the next operator's launch
+    std::vector<uint32_t> arrivals_upto;   // MT_SCHED_COUNTER_BARRIER: streams that have ended stages 0 .. st, summed
     int32_t prio[MT_MAX_TENANTS] = {0};   // wave priority of a tenant's kernels, 0..3; -1: 3 for its short kernels, 0 for the others
     // graph replay
     hipGraphExec_t graph_exec = nullptr;
@@ -570,6 +572,38 @@ PlainPool &plain_pool(int device) {
     return pools[device];
 }
 
+// Words of signal memory (what the queues' wait-for-value packets poll) belong to the process and are never freed:
+// contexts borrow them and hand them back.  Memory of this kind that a kernel has touched is not given back to the
+// allocator while the process runs.
+struct SignalPool {
+    std::mutex mu;
+    std::map<int, std::vector<uint32_t *>> idle;     // per device
+};
+SignalPool &signal_pool() {
+    static SignalPool p;
+    return p;
+}
+int32_t take_signal_word(int device, uint32_t **out) {
+    SignalPool &p = signal_pool();
+    std::lock_guard<std::mutex> lk(p.mu);
+    auto &v = p.idle[device];
+    if (!v.empty()) { *out = v.back(); v.pop_back(); return MT_OK; }
+    int can = 0;
+    HIP_TRY(hipDeviceGetAttribute(&can, hipDeviceAttributeCanUseStreamWaitValue, device));
+    if (!can) return fail(MT_ERR_HIP, "the device does not support stream memory operations");
+    uint32_t *w = nullptr;
+    HIP_TRY(hipExtMallocWithFlags((void **)&w, 8, hipMallocSignalMemory));    // this kind of memory comes in 8-byte allocations
+    HIP_TRY(hipMemset(w, 0, 8));
+    *out = w;
+    return MT_OK;
+}
+void return_signal_word(int device, uint32_t *w) {
+    if (!w) return;
+    SignalPool &p = signal_pool();
+    std::lock_guard<std::mutex> lk(p.mu);
+    p.idle[device].push_back(w);
+}
+
 // A new stream for `share` units starting at first_cu (0 = all units: a plain stream), timed; slow ones are parked.
 int32_t make_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t *out) {
     hipStream_t s = nullptr;
@@ -666,6 +700,8 @@ hipError_t wait_for_previous_stage(mt_ctx *ctx, const mt_schedule *s, int st, in
         return hipStreamWaitEvent(s->stream_at[st][stream], st == 0 ? ctx->ev_start : ctx->ev_stage[st - 1], 0);
     const int prev = s->stages[st].prev_stage;
     if (prev < 0) return hipStreamWaitEvent(s->stream_at[st][stream], ctx->ev_start, 0);
+    if (s->flags & MT_SCHED_COUNTER_BARRIER)      // one wait per stream: every stream of the stages so far has bumped the word
+        return hipStreamWaitValue32(s->stream_at[st][stream], ctx->barrier_word, s->arrivals_upto[prev], hipStreamWaitValueGte, 0xffffffffu);
     hipError_t e = hipSuccess;
     for (int pm : s->stages[prev].streams)
         if (s->stream_at[prev][pm] != s->stream_at[st][stream] && e == hipSuccess)     // the same stream is in order by itself
@@ -714,6 +750,7 @@ int32_t capture_slice_graphs(mt_ctx *ctx, mt_schedule *s, const void *const *inp
 // event and the streams of the next stage wait for all of them.  Under whole-schedule graph capture the main stream
 // waits for them too and records a stage event that the next stage waits for (a capture has to join its origin).
 int32_t issue_schedule(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, void *const *outputs, int *n_launch, bool alt = false) {
+    if (s->flags & MT_SCHED_COUNTER_BARRIER) HIP_TRY(hipStreamWriteValue32(ctx->main_stream, ctx->barrier_word, 0u, 0));
     HIP_TRY(hipEventRecord(ctx->ev_start, ctx->main_stream));
     int launches = 0;
     for (int st = 0; st < s->n_stages; ++st) {
@@ -733,6 +770,11 @@ int32_t issue_schedule(mt_ctx *ctx, mt_schedule *s, const void *const *inputs, v
         }
         if (ends_on_streams(s)) {
             for (int sm : sp.streams) HIP_TRY(hipEventRecord(ctx->ev_done[st][sm], s->stream_at[st][sm]));
+            if ((s->flags & MT_SCHED_COUNTER_BARRIER) && st < s->end_stage)
+                for (int sm : sp.streams) {
+                    const int e = launch_arrive(ctx->barrier_word, s->stream_at[st][sm]);
+                    if (e != 0) return fail(MT_ERR_HIP, std::string("arrival kernel: ") + hipGetErrorString((hipError_t)e));
+                }
             continue;
         }
         for (int sm : sp.streams) {
@@ -789,6 +831,8 @@ void issue_worker(mt_ctx *ctx, int w, uint64_t seen) {
                         e = hipEventRecord(ctx->ev_last[it.tenant], s->stream_at[st][w]);
                 }
                 if (e == hipSuccess) e = hipEventRecord(ctx->ev_done[st][w], s->stream_at[st][w]);
+                if (e == hipSuccess && (s->flags & MT_SCHED_COUNTER_BARRIER) && st < s->end_stage)
+                    e = (hipError_t)launch_arrive(ctx->barrier_word, s->stream_at[st][w]);
                 if (e != hipSuccess) {
                     std::lock_guard<std::mutex> lk(pool.mu);
                     pool.error_msg = std::string("issuing thread: ") + hipGetErrorString(e);
@@ -837,6 +881,7 @@ int32_t issue_schedule_parallel(mt_ctx *ctx, mt_schedule *s, const void *const *
     for (int st = 0; st < MT_MAX_STAGES; ++st) pool.stage_done[st].store(0);
     pool.finished.store(0);
     pool.error.store(0);
+    if (s->flags & MT_SCHED_COUNTER_BARRIER) HIP_TRY(hipStreamWriteValue32(ctx->main_stream, ctx->barrier_word, 0u, 0));
     HIP_TRY(hipEventRecord(ctx->ev_start, ctx->main_stream));
     {
         std::lock_guard<std::mutex> lk(pool.mu);
@@ -932,6 +977,7 @@ int32_t mt_destroy(mt_ctx *ctx) {
         if (kv.first.share != 0) (void)hipStreamDestroy(kv.second.stream);       // plain streams belong to the process
     for (hipStream_t ps : ctx->parked_streams) (void)hipStreamDestroy(ps);
     if (ctx->probe_buf) (void)hipFree(ctx->probe_buf);
+    return_signal_word(ctx->device, ctx->barrier_word);
     if (ctx->ev_start) (void)hipEventDestroy(ctx->ev_start);
     for (int s = 0; s < MT_MAX_STAGES; ++s) {
         if (ctx->ev_stage[s]) (void)hipEventDestroy(ctx->ev_stage[s]);
@@ -1080,6 +1126,94 @@ int32_t mt_probe_dispatch_latency(mt_ctx *ctx, int32_t n_streams, int32_t share,
     for (hipStream_t st : streams) (void)hipStreamDestroy(st);
     (void)hipFree(dev);
     return rc;
+}
+
+int32_t mt_probe_barrier_cost(mt_ctx *ctx, int32_t n_streams, int32_t kind, int32_t rounds, float *us_per_round) {
+    if (!ctx || !us_per_round) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (n_streams < 1 || n_streams > MT_MAX_TENANTS || kind < 0 || kind > 4 || rounds < 1 || rounds > 4096)
+        return fail(MT_ERR_INVALID_ARG, "argument out of range");
+    HIP_TRY(hipSetDevice(ctx->device));
+    if (kind == 2 || kind == 3) {
+        int can = 0;
+        HIP_TRY(hipDeviceGetAttribute(&can, hipDeviceAttributeCanUseStreamWaitValue, ctx->device));
+        if (!can) return fail(MT_ERR_HIP, "the device does not support stream memory operations");
+    }
+    // the plain tenant streams of the process, as mt_run uses them
+    std::vector<hipStream_t> st(n_streams);
+    std::vector<StreamKey> keys(n_streams);
+    for (int i = 0; i < n_streams; ++i) {
+        int32_t rc = get_stream(ctx, i, 0, 0, &st[i], &keys[i]);
+        if (rc != MT_OK) return rc;
+    }
+    auto release = [&]() {
+        for (int i = 0; i < n_streams; ++i) {
+            auto it = ctx->streams.find(keys[i]);
+            if (it != ctx->streams.end() && it->second.refs > 0) it->second.refs--;
+        }
+    };
+    if (!ctx->probe_buf) HIP_TRY(hipMalloc((void **)&ctx->probe_buf, 256));
+    // one word per stream (kind 2) or one in all (kind 3), borrowed from the process's pool and zeroed by the host
+    uint32_t *words[MT_MAX_TENANTS] = {};
+    auto free_words = [&]() {
+        for (uint32_t *w : words) return_signal_word(ctx->device, w);
+    };
+    for (int i = 0; (kind == 2 || (kind == 3 && i == 0)) && i < n_streams; ++i) {
+        int32_t rc = take_signal_word(ctx->device, &words[i]);
+        hipError_t e = rc == MT_OK ? hipMemset(words[i], 0, 8) : hipSuccess;
+        if (rc != MT_OK || e != hipSuccess) {
+            free_words(); release();
+            return rc != MT_OK ? rc : fail(MT_ERR_HIP, std::string("signal memory: ") + hipGetErrorString(e));
+        }
+    }
+    hipError_t e = hipSuccess;
+    float ms = 0.f;
+    uint32_t epoch = 0;
+    for (int rep = 0; rep < 2 && e == hipSuccess; ++rep) {                   // first pass warms up
+        e = hipEventRecord(ctx->ev_prof[0], ctx->main_stream);
+        for (int i = 0; i < n_streams && e == hipSuccess; ++i) e = hipStreamWaitEvent(st[i], ctx->ev_prof[0], 0);
+        for (int r = 0; r < rounds && e == hipSuccess; ++r) {
+            ++epoch;
+            for (int i = 0; i < n_streams && e == hipSuccess; ++i) e = (hipError_t)launch_probe(ctx->probe_buf + 2 * i, 1, st[i]);
+            if (kind == 1) {
+                hipEvent_t *ev = ctx->ev_done[r & 1];                        // two event sets alternate between rounds
+                for (int i = 0; i < n_streams && e == hipSuccess; ++i) e = hipEventRecord(ev[i], st[i]);
+                for (int i = 0; i < n_streams; ++i)
+                    for (int j = 0; j < n_streams && e == hipSuccess; ++j)
+                        if (j != i) e = hipStreamWaitEvent(st[i], ev[j], 0);
+            } else if (kind == 2) {
+                for (int i = 0; i < n_streams && e == hipSuccess; ++i) e = hipStreamWriteValue32(st[i], words[i], epoch, 0);
+                for (int i = 0; i < n_streams; ++i)
+                    for (int j = 0; j < n_streams && e == hipSuccess; ++j)
+                        if (j != i) e = hipStreamWaitValue32(st[i], words[j], epoch, hipStreamWaitValueGte, 0xffffffffu);
+            }
+            else if (kind == 3) {
+                for (int i = 0; i < n_streams && e == hipSuccess; ++i) e = (hipError_t)launch_arrive(words[0], st[i]);
+                for (int i = 0; i < n_streams && e == hipSuccess; ++i)
+                    e = hipStreamWaitValue32(st[i], words[0], epoch * (uint32_t)n_streams, hipStreamWaitValueGte, 0xffffffffu);
+            } else if (kind == 4) {
+                hipEvent_t *ev = ctx->ev_done[r & 1];
+                for (int i = 0; i < n_streams && e == hipSuccess; ++i) {
+                    e = hipEventRecord(ev[i], st[i]);
+                    if (e == hipSuccess) e = hipStreamWaitEvent(ctx->main_stream, ev[i], 0);
+                }
+                if (e == hipSuccess) e = hipEventRecord(ctx->ev_stage[r & 1], ctx->main_stream);
+                for (int i = 0; i < n_streams && e == hipSuccess; ++i) e = hipStreamWaitEvent(st[i], ctx->ev_stage[r & 1], 0);
+            }
+        }
+        for (int i = 0; i < n_streams && e == hipSuccess; ++i) {
+            e = hipEventRecord(ctx->ev_done[2][i], st[i]);
+            if (e == hipSuccess) e = hipStreamWaitEvent(ctx->main_stream, ctx->ev_done[2][i], 0);
+        }
+        if (e == hipSuccess) e = hipEventRecord(ctx->ev_prof[1], ctx->main_stream);
+        if (e == hipSuccess) e = hipEventSynchronize(ctx->ev_prof[1]);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, ctx->ev_prof[0], ctx->ev_prof[1]);
+    }
+    (void)hipDeviceSynchronize();
+    free_words();
+    release();
+    if (e != hipSuccess) return fail(MT_ERR_HIP, std::string("barrier probe: ") + hipGetErrorString(e));
+    *us_per_round = ms * 1e3f / (float)rounds;
+    return MT_OK;
 }
 
 int32_t mt_probe_peak_mfma(mt_ctx *ctx, int32_t dtype, int32_t iters, float *tflops) {
@@ -1467,6 +1601,8 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
         return fail(MT_ERR_INVALID_ARG, "per-stream graphs cannot be combined with whole-schedule replay, parallel issue or first-operator timing");
     if ((flags & MT_SCHED_TIME_FIRST_OP) && (flags & (MT_SCHED_GRAPH | MT_SCHED_PARALLEL_ISSUE)))
         return fail(MT_ERR_INVALID_ARG, "first-operator timing needs the single issuing thread and plain streams");
+    if ((flags & MT_SCHED_COUNTER_BARRIER) && (flags & (MT_SCHED_GRAPH | MT_SCHED_STREAM_GRAPHS | MT_SCHED_HOST_BARRIER)))
+        return fail(MT_ERR_INVALID_ARG, "the counter barrier runs on plain streams with device-side waits: not with graphs or the host-side barrier");
     if ((flags & MT_SCHED_HOST_BARRIER) && !(flags & MT_SCHED_PARALLEL_ISSUE))
         return fail(MT_ERR_INVALID_ARG, "the host-side barrier needs one issuing thread per stream (MT_SCHED_PARALLEL_ISSUE)");
     if ((flags & MT_SCHED_TIME_TENANTS) && (flags & (MT_SCHED_GRAPH | MT_SCHED_STREAM_GRAPHS)))
@@ -1555,6 +1691,18 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
         s->stages[st].prev_stage = last;
         if (!s->stages[st].items.empty()) last = st;
         s->end_stage = last;
+    }
+    if (flags & MT_SCHED_COUNTER_BARRIER) {
+        s->arrivals_upto.assign(n_stages, 0);
+        uint32_t sum = 0;
+        for (int st = 0; st < n_stages; ++st) {
+            sum += (uint32_t)s->stages[st].streams.size();
+            s->arrivals_upto[st] = sum;
+        }
+        if (!ctx->barrier_word) {
+            rc = take_signal_word(ctx->device, &ctx->barrier_word);
+            if (rc != MT_OK) { release_streams(s.get()); return rc; }
+        }
     }
     // The streams this schedule launches on are checked together: now and then a queue (masked, or the runtime's own
     // for a plain stream) passes the timing of make_stream alone but cannot run beside the others, and a

@@ -8,10 +8,19 @@
   fusion   every tenant alone and all tenants together, with and without the fused launches of neighbouring operators
            and with wave priorities (the runtime's additions to the paper's method)
 
+  barriers what a stage barrier costs (Sec. III-B "Stage"): the probe of mt_probe_barrier_cost for 1..8 streams and
+           even-split staged schedules of a workload under the event, counter and host-side barriers
+  layers   per-operator table of one tenant: GEMM shape, kernel, time alone on the GPU, fraction of its own roofline bound
+  rocprof  turns the CSV files of `rocprofv3 --kernel-trace --stats` / `--pmc ...` runs of `bench.py --roofline-only`
+           into the per-family summary kept under profiles/
+
     python -m paper_2111_14255_amd.report search --config cfg2
     python -m paper_2111_14255_amd.report issue --config cfg2
     python -m paper_2111_14255_amd.report mixes
     python -m paper_2111_14255_amd.report fusion --config cfg2
+    python -m paper_2111_14255_amd.report barriers --config cfg3
+    python -m paper_2111_14255_amd.report layers --config cfg5 --tenant 0
+    python -m paper_2111_14255_amd.report rocprof --config cfg5 --dir gpurun_out/prof_cfg5
 """
 import argparse
 import sys
@@ -255,17 +264,257 @@ def report_fusion(args):
     ctx.close()
 
 
+def _even(lens, n_stages):
+    P = n_stages - 1
+    return [[-(-n * (j + 1) // (P + 1)) for j in range(P)] for n in lens]
+
+
+def report_barriers(args):
+    import ctypes as C
+    from synth import configs
+    from . import binding as B
+    cfg = configs.ALL[args.config]
+    ctx, specs, inputs, outputs = _setup(cfg)
+    print("# Cost of a stage barrier on MI355X (Sec. III-B \"Stage\")")
+    print()
+    print("Command: `python -m paper_2111_14255_amd.report barriers --config %s`" % cfg.name)
+    print()
+    print("## Probe: rounds of one short kernel per stream, a barrier between rounds (`mt_probe_barrier_cost`, 200 rounds, best of 3)")
+    print()
+    print("us per round; the barrier's cost is the difference to the first column.  events = every stream records an event and "
+          "waits for the events of all others (n + n(n-1) runtime calls); memory ops = every stream writes a word of its own and "
+          "waits for the words of all others; counter = a one-thread kernel per stream adds 1 to one word, every stream waits once "
+          "for the total (2n calls); via main = events through the main stream (3n + 1 calls).  One issuing host thread: with "
+          "three streams and more a round is bound by the runtime calls themselves.")
+    print()
+    print("| streams | no barrier | events | memory ops | counter | via main |")
+    print("|---|---|---|---|---|---|")
+    for n in (1, 2, 3, 4, 5, 8):
+        row = []
+        for kind in range(5):
+            best = 1e30
+            for _ in range(3):
+                v = C.c_float()
+                B.check(ctx.lib.mt_probe_barrier_cost(ctx.h, n, kind, 200, C.byref(v)))
+                best = min(best, v.value)
+            row.append(best)
+        print("| %d | %.1f | %.1f | %.1f | %.1f | %.1f |" % (n, *row))
+        sys.stdout.flush()
+    lens = ctx.lens()
+    print()
+    print("## %s (%s, batch %d, %s): even split into 1 / 2 / 4 / 8 stages, median makespan of 21 runs, ms" % (
+        cfg.name, " + ".join(cfg.tenants), cfg.batch, cfg.dtype))
+    print()
+    print("main thread = the paper's single issuing thread (Sec. III-D); threads = one issuing host thread per stream; host = the "
+          "issuing thread of a stream waits on the host for the events of the stage before.  Outputs are bit-identical in every cell.")
+    print()
+    PI = B.MT_SCHED_PARALLEL_ISSUE
+    forms = (("events, main thread", 0), ("counter, main thread", B.MT_SCHED_COUNTER_BARRIER), ("events, threads", PI),
+             ("counter, threads", PI | B.MT_SCHED_COUNTER_BARRIER), ("host, threads", PI | B.MT_SCHED_HOST_BARRIER))
+    print("| stages | " + " | ".join(f[0] for f in forms) + " |")
+    print("|---|" + "---|" * len(forms))
+    for ns in (1, 2, 4, 8):
+        row = []
+        for _, flags in forms:
+            sc = ctx.schedule(_even(lens, ns), ns, flags=flags)
+            row.append(_time(ctx, sc, inputs, outputs, steps=21, warmup=3)["median"])
+            sc.close()
+        print("| %d | " % ns + " | ".join("%.4f" % v for v in row) + " |")
+        sys.stdout.flush()
+    ctx.close()
+
+
+def report_layers(args):
+    from synth import configs
+    from . import binding as B
+    cfg = configs.ALL[args.config]
+    ctx, specs, inputs, outputs = _setup(cfg)
+    t = args.tenant
+    m = specs[t]
+    best = None
+    for _ in range(3):
+        ms = ctx.profile_ops(t, inputs[t], outputs[t], 20)
+        best = ms if best is None else [min(a, b) for a, b in zip(best, ms)]
+    print("# Per-operator pass of %s (tenant %d of %s, batch %d, %s) alone on MI355X" % (m.name, t, cfg.name, m.batch, m.dtype))
+    print()
+    print("Command: `python -m paper_2111_14255_amd.report layers --config %s --tenant %d`" % (cfg.name, t))
+    print()
+    print("Every operator 1 + 20 times back to back on one stream between two events (`mt_profile_ops`), best of 3 passes.  M x N x K = "
+          "pixels x output channels x reduction length; bound = max(flops / 2.5 PFLOP/s, bytes / 8 TB/s) of the operator's algorithmic "
+          "work; an empty dependent launch takes about 3.5 us on this machine, which a single short kernel cannot go below.")
+    print()
+    print("| op | kind | M | N | K | window | kernel | split | workgroups | us | bound us | frac | TFLOP/s | GB/s |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+    tot = totb = 0.0
+    fam = {}
+    for i, (op, d) in enumerate(zip(m.ops, best)):
+        info = ctx.op_info(t, i)
+        M = m.batch * info.out_h * info.out_w
+        K = op.r * op.s * (info.in_c // max(1, op.groups)) if op.kind in ("conv", "fc") else op.r * op.s
+        us = d * 1e3
+        bound = max(info.flops / 2.5e15, info.bytes / 8e12) * 1e6
+        kn = B.load().mt_kernel_name(info.kernel_id).decode()
+        print("| %d | %s | %d | %d | %d | %dx%d s%d | %s | %d | %d | %.2f | %.2f | %.3f | %.1f | %.0f |" % (
+            i, op.kind, M, info.out_c, K, op.r, op.s, op.stride_h, kn, info.split_k, info.grid_blocks, us, bound, bound / us,
+            info.flops / (d * 1e-3) / 1e12, info.bytes / (d * 1e-3) / 1e9))
+        tot += us
+        totb += bound
+        f = fam.setdefault(kn, [0, 0.0, 0.0])
+        f[0] += 1
+        f[1] += us
+        f[2] += bound
+    print()
+    print("Sum of the operator times %.1f us, sum of their bounds %.1f us (%.3f)." % (tot, totb, totb / tot))
+    print()
+    print("| family | launches | us | bound us | frac |")
+    print("|---|---|---|---|---|")
+    for k, v in sorted(fam.items(), key=lambda kv: -kv[1][1]):
+        print("| %s | %d | %.1f | %.1f | %.3f |" % (k, v[0], v[1], v[2], v[2] / v[1]))
+    ctx.close()
+
+
+def _family_of(kernel_name):
+    import re
+    m = re.search(r"igemm_kernel<[^,]+, (\d+), (\d+)", kernel_name) or re.match(r"_ZN2mt12igemm_kernelI(?:DF16_|NS_4bf16E)Li(\d+)ELi(\d+)E", kernel_name)
+    if m:
+        return "igemm_%sx%s" % (m.group(1), m.group(2))
+    for key, fam in (("pw_direct_kernel", "igemm_pointwise"), ("gemv_kernel", "gemv"), ("dwconv", "dwconv"), ("gap_kernel", "global_avgpool"),
+                     ("pool", "pool"), ("conv_direct", "conv_direct"), ("lrn_kernel", "lrn"), ("add_kernel", "add")):
+        if key in kernel_name:
+            return fam
+    return None
+
+
+def report_rocprof(args):
+    """Reads <dir>/live.json (stdout of `bench.py --roofline-only`), <dir>/trace/*kernel_stats.csv and the
+    *counter_collection.csv files of the --pmc runs under <dir>/pmc_*/ ; prints the summary and, with --traffic-out,
+    writes the per-family HBM bytes that bench.py reports as roofline.traffic."""
+    import collections
+    import csv
+    import glob
+    import json
+    import os
+    d = args.dir
+    live = json.load(open(os.path.join(d, "live.json")))["families"]
+    print("# Kernel time, HBM traffic and unit utilisation of the per-operator pass, workload %s (MI355X)" % args.config)
+    print()
+    print("Commands (run from /tmp on the MI355X box, repository root = $R; every --pmc set is a run of its own):")
+    print()
+    print("    python3 $R/bench.py --config %s --roofline-only > live.json" % args.config)
+    print("    rocprofv3 --kernel-trace --stats -d trace -o roof --output-format csv -- python3 $R/bench.py --config %s --roofline-only" % args.config)
+    for name in sorted(os.path.basename(x) for x in glob.glob(os.path.join(d, "pmc_*"))):
+        cs = set()
+        for f in glob.glob(os.path.join(d, name, "**", "*counter_collection.csv"), recursive=True):
+            for r in csv.DictReader(open(f)):
+                cs.add(r["Counter_Name"])
+        print("    rocprofv3 --pmc %s -d %s -o p --output-format csv -- python3 $R/bench.py --config %s --roofline-only" % (" ".join(sorted(cs)), name, args.config))
+    print("    python -m paper_2111_14255_amd.report rocprof --config %s --dir <the directory holding the above>" % args.config)
+    print()
+    print("`bench.py --roofline-only` launches every operator of every tenant 11 times back to back on one stream (1 warm-up + 10 timed), "
+          "after a 64 MiB elementwise copy that calibrates the byte counters.")
+    print()
+    stats = []
+    for f in glob.glob(os.path.join(d, "trace", "**", "*kernel_stats.csv"), recursive=True):
+        stats = list(csv.DictReader(open(f)))
+    fam = collections.defaultdict(lambda: [0, 0.0])
+    print("## rocprofv3 --kernel-trace --stats (top kernels)")
+    print()
+    print("| kernel | calls | total us | avg us | % |")
+    print("|---|---|---|---|---|")
+    for r in stats[:12]:
+        print("| %s | %s | %.1f | %.2f | %s |" % (r["Name"][:90], r["Calls"], float(r["TotalDurationNs"]) / 1e3, float(r["AverageNs"]) / 1e3, r["Percentage"]))
+    for r in stats:
+        k = _family_of(r["Name"])
+        if k:
+            fam[k][0] += int(r["Calls"])
+            fam[k][1] += float(r["TotalDurationNs"]) / 1e3
+    print()
+    print("| family | launches per pass | rocprofv3 avg us (all 11 launches of every operator) | bench.py HIP events avg us (the 10 timed ones) |")
+    print("|---|---|---|---|")
+    for k, v in live.items():
+        kk = "pool" if k in ("maxpool", "avgpool") else k
+        if kk in fam and fam[kk][0]:
+            print("| %s | %d | %.2f | %.2f |" % (k, v["launches"], fam[kk][1] / fam[kk][0], v["ms"] * 1e3 / v["launches"]))
+    # counters: mean per dispatch and family
+    per = collections.defaultdict(lambda: collections.defaultdict(list))
+    cal = collections.defaultdict(list)
+    for f in glob.glob(os.path.join(d, "pmc_*", "**", "*counter_collection.csv"), recursive=True):
+        for r in csv.DictReader(open(f)):
+            k = _family_of(r["Kernel_Name"])
+            if k:
+                per[k][r["Counter_Name"]].append(float(r["Counter_Value"]))
+            if "elementwise" in r["Kernel_Name"] and int(r["Grid_Size"]) >= 32 * 1024 * 1024 // 8:
+                cal[r["Counter_Name"]].append(float(r["Counter_Value"]))
+    mean = lambda v: sum(v) / len(v) if v else 0.0
+    traffic = {}
+    if cal.get("FETCH_SIZE") and cal.get("WRITE_SIZE"):
+        fs, ws = 65536.0 / max(cal["FETCH_SIZE"]), 65536.0 / max(cal["WRITE_SIZE"])
+        print()
+        print("## HBM traffic (FETCH_SIZE / WRITE_SIZE, KiB per dispatch, mean over the dispatches of a family)")
+        print()
+        print("Calibration: the 64 MiB copy (65536 KiB read, 65536 KiB written) reads FETCH_SIZE = %.1f and WRITE_SIZE = %.1f, so FETCH_SIZE "
+              "is scaled by %.3f and WRITE_SIZE by %.3f." % (max(cal["FETCH_SIZE"]), max(cal["WRITE_SIZE"]), fs, ws))
+        print()
+        print("| family | dispatches | FETCH_SIZE | WRITE_SIZE | HBM bytes per launch (scaled) | algorithmic bytes per launch | ratio |")
+        print("|---|---|---|---|---|---|---|")
+        for k, v in live.items():
+            kk = "pool" if k in ("maxpool", "avgpool") else k
+            if "FETCH_SIZE" not in per[kk]:
+                continue
+            fm, wm = mean(per[kk]["FETCH_SIZE"]), mean(per[kk]["WRITE_SIZE"])
+            hb = (fm * fs + wm * ws) * 1024
+            alg = v["bytes"] / v["launches"]
+            traffic[k] = {"hbm_bytes_per_launch": int(hb), "fetch_kib": round(fm, 1), "write_kib": round(wm, 1),
+                          "fetch_scale": round(fs, 3), "write_scale": round(ws, 3)}
+            print("| %s | %d | %.1f | %.1f | %d | %d | %.2f |" % (k, len(per[kk]["FETCH_SIZE"]), fm, wm, hb, alg, hb / alg))
+    if any("SQ_VALU_MFMA_BUSY_CYCLES" in c for c in per.values()):
+        print()
+        print("## Unit utilisation from counters (sums over the dispatches of a family)")
+        print()
+        print("MFMA busy = SQ_VALU_MFMA_BUSY_CYCLES / (4 SIMDs x SQ_BUSY_CU_CYCLES): the share of the busy compute units' matrix-core "
+              "cycles that executed a matrix instruction.  MFMA vs peak = the same cycles over (1024 SIMDs x GRBM_GUI_ACTIVE / 8 XCDs): "
+              "against the whole chip for the whole launch.  LDS busy = SQ_LDS_IDX_ACTIVE / SQ_BUSY_CU_CYCLES, address unit busy = "
+              "TA_TA_BUSY_sum / SQ_BUSY_CU_CYCLES, wait = SQ_WAIT_INST_ANY / SQ_WAVE_CYCLES (share of wave time spent waiting for "
+              "any instruction's operands), L2 hit = TCC_HIT_sum / (TCC_HIT_sum + TCC_MISS_sum).  The time-derived figure beside them "
+              "is algorithmic flops / duration / 2.5 PFLOP/s from bench.py's HIP events.  Counter runs slow the kernels down, so "
+              "ratios of cycle counts are meaningful, absolute cycle counts are not.")
+        print()
+        print("| family | MFMA busy on busy units | MFMA vs chip peak (counters) | MFMA vs peak (time-derived) | LDS busy | address unit busy | wave wait share | L2 hit |")
+        print("|---|---|---|---|---|---|---|---|")
+        for k, v in live.items():
+            kk = "pool" if k in ("maxpool", "avgpool") else k
+            c = per[kk]
+            if not c:
+                continue
+            sm = lambda n: sum(c.get(n, []))
+            cu = sm("SQ_BUSY_CU_CYCLES")
+            gui = sm("GRBM_GUI_ACTIVE")
+            hit, miss = sm("TCC_HIT_sum"), sm("TCC_MISS_sum")
+            td = v["flops"] / (v["ms"] * 1e-3) / 2.5e15 if v["ms"] > 0 else 0.0
+            fmt = lambda a, b: "%.3f" % (a / b) if b else "-"
+            print("| %s | %s | %s | %.4f | %s | %s | %s | %s |" % (
+                k, fmt(sm("SQ_VALU_MFMA_BUSY_CYCLES"), 4 * cu), fmt(sm("SQ_VALU_MFMA_BUSY_CYCLES"), 1024 * gui / 8), td,
+                fmt(sm("SQ_LDS_IDX_ACTIVE"), cu), fmt(sm("TA_TA_BUSY_sum"), cu), fmt(sm("SQ_WAIT_INST_ANY"), sm("SQ_WAVE_CYCLES")),
+                fmt(hit, hit + miss)))
+    if args.traffic_out and traffic:
+        json.dump(traffic, open(args.traffic_out, "w"), indent=1)
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=["search", "issue", "mixes", "fusion"])
+    ap.add_argument("what", choices=["search", "issue", "mixes", "fusion", "barriers", "layers", "rocprof"])
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--rounds", type=int, default=3)
     ap.add_argument("--candidates", type=int, default=8)
     ap.add_argument("--runs", type=int, default=7)
     ap.add_argument("--seeds", type=int, default=5)
     ap.add_argument("--only", default="", help="mixes: comma-separated subset of the mix names")
+    ap.add_argument("--tenant", type=int, default=0, help="layers: which tenant of the workload")
+    ap.add_argument("--dir", default="", help="rocprof: directory with live.json, trace/ and pmc_*/")
+    ap.add_argument("--traffic-out", default="", help="rocprof: write the per-family HBM bytes here (profiles/traffic_<workload>.json)")
     args = ap.parse_args()
-    {"search": report_search, "issue": report_issue, "mixes": report_mixes, "fusion": report_fusion}[args.what](args)
+    {"search": report_search, "issue": report_issue, "mixes": report_mixes, "fusion": report_fusion, "barriers": report_barriers,
+     "layers": report_layers, "rocprof": report_rocprof}[args.what](args)
 
 
 if __name__ == "__main__":

@@ -86,6 +86,12 @@ def test_cfg2_r18_vgg16_mbv2_fp16():
                                        flags=B.MT_SCHED_PARALLEL_ISSUE | B.MT_SCHED_HOST_BARRIER | B.MT_SCHED_FUSE_EXPAND, label="parallel-issue"),
         lambda ctx, lens: ctx.schedule([[0, 0], [lens[1], lens[1]], [0, lens[2]]], 3, cu_share=[64, 128, 64],
                                        flags=B.MT_SCHED_PARALLEL_ISSUE | B.MT_SCHED_HOST_BARRIER, label="parallel-issue"),
+        # the stage barrier taken with a counter word and one wait per stream instead of events
+        lambda ctx, lens: ctx.schedule(even_split(lens, 4), 4, flags=B.MT_SCHED_COUNTER_BARRIER, label="counter-barrier"),
+        lambda ctx, lens: ctx.schedule([[0, 0], [lens[1], lens[1]], [0, lens[2]]], 3, concurrency=[2, 1, 3],
+                                       flags=B.MT_SCHED_COUNTER_BARRIER | B.MT_SCHED_FUSE_EXPAND, label="counter-barrier-empty-slices"),
+        lambda ctx, lens: ctx.schedule(even_split(lens, 5), 5, cu_share=[64, 128, 64],
+                                       flags=B.MT_SCHED_COUNTER_BARRIER | B.MT_SCHED_PARALLEL_ISSUE, label="parallel-issue"),
     ])
     mix.close()
 
@@ -135,6 +141,10 @@ def test_paper_mix_r18_r34_fp16_with_share_search_and_first_op_timing():
             ctx.schedule([[], []], 1, flags=B.MT_SCHED_TIME_TENANTS | B.MT_SCHED_GRAPH)
         with pytest.raises(B.MtError):
             ctx.schedule([[], []], 1, flags=B.MT_SCHED_HOST_BARRIER)              # needs one issuing thread per stream
+        with pytest.raises(B.MtError):
+            ctx.schedule([[], []], 1, flags=B.MT_SCHED_COUNTER_BARRIER | B.MT_SCHED_GRAPH)
+        with pytest.raises(B.MtError):
+            ctx.schedule([[], []], 1, flags=B.MT_SCHED_COUNTER_BARRIER | B.MT_SCHED_PARALLEL_ISSUE | B.MT_SCHED_HOST_BARRIER)
         ref = mix.oracle()
         outs = [ctx.make_output(t) for t in range(2)]
         rho, cost, rec, shares = ctx.search(mix.inputs, outs, 3, rounds=1, candidates=3, runs=3, warmup=1, seed=9,

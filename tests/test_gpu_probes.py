@@ -56,3 +56,23 @@ def test_cu_mask_probe_and_dispatch_latency():
         assert all(1.0 < v < 200.0 for v in us)
     finally:
         ctx.close()
+
+
+def test_barrier_cost_probe_every_kind():
+    ctx = api.Context(0)
+    try:
+        for n in (1, 3):
+            base = None
+            for kind in range(5):
+                print("barrier probe, %d streams, kind %d" % (n, kind), flush=True)
+                v = C.c_float()
+                B.check(ctx.lib.mt_probe_barrier_cost(ctx.h, n, kind, 20, C.byref(v)))
+                assert 1.0 < v.value < 5000.0
+                if kind == 0:
+                    base = v.value
+            assert base is not None
+        for bad in ((0, 0, 10), (2, 5, 10), (2, 1, 0), (17, 1, 10)):
+            with pytest.raises(B.MtError):
+                B.check(ctx.lib.mt_probe_barrier_cost(ctx.h, bad[0], bad[1], bad[2], C.byref(C.c_float())))
+    finally:
+        ctx.close()
