@@ -165,6 +165,115 @@ __global__ void __launch_bounds__(256) dwconv_fixed_kernel(OpArgs a) {
     store_pack<T, V>((T *)a.y + m * a.y_ct + a.y_coff + c0, acc);
 }
 
+// 3x3 depthwise convolution with padding 1 on a large map: a thread owns one (column, channel vector) of a band of
+// `rows` output rows and keeps the three input rows of the window in registers, so that an output row costs one new
+// input row (stride 1) or two (stride 2) instead of three.  Along a row the neighbouring columns are the own columns of
+// the threads CV lanes to either side (channel vector is the fastest thread index), so at stride 1 a thread loads only
+// its own column of a new row and takes the left and right taps from those lanes with wavefront shuffles; lanes whose
+// neighbour lies in another wavefront load it themselves.  At stride 2 the left tap is the neighbour's right column.
+// Taps are multiplied in the order (r, s) of the other depthwise kernels and every value has the bits a load would give,
+// so the result is bit-identical to theirs.  Lanes beyond the last thread mirror it (they take part in the shuffles)
+// and store nothing.
+typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+
+template <typename T, int ST>
+__global__ void __launch_bounds__(256) dwconv3_rows_kernel(OpArgs a, int rows, int bands) {
+    static_assert(sizeof(T) == 2, "16-byte vectors of 8 channels");
+    constexpr int V = 8;
+    set_wave_priority(a.prio);
+    const int CV = a.C / V;
+    const uint32_t total = (uint32_t)a.N * bands * a.Q * CV;
+    const uint32_t gid0 = blockIdx.x * blockDim.x + threadIdx.x;
+    const bool live = gid0 < total;
+    const ElemIdx e = split_index(live ? gid0 : total - 1, CV, a.Q, bands);
+    const int cv = e.cv, q = e.q, band = e.p, n = e.n;
+    const int lane = threadIdx.x & 63;
+    const int c0 = cv * V;
+    const T *x = (const T *)a.x + (int64_t)n * a.H * a.W * a.C + c0;
+    const T *w = (const T *)a.w + c0;
+    u32x4v wv[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) wv[t] = *reinterpret_cast<const u32x4v *>(w + (int64_t)t * a.C);
+    float bv[V];
+#pragma unroll
+    for (int i = 0; i < V; i += 4) {
+        const float4 b4 = *reinterpret_cast<const float4 *>(a.bias + c0 + i);
+        bv[i] = b4.x; bv[i + 1] = b4.y; bv[i + 2] = b4.z; bv[i + 3] = b4.w;
+    }
+    const bool l_lane = lane >= CV, r_lane = lane + CV < 64;      // the neighbouring column's thread is in this wavefront
+    const int iw1 = q * ST - 1 + 1;                               // the centre tap's column: always inside the map
+    const bool ok_s[3] = {q * ST - 1 >= 0, true, q * ST + 1 < a.W};
+    auto shuffle = [&](u32x4v v, int src) {
+        u32x4v o;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) o[k] = (uint32_t)__shfl((int)v[k], src, 64);
+        return o;
+    };
+    auto at = [&](const T *row, int iw) { return *reinterpret_cast<const u32x4v *>(row + (int64_t)iw * a.C); };
+    // one input row: the three taps of this thread's window (values of taps in the padding are never used)
+    auto load_row = [&](int ih, u32x4v (&taps)[3], bool &ok) {
+        ok = (unsigned)ih < (unsigned)a.H;
+        const T *row = x + (int64_t)min(max(ih, 0), a.H - 1) * a.W * a.C;
+        const u32x4v c = at(row, iw1);
+        taps[1] = c;
+        if constexpr (ST == 1) {
+            u32x4v l = shuffle(c, lane - CV), r = shuffle(c, lane + CV);
+            if (!l_lane && ok_s[0]) l = at(row, iw1 - 1);
+            if (!r_lane && ok_s[2]) r = at(row, iw1 + 1);
+            taps[0] = l;
+            taps[2] = r;
+        } else {
+            const u32x4v r = at(row, ok_s[2] ? iw1 + 1 : iw1);
+            u32x4v l = shuffle(r, lane - CV);                     // the left neighbour's right column is this thread's left one
+            if (!l_lane && ok_s[0]) l = at(row, iw1 - 1);
+            taps[0] = l;
+            taps[2] = r;
+        }
+    };
+    const int p0 = band * rows, p1 = min(a.P, p0 + rows);
+    u32x4v win[3][3];
+    bool rok[3];
+    load_row(p0 * ST - 1, win[0], rok[0]);
+    load_row(p0 * ST, win[1], rok[1]);
+    for (int p = p0; p < p1; ++p) {                               // uniform trip count within a wavefront's band... per thread the same p range
+        load_row(p * ST + 1, win[2], rok[2]);
+        float acc[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] = 0.f;
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+#pragma unroll
+            for (int sx = 0; sx < 3; ++sx) {
+                const Pack<T, V> xv = __builtin_bit_cast(Pack<T, V>, win[r][sx]);
+                const Pack<T, V> wt = __builtin_bit_cast(Pack<T, V>, wv[r * 3 + sx]);
+                const bool ok = rok[r] & ok_s[sx];
+#pragma unroll
+                for (int i = 0; i < V; ++i) acc[i] = ok ? fmaf(to_f32(xv.e[i]), to_f32(wt.e[i]), acc[i]) : acc[i];
+            }
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] = apply_act(acc[i] + bv[i], a.act);
+        if (live) store_pack<T, V>((T *)a.y + ((int64_t)(n * a.P + p) * a.Q + q) * a.y_ct + a.y_coff + c0, acc);
+        if constexpr (ST == 1) {
+#pragma unroll
+            for (int sx = 0; sx < 3; ++sx) { win[0][sx] = win[1][sx]; win[1][sx] = win[2][sx]; }
+            rok[0] = rok[1]; rok[1] = rok[2];
+        } else {
+#pragma unroll
+            for (int sx = 0; sx < 3; ++sx) win[0][sx] = win[2][sx];
+            rok[0] = rok[2];
+            if (p + 1 < p1) load_row((p + 1) * ST, win[1], rok[1]);
+        }
+    }
+}
+
+// Output rows per thread of the banded 3x3 depthwise kernel: 1 (the one-pixel kernel) unless the map is large enough
+// to leave at least 65536 threads with 2 or 4 rows each.  A pure function of the operator's shape.
+static int dwconv_band_rows(const OpArgs &a) {
+    if (a.dtype == MT_F32 || a.R != 3 || a.S != 3 || a.ph != 1 || a.pw != 1 || a.sh != a.sw || a.sh < 1 || a.sh > 2 || a.vec != 8) return 1;
+    const int64_t th = (int64_t)a.N * a.P * a.Q * (a.C / 8);
+    return th >= 4 * 65536 ? 4 : th >= 2 * 65536 ? 2 : 1;
+}
+
 template <typename T, int V, bool IS_MAX, int KS>
 __global__ void __launch_bounds__(256) pool_fixed_kernel(OpArgs a) {
     set_wave_priority(a.prio);
@@ -406,6 +515,16 @@ static int launch_typed(const OpArgs &a, hipStream_t st) {
         case K_DWCONV: {
             if (a.vec == VMAX) {
                 const int64_t th = (int64_t)a.N * a.P * a.Q * (a.C / VMAX);
+                const int rows = dwconv_band_rows(a);
+                if constexpr (sizeof(T) == 2) {
+                    if (rows > 1) {
+                        const int bands = (a.P + rows - 1) / rows;
+                        const int64_t tb = (int64_t)a.N * bands * a.Q * (a.C / VMAX);
+                        if (a.sh == 1) hipLaunchKernelGGL((dwconv3_rows_kernel<T, 1>), blocks(tb), block, 0, st, a, rows, bands);
+                        else hipLaunchKernelGGL((dwconv3_rows_kernel<T, 2>), blocks(tb), block, 0, st, a, rows, bands);
+                        break;
+                    }
+                }
                 if (a.R == 3 && a.S == 3)
                     hipLaunchKernelGGL((dwconv_fixed_kernel<T, VMAX, 3>), blocks(th), block, 0, st, a);
                 else

@@ -162,6 +162,12 @@ CHANNELWISE = [
     ("dw_stride2", 1, 15, 15, 96, lambda g: g.dwconv(0, 3, 2, 1, act="relu6", bn=True)),
     ("dw_c96_stride1", 1, 14, 14, 96, lambda g: g.dwconv(0, 3, 1, 1, act="relu6", bn=True)),
     ("dw_c960", 1, 7, 7, 960, lambda g: g.dwconv(0, 3, 1, 1, act="relu6", bn=True)),
+    # large maps: the banded kernel (several output rows per thread, neighbouring columns by wavefront shuffles)
+    ("dw_banded_c32_two_rows", 2, 64, 128, 32, lambda g: g.dwconv(0, 3, 1, 1, act="relu6", bn=True)),          # 4 vectors per pixel
+    ("dw_banded_c96_four_rows_ragged", 4, 61, 59, 96, lambda g: g.dwconv(0, 3, 1, 1, act="relu", bn=True)),     # 12 per pixel, bands of 4 over 61 rows
+    ("dw_banded_c144_stride2", 8, 57, 57, 144, lambda g: g.dwconv(0, 3, 2, 1, act="relu6", bn=True)),           # 18 per pixel, odd width, stride 2
+    ("dw_banded_c576_no_neighbour_in_wave", 4, 30, 31, 576, lambda g: g.dwconv(0, 3, 1, 1, act="none", bn=True)),   # 72 per pixel: every neighbour is loaded
+    ("dw_banded_c64_stride2_even", 16, 32, 32, 64, lambda g: g.dwconv(0, 3, 2, 1, act="relu", bn=True)),
     ("dw_scalar_c20", 1, 9, 9, 20, lambda g: g.dwconv(0, 3, 1, 1, act="relu", bn=False)),
     ("dw_5x5", 1, 11, 11, 16, lambda g: g.dwconv(0, 5, 1, 2, act="relu", bn=False)),
     ("dw_7x7_generic", 1, 9, 10, 24, lambda g: g.dwconv(0, 7, 1, 3, act="relu", bn=True)),
