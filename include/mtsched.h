@@ -269,18 +269,16 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
 #define MT_SCHED_SHARE_PER_STAGE 8
 /* MT_SCHED_FUSE_DEPTHWISE: a 3x3 depthwise convolution whose consumer is a 1x1 convolution issued in the same stage
  * (on the 64x16 tile, unsplit) runs inside that convolution's launch: same arithmetic in the same order, so the
- * outputs, the intermediate tensor included, have the same bits as two launches.  Off by default: measured on
- * MobileNetV2 at batch 1 the fused launch takes as long as the two it replaces (10.3 us against 4.0 + 4.9 us plus
- * the gap between them), because one workgroup then computes the depthwise output of its 16 pixels alone. */
+ * outputs, the intermediate tensor included, have the same bits as two launches.  Opt-in: one workgroup then computes
+ * the depthwise output of its 16 pixels alone, which on small maps takes as long as the two launches it replaces. */
 #define MT_SCHED_FUSE_DEPTHWISE 16
 /* MT_SCHED_FUSE_EXPAND: a 1x1 convolution (stride 1, no residual, fp16 / bf16, output channels a multiple of 8) whose
  * output only the next operator reads, a 3x3 depthwise convolution with padding 1 and stride 1 or 2 issued in the same
  * stage, runs with it in one launch: the first two operators of the chain 1x1 -> depthwise -> 1x1 of an inverted
  * residual block.  Needs three rows of the map to fit one workgroup: width * 3 <= 512 pixels with at most 64 input
  * channels, <= 256 with at most 128, <= 64 with at most 256.  Same arithmetic in the same order as the two launches,
- * so every output, both intermediate tensors included, keeps its bits.  Measured on MobileNetV2 at batch 1 alone on
- * the GPU: 15 pairs fused, 0.28 -> 0.25 ms per pass.  With MT_SCHED_FUSE_DEPTHWISE also set, a depthwise operator
- * joins its producer when it can and its consumer otherwise. */
+ * so every output, both intermediate tensors included, keeps its bits.  With MT_SCHED_FUSE_DEPTHWISE also set, a
+ * depthwise operator joins its producer when it can and its consumer otherwise. */
 #define MT_SCHED_FUSE_EXPAND 64
 /* MT_SCHED_FUSE_POOL: a convolution on the matrix cores (fp16 / bf16, no residual, output channels a multiple of 8, even
  * output height and width) whose output only the next operator reads, a 2x2 max pooling with stride 2 issued in the

@@ -21,7 +21,13 @@ def _runtime_environment():
     stage barriers) poll the signal instead of sleeping until the driver's interrupt wakes the thread.  Measured on
     MI355X: the same three-tenant pass 0.294 -> 0.286 ms per step on the host's clock (makespan 0.279 -> 0.272 ms),
     even two- to seven-stage schedules 4 to 8 % shorter.  The price is a busy host thread per waiting call; a value
-    already set in the environment is kept."""
+    already set in the environment is kept.
+
+    MTSCHED_KEEP_ENV=1 switches all of this off: the process environment is left as it is (for hosts that set these
+    variables themselves, or that must not have a polling thread).  None of the settings has any effect when the HIP
+    runtime was initialised before this package is imported."""
+    if _os.environ.get("MTSCHED_KEEP_ENV", "") not in ("", "0"):
+        return
     want = _os.environ.get("MTSCHED_HW_QUEUES")
     try:
         have = int(_os.environ.get("GPU_MAX_HW_QUEUES", "0") or 0)

@@ -23,9 +23,9 @@ def _hipcc():
     raise RuntimeError("hipcc not found")
 
 
-def _compile(src, extra):
-    out = os.path.join(OBJ, os.path.basename(src) + ".o")
-    cmd = [_hipcc(), "-c", os.path.join(CSRC, src), "-o", out] + COMMON + extra + os.environ.get("MT_EXTRA_DEFS", "").split()
+def _compile(src, extra, obj_dir=None):
+    out = os.path.join(obj_dir or OBJ, os.path.basename(src) + ".o")
+    cmd = [_hipcc(), "-c", os.path.join(CSRC, src), "-o", out] + COMMON + extra
     r = subprocess.run(cmd, capture_output=True, text=True)
     noise = "is not a recognized feature for this target"
     err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
@@ -36,16 +36,30 @@ def _compile(src, extra):
     return out
 
 
-def build(verbose=False, lib=None):
+# host-side sanitizers (address + undefined behaviour) for the two host sources; device code is never instrumented
+SANITIZE_HOST = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+
+
+def build(verbose=False, lib=None, sanitize=False):
+    """sanitize=True builds the host objects with AddressSanitizer and UBSan into `lib` (give another path than the
+    product library's): the CPU-only tests can then run against it with the sanitizer runtime preloaded, e.g.
+    MTSCHED_LIB=<lib> LD_PRELOAD="$LD_PRELOAD:$(clang -print-file-name=libclang_rt.asan-x86_64.so)" pytest -m "not gpu"."""
     global LIB
-    if lib:
+    out = lib or LIB
+    if not sanitize and lib:
         LIB = lib
-    os.makedirs(OBJ, exist_ok=True)
-    jobs = [(s, DEVICE_FLAGS) for s in DEVICE_SOURCES] + [(s, ["-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include"]) for s in HOST_SOURCES]
+    obj_dir = OBJ + ("_asan" if sanitize else "")
+    os.makedirs(obj_dir, exist_ok=True)
+    host_extra = ["-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include"] + (SANITIZE_HOST if sanitize else [])
+    jobs = [(s, DEVICE_FLAGS, obj_dir) for s in DEVICE_SOURCES] + [(s, host_extra, obj_dir) for s in HOST_SOURCES]
     with ThreadPoolExecutor(max_workers=4) as ex:
         objs = list(ex.map(lambda j: _compile(*j), jobs))
-    cmd = [_hipcc(), "-shared", "-fPIC", "-o", LIB] + objs + ["--offload-arch=gfx950"]
+    cmd = [_hipcc(), "-shared", "-fPIC", "-o", out] + objs + ["--offload-arch=gfx950"]
+    if sanitize:
+        cmd += ["-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize", "-shared-libsan"]
     subprocess.check_call(cmd)
+    if sanitize:
+        return out
     if verbose:
         print("built", LIB)
     return LIB
@@ -56,4 +70,7 @@ def lib_path():
 
 
 if __name__ == "__main__":
-    build(verbose=True)
+    if "--sanitize" in sys.argv:
+        print("built", build(lib=os.path.join(HERE, "libmtsched_asan.so"), sanitize=True))
+    else:
+        build(verbose=True)

@@ -856,23 +856,17 @@ static void launch_cfg(const OpArgs &a, hipStream_t st) {
         hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, 2, A_SCALAR>), grid, dim3(256), 0, st, a);
 }
 
-#ifndef MT_STAGES_128
-#define MT_STAGES_128 2
-#endif
 template <typename T>
 static int launch_igemm_typed(const OpArgs &a, hipStream_t st) {
     switch (a.kernel_id) {
-        case K_IGEMM_128x128: launch_cfg<T, 128, 128, 2, 2, 32, MT_STAGES_128>(a, st); break;
+        case K_IGEMM_128x128: launch_cfg<T, 128, 128, 2, 2, 32, 2>(a, st); break;
         case K_IGEMM_128x64:
             if (a.wk == 2) launch_cfg<T, 128, 64, 2, 2, 32, 2, 2>(a, st);
             else launch_cfg<T, 128, 64, 2, 2, 32, 2>(a, st);
             break;
-#ifndef MT_STAGES_64
-#define MT_STAGES_64 4
-#endif
         case K_IGEMM_64x64:
-            if (a.wk == 2) launch_cfg<T, 64, 64, 2, 2, 32, MT_STAGES_64, 2>(a, st);
-            else launch_cfg<T, 64, 64, 2, 2, 32, MT_STAGES_64, 1>(a, st);
+            if (a.wk == 2) launch_cfg<T, 64, 64, 2, 2, 32, 4, 2>(a, st);
+            else launch_cfg<T, 64, 64, 2, 2, 32, 4, 1>(a, st);
             break;
         case K_IGEMM_64x16: launch_cfg<T, 64, 16, 4, 1, 16, 4>(a, st); break;
         case K_IGEMM_PW: {

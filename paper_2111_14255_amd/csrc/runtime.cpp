@@ -102,26 +102,12 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
     } else {
         kid = K_IGEMM_64x64; bn = 64; bm = 64;
     }
-#ifdef MT_TUNE_ENV      // tile and split overrides for tuning sweeps; never compiled into the product library
-    if (const char *e = std::getenv("MTSCHED_TUNE_TILE")) {
-        const int t = std::atoi(e);
-        if (t == 1) { kid = K_IGEMM_128x128; bn = 128; bm = 128; }
-        if (t == 8) { kid = K_IGEMM_128x64; bn = 128; bm = 64; }
-        if (t == 2) { kid = K_IGEMM_64x64; bn = 64; bm = 64; }
-        if (t == 3) { kid = K_IGEMM_64x16; bn = 64; bm = 16; }
-    }
-#endif
     p.kernel_id = kid;
     p.n_pad = cdiv(Kc, bn) * bn;
     const int tiles = cdiv(M, bm) * (p.n_pad / bn);
     const int nkt = p.k_pad / IGEMM_BK;
     int target = (kid == K_IGEMM_64x16) ? 2048 : 768;
     int max_split = 8, min_kt = 6;    // a split below 6 reduction tiles costs more in the partial-sum exchange than it saves
-#ifdef MT_TUNE_ENV
-    if (const char *e = std::getenv("MTSCHED_TUNE_TARGET")) target = std::atoi(e);
-    if (const char *e = std::getenv("MTSCHED_TUNE_MAXSPLIT")) max_split = std::atoi(e);
-    if (const char *e = std::getenv("MTSCHED_TUNE_MINKT")) min_kt = std::atoi(e);
-#endif
     int split = 1;
     p.wk = 1;
     // Long reductions on the 128x64 tile are bound by the matrix cores: eight waves per tile (two per SIMD) overlap LDS
@@ -130,9 +116,6 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
     // (17.3 -> 19.3 us) and keep four waves.  The same change on the 128x128 tile loses everywhere.
     if (kid == K_IGEMM_128x64 && p.vec_a != 0 && nkt >= 18) p.wk = 2;
     int wk_tiles = 512;
-#ifdef MT_TUNE_ENV
-    if (const char *e = std::getenv("MTSCHED_TUNE_WK_TILES")) wk_tiles = std::atoi(e);
-#endif
     if (kid == K_IGEMM_64x64 && p.vec_a != 0 && tiles <= wk_tiles) {
         // Few workgroups per compute unit: eight waves per tile (two per SIMD, the MFMA steps of every LDS tile split
         // between two wave groups) and only as many splits as keep about one workgroup per unit.  Measured on MI355X,
@@ -146,13 +129,6 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
         const int per = cdiv(nkt, split);
         split = cdiv(nkt, per);            // no empty split
     }
-#ifdef MT_TUNE_ENV
-    if (const char *e = std::getenv("MTSCHED_TUNE_SPLIT")) {
-        split = std::max(1, std::min(std::atoi(e), nkt));
-        const int per = cdiv(nkt, split);
-        split = cdiv(nkt, per);
-    }
-#endif
     p.split_k = std::max(1, split);
     // Which operand each XCD's L2 keeps to itself: consecutive tiles (one XCD) walk the channel tiles of one pixel
     // tile (0) when the activations are the larger operand, the pixel tiles of one channel tile (1) otherwise.
@@ -391,8 +367,9 @@ struct mt_ctx {
     hipEvent_t ev_prof[2]{};
     hipEvent_t ev_first[MT_MAX_TENANTS]{};   // after the first operator of each tenant (MT_SCHED_TIME_FIRST_OP)
     hipEvent_t ev_last[MT_MAX_TENANTS]{};    // after the last operator of each tenant (MT_SCHED_TIME_TENANTS)
-    // Graph executables of destroyed schedules.  They are released only at mt_destroy, after a device-wide
-    // synchronisation: destroying one right after its last launch has crashed inside the HIP runtime.
+    // Graph executables of destroyed schedules.  They are released in batches after a device-wide synchronisation (at
+    // the end of a search, every 64 candidates inside one, in mt_release_idle_streams and in mt_destroy): destroying one
+    // right after its last launch has crashed inside the HIP runtime.
     std::vector<hipGraphExec_t> retired_graphs;
     // Schedules created from this context and not destroyed yet; mt_destroy detaches them so that a later
     // mt_schedule_destroy does not touch the freed context.
@@ -541,8 +518,6 @@ int launch_item(const mt_ctx *ctx, const mt_schedule *s, const IssueItem &it, co
 // timed again, so a slow queue slot that becomes free is parked again when it comes up).
 int32_t purge_idle_streams(mt_ctx *ctx) {
     HIP_TRY(hipDeviceSynchronize());
-    static const bool trace = std::getenv("MTSCHED_TRACE") != nullptr;
-    if (trace) std::fprintf(stderr, "[mtsched] purge: %zu pooled streams, %zu parked\n", ctx->streams.size(), ctx->parked_streams.size());
     for (auto e = ctx->streams.begin(); e != ctx->streams.end();) {
         if (e->second.refs == 0 && e->first.share != 0) {
             (void)hipStreamDestroy(e->second.stream);
@@ -630,8 +605,6 @@ int32_t make_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_
         float us = 0.f;
         int32_t rc = dispatch_latency_us(ctx, s, ctx->probe_buf, 12, &us);
         if (rc != MT_OK) { (void)hipStreamDestroy(s); return rc; }
-        static const bool trace = std::getenv("MTSCHED_TRACE") != nullptr;
-        if (trace) std::fprintf(stderr, "[mtsched] stream tenant %d share %d attempt %d: %.2f us per dependent launch (best %.2f)\n", tenant, share, attempt, us, ctx->best_dispatch_us);
         if (ctx->best_dispatch_us == 0.f || us < ctx->best_dispatch_us) ctx->best_dispatch_us = us;
         if (us <= 1.2f * ctx->best_dispatch_us || attempt == 3) break;
         // A parked plain stream is never released: after one was destroyed, schedules that mixed plain and masked
@@ -996,9 +969,21 @@ int32_t mt_destroy(mt_ctx *ctx) {
     return MT_OK;
 }
 
+// Graph executables of destroyed schedules are released in batches, each after a device-wide synchronisation, so that a
+// long search under graph replay (two instantiated graphs per candidate) does not keep them all until mt_destroy.
+static int32_t release_retired_graphs(mt_ctx *ctx) {
+    if (ctx->retired_graphs.empty()) return MT_OK;
+    HIP_TRY(hipDeviceSynchronize());
+    for (hipGraphExec_t g : ctx->retired_graphs) (void)hipGraphExecDestroy(g);
+    ctx->retired_graphs.clear();
+    return MT_OK;
+}
+
 int32_t mt_release_idle_streams(mt_ctx *ctx) {
     if (!ctx) return fail(MT_ERR_INVALID_ARG, "ctx is NULL");
     HIP_TRY(hipSetDevice(ctx->device));
+    int32_t rc = release_retired_graphs(ctx);
+    if (rc != MT_OK) return rc;
     return purge_idle_streams(ctx);
 }
 
@@ -1713,7 +1698,6 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
     // and the issuing thread's own launch time does not explain it.  The stream whose removal helps most is then parked
     // and replaced (a masked one only if no other schedule holds it), up to three times.
     if (!(flags & MT_SCHED_GRAPH)) {
-        static const bool trace = std::getenv("MTSCHED_TRACE") != nullptr;
         struct Used { int row, idx; };
         std::vector<Used> used;
         std::vector<hipStream_t> all;
@@ -1753,7 +1737,6 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
             bool bad = false;
             rc = measure(all, &us, &bad);
             if (rc != MT_OK) { release_streams(s.get()); return rc; }
-            if (trace) std::fprintf(stderr, "[mtsched] schedule streams (%zu): %.2f us per concurrent round (best single %.2f)%s\n", all.size(), us, ctx->best_dispatch_us, bad ? " -> bad" : "");
             if (!bad) break;
             // leave one out: the stream without which the rest runs fastest is the one to replace
             int culprit = (int)all.size() - 1;
@@ -1782,7 +1765,6 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
             } else {
                 ctx->parked_streams.push_back(it->second.stream);
             }
-            if (trace) std::fprintf(stderr, "[mtsched]   stream of tenant %d (share %d) replaced\n", u.idx, aq.share);
             it->second.stream = fresh;
             for (int st = 0; st < n_stages; ++st)
                 if (!per_stage || st == u.row) s->stream_at[st][u.idx] = fresh;
@@ -2027,17 +2009,6 @@ struct ProfileCost {
 double profile_schedule(ProfileCost *pc, const int32_t *pointers, const int32_t *cu_share) {
     if (pc->rc != MT_OK) return 1e30;
     mt_schedule *s = nullptr;
-    static const bool trace = std::getenv("MTSCHED_TRACE") != nullptr;
-    if (trace) {
-        std::fprintf(stderr, "[mtsched] profile rho =");
-        for (int i = 0; i < pc->n_tenants * (pc->o->n_stages - 1); ++i) std::fprintf(stderr, " %d", pointers[i]);
-        if (cu_share) {
-            std::fprintf(stderr, "  shares =");
-            for (int i = 0; i < pc->n_tenants; ++i) std::fprintf(stderr, " %d", cu_share[i]);
-        }
-        std::fprintf(stderr, "\n");
-        std::fflush(stderr);
-    }
     pc->rc = mt_schedule_create(pc->ctx, pc->n_tenants, pc->o->n_stages, pointers, pc->conc, cu_share, pc->o->issue_order,
                                 pc->o->flags, &s);
     if (pc->rc == MT_OK && pc->prio) pc->rc = mt_schedule_set_wave_priority(s, pc->prio);
@@ -2051,13 +2022,13 @@ double profile_schedule(ProfileCost *pc, const int32_t *pointers, const int32_t 
         if (r >= pc->o->warmup) samples.push_back(tm.makespan_ms);
     }
     mt_schedule_destroy(s);
+    if (pc->rc == MT_OK && pc->ctx->retired_graphs.size() >= 64) pc->rc = release_retired_graphs(pc->ctx);
     double c = 1e30;
     if (pc->rc == MT_OK && !samples.empty()) {
         std::sort(samples.begin(), samples.end());
         const size_t h = samples.size() / 2;
         c = samples.size() % 2 ? samples[h] : 0.5 * (samples[h - 1] + samples[h]);
     }
-    if (trace) { std::fprintf(stderr, "[mtsched]   cost %.4f ms rc %d\n", c, pc->rc); std::fflush(stderr); }
     return c;
 }
 
@@ -2267,6 +2238,8 @@ int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *in
             }
         }
     }
+    rc = release_retired_graphs(ctx);          // what the candidates of a search under graph replay left behind
+    if (rc != MT_OK) return rc;
     if (best_wave_priority) std::memcpy(best_wave_priority, prio, sizeof(int32_t) * n);
     if (best_concurrency) std::memcpy(best_concurrency, conc, sizeof(int32_t) * opts->n_stages);
     if (best_cu_share) std::memcpy(best_cu_share, shares, sizeof(int32_t) * n);

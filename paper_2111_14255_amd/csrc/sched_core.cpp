@@ -189,7 +189,7 @@ int32_t search_pointers(int32_t n_tenants, const int32_t *lens, const mt_search_
     }
     if (n_records) *n_records = rec.n;
     if (!rec.have) return fail(MT_ERR_INVALID_SCHEDULE, "search evaluated no feasible schedule");
-    std::memcpy(best_pointers, rec.best.data(), sizeof(int32_t) * n_tenants * P);
+    if (n_tenants * P > 0) std::memcpy(best_pointers, rec.best.data(), sizeof(int32_t) * n_tenants * P);   // one stage: nothing to copy
     if (best_cost) *best_cost = rec.best_cost;
     return MT_OK;
 }
