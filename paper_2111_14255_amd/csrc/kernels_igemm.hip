@@ -484,8 +484,18 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
                     if (owner)
                         __hip_atomic_store(&wsp[((i * TM + j) * ACC_REGS + v) * 256 + tid], acc[i][j][v], __ATOMIC_RELAXED,
                                            __HIP_MEMORY_SCOPE_AGENT);
-        // The partial sums are written through to device-coherent memory; wait until every store of every wave
-        // has completed before the arrival counter is bumped.
+        // Hand-off without a device-wide fence (a release at agent scope writes the whole L2 of the XCD back, about 80 us
+        // per launch when tried).  What orders it instead:
+        //  * the partial sums are relaxed ATOMIC stores at agent scope, i.e. written through to memory that every XCD
+        //    reads coherently; they are complete when the wave's vector-memory counter has drained, which the
+        //    s_waitcnt below waits for.  Its "memory" clobber keeps the compiler from moving any access across it, and
+        //    the workgroup barrier after it (a workgroup-scope fence for the compiler, an s_barrier for the hardware)
+        //    makes thread 0 bump the counter only after every wave of the workgroup has drained;
+        //  * the counter is bumped by an atomic read-modify-write at agent scope, performed at the memory side, so the
+        //    arrivals of one tile are totally ordered and exactly one workgroup sees split_k - 1;
+        //  * that workgroup reads the partial sums with relaxed ATOMIC loads at agent scope (served by coherent
+        //    memory, never by a stale line of its own L1 or L2) after the second barrier; atomics are not moved across
+        //    the barrier's fence by the compiler, and the loads depend on s_last through the branch below.
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (tid == 0) {
