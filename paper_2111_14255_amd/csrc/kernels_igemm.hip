@@ -549,6 +549,22 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
         constexpr int ELD = BN + 4;                       // row stride in floats: 4 lanes apart land 16 banks apart
         static_assert((size_t)BM * ELD * sizeof(float) <= sizeof(smem), "epilogue tile must fit the tile buffers");
         float *et = reinterpret_cast<float *>(&smem[0]);
+        constexpr int CPR = BN / 8;                       // 8-channel chunks per pixel row of the tile
+        // The residual chunks this thread will add are requested now, all of them, so that their trip to memory runs
+        // under the accumulator exchange below.  (Inside the store loop every load would have to wait behind the store
+        // of the chunk before it, which may alias it for all the compiler knows: one memory latency per chunk.)
+        constexpr int EP_IT = (BM * CPR + NT - 1) / NT;
+        u32x4 res_raw[EP_IT];
+        const bool add_res = res != nullptr && !a.pool2;
+        if (add_res) {
+#pragma unroll
+            for (int it = 0; it < EP_IT; ++it) {
+                const int c = tid + it * NT;
+                const int m = m0 + c / CPR, k = n0 + (c % CPR) * 8;
+                const bool live = (c < BM * CPR) & (m < M) & (k < a.K);
+                res_raw[it] = live ? *reinterpret_cast<const u32x4 *>(res + (int64_t)m * a.res_ct + k) : u32x4{0u, 0u, 0u, 0u};
+            }
+        }
         __syncthreads();                                  // the accumulator exchange above may still be read
         if (owner) {
 #pragma unroll
@@ -571,7 +587,6 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
                     }
         }
         __syncthreads();
-        constexpr int CPR = BN / 8;                       // 8-channel chunks per pixel row of the tile
         if (a.pool2) {
             // Four consecutive tile rows are one 2x2 window (see the pixel walk above) and the pooled pixel index is the
             // quad index.  Activation and rounding are monotonic, so the maximum is taken before them on fp32 values.
@@ -595,19 +610,20 @@ __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
             }
             return;
         }
-        for (int c = tid; c < BM * CPR; c += NT) {
+#pragma unroll
+        for (int it = 0; it < EP_IT; ++it) {
+            const int c = tid + it * NT;
             const int row = c / CPR, col = (c % CPR) * 8;
             const int m = m0 + row, k = n0 + col;
-            if (m >= M || k >= a.K) continue;
+            if (c >= BM * CPR || m >= M || k >= a.K) continue;
             float v[8];
             const float4 lo = *reinterpret_cast<const float4 *>(&et[row * ELD + col]);
             const float4 hi = *reinterpret_cast<const float4 *>(&et[row * ELD + col + 4]);
             v[0] = lo.x; v[1] = lo.y; v[2] = lo.z; v[3] = lo.w; v[4] = hi.x; v[5] = hi.y; v[6] = hi.z; v[7] = hi.w;
-            if (res) {
-                float rv[8];
-                load_pack<T, 8>(res + (int64_t)m * a.res_ct + k, rv);
+            if (add_res) {
+                const Pack<T, 8> rp = __builtin_bit_cast(Pack<T, 8>, res_raw[it]);
 #pragma unroll
-                for (int t = 0; t < 8; ++t) v[t] += rv[t];
+                for (int t = 0; t < 8; ++t) v[t] += to_f32(rp.e[t]);
             }
 #pragma unroll
             for (int t = 0; t < 8; ++t) v[t] = apply_act(v[t], a.act);
