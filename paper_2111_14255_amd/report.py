@@ -11,6 +11,7 @@
   barriers what a stage barrier costs (Sec. III-B "Stage"): the probe of mt_probe_barrier_cost for 1..8 streams and
            even-split staged schedules of a workload under the event, counter and host-side barriers
   layers   per-operator table of one tenant: GEMM shape, kernel, time alone on the GPU, fraction of its own roofline bound
+  benchsum markdown table of bench.py outputs (all schedules and kernel families of each workload)
   rocprof  turns the CSV files of `rocprofv3 --kernel-trace --stats` / `--pmc ...` runs of `bench.py --roofline-only`
            into the per-family summary kept under profiles/
 
@@ -500,21 +501,73 @@ def report_rocprof(args):
         json.dump(traffic, open(args.traffic_out, "w"), indent=1)
 
 
+def report_benchsum(args):
+    """Markdown summary of bench.py JSON lines (one file per workload, given with --files a.json,b.json,...)."""
+    import json
+    print("# bench.py on one MI355X: the three schedules of every workload")
+    print()
+    print("Commands: `python bench.py` (cfg5, the headline) and `python bench.py --config cfg1|cfg2|cfg3|cfg4`; this table: "
+          "`python -m paper_2111_14255_amd.report benchsum --files <their outputs>`.")
+    print()
+    print("Makespan = mean of the timed steps, ms; img/s from the host's clock around the timed steps.  Rows of one workload that "
+          "share a suffix ran in the same mode: (none) = the headline mode (one issuing host thread per stream, host-side stage "
+          "barriers, fused operator pairs; searched = pointers + streams in use + CU shares + wave priorities, leaders re-measured "
+          "in a play-off), +main_thread = the paper's single issuing thread on plain streams (pointer search only), +graph = "
+          "whole-schedule graph replay.  `one stage` = the searched pointer matrix puts every operator into stage 1.")
+    print()
+    for f in args.files.split(","):
+        d = json.loads(open(f).read().strip().splitlines()[-1])
+        cpu = d.get("cpu_baseline")
+        print("## %s" % d["config"]["workload"])
+        print()
+        print("`value` %.0f img/s (%.4f ms per step), %.2fx sequential, %.2fx all-concurrent in the same mode; bounds of the pass: "
+              "flops %.0f us, bytes %.0f us; makespan / bound %.3f%s." % (
+                  d["value"], d["ms_per_step"], d["speedup_vs_sequential"], d["speedup_vs_all_concurrent"], d["bounds"]["flops_bound_us"],
+                  d["bounds"]["bytes_bound_us"], d["bounds"]["makespan_frac_of_bound"],
+                  "; CPU oracle %.2f img/s on %d threads (%s)" % (cpu["value"], cpu["cores"], cpu["sample"]) if cpu else ""))
+        r = d["roofline"]
+        print("Dominant kernel family %s: %s bound, %.1f %s = %.4f of the published peak (%.4f of the measured %s), %d launches per "
+              "step of %.2f us, arithmetic intensity %.0f flop/B, measured HBM bytes per launch %s." % (
+                  r["kernel"], r["bound"], r["achieved"], r["unit"], r["frac"], r["frac_of_measured_peak"] or 0.0,
+                  json.dumps(r["measured_peaks"]), r["launches_per_step"], r["avg_launch_us"], r["arithmetic_intensity_flop_per_byte"] or 0.0,
+                  r["traffic"]))
+        print()
+        print("| schedule | makespan ms | stdev | img/s | vs sequential | vs all-concurrent | host issue ms | searched result |")
+        print("|---|---|---|---|---|---|---|---|")
+        for k, v in d["schedules"].items():
+            extra = ""
+            if "pointers" in v:
+                extra = "one stage" if v.get("one_stage_matrix") else "rho = %s" % json.dumps(v["pointers"])
+                if "cu_share" in v:
+                    extra += "; streams %d, shares %s, priorities %s" % (v["stage_concurrency"][0], json.dumps(v["cu_share"]), json.dumps(v["wave_priority"]))
+                extra += "; search %.1f s" % v["search_seconds"]
+            print("| %s | %.4f | %.4f | %.0f | %.2f | %.2f | %.3f | %s |" % (
+                k, v["makespan_ms_mean"], v["makespan_ms_stdev"], v["img_per_s"], v["speedup_vs_sequential"], v["speedup_vs_all_concurrent"],
+                v["host_issue_ms_mean"], extra))
+        print()
+        print("| kernel family | launches | us per step | TFLOP/s | GB/s | of MFMA peak | of HBM peak |")
+        print("|---|---|---|---|---|---|---|")
+        for k, v in sorted(r["families"].items(), key=lambda kv: -kv[1]["us"]):
+            print("| %s | %d | %.1f | %.1f | %.0f | %.4f | %.4f |" % (k, v["launches"], v["us"], v["TFLOP/s"], v["GB/s"], v["frac_of_mfma_peak"], v["frac_of_hbm_peak"]))
+        print()
+
+
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=["search", "issue", "mixes", "fusion", "barriers", "layers", "rocprof"])
+    ap.add_argument("what", choices=["search", "issue", "mixes", "fusion", "barriers", "layers", "rocprof", "benchsum"])
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--rounds", type=int, default=3)
     ap.add_argument("--candidates", type=int, default=8)
     ap.add_argument("--runs", type=int, default=7)
     ap.add_argument("--seeds", type=int, default=5)
     ap.add_argument("--only", default="", help="mixes: comma-separated subset of the mix names")
+    ap.add_argument("--files", default="", help="benchsum: comma-separated bench.py outputs")
     ap.add_argument("--tenant", type=int, default=0, help="layers: which tenant of the workload")
     ap.add_argument("--dir", default="", help="rocprof: directory with live.json, trace/ and pmc_*/")
     ap.add_argument("--traffic-out", default="", help="rocprof: write the per-family HBM bytes here (profiles/traffic_<workload>.json)")
     args = ap.parse_args()
     {"search": report_search, "issue": report_issue, "mixes": report_mixes, "fusion": report_fusion, "barriers": report_barriers,
-     "layers": report_layers, "rocprof": report_rocprof}[args.what](args)
+     "layers": report_layers, "rocprof": report_rocprof, "benchsum": report_benchsum}[args.what](args)
 
 
 if __name__ == "__main__":
