@@ -57,6 +57,7 @@ enum KernelId : int32_t {
     K_LRN = 10,             // local response normalisation across channels
     K_ADD = 11,             // element-wise sum of two tensors, activation
     K_IGEMM_PW = 12,        // 1x1 convolution on a small map: MFMA operands straight from memory, no LDS tiles
+    K_STEM = 13,            // first convolution of a network (3 input channels, even horizontal stride): im2col rows straight from memory
     K_COUNT
 };
 
@@ -111,6 +112,24 @@ inline void make_divisor(uint32_t d, uint32_t &m, uint32_t &s1, uint32_t &s2) {
     s1 = l < 1 ? l : 1;
     s2 = l > 1 ? l - 1 : 0;
 }
+
+// Reduction index of the first-layer kernel (K_STEM): per filter row a run of `dummy` + 3 * S input elements, padded to
+// `gr` groups of 8; two groups per matrix-instruction step.  The packed filter bank is ksteps x (channels / 32) x 64
+// lanes x 8 elements, i.e. the operand fragments in the order the kernel reads them.
+struct StemGeom {
+    int dummy, seg, gr, ng, ksteps;
+};
+inline StemGeom stem_geom(int R, int S, int pw) {
+    StemGeom g;
+    g.dummy = (3 * pw) & 1;
+    g.seg = g.dummy + 3 * S;
+    g.gr = (g.seg + 7) / 8;
+    g.ng = R * g.gr;
+    g.ksteps = (g.ng + 1) / 2;
+    return g;
+}
+bool stem_supported(int R, int S, int dummy, int channels);        // is there an instantiation for this window / width
+int launch_stem(const OpArgs &a, void *stream);
 
 // Launchers (defined in the .hip files).  Return a hipError_t as int.
 int launch_direct(const OpArgs &a, void *stream);

@@ -26,14 +26,9 @@
 
 #include "internal.h"
 #include "device_types.h"
+#include "mfma.h"
 
 namespace mt {
-
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // 16-byte register chunk
 
 constexpr int BK = IGEMM_BK;     // reduction elements per LDS tile
 constexpr int LDK = BK + 8;      // padded LDS row (144 bytes: 16-byte reads of a wave fall in distinct banks)
@@ -44,37 +39,6 @@ constexpr uint32_t OOB_OFFSET = 0x80000000u;   // beyond any tensor: buffer load
 // chunks of depthwise output a workgroup takes at most (measured on MobileNetV2 at batch 1: 32 channels per workgroup
 // are 7 % slower, 256 to 1024 chunks 1 to 4 % slower).
 constexpr int PWDW_HC = 16, PWDW_WGS = 64, PWDW_ITEMS = 128;
-
-template <typename T, int MF>
-struct Mma;
-template <>
-struct Mma<f16, 32> {
-    typedef f32x16 Acc;
-    static __device__ __forceinline__ Acc run(u32x4 a, u32x4 b, Acc c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-    }
-};
-template <>
-struct Mma<bf16, 32> {
-    typedef f32x16 Acc;
-    static __device__ __forceinline__ Acc run(u32x4 a, u32x4 b, Acc c) {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    }
-};
-template <>
-struct Mma<f16, 16> {
-    typedef f32x4 Acc;
-    static __device__ __forceinline__ Acc run(u32x4 a, u32x4 b, Acc c) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-    }
-};
-template <>
-struct Mma<bf16, 16> {
-    typedef f32x4 Acc;
-    static __device__ __forceinline__ Acc run(u32x4 a, u32x4 b, Acc c) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    }
-};
 
 // BN: output channels per workgroup, BM: pixels per workgroup, WN x WM: wave grid (4 waves), MF: MFMA edge,
 // STAGES: reduction tiles whose global loads are in flight (register sets), even.

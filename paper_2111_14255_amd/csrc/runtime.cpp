@@ -218,6 +218,22 @@ int32_t finalize_model(mt_model *m) {
                     if (d.kind == MT_FC) { p.H = p.W = 1; p.C = gemm_k; p.x_ct = gemm_k; p.R = p.S = 1; }
                     // im2col gather mode: 2 = tile inside one tap (C % 64 == 0, at most 64 taps), 1 = 16-byte chunks, 0 = element-wise
                     p.vec_a = (p.C % IGEMM_BK == 0 && p.R * p.S <= 64) ? 2 : (p.C % 8 == 0) ? 1 : 0;
+                    const StemGeom sg = stem_geom(R, S, pw);
+                    if (d.kind == MT_CONV && groups == 1 && in.c == 3 && sw % 2 == 0 && in.w % 2 == 0 && res_ct == 0 &&
+                        ctot % 8 == 0 && d.out_c_offset % 8 == 0 && stem_supported(R, S, sg.dummy, o.out_c)) {
+                        // first layer: the im2col rows are contiguous runs of an input row and go straight into the
+                        // MFMA operand registers.  Measured on MI355X (ResNet-50 stem at batch 16, bf16): 45.7 us with the
+                        // element-wise gather of the tile kernel.
+                        p.kernel_id = K_STEM;
+                        p.n_pad = o.out_c;
+                        p.k_pad = sg.ksteps * 16;
+                        const int n_tiles = (m->batch * o.out_h * o.out_w + 31) / 32;
+                        p.grid_x = std::min((n_tiles + 3) / 4, 512);
+                        p.grid_y = p.grid_z = 1;
+                        make_divisor((uint32_t)p.Q, p.divq_m, p.divq_s1, p.divq_s2);
+                        make_divisor((uint32_t)p.P * (uint32_t)p.Q, p.divpq_m, p.divpq_s1, p.divpq_s2);
+                        break;
+                    }
                     plan_igemm(p, m->batch * o.out_h * o.out_w, o.out_c / groups, gemm_k);
                 }
                 break;
@@ -260,7 +276,7 @@ int32_t finalize_model(mt_model *m) {
     for (OpRec &o : m->ops) {
         const OpArgs &p = o.plan;
         if (needs_weights(p.kind)) {
-            bool igemm = is_gemm_kernel(p.kernel_id);
+            bool igemm = is_gemm_kernel(p.kernel_id) || p.kernel_id == K_STEM;
             size_t wcount = igemm ? (size_t)p.groups * p.n_pad * p.k_pad
                                   : (p.kind == MT_DWCONV ? (size_t)p.C * p.R * p.S : (size_t)p.groups * p.K * o.plan.R * o.plan.S * p.C);
             if (p.kind == MT_FC && !igemm) wcount = (size_t)p.K * o.in_h * o.in_w * o.in_c;
@@ -428,6 +444,7 @@ namespace {
 
 // One kernel launch; returns a hipError_t as int.
 int launch_kernel(const OpArgs &a, hipStream_t st) {
+    if (a.kernel_id == K_STEM) return launch_stem(a, st);
     return is_gemm_kernel(a.kernel_id) ? launch_igemm(a, st) : launch_direct(a, st);
 }
 
@@ -897,6 +914,7 @@ const char *mt_kernel_name(int32_t id) {
         case K_IGEMM_64x64: return "igemm_64x64";
         case K_IGEMM_64x16: return "igemm_64x16";
         case K_IGEMM_PW: return "igemm_pointwise";
+        case K_STEM: return "stem_rows";
         case K_DWCONV: return "dwconv";
         case K_MAXPOOL: return "maxpool";
         case K_AVGPOOL: return "avgpool";
@@ -1429,10 +1447,31 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
     for (size_t i = 0; i < nops; ++i) {
         OpRec &o = t->model.ops[i];
         OpArgs a = o.plan;
-        const bool igemm = is_gemm_kernel(a.kernel_id);
+        const bool igemm = is_gemm_kernel(a.kernel_id) || a.kernel_id == K_STEM;
         if (needs_weights(a.kind)) {
             const uint8_t *src = o.w_host.data();
-            if (igemm) {
+            if (a.kernel_id == K_STEM) {
+                // [K][R][S][3] -> [step][channel tile][lane][8]: the matrix-instruction fragments in reading order, zeros at
+                // the dummy and padding positions of every filter row's run
+                const StemGeom sg = stem_geom(a.R, a.S, a.pw);
+                const int tn = a.n_pad / 32;
+                packed.assign((size_t)sg.ksteps * tn * 64 * 8 * es, 0);
+                for (int t = 0; t < sg.ksteps; ++t)
+                    for (int i = 0; i < tn; ++i)
+                        for (int lane = 0; lane < 64; ++lane) {
+                            const int k = 32 * i + lane % 32, G = 2 * t + lane / 32;
+                            if (G >= sg.ng || k >= a.K) continue;
+                            const int r = G / sg.gr, g = G % sg.gr;
+                            for (int e = 0; e < 8; ++e) {
+                                const int elem = 8 * g + e;
+                                if (elem < sg.dummy || elem >= sg.seg) continue;
+                                const int sc = elem - sg.dummy;    // s * 3 + c
+                                std::memcpy(packed.data() + ((((size_t)t * tn + i) * 64 + lane) * 8 + e) * es,
+                                            src + ((size_t)k * a.gemm_k + (size_t)r * a.S * 3 + sc) * es, es);
+                            }
+                        }
+                src = packed.data();
+            } else if (igemm) {
                 // [groups][K][gemm_k] -> [groups][n_pad][k_pad], zero padded
                 packed.assign((size_t)a.groups * a.n_pad * a.k_pad * es, 0);
                 for (int g = 0; g < a.groups; ++g)

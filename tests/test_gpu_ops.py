@@ -13,6 +13,7 @@ pytestmark = pytest.mark.gpu
 # kernel ids as reported by mt_op_info
 DIRECT, IG128, IG64, IG16, DW, MAXP, AVGP, GAP, IG128x64, GEMV = range(10)
 PW = 12
+STEM = 13
 
 
 def g_conv(dtype, n, h, w, c, k, r, stride=1, pad=0, act="relu", bn=True, res=False, coff=0, ctot=0):
@@ -42,7 +43,7 @@ CONV_CASES = [
     ("ig64_7x1", dict(n=1, h=17, w=17, c=32, k=48, r=(7, 1), pad=(3, 0)), IG64),
     ("ig64_5x5", dict(n=1, h=12, w=12, c=8, k=64, r=5, pad=2), IG64),
     ("ig64_splitk", dict(n=1, h=7, w=7, c=256, k=128, r=3, pad=1, res=True), IG64),
-    ("ig64_first_layer_7x7s2", dict(n=1, h=40, w=40, c=3, k=64, r=7, stride=2, pad=3), IG64),
+    ("ig64_first_layer_7x7s2_odd_width", dict(n=1, h=41, w=41, c=3, k=64, r=7, stride=2, pad=3), IG64),
     ("ig64_first_layer_11x11s4", dict(n=1, h=67, w=67, c=3, k=96, r=11, stride=4), IG64),
     ("ig64_c12_scalar", dict(n=1, h=9, w=9, c=12, k=20, r=3, pad=1, act="none"), IG64),
     ("ig64_concat_unaligned", dict(n=1, h=8, w=8, c=16, k=10, r=3, pad=1, coff=3, ctot=18), IG64),
@@ -63,6 +64,19 @@ CONV_CASES = [
     ("ig128x64_long_reduction_eight_waves", dict(n=1, h=128, w=128, c=128, k=128, r=3, pad=1, res=True), IG128x64),
     ("ig128", dict(n=2, h=182, w=182, c=8, k=128, r=3, pad=1, res=True), IG128),
     ("ig128_first_layer", dict(n=2, h=200, w=200, c=3, k=120, r=3, pad=1), IG128),
+    # first-layer kernel: three input channels, even horizontal stride, even width, 32 or 64 output channels
+    ("stem_7x7_ragged_tile", dict(n=1, h=40, w=40, c=3, k=64, r=7, stride=2, pad=3), STEM),
+    ("stem_7x7_three_images", dict(n=3, h=38, w=46, c=3, k=64, r=7, stride=2, pad=3), STEM),
+    ("stem_7x7_all_border", dict(n=2, h=8, w=8, c=3, k=64, r=7, stride=2, pad=3), STEM),
+    ("stem_7x7_one_pixel_row", dict(n=1, h=2, w=2, c=3, k=64, r=7, stride=2, pad=3), STEM),
+    ("stem_7x7_k32_no_act", dict(n=2, h=30, w=34, c=3, k=32, r=7, stride=2, pad=3, act="none", bn=False), STEM),
+    ("stem_7x7_224", dict(n=2, h=224, w=224, c=3, k=64, r=7, stride=2, pad=3), STEM),
+    ("stem_7x7_grid_stride", dict(n=9, h=224, w=224, c=3, k=64, r=7, stride=2, pad=3), STEM),
+    ("stem_3x3_k32_relu6", dict(n=2, h=34, w=30, c=3, k=32, r=3, stride=2, pad=1, act="relu6"), STEM),
+    ("stem_3x3_k64", dict(n=1, h=224, w=224, c=3, k=64, r=3, stride=2, pad=1), STEM),
+    ("stem_3x3_all_border", dict(n=3, h=2, w=4, c=3, k=32, r=3, stride=2, pad=1), STEM),
+    ("stem_7x7_concat", dict(n=1, h=36, w=36, c=3, k=64, r=7, stride=2, pad=3, coff=64, ctot=136), STEM),
+    ("stem_7x7_row_stride_1", dict(n=1, h=20, w=44, c=3, k=64, r=7, stride=(1, 2), pad=3), STEM),
 ]
 
 
@@ -73,6 +87,10 @@ def _expand_cases():
     for name, kw, kid in CONV_CASES:
         if kid != IG64:
             out.append((name, kw, kid))
+            continue
+        if name == "ig64_first_layer_7x7s2_odd_width":
+            out.append((name + "_small", kw, IG16))
+            out.append((name + "_big", dict(kw, h=139, w=139), IG64))
             continue
         op = g_conv("f16", **kw).ops[1 if kw.get("res") else 0]
         if kw["n"] * op.out_shape[0] * op.out_shape[1] > 4096:
