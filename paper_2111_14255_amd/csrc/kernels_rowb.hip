@@ -1,0 +1,206 @@
+// Convolutions whose whole filter bank fits in LDS (1x1 and 3x3 windows on 64 .. 256 input channels, up to 72 KB of
+// filters), with the activations going from memory straight into the MFMA operand registers.
+//
+// The tile kernel stages both operands of every 64-deep reduction tile in LDS and synchronises the workgroup once per
+// tile; on layers with few output channels (a 64 x 64 tile re-reads 16 KB per 0.5 MFLOP) it spends its time waiting.
+// Here the filters are copied to LDS once per workgroup, packed on the host in the order the matrix instruction reads
+// them (step, channel tile, lane), and a wave owns 32 output pixels on its own: in reduction step t lanes 0..31 load
+// channels 16 * (t % SPT) + 0..7 of tap t / SPT of their pixel and lanes 32..63 the next 8, one 16-byte buffer load each
+// (a tap outside the image gets an out-of-range offset and reads zeros).  No activation tile in LDS, no workgroup
+// barrier after the prologue, waves progress independently.
+//   * Short reductions (at most 16 steps: 1x1 windows) keep all operand registers of the pixel tile and walk the
+//     output channels in groups of 64 (the activations are read once).
+//   * Long reductions (3x3 on 64 channels: 36 steps, 64 output channels) keep a window of 12 loads in flight: the
+//     register of step t is refilled with step t + 12 as soon as its matrix instructions are issued.
+// Epilogue per group of 64 channels: the residual tile is fetched with 16-byte loads (whole cache lines per pixel),
+// handed to the accumulator layout through a private LDS block of the wave, added in fp32 after the bias, then
+// activation, one rounding, and the way back through the same block to 16-byte stores.  fp32 accumulation in step order.
+#include <hip/hip_runtime.h>
+
+#include "internal.h"
+#include "device_types.h"
+#include "mfma.h"
+
+namespace mt {
+
+namespace {
+
+constexpr uint32_t ROWB_OOB = 0x80000000u;   // beyond any tensor: buffer loads return zeros
+
+template <typename T, int R, int S, int SPT, int NTA, int NW>
+__global__ void __launch_bounds__(64 * NW) rowb_kernel(OpArgs a) {
+    set_wave_priority(a.prio);
+    constexpr int TAPS = R * S;
+    constexpr int KS = TAPS * SPT;            // MFMA steps (16 reduction elements each)
+    constexpr int C = 16 * SPT;               // input channels
+    constexpr int NGRP = NTA / 2;             // groups of 64 output channels
+    constexpr bool STATIONARY = KS <= 16;
+    constexpr int WIN = STATIONARY ? KS : 12; // operand registers (steps in flight)
+    constexpr int SLD = 64 + 8;               // staging row in elements
+    static_assert(NTA % 2 == 0, "output channels come in groups of 64");
+    static_assert(STATIONARY || NGRP == 1, "a long reduction is walked once");
+    static_assert(TAPS <= 32, "one validity bit per tap");
+    typedef typename Mma<T, 32>::Acc Acc;
+
+    __shared__ __attribute__((aligned(16))) u32x4 Wf[KS * NTA * 64];
+    __shared__ __attribute__((aligned(16))) uint16_t stage[NW][32 * SLD];
+    __shared__ __attribute__((aligned(16))) float bias_s[NTA * 32];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int h = lane >> 5, px = lane & 31;
+
+    {
+        const u32x4 *wp = reinterpret_cast<const u32x4 *>(a.w);
+        for (int c = tid; c < KS * NTA * 64; c += 64 * NW) Wf[c] = wp[c];
+        for (int c = tid; c < NTA * 32; c += 64 * NW) bias_s[c] = a.bias[c];
+    }
+    __syncthreads();
+
+    const int M = a.N * a.P * a.Q;
+    const int n_tiles = (M + 31) / 32;
+    const int size = a.N * a.H * a.W * C * 2;       // < 2 GiB by construction of the model
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.x), 0, size, 0x00027000);
+    T *y = reinterpret_cast<T *>(a.y);
+    const T *res = reinterpret_cast<const T *>(a.res);
+    uint16_t *sg = stage[wave];
+    // staging coordinates of this lane's four 16-byte pieces: pixel row and first channel
+    const int srow = lane >> 3, scol = (lane & 7) * 8;
+
+    for (int tile = blockIdx.x * NW + wave; tile < n_tiles; tile += gridDim.x * NW) {
+        const int m = tile * 32 + px;
+        const bool ok = m < M;
+        const uint32_t mm = ok ? (uint32_t)m : 0u;
+        const uint32_t t1 = __umulhi(a.divpq_m, mm);
+        const int n = (int)((t1 + ((mm - t1) >> a.divpq_s1)) >> a.divpq_s2);
+        const uint32_t rem = mm - (uint32_t)n * (uint32_t)(a.P * a.Q);
+        const uint32_t t2 = __umulhi(a.divq_m, rem);
+        const int p = (int)((t2 + ((rem - t2) >> a.divq_s1)) >> a.divq_s2);
+        const int q = (int)(rem - (uint32_t)p * (uint32_t)a.Q);
+        const int ih0 = p * a.sh - a.ph, iw0 = q * a.sw - a.pw;
+        const int pix = (((n * a.H + ih0) * a.W + iw0) * C + 8 * h) * 2;    // byte offset of tap (0, 0), this lane's half
+        uint32_t tapmask = 0;
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int s = 0; s < S; ++s) {
+                const bool v = ok & ((uint32_t)(ih0 + r) < (uint32_t)a.H) & ((uint32_t)(iw0 + s) < (uint32_t)a.W);
+                tapmask |= v ? (1u << (r * S + s)) : 0u;
+            }
+        auto load_step = [&](int t) {
+            const int tap = t / SPT, r = tap / S, s = tap % S;
+            const int o = pix + ((r * a.W + s) * C + (t % SPT) * 16) * 2;
+            const uint32_t voff = ((tapmask >> tap) & 1u) ? (uint32_t)o : ROWB_OOB;
+            return __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, 0, 0);
+        };
+
+        u32x4 b[WIN];
+        if constexpr (STATIONARY) {
+#pragma unroll
+            for (int t = 0; t < KS; ++t) b[t] = load_step(t);
+        }
+#pragma unroll 1
+        for (int grp = 0; grp < NGRP; ++grp) {
+            const int kb = grp * 64;
+            u32x4 rr[4];
+            if (res) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int mr = tile * 32 + srow + 8 * j;
+                    rr[j] = mr < M ? *reinterpret_cast<const u32x4 *>(res + (int64_t)mr * a.res_ct + kb + scol) : u32x4{0u, 0u, 0u, 0u};
+                }
+            }
+            Acc acc[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+            if constexpr (!STATIONARY) {
+#pragma unroll
+                for (int t = 0; t < WIN; ++t) b[t] = load_step(t);
+            }
+#pragma unroll
+            for (int t = 0; t < KS; ++t) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    acc[i] = Mma<T, 32>::run(Wf[(t * NTA + grp * 2 + i) * 64 + lane], b[t % WIN], acc[i]);
+                if constexpr (!STATIONARY) {
+                    if (t + WIN < KS) b[t % WIN] = load_step(t + WIN);
+                }
+            }
+            // ---- epilogue of the group; the staging block is private to the wave and LDS serves a wave's accesses in
+            // order, so compiler fences are all the synchronisation it takes
+            if (res) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(&sg[(srow + 8 * j) * SLD + scol]) = rr[j];
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int kl = i * 32 + 8 * g + 4 * h;
+                    const float4 bv = *reinterpret_cast<const float4 *>(&bias_s[kb + kl]);
+                    float v[4] = {acc[i][g * 4 + 0] + bv.x, acc[i][g * 4 + 1] + bv.y, acc[i][g * 4 + 2] + bv.z, acc[i][g * 4 + 3] + bv.w};
+                    Pack<T, 4> *slot = reinterpret_cast<Pack<T, 4> *>(&sg[px * SLD + kl]);
+                    if (res) {
+                        const Pack<T, 4> rp = *slot;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] += to_f32(rp.e[e]);
+                    }
+                    Pack<T, 4> o;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) from_f32(apply_act(v[e], a.act), o.e[e]);
+                    *slot = o;
+                }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int row = srow + 8 * j;
+                const int mr = tile * 32 + row;
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(&sg[row * SLD + scol]);
+                if (mr < M) *reinterpret_cast<u32x4 *>(y + (int64_t)mr * a.y_ct + a.y_coff + kb + scol) = v;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+    }
+}
+
+struct RowbShape {
+    int r, c, n, waves;
+};
+// the instantiations: window edge, input channels, output channels, waves per workgroup
+constexpr RowbShape ROWB_SHAPES[] = {{1, 64, 64, 8}, {1, 64, 256, 8}, {1, 256, 64, 8}, {1, 256, 128, 8}, {3, 64, 64, 8}};
+
+}  // namespace
+
+int rowb_waves(int R, int S, int C, int channels) {
+    if (R != S) return 0;
+    for (const RowbShape &s : ROWB_SHAPES)
+        if (s.r == R && s.c == C && s.n == channels) return s.waves;
+    return 0;
+}
+
+int launch_rowb(const OpArgs &a, void *stream) {
+    hipStream_t st = (hipStream_t)stream;
+    const dim3 grid(a.grid_x), block(a.block);
+    auto go = [&]<typename T>() {
+        if (a.R == 1 && a.C == 64 && a.n_pad == 64) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 4, 2, 8>), grid, block, 0, st, a);
+        else if (a.R == 1 && a.C == 64 && a.n_pad == 256) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 4, 8, 8>), grid, block, 0, st, a);
+        else if (a.R == 1 && a.C == 256 && a.n_pad == 64) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 16, 2, 8>), grid, block, 0, st, a);
+        else if (a.R == 1 && a.C == 256 && a.n_pad == 128) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 16, 4, 8>), grid, block, 0, st, a);
+        else if (a.R == 3 && a.C == 64 && a.n_pad == 64) hipLaunchKernelGGL((rowb_kernel<T, 3, 3, 4, 2, 8>), grid, block, 0, st, a);
+    };
+    if (rowb_waves(a.R, a.S, a.C, a.n_pad) == 0) return (int)hipErrorInvalidValue;
+    if (a.dtype == MT_F16) go.template operator()<f16>();
+    else go.template operator()<bf16>();
+    return (int)hipGetLastError();
+}
+
+}  // namespace mt

@@ -16,8 +16,7 @@
 // result does not depend on how the hardware range-checks a partly out-of-range 16-byte access.
 //
 // The packed filters (KS steps x TN channel tiles x 64 lanes x 16 bytes, already in fragment order) are copied to LDS
-// once per workgroup; a wave then walks 32-pixel tiles with a grid stride, the loads of its next tile in flight while
-// the matrix instructions of the current one run.  Epilogue: bias, activation, one rounding, then the wave's
+// once per workgroup; a wave then walks 32-pixel tiles with a grid stride.  Epilogue: bias, activation, one rounding, then the wave's
 // 32 x (32 * TN) tile goes through a private LDS block so that every store instruction writes whole 16-byte pieces of
 // consecutive channels (full cache lines per pixel).  fp32 accumulation in step order t = 0 .. KS-1.
 #include <hip/hip_runtime.h>
@@ -52,13 +51,6 @@ __global__ void __launch_bounds__(256) stem_kernel(OpArgs a) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int h = lane >> 5, px = lane & 31;
-
-    {
-        const u32x4 *wp = reinterpret_cast<const u32x4 *>(a.w);
-        for (int c = tid; c < KS * TN * 64; c += 256) Wf[c] = wp[c];
-        if (tid < KC) bias_s[tid] = a.bias[tid];
-    }
-    __syncthreads();
 
     const int M = a.N * a.P * a.Q;
     const int n_tiles = (M + 31) / 32;
@@ -128,21 +120,38 @@ __global__ void __launch_bounds__(256) stem_kernel(OpArgs a) {
         for (int i = 0; i < TN; ++i)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+        // Interior tiles (every pixel's window inside the image: all lanes hold VM_FULL) only clear the dummy and the
+        // padding, with masks known at compile time; border tiles expand each lane's own mask.
+        constexpr uint32_t VM_FULL = (SEG >= 32 ? 0xFFFFFFFFu : ((1u << SEG) - 1u)) & ~((1u << DUMMY) - 1u);
+        auto dmask = [](uint32_t two) { return ((two & 1u) ? 0x0000FFFFu : 0u) | ((two & 2u) ? 0xFFFF0000u : 0u); };
+        auto steps = [&]<bool INTERIOR>() {
 #pragma unroll
-        for (int t = 0; t < KS; ++t) {
-            const int G0 = 2 * t, G1 = 2 * t + 1;
-            const int g = h ? (G1 < NG ? G1 % GR : 0) : G0 % GR;
-            const uint32_t bits = vm >> (8 * g);
-            u32x4 bm = b[t];
+            for (int t = 0; t < KS; ++t) {
+                const int G0 = 2 * t, G1 = 2 * t + 1;
+                const int g0 = G0 % GR, g1 = G1 < NG ? G1 % GR : 0;
+                u32x4 bm = b[t];
+                if constexpr (INTERIOR) {
 #pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                const uint32_t lo = (uint32_t)((int32_t)(bits << (31 - 2 * d)) >> 31);
-                const uint32_t hi = (uint32_t)((int32_t)(bits << (30 - 2 * d)) >> 31);
-                bm[d] &= (lo & 0x0000FFFFu) | (hi & 0xFFFF0000u);
+                    for (int d = 0; d < 4; ++d) {
+                        const uint32_t m0 = dmask(VM_FULL >> (8 * g0 + 2 * d)), m1 = dmask(VM_FULL >> (8 * g1 + 2 * d));
+                        if (m0 != 0xFFFFFFFFu || m1 != 0xFFFFFFFFu) bm[d] &= h ? m1 : m0;
+                    }
+                } else {
+                    const uint32_t bits = vm >> (8 * (h ? g1 : g0));
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        const uint32_t lo = (uint32_t)((int32_t)(bits << (31 - 2 * d)) >> 31);
+                        const uint32_t hi = (uint32_t)((int32_t)(bits << (30 - 2 * d)) >> 31);
+                        bm[d] &= (lo & 0x0000FFFFu) | (hi & 0xFFFF0000u);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < TN; ++i) acc[i] = Mma<T, 32>::run(Wf[(t * TN + i) * 64 + lane], bm, acc[i]);
             }
-#pragma unroll
-            for (int i = 0; i < TN; ++i) acc[i] = Mma<T, 32>::run(Wf[(t * TN + i) * 64 + lane], bm, acc[i]);
-        }
+        };
+        // lanes past the last pixel hold zeros and an empty mask; they do not force the slow form
+        if (__builtin_amdgcn_ballot_w64(vm != VM_FULL && tile * 32 + px < M) == 0) steps.template operator()<true>();
+        else steps.template operator()<false>();
         uint16_t *sg = stage[wave];
 #pragma unroll
         for (int i = 0; i < TN; ++i)
@@ -175,19 +184,23 @@ __global__ void __launch_bounds__(256) stem_kernel(OpArgs a) {
 
     const int stride = gridDim.x * 4;
     int tile = blockIdx.x * 4 + wave;
-    u32x4 b0[KS], b1[KS];
-    uint32_t vm0 = 0, vm1 = 0;
-    if (tile < n_tiles) fetch(tile, b0, vm0);
+    u32x4 b[KS];
+    uint32_t vm = 0;
+    // the first tile's activations are requested before the filters, so that both trips to memory overlap
+    if (tile < n_tiles) fetch(tile, b, vm);
+    {
+        const u32x4 *wp = reinterpret_cast<const u32x4 *>(a.w);
+        for (int c = tid; c < KS * TN * 64; c += 256) Wf[c] = wp[c];
+        if (tid < KC) bias_s[tid] = a.bias[tid];
+    }
+    __syncthreads();
+    // One tile in flight per wave: the other waves of the SIMD cover its trips to memory.  (Requesting the next tile
+    // before finishing the current one doubles the operand registers and leaves two waves per SIMD instead of three:
+    // measured on MI355X, ResNet stem at batch 16 / 128, 15.1 / 67.8 us against 12.6 / 58.1 us.)
     while (tile < n_tiles) {
-        int nxt = tile + stride;
-        if (nxt < n_tiles) fetch(nxt, b1, vm1);
-        finish(tile, b0, vm0);
-        tile = nxt;
-        if (tile >= n_tiles) break;
-        nxt = tile + stride;
-        if (nxt < n_tiles) fetch(nxt, b0, vm0);
-        finish(tile, b1, vm1);
-        tile = nxt;
+        finish(tile, b, vm);
+        tile += stride;
+        if (tile < n_tiles) fetch(tile, b, vm);
     }
 }
 

@@ -222,13 +222,15 @@ int32_t finalize_model(mt_model *m) {
                     if (d.kind == MT_CONV && groups == 1 && in.c == 3 && sw % 2 == 0 && in.w % 2 == 0 && res_ct == 0 &&
                         ctot % 8 == 0 && d.out_c_offset % 8 == 0 && stem_supported(R, S, sg.dummy, o.out_c)) {
                         // first layer: the im2col rows are contiguous runs of an input row and go straight into the
-                        // MFMA operand registers.  Measured on MI355X (ResNet-50 stem at batch 16, bf16): 45.7 us with the
-                        // element-wise gather of the tile kernel.
+                        // MFMA operand registers.  Measured on MI355X (ResNet-50 stem, bf16, batch 1 / 16 / 128): 4.8 / 12.6 /
+                        // 58 us against 7 / 45.7 / 303 us with the element-wise gather of the tile kernel.
                         p.kernel_id = K_STEM;
                         p.n_pad = o.out_c;
                         p.k_pad = sg.ksteps * 16;
                         const int n_tiles = (m->batch * o.out_h * o.out_w + 31) / 32;
-                        p.grid_x = std::min((n_tiles + 3) / 4, 512);
+                                                // as many workgroups as stay resident (3 per compute unit for the 7x7 window with 64 channels, by
+                        // registers and LDS; 6 or more for the lighter forms); the waves walk the tiles with a grid stride
+                        p.grid_x = std::min((n_tiles + 3) / 4, (R == 7 && o.out_c == 64) ? 768 : 1536);
                         p.grid_y = p.grid_z = 1;
                         make_divisor((uint32_t)p.Q, p.divq_m, p.divq_s1, p.divq_s2);
                         make_divisor((uint32_t)p.P * (uint32_t)p.Q, p.divpq_m, p.divpq_s1, p.divpq_s2);
