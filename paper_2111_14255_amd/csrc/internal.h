@@ -58,6 +58,7 @@ enum KernelId : int32_t {
     K_ADD = 11,             // element-wise sum of two tensors, activation
     K_IGEMM_PW = 12,        // 1x1 convolution on a small map: MFMA operands straight from memory, no LDS tiles
     K_STEM = 13,            // first convolution of a network (3 input channels, even horizontal stride): im2col rows straight from memory
+    K_ROWB = 14,            // filter bank resident in LDS, activations straight from memory (few output channels or short reductions)
     K_COUNT
 };
 
@@ -130,6 +131,11 @@ inline StemGeom stem_geom(int R, int S, int pw) {
 }
 bool stem_supported(int R, int S, int dummy, int channels);        // is there an instantiation for this window / width
 int launch_stem(const OpArgs &a, void *stream);
+// K_ROWB: waves per workgroup of the instantiation for this window / channel counts, 0 if there is none.  Its packed
+// filter bank is steps x (channels / 32) x 64 lanes x 8 elements, a step being 16 consecutive elements of the (r, s, c)
+// reduction index.
+int rowb_waves(int R, int S, int C, int channels);
+int launch_rowb(const OpArgs &a, void *stream);
 
 // Launchers (defined in the .hip files).  Return a hipError_t as int.
 int launch_direct(const OpArgs &a, void *stream);

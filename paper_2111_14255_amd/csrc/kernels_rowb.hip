@@ -21,6 +21,15 @@
 #include "device_types.h"
 #include "mfma.h"
 
+#ifndef ROWB_NW1
+#define ROWB_NW1 8
+#endif
+#ifndef ROWB_NW3
+#define ROWB_NW3 8
+#endif
+#ifndef ROWB_WIN
+#define ROWB_WIN 12
+#endif
 namespace mt {
 
 namespace {
@@ -35,7 +44,7 @@ __global__ void __launch_bounds__(64 * NW) rowb_kernel(OpArgs a) {
     constexpr int C = 16 * SPT;               // input channels
     constexpr int NGRP = NTA / 2;             // groups of 64 output channels
     constexpr bool STATIONARY = KS <= 16;
-    constexpr int WIN = STATIONARY ? KS : 12; // operand registers (steps in flight)
+    constexpr int WIN = STATIONARY ? KS : ROWB_WIN; // operand registers (steps in flight)
     constexpr int SLD = 64 + 8;               // staging row in elements
     static_assert(NTA % 2 == 0, "output channels come in groups of 64");
     static_assert(STATIONARY || NGRP == 1, "a long reduction is walked once");
@@ -176,7 +185,7 @@ struct RowbShape {
     int r, c, n, waves;
 };
 // the instantiations: window edge, input channels, output channels, waves per workgroup
-constexpr RowbShape ROWB_SHAPES[] = {{1, 64, 64, 8}, {1, 64, 256, 8}, {1, 256, 64, 8}, {1, 256, 128, 8}, {3, 64, 64, 8}};
+constexpr RowbShape ROWB_SHAPES[] = {{1, 64, 64, ROWB_NW1}, {1, 64, 256, ROWB_NW1}, {1, 256, 64, ROWB_NW1}, {1, 256, 128, ROWB_NW1}, {3, 64, 64, ROWB_NW3}};
 
 }  // namespace
 
@@ -191,11 +200,11 @@ int launch_rowb(const OpArgs &a, void *stream) {
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid(a.grid_x), block(a.block);
     auto go = [&]<typename T>() {
-        if (a.R == 1 && a.C == 64 && a.n_pad == 64) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 4, 2, 8>), grid, block, 0, st, a);
-        else if (a.R == 1 && a.C == 64 && a.n_pad == 256) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 4, 8, 8>), grid, block, 0, st, a);
-        else if (a.R == 1 && a.C == 256 && a.n_pad == 64) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 16, 2, 8>), grid, block, 0, st, a);
-        else if (a.R == 1 && a.C == 256 && a.n_pad == 128) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 16, 4, 8>), grid, block, 0, st, a);
-        else if (a.R == 3 && a.C == 64 && a.n_pad == 64) hipLaunchKernelGGL((rowb_kernel<T, 3, 3, 4, 2, 8>), grid, block, 0, st, a);
+        if (a.R == 1 && a.C == 64 && a.n_pad == 64) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 4, 2, ROWB_NW1>), grid, block, 0, st, a);
+        else if (a.R == 1 && a.C == 64 && a.n_pad == 256) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 4, 8, ROWB_NW1>), grid, block, 0, st, a);
+        else if (a.R == 1 && a.C == 256 && a.n_pad == 64) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 16, 2, ROWB_NW1>), grid, block, 0, st, a);
+        else if (a.R == 1 && a.C == 256 && a.n_pad == 128) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 16, 4, ROWB_NW1>), grid, block, 0, st, a);
+        else if (a.R == 3 && a.C == 64 && a.n_pad == 64) hipLaunchKernelGGL((rowb_kernel<T, 3, 3, 4, 2, ROWB_NW3>), grid, block, 0, st, a);
     };
     if (rowb_waves(a.R, a.S, a.C, a.n_pad) == 0) return (int)hipErrorInvalidValue;
     if (a.dtype == MT_F16) go.template operator()<f16>();

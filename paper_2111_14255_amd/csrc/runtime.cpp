@@ -59,6 +59,13 @@ struct mt_model {
 
 namespace {
 
+#ifndef ROWB_MIN_PIXELS
+#define ROWB_MIN_PIXELS 8192
+#endif
+#ifndef ROWB_MAX_PIXELS_3X3
+#define ROWB_MAX_PIXELS_3X3 131072
+#endif
+
 bool needs_weights(int kind) { return kind == MT_CONV || kind == MT_DWCONV || kind == MT_FC; }
 
 // Kernel, tile and split choice of a convolution / fully connected layer: a pure function of the GEMM shape.
@@ -236,7 +243,22 @@ int32_t finalize_model(mt_model *m) {
                         make_divisor((uint32_t)p.P * (uint32_t)p.Q, p.divpq_m, p.divpq_s1, p.divpq_s2);
                         break;
                     }
-                    plan_igemm(p, m->batch * o.out_h * o.out_w, o.out_c / groups, gemm_k);
+                    const int M = m->batch * o.out_h * o.out_w;
+                    const int rw = (d.kind == MT_CONV && groups == 1 && ph < R && (R == 3 || (ph == 0 && pw == 0))) ? rowb_waves(R, S, in.c, o.out_c) : 0;
+                    if (rw > 0 && res_ct % 8 == 0 && ctot % 8 == 0 && d.out_c_offset % 8 == 0 && M >= ROWB_MIN_PIXELS && (R == 1 || M <= ROWB_MAX_PIXELS_3X3)) {
+                        // few output channels or a short reduction on a large map: filters resident in LDS, one wave per 32 pixels
+                        p.kernel_id = K_ROWB;
+                        p.n_pad = o.out_c;
+                        p.k_pad = gemm_k;
+                        p.block = 64 * rw;
+                        const int n_tiles = (M + 31) / 32;
+                        p.grid_x = std::min((n_tiles + rw - 1) / rw, 512);
+                        p.grid_y = p.grid_z = 1;
+                        make_divisor((uint32_t)p.Q, p.divq_m, p.divq_s1, p.divq_s2);
+                        make_divisor((uint32_t)p.P * (uint32_t)p.Q, p.divpq_m, p.divpq_s1, p.divpq_s2);
+                        break;
+                    }
+                    plan_igemm(p, M, o.out_c / groups, gemm_k);
                 }
                 break;
             }
@@ -278,7 +300,7 @@ int32_t finalize_model(mt_model *m) {
     for (OpRec &o : m->ops) {
         const OpArgs &p = o.plan;
         if (needs_weights(p.kind)) {
-            bool igemm = is_gemm_kernel(p.kernel_id) || p.kernel_id == K_STEM;
+            bool igemm = is_gemm_kernel(p.kernel_id) || p.kernel_id == K_STEM || p.kernel_id == K_ROWB;
             size_t wcount = igemm ? (size_t)p.groups * p.n_pad * p.k_pad
                                   : (p.kind == MT_DWCONV ? (size_t)p.C * p.R * p.S : (size_t)p.groups * p.K * o.plan.R * o.plan.S * p.C);
             if (p.kind == MT_FC && !igemm) wcount = (size_t)p.K * o.in_h * o.in_w * o.in_c;
@@ -447,6 +469,7 @@ namespace {
 // One kernel launch; returns a hipError_t as int.
 int launch_kernel(const OpArgs &a, hipStream_t st) {
     if (a.kernel_id == K_STEM) return launch_stem(a, st);
+    if (a.kernel_id == K_ROWB) return launch_rowb(a, st);
     return is_gemm_kernel(a.kernel_id) ? launch_igemm(a, st) : launch_direct(a, st);
 }
 
@@ -917,6 +940,7 @@ const char *mt_kernel_name(int32_t id) {
         case K_IGEMM_64x16: return "igemm_64x16";
         case K_IGEMM_PW: return "igemm_pointwise";
         case K_STEM: return "stem_rows";
+        case K_ROWB: return "igemm_resident_filters";
         case K_DWCONV: return "dwconv";
         case K_MAXPOOL: return "maxpool";
         case K_AVGPOOL: return "avgpool";
@@ -1449,7 +1473,7 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
     for (size_t i = 0; i < nops; ++i) {
         OpRec &o = t->model.ops[i];
         OpArgs a = o.plan;
-        const bool igemm = is_gemm_kernel(a.kernel_id) || a.kernel_id == K_STEM;
+        const bool igemm = is_gemm_kernel(a.kernel_id) || a.kernel_id == K_STEM || a.kernel_id == K_ROWB;
         if (needs_weights(a.kind)) {
             const uint8_t *src = o.w_host.data();
             if (a.kernel_id == K_STEM) {
@@ -1471,6 +1495,20 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
                                 std::memcpy(packed.data() + ((((size_t)t * tn + i) * 64 + lane) * 8 + e) * es,
                                             src + ((size_t)k * a.gemm_k + (size_t)r * a.S * 3 + sc) * es, es);
                             }
+                        }
+                src = packed.data();
+            } else if (a.kernel_id == K_ROWB) {
+                // [K][gemm_k] -> [step][channel tile][lane][8]: lane l of a step holds elements 16 * step + 8 * (l / 32) .. + 7
+                // of output channel 32 * tile + l % 32
+                const int steps = a.gemm_k / 16, tn = a.n_pad / 32;
+                packed.assign((size_t)steps * tn * 64 * 8 * es, 0);
+                for (int t = 0; t < steps; ++t)
+                    for (int i = 0; i < tn; ++i)
+                        for (int lane = 0; lane < 64; ++lane) {
+                            const int k = 32 * i + lane % 32;
+                            if (k >= a.K) continue;
+                            std::memcpy(packed.data() + (((size_t)t * tn + i) * 64 + lane) * 8 * es,
+                                        src + ((size_t)k * a.gemm_k + 16 * t + 8 * (lane / 32)) * es, (size_t)8 * es);
                         }
                 src = packed.data();
             } else if (igemm) {

@@ -14,6 +14,7 @@ pytestmark = pytest.mark.gpu
 DIRECT, IG128, IG64, IG16, DW, MAXP, AVGP, GAP, IG128x64, GEMV = range(10)
 PW = 12
 STEM = 13
+ROWB = 14
 
 
 def g_conv(dtype, n, h, w, c, k, r, stride=1, pad=0, act="relu", bn=True, res=False, coff=0, ctot=0):
@@ -76,6 +77,16 @@ CONV_CASES = [
     ("stem_3x3_k64", dict(n=1, h=224, w=224, c=3, k=64, r=3, stride=2, pad=1), STEM),
     ("stem_3x3_all_border", dict(n=3, h=2, w=4, c=3, k=32, r=3, stride=2, pad=1), STEM),
     ("stem_7x7_concat", dict(n=1, h=36, w=36, c=3, k=64, r=7, stride=2, pad=3, coff=64, ctot=136), STEM),
+    # filters resident in LDS, activations straight from memory: 1x1 / 3x3 on 64 or 256 channels, maps of 8192 pixels or more
+    ("rowb_1x1_c64_n64", dict(n=1, h=96, w=96, c=64, k=64, r=1), ROWB),
+    ("rowb_1x1_c64_n256_res", dict(n=1, h=92, w=92, c=64, k=256, r=1, res=True), ROWB),
+    ("rowb_1x1_c256_n64_ragged", dict(n=1, h=91, w=93, c=256, k=64, r=1, act="relu6"), ROWB),
+    ("rowb_1x1_c256_n128", dict(n=2, h=66, w=66, c=256, k=128, r=1, act="none", bn=False), ROWB),
+    ("rowb_1x1_stride2", dict(n=4, h=100, w=100, c=64, k=256, r=1, stride=2), ROWB),
+    ("rowb_3x3_res_ragged", dict(n=1, h=95, w=97, c=64, k=64, r=3, pad=1, res=True), ROWB),
+    ("rowb_3x3_stride2", dict(n=3, h=120, w=116, c=64, k=64, r=3, stride=2, pad=1), ROWB),
+    ("rowb_3x3_no_padding", dict(n=1, h=100, w=100, c=64, k=64, r=3), ROWB),
+    ("rowb_concat", dict(n=1, h=96, w=96, c=64, k=64, r=1, coff=64, ctot=192), ROWB),
     ("stem_7x7_row_stride_1", dict(n=1, h=20, w=44, c=3, k=64, r=7, stride=(1, 2), pad=3), STEM),
 ]
 
