@@ -121,8 +121,14 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
     // reads with MFMA better than four.  Measured on MI355X at batch 8: 3x3 layers of 128 / 256 / 512 channels on
     // 112^2 / 56^2 / 28^2 maps 62.9 -> 56.5, 62.2 -> 54.9, 59.5 -> 52.1 us; the short reductions of 1x1 layers lose
     // (17.3 -> 19.3 us) and keep four waves.  The same change on the 128x128 tile loses everywhere.
-    if (kid == K_IGEMM_128x64 && p.vec_a != 0 && nkt >= 18) p.wk = 2;
-    int wk_tiles = 512;
+    #ifndef IG_WK_NKT
+#define IG_WK_NKT 18
+#endif
+    if (kid == K_IGEMM_128x64 && p.vec_a != 0 && nkt >= IG_WK_NKT) p.wk = 2;
+#ifndef IG_WK_TILES
+#define IG_WK_TILES 512
+#endif
+    int wk_tiles = IG_WK_TILES;
     if (kid == K_IGEMM_64x64 && p.vec_a != 0 && tiles <= wk_tiles) {
         // Few workgroups per compute unit: eight waves per tile (two per SIMD, the MFMA steps of every LDS tile split
         // between two wave groups) and only as many splits as keep about one workgroup per unit.  Measured on MI355X,
@@ -2191,10 +2197,16 @@ int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *in
         int32_t trial[MT_MAX_STAGES];
         int best_c = n;
         pc.conc = trial;
+        // `cost` comes from the longer runs of the play-off when there was one: the stream counts are then measured
+        // the same way, so that one of them replaces "one stream per tenant" only on an equal footing
+        mt_search_opts longer = *opts;
+        if (playoff) longer.runs = opts->playoff_runs >= 1 ? opts->playoff_runs : 21;
+        ProfileCost pcl{ctx, &longer, inputs, outputs, n};
+        pcl.conc = trial;
         for (int c = 2; c < n; ++c) {
             for (int st = 0; st < opts->n_stages; ++st) trial[st] = c;
-            const double cc = profile_schedule(&pc, best_pointers, nullptr);
-            if (pc.rc != MT_OK) return pc.rc;
+            const double cc = profile_schedule(&pcl, best_pointers, nullptr);
+            if (pcl.rc != MT_OK) return pcl.rc;
             if (cc < cost) { cost = cc; best_c = c; }
         }
         for (int st = 0; st < opts->n_stages; ++st) conc[st] = best_c;
@@ -2314,6 +2326,44 @@ int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *in
                 std::memset(shares, 0, sizeof(shares));
                 rc = purge_idle_streams(ctx);
                 if (rc != MT_OK) return rc;
+            }
+        }
+    }
+    if (playoff) {
+        // Last check: the result as a whole (pointers, stream count, shares, priorities) against the plain configuration
+        // it started from (everything in stage 1, one stream per tenant, no shares, default priorities), both measured
+        // twice in turn with the longer runs.  The coordinates were accepted one after the other on single
+        // measurements; if together they do not beat the start, the start is returned.
+        bool plain = true;
+        for (int i = 0; i < n; ++i) plain = plain && shares[i] == 0 && prio[i] == ((opts->flags & MT_SCHED_PRIORITIZE_SHORT) ? -1 : 0);
+        for (int st = 0; st < opts->n_stages; ++st) plain = plain && conc[st] == n;
+        for (size_t k = 0; k < width; ++k) plain = plain && best_pointers[k] >= lens[k / P];
+        if (!plain) {
+            mt_search_opts longer = *opts;
+            longer.runs = opts->playoff_runs >= 1 ? opts->playoff_runs : 21;
+            std::vector<int32_t> all_first(width);
+            for (size_t k = 0; k < width; ++k) all_first[k] = lens[k / P];
+            bool masked = false;
+            for (int i = 0; i < n; ++i) masked = masked || shares[i] != 0;
+            double found = 1e30, start = 1e30;
+            for (int turn = 0; turn < 2; ++turn) {
+                ProfileCost pa{ctx, &longer, inputs, outputs, n};
+                pa.conc = conc[0] == n ? nullptr : conc;
+                pa.prio = prio;
+                found = std::min(found, profile_schedule(&pa, best_pointers, masked ? shares : nullptr));
+                if (pa.rc != MT_OK) return pa.rc;
+                ProfileCost pb{ctx, &longer, inputs, outputs, n};
+                start = std::min(start, profile_schedule(&pb, all_first.data(), nullptr));
+                if (pb.rc != MT_OK) return pb.rc;
+            }
+            if (start < found) {
+                std::memcpy(best_pointers, all_first.data(), sizeof(int32_t) * width);
+                for (int st = 0; st < opts->n_stages; ++st) conc[st] = n;
+                std::memset(shares, 0, sizeof(shares));
+                for (int i = 0; i < n; ++i) prio[i] = (opts->flags & MT_SCHED_PRIORITIZE_SHORT) ? -1 : 0;
+                cost = start;
+            } else {
+                cost = found;
             }
         }
     }
