@@ -132,9 +132,10 @@ inline StemGeom stem_geom(int R, int S, int pw) {
 bool stem_supported(int R, int S, int dummy, int channels);        // is there an instantiation for this window / width
 int launch_stem(const OpArgs &a, void *stream);
 // K_ROWB: waves per workgroup of the instantiation for this window / channel counts, 0 if there is none.  Its packed
-// filter bank is steps x (channels / 32) x 64 lanes x 8 elements, a step being 16 consecutive elements of the (r, s, c)
-// reduction index.
+// filter bank is slices x steps x tiles per slice x 64 lanes x 8 elements, a step being 16 consecutive elements of the
+// (r, s, c) reduction index and a tile 32 output channels.
 int rowb_waves(int R, int S, int C, int channels);
+int rowb_tiles(int R, int S, int C, int channels);   // 32-channel tiles per slice of output channels (a workgroup holds one slice's filters)
 int launch_rowb(const OpArgs &a, void *stream);
 
 // Launchers (defined in the .hip files).  Return a hipError_t as int.

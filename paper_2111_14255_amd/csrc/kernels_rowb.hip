@@ -21,15 +21,6 @@
 #include "device_types.h"
 #include "mfma.h"
 
-#ifndef ROWB_NW1
-#define ROWB_NW1 8
-#endif
-#ifndef ROWB_NW3
-#define ROWB_NW3 8
-#endif
-#ifndef ROWB_WIN
-#define ROWB_WIN 12
-#endif
 namespace mt {
 
 namespace {
@@ -44,7 +35,7 @@ __global__ void __launch_bounds__(64 * NW) rowb_kernel(OpArgs a) {
     constexpr int C = 16 * SPT;               // input channels
     constexpr int NGRP = NTA / 2;             // groups of 64 output channels
     constexpr bool STATIONARY = KS <= 16;
-    constexpr int WIN = STATIONARY ? KS : ROWB_WIN; // operand registers (steps in flight)
+    constexpr int WIN = STATIONARY ? KS : 12;  // operand registers (steps in flight)
     constexpr int SLD = 64 + 8;               // staging row in elements
     static_assert(NTA % 2 == 0, "output channels come in groups of 64");
     static_assert(STATIONARY || NGRP == 1, "a long reduction is walked once");
@@ -59,10 +50,15 @@ __global__ void __launch_bounds__(64 * NW) rowb_kernel(OpArgs a) {
     const int lane = tid & 63, wave = tid >> 6;
     const int h = lane >> 5, px = lane & 31;
 
+    // A workgroup owns one slice of 32 * NTA output channels (its filters are one contiguous block of the packed bank)
+    // and every n_slices-th chunk of NW pixel tiles.
+    const int n_slices = a.n_pad / (32 * NTA);
+    const int slice = blockIdx.x % n_slices;
+    const int kslice = slice * 32 * NTA;
     {
-        const u32x4 *wp = reinterpret_cast<const u32x4 *>(a.w);
+        const u32x4 *wp = reinterpret_cast<const u32x4 *>(a.w) + (size_t)slice * KS * NTA * 64;
         for (int c = tid; c < KS * NTA * 64; c += 64 * NW) Wf[c] = wp[c];
-        for (int c = tid; c < NTA * 32; c += 64 * NW) bias_s[c] = a.bias[c];
+        for (int c = tid; c < NTA * 32; c += 64 * NW) bias_s[c] = a.bias[kslice + c];
     }
     __syncthreads();
 
@@ -76,7 +72,7 @@ __global__ void __launch_bounds__(64 * NW) rowb_kernel(OpArgs a) {
     // staging coordinates of this lane's four 16-byte pieces: pixel row and first channel
     const int srow = lane >> 3, scol = (lane & 7) * 8;
 
-    for (int tile = blockIdx.x * NW + wave; tile < n_tiles; tile += gridDim.x * NW) {
+    for (int tile = (blockIdx.x / n_slices) * NW + wave; tile < n_tiles; tile += (gridDim.x / n_slices) * NW) {
         const int m = tile * 32 + px;
         const bool ok = m < M;
         const uint32_t mm = ok ? (uint32_t)m : 0u;
@@ -116,7 +112,7 @@ __global__ void __launch_bounds__(64 * NW) rowb_kernel(OpArgs a) {
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     const int mr = tile * 32 + srow + 8 * j;
-                    rr[j] = mr < M ? *reinterpret_cast<const u32x4 *>(res + (int64_t)mr * a.res_ct + kb + scol) : u32x4{0u, 0u, 0u, 0u};
+                    rr[j] = mr < M ? *reinterpret_cast<const u32x4 *>(res + (int64_t)mr * a.res_ct + kslice + kb + scol) : u32x4{0u, 0u, 0u, 0u};
                 }
             }
             Acc acc[2];
@@ -172,7 +168,7 @@ __global__ void __launch_bounds__(64 * NW) rowb_kernel(OpArgs a) {
                 const int row = srow + 8 * j;
                 const int mr = tile * 32 + row;
                 const u32x4 v = *reinterpret_cast<const u32x4 *>(&sg[row * SLD + scol]);
-                if (mr < M) *reinterpret_cast<u32x4 *>(y + (int64_t)mr * a.y_ct + a.y_coff + kb + scol) = v;
+                if (mr < M) *reinterpret_cast<u32x4 *>(y + (int64_t)mr * a.y_ct + a.y_coff + kslice + kb + scol) = v;
             }
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
@@ -181,32 +177,35 @@ __global__ void __launch_bounds__(64 * NW) rowb_kernel(OpArgs a) {
     }
 }
 
-struct RowbShape {
-    int r, c, n, waves;
-};
-// the instantiations: window edge, input channels, output channels, waves per workgroup
-constexpr RowbShape ROWB_SHAPES[] = {{1, 64, 64, ROWB_NW1}, {1, 64, 256, ROWB_NW1}, {1, 256, 64, ROWB_NW1}, {1, 256, 128, ROWB_NW1}, {3, 64, 64, ROWB_NW3}};
-
 }  // namespace
 
-int rowb_waves(int R, int S, int C, int channels) {
+// Channel tiles (of 32) per slice and waves per workgroup for a window / channel combination, 0 if there is no
+// instantiation.  A slice's filters (32 * tiles * R * S * C elements) stay at or below 72 KB.
+int rowb_tiles(int R, int S, int C, int channels) {
     if (R != S) return 0;
-    for (const RowbShape &s : ROWB_SHAPES)
-        if (s.r == R && s.c == C && s.n == channels) return s.waves;
+    if (R == 3) return (C == 64 && channels == 64) ? 2 : 0;
+    if (R != 1) return 0;
+    if (C == 64) return channels % 256 == 0 ? 8 : channels % 64 == 0 ? 2 : 0;
+    if (C == 128) return channels % 128 == 0 ? 4 : 0;
+    if (C == 256) return channels % 128 == 0 ? 4 : channels % 64 == 0 ? 2 : 0;
     return 0;
 }
+
+int rowb_waves(int R, int S, int C, int channels) { return rowb_tiles(R, S, C, channels) ? 8 : 0; }
 
 int launch_rowb(const OpArgs &a, void *stream) {
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid(a.grid_x), block(a.block);
+    const int nta = rowb_tiles(a.R, a.S, a.C, a.n_pad);
+    if (nta == 0 || (int)block.x != 64 * rowb_waves(a.R, a.S, a.C, a.n_pad)) return (int)hipErrorInvalidValue;
     auto go = [&]<typename T>() {
-        if (a.R == 1 && a.C == 64 && a.n_pad == 64) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 4, 2, ROWB_NW1>), grid, block, 0, st, a);
-        else if (a.R == 1 && a.C == 64 && a.n_pad == 256) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 4, 8, ROWB_NW1>), grid, block, 0, st, a);
-        else if (a.R == 1 && a.C == 256 && a.n_pad == 64) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 16, 2, ROWB_NW1>), grid, block, 0, st, a);
-        else if (a.R == 1 && a.C == 256 && a.n_pad == 128) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 16, 4, ROWB_NW1>), grid, block, 0, st, a);
-        else if (a.R == 3 && a.C == 64 && a.n_pad == 64) hipLaunchKernelGGL((rowb_kernel<T, 3, 3, 4, 2, ROWB_NW3>), grid, block, 0, st, a);
+        if (a.R == 3) hipLaunchKernelGGL((rowb_kernel<T, 3, 3, 4, 2, 8>), grid, block, 0, st, a);
+        else if (a.C == 64 && nta == 2) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 4, 2, 8>), grid, block, 0, st, a);
+        else if (a.C == 64) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 4, 8, 8>), grid, block, 0, st, a);
+        else if (a.C == 128) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 8, 4, 8>), grid, block, 0, st, a);
+        else if (nta == 2) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 16, 2, 8>), grid, block, 0, st, a);
+        else hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 16, 4, 8>), grid, block, 0, st, a);
     };
-    if (rowb_waves(a.R, a.S, a.C, a.n_pad) == 0) return (int)hipErrorInvalidValue;
     if (a.dtype == MT_F16) go.template operator()<f16>();
     else go.template operator()<bf16>();
     return (int)hipGetLastError();

@@ -257,8 +257,11 @@ int32_t finalize_model(mt_model *m) {
                         p.n_pad = o.out_c;
                         p.k_pad = gemm_k;
                         p.block = 64 * rw;
+                        // one workgroup per (slice of output channels, chunk of rw pixel tiles); chunks beyond what stays
+                        // resident are walked with a stride
                         const int n_tiles = (M + 31) / 32;
-                        p.grid_x = std::min((n_tiles + rw - 1) / rw, 512);
+                        const int slices = o.out_c / (32 * rowb_tiles(R, S, in.c, o.out_c));
+                        p.grid_x = slices * std::max(1, std::min((n_tiles + rw - 1) / rw, 512 / slices));
                         p.grid_y = p.grid_z = 1;
                         make_divisor((uint32_t)p.Q, p.divq_m, p.divq_s1, p.divq_s2);
                         make_divisor((uint32_t)p.P * (uint32_t)p.Q, p.divpq_m, p.divpq_s1, p.divpq_s2);
@@ -1504,18 +1507,19 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
                         }
                 src = packed.data();
             } else if (a.kernel_id == K_ROWB) {
-                // [K][gemm_k] -> [step][channel tile][lane][8]: lane l of a step holds elements 16 * step + 8 * (l / 32) .. + 7
-                // of output channel 32 * tile + l % 32
-                const int steps = a.gemm_k / 16, tn = a.n_pad / 32;
-                packed.assign((size_t)steps * tn * 64 * 8 * es, 0);
-                for (int t = 0; t < steps; ++t)
-                    for (int i = 0; i < tn; ++i)
-                        for (int lane = 0; lane < 64; ++lane) {
-                            const int k = 32 * i + lane % 32;
-                            if (k >= a.K) continue;
-                            std::memcpy(packed.data() + (((size_t)t * tn + i) * 64 + lane) * 8 * es,
-                                        src + ((size_t)k * a.gemm_k + 16 * t + 8 * (lane / 32)) * es, (size_t)8 * es);
-                        }
+                // [K][gemm_k] -> [slice][step][channel tile][lane][8]: lane l of a step holds elements 16 * step + 8 * (l / 32)
+                // .. + 7 of output channel 32 * (slice * tiles + tile) + l % 32
+                const int steps = a.gemm_k / 16, tn = rowb_tiles(a.R, a.S, a.C, a.n_pad), slices = a.n_pad / (32 * tn);
+                packed.assign((size_t)slices * steps * tn * 64 * 8 * es, 0);
+                for (int sl = 0; sl < slices; ++sl)
+                    for (int t = 0; t < steps; ++t)
+                        for (int i = 0; i < tn; ++i)
+                            for (int lane = 0; lane < 64; ++lane) {
+                                const int k = 32 * (sl * tn + i) + lane % 32;
+                                if (k >= a.K) continue;
+                                std::memcpy(packed.data() + ((((size_t)sl * steps + t) * tn + i) * 64 + lane) * 8 * es,
+                                            src + ((size_t)k * a.gemm_k + 16 * t + 8 * (lane / 32)) * es, (size_t)8 * es);
+                            }
                 src = packed.data();
             } else if (igemm) {
                 // [groups][K][gemm_k] -> [groups][n_pad][k_pad], zero padded

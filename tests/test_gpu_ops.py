@@ -86,6 +86,10 @@ CONV_CASES = [
     ("rowb_3x3_res_ragged", dict(n=1, h=95, w=97, c=64, k=64, r=3, pad=1, res=True), ROWB),
     ("rowb_3x3_stride2", dict(n=3, h=120, w=116, c=64, k=64, r=3, stride=2, pad=1), ROWB),
     ("rowb_3x3_no_padding", dict(n=1, h=100, w=100, c=64, k=64, r=3), ROWB),
+    ("rowb_1x1_c128_n512_sliced_res", dict(n=1, h=92, w=92, c=128, k=512, r=1, res=True), ROWB),
+    ("rowb_1x1_c256_n512_stride2", dict(n=4, h=100, w=100, c=256, k=512, r=1, stride=2), ROWB),
+    ("rowb_1x1_c64_n128_two_slices", dict(n=1, h=96, w=96, c=64, k=128, r=1, act="none"), ROWB),
+    ("rowb_1x1_c256_n192_three_slices", dict(n=1, h=91, w=93, c=256, k=192, r=1), ROWB),
     ("rowb_concat", dict(n=1, h=96, w=96, c=64, k=64, r=1, coff=64, ctot=192), ROWB),
     ("stem_7x7_row_stride_1", dict(n=1, h=20, w=44, c=3, k=64, r=7, stride=(1, 2), pad=3), STEM),
 ]
