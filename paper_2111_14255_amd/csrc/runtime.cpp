@@ -59,12 +59,11 @@ struct mt_model {
 
 namespace {
 
-#ifndef ROWB_MIN_PIXELS
-#define ROWB_MIN_PIXELS 8192
-#endif
-#ifndef ROWB_MAX_PIXELS_3X3
-#define ROWB_MAX_PIXELS_3X3 131072
-#endif
+// Pixel range of the resident-filter kernel.  Below 8192 pixels there are too few 32-pixel wave tiles to fill the chip
+// (ResNet-50 256 -> 1024 on a 14x14 map at batch 16: 10.9 us against 8.7 us on the 128x64 tile).  A 3x3 window reads every
+// input line nine times through the L1, which bounds it on large maps (64 -> 64 on 56x56 at batch 16 / 128: 12.1 / 70.4 us
+// against 15.0 / 65.7 us on the tile kernel).
+constexpr int ROWB_MIN_PIXELS = 8192, ROWB_MAX_PIXELS_3X3 = 131072;
 
 bool needs_weights(int kind) { return kind == MT_CONV || kind == MT_DWCONV || kind == MT_FC; }
 
@@ -121,14 +120,8 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
     // reads with MFMA better than four.  Measured on MI355X at batch 8: 3x3 layers of 128 / 256 / 512 channels on
     // 112^2 / 56^2 / 28^2 maps 62.9 -> 56.5, 62.2 -> 54.9, 59.5 -> 52.1 us; the short reductions of 1x1 layers lose
     // (17.3 -> 19.3 us) and keep four waves.  The same change on the 128x128 tile loses everywhere.
-    #ifndef IG_WK_NKT
-#define IG_WK_NKT 18
-#endif
-    if (kid == K_IGEMM_128x64 && p.vec_a != 0 && nkt >= IG_WK_NKT) p.wk = 2;
-#ifndef IG_WK_TILES
-#define IG_WK_TILES 512
-#endif
-    int wk_tiles = IG_WK_TILES;
+        if (kid == K_IGEMM_128x64 && p.vec_a != 0 && nkt >= 18) p.wk = 2;
+    int wk_tiles = 512;
     if (kid == K_IGEMM_64x64 && p.vec_a != 0 && tiles <= wk_tiles) {
         // Few workgroups per compute unit: eight waves per tile (two per SIMD, the MFMA steps of every LDS tile split
         // between two wave groups) and only as many splits as keep about one workgroup per unit.  Measured on MI355X,

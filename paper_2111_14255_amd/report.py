@@ -379,7 +379,7 @@ def _family_of(kernel_name):
     m = re.search(r"igemm_kernel<[^,]+, (\d+), (\d+)", kernel_name) or re.match(r"_ZN2mt12igemm_kernelI(?:DF16_|NS_4bf16E)Li(\d+)ELi(\d+)E", kernel_name)
     if m:
         return "igemm_%sx%s" % (m.group(1), m.group(2))
-    for key, fam in (("pw_direct_kernel", "igemm_pointwise"), ("gemv_kernel", "gemv"), ("dwconv", "dwconv"), ("gap_kernel", "global_avgpool"),
+    for key, fam in (("stem_kernel", "stem_rows"), ("rowb_kernel", "igemm_resident_filters"), ("pw_direct_kernel", "igemm_pointwise"), ("gemv_kernel", "gemv"), ("dwconv", "dwconv"), ("gap_kernel", "global_avgpool"),
                      ("pool", "pool"), ("conv_direct", "conv_direct"), ("lrn_kernel", "lrn"), ("add_kernel", "add")):
         if key in kernel_name:
             return fam
@@ -403,7 +403,7 @@ def report_rocprof(args):
     print()
     print("    python3 $R/bench.py --config %s --roofline-only > live.json" % args.config)
     print("    rocprofv3 --kernel-trace --stats -d trace -o roof --output-format csv -- python3 $R/bench.py --config %s --roofline-only" % args.config)
-    for name in sorted(os.path.basename(x) for x in glob.glob(os.path.join(d, "pmc_*"))):
+    for name in sorted(os.path.basename(x) for x in glob.glob(os.path.join(d, "pmc_*")) if os.path.isdir(x)):
         cs = set()
         for f in glob.glob(os.path.join(d, name, "**", "*counter_collection.csv"), recursive=True):
             for r in csv.DictReader(open(f)):
