@@ -136,6 +136,7 @@ int launch_stem(const OpArgs &a, void *stream);
 // (r, s, c) reduction index and a tile 32 output channels.
 int rowb_waves(int R, int S, int C, int channels);
 int rowb_tiles(int R, int S, int C, int channels);   // 32-channel tiles per slice of output channels (a workgroup holds one slice's filters)
+bool rowb_patch_form(const OpArgs &a);   // 3x3, stride 1: activations staged once per tile as an input patch in LDS
 int launch_rowb(const OpArgs &a, void *stream);
 
 // Launchers (defined in the .hip files).  Return a hipError_t as int.

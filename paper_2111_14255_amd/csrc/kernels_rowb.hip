@@ -177,6 +177,158 @@ __global__ void __launch_bounds__(64 * NW) rowb_kernel(OpArgs a) {
     }
 }
 
+// 3x3 window, stride 1, 64 -> 64 channels: the activations go through LDS once, as the input patch of the wave's pixel
+// tile, instead of once per tap through the L1.  A wave owns 4 x 8 output pixels; their 6 x 10 input pixels (128 bytes
+// each, padded to 144 so that the fragment reads of neighbouring pixels fall into different banks) are
+// fetched with whole-cache-line 16-byte loads (pixels outside the image read zeros) into a private LDS block, and the
+// operand fragment of tap (r, s), channels 16 u + 8 h .. + 7 is the 16-byte piece at patch pixel (dy + r, dx + s).  Every
+// input line is read from memory once per tile instead of nine times; the patch of the next tile is in flight (in
+// registers) while the matrix instructions of the current one run.  Filters resident in LDS as above; the epilogue
+// reuses the patch block as its staging block.  fp32 accumulation in step order (tap-major, 16 channels per step), the
+// same order as the streaming form above.
+template <typename T>
+__global__ void __launch_bounds__(512) rowp_kernel(OpArgs a) {
+    set_wave_priority(a.prio);
+    constexpr int KS = 36, NTA = 2, NW = 8, C = 64, SPT = 4;
+    constexpr int TP = 4, TQ = 8;                 // output rows x columns of a wave tile
+    constexpr int PR = TP + 2, PC = TQ + 2;       // its input patch
+    constexpr int PIX = 72;                       // elements per patch pixel (128 + 16 bytes)
+    // Elements per patch row: 10 pixels and 224 bytes, so that rows are 128 bytes apart modulo the 256 bytes of the LDS
+    // banks.  The 16 lanes served together (8 pixels of two rows) then read 16 different 16-byte bank groups: pixels 144
+    // bytes apart fall on groups 0, 9, 2, 11, 4, 13, 6, 15, the next row on the other eight.
+    constexpr int PROW = PC * PIX + 112;
+    constexpr int NCHUNK = PR * PC * 8;           // 16-byte pieces of a patch
+    constexpr int NLD = (NCHUNK + 63) / 64;
+    constexpr int SLD = PIX;                      // staging rows of the epilogue live in the same block
+    typedef typename Mma<T, 32>::Acc Acc;
+
+    __shared__ __attribute__((aligned(16))) u32x4 Wf[KS * NTA * 64];
+    __shared__ __attribute__((aligned(16))) uint16_t patch[NW][PR * PROW];
+    __shared__ __attribute__((aligned(16))) float bias_s[64];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int h = lane >> 5, px = lane & 31;
+    const int dy = px >> 3, dx = px & 7;
+    {
+        const u32x4 *wp = reinterpret_cast<const u32x4 *>(a.w);
+        for (int c = tid; c < KS * NTA * 64; c += 64 * NW) Wf[c] = wp[c];
+        if (tid < 64) bias_s[tid] = a.bias[tid];
+    }
+    __syncthreads();
+
+    const int tiles_q = (a.Q + TQ - 1) / TQ, tiles_p = (a.P + TP - 1) / TP;
+    const int per_img = tiles_p * tiles_q;
+    const int n_tiles = a.N * per_img;
+    const int size = a.N * a.H * a.W * C * 2;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(a.x), 0, size, 0x00027000);
+    T *y = reinterpret_cast<T *>(a.y);
+    const T *res = reinterpret_cast<const T *>(a.res);
+    uint16_t *pt = patch[wave];
+    const int srow = lane >> 3, scol = (lane & 7) * 8;
+
+    struct Where {
+        int n, p0, q0;
+    };
+    auto where = [&](int tile) {
+        Where w;
+        w.n = tile / per_img;
+        const int rem = tile - w.n * per_img;
+        const int tp = rem / tiles_q;
+        w.p0 = tp * TP;
+        w.q0 = (rem - tp * tiles_q) * TQ;
+        return w;
+    };
+    // piece c = lane + 64 k of the patch: pixel j = c / 8 = lane / 8 + 8 k, channels 8 * (lane % 8) ..
+    auto fetch = [&](const Where &w, u32x4 (&g)[NLD]) {
+#pragma unroll
+        for (int k = 0; k < NLD; ++k) {
+            const int j = (lane >> 3) + 8 * k;
+            const int pr = (j * 205) >> 11, pc = j - pr * PC;      // j / 10 for j < 64
+            const int ih = w.p0 - a.ph + pr, iw = w.q0 - a.pw + pc;
+            const bool v = (j < PR * PC) & ((uint32_t)ih < (uint32_t)a.H) & ((uint32_t)iw < (uint32_t)a.W);
+            const uint32_t voff = v ? (uint32_t)((((w.n * a.H + ih) * a.W + iw) * C + (lane & 7) * 8) * 2) : ROWB_OOB;
+            g[k] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, 0, 0);
+        }
+    };
+    auto wave_fence = [] {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+
+    const int stride = gridDim.x * NW;
+    int tile = blockIdx.x * NW + wave;
+    u32x4 g[NLD];
+    if (tile < n_tiles) fetch(where(tile), g);
+    for (; tile < n_tiles; tile += stride) {
+        const Where w = where(tile);
+        // the patch block is private to the wave and LDS serves a wave's accesses in order: compiler fences suffice
+        wave_fence();
+#pragma unroll
+        for (int k = 0; k < NLD; ++k) {
+            const int j = (lane >> 3) + 8 * k;
+            const int pr = (j * 205) >> 11, pc = j - pr * PC;
+            if (j < PR * PC) *reinterpret_cast<u32x4 *>(&pt[pr * PROW + pc * PIX + (lane & 7) * 8]) = g[k];
+        }
+        wave_fence();
+        if (tile + stride < n_tiles) fetch(where(tile + stride), g);
+
+        // rows of the staging block = pixels of the tile in (dy, dx) order
+        u32x4 rr[4];
+        int mrow[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int row = srow + 8 * j;
+            const int p = w.p0 + (row >> 3), q = w.q0 + (row & 7);
+            mrow[j] = (p < a.P && q < a.Q) ? (w.n * a.P + p) * a.Q + q : -1;
+            if (res) rr[j] = mrow[j] >= 0 ? *reinterpret_cast<const u32x4 *>(res + (int64_t)mrow[j] * a.res_ct + scol) : u32x4{0u, 0u, 0u, 0u};
+        }
+        Acc acc[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+#pragma unroll
+        for (int t = 0; t < KS; ++t) {
+            const int tap = t / SPT, r = tap / 3, sx = tap % 3, u = t % SPT;
+            const u32x4 b = *reinterpret_cast<const u32x4 *>(&pt[(dy + r) * PROW + (dx + sx) * PIX + u * 16 + h * 8]);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) acc[i] = Mma<T, 32>::run(Wf[(t * NTA + i) * 64 + lane], b, acc[i]);
+        }
+        wave_fence();                                   // every fragment is read before the block becomes the staging block
+        if (res) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4 *>(&pt[(srow + 8 * j) * SLD + scol]) = rr[j];
+            wave_fence();
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const int kl = i * 32 + 8 * gq + 4 * h;
+                const float4 bv = *reinterpret_cast<const float4 *>(&bias_s[kl]);
+                float v[4] = {acc[i][gq * 4 + 0] + bv.x, acc[i][gq * 4 + 1] + bv.y, acc[i][gq * 4 + 2] + bv.z, acc[i][gq * 4 + 3] + bv.w};
+                Pack<T, 4> *slot = reinterpret_cast<Pack<T, 4> *>(&pt[px * SLD + kl]);
+                if (res) {
+                    const Pack<T, 4> rp = *slot;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] += to_f32(rp.e[e]);
+                }
+                Pack<T, 4> o;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) from_f32(apply_act(v[e], a.act), o.e[e]);
+                *slot = o;
+            }
+        wave_fence();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(&pt[(srow + 8 * j) * SLD + scol]);
+            if (mrow[j] >= 0) *reinterpret_cast<u32x4 *>(y + (int64_t)mrow[j] * a.y_ct + a.y_coff + scol) = v;
+        }
+    }
+}
+
 }  // namespace
 
 // Channel tiles (of 32) per slice and waves per workgroup for a window / channel combination, 0 if there is no
@@ -191,6 +343,9 @@ int rowb_tiles(int R, int S, int C, int channels) {
     return 0;
 }
 
+// The 3x3 layers of stride 1 take the patch form (rowp_kernel); its grid walks 4 x 8 pixel tiles, not runs of 32 pixels.
+bool rowb_patch_form(const OpArgs &a) { return a.R == 3 && a.S == 3 && a.sh == 1 && a.sw == 1 && a.C == 64 && a.n_pad == 64; }
+
 int rowb_waves(int R, int S, int C, int channels) { return rowb_tiles(R, S, C, channels) ? 8 : 0; }
 
 int launch_rowb(const OpArgs &a, void *stream) {
@@ -199,7 +354,8 @@ int launch_rowb(const OpArgs &a, void *stream) {
     const int nta = rowb_tiles(a.R, a.S, a.C, a.n_pad);
     if (nta == 0 || (int)block.x != 64 * rowb_waves(a.R, a.S, a.C, a.n_pad)) return (int)hipErrorInvalidValue;
     auto go = [&]<typename T>() {
-        if (a.R == 3) hipLaunchKernelGGL((rowb_kernel<T, 3, 3, 4, 2, 8>), grid, block, 0, st, a);
+        if (a.R == 3 && rowb_patch_form(a)) hipLaunchKernelGGL((rowp_kernel<T>), grid, block, 0, st, a);
+        else if (a.R == 3) hipLaunchKernelGGL((rowb_kernel<T, 3, 3, 4, 2, 8>), grid, block, 0, st, a);
         else if (a.C == 64 && nta == 2) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 4, 2, 8>), grid, block, 0, st, a);
         else if (a.C == 64) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 4, 8, 8>), grid, block, 0, st, a);
         else if (a.C == 128) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 8, 4, 8>), grid, block, 0, st, a);

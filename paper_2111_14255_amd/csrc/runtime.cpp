@@ -244,7 +244,8 @@ int32_t finalize_model(mt_model *m) {
                     }
                     const int M = m->batch * o.out_h * o.out_w;
                     const int rw = (d.kind == MT_CONV && groups == 1 && ph < R && (R == 3 || (ph == 0 && pw == 0))) ? rowb_waves(R, S, in.c, o.out_c) : 0;
-                    if (rw > 0 && res_ct % 8 == 0 && ctot % 8 == 0 && d.out_c_offset % 8 == 0 && M >= ROWB_MIN_PIXELS && (R == 1 || M <= ROWB_MAX_PIXELS_3X3)) {
+                    if (rw > 0 && res_ct % 8 == 0 && ctot % 8 == 0 && d.out_c_offset % 8 == 0 && M >= ROWB_MIN_PIXELS &&
+                        (R == 1 || M <= ROWB_MAX_PIXELS_3X3 || (sh == 1 && sw == 1))) {
                         // few output channels or a short reduction on a large map: filters resident in LDS, one wave per 32 pixels
                         p.kernel_id = K_ROWB;
                         p.n_pad = o.out_c;
@@ -255,6 +256,11 @@ int32_t finalize_model(mt_model *m) {
                         const int n_tiles = (M + 31) / 32;
                         const int slices = o.out_c / (32 * rowb_tiles(R, S, in.c, o.out_c));
                         p.grid_x = slices * std::max(1, std::min((n_tiles + rw - 1) / rw, 512 / slices));
+                        if (rowb_patch_form(p)) {
+                            // 4 x 8 pixel tiles, eight per workgroup, one workgroup per compute unit (143 KB of LDS)
+                            const int t2 = m->batch * ((o.out_h + 3) / 4) * ((o.out_w + 7) / 8);
+                            p.grid_x = std::max(1, std::min((t2 + rw - 1) / rw, 256));
+                        }
                         p.grid_y = p.grid_z = 1;
                         make_divisor((uint32_t)p.Q, p.divq_m, p.divq_s1, p.divq_s2);
                         make_divisor((uint32_t)p.P * (uint32_t)p.Q, p.divpq_m, p.divpq_s1, p.divpq_s2);

@@ -84,6 +84,8 @@ CONV_CASES = [
     ("rowb_1x1_c256_n128", dict(n=2, h=66, w=66, c=256, k=128, r=1, act="none", bn=False), ROWB),
     ("rowb_1x1_stride2", dict(n=4, h=100, w=100, c=64, k=256, r=1, stride=2), ROWB),
     ("rowb_3x3_res_ragged", dict(n=1, h=95, w=97, c=64, k=64, r=3, pad=1, res=True), ROWB),
+    ("rowb_3x3_patch_three_images", dict(n=3, h=60, w=52, c=64, k=64, r=3, pad=1, act="relu6"), ROWB),
+    ("rowb_3x3_patch_grid_stride", dict(n=5, h=112, w=112, c=64, k=64, r=3, pad=1, res=True), ROWB),
     ("rowb_3x3_stride2", dict(n=3, h=120, w=116, c=64, k=64, r=3, stride=2, pad=1), ROWB),
     ("rowb_3x3_no_padding", dict(n=1, h=100, w=100, c=64, k=64, r=3), ROWB),
     ("rowb_1x1_c128_n512_sliced_res", dict(n=1, h=92, w=92, c=128, k=512, r=1, res=True), ROWB),
