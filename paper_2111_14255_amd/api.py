@@ -35,6 +35,34 @@ def from_storage(a, dtype):
     return (np.asarray(a).view(np.uint16).astype(np.uint32) << 16).view(np.float32)
 
 
+def save_records(path, lens, n_stages, records, note=""):
+    """Writes the record memory D of a search (Alg. 1: every profiled pointer matrix with its cost) as JSON, so that
+    the search can be audited or its leaders measured again later (Context.replay_records)."""
+    import json
+    doc = {"lens": [int(v) for v in lens], "n_stages": int(n_stages), "note": note,
+           "records": [{"pointers": [[int(v) for v in row] for row in rho], "cost_ms": float(c)} for rho, c in records]}
+    with open(path, "w") as f:
+        json.dump(doc, f)
+
+
+def load_records(path):
+    """Returns (lens, n_stages, records) as written by save_records; checks that every matrix fits the operator counts."""
+    import json
+    with open(path) as f:
+        doc = json.load(f)
+    lens, n_stages = [int(v) for v in doc["lens"]], int(doc["n_stages"])
+    records = []
+    for r in doc["records"]:
+        rho = [[int(v) for v in row] for row in r["pointers"]]
+        if len(rho) != len(lens) or any(len(row) != n_stages - 1 for row in rho):
+            raise ValueError("record does not match lens / n_stages")
+        for row, n in zip(rho, lens):
+            if any(v < 0 or v > n for v in row) or any(b < a for a, b in zip(row, row[1:])):
+                raise ValueError("record holds an infeasible pointer row")
+        records.append((rho, float(r["cost_ms"])))
+    return lens, n_stages, records
+
+
 def torch_dtype(dtype):
     import torch
     return {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[dtype]
@@ -321,6 +349,34 @@ class Context:
         if search_concurrency:
             out += ([conc[i] for i in range(n_stages)],)
         return out
+
+    def replay_records(self, records, n_stages, inputs, outputs, top_k=3, runs=21, warmup=2, flags=0, order=B.MT_ISSUE_BFS):
+        """Play-off over a stored record memory (load_records): the top_k records of lowest stored cost and the
+        one-stage matrix are profiled again on this context (median makespan of `runs` runs each); returns
+        (pointer matrix, cost, number of matrices measured)."""
+        n, P = self.num_tenants(), n_stages - 1
+        lens = self.lens()
+        bound = self.bind(inputs, outputs)
+
+        def cost(ptr, _user):
+            rho = [[ptr[i * P + j] for j in range(P)] for i in range(n)]
+            s = self.schedule(rho, n_stages, order=order, flags=flags)
+            try:
+                for _ in range(warmup):
+                    self.run(s, bound)
+                v = sorted(self.run(s, bound)["makespan_ms"] for _ in range(runs))
+            finally:
+                s.close()
+            return v[len(v) // 2]
+
+        flat = [v for rho, _ in records for row in rho for v in row]
+        costs = (C.c_double * max(1, len(records)))(*[c for _, c in records])
+        best = (C.c_int32 * max(1, n * P))()
+        bc, nev = C.c_double(), C.c_int32()
+        fn = B.mt_cost_fn(cost)
+        B.check(self.lib.mt_playoff_pointers(n, (C.c_int32 * n)(*lens), n_stages, (C.c_int32 * max(1, len(flat)))(*flat), costs,
+                                             len(records), top_k, fn, None, best, C.byref(bc), C.byref(nev)))
+        return [[best[i * P + j] for j in range(P)] for i in range(n)], bc.value, nev.value
 
     def close(self):
         if self.h:

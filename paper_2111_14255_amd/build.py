@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libmtsched.so")
 
-DEVICE_SOURCES = ["kernels_direct.hip", "kernels_igemm.hip", "kernels_stem.hip", "kernels_rowb.hip"]
+DEVICE_SOURCES = ["kernels_direct.hip", "kernels_igemm.hip", "kernels_stem.hip", "kernels_rowb.hip", "kernels_patch.hip"]
 HOST_SOURCES = ["sched_core.cpp", "runtime.cpp"]
 COMMON = ["-O3", "-fPIC", "-std=c++20", "-Wall", "-Wno-unused-function"]
 # packed-fp32 code generation is switched off for all device code

@@ -59,6 +59,7 @@ enum KernelId : int32_t {
     K_IGEMM_PW = 12,        // 1x1 convolution on a small map: MFMA operands straight from memory, no LDS tiles
     K_STEM = 13,            // first convolution of a network (3 input channels, even horizontal stride): im2col rows straight from memory
     K_ROWB = 14,            // filter bank resident in LDS, activations straight from memory (few output channels or short reductions)
+    K_PCONV = 15,           // 3x3, stride 1, padding 1: 64 x 64 implicit GEMM whose activations are staged as an input patch per 64 channels
     K_COUNT
 };
 
@@ -136,6 +137,10 @@ int launch_stem(const OpArgs &a, void *stream);
 // (r, s, c) reduction index and a tile 32 output channels.
 int rowb_waves(int R, int S, int C, int channels);
 int rowb_tiles(int R, int S, int C, int channels);   // 32-channel tiles per slice of output channels (a workgroup holds one slice's filters)
+// K_PCONV: patch pixels of the instantiation that holds a map of width W (0: none).  Its filter bank is [n_pad][k_pad]
+// like the tile kernel's, with the reduction index ordered (64-channel chunk, tap, channel).
+int pconv_patch_pixels(int W);
+int launch_pconv(const OpArgs &a, void *stream);
 bool rowb_patch_form(const OpArgs &a);   // 3x3, stride 1: activations staged once per tile as an input patch in LDS
 int launch_rowb(const OpArgs &a, void *stream);
 

@@ -64,6 +64,9 @@ namespace {
 // input line nine times through the L1, which bounds it on large maps (64 -> 64 on 56x56 at batch 16 / 128: 12.1 / 70.4 us
 // against 15.0 / 65.7 us on the tile kernel).
 constexpr int ROWB_MIN_PIXELS = 8192, ROWB_MAX_PIXELS_3X3 = 131072;
+#ifndef PCONV_MIN_TILES
+#define PCONV_MIN_TILES 150
+#endif
 
 bool needs_weights(int kind) { return kind == MT_CONV || kind == MT_DWCONV || kind == MT_FC; }
 
@@ -136,6 +139,15 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
         split = cdiv(nkt, per);            // no empty split
     }
     p.split_k = std::max(1, split);
+    if (kid == K_IGEMM_64x64 && p.split_k == 1 && tiles >= PCONV_MIN_TILES && p.kind == MT_CONV && p.groups <= 1 && p.R == 3 && p.S == 3 &&
+        p.sh == 1 && p.sw == 1 && p.ph == 1 && p.pw == 1 && p.C % 64 == 0 && p.K % 8 == 0 && p.y_ct % 8 == 0 && p.y_coff % 8 == 0 &&
+        p.res_ct % 8 == 0 && pconv_patch_pixels(p.W) > 0) {
+        // 3x3 layers that would run on the 64x64 tile unsplit: same tile, activations staged as an input patch
+        p.kernel_id = K_PCONV;
+        p.wk = 1;
+        p.block = 512;
+        p.k_pad = gemm_k;
+    }
     // Which operand each XCD's L2 keeps to itself: consecutive tiles (one XCD) walk the channel tiles of one pixel
     // tile (0) when the activations are the larger operand, the pixel tiles of one channel tile (1) otherwise.
     p.tile_order = ((double)Kc * gemm_k > (double)p.N * p.H * p.W * p.C) ? 1 : 0;
@@ -308,7 +320,7 @@ int32_t finalize_model(mt_model *m) {
     for (OpRec &o : m->ops) {
         const OpArgs &p = o.plan;
         if (needs_weights(p.kind)) {
-            bool igemm = is_gemm_kernel(p.kernel_id) || p.kernel_id == K_STEM || p.kernel_id == K_ROWB;
+            bool igemm = is_gemm_kernel(p.kernel_id) || p.kernel_id == K_STEM || p.kernel_id == K_ROWB || p.kernel_id == K_PCONV;
             size_t wcount = igemm ? (size_t)p.groups * p.n_pad * p.k_pad
                                   : (p.kind == MT_DWCONV ? (size_t)p.C * p.R * p.S : (size_t)p.groups * p.K * o.plan.R * o.plan.S * p.C);
             if (p.kind == MT_FC && !igemm) wcount = (size_t)p.K * o.in_h * o.in_w * o.in_c;
@@ -478,6 +490,7 @@ namespace {
 int launch_kernel(const OpArgs &a, hipStream_t st) {
     if (a.kernel_id == K_STEM) return launch_stem(a, st);
     if (a.kernel_id == K_ROWB) return launch_rowb(a, st);
+    if (a.kernel_id == K_PCONV) return launch_pconv(a, st);
     return is_gemm_kernel(a.kernel_id) ? launch_igemm(a, st) : launch_direct(a, st);
 }
 
@@ -949,6 +962,7 @@ const char *mt_kernel_name(int32_t id) {
         case K_IGEMM_PW: return "igemm_pointwise";
         case K_STEM: return "stem_rows";
         case K_ROWB: return "igemm_resident_filters";
+        case K_PCONV: return "igemm_patch_64x64";
         case K_DWCONV: return "dwconv";
         case K_MAXPOOL: return "maxpool";
         case K_AVGPOOL: return "avgpool";
@@ -1481,7 +1495,7 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
     for (size_t i = 0; i < nops; ++i) {
         OpRec &o = t->model.ops[i];
         OpArgs a = o.plan;
-        const bool igemm = is_gemm_kernel(a.kernel_id) || a.kernel_id == K_STEM || a.kernel_id == K_ROWB;
+        const bool igemm = is_gemm_kernel(a.kernel_id) || a.kernel_id == K_STEM || a.kernel_id == K_ROWB || a.kernel_id == K_PCONV;
         if (needs_weights(a.kind)) {
             const uint8_t *src = o.w_host.data();
             if (a.kernel_id == K_STEM) {
@@ -1504,6 +1518,16 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
                                             src + ((size_t)k * a.gemm_k + (size_t)r * a.S * 3 + sc) * es, es);
                             }
                         }
+                src = packed.data();
+            } else if (a.kernel_id == K_PCONV) {
+                // [K][tap][C] -> [n_pad][chunk of 64 channels][tap][64], zero padded rows
+                packed.assign((size_t)a.n_pad * a.k_pad * es, 0);
+                const int ncc = a.C / 64;
+                for (int k = 0; k < a.K; ++k)
+                    for (int cc = 0; cc < ncc; ++cc)
+                        for (int tap = 0; tap < 9; ++tap)
+                            std::memcpy(packed.data() + ((size_t)k * a.k_pad + ((size_t)cc * 9 + tap) * 64) * es,
+                                        src + ((size_t)k * a.gemm_k + (size_t)tap * a.C + cc * 64) * es, (size_t)64 * es);
                 src = packed.data();
             } else if (a.kernel_id == K_ROWB) {
                 // [K][gemm_k] -> [slice][step][channel tile][lane][8]: lane l of a step holds elements 16 * step + 8 * (l / 32)

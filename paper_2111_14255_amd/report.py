@@ -379,7 +379,7 @@ def _family_of(kernel_name):
     m = re.search(r"igemm_kernel<[^,]+, (\d+), (\d+)", kernel_name) or re.match(r"_ZN2mt12igemm_kernelI(?:DF16_|NS_4bf16E)Li(\d+)ELi(\d+)E", kernel_name)
     if m:
         return "igemm_%sx%s" % (m.group(1), m.group(2))
-    for key, fam in (("stem_kernel", "stem_rows"), ("rowb_kernel", "igemm_resident_filters"), ("rowp_kernel", "igemm_resident_filters"), ("pw_direct_kernel", "igemm_pointwise"), ("gemv_kernel", "gemv"), ("dwconv", "dwconv"), ("gap_kernel", "global_avgpool"),
+    for key, fam in (("stem_kernel", "stem_rows"), ("rowb_kernel", "igemm_resident_filters"), ("rowp_kernel", "igemm_resident_filters"), ("pconv_kernel", "igemm_patch_64x64"), ("pw_direct_kernel", "igemm_pointwise"), ("gemv_kernel", "gemv"), ("dwconv", "dwconv"), ("gap_kernel", "global_avgpool"),
                      ("pool", "pool"), ("conv_direct", "conv_direct"), ("lrn_kernel", "lrn"), ("add_kernel", "add")):
         if key in kernel_name:
             return fam

@@ -219,6 +219,32 @@ def test_random_search_on_the_gpu_returns_a_valid_schedule_with_the_same_bits():
         mix.close()
 
 
+def test_stored_record_memory_can_be_replayed_on_the_gpu(tmp_path):
+    # the record memory D of a search (Alg. 1) written to a file, read back, and its leaders profiled again
+    from paper_2111_14255_amd import api
+    cfg = configs.ALL["cfg1"]
+    mix = Mix(cfg.models(), cfg.seed, cfg.input_dist)
+    try:
+        ctx = mix.ctx
+        lens = ctx.lens()
+        outs = [ctx.make_output(t) for t in range(3)]
+        rho, cost, rec = ctx.search(mix.inputs, outs, 3, rounds=2, candidates=3, runs=3, warmup=1, seed=5)
+        path = str(tmp_path / "d.json")
+        api.save_records(path, lens, 3, rec, note="cfg1")
+        lens2, n_stages2, rec2 = api.load_records(path)
+        assert lens2 == lens and n_stages2 == 3 and rec2 == rec
+        rho2, cost2, measured = ctx.replay_records(rec2, 3, mix.inputs, outs, top_k=3, runs=5)
+        distinct = {tuple(tuple(r) for r in m) for m, _ in rec2}
+        assert 1 <= measured <= min(3, len(distinct)) + 1
+        assert rho2 in [r for r, _ in rec2] or rho2 == [[n, n] for n in lens]
+        assert 0 < cost2 < 20 * cost
+        got, _ = mix.run(ctx.schedule(rho2, 3))
+        for t in range(3):
+            assert_close(got[t], mix.oracle()[t], cfg.dtype, "replayed schedule tenant %d" % t)
+    finally:
+        mix.close()
+
+
 def test_tenant_registered_after_a_parallel_issue_run():
     # the issuing thread added for a later tenant must wait for the next run instead of waking for the finished one
     from synth import weights

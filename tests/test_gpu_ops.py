@@ -15,6 +15,7 @@ DIRECT, IG128, IG64, IG16, DW, MAXP, AVGP, GAP, IG128x64, GEMV = range(10)
 PW = 12
 STEM = 13
 ROWB = 14
+PCONV = 15
 
 
 def g_conv(dtype, n, h, w, c, k, r, stride=1, pad=0, act="relu", bn=True, res=False, coff=0, ctot=0):
@@ -93,6 +94,14 @@ CONV_CASES = [
     ("rowb_1x1_c64_n128_two_slices", dict(n=1, h=96, w=96, c=64, k=128, r=1, act="none"), ROWB),
     ("rowb_1x1_c256_n192_three_slices", dict(n=1, h=91, w=93, c=256, k=192, r=1), ROWB),
     ("rowb_concat", dict(n=1, h=96, w=96, c=64, k=64, r=1, coff=64, ctot=192), ROWB),
+    # 3x3 / stride 1 / padding 1 on 64 k channels, 150 or more 64x64 tiles: activations staged as an input patch
+    ("pconv_w56_two_channel_tiles", dict(n=2, h=56, w=56, c=64, k=128, r=3, pad=1), PCONV),
+    ("pconv_w31_res_ragged", dict(n=3, h=27, w=31, c=128, k=256, r=3, pad=1, res=True), PCONV),
+    ("pconv_w14_tiles_span_rows", dict(n=16, h=14, w=14, c=256, k=256, r=3, pad=1, res=True), PCONV),
+    ("pconv_w7_tiles_span_images", dict(n=40, h=7, w=7, c=64, k=320, r=3, pad=1, act="relu6"), PCONV),
+    ("pconv_w112_large_patch", dict(n=1, h=112, w=112, c=64, k=128, r=3, pad=1, act="none", bn=False), PCONV),
+    ("pconv_partial_channel_tile", dict(n=8, h=28, w=28, c=64, k=72, r=3, pad=1), PCONV),
+    ("pconv_concat", dict(n=8, h=28, w=28, c=64, k=128, r=3, pad=1, coff=64, ctot=256), PCONV),
     ("stem_7x7_row_stride_1", dict(n=1, h=20, w=44, c=3, k=64, r=7, stride=(1, 2), pad=3), STEM),
 ]
 

@@ -166,6 +166,28 @@ def lib_playoff(lens, n_stages, recs, top_k, cost):
     return [[best[i * P + j] for j in range(P)] for i in range(n)], bc.value, seen
 
 
+def test_record_memory_round_trips_through_a_file_and_feeds_the_playoff(tmp_path):
+    from paper_2111_14255_amd import api
+    lens = [9, 12]
+    target = [[2, 6], [4, 8]]
+    rho, c, recs = lib_search(lens, 3, 3, 4, 5, B.MT_SEARCH_COORDINATE, _cost(target))
+    path = str(tmp_path / "records.json")
+    api.save_records(path, lens, 3, recs, note="unit test")
+    lens2, n_stages2, recs2 = api.load_records(path)
+    assert (lens2, n_stages2, recs2) == (lens, 3, recs)
+    # the stored memory is all the play-off needs: same winner as on the live records, and as the oracle's rule
+    final = lambda r: _cost(target)(r) + 0.25
+    got = lib_playoff(lens2, n_stages2, recs2, 3, final)
+    assert got[:2] == lib_playoff(lens, 3, recs, 3, final)[:2] == S.playoff(lens, 2, recs, 3, final)[:2]
+    # a file whose matrices do not fit the operator counts is refused
+    import json
+    doc = json.load(open(path))
+    doc["records"][0]["pointers"][0] = [7, 3]
+    json.dump(doc, open(path, "w"))
+    with pytest.raises(ValueError):
+        api.load_records(path)
+
+
 def test_playoff_matches_oracle_and_can_overturn_the_first_measurement():
     lens = [23, 21, 54]
     target = [[5, 11, 17], [3, 9, 20], [10, 30, 50]]
