@@ -64,9 +64,7 @@ namespace {
 // input line nine times through the L1, which bounds it on large maps (64 -> 64 on 56x56 at batch 16 / 128: 12.1 / 70.4 us
 // against 15.0 / 65.7 us on the tile kernel).
 constexpr int ROWB_MIN_PIXELS = 8192, ROWB_MAX_PIXELS_3X3 = 131072;
-#ifndef PCONV_MIN_TILES
-#define PCONV_MIN_TILES 150
-#endif
+constexpr int PCONV_MIN_TILES = 150;
 
 bool needs_weights(int kind) { return kind == MT_CONV || kind == MT_DWCONV || kind == MT_FC; }
 
@@ -139,14 +137,24 @@ void plan_igemm(OpArgs &p, int M, int Kc, int gemm_k) {
         split = cdiv(nkt, per);            // no empty split
     }
     p.split_k = std::max(1, split);
-    if (kid == K_IGEMM_64x64 && p.split_k == 1 && tiles >= PCONV_MIN_TILES && p.kind == MT_CONV && p.groups <= 1 && p.R == 3 && p.S == 3 &&
-        p.sh == 1 && p.sw == 1 && p.ph == 1 && p.pw == 1 && p.C % 64 == 0 && p.K % 8 == 0 && p.y_ct % 8 == 0 && p.y_coff % 8 == 0 &&
-        p.res_ct % 8 == 0 && pconv_patch_pixels(p.W) > 0) {
+    // Only where the 64x64 tile would run unsplit on 150 tiles or more.  On larger problems the patch form is level with
+    // the wide tiles on maps up to 28 pixels wide and loses on wider ones, whose patch leaves room for one workgroup per
+    // compute unit (batch 8, 256 channels on 56x56: 72 against 57 us; 128 channels on 112x112: 90 against 53 us).
+    const bool pconv_size = kid == K_IGEMM_64x64 && p.split_k == 1 && tiles >= PCONV_MIN_TILES;
+    if (pconv_size && p.kind == MT_CONV && p.groups <= 1 && p.R == 3 && p.S == 3 && p.sh == 1 && p.sw == 1 && p.ph == 1 && p.pw == 1 &&
+        p.C % 64 == 0 && p.K % 8 == 0 && p.y_ct % 8 == 0 && p.y_coff % 8 == 0 && p.res_ct % 8 == 0 && pconv_patch_pixels(p.W) > 0) {
         // 3x3 layers that would run on the 64x64 tile unsplit: same tile, activations staged as an input patch
         p.kernel_id = K_PCONV;
         p.wk = 1;
         p.block = 512;
         p.k_pad = gemm_k;
+        p.split_k = 1;
+        p.n_pad = cdiv(Kc, 64) * 64;
+        p.tile_order = 0;
+        make_divisor((uint32_t)p.Q, p.divq_m, p.divq_s1, p.divq_s2);
+        make_divisor((uint32_t)p.P * (uint32_t)p.Q, p.divpq_m, p.divpq_s1, p.divpq_s2);
+        p.grid_x = cdiv(cdiv(M, 64) * (p.n_pad / 64), 8) * 8;
+        return;
     }
     // Which operand each XCD's L2 keeps to itself: consecutive tiles (one XCD) walk the channel tiles of one pixel
     // tile (0) when the activations are the larger operand, the pixel tiles of one channel tile (1) otherwise.
