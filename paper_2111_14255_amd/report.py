@@ -21,7 +21,7 @@
     python -m paper_2111_14255_amd.report fusion --config cfg2
     python -m paper_2111_14255_amd.report barriers --config cfg3
     python -m paper_2111_14255_amd.report layers --config cfg5 --tenant 0
-    python -m paper_2111_14255_amd.report rocprof --config cfg5 --dir gpurun_out/prof_cfg5
+    python -m paper_2111_14255_amd.report rocprof --config cfg5 --dir <directory with the rocprofv3 output>
 """
 import argparse
 import sys
