@@ -115,22 +115,22 @@ inline void make_divisor(uint32_t d, uint32_t &m, uint32_t &s1, uint32_t &s2) {
     s2 = l > 1 ? l - 1 : 0;
 }
 
-// Reduction index of the first-layer kernel (K_STEM): per filter row a run of `dummy` + 3 * S input elements, padded to
+// Reduction index of the first-layer kernel (K_STEM): per filter row a run of `dummy` (1 in the aligned form, else 0) + 3 * S input elements, padded to
 // `gr` groups of 8; two groups per matrix-instruction step.  The packed filter bank is ksteps x (channels / 32) x 64
 // lanes x 8 elements, i.e. the operand fragments in the order the kernel reads them.
 struct StemGeom {
     int dummy, seg, gr, ng, ksteps;
 };
-inline StemGeom stem_geom(int R, int S, int pw) {
+inline StemGeom stem_geom(int R, int S, int form) {
     StemGeom g;
-    g.dummy = (3 * pw) & 1;
+    g.dummy = form == 1 ? 1 : 0;
     g.seg = g.dummy + 3 * S;
     g.gr = (g.seg + 7) / 8;
     g.ng = R * g.gr;
     g.ksteps = (g.ng + 1) / 2;
     return g;
 }
-bool stem_supported(int R, int S, int dummy, int channels);        // is there an instantiation for this window / width
+int stem_form(int R, int S, int sw, int W, int pw, int channels);    // 0: none, 1: aligned form (one dummy element per run), 2: general form
 int launch_stem(const OpArgs &a, void *stream);
 // K_ROWB: waves per workgroup of the instantiation for this window / channel counts, 0 if there is none.  Its packed
 // filter bank is slices x steps x tiles per slice x 64 lanes x 8 elements, a step being 16 consecutive elements of the

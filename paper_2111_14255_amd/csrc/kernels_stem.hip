@@ -1,11 +1,12 @@
-// First convolution of a network (three input channels, even horizontal stride, 2-byte storage) on the gfx950
-// matrix cores, with the activations going from memory straight into the MFMA operand registers.
+// First convolution of a network (three input channels, 2-byte storage, 3x3 or 7x7 window) on the gfx950 matrix
+// cores, with the activations going from memory straight into the MFMA operand registers.
 //
 // With C = 3 the reduction index (r, s, c) of one output pixel is, for every filter row r, one contiguous run of
-// 3 * S elements of an NHWC input row.  The run is widened by DUMMY leading elements so that it starts at a 4-byte
-// address (the start element 3 * (q * sw - pw) - DUMMY is even when sw is even and DUMMY = (3 * pw) % 2; the input
-// width must be even) and padded to whole 16-byte groups of 8 elements; GR groups per filter row, R * GR groups per
-// pixel.  The filter bank is packed on the host in the same index, with zeros at the dummy and padding positions.
+// 3 * S elements of an NHWC input row.  In the aligned form (even horizontal stride, even width) the run is widened by
+// DUMMY leading elements so that it starts at a 4-byte address (the start element 3 * (q * sw - pw) - DUMMY is even
+// with DUMMY = (3 * pw) % 2); in the general form a run may start on an odd element, and a group is then loaded from
+// one element earlier with a fifth dword and shifted down 16 bits in registers.  Runs are padded to whole 16-byte
+// groups of 8 elements; GR groups per filter row, R * GR groups per pixel.  The filter bank is packed on the host in the same index, with zeros at the dummy and padding positions.
 // An MFMA step of v_mfma_f32_32x32x16 takes two groups: lanes 0..31 feed group 2t of their pixel, lanes 32..63 group
 // 2t + 1, each with ONE 16-byte buffer load.  Neighbouring pixels read overlapping addresses, so a wave's load
 // touches a handful of cache lines; there is no im2col tile in LDS and no workgroup barrier in the loop.
@@ -31,8 +32,9 @@ namespace {
 
 constexpr uint32_t STEM_OOB = 0x80000000u;   // beyond any tensor: buffer loads return zeros
 
-template <typename T, int R, int S, int DUMMY, int TN>
+template <typename T, int R, int S, int DUMMY, int TN, bool ALIGNED>
 __global__ void __launch_bounds__(256) stem_kernel(OpArgs a) {
+    static_assert(ALIGNED || DUMMY == 0, "the general form has no dummy element");
     set_wave_priority(a.prio);
     constexpr int SEG = DUMMY + 3 * S;        // elements of one filter row's run
     constexpr int GR = (SEG + 7) / 8;         // 16-byte groups per filter row
@@ -72,13 +74,18 @@ __global__ void __launch_bounds__(256) stem_kernel(OpArgs a) {
         const int p = (int)((t2 + ((rem - t2) >> a.divq_s1)) >> a.divq_s2);
         const int q = (int)(rem - (uint32_t)p * (uint32_t)a.Q);
         const int ih0 = p * a.sh - a.ph, col0 = q * a.sw - a.pw;
-        const int base = (((n * a.H + ih0) * a.W + col0) * 3 - DUMMY) * 2;
+        const int base_e = ((n * a.H + ih0) * a.W + col0) * 3 - DUMMY;      // first element of the run of filter row 0
         const int s_lo = max(0, -col0), s_hi = min(S - 1, a.W - 1 - col0);
         const int e_lo = DUMMY + 3 * s_lo, e_hi = DUMMY + 3 * s_hi + 2;       // inclusive, e_hi <= 31
         const uint32_t upto = e_hi >= 31 ? 0xFFFFFFFFu : ((1u << (e_hi + 1)) - 1u);
         vm = (ok && s_hi >= s_lo) ? (upto & ~((1u << e_lo) - 1u)) : 0u;
+        // ALIGNED: every run starts on an even element, a group is one 16-byte load.  Otherwise a run may start on an odd
+        // element (odd stride, odd width, ...): the load starts one element earlier, takes a fifth dword, and the five
+        // dwords are shifted down by 16 bits in registers.
+        constexpr int SPAN = ALIGNED ? 16 : 20;                               // bytes a group's loads cover
         int off[KS];
         uint32_t live = 0;                    // bit t: the group lies in a row of the image
+        uint32_t oddbits = 0;                 // bit t: the run of that group starts on an odd element
         bool straddles = false;
 #pragma unroll
         for (int t = 0; t < KS; ++t) {
@@ -87,29 +94,49 @@ __global__ void __launch_bounds__(256) stem_kernel(OpArgs a) {
             const int g = h ? (G1 < NG ? G1 % GR : 0) : G0 % GR;
             const bool gok = h ? (G1 < NG) : true;
             const bool v = ok & gok & ((uint32_t)(ih0 + r) < (uint32_t)a.H);
-            const int o = base + r * rowbytes + g * 16;
+            const int e0 = base_e + r * a.W * 3;
+            const int odd = ALIGNED ? 0 : (e0 & 1);
+            const int o = (e0 - odd) * 2 + g * 16;
             off[t] = o;
             live |= v ? (1u << t) : 0u;
-            straddles |= v & (((o < 0) & (o > -16)) | ((o < size) & (o > size - 16)));
+            oddbits |= odd ? (1u << t) : 0u;
+            straddles |= v & (((o < 0) & (o > -SPAN)) | ((o < size) & (o > size - SPAN)));
         }
         if (__builtin_amdgcn_ballot_w64(straddles) == 0) {
 #pragma unroll
             for (int t = 0; t < KS; ++t) {
                 // a group wholly in front of the tensor holds only columns left of the image: zeros are its value
                 const uint32_t voff = (((live >> t) & 1u) && off[t] >= 0) ? (uint32_t)off[t] : STEM_OOB;
-                b[t] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, 0, 0);
+                const u32x4 w = __builtin_amdgcn_raw_buffer_load_b128(rsrc, voff, 0, 0);
+                if constexpr (ALIGNED) {
+                    b[t] = w;
+                } else {
+                    const uint32_t w4 = __builtin_amdgcn_raw_buffer_load_b32(rsrc, voff + 16u, 0, 0);
+                    const uint32_t sh = ((oddbits >> t) & 1u) * 16u;
+                    b[t] = u32x4{__builtin_amdgcn_alignbit(w[1], w[0], sh), __builtin_amdgcn_alignbit(w[2], w[1], sh),
+                                 __builtin_amdgcn_alignbit(w[3], w[2], sh), __builtin_amdgcn_alignbit(w4, w[3], sh)};
+                }
             }
         } else {
+            // first / last rows of the tensor: dword by dword, and a last element that fills half a dword on its own
 #pragma unroll
             for (int t = 0; t < KS; ++t) {
-                uint32_t w[4];
+                uint32_t w[5];
 #pragma unroll
-                for (int d = 0; d < 4; ++d) {
+                for (int d = 0; d < (ALIGNED ? 4 : 5); ++d) {
                     const int od = off[t] + 4 * d;
-                    const uint32_t voff = (((live >> t) & 1u) && od >= 0) ? (uint32_t)od : STEM_OOB;
-                    w[d] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, voff, 0, 0);
+                    const bool in = ((live >> t) & 1u) && od >= 0;
+                    const uint32_t voff = in ? (uint32_t)od : STEM_OOB;
+                    if (!ALIGNED && in && od + 2 == size) w[d] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(rsrc, voff, 0, 0);
+                    else w[d] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, voff, 0, 0);
                 }
-                b[t] = u32x4{w[0], w[1], w[2], w[3]};
+                if constexpr (ALIGNED) {
+                    b[t] = u32x4{w[0], w[1], w[2], w[3]};
+                } else {
+                    const uint32_t sh = ((oddbits >> t) & 1u) * 16u;
+                    b[t] = u32x4{__builtin_amdgcn_alignbit(w[1], w[0], sh), __builtin_amdgcn_alignbit(w[2], w[1], sh),
+                                 __builtin_amdgcn_alignbit(w[3], w[2], sh), __builtin_amdgcn_alignbit(w[4], w[3], sh)};
+                }
             }
         }
     };
@@ -206,20 +233,31 @@ __global__ void __launch_bounds__(256) stem_kernel(OpArgs a) {
 
 }  // namespace
 
-bool stem_supported(int R, int S, int dummy, int channels) {
-    const bool shape = dummy == 1 && ((R == 7 && S == 7) || (R == 3 && S == 3));
-    return shape && (channels == 32 || channels == 64);
+// 0: no instantiation; 1: aligned form (even horizontal stride, even width, odd 3 * pad: with one dummy element every run
+// starts on a 4-byte address); 2: general form (runs may start on an odd element).
+int stem_form(int R, int S, int sw, int W, int pw, int channels) {
+    if (!((R == 7 && S == 7) || (R == 3 && S == 3)) || !(channels == 32 || channels == 64)) return 0;
+    return (sw % 2 == 0 && W % 2 == 0 && ((3 * pw) & 1)) ? 1 : 2;
 }
 
 int launch_stem(const OpArgs &a, void *stream) {
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid(a.grid_x), block(256);
     const int tn = a.n_pad / 32;
+    const int form = stem_form(a.R, a.S, a.sw, a.W, a.pw, a.n_pad);
+    if (form == 0) return (int)hipErrorInvalidValue;
     auto go = [&]<typename T>() {
-        if (a.R == 7 && tn == 2) hipLaunchKernelGGL((stem_kernel<T, 7, 7, 1, 2>), grid, block, 0, st, a);
-        else if (a.R == 7) hipLaunchKernelGGL((stem_kernel<T, 7, 7, 1, 1>), grid, block, 0, st, a);
-        else if (tn == 2) hipLaunchKernelGGL((stem_kernel<T, 3, 3, 1, 2>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((stem_kernel<T, 3, 3, 1, 1>), grid, block, 0, st, a);
+        if (form == 1) {
+            if (a.R == 7 && tn == 2) hipLaunchKernelGGL((stem_kernel<T, 7, 7, 1, 2, true>), grid, block, 0, st, a);
+            else if (a.R == 7) hipLaunchKernelGGL((stem_kernel<T, 7, 7, 1, 1, true>), grid, block, 0, st, a);
+            else if (tn == 2) hipLaunchKernelGGL((stem_kernel<T, 3, 3, 1, 2, true>), grid, block, 0, st, a);
+            else hipLaunchKernelGGL((stem_kernel<T, 3, 3, 1, 1, true>), grid, block, 0, st, a);
+        } else {
+            if (a.R == 7 && tn == 2) hipLaunchKernelGGL((stem_kernel<T, 7, 7, 0, 2, false>), grid, block, 0, st, a);
+            else if (a.R == 7) hipLaunchKernelGGL((stem_kernel<T, 7, 7, 0, 1, false>), grid, block, 0, st, a);
+            else if (tn == 2) hipLaunchKernelGGL((stem_kernel<T, 3, 3, 0, 2, false>), grid, block, 0, st, a);
+            else hipLaunchKernelGGL((stem_kernel<T, 3, 3, 0, 1, false>), grid, block, 0, st, a);
+        }
     };
     if (a.dtype == MT_F16) go.template operator()<f16>();
     else go.template operator()<bf16>();

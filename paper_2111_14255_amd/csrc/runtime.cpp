@@ -244,9 +244,10 @@ int32_t finalize_model(mt_model *m) {
                     if (d.kind == MT_FC) { p.H = p.W = 1; p.C = gemm_k; p.x_ct = gemm_k; p.R = p.S = 1; }
                     // im2col gather mode: 2 = tile inside one tap (C % 64 == 0, at most 64 taps), 1 = 16-byte chunks, 0 = element-wise
                     p.vec_a = (p.C % IGEMM_BK == 0 && p.R * p.S <= 64) ? 2 : (p.C % 8 == 0) ? 1 : 0;
-                    const StemGeom sg = stem_geom(R, S, pw);
-                    if (d.kind == MT_CONV && groups == 1 && in.c == 3 && sw % 2 == 0 && in.w % 2 == 0 && res_ct == 0 &&
-                        ctot % 8 == 0 && d.out_c_offset % 8 == 0 && stem_supported(R, S, sg.dummy, o.out_c)) {
+                    const int sform = (d.kind == MT_CONV && groups == 1 && in.c == 3 && res_ct == 0 && ctot % 8 == 0 && d.out_c_offset % 8 == 0)
+                                          ? stem_form(R, S, sw, in.w, pw, o.out_c) : 0;
+                    const StemGeom sg = stem_geom(R, S, sform);
+                    if (sform > 0) {
                         // first layer: the im2col rows are contiguous runs of an input row and go straight into the
                         // MFMA operand registers.  Measured on MI355X (ResNet-50 stem, bf16, batch 1 / 16 / 128): 4.8 / 12.6 /
                         // 58 us against 7 / 45.7 / 303 us with the element-wise gather of the tile kernel.
@@ -1509,7 +1510,7 @@ int32_t mt_register(mt_ctx *ctx, const mt_model *m, void *device_arena, size_t a
             if (a.kernel_id == K_STEM) {
                 // [K][R][S][3] -> [step][channel tile][lane][8]: the matrix-instruction fragments in reading order, zeros at
                 // the dummy and padding positions of every filter row's run
-                const StemGeom sg = stem_geom(a.R, a.S, a.pw);
+                const StemGeom sg = stem_geom(a.R, a.S, stem_form(a.R, a.S, a.sw, a.W, a.pw, a.n_pad));
                 const int tn = a.n_pad / 32;
                 packed.assign((size_t)sg.ksteps * tn * 64 * 8 * es, 0);
                 for (int t = 0; t < sg.ksteps; ++t)

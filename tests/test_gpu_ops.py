@@ -45,7 +45,7 @@ CONV_CASES = [
     ("ig64_7x1", dict(n=1, h=17, w=17, c=32, k=48, r=(7, 1), pad=(3, 0)), IG64),
     ("ig64_5x5", dict(n=1, h=12, w=12, c=8, k=64, r=5, pad=2), IG64),
     ("ig64_splitk", dict(n=1, h=7, w=7, c=256, k=128, r=3, pad=1, res=True), IG64),
-    ("ig64_first_layer_7x7s2_odd_width", dict(n=1, h=41, w=41, c=3, k=64, r=7, stride=2, pad=3), IG64),
+    ("ig64_first_layer_5x5", dict(n=1, h=41, w=41, c=3, k=64, r=5, stride=2, pad=2), IG64),
     ("ig64_first_layer_11x11s4", dict(n=1, h=67, w=67, c=3, k=96, r=11, stride=4), IG64),
     ("ig64_c12_scalar", dict(n=1, h=9, w=9, c=12, k=20, r=3, pad=1, act="none"), IG64),
     ("ig64_concat_unaligned", dict(n=1, h=8, w=8, c=16, k=10, r=3, pad=1, coff=3, ctot=18), IG64),
@@ -102,6 +102,14 @@ CONV_CASES = [
     ("pconv_w112_large_patch", dict(n=1, h=112, w=112, c=64, k=128, r=3, pad=1, act="none", bn=False), PCONV),
     ("pconv_partial_channel_tile", dict(n=8, h=28, w=28, c=64, k=72, r=3, pad=1), PCONV),
     ("pconv_concat", dict(n=8, h=28, w=28, c=64, k=128, r=3, pad=1, coff=64, ctot=256), PCONV),
+    # general form: runs that start on odd elements (odd stride, odd width, even 3 * pad)
+    ("stem_general_3x3_s1_vgg_like", dict(n=2, h=30, w=30, c=3, k=64, r=3, pad=1), STEM),
+    ("stem_general_3x3_s2_odd_map_ends_on_half_dword", dict(n=1, h=35, w=35, c=3, k=32, r=3, stride=2), STEM),
+    ("stem_general_7x7_odd_width", dict(n=3, h=41, w=41, c=3, k=64, r=7, stride=2, pad=3), STEM),
+    ("stem_general_3x3_s1_odd_width_all_border", dict(n=3, h=3, w=5, c=3, k=32, r=3, pad=1, act="none", bn=False), STEM),
+    ("stem_general_7x7_s1_even_pad", dict(n=1, h=36, w=38, c=3, k=32, r=7, stride=1, pad=2), STEM),
+    ("stem_general_3x3_224", dict(n=1, h=224, w=224, c=3, k=64, r=3, pad=1), STEM),
+    ("stem_general_3x3_s2_299", dict(n=1, h=299, w=299, c=3, k=32, r=3, stride=2), STEM),
     ("stem_7x7_row_stride_1", dict(n=1, h=20, w=44, c=3, k=64, r=7, stride=(1, 2), pad=3), STEM),
 ]
 
@@ -114,7 +122,7 @@ def _expand_cases():
         if kid != IG64:
             out.append((name, kw, kid))
             continue
-        if name == "ig64_first_layer_7x7s2_odd_width":
+        if name == "ig64_first_layer_5x5":
             out.append((name + "_small", kw, IG16))
             out.append((name + "_big", dict(kw, h=139, w=139), IG64))
             continue
@@ -413,7 +421,8 @@ POOL_BLOCKS = [
     ("ragged_6x10_c24_k40", 3, 6, 10, 24, 40, 3, 1, 1, "none", True),
     ("pointwise_stride2_conv_large_map", 2, 140, 100, 32, 72, 1, 2, 0, "relu", True),
     ("pointwise_small_map_direct_operand_kernel_not_fused", 2, 20, 12, 32, 72, 1, 2, 0, "relu", False),
-    ("first_layer_c3_element_gather", 1, 32, 32, 3, 64, 3, 1, 1, "relu", True),
+    ("first_layer_c3_element_gather", 1, 32, 32, 3, 48, 3, 1, 1, "relu", True),
+    ("first_layer_kernel_is_not_fused", 1, 32, 32, 3, 64, 3, 1, 1, "relu", False),
     ("odd_map_15x15_not_fused", 1, 15, 15, 64, 64, 3, 1, 1, "relu", False),
     ("k_not_multiple_of_8_not_fused", 1, 16, 16, 64, 36, 3, 1, 1, "relu", False),
 ]
