@@ -170,6 +170,39 @@ def test_conv_igemm(name, kw, kid, dtype):
         mix.close()
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("name,kw", [
+    ("aligned_7x7", dict(n=2, h=20, w=24, c=3, k=64, r=7, stride=2, pad=3)),
+    ("aligned_3x3", dict(n=1, h=18, w=16, c=3, k=32, r=3, stride=2, pad=1)),
+    ("general_3x3", dict(n=1, h=12, w=13, c=3, k=32, r=3, pad=1)),
+    ("general_7x7_odd_width", dict(n=1, h=21, w=23, c=3, k=64, r=7, stride=2, pad=3)),
+])
+def test_first_layer_masks_keep_non_finite_pixels_out_of_foreign_windows(name, kw, dtype):
+    """The first-layer kernel loads whole 16-byte groups, which also hold elements of neighbouring pixels (the dummy
+    in front of a run, the padding behind it, columns beyond the border).  Their filter weights are zero, but only
+    clearing them in registers keeps a NaN next to a window out of that window's output."""
+    spec = g_conv(dtype, act="none", bn=False, **kw)
+    mix = Mix([spec], seed=5)
+    try:
+        assert mix.ctx.op_info(0, 0).kernel_id == STEM
+        x = mix.x[0]
+        h, w = kw["h"], kw["w"]
+        for (r, c) in ((5, 7), (9, 0), (3, w - 1), (h - 1, w // 2), (0, 1)):
+            x[0, r, c, :] = np.nan
+        mix.inputs[0] = mix.ctx.make_input(0, x)
+        mix._oracle = None
+        got, _ = mix.run(mix.ctx.sequential())
+        ref = mix.oracle()[0]
+        bad = ~np.isfinite(ref)
+        assert bad.any() and not bad.all()
+        assert np.array_equal(~np.isfinite(got[0]), bad), name
+        scale = float(np.abs(ref[~bad]).max())
+        err = float(np.abs(got[0][~bad].astype(np.float64) - ref[~bad].astype(np.float64)).max())
+        assert err <= 2e-2 * scale, (name, err, scale)
+    finally:
+        mix.close()
+
+
 def g_fc(dtype, n, h, w, c, k, act="none"):
     g = GraphBuilder("t", dtype, n, h, w, c)
     g.fc(0, k, act=act)
