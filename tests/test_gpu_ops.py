@@ -203,6 +203,32 @@ def test_first_layer_masks_keep_non_finite_pixels_out_of_foreign_windows(name, k
         mix.close()
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_patch_staged_kernel_masks_taps_that_leave_the_image(dtype):
+    """In the flattened patch the pixel left of column 0 is the last pixel of the row above, and the row above row 0
+    is the last row of the image before: a NaN there must not reach windows that do not contain it."""
+    kw = dict(n=16, h=14, w=14, c=64, k=256, r=3, pad=1)
+    spec = g_conv(dtype, act="none", bn=False, **kw)
+    mix = Mix([spec], seed=6)
+    try:
+        assert mix.ctx.op_info(0, 0).kernel_id == PCONV
+        x = mix.x[0]
+        for (n, r, c) in ((0, 3, 13), (1, 13, 5), (2, 0, 0), (5, 13, 13), (6, 0, 7), (9, 6, 0)):
+            x[n, r, c, 17] = np.nan
+        mix.inputs[0] = mix.ctx.make_input(0, x)
+        mix._oracle = None
+        got, _ = mix.run(mix.ctx.sequential())
+        ref = mix.oracle()[0]
+        bad = ~np.isfinite(ref)
+        assert bad.any() and not bad.all()
+        assert np.array_equal(~np.isfinite(got[0]), bad)
+        scale = float(np.abs(ref[~bad]).max())
+        err = float(np.abs(got[0][~bad].astype(np.float64) - ref[~bad].astype(np.float64)).max())
+        assert err <= 2e-2 * scale, (err, scale)
+    finally:
+        mix.close()
+
+
 def g_fc(dtype, n, h, w, c, k, act="none"):
     g = GraphBuilder("t", dtype, n, h, w, c)
     g.fc(0, k, act=act)
