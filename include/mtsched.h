@@ -185,6 +185,13 @@ int32_t mt_probe_barrier_cost(mt_ctx *ctx, int32_t n_streams, int32_t kind, int3
  * stream waits for the stream's completion event (the pattern of a stage).  us_per_launch: host [n_streams]. */
 int32_t mt_probe_dispatch_latency(mt_ctx *ctx, int32_t n_streams, int32_t share, int32_t n_launches, float *us_per_launch);
 
+/* Diagnostic: which streams of this process can run side by side.  Creates n_streams unmasked streams (2 .. 32; they are
+ * destroyed before the call returns) and measures the mean time per launch of `n_launches` (1 .. 256) dependent
+ * one-workgroup kernels on each stream alone (single_us: host [n_streams]) and, for every pair, the mean time of a
+ * round in which both streams launch one such kernel (pair_us: host [n_streams * n_streams], symmetric, the diagonal
+ * repeats single_us).  A pair that takes about two single launches per round is served one stream at a time. */
+int32_t mt_probe_stream_conflicts(mt_ctx *ctx, int32_t n_streams, int32_t n_launches, float *single_us, float *pair_us);
+
 /* Diagnostic: what the chip sustains on a register-only loop of 32x32x16 matrix instructions (dtype MT_F16 or MT_BF16;
  * two workgroups of four waves per compute unit, four independent accumulators per wave, 4 * iters instructions per
  * wave; iters 1 .. 2^20).  tflops: host scalar, 2 * 32 * 32 * 16 flops per instruction over the kernel's event time.

@@ -87,6 +87,7 @@ SIGNATURES = {
     "mt_destroy": (_i32, [_vp]),
     "mt_get_device_info": (_i32, [_vp, C.POINTER(mt_device_info)]),
     "mt_probe_dispatch_latency": (_i32, [_vp, _i32, _i32, _i32, _pf]),
+    "mt_probe_stream_conflicts": (_i32, [_vp, _i32, _i32, _pf, _pf]),
     "mt_probe_barrier_cost": (_i32, [_vp, _i32, _i32, _i32, _pf]),
     "mt_probe_cu_mask": (_i32, [_vp, _i32, _i32, _i32, C.POINTER(C.c_uint32)]),
     "mt_probe_peak_mfma": (_i32, [_vp, _i32, _i32, _pf]),

@@ -605,14 +605,23 @@ int32_t purge_idle_streams(mt_ctx *ctx) {
 
 // Plain streams belong to the process, not to a context: the runtime deals its hardware queues to the plain streams
 // of the process in creation order, so every plain stream a context created and destroyed moved the turn of the next
-// one, and after a few contexts the tenant streams of a new context shared queues (measured: the five-tenant mix
-// all-concurrent 1.79 ms as the seventh context of a process against 1.46 ms as the first).  One main stream and one
-// stream per tenant index exist per device, created on first use, timed and parked as described in get_stream, and
-// never destroyed; contexts of one process therefore share them (their work is ordered, not wrong).
+// one.  One main stream and one stream per tenant index exist per device, created on first use and never destroyed;
+// contexts of one process therefore share them (their work is ordered, not wrong).
+//
+// Which streams can run side by side: the hardware queues behind the streams are served by four dispatch pipes, and
+// two queues of one pipe take turns (measured with chains of one-workgroup kernels: a pair of streams takes either one
+// launch time per round, 10 us, or two, 20 us, nothing in between; the relation is transitive and twelve streams fall
+// into four classes of sizes like 4 / 4 / 2 / 2, in no fixed order of creation).  A new plain stream is therefore
+// classified by running it beside one representative of every class found so far, and tenant index i gets a stream
+// of class i % 4: the streams of up to four tenants run side by side, those of eight are spread two per pipe.  Streams
+// of a class nobody asked for yet wait in `spare`.
+constexpr int N_PIPES = 4;
 struct PlainPool {
     hipStream_t main_stream = nullptr;
     hipStream_t tenant[MT_MAX_TENANTS] = {};
     std::vector<hipStream_t> parked;
+    std::vector<hipStream_t> rep;                   // one stream of every class, in the order the classes were found
+    std::vector<std::vector<hipStream_t>> spare;    // per class: classified streams not handed out yet
 };
 PlainPool &plain_pool(int device) {
     static std::map<int, PlainPool> pools;
@@ -651,38 +660,77 @@ void return_signal_word(int device, uint32_t *w) {
     p.idle[device].push_back(w);
 }
 
-// A new stream for `share` units starting at first_cu (0 = all units: a plain stream), timed; slow ones are parked.
+// Class of a new plain stream: the first class whose representative it cannot run beside (a round of both takes more
+// than 1.5 launch times), else a new class.
+int32_t classify_stream(mt_ctx *ctx, PlainPool &pool, hipStream_t s, int *cls) {
+    float single = 0.f;
+    int32_t rc = dispatch_latency_us(ctx, s, ctx->probe_buf, 8, &single);
+    if (rc != MT_OK) return rc;
+    if (ctx->best_dispatch_us == 0.f || single < ctx->best_dispatch_us) ctx->best_dispatch_us = single;
+    for (size_t c = 0; c < pool.rep.size(); ++c) {
+        float us = 0.f, host_us = 0.f;
+        rc = concurrent_latency_us(ctx, {pool.rep[c], s}, 8, &us, &host_us);
+        if (rc != MT_OK) return rc;
+        if (us > 1.5f * single) { *cls = (int)c; return MT_OK; }
+    }
+    *cls = (int)pool.rep.size();
+    pool.rep.push_back(s);
+    pool.spare.emplace_back();
+    return MT_OK;
+}
+
+// A plain stream of class `want` (of any class after 16 creations that did not produce one).
+int32_t plain_stream_of_class(mt_ctx *ctx, int want, hipStream_t *out) {
+    PlainPool &pool = plain_pool(ctx->device);
+    if (!ctx->probe_buf) HIP_TRY(hipMalloc((void **)&ctx->probe_buf, 256));
+    for (int attempt = 0; attempt <= 16; ++attempt) {
+        if (want < (int)pool.spare.size() && !pool.spare[want].empty()) {
+            *out = pool.spare[want].back();
+            pool.spare[want].pop_back();
+            return MT_OK;
+        }
+        if (attempt == 16) break;
+        hipStream_t s = nullptr;
+        HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+        int cls = 0;
+        int32_t rc = classify_stream(ctx, pool, s, &cls);
+        if (rc != MT_OK) { (void)hipStreamDestroy(s); return rc; }
+        pool.spare[cls].push_back(s);
+    }
+    for (auto &v : pool.spare)
+        if (!v.empty()) {
+            *out = v.back();
+            v.pop_back();
+            return MT_OK;
+        }
+    return fail(MT_ERR_HIP, "no plain stream could be created");
+}
+
+// A new stream for `share` units starting at first_cu (0 = all units: a plain stream of the class of the tenant index).
 int32_t make_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_t *out) {
-    hipStream_t s = nullptr;
-    const int cus = ctx->prop.multiProcessorCount;
-    std::vector<uint32_t> mask((cus + 31) / 32, 0u);
     // A stream over all units is a plain stream on one of the runtime's own hardware queues (GPU_MAX_HW_QUEUES of them,
     // dealt to the plain streams of the process in turn).  Giving it a full CU mask, and with it a queue of its own,
     // was measured and dropped: after the queue creations and destructions of a share search such streams sometimes
-    // ran three tenants in 0.9 ms instead of 0.32 ms, the timing below not showing it.
+    // ran three tenants in 0.9 ms instead of 0.32 ms.
+    if (share == 0) return plain_stream_of_class(ctx, tenant % N_PIPES, out);
+    hipStream_t s = nullptr;
+    const int cus = ctx->prop.multiProcessorCount;
+    std::vector<uint32_t> mask((cus + 31) / 32, 0u);
     for (int j = 0; j < share; ++j) {
         const int cu = (first_cu + j) % cus;
         mask[cu / 32] |= 1u << (cu % 32);
     }
-    // On MI355X roughly one in four hardware queues dispatches dependent kernels about 1.5x slower than the others
-    // (measured: 16-19 us against 12 us per launch of a fixed probe kernel, in creation order 1, 5, 9, ... for masked
-    // streams; a tenant on such a queue slows the whole pass: three tenants on plain streams took 0.89 ms with one of
-    // them on the slow queue against 0.33 ms without).  A new stream is therefore timed, and a slow one is parked
-    // (kept alive so that its queue, or its turn among the runtime's queues, stays taken) and replaced by the next one.
+    // A masked stream owns a hardware queue.  It is timed, and one that dispatches dependent kernels more than 1.2
+    // times slower than the best stream seen is parked (kept alive so that its queue stays taken) and replaced.
     if (!ctx->probe_buf) HIP_TRY(hipMalloc((void **)&ctx->probe_buf, 256));
-    PlainPool &pool = plain_pool(ctx->device);
     for (int attempt = 0;; ++attempt) {
-        if (share == 0) HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
-        else HIP_TRY(hipExtStreamCreateWithCUMask(&s, (uint32_t)mask.size(), mask.data()));
+        HIP_TRY(hipExtStreamCreateWithCUMask(&s, (uint32_t)mask.size(), mask.data()));
         float us = 0.f;
         int32_t rc = dispatch_latency_us(ctx, s, ctx->probe_buf, 12, &us);
         if (rc != MT_OK) { (void)hipStreamDestroy(s); return rc; }
         if (ctx->best_dispatch_us == 0.f || us < ctx->best_dispatch_us) ctx->best_dispatch_us = us;
         if (us <= 1.2f * ctx->best_dispatch_us || attempt == 3) break;
-        // A parked plain stream is never released: after one was destroyed, schedules that mixed plain and masked
-        // streams ran in 0.95 ms instead of 0.35 ms.
-        if (share == 0) pool.parked.push_back(s);
-        else ctx->parked_streams.push_back(s);
+        ctx->parked_streams.push_back(s);
     }
     *out = s;
     return MT_OK;
@@ -1108,7 +1156,7 @@ int32_t mt_probe_cu_mask(mt_ctx *ctx, int32_t share, int32_t first_cu, int32_t n
 
 namespace {
 // Mean time per launch of n dependent one-workgroup kernels on `st`, measured the way a stage runs: the main stream
-// records a start event, the stream waits for it, runs, records its done event, the main stream waits for that.
+// records a start event, the stream waits for it, runs, records its done event, the host waits for that.
 int32_t dispatch_latency_us(mt_ctx *ctx, hipStream_t st, uint32_t *scratch, int n, float *us) {
     for (int rep = 0; rep < 2; ++rep) {          // first pass warms up
         HIP_TRY(hipEventRecord(ctx->ev_prof[0], ctx->main_stream));
@@ -1118,12 +1166,10 @@ int32_t dispatch_latency_us(mt_ctx *ctx, hipStream_t st, uint32_t *scratch, int 
             if (rc) return fail(MT_ERR_HIP, std::string("probe launch: ") + hipGetErrorString((hipError_t)rc));
         }
         HIP_TRY(hipEventRecord(ctx->ev_done[0][0], st));
-        HIP_TRY(hipStreamWaitEvent(ctx->main_stream, ctx->ev_done[0][0], 0));
-        HIP_TRY(hipEventRecord(ctx->ev_prof[1], ctx->main_stream));
-        HIP_TRY(hipEventSynchronize(ctx->ev_prof[1]));
+        HIP_TRY(hipEventSynchronize(ctx->ev_done[0][0]));
     }
     float ms = 0;
-    HIP_TRY(hipEventElapsedTime(&ms, ctx->ev_prof[0], ctx->ev_prof[1]));
+    HIP_TRY(hipEventElapsedTime(&ms, ctx->ev_prof[0], ctx->ev_done[0][0]));
     *us = ms * 1e3f / n;
     return MT_OK;
 }
@@ -1133,7 +1179,9 @@ int32_t concurrent_latency_us(mt_ctx *ctx, const std::vector<hipStream_t> &strea
     const int m = (int)streams.size();
     if (m < 1 || m > MT_MAX_TENANTS) return fail(MT_ERR_INVALID_ARG, "stream count out of range");
     if (!ctx->probe_buf) HIP_TRY(hipMalloc((void **)&ctx->probe_buf, 256));
-    float host = 0.f;
+    float host = 0.f, worst = 0.f;
+    // Measured the way mt_run measures a stage: the main stream only records the start, every stream records its own
+    // end, the host waits for those; no queue sits in a wait for another queue while the chains run.
     for (int rep = 0; rep < 2; ++rep) {
         HIP_TRY(hipEventRecord(ctx->ev_prof[0], ctx->main_stream));
         for (int j = 0; j < m; ++j) HIP_TRY(hipStreamWaitEvent(streams[j], ctx->ev_prof[0], 0));
@@ -1144,16 +1192,16 @@ int32_t concurrent_latency_us(mt_ctx *ctx, const std::vector<hipStream_t> &strea
                 if (rc) return fail(MT_ERR_HIP, std::string("probe launch: ") + hipGetErrorString((hipError_t)rc));
             }
         host = std::chrono::duration<float, std::micro>(std::chrono::steady_clock::now() - t0).count() / n;
+        for (int j = 0; j < m; ++j) HIP_TRY(hipEventRecord(ctx->ev_done[0][j], streams[j]));
+        worst = 0.f;
         for (int j = 0; j < m; ++j) {
-            HIP_TRY(hipEventRecord(ctx->ev_done[0][j], streams[j]));
-            HIP_TRY(hipStreamWaitEvent(ctx->main_stream, ctx->ev_done[0][j], 0));
+            HIP_TRY(hipEventSynchronize(ctx->ev_done[0][j]));
+            float ms = 0.f;
+            HIP_TRY(hipEventElapsedTime(&ms, ctx->ev_prof[0], ctx->ev_done[0][j]));
+            worst = std::max(worst, ms);
         }
-        HIP_TRY(hipEventRecord(ctx->ev_prof[1], ctx->main_stream));
-        HIP_TRY(hipEventSynchronize(ctx->ev_prof[1]));
     }
-    float ms = 0;
-    HIP_TRY(hipEventElapsedTime(&ms, ctx->ev_prof[0], ctx->ev_prof[1]));
-    *us = ms * 1e3f / n;
+    *us = worst * 1e3f / n;
     *host_us = host;
     return MT_OK;
 }
@@ -1185,6 +1233,31 @@ int32_t mt_probe_dispatch_latency(mt_ctx *ctx, int32_t n_streams, int32_t share,
     (void)hipDeviceSynchronize();
     for (hipStream_t st : streams) (void)hipStreamDestroy(st);
     (void)hipFree(dev);
+    return rc;
+}
+
+int32_t mt_probe_stream_conflicts(mt_ctx *ctx, int32_t n_streams, int32_t n_launches, float *single_us, float *pair_us) {
+    if (!ctx || !single_us || !pair_us) return fail(MT_ERR_INVALID_ARG, "NULL argument");
+    if (n_streams < 2 || n_streams > 32 || n_launches < 1 || n_launches > 256) return fail(MT_ERR_INVALID_ARG, "argument out of range");
+    HIP_TRY(hipSetDevice(ctx->device));
+    if (!ctx->probe_buf) HIP_TRY(hipMalloc((void **)&ctx->probe_buf, 256));
+    std::vector<hipStream_t> streams;
+    int32_t rc = MT_OK;
+    for (int i = 0; i < n_streams && rc == MT_OK; ++i) {
+        hipStream_t st = nullptr;
+        hipError_t e = hipStreamCreateWithFlags(&st, hipStreamNonBlocking);
+        if (e != hipSuccess) { rc = fail(MT_ERR_HIP, std::string("stream create: ") + hipGetErrorString(e)); break; }
+        streams.push_back(st);
+        rc = dispatch_latency_us(ctx, st, ctx->probe_buf, n_launches, &single_us[i]);
+    }
+    for (int i = 0; i < n_streams && rc == MT_OK; ++i)
+        for (int j = 0; j < n_streams && rc == MT_OK; ++j) {
+            if (j <= i) { pair_us[i * n_streams + j] = j == i ? single_us[i] : pair_us[j * n_streams + i]; continue; }
+            float host_us = 0.f;
+            rc = concurrent_latency_us(ctx, {streams[i], streams[j]}, n_launches, &pair_us[i * n_streams + j], &host_us);
+        }
+    (void)hipDeviceSynchronize();
+    for (hipStream_t st : streams) (void)hipStreamDestroy(st);
     return rc;
 }
 
@@ -1818,7 +1891,11 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
     // time.  Bad: a round takes more than 1.8 single-stream launches per started group of four streams, twice in a row,
     // and the issuing thread's own launch time does not explain it.  The stream whose removal helps most is then parked
     // and replaced (a masked one only if no other schedule holds it), up to three times.
-    if (!(flags & MT_SCHED_GRAPH)) {
+    // (Plain streams are placed by class when they are created, see PlainPool; the check is for sets with masked streams.)
+    bool any_masked = false;
+    for (const auto &row : acq)
+        for (int i = 0; i < n_tenants; ++i) any_masked = any_masked || row[i].share != 0;
+    if (!(flags & MT_SCHED_GRAPH) && any_masked) {
         struct Used { int row, idx; };
         std::vector<Used> used;
         std::vector<hipStream_t> all;

@@ -76,3 +76,34 @@ def test_barrier_cost_probe_every_kind():
                 B.check(ctx.lib.mt_probe_barrier_cost(ctx.h, bad[0], bad[1], bad[2], C.byref(C.c_float())))
     finally:
         ctx.close()
+
+
+def test_stream_conflict_probe_and_tenant_streams_side_by_side():
+    """The pair probe returns a symmetric table whose entries are one or about two launch times, and the streams the
+    runtime hands to tenant indices 0 .. 3 run side by side: four single-operator chains on four streams take far less
+    than four times one chain."""
+    ctx = api.Context(0)
+    try:
+        n = 6
+        single = (C.c_float * n)()
+        pair = (C.c_float * (n * n))()
+        print("stream conflict probe", flush=True)
+        B.check(ctx.lib.mt_probe_stream_conflicts(ctx.h, n, 16, single, pair))
+        lo = min(single)
+        assert 1.0 < lo < 200.0
+        for i in range(n):
+            assert pair[i * n + i] == single[i]
+            for j in range(n):
+                assert pair[i * n + j] == pair[j * n + i]
+                assert 0.7 * lo < pair[i * n + j] < 4.0 * lo
+        for bad in ((1, 16), (33, 16), (4, 0), (4, 257)):
+            with pytest.raises(B.MtError):
+                B.check(ctx.lib.mt_probe_stream_conflicts(ctx.h, bad[0], bad[1], single, pair))
+        # kind 0 of the barrier probe: rounds of one short kernel per tenant stream, no barrier
+        one, four = C.c_float(), C.c_float()
+        B.check(ctx.lib.mt_probe_barrier_cost(ctx.h, 1, 0, 64, C.byref(one)))
+        B.check(ctx.lib.mt_probe_barrier_cost(ctx.h, 4, 0, 64, C.byref(four)))
+        print("round of 1 stream %.1f us, of 4 streams %.1f us" % (one.value, four.value), flush=True)
+        assert four.value < 2.5 * one.value
+    finally:
+        ctx.close()
