@@ -1883,15 +1883,11 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
             if (rc != MT_OK) { release_streams(s.get()); return rc; }
         }
     }
-    // The streams this schedule launches on are checked together: now and then a queue (masked, or the runtime's own
-    // for a plain stream) passes the timing of make_stream alone but cannot run beside the others, and a
-    // ResNet-18 + VGG-16 + MobileNetV2 pass then takes 1.0-1.6 ms instead of 0.4 ms.  Every stream launches one probe
-    // kernel per round: up to four streams run side by side (14-16.5 us per round, one kernel taking 11-12 us), a bad
-    // set of three takes 27-30 us, and five streams always take 26-30 us, as if four queues at most were served at a
-    // time.  Bad: a round takes more than 1.8 single-stream launches per started group of four streams, twice in a row,
-    // and the issuing thread's own launch time does not explain it.  The stream whose removal helps most is then parked
-    // and replaced (a masked one only if no other schedule holds it), up to three times.
-    // (Plain streams are placed by class when they are created, see PlainPool; the check is for sets with masked streams.)
+    // A schedule that uses masked streams checks its streams together (plain streams are placed by dispatch pipe when
+    // they are created, see PlainPool; masked ones are not).  Every stream launches one probe kernel per round; a round
+    // of more than 1.8 single-stream launches per started group of four streams, twice in a row and not explained by
+    // the issuing thread's own launch time, means that streams of the set take turns on one pipe.  The stream whose
+    // removal helps most is then parked and replaced (a masked one only if no other schedule holds it), up to three times.
     bool any_masked = false;
     for (const auto &row : acq)
         for (int i = 0; i < n_tenants; ++i) any_masked = any_masked || row[i].share != 0;
@@ -2302,8 +2298,8 @@ int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *in
         if (pcf.rc != MT_OK) return pcf.rc;
         if (rc != MT_OK) return rc;
     }
-    // Streams in use at a time, the same number in every stage: on this machine about four queues are served at once
-    // (the main stream is one of them), so with five tenants or more fewer streams than tenants can be faster.
+    // Streams in use at a time, the same number in every stage: the queues of this machine are served by four dispatch
+    // pipes (see PlainPool), so with five tenants or more fewer streams than tenants can be faster.
     int32_t conc[MT_MAX_STAGES];
     for (int st = 0; st < opts->n_stages; ++st) conc[st] = n;
     if (opts->search_concurrency && n > 2) {
