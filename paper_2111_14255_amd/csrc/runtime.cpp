@@ -660,9 +660,10 @@ void return_signal_word(int device, uint32_t *w) {
     p.idle[device].push_back(w);
 }
 
-// Class of a new plain stream: the first class whose representative it cannot run beside (a round of both takes more
-// than 1.5 launch times), else a new class.
-int32_t classify_stream(mt_ctx *ctx, PlainPool &pool, hipStream_t s, int *cls) {
+// Class of a new stream: the first class whose representative it cannot run beside (a round of both takes more than
+// 1.5 launch times), else a new class, of which a plain stream becomes the representative (a masked one is reported
+// as class -1 then).
+int32_t classify_stream(mt_ctx *ctx, PlainPool &pool, hipStream_t s, bool plain, int *cls) {
     float single = 0.f;
     int32_t rc = dispatch_latency_us(ctx, s, ctx->probe_buf, 8, &single);
     if (rc != MT_OK) return rc;
@@ -673,9 +674,26 @@ int32_t classify_stream(mt_ctx *ctx, PlainPool &pool, hipStream_t s, int *cls) {
         if (rc != MT_OK) return rc;
         if (us > 1.5f * single) { *cls = (int)c; return MT_OK; }
     }
+    if (!plain) { *cls = -1; return MT_OK; }
     *cls = (int)pool.rep.size();
     pool.rep.push_back(s);
     pool.spare.emplace_back();
+    return MT_OK;
+}
+
+// Makes sure a representative of every pipe class exists (new plain streams go to the spare lists), so that masked
+// streams can be classified; gives up after 12 creations.
+int32_t discover_classes(mt_ctx *ctx) {
+    PlainPool &pool = plain_pool(ctx->device);
+    if (!ctx->probe_buf) HIP_TRY(hipMalloc((void **)&ctx->probe_buf, 256));
+    for (int attempt = 0; attempt < 12 && (int)pool.rep.size() < N_PIPES; ++attempt) {
+        hipStream_t s = nullptr;
+        HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+        int cls = 0;
+        int32_t rc = classify_stream(ctx, pool, s, true, &cls);
+        if (rc != MT_OK) { (void)hipStreamDestroy(s); return rc; }
+        pool.spare[cls].push_back(s);
+    }
     return MT_OK;
 }
 
@@ -693,7 +711,7 @@ int32_t plain_stream_of_class(mt_ctx *ctx, int want, hipStream_t *out) {
         hipStream_t s = nullptr;
         HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
         int cls = 0;
-        int32_t rc = classify_stream(ctx, pool, s, &cls);
+        int32_t rc = classify_stream(ctx, pool, s, true, &cls);
         if (rc != MT_OK) { (void)hipStreamDestroy(s); return rc; }
         pool.spare[cls].push_back(s);
     }
@@ -720,16 +738,19 @@ int32_t make_stream(mt_ctx *ctx, int tenant, int share, int first_cu, hipStream_
         const int cu = (first_cu + j) % cus;
         mask[cu / 32] |= 1u << (cu % 32);
     }
-    // A masked stream owns a hardware queue.  It is timed, and one that dispatches dependent kernels more than 1.2
-    // times slower than the best stream seen is parked (kept alive so that its queue stays taken) and replaced.
-    if (!ctx->probe_buf) HIP_TRY(hipMalloc((void **)&ctx->probe_buf, 256));
+    // A masked stream owns a hardware queue, which sits on one of the four dispatch pipes like any other: it is
+    // classified like a plain stream, and one of another class than the tenant index asks for (i % 4) is parked (kept
+    // alive so that the next queue lands on the next pipe; purge_idle_streams destroys it later) and replaced, up to
+    // seven times.
+    int32_t rc = discover_classes(ctx);
+    if (rc != MT_OK) return rc;
+    PlainPool &pool = plain_pool(ctx->device);
     for (int attempt = 0;; ++attempt) {
         HIP_TRY(hipExtStreamCreateWithCUMask(&s, (uint32_t)mask.size(), mask.data()));
-        float us = 0.f;
-        int32_t rc = dispatch_latency_us(ctx, s, ctx->probe_buf, 12, &us);
+        int cls = -1;
+        rc = classify_stream(ctx, pool, s, false, &cls);
         if (rc != MT_OK) { (void)hipStreamDestroy(s); return rc; }
-        if (ctx->best_dispatch_us == 0.f || us < ctx->best_dispatch_us) ctx->best_dispatch_us = us;
-        if (us <= 1.2f * ctx->best_dispatch_us || attempt == 3) break;
+        if (cls == tenant % N_PIPES || (int)pool.rep.size() < N_PIPES || attempt == 7) break;
         ctx->parked_streams.push_back(s);
     }
     *out = s;
