@@ -248,10 +248,12 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
 /* pointers: host [n_tenants][n_stages-1], row i non-decreasing, 0 <= value <= length of M_i.  A pointer is
  * the 1-based index of the last operator of a stage (Eq. 3); the last stage takes the remainder; equal
  * neighbours give an empty slice (Eq. 5, "None").  n_tenants must equal the number of registered tenants.
- * stage_concurrency: host [n_stages] or NULL (= n_tenants each).  In a stage with concurrency c the tenants
- * that have work are ranked in tenant order and rank j is issued on the stream of rank j mod c; c = 1 runs
- * them one after another on one stream (the sequential baseline), c >= active tenants is the paper's
- * one-stream-per-model.
+ * stage_concurrency: host [n_stages] or NULL (= n_tenants each).  In a stage with concurrency c at least as large
+ * as the number of tenants that have work, every tenant is issued on its own stream (the paper's one stream per
+ * model).  With a smaller c the streams of tenant indices 0 .. c - 1 are used and the tenants with work are dealt
+ * to them longest first: in descending order of the operator count of their slice (ties: lower index) each goes to
+ * the stream that holds the fewest operators so far (ties: lowest stream); a stream issues its tenants in tenant
+ * order.  c = 1 runs them one after another on one stream (the sequential baseline).
  * cu_share: host [n_tenants] or NULL.  Number of compute units tenant i's stream may use; 0 = all.  The ranges are
  * laid out one after another (tenant i starts where tenant i-1 ended, modulo the unit count), so shares that sum to
  * at most the unit count are disjoint.  A share between 1 and 7 is rejected with MT_ERR_INVALID_SCHEDULE: consecutive

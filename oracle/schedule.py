@@ -69,10 +69,21 @@ def expand(lens, rho):
 
 
 def stream_map(stage, concurrency):
-    """Host stream (a tenant index) of every tenant active in the stage."""
+    """Host stream (a tenant index) of every tenant active in the stage: its own stream when there are enough
+    streams (Sec. III-B, Eq. 2); otherwise streams 0 .. c-1, tenants taken longest slice first (ties: lower index),
+    each to the stream carrying the fewest operators so far (ties: lowest stream)."""
     active = [i for i, (b, e) in enumerate(stage) if e > b]
-    c = max(1, min(concurrency, len(active))) if active else 1
-    return {t: active[j % c] for j, t in enumerate(active)}
+    c = max(1, concurrency)
+    if c >= len(active):
+        return {t: t for t in active}
+    size = {t: stage[t][1] - stage[t][0] for t in active}
+    load = [0] * c
+    out = {}
+    for t in sorted(active, key=lambda t: (-size[t], t)):
+        k = min(range(c), key=lambda k: (load[k], k))
+        out[t] = k
+        load[k] += size[t]
+    return out
 
 
 def issue_order(stage, concurrency, order="bfs"):

@@ -46,7 +46,10 @@ void expand_pointers(int32_t n_tenants, const int32_t *lens, int32_t n_stages, c
         }
 }
 
-// Tenants with work are ranked in tenant order; rank j shares the stream of rank j mod c.
+// Which stream each tenant with work is issued on.  With at least as many streams as such tenants every tenant keeps
+// its own stream (Sec. III-B, Eq. 2).  With fewer, the streams in use are those of tenant indices 0 .. c - 1 and the
+// tenants are dealt to them longest first: in descending order of the operator count of their slice (ties: lower
+// tenant index first) each goes to the stream that holds the fewest operators so far (ties: lowest stream).
 void stream_map(int32_t n_tenants, const int32_t *slices, int32_t concurrency, int32_t *host_stream) {
     std::vector<int> active;
     for (int i = 0; i < n_tenants; ++i) {
@@ -54,8 +57,21 @@ void stream_map(int32_t n_tenants, const int32_t *slices, int32_t concurrency, i
         if (slices[2 * i + 1] > slices[2 * i]) active.push_back(i);
     }
     if (active.empty()) return;
-    int c = std::max(1, std::min<int>(concurrency, (int)active.size()));
-    for (size_t j = 0; j < active.size(); ++j) host_stream[active[j]] = active[j % c];
+    const int c = std::max(1, concurrency);
+    if (c >= (int)active.size()) {
+        for (int t : active) host_stream[t] = t;
+        return;
+    }
+    auto ops = [&](int t) { return slices[2 * t + 1] - slices[2 * t]; };
+    std::stable_sort(active.begin(), active.end(), [&](int a, int b) { return ops(a) > ops(b); });
+    std::vector<int64_t> load(c, 0);
+    for (int t : active) {
+        int best = 0;
+        for (int k = 1; k < c; ++k)
+            if (load[k] < load[best]) best = k;
+        host_stream[t] = best;
+        load[best] += ops(t);
+    }
 }
 
 std::vector<IssueItem> issue_order(int32_t n_tenants, const int32_t *slices, int32_t concurrency, int32_t order) {

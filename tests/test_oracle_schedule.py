@@ -76,10 +76,31 @@ def test_concurrency_multiplexing():
     stage = [(0, 2), (0, 0), (1, 3), (0, 1)]
     seq = S.issue_order(stage, 1, "bfs")       # sequential: one stream, tenants in order
     assert seq == [(0, 0, 0), (0, 0, 1), (0, 2, 1), (0, 2, 2), (0, 3, 0)]
-    two = S.issue_order(stage, 2, "bfs")       # active tenants 0,2,3 -> streams 0,2,0
-    assert S.stream_map(stage, 2) == {0: 0, 2: 2, 3: 0}
-    assert two == [(0, 0, 0), (2, 2, 1), (0, 0, 1), (2, 2, 2), (0, 3, 0)]
-    assert S.stream_map(stage, 9) == {0: 0, 2: 2, 3: 3}
+    two = S.issue_order(stage, 2, "bfs")       # active tenants 0,2,3 with 2,2,1 operators -> streams 0,1,0
+    assert S.stream_map(stage, 2) == {0: 0, 2: 1, 3: 0}
+    assert two == [(0, 0, 0), (1, 2, 1), (0, 0, 1), (1, 2, 2), (0, 3, 0)]
+    assert S.stream_map(stage, 9) == {0: 0, 2: 2, 3: 3}     # enough streams: every tenant keeps its own
+
+
+def test_fewer_streams_than_tenants_longest_first():
+    # hand case: slices of 10, 3, 8, 2, 7 operators on two streams: 10 | 8, then 7 joins the 8, 3 the 10, 2 the 13
+    stage = [(0, 10), (5, 8), (1, 9), (0, 2), (3, 10)]
+    assert S.stream_map(stage, 2) == {0: 0, 2: 1, 4: 1, 1: 0, 3: 0}
+    # equal tenants fall back to round-robin in tenant order
+    assert S.stream_map([(0, 5)] * 8, 4) == {t: t % 4 for t in range(8)}
+    # the greedy rule's guarantee: the fullest stream holds at most 4/3 - 1/(3c) of the best possible split
+    import itertools, random
+    rng = random.Random(5)
+    for _ in range(200):
+        n = rng.randint(2, 7)
+        sizes = [rng.randint(1, 30) for _ in range(n)]
+        c = rng.randint(1, n - 1)
+        stage = [(0, v) for v in sizes]
+        m = S.stream_map(stage, c)
+        assert set(m) == set(range(n)) and all(0 <= k < c for k in m.values())
+        got = max(sum(sizes[t] for t in range(n) if m[t] == k) for k in range(c))
+        best = min(max(sum(sizes[t] for t in range(n) if a[t] == k) for k in range(c)) for a in itertools.product(range(c), repeat=n))
+        assert got * 3 * c <= best * (4 * c - 1)
 
 
 def test_counter_rng_reference_values():
