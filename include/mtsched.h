@@ -326,6 +326,18 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
  * streams that share a hardware queue cannot block each other); not with MT_SCHED_GRAPH, MT_SCHED_STREAM_GRAPHS or
  * MT_SCHED_HOST_BARRIER.  MT_ERR_HIP from mt_schedule_create if the device has no stream memory operations. */
 #define MT_SCHED_COUNTER_BARRIER 2048
+/* Co-issue (an issue mechanism of this runtime; the paper issues one launch per operator, Sec. III-D): where a stage
+ * puts two tenants on one stream (stage_concurrency below the number of tenants with work), the stream would run the
+ * first tenant's slice and then the second's.  With this flag the two slices are walked together: operator i of both
+ * runs as ONE launch whose workgroups are split between the two tenants, wherever the two operators have the same
+ * kernel and launch shape (same architecture and batch: everything in their kernel arguments but the buffers is equal)
+ * and the kernel has a two-operator form; the other operators of the pair are launched one after the other as
+ * before.  Slices of different lengths are not co-issued.  Every operator computes exactly what it computes alone
+ * (same tile program, same split, same summation order), so outputs are bit-identical; what changes is the number of
+ * launches the command processor has to dispatch and complete, which is what bounds many small kernels on several
+ * streams.  mt_timings.n_fused counts the operators that ran inside another tenant's launch.  Not with
+ * MT_SCHED_GRAPH, MT_SCHED_STREAM_GRAPHS or MT_SCHED_TIME_FIRST_OP. */
+#define MT_SCHED_COISSUE 4096
 int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, const int32_t *pointers,
                            const int32_t *stage_concurrency, const int32_t *cu_share,
                            int32_t issue_order, int32_t flags, mt_schedule **out);

@@ -36,6 +36,7 @@ MT_SCHED_TIME_TENANTS = 512
 MT_SCHED_HOST_BARRIER = 1024
 MT_SCHED_STREAM_GRAPHS = 32
 MT_SCHED_COUNTER_BARRIER = 2048
+MT_SCHED_COISSUE = 4096
 MT_SEARCH_COORDINATE, MT_SEARCH_RANDOM = 0, 1
 
 

@@ -275,7 +275,7 @@ static int dwconv_band_rows(const OpArgs &a) {
 }
 
 template <typename T, int V, bool IS_MAX, int KS>
-__global__ void __launch_bounds__(256) pool_fixed_kernel(OpArgs a) {
+__device__ __forceinline__ void pool_fixed_kernel_body(const OpArgs &a) {
     set_wave_priority(a.prio);
     const int CV = a.C / V;
     const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
@@ -313,6 +313,15 @@ __global__ void __launch_bounds__(256) pool_fixed_kernel(OpArgs a) {
         for (int i = 0; i < V; ++i) acc[i] = acc[i] / (float)cnt;
     }
     store_pack<T, V>((T *)a.y + m * a.y_ct + a.y_coff + c0, acc);
+}
+template <typename T, int V, bool IS_MAX, int KS>
+__global__ void __launch_bounds__(256) pool_fixed_kernel(OpArgs a) {
+    pool_fixed_kernel_body<T, V, IS_MAX, KS>(a);
+}
+// two operators of equal launch shape in one launch, one per value of blockIdx.y
+template <typename T, int V, bool IS_MAX, int KS>
+__global__ void __launch_bounds__(256) pool_fixed_pair_kernel(OpArgsPair p) {
+    pool_fixed_kernel_body<T, V, IS_MAX, KS>(p.a[blockIdx.y]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -358,7 +367,7 @@ __global__ void __launch_bounds__(256) pool_kernel(OpArgs a) {
 // arranged as LANES_HW spatial slices x LANES_C channel vectors; each lane sums its slice in order and
 // the slices are combined by a fixed butterfly of wavefront shuffles, so the sum order is fixed.
 template <typename T, int V>
-__global__ void __launch_bounds__(256) gap_kernel(OpArgs a, int lanes_c) {
+__device__ __forceinline__ void gap_kernel_body(const OpArgs &a, int lanes_c) {
     set_wave_priority(a.prio);
     const int CV = a.C / V;
     const int lanes_hw = 64 / lanes_c;
@@ -399,6 +408,15 @@ __global__ void __launch_bounds__(256) gap_kernel(OpArgs a, int lanes_c) {
         for (int j = 0; j < V; ++j) acc[j] = acc[j] / (float)HW;
         store_pack<T, V>((T *)a.y + (int64_t)n * a.y_ct + a.y_coff + cv * V, acc);
     }
+}
+template <typename T, int V>
+__global__ void __launch_bounds__(256) gap_kernel(OpArgs a, int lanes_c) {
+    gap_kernel_body<T, V>(a, lanes_c);
+}
+// two operators of equal launch shape in one launch, one per value of blockIdx.y
+template <typename T, int V>
+__global__ void __launch_bounds__(256) gap_pair_kernel(OpArgsPair p, int lanes_c) {
+    gap_kernel_body<T, V>(p.a[blockIdx.y], lanes_c);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -504,7 +522,7 @@ __global__ void fill_u32_kernel(uint32_t *p, size_t n, uint32_t v) {
 
 // ---------------------------------------------------------------------------------------------
 template <typename T>
-static int launch_typed(const OpArgs &a, hipStream_t st) {
+static int launch_typed(const OpArgs &a, hipStream_t st, const OpArgs *mate) {
     const dim3 block(256);
     auto blocks = [](int64_t threads) { return dim3((unsigned)((threads + 255) / 256)); };
     constexpr int VMAX = 16 / sizeof(T);          // 16-byte accesses
@@ -540,11 +558,11 @@ static int launch_typed(const OpArgs &a, hipStream_t st) {
             if (a.vec == VMAX) {
                 const int64_t th = (int64_t)a.N * a.P * a.Q * (a.C / VMAX);
                 if (mx && a.R == 2 && a.S == 2)
-                    hipLaunchKernelGGL((pool_fixed_kernel<T, VMAX, true, 2>), blocks(th), block, 0, st, a);
+                    MT_LAUNCH((pool_fixed_kernel<T, VMAX, true, 2>), (pool_fixed_pair_kernel<T, VMAX, true, 2>), blocks(th), block, st, a, mate);
                 else if (mx && a.R == 3 && a.S == 3)
-                    hipLaunchKernelGGL((pool_fixed_kernel<T, VMAX, true, 3>), blocks(th), block, 0, st, a);
+                    MT_LAUNCH((pool_fixed_kernel<T, VMAX, true, 3>), (pool_fixed_pair_kernel<T, VMAX, true, 3>), blocks(th), block, st, a, mate);
                 else if (!mx && a.R == 3 && a.S == 3)
-                    hipLaunchKernelGGL((pool_fixed_kernel<T, VMAX, false, 3>), blocks(th), block, 0, st, a);
+                    MT_LAUNCH((pool_fixed_kernel<T, VMAX, false, 3>), (pool_fixed_pair_kernel<T, VMAX, false, 3>), blocks(th), block, st, a, mate);
                 else if (mx)
                     hipLaunchKernelGGL((pool_kernel<T, VMAX, true>), blocks(th), block, 0, st, a);
                 else
@@ -566,7 +584,7 @@ static int launch_typed(const OpArgs &a, hipStream_t st) {
             const int groups = (CV + lanes_c - 1) / lanes_c;
             const int64_t th = (int64_t)a.N * groups * 64;
             if (V == VMAX)
-                hipLaunchKernelGGL((gap_kernel<T, VMAX>), blocks(th), block, 0, st, a, lanes_c);
+                MT_LAUNCH((gap_kernel<T, VMAX>), (gap_pair_kernel<T, VMAX>), blocks(th), block, st, a, mate, lanes_c);
             else
                 hipLaunchKernelGGL((gap_kernel<T, 1>), blocks(th), block, 0, st, a, lanes_c);
             break;
@@ -596,12 +614,13 @@ static int launch_typed(const OpArgs &a, hipStream_t st) {
     return (int)hipGetLastError();
 }
 
-int launch_direct(const OpArgs &a, void *stream) {
+int launch_direct(const OpArgs &a, void *stream, const OpArgs *mate) {
     hipStream_t st = (hipStream_t)stream;
+    if (mate && !coissue_supported(a)) return (int)hipErrorInvalidValue;
     switch (a.dtype) {
-        case MT_F32: return launch_typed<float>(a, st);
-        case MT_F16: return launch_typed<f16>(a, st);
-        case MT_BF16: return launch_typed<bf16>(a, st);
+        case MT_F32: return launch_typed<float>(a, st, mate);
+        case MT_F16: return launch_typed<f16>(a, st, mate);
+        case MT_BF16: return launch_typed<bf16>(a, st, mate);
     }
     return (int)hipErrorInvalidValue;
 }

@@ -51,7 +51,7 @@ constexpr int PWDW_HC = 16, PWDW_WGS = 64, PWDW_ITEMS = 128;
 // tile walk is a scalar offset, and a chunk in the padding halo is given an out-of-range offset, for which
 // the hardware returns zeros: no select and no 64-bit address arithmetic in the loop.
 template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES, int AMODE, int WK = 1>
-__global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
+__device__ __forceinline__ void igemm_body(const OpArgs &a) {
     set_wave_priority(a.prio);
     static_assert(WN * WM == 4, "four waves per output tile");
     // WK > 1: WK groups of four waves share the output tile and split the MFMA steps of every LDS tile between them
@@ -835,30 +835,45 @@ __global__ void __launch_bounds__(256) pw_direct_kernel(OpArgs a) {
     }
 }
 
+template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES, int AMODE, int WK = 1>
+__global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
+    igemm_body<T, BN, BM, WN, WM, MF, STAGES, AMODE, WK>(a);
+}
+// Co-issue: the same tile program for two operators of equal launch shape, one per value of blockIdx.y.
+template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES, int AMODE, int WK = 1>
+__global__ void __launch_bounds__(256 * WK) igemm_pair_kernel(OpArgsPair p) {
+    igemm_body<T, BN, BM, WN, WM, MF, STAGES, AMODE, WK>(p.a[blockIdx.y]);
+}
+
 template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES, int WK = 1>
-static void launch_cfg(const OpArgs &a, hipStream_t st) {
-    const dim3 grid(a.grid_x);
-    if (a.vec_a == A_UNIFORM)
-        hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, STAGES, A_UNIFORM, WK>), grid, dim3(256 * WK), 0, st, a);
-    else if (a.vec_a == A_VEC8)
-        hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, STAGES, A_VEC8, WK>), grid, dim3(256 * WK), 0, st, a);
-    else
+static void launch_cfg(const OpArgs &a, hipStream_t st, const OpArgs *mate) {
+    const dim3 grid(a.grid_x, mate ? 2 : 1);
+    OpArgsPair p;
+    if (mate) { p.a[0] = a; p.a[1] = *mate; }
+    if (a.vec_a == A_UNIFORM) {
+        if (mate) hipLaunchKernelGGL((igemm_pair_kernel<T, BN, BM, WN, WM, MF, STAGES, A_UNIFORM, WK>), grid, dim3(256 * WK), 0, st, p);
+        else hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, STAGES, A_UNIFORM, WK>), grid, dim3(256 * WK), 0, st, a);
+    } else if (a.vec_a == A_VEC8) {
+        if (mate) hipLaunchKernelGGL((igemm_pair_kernel<T, BN, BM, WN, WM, MF, STAGES, A_VEC8, WK>), grid, dim3(256 * WK), 0, st, p);
+        else hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, STAGES, A_VEC8, WK>), grid, dim3(256 * WK), 0, st, a);
+    } else {
         hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, 2, A_SCALAR>), grid, dim3(256), 0, st, a);
+    }
 }
 
 template <typename T>
-static int launch_igemm_typed(const OpArgs &a, hipStream_t st) {
+static int launch_igemm_typed(const OpArgs &a, hipStream_t st, const OpArgs *mate) {
     switch (a.kernel_id) {
-        case K_IGEMM_128x128: launch_cfg<T, 128, 128, 2, 2, 32, 2>(a, st); break;
+        case K_IGEMM_128x128: launch_cfg<T, 128, 128, 2, 2, 32, 2>(a, st, mate); break;
         case K_IGEMM_128x64:
-            if (a.wk == 2) launch_cfg<T, 128, 64, 2, 2, 32, 2, 2>(a, st);
-            else launch_cfg<T, 128, 64, 2, 2, 32, 2>(a, st);
+            if (a.wk == 2) launch_cfg<T, 128, 64, 2, 2, 32, 2, 2>(a, st, mate);
+            else launch_cfg<T, 128, 64, 2, 2, 32, 2>(a, st, mate);
             break;
         case K_IGEMM_64x64:
-            if (a.wk == 2) launch_cfg<T, 64, 64, 2, 2, 32, 4, 2>(a, st);
-            else launch_cfg<T, 64, 64, 2, 2, 32, 4, 1>(a, st);
+            if (a.wk == 2) launch_cfg<T, 64, 64, 2, 2, 32, 4, 2>(a, st, mate);
+            else launch_cfg<T, 64, 64, 2, 2, 32, 4, 1>(a, st, mate);
             break;
-        case K_IGEMM_64x16: launch_cfg<T, 64, 16, 4, 1, 16, 4>(a, st); break;
+        case K_IGEMM_64x16: launch_cfg<T, 64, 16, 4, 1, 16, 4>(a, st, mate); break;
         case K_IGEMM_PW: {
             const dim3 grid(a.grid_x), block(256);
             if (a.split_k > 1) hipLaunchKernelGGL((pw_direct_kernel<T, 4>), grid, block, 0, st, a);
@@ -1374,11 +1389,29 @@ int static_scratch_address(int device, void **ptr) {
     return 0;
 }
 
-int launch_igemm(const OpArgs &a, void *stream) {
+int launch_igemm(const OpArgs &a, void *stream, const OpArgs *mate) {
     hipStream_t st = (hipStream_t)stream;
-    if (a.dtype == MT_F16) return launch_igemm_typed<f16>(a, st);
-    if (a.dtype == MT_BF16) return launch_igemm_typed<bf16>(a, st);
+    if (mate && !coissue_supported(a)) return (int)hipErrorInvalidValue;
+    if (a.dtype == MT_F16) return launch_igemm_typed<f16>(a, st, mate);
+    if (a.dtype == MT_BF16) return launch_igemm_typed<bf16>(a, st, mate);
     return (int)hipErrorInvalidValue;
+}
+
+// Kernels that exist in a two-operator form (the tile kernels with 16-byte or tap-uniform gathers, the patch-staged and
+// resident-filter kernels, the first-layer kernel, the fixed-window pooling and the global average pooling), for the
+// 16-bit storage types.
+bool coissue_supported(const OpArgs &a) {
+    if (a.dtype != MT_F16 && a.dtype != MT_BF16) return false;
+    if (a.groups > 1) return false;
+    switch (a.kernel_id) {
+        case K_IGEMM_128x128: case K_IGEMM_128x64: case K_IGEMM_64x64: case K_IGEMM_64x16:
+            return a.vec_a == A_UNIFORM || a.vec_a == A_VEC8;
+        case K_PCONV: case K_ROWB: case K_STEM: return true;
+        case K_MAXPOOL: return a.vec == 8 && ((a.R == 2 && a.S == 2) || (a.R == 3 && a.S == 3));
+        case K_AVGPOOL: return a.vec == 8 && a.R == 3 && a.S == 3;
+        case K_GAP: return a.vec == 8;
+        default: return false;
+    }
 }
 
 }  // namespace mt

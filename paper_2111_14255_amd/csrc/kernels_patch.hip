@@ -33,7 +33,7 @@ constexpr int PC_LDK = IGEMM_BK + 8;     // LDS row: 64 elements + 16 bytes
 
 // PPX: patch pixels the LDS block holds (>= 64 + 2 W + 2)
 template <typename T, int PPX>
-__global__ void __launch_bounds__(512) pconv_kernel(OpArgs a) {
+__device__ __forceinline__ void pconv_kernel_body(const OpArgs &a) {
     set_wave_priority(a.prio);
     constexpr int BN = 64, BM = 64, NT = 512, LDK = PC_LDK;
     constexpr int A_TILE = BN * LDK;
@@ -237,6 +237,15 @@ __global__ void __launch_bounds__(512) pconv_kernel(OpArgs a) {
     for (int t = 0; t < 8; ++t) v[t] = apply_act(v[t], a.act);
     store_pack<T, 8>(y + (int64_t)em * a.y_ct + a.y_coff + ek, v);
 }
+template <typename T, int PPX>
+__global__ void __launch_bounds__(512) pconv_kernel(OpArgs a) {
+    pconv_kernel_body<T, PPX>(a);
+}
+// two operators of equal launch shape in one launch, one per value of blockIdx.y
+template <typename T, int PPX>
+__global__ void __launch_bounds__(512) pconv_pair_kernel(OpArgsPair p) {
+    pconv_kernel_body<T, PPX>(p.a[blockIdx.y]);
+}
 
 }  // namespace
 
@@ -246,15 +255,15 @@ int pconv_patch_pixels(int W) {
     return need <= 128 ? 128 : need <= 192 ? 192 : need <= 320 ? 320 : 0;
 }
 
-int launch_pconv(const OpArgs &a, void *stream) {
+int launch_pconv(const OpArgs &a, void *stream, const OpArgs *mate) {
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid(a.grid_x), block(512);
     const int ppx = pconv_patch_pixels(a.W);
     if (ppx == 0 || a.R != 3 || a.S != 3 || a.sh != 1 || a.sw != 1 || a.ph != 1 || a.pw != 1 || a.C % 64 != 0) return (int)hipErrorInvalidValue;
     auto go = [&]<typename T>() {
-        if (ppx == 128) hipLaunchKernelGGL((pconv_kernel<T, 128>), grid, block, 0, st, a);
-        else if (ppx == 192) hipLaunchKernelGGL((pconv_kernel<T, 192>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((pconv_kernel<T, 320>), grid, block, 0, st, a);
+        if (ppx == 128) MT_LAUNCH((pconv_kernel<T, 128>), (pconv_pair_kernel<T, 128>), grid, block, st, a, mate);
+        else if (ppx == 192) MT_LAUNCH((pconv_kernel<T, 192>), (pconv_pair_kernel<T, 192>), grid, block, st, a, mate);
+        else MT_LAUNCH((pconv_kernel<T, 320>), (pconv_pair_kernel<T, 320>), grid, block, st, a, mate);
     };
     if (a.dtype == MT_F16) go.template operator()<f16>();
     else go.template operator()<bf16>();

@@ -28,7 +28,7 @@ namespace {
 constexpr uint32_t ROWB_OOB = 0x80000000u;   // beyond any tensor: buffer loads return zeros
 
 template <typename T, int R, int S, int SPT, int NTA, int NW>
-__global__ void __launch_bounds__(64 * NW) rowb_kernel(OpArgs a) {
+__device__ __forceinline__ void rowb_kernel_body(const OpArgs &a) {
     set_wave_priority(a.prio);
     constexpr int TAPS = R * S;
     constexpr int KS = TAPS * SPT;            // MFMA steps (16 reduction elements each)
@@ -176,6 +176,15 @@ __global__ void __launch_bounds__(64 * NW) rowb_kernel(OpArgs a) {
         }
     }
 }
+template <typename T, int R, int S, int SPT, int NTA, int NW>
+__global__ void __launch_bounds__(64 * NW) rowb_kernel(OpArgs a) {
+    rowb_kernel_body<T, R, S, SPT, NTA, NW>(a);
+}
+// two operators of equal launch shape in one launch, one per value of blockIdx.y
+template <typename T, int R, int S, int SPT, int NTA, int NW>
+__global__ void __launch_bounds__(64 * NW) rowb_pair_kernel(OpArgsPair p) {
+    rowb_kernel_body<T, R, S, SPT, NTA, NW>(p.a[blockIdx.y]);
+}
 
 // 3x3 window, stride 1, 64 -> 64 channels: the activations go through LDS once, as the input patch of the wave's pixel
 // tile, instead of once per tap through the L1.  A wave owns 4 x 8 output pixels; their 6 x 10 input pixels (128 bytes
@@ -187,7 +196,7 @@ __global__ void __launch_bounds__(64 * NW) rowb_kernel(OpArgs a) {
 // reuses the patch block as its staging block.  fp32 accumulation in step order (tap-major, 16 channels per step), the
 // same order as the streaming form above.
 template <typename T>
-__global__ void __launch_bounds__(512) rowp_kernel(OpArgs a) {
+__device__ __forceinline__ void rowp_kernel_body(const OpArgs &a) {
     set_wave_priority(a.prio);
     constexpr int KS = 36, NTA = 2, NW = 8, C = 64, SPT = 4;
     constexpr int TP = 4, TQ = 8;                 // output rows x columns of a wave tile
@@ -328,6 +337,15 @@ __global__ void __launch_bounds__(512) rowp_kernel(OpArgs a) {
         }
     }
 }
+template <typename T>
+__global__ void __launch_bounds__(512) rowp_kernel(OpArgs a) {
+    rowp_kernel_body<T>(a);
+}
+// two operators of equal launch shape in one launch, one per value of blockIdx.y
+template <typename T>
+__global__ void __launch_bounds__(512) rowp_pair_kernel(OpArgsPair p) {
+    rowp_kernel_body<T>(p.a[blockIdx.y]);
+}
 
 }  // namespace
 
@@ -348,19 +366,19 @@ bool rowb_patch_form(const OpArgs &a) { return a.R == 3 && a.S == 3 && a.sh == 1
 
 int rowb_waves(int R, int S, int C, int channels) { return rowb_tiles(R, S, C, channels) ? 8 : 0; }
 
-int launch_rowb(const OpArgs &a, void *stream) {
+int launch_rowb(const OpArgs &a, void *stream, const OpArgs *mate) {
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid(a.grid_x), block(a.block);
     const int nta = rowb_tiles(a.R, a.S, a.C, a.n_pad);
     if (nta == 0 || (int)block.x != 64 * rowb_waves(a.R, a.S, a.C, a.n_pad)) return (int)hipErrorInvalidValue;
     auto go = [&]<typename T>() {
-        if (a.R == 3 && rowb_patch_form(a)) hipLaunchKernelGGL((rowp_kernel<T>), grid, block, 0, st, a);
-        else if (a.R == 3) hipLaunchKernelGGL((rowb_kernel<T, 3, 3, 4, 2, 8>), grid, block, 0, st, a);
-        else if (a.C == 64 && nta == 2) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 4, 2, 8>), grid, block, 0, st, a);
-        else if (a.C == 64) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 4, 8, 8>), grid, block, 0, st, a);
-        else if (a.C == 128) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 8, 4, 8>), grid, block, 0, st, a);
-        else if (nta == 2) hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 16, 2, 8>), grid, block, 0, st, a);
-        else hipLaunchKernelGGL((rowb_kernel<T, 1, 1, 16, 4, 8>), grid, block, 0, st, a);
+        if (a.R == 3 && rowb_patch_form(a)) MT_LAUNCH((rowp_kernel<T>), (rowp_pair_kernel<T>), grid, block, st, a, mate);
+        else if (a.R == 3) MT_LAUNCH((rowb_kernel<T, 3, 3, 4, 2, 8>), (rowb_pair_kernel<T, 3, 3, 4, 2, 8>), grid, block, st, a, mate);
+        else if (a.C == 64 && nta == 2) MT_LAUNCH((rowb_kernel<T, 1, 1, 4, 2, 8>), (rowb_pair_kernel<T, 1, 1, 4, 2, 8>), grid, block, st, a, mate);
+        else if (a.C == 64) MT_LAUNCH((rowb_kernel<T, 1, 1, 4, 8, 8>), (rowb_pair_kernel<T, 1, 1, 4, 8, 8>), grid, block, st, a, mate);
+        else if (a.C == 128) MT_LAUNCH((rowb_kernel<T, 1, 1, 8, 4, 8>), (rowb_pair_kernel<T, 1, 1, 8, 4, 8>), grid, block, st, a, mate);
+        else if (nta == 2) MT_LAUNCH((rowb_kernel<T, 1, 1, 16, 2, 8>), (rowb_pair_kernel<T, 1, 1, 16, 2, 8>), grid, block, st, a, mate);
+        else MT_LAUNCH((rowb_kernel<T, 1, 1, 16, 4, 8>), (rowb_pair_kernel<T, 1, 1, 16, 4, 8>), grid, block, st, a, mate);
     };
     if (a.dtype == MT_F16) go.template operator()<f16>();
     else go.template operator()<bf16>();

@@ -33,7 +33,7 @@ namespace {
 constexpr uint32_t STEM_OOB = 0x80000000u;   // beyond any tensor: buffer loads return zeros
 
 template <typename T, int R, int S, int DUMMY, int TN, bool ALIGNED>
-__global__ void __launch_bounds__(256) stem_kernel(OpArgs a) {
+__device__ __forceinline__ void stem_kernel_body(const OpArgs &a) {
     static_assert(ALIGNED || DUMMY == 0, "the general form has no dummy element");
     set_wave_priority(a.prio);
     constexpr int SEG = DUMMY + 3 * S;        // elements of one filter row's run
@@ -230,6 +230,15 @@ __global__ void __launch_bounds__(256) stem_kernel(OpArgs a) {
         if (tile < n_tiles) fetch(tile, b, vm);
     }
 }
+template <typename T, int R, int S, int DUMMY, int TN, bool ALIGNED>
+__global__ void __launch_bounds__(256) stem_kernel(OpArgs a) {
+    stem_kernel_body<T, R, S, DUMMY, TN, ALIGNED>(a);
+}
+// two operators of equal launch shape in one launch, one per value of blockIdx.y
+template <typename T, int R, int S, int DUMMY, int TN, bool ALIGNED>
+__global__ void __launch_bounds__(256) stem_pair_kernel(OpArgsPair p) {
+    stem_kernel_body<T, R, S, DUMMY, TN, ALIGNED>(p.a[blockIdx.y]);
+}
 
 }  // namespace
 
@@ -240,7 +249,7 @@ int stem_form(int R, int S, int sw, int W, int pw, int channels) {
     return (sw % 2 == 0 && W % 2 == 0 && ((3 * pw) & 1)) ? 1 : 2;
 }
 
-int launch_stem(const OpArgs &a, void *stream) {
+int launch_stem(const OpArgs &a, void *stream, const OpArgs *mate) {
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid(a.grid_x), block(256);
     const int tn = a.n_pad / 32;
@@ -248,15 +257,15 @@ int launch_stem(const OpArgs &a, void *stream) {
     if (form == 0) return (int)hipErrorInvalidValue;
     auto go = [&]<typename T>() {
         if (form == 1) {
-            if (a.R == 7 && tn == 2) hipLaunchKernelGGL((stem_kernel<T, 7, 7, 1, 2, true>), grid, block, 0, st, a);
-            else if (a.R == 7) hipLaunchKernelGGL((stem_kernel<T, 7, 7, 1, 1, true>), grid, block, 0, st, a);
-            else if (tn == 2) hipLaunchKernelGGL((stem_kernel<T, 3, 3, 1, 2, true>), grid, block, 0, st, a);
-            else hipLaunchKernelGGL((stem_kernel<T, 3, 3, 1, 1, true>), grid, block, 0, st, a);
+            if (a.R == 7 && tn == 2) MT_LAUNCH((stem_kernel<T, 7, 7, 1, 2, true>), (stem_pair_kernel<T, 7, 7, 1, 2, true>), grid, block, st, a, mate);
+            else if (a.R == 7) MT_LAUNCH((stem_kernel<T, 7, 7, 1, 1, true>), (stem_pair_kernel<T, 7, 7, 1, 1, true>), grid, block, st, a, mate);
+            else if (tn == 2) MT_LAUNCH((stem_kernel<T, 3, 3, 1, 2, true>), (stem_pair_kernel<T, 3, 3, 1, 2, true>), grid, block, st, a, mate);
+            else MT_LAUNCH((stem_kernel<T, 3, 3, 1, 1, true>), (stem_pair_kernel<T, 3, 3, 1, 1, true>), grid, block, st, a, mate);
         } else {
-            if (a.R == 7 && tn == 2) hipLaunchKernelGGL((stem_kernel<T, 7, 7, 0, 2, false>), grid, block, 0, st, a);
-            else if (a.R == 7) hipLaunchKernelGGL((stem_kernel<T, 7, 7, 0, 1, false>), grid, block, 0, st, a);
-            else if (tn == 2) hipLaunchKernelGGL((stem_kernel<T, 3, 3, 0, 2, false>), grid, block, 0, st, a);
-            else hipLaunchKernelGGL((stem_kernel<T, 3, 3, 0, 1, false>), grid, block, 0, st, a);
+            if (a.R == 7 && tn == 2) MT_LAUNCH((stem_kernel<T, 7, 7, 0, 2, false>), (stem_pair_kernel<T, 7, 7, 0, 2, false>), grid, block, st, a, mate);
+            else if (a.R == 7) MT_LAUNCH((stem_kernel<T, 7, 7, 0, 1, false>), (stem_pair_kernel<T, 7, 7, 0, 1, false>), grid, block, st, a, mate);
+            else if (tn == 2) MT_LAUNCH((stem_kernel<T, 3, 3, 0, 2, false>), (stem_pair_kernel<T, 3, 3, 0, 2, false>), grid, block, st, a, mate);
+            else MT_LAUNCH((stem_kernel<T, 3, 3, 0, 1, false>), (stem_pair_kernel<T, 3, 3, 0, 1, false>), grid, block, st, a, mate);
         }
     };
     if (a.dtype == MT_F16) go.template operator()<f16>();

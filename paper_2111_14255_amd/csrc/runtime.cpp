@@ -496,11 +496,24 @@ namespace {
     } while (0)
 
 // One kernel launch; returns a hipError_t as int.
-int launch_kernel(const OpArgs &a, hipStream_t st) {
-    if (a.kernel_id == K_STEM) return launch_stem(a, st);
-    if (a.kernel_id == K_ROWB) return launch_rowb(a, st);
-    if (a.kernel_id == K_PCONV) return launch_pconv(a, st);
-    return is_gemm_kernel(a.kernel_id) ? launch_igemm(a, st) : launch_direct(a, st);
+int launch_kernel(const OpArgs &a, hipStream_t st, const OpArgs *mate = nullptr) {
+    if (a.kernel_id == K_STEM) return launch_stem(a, st, mate);
+    if (a.kernel_id == K_ROWB) return launch_rowb(a, st, mate);
+    if (a.kernel_id == K_PCONV) return launch_pconv(a, st, mate);
+    return is_gemm_kernel(a.kernel_id) ? launch_igemm(a, st, mate) : launch_direct(a, st, mate);
+}
+
+// Two operators can run as one launch if their kernel has a two-operator form and everything in their arguments but
+// the buffers (and the wave priority, which the launch takes from the first) is equal: same kernel, tile, split, shape.
+bool coissue_pair_ok(const OpArgs &a, const OpArgs &b) {
+    if (!coissue_supported(a) || !coissue_supported(b)) return false;
+    if ((a.res == nullptr) != (b.res == nullptr) || (a.ws == nullptr) != (b.ws == nullptr)) return false;
+    OpArgs x = a, y = b;
+    for (OpArgs *o : {&x, &y}) {
+        o->x = nullptr; o->w = nullptr; o->bias = nullptr; o->res = nullptr; o->y = nullptr; o->ws = nullptr; o->counters = nullptr;
+        o->prio = 0;
+    }
+    return std::memcmp(&x, &y, sizeof(OpArgs)) == 0;
 }
 
 // One operator; returns a hipError_t as int.  A grouped convolution is one operator of the sequence issued as one
@@ -574,6 +587,16 @@ int launch_item(const mt_ctx *ctx, const mt_schedule *s, const IssueItem &it, co
         OpArgs prev = patched(t, it.op - 1, inputs[it.tenant], outputs[it.tenant]);
         prev.prio = a.prio;
         return it.fuse == 2 ? launch_dwpw(prev, a, st) : launch_pwdw(prev, a, st);
+    }
+    if (it.mate >= 0) {
+        const Tenant &tm = *ctx->tenants[it.mate];
+        OpArgs b = patched(tm, it.op, inputs[it.mate], outputs[it.mate]);
+        if (s->st_base && b.ws) {
+            b.ws = (float *)(s->st_base + s->st_ws_base[it.mate] + tm.st_ws_off[it.op]);
+            b.counters = (uint32_t *)(s->st_base + s->st_cnt_base[it.mate] + tm.st_cnt_off[it.op]);
+        }
+        b.prio = a.prio;
+        return launch_kernel(a, st, &b);
     }
     if (it.fuse == 4) {
         OpArgs b = t.pool_args[it.op];
@@ -1803,6 +1826,8 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
         return fail(MT_ERR_INVALID_ARG, "first-operator timing needs the single issuing thread and plain streams");
     if ((flags & MT_SCHED_COUNTER_BARRIER) && (flags & (MT_SCHED_GRAPH | MT_SCHED_STREAM_GRAPHS | MT_SCHED_HOST_BARRIER)))
         return fail(MT_ERR_INVALID_ARG, "the counter barrier runs on plain streams with device-side waits: not with graphs or the host-side barrier");
+    if ((flags & MT_SCHED_COISSUE) && (flags & (MT_SCHED_GRAPH | MT_SCHED_STREAM_GRAPHS | MT_SCHED_TIME_FIRST_OP)))
+        return fail(MT_ERR_INVALID_ARG, "co-issue runs on plain streams without first-operator timing");
     if ((flags & MT_SCHED_HOST_BARRIER) && !(flags & MT_SCHED_PARALLEL_ISSUE))
         return fail(MT_ERR_INVALID_ARG, "the host-side barrier needs one issuing thread per stream (MT_SCHED_PARALLEL_ISSUE)");
     if ((flags & MT_SCHED_TIME_TENANTS) && (flags & (MT_SCHED_GRAPH | MT_SCHED_STREAM_GRAPHS)))
@@ -1875,6 +1900,44 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
             }
         };
         mark_pairs(sp.items, true);
+        // Co-issue: two tenants that share a stream and whose slices have the same length walk them together; operator i
+        // of the second runs inside the launch of operator i of the first where the two can (coissue_pair_ok), else
+        // right after it as a launch of its own.  The first tenant's items carry the mate, the second's stay in the list
+        // (they count as issued and carry the end-of-tenant timing) and launch nothing.
+        if (flags & MT_SCHED_COISSUE) {
+            int32_t hs[MT_MAX_TENANTS];
+            stream_map(n_tenants, &slices[(size_t)st * n_tenants * 2], conc, hs);
+            for (int sm = 0; sm < n_tenants; ++sm) {
+                std::vector<int> on;                         // tenants of this stream, in tenant order
+                for (int i = 0; i < n_tenants; ++i)
+                    if (hs[i] == sm) on.push_back(i);
+                for (size_t k = 0; k + 1 < on.size(); k += 2) {
+                    const int ta = on[k], tb = on[k + 1];
+                    const int ba = slices[((size_t)st * n_tenants + ta) * 2], ea = slices[((size_t)st * n_tenants + ta) * 2 + 1];
+                    const int bb = slices[((size_t)st * n_tenants + tb) * 2], eb = slices[((size_t)st * n_tenants + tb) * 2 + 1];
+                    if (ea - ba != eb - bb || ba != bb) continue;
+                    // operator i of the second tenant follows operator i of the first in the issue sequence
+                    std::vector<IssueItem> second(ea - ba), merged;
+                    for (const IssueItem &it : sp.items)
+                        if (it.tenant == tb) second[it.op - bb] = it;
+                    merged.reserve(sp.items.size());
+                    for (const IssueItem &it : sp.items) {
+                        if (it.tenant == tb) continue;
+                        merged.push_back(it);
+                        if (it.tenant != ta) continue;
+                        IssueItem other = second[it.op - ba];
+                        if (it.fuse == 0 && other.fuse == 0 &&
+                            coissue_pair_ok(ctx->tenants[ta]->args[it.op], ctx->tenants[tb]->args[it.op])) {
+                            merged.back().mate = tb;
+                            other.fuse = 1;
+                            ++s->n_fused;
+                        }
+                        merged.push_back(other);
+                    }
+                    sp.items.swap(merged);
+                }
+            }
+        }
         if ((flags & MT_SCHED_GRAPH) && n_tenants > 1) {
             s->alt_items.resize(n_stages);
             s->alt_items[st] = issue_order(n_tenants, &slices[(size_t)st * n_tenants * 2], conc, order == MT_ISSUE_BFS ? MT_ISSUE_DFS : MT_ISSUE_BFS);
