@@ -92,3 +92,34 @@ def test_same_length_different_shapes_are_not_paired():
         assert fused == [1]
     finally:
         mix.close()
+
+
+def test_coissued_split_layers_in_the_fixed_scratch_array():
+    # both tenants' layers are split along the reduction: the pair's partial sums and arrival counters live side by
+    # side, in the arenas (mt_run) or in the library's fixed array (mt_run_static_scratch)
+    def net():
+        g = GraphBuilder("small_split", "f16", 1, 7, 7, 256)
+        t = g.conv(0, 256, 3, pad=1, bn=True)
+        t = g.conv(t, 512, 3, pad=1, bn=True)
+        t = g.gap(t)
+        g.fc(t, 100)
+        return g.done()
+    print("case two split-K tenants", flush=True)
+    mix = Mix([net(), net()], seed=924)
+    try:
+        ctx = mix.ctx
+        assert any(ctx.op_info(0, i).split_k > 1 for i in range(ctx.lens()[0]))
+        s = ctx.schedule([[], []], 1, concurrency=[1], flags=CO, label="co-issue")
+        fused = compare(mix, ctx.sequential(), [s], "f16")
+        assert fused[0] >= 2
+        ref, _ = mix.run(ctx.sequential())
+        for _ in range(2):
+            outs = [ctx.make_output(t) for t in range(2)]
+            for o in outs:
+                o.fill_(float("nan"))
+            tm = ctx.run_static_scratch(s, mix.inputs, outs)
+            assert tm["n_fused"] == fused[0]
+            for t in range(2):
+                np.testing.assert_array_equal(ctx.output_to_numpy(t, outs[t]), ref[t])
+    finally:
+        mix.close()
