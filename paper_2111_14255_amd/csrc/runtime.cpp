@@ -2525,6 +2525,37 @@ int32_t mt_search(mt_ctx *ctx, const mt_search_opts *opts, const void *const *in
             }
         }
     }
+    if (playoff && opts->wave_priority_rounds > 0) {
+        // The descent over priorities accepts every candidate that measured lower, 4 n of them per round on short
+        // runs: what it returns is measured against the default priorities with the longer runs, twice in turn, and
+        // kept only if it is lower there too.
+        bool changed = false;
+        for (int i = 0; i < n; ++i) changed = changed || prio[i] != ((opts->flags & MT_SCHED_PRIORITIZE_SHORT) ? -1 : 0);
+        if (changed) {
+            mt_search_opts longer = *opts;
+            longer.runs = opts->playoff_runs >= 1 ? opts->playoff_runs : 21;
+            bool masked = false;
+            for (int i = 0; i < n; ++i) masked = masked || shares[i] != 0;
+            double with = 1e30, without = 1e30;
+            for (int turn = 0; turn < 2; ++turn) {
+                ProfileCost pa{ctx, &longer, inputs, outputs, n};
+                pa.conc = conc[0] == n ? nullptr : conc;
+                pa.prio = prio;
+                with = std::min(with, profile_schedule(&pa, best_pointers, masked ? shares : nullptr));
+                if (pa.rc != MT_OK) return pa.rc;
+                ProfileCost pb{ctx, &longer, inputs, outputs, n};
+                pb.conc = conc[0] == n ? nullptr : conc;
+                without = std::min(without, profile_schedule(&pb, best_pointers, masked ? shares : nullptr));
+                if (pb.rc != MT_OK) return pb.rc;
+            }
+            if (without <= with) {
+                for (int i = 0; i < n; ++i) prio[i] = (opts->flags & MT_SCHED_PRIORITIZE_SHORT) ? -1 : 0;
+                cost = without;
+            } else {
+                cost = with;
+            }
+        }
+    }
     if (playoff) {
         // Last check: the result as a whole (pointers, stream count, shares, priorities) against the plain configuration
         // it started from (everything in stage 1, one stream per tenant, no shares, default priorities), both measured
