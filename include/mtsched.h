@@ -140,7 +140,7 @@ typedef struct mt_timings {
     int32_t n_stages;
     float stage_ms[MT_MAX_STAGES];
     float first_op_done_ms[MT_MAX_TENANTS];
-    int32_t n_fused;       /* operators (of the n_launches issued) that ran inside a neighbouring operator's launch */
+    int32_t n_fused;       /* operators (of the n_launches issued) that ran inside another launch: a neighbouring operator's (fused pairs) or, under co-issue, the same operator of another tenant */
     float tenant_done_ms[MT_MAX_TENANTS];
 } mt_timings;
 
