@@ -331,8 +331,9 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
  * first tenant's slice and then the second's.  With this flag the two slices are walked together: operator i of both
  * runs as ONE launch whose workgroups are split between the two tenants, wherever the two operators have the same
  * kernel and launch shape (same architecture and batch: everything in their kernel arguments but the buffers is equal)
- * and the kernel has a two-operator form; the other operators of the pair are launched one after the other as
- * before.  Slices of different lengths are not co-issued.  Every operator computes exactly what it computes alone
+ * and the kernel has a two-operator form (every kernel of the 16-bit storage types that works on 16-byte vectors; not
+ * grouped convolutions, and not operators that run as a fused pair of their own tenant); the other operators are
+ * launched one tenant after the other inside the same walk.  Slices of different lengths are not co-issued.  Every operator computes exactly what it computes alone
  * (same tile program, same split, same summation order), so outputs are bit-identical; what changes is the number of
  * launches the command processor has to dispatch and complete, which is what bounds many small kernels on several
  * streams.  mt_timings.n_fused counts the operators that ran inside another tenant's launch.  Not with

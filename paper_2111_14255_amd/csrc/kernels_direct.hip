@@ -81,7 +81,7 @@ __global__ void __launch_bounds__(256) conv_direct_kernel(OpArgs a) {
 // Depthwise convolution, any window.  One thread per (pixel, V-channel vector); weights repacked as [R][S][C] so
 // that the weight vector of a tap is one contiguous load, shared by every pixel through the caches.
 template <typename T, int V>
-__global__ void __launch_bounds__(256) dwconv_kernel(OpArgs a) {
+__device__ __forceinline__ void dwconv_kernel_body(const OpArgs &a) {
     set_wave_priority(a.prio);
     const int CV = a.C / V;
     const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
@@ -117,13 +117,22 @@ __global__ void __launch_bounds__(256) dwconv_kernel(OpArgs a) {
     }
     store_pack<T, V>((T *)a.y + m * a.y_ct + a.y_coff + c0, acc);
 }
+template <typename T, int V>
+__global__ void __launch_bounds__(256) dwconv_kernel(OpArgs a) {
+    dwconv_kernel_body<T, V>(a);
+}
+// two operators of equal launch shape in one launch, one per value of blockIdx.y
+template <typename T, int V>
+__global__ void __launch_bounds__(256) dwconv_pair_kernel(OpArgsPair p) {
+    dwconv_kernel_body<T, V>(p.a[blockIdx.y]);
+}
 
 // ---------------------------------------------------------------------------------------------
 // Fixed-window variants (KS x KS known at compile time, 16-byte channel vectors).  All taps are loaded first,
 // from clamped addresses and without branches, so the loads of a thread overlap instead of each waiting for the
 // one before it; taps in the padding halo are masked afterwards.  Tap order of the sums is the same (r, s).
 template <typename T, int V, int KS>
-__global__ void __launch_bounds__(256) dwconv_fixed_kernel(OpArgs a) {
+__device__ __forceinline__ void dwconv_fixed_kernel_body(const OpArgs &a) {
     set_wave_priority(a.prio);
     const int CV = a.C / V;
     const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
@@ -164,6 +173,15 @@ __global__ void __launch_bounds__(256) dwconv_fixed_kernel(OpArgs a) {
     for (int i = 0; i < V; ++i) acc[i] = apply_act(acc[i] + bv[i], a.act);
     store_pack<T, V>((T *)a.y + m * a.y_ct + a.y_coff + c0, acc);
 }
+template <typename T, int V, int KS>
+__global__ void __launch_bounds__(256) dwconv_fixed_kernel(OpArgs a) {
+    dwconv_fixed_kernel_body<T, V, KS>(a);
+}
+// two operators of equal launch shape in one launch, one per value of blockIdx.y
+template <typename T, int V, int KS>
+__global__ void __launch_bounds__(256) dwconv_fixed_pair_kernel(OpArgsPair p) {
+    dwconv_fixed_kernel_body<T, V, KS>(p.a[blockIdx.y]);
+}
 
 // 3x3 depthwise convolution with padding 1 on a large map: a thread owns one (column, channel vector) of a band of
 // `rows` output rows and keeps the three input rows of the window in registers, so that an output row costs one new
@@ -177,7 +195,7 @@ __global__ void __launch_bounds__(256) dwconv_fixed_kernel(OpArgs a) {
 typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
 
 template <typename T, int ST>
-__global__ void __launch_bounds__(256) dwconv3_rows_kernel(OpArgs a, int rows, int bands) {
+__device__ __forceinline__ void dwconv3_rows_kernel_body(const OpArgs &a, int rows, int bands) {
     static_assert(sizeof(T) == 2, "16-byte vectors of 8 channels");
     constexpr int V = 8;
     set_wave_priority(a.prio);
@@ -265,6 +283,15 @@ __global__ void __launch_bounds__(256) dwconv3_rows_kernel(OpArgs a, int rows, i
         }
     }
 }
+template <typename T, int ST>
+__global__ void __launch_bounds__(256) dwconv3_rows_kernel(OpArgs a, int rows, int bands) {
+    dwconv3_rows_kernel_body<T, ST>(a, rows, bands);
+}
+// two operators of equal launch shape in one launch, one per value of blockIdx.y
+template <typename T, int ST>
+__global__ void __launch_bounds__(256) dwconv3_rows_pair_kernel(OpArgsPair p, int rows, int bands) {
+    dwconv3_rows_kernel_body<T, ST>(p.a[blockIdx.y], rows, bands);
+}
 
 // Output rows per thread of the banded 3x3 depthwise kernel: 1 (the one-pixel kernel) unless the map is large enough
 // to leave at least 65536 threads with 2 or 4 rows each.  A pure function of the operator's shape.
@@ -327,7 +354,7 @@ __global__ void __launch_bounds__(256) pool_fixed_pair_kernel(OpArgsPair p) {
 // ---------------------------------------------------------------------------------------------
 // Window pooling: one thread per (output pixel, V-channel vector).
 template <typename T, int V, bool IS_MAX>
-__global__ void __launch_bounds__(256) pool_kernel(OpArgs a) {
+__device__ __forceinline__ void pool_kernel_body(const OpArgs &a) {
     set_wave_priority(a.prio);
     const int CV = a.C / V;
     const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
@@ -360,6 +387,15 @@ __global__ void __launch_bounds__(256) pool_kernel(OpArgs a) {
         for (int i = 0; i < V; ++i) acc[i] = acc[i] / (float)cnt;
     }
     store_pack<T, V>((T *)a.y + m * a.y_ct + a.y_coff + c0, acc);
+}
+template <typename T, int V, bool IS_MAX>
+__global__ void __launch_bounds__(256) pool_kernel(OpArgs a) {
+    pool_kernel_body<T, V, IS_MAX>(a);
+}
+// two operators of equal launch shape in one launch, one per value of blockIdx.y
+template <typename T, int V, bool IS_MAX>
+__global__ void __launch_bounds__(256) pool_pair_kernel(OpArgsPair p) {
+    pool_kernel_body<T, V, IS_MAX>(p.a[blockIdx.y]);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -424,7 +460,7 @@ __global__ void __launch_bounds__(256) gap_pair_kernel(OpArgsPair p, int lanes_c
 // One thread per (pixel, V-channel vector); it loads its own vector and the two neighbouring vectors (the window
 // reaches at most 7 channels to either side, V >= 8 for the vector form), all before any arithmetic.
 template <typename T, int V>
-__global__ void __launch_bounds__(256) lrn_kernel(OpArgs a) {
+__device__ __forceinline__ void lrn_kernel_body(const OpArgs &a) {
     set_wave_priority(a.prio);
     const int CV = a.C / V;
     const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
@@ -477,10 +513,19 @@ __global__ void __launch_bounds__(256) lrn_kernel(OpArgs a) {
     }
     store_pack<T, V>((T *)a.y + (int64_t)m * a.y_ct + a.y_coff + c0, out);
 }
+template <typename T, int V>
+__global__ void __launch_bounds__(256) lrn_kernel(OpArgs a) {
+    lrn_kernel_body<T, V>(a);
+}
+// two operators of equal launch shape in one launch, one per value of blockIdx.y
+template <typename T, int V>
+__global__ void __launch_bounds__(256) lrn_pair_kernel(OpArgsPair p) {
+    lrn_kernel_body<T, V>(p.a[blockIdx.y]);
+}
 
 // Element-wise sum of two tensors of the same shape, activation, one rounding.
 template <typename T, int V>
-__global__ void __launch_bounds__(256) add_kernel(OpArgs a) {
+__device__ __forceinline__ void add_kernel_body(const OpArgs &a) {
     set_wave_priority(a.prio);
     const int CV = a.C / V;
     const uint32_t total = (uint32_t)a.N * a.P * a.Q * CV;
@@ -494,6 +539,15 @@ __global__ void __launch_bounds__(256) add_kernel(OpArgs a) {
 #pragma unroll
     for (int i = 0; i < V; ++i) u[i] = apply_act(u[i] + v[i], a.act);
     store_pack<T, V>((T *)a.y + (int64_t)m * a.y_ct + a.y_coff + c0, u);
+}
+template <typename T, int V>
+__global__ void __launch_bounds__(256) add_kernel(OpArgs a) {
+    add_kernel_body<T, V>(a);
+}
+// two operators of equal launch shape in one launch, one per value of blockIdx.y
+template <typename T, int V>
+__global__ void __launch_bounds__(256) add_pair_kernel(OpArgsPair p) {
+    add_kernel_body<T, V>(p.a[blockIdx.y]);
 }
 
 // Records the hardware id registers of the compute unit each one-wavefront workgroup runs on, then keeps the unit
@@ -538,15 +592,15 @@ static int launch_typed(const OpArgs &a, hipStream_t st, const OpArgs *mate) {
                     if (rows > 1) {
                         const int bands = (a.P + rows - 1) / rows;
                         const int64_t tb = (int64_t)a.N * bands * a.Q * (a.C / VMAX);
-                        if (a.sh == 1) hipLaunchKernelGGL((dwconv3_rows_kernel<T, 1>), blocks(tb), block, 0, st, a, rows, bands);
-                        else hipLaunchKernelGGL((dwconv3_rows_kernel<T, 2>), blocks(tb), block, 0, st, a, rows, bands);
+                        if (a.sh == 1) MT_LAUNCH((dwconv3_rows_kernel<T, 1>), (dwconv3_rows_pair_kernel<T, 1>), blocks(tb), block, st, a, mate, rows, bands);
+                        else MT_LAUNCH((dwconv3_rows_kernel<T, 2>), (dwconv3_rows_pair_kernel<T, 2>), blocks(tb), block, st, a, mate, rows, bands);
                         break;
                     }
                 }
                 if (a.R == 3 && a.S == 3)
-                    hipLaunchKernelGGL((dwconv_fixed_kernel<T, VMAX, 3>), blocks(th), block, 0, st, a);
+                    MT_LAUNCH((dwconv_fixed_kernel<T, VMAX, 3>), (dwconv_fixed_pair_kernel<T, VMAX, 3>), blocks(th), block, st, a, mate);
                 else
-                    hipLaunchKernelGGL((dwconv_kernel<T, VMAX>), blocks(th), block, 0, st, a);
+                    MT_LAUNCH((dwconv_kernel<T, VMAX>), (dwconv_pair_kernel<T, VMAX>), blocks(th), block, st, a, mate);
             } else {
                 hipLaunchKernelGGL((dwconv_kernel<T, 1>), blocks((int64_t)a.N * a.P * a.Q * a.C), block, 0, st, a);
             }
@@ -564,9 +618,9 @@ static int launch_typed(const OpArgs &a, hipStream_t st, const OpArgs *mate) {
                 else if (!mx && a.R == 3 && a.S == 3)
                     MT_LAUNCH((pool_fixed_kernel<T, VMAX, false, 3>), (pool_fixed_pair_kernel<T, VMAX, false, 3>), blocks(th), block, st, a, mate);
                 else if (mx)
-                    hipLaunchKernelGGL((pool_kernel<T, VMAX, true>), blocks(th), block, 0, st, a);
+                    MT_LAUNCH((pool_kernel<T, VMAX, true>), (pool_pair_kernel<T, VMAX, true>), blocks(th), block, st, a, mate);
                 else
-                    hipLaunchKernelGGL((pool_kernel<T, VMAX, false>), blocks(th), block, 0, st, a);
+                    MT_LAUNCH((pool_kernel<T, VMAX, false>), (pool_pair_kernel<T, VMAX, false>), blocks(th), block, st, a, mate);
             } else {
                 const int64_t th = (int64_t)a.N * a.P * a.Q * a.C;
                 if (mx)
@@ -596,8 +650,8 @@ static int launch_typed(const OpArgs &a, hipStream_t st, const OpArgs *mate) {
             if constexpr (VMAX >= 8) {          // the vector form of the normalisation needs the window inside one neighbour vector
                 if (a.vec == VMAX) {
                     const int64_t th = (int64_t)a.N * a.P * a.Q * (a.C / VMAX);
-                    if (lrn) hipLaunchKernelGGL((lrn_kernel<T, VMAX>), blocks(th), block, 0, st, a);
-                    else hipLaunchKernelGGL((add_kernel<T, VMAX>), blocks(th), block, 0, st, a);
+                    if (lrn) MT_LAUNCH((lrn_kernel<T, VMAX>), (lrn_pair_kernel<T, VMAX>), blocks(th), block, st, a, mate);
+                    else MT_LAUNCH((add_kernel<T, VMAX>), (add_pair_kernel<T, VMAX>), blocks(th), block, st, a, mate);
                     done = true;
                 }
             }

@@ -650,7 +650,7 @@ __device__ __forceinline__ void unpack8(u32x4 v, float (&f)[8]) {
 }
 
 template <typename T, int MB, int ROWS, bool STREAM_W>
-__global__ void __launch_bounds__(256) gemv_kernel(OpArgs a) {
+__device__ __forceinline__ void gemv_kernel_body(const OpArgs &a) {
     set_wave_priority(a.prio);
     const int wave = (int)(((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6);
     const int lane = threadIdx.x & 63;
@@ -732,6 +732,15 @@ __global__ void __launch_bounds__(256) gemv_kernel(OpArgs a) {
         }
     }
 }
+template <typename T, int MB, int ROWS, bool STREAM_W>
+__global__ void __launch_bounds__(256) gemv_kernel(OpArgs a) {
+    gemv_kernel_body<T, MB, ROWS, STREAM_W>(a);
+}
+// two operators of equal launch shape in one launch, one per value of blockIdx.y
+template <typename T, int MB, int ROWS, bool STREAM_W>
+__global__ void __launch_bounds__(256) gemv_pair_kernel(OpArgsPair p) {
+    gemv_kernel_body<T, MB, ROWS, STREAM_W>(p.a[blockIdx.y]);
+}
 
 // ---------------------------------------------------------------------------------------------
 // ---------------------------------------------------------------------------------------------
@@ -743,7 +752,7 @@ __global__ void __launch_bounds__(256) gemv_kernel(OpArgs a) {
 // SLICES = 4 (long reductions): the four waves split the reduction of one tile into four contiguous ranges and wave 0
 // adds the partial sums in range order through LDS.
 template <typename T, int SLICES>
-__global__ void __launch_bounds__(256) pw_direct_kernel(OpArgs a) {
+__device__ __forceinline__ void pw_direct_kernel_body(const OpArgs &a) {
     set_wave_priority(a.prio);
     typedef typename Mma<T, 16>::Acc Acc;
     constexpr int CH = 8;                                // reduction steps whose loads are in flight together
@@ -834,6 +843,15 @@ __global__ void __launch_bounds__(256) pw_direct_kernel(OpArgs a) {
         }
     }
 }
+template <typename T, int SLICES>
+__global__ void __launch_bounds__(256) pw_direct_kernel(OpArgs a) {
+    pw_direct_kernel_body<T, SLICES>(a);
+}
+// two operators of equal launch shape in one launch, one per value of blockIdx.y
+template <typename T, int SLICES>
+__global__ void __launch_bounds__(256) pw_direct_pair_kernel(OpArgsPair p) {
+    pw_direct_kernel_body<T, SLICES>(p.a[blockIdx.y]);
+}
 
 template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES, int AMODE, int WK = 1>
 __global__ void __launch_bounds__(256 * WK) igemm_kernel(OpArgs a) {
@@ -876,16 +894,16 @@ static int launch_igemm_typed(const OpArgs &a, hipStream_t st, const OpArgs *mat
         case K_IGEMM_64x16: launch_cfg<T, 64, 16, 4, 1, 16, 4>(a, st, mate); break;
         case K_IGEMM_PW: {
             const dim3 grid(a.grid_x), block(256);
-            if (a.split_k > 1) hipLaunchKernelGGL((pw_direct_kernel<T, 4>), grid, block, 0, st, a);
-            else hipLaunchKernelGGL((pw_direct_kernel<T, 1>), grid, block, 0, st, a);
+            if (a.split_k > 1) MT_LAUNCH((pw_direct_kernel<T, 4>), (pw_direct_pair_kernel<T, 4>), grid, block, st, a, mate);
+            else MT_LAUNCH((pw_direct_kernel<T, 1>), (pw_direct_pair_kernel<T, 1>), grid, block, st, a, mate);
             break;
         }
         case K_GEMV: {
             const dim3 grid(a.grid_x), block(256);
             const bool stream_w = (int64_t)a.n_pad * a.k_pad * 2 >= (16ll << 20);
             auto go = [&]<int MB>() {
-                if (stream_w) hipLaunchKernelGGL((gemv_kernel<T, MB, 2, true>), grid, block, 0, st, a);
-                else hipLaunchKernelGGL((gemv_kernel<T, MB, 2, false>), grid, block, 0, st, a);
+                if (stream_w) MT_LAUNCH((gemv_kernel<T, MB, 2, true>), (gemv_pair_kernel<T, MB, 2, true>), grid, block, st, a, mate);
+                else MT_LAUNCH((gemv_kernel<T, MB, 2, false>), (gemv_pair_kernel<T, MB, 2, false>), grid, block, st, a, mate);
             };
             if (a.N <= 1) go.template operator()<1>();
             else if (a.N <= 2) go.template operator()<2>();
@@ -1397,19 +1415,18 @@ int launch_igemm(const OpArgs &a, void *stream, const OpArgs *mate) {
     return (int)hipErrorInvalidValue;
 }
 
-// Kernels that exist in a two-operator form (the tile kernels with 16-byte or tap-uniform gathers, the patch-staged and
-// resident-filter kernels, the first-layer kernel, the fixed-window pooling and the global average pooling), for the
-// 16-bit storage types.
+// Kernels that exist in a two-operator form: every kernel of the 16-bit storage types that works on 16-byte vectors
+// (the tile kernels with 16-byte or tap-uniform gathers, the small-map 1x1 kernel, the weight-streaming kernel, the
+// patch-staged, resident-filter and first-layer kernels, depthwise, pooling, normalisation and add).  Not: fp32 storage,
+// grouped convolutions (several launches per operator), element-wise gathers and scalar channel counts.
 bool coissue_supported(const OpArgs &a) {
     if (a.dtype != MT_F16 && a.dtype != MT_BF16) return false;
     if (a.groups > 1) return false;
     switch (a.kernel_id) {
         case K_IGEMM_128x128: case K_IGEMM_128x64: case K_IGEMM_64x64: case K_IGEMM_64x16:
             return a.vec_a == A_UNIFORM || a.vec_a == A_VEC8;
-        case K_PCONV: case K_ROWB: case K_STEM: return true;
-        case K_MAXPOOL: return a.vec == 8 && ((a.R == 2 && a.S == 2) || (a.R == 3 && a.S == 3));
-        case K_AVGPOOL: return a.vec == 8 && a.R == 3 && a.S == 3;
-        case K_GAP: return a.vec == 8;
+        case K_IGEMM_PW: case K_GEMV: case K_PCONV: case K_ROWB: case K_STEM: return true;
+        case K_DWCONV: case K_MAXPOOL: case K_AVGPOOL: case K_GAP: case K_LRN: case K_ADD: return a.vec == 8;
         default: return false;
     }
 }

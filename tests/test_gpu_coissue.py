@@ -31,8 +31,7 @@ def compare(mix, plain, scheds, dtype):
 
 
 def test_equal_tenants_are_paired_and_keep_their_bits():
-    # four ResNet-50 with their own weights and inputs; at this batch the 1x1 layers on the small maps run on the
-    # kernel without LDS tiles, which has no two-operator form
+    # four ResNet-50 with their own weights and inputs: every operator has a two-operator form
     print("case 4 x resnet50 batch 2 bf16", flush=True)
     mix = Mix([zoo.resnet50("bf16", 2) for _ in range(4)], seed=921)
     try:
@@ -45,7 +44,7 @@ def test_equal_tenants_are_paired_and_keep_their_bits():
                          ctx.schedule([[] for _ in lens], 1, concurrency=[1], flags=CO, label="co-issue, one stream"),
                          ctx.schedule(two, 2, concurrency=[2, 2], flags=CO | PAR, label="co-issue, two stages"),
                          ctx.schedule([[] for _ in lens], 1, flags=CO, label="co-issue asked for, a stream per tenant")], "bf16")
-        assert fused[0] == fused[1] == fused[2] == fused[3] and 2 * 20 <= fused[0] <= 2 * lens[0]   # two pairs of tenants
+        assert fused[:4] == [2 * lens[0]] * 4            # two pairs of tenants: one of every two operators runs inside its mate's launch
         assert fused[4] == 0                              # nothing shares a stream
         with pytest.raises(B.MtError):
             ctx.schedule([[] for _ in lens], 1, concurrency=[2], flags=CO | B.MT_SCHED_GRAPH)
@@ -54,9 +53,9 @@ def test_equal_tenants_are_paired_and_keep_their_bits():
 
 
 def test_mixed_tenants_pair_where_they_can_and_stay_in_order_where_not():
-    # ResNet-18 twice and MobileNetV2 twice on one stream: neighbours (0, 1) and (2, 3) are walked together; depthwise and
-    # the small 1x1 kernels have no two-operator form and are launched one after the other, inside the same walk;
-    # also together with the fused pairs of one tenant (1x1 + depthwise, convolution + pooling)
+    # ResNet-18 twice and MobileNetV2 twice on one stream: neighbours (0, 1) and (2, 3) are walked together; with the
+    # fused pairs of one tenant (1x1 + depthwise, convolution + pooling) the operators of such a pair are not co-issued
+    # and are launched one tenant after the other, inside the same walk
     print("case r18 r18 mbv2 mbv2 f16", flush=True)
     mix = Mix([zoo.resnet18("f16", 1), zoo.resnet18("f16", 1), zoo.BUILDERS["mobilenetv2"]("f16", 1), zoo.BUILDERS["mobilenetv2"]("f16", 1)], seed=922)
     try:
@@ -67,7 +66,7 @@ def test_mixed_tenants_pair_where_they_can_and_stay_in_order_where_not():
                         [ctx.schedule([[] for _ in lens], 1, concurrency=[1], flags=CO, label="co-issue, one stream"),
                          ctx.schedule([[] for _ in lens], 1, concurrency=[1], flags=CO | FE, label="co-issue and fused pairs"),
                          ctx.schedule([[] for _ in lens], 1, concurrency=[2], flags=CO | PAR, label="co-issue, unequal neighbours")], "f16")
-        assert 0 < fused[0] < lens[0] + lens[2]           # some operators pair, the depthwise ones do not
+        assert fused[0] == lens[0] + lens[2]              # every operator of tenants 1 and 3 runs inside its mate's launch
         assert fused[1] > 0
         assert fused[2] == 0                              # longest first puts a ResNet-18 beside a MobileNetV2: nothing to pair
     finally:
@@ -87,9 +86,8 @@ def test_same_length_different_shapes_are_not_paired():
     try:
         ctx = mix.ctx
         fused = compare(mix, ctx.sequential(), [ctx.schedule([[], []], 1, concurrency=[1], flags=CO, label="co-issue")], "f16")
-        # the convolutions differ in width; pooling and classifier are the same operator in both tenants, but the
-        # weight-streaming kernel of a two-image classifier has no two-operator form: only the pooling pairs
-        assert fused == [1]
+        # the convolutions differ in width; pooling and classifier are the same operator in both tenants
+        assert fused == [2]
     finally:
         mix.close()
 
@@ -121,5 +119,24 @@ def test_coissued_split_layers_in_the_fixed_scratch_array():
             assert tm["n_fused"] == fused[0]
             for t in range(2):
                 np.testing.assert_array_equal(ctx.output_to_numpy(t, outs[t]), ref[t])
+    finally:
+        mix.close()
+
+
+@pytest.mark.parametrize("arch,dtype", [("alexnet_published", "bf16"), ("inceptionv3", "bf16"), ("vgg16", "f16"), ("tinyD", "f16")])
+def test_every_kernel_family_in_its_two_operator_form(arch, dtype):
+    # grouped convolutions and normalisation (AlexNet as published), asymmetric windows, average pooling and concat
+    # writes (Inception-v3), the weight-streaming classifier and the pooled epilogue (VGG-16), add and 5x5 depthwise (tinyD)
+    print("case 2 x", arch, dtype, flush=True)
+    mix = Mix([zoo.BUILDERS[arch](dtype, 1), zoo.BUILDERS[arch](dtype, 1)], seed=925)
+    try:
+        ctx = mix.ctx
+        lens = ctx.lens()
+        fused = compare(mix, ctx.sequential(),
+                        [ctx.schedule([[], []], 1, concurrency=[1], flags=CO, label="co-issue"),
+                         ctx.schedule([[], []], 1, concurrency=[1], flags=CO | B.MT_SCHED_FUSE_POOL | B.MT_SCHED_FUSE_EXPAND, label="co-issue and fused pairs"),
+                         ctx.schedule([[lens[0] // 3, 2 * lens[0] // 3]] * 2, 3, concurrency=[1, 1, 1], flags=CO | PAR, label="co-issue, three stages")], dtype)
+        assert 0 < fused[0] <= lens[0] and fused[2] == fused[0]
+        print("  operators inside the mate's launch: %d of %d" % (fused[0], lens[0]), flush=True)
     finally:
         mix.close()
