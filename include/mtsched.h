@@ -336,7 +336,8 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
  * launched one tenant after the other inside the same walk.  Slices of different lengths are not co-issued.  Every operator computes exactly what it computes alone
  * (same tile program, same split, same summation order), so outputs are bit-identical; what changes is the number of
  * launches the command processor has to dispatch and complete, which is what bounds many small kernels on several
- * streams.  mt_timings.n_fused counts the operators that ran inside another tenant's launch.  Not with
+ * streams.  A two-operator launch runs at the wave priority of the first of its two tenants.  mt_timings.n_fused
+ * counts the operators that ran inside another tenant's launch.  Not with
  * MT_SCHED_GRAPH, MT_SCHED_STREAM_GRAPHS or MT_SCHED_TIME_FIRST_OP. */
 #define MT_SCHED_COISSUE 4096
 int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, const int32_t *pointers,
