@@ -11,6 +11,8 @@
   barriers what a stage barrier costs (Sec. III-B "Stage"): the probe of mt_probe_barrier_cost for 1..8 streams and
            even-split staged schedules of a workload under the event, counter and host-side barriers
   layers   per-operator table of one tenant: GEMM shape, kernel, time alone on the GPU, fraction of its own roofline bound
+  streams  which streams can run side by side (mt_probe_stream_conflicts: the dispatch pipes), and a workload in one
+           stage on 1 .. n streams, with the tenants that share a stream issued one after the other or co-issued
   benchsum markdown table of bench.py outputs (all schedules and kernel families of each workload)
   rocprof  turns the CSV files of `rocprofv3 --kernel-trace --stats` / `--pmc ...` runs of `bench.py --roofline-only`
            into the per-family summary kept under profiles/
@@ -21,6 +23,7 @@
     python -m paper_2111_14255_amd.report fusion --config cfg2
     python -m paper_2111_14255_amd.report barriers --config cfg3
     python -m paper_2111_14255_amd.report layers --config cfg5 --tenant 0
+    python -m paper_2111_14255_amd.report streams --config cfg5
     python -m paper_2111_14255_amd.report rocprof --config cfg5 --dir <directory with the rocprofv3 output>
 """
 import argparse
@@ -209,6 +212,68 @@ def report_mixes(args):
             conc[0], "/".join(str(v) for v in shares), seq["median"] / best, dt))
         sys.stdout.flush()
         ctx.close()
+
+
+def report_streams(args):
+    import ctypes as C
+    import hashlib
+    from synth import configs
+    from . import binding as B
+    cfg = configs.ALL[args.config]
+    ctx, specs, inputs, outputs = _setup(cfg)
+    n = len(specs)
+    print("# Streams that run side by side, stream counts and co-issue, workload %s (%s), MI355X" % (cfg.name, " + ".join(cfg.tenants)))
+    print()
+    print("Command: `python -m paper_2111_14255_amd.report streams --config %s`" % args.config)
+    print()
+    print("## Pairs of new streams (`mt_probe_stream_conflicts`)")
+    print()
+    print("Twelve new unmasked streams; every cell: us per round of 16 rounds in which the two streams launch one one-workgroup "
+          "kernel each, every stream recording its own end and the host waiting (the diagonal: the stream alone).  A pair at "
+          "twice the single figure is served one stream at a time: the two sit on the same dispatch pipe.  The library "
+          "classifies its tenant streams this way when it creates them and gives tenant index i a stream of class i % 4.")
+    print()
+    m = 12
+    single = (C.c_float * m)()
+    pair = (C.c_float * (m * m))()
+    B.check(ctx.lib.mt_probe_stream_conflicts(ctx.h, m, 16, single, pair))
+    lo = min(single)
+    cls = []
+    for i in range(m):                      # classes by the first earlier stream this one conflicts with
+        k = next((cls[j] for j in range(i) if pair[i * m + j] > 1.5 * lo), None)
+        cls.append(max(cls) + 1 if k is None and cls else (0 if k is None else k))
+    print("| stream | class | " + " | ".join(str(j) for j in range(m)) + " |")
+    print("|---|---|" + "---|" * m)
+    for i in range(m):
+        print("| %d | %d | " % (i, cls[i]) + " | ".join("%.1f" % pair[i * m + j] for j in range(m)) + " |")
+    print()
+    print("Classes found: %d, sizes %s." % (max(cls) + 1, " / ".join(str(cls.count(k)) for k in range(max(cls) + 1))))
+    print()
+    print("## One stage on c streams, tenants of a stream one after the other or co-issued")
+    print()
+    print("Median makespan of 30 runs, ms; one issuing host thread per stream.  Co-issue (`MT_SCHED_COISSUE`): two tenants of "
+          "equal architecture on one stream run operator i of both as one launch.  `inside` = operators that ran inside a "
+          "mate's launch, of %d.  The last column: md5 of all tenants' output bits, which must not change along a row or a column." % sum(ctx.lens()))
+    print()
+    print("| streams | one after the other | co-issued | inside | ratio | output bits |")
+    print("|---|---|---|---|---|---|")
+    FL = B.MT_SCHED_PARALLEL_ISSUE | B.MT_SCHED_HOST_BARRIER
+    import torch
+    for c in [v for v in (1, 2, 3, 4, 5, 6, 8) if v <= n]:
+        row, digests, inside = [], set(), 0
+        for flags in (FL, FL | B.MT_SCHED_COISSUE):
+            sched = ctx.schedule([[] for _ in specs], 1, concurrency=[c], flags=flags)
+            for o in outputs:
+                o.zero_()
+            r = _time(ctx, sched, inputs, outputs, steps=30)
+            torch.cuda.synchronize()
+            digests.add(hashlib.md5(b"".join(ctx.output_to_numpy(t, outputs[t]).tobytes() for t in range(n))).hexdigest()[:8])
+            inside = ctx.run(sched, inputs, outputs)["n_fused"]
+            row.append(r["median"])
+            sched.close()
+        print("| %d | %.3f | %.3f | %d | %.2f | %s |" % (c, row[0], row[1], inside, row[0] / row[1], " / ".join(sorted(digests))))
+        sys.stdout.flush()
+    ctx.close()
 
 
 def report_fusion(args):
@@ -554,7 +619,7 @@ def report_benchsum(args):
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("what", choices=["search", "issue", "mixes", "fusion", "barriers", "layers", "rocprof", "benchsum"])
+    ap.add_argument("what", choices=["search", "issue", "mixes", "fusion", "barriers", "layers", "streams", "rocprof", "benchsum"])
     ap.add_argument("--config", default="cfg2")
     ap.add_argument("--rounds", type=int, default=3)
     ap.add_argument("--candidates", type=int, default=8)
@@ -566,7 +631,7 @@ def main():
     ap.add_argument("--dir", default="", help="rocprof: directory with live.json, trace/ and pmc_*/")
     ap.add_argument("--traffic-out", default="", help="rocprof: write the per-family HBM bytes here (profiles/traffic_<workload>.json)")
     args = ap.parse_args()
-    {"search": report_search, "issue": report_issue, "mixes": report_mixes, "fusion": report_fusion, "barriers": report_barriers,
+    {"search": report_search, "issue": report_issue, "mixes": report_mixes, "fusion": report_fusion, "barriers": report_barriers, "streams": report_streams,
      "layers": report_layers, "rocprof": report_rocprof, "benchsum": report_benchsum}[args.what](args)
 
 
