@@ -327,18 +327,18 @@ int32_t mt_tenant_read_tensor(mt_ctx *ctx, int32_t tenant, int32_t tensor_id, vo
  * MT_SCHED_HOST_BARRIER.  MT_ERR_HIP from mt_schedule_create if the device has no stream memory operations. */
 #define MT_SCHED_COUNTER_BARRIER 2048
 /* Co-issue (an issue mechanism of this runtime; the paper issues one launch per operator, Sec. III-D): where a stage
- * puts two tenants on one stream (stage_concurrency below the number of tenants with work), the stream would run the
- * first tenant's slice and then the second's.  With this flag the two slices are walked together: operator i of both
- * runs as ONE launch whose workgroups are split between the two tenants, wherever the two operators have the same
- * kernel and launch shape (same architecture and batch: everything in their kernel arguments but the buffers is equal)
- * and the kernel has a two-operator form (every kernel of the 16-bit storage types that works on 16-byte vectors; not
- * grouped convolutions, and not operators that run as a fused pair of their own tenant); the other operators are
- * launched one tenant after the other inside the same walk.  Slices of different lengths are not co-issued.  Every operator computes exactly what it computes alone
- * (same tile program, same split, same summation order), so outputs are bit-identical; what changes is the number of
- * launches the command processor has to dispatch and complete, which is what bounds many small kernels on several
- * streams.  A two-operator launch runs at the wave priority of the first of its two tenants.  mt_timings.n_fused
- * counts the operators that ran inside another tenant's launch.  Not with
- * MT_SCHED_GRAPH, MT_SCHED_STREAM_GRAPHS or MT_SCHED_TIME_FIRST_OP. */
+ * puts several tenants on one stream (stage_concurrency below the number of tenants with work), the stream would run
+ * the first tenant's slice, then the second's, and so on.  With this flag up to four neighbouring tenants of a stream
+ * whose slices cover the same operator range are walked together: operator i of all of them runs as ONE launch whose
+ * workgroups are split between the tenants, wherever the operators have the same kernel and launch shape as the first
+ * tenant's (same architecture and batch: everything in their kernel arguments but the buffers is equal) and the kernel
+ * has a several-operator form (every kernel of the 16-bit storage types that works on 16-byte vectors; not grouped
+ * convolutions, and not operators that run as a fused pair of their own tenant); the other operators are launched
+ * one tenant after the other inside the same walk.  Every operator computes exactly what it computes alone (same tile
+ * program, same split, same summation order), so outputs are bit-identical; what changes is the number of launches the
+ * command processor has to dispatch and complete, which is what bounds many small kernels on several streams.  Such a
+ * launch runs at the wave priority of the first of its tenants.  mt_timings.n_fused counts the operators that ran
+ * inside another tenant's launch.  Not with MT_SCHED_GRAPH, MT_SCHED_STREAM_GRAPHS or MT_SCHED_TIME_FIRST_OP. */
 #define MT_SCHED_COISSUE 4096
 int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, const int32_t *pointers,
                            const int32_t *stage_concurrency, const int32_t *cu_share,

@@ -36,16 +36,17 @@ __device__ __forceinline__ void set_wave_priority(int p) {
     else if (p == 3) __builtin_amdgcn_s_setprio(3);
 }
 
-// Launches K1 with the operator's arguments, or, when `mate` points to a second operator of equal launch shape, K2
-// (the two-operator form of the same kernel) on a grid of twice the workgroups, blockIdx.y naming the operator.
+// Launches K1 with the operator's arguments, or, when `mate` points to n_mates (1 .. 3) further operators of equal
+// launch shape, K2 (the several-operator form of the same kernel) on a grid of 1 + n_mates times the workgroups,
+// blockIdx.y naming the operator.
 #define MT_LAUNCH(K1, K2, grid, block, st, a, mate, ...)                                    \
     do {                                                                                    \
         if (mate) {                                                                         \
             OpArgsPair pair_;                                                               \
             pair_.a[0] = (a);                                                               \
-            pair_.a[1] = *(mate);                                                           \
+            for (int i_ = 0; i_ < n_mates; ++i_) pair_.a[1 + i_] = (mate)[i_];              \
             dim3 grid2_ = (grid);                                                           \
-            grid2_.y = 2;                                                                   \
+            grid2_.y = 1 + n_mates;                                                         \
             hipLaunchKernelGGL(K2, grid2_, block, 0, st, pair_ __VA_OPT__(, ) __VA_ARGS__); \
         } else {                                                                            \
             hipLaunchKernelGGL(K1, grid, block, 0, st, a __VA_OPT__(, ) __VA_ARGS__);       \

@@ -15,7 +15,7 @@ int32_t fail(int32_t code, const std::string &msg);
 // ---- scheduling layer (host only) ------------------------------------------------------
 struct IssueItem {
     int32_t stream, tenant, op;
-    int32_t mate = -1;     // runtime only: tenant whose operator of the same index runs in this item's launch (co-issue), -1 = none
+    int32_t mates[3] = {-1, -1, -1};   // runtime only: tenants whose operator of the same index runs in this item's launch (co-issue), -1 = none
     int32_t fuse = 0;      // runtime only: 1 = issued as part of a neighbour's launch, 2 / 3 = launches the pair (op - 1, op): depthwise + 1x1 / 1x1 + depthwise, 4 = convolution launched with the pooling operator op + 1 in its epilogue (that operator then carries 1)
 };
 int32_t validate_pointers(int32_t n_tenants, const int32_t *lens, int32_t n_stages, const int32_t *pointers);
@@ -107,10 +107,11 @@ struct OpArgs {
     uint32_t *counters;          // split-K arrival counters, one per output tile, zero between launches
 };
 
-// Two operators of different tenants that run as one launch (co-issue): workgroups with blockIdx.y == i work on a[i].
-// Both operators have the same kernel, tile, split and launch shape; only their buffers differ.
+// Up to four operators of different tenants that run as one launch (co-issue): workgroups with blockIdx.y == i work on
+// a[i].  All of them have the same kernel, tile, split and launch shape; only their buffers differ.
+constexpr int COISSUE_MAX = 4;
 struct OpArgsPair {
-    OpArgs a[2];
+    OpArgs a[COISSUE_MAX];
 };
 
 // Magic numbers of the division above: l = ceil(log2 d), m = floor(2^32 (2^l - d) / d) + 1, s1 = min(l, 1), s2 = max(l - 1, 0).
@@ -138,7 +139,7 @@ inline StemGeom stem_geom(int R, int S, int form) {
     return g;
 }
 int stem_form(int R, int S, int sw, int W, int pw, int channels);    // 0: none, 1: aligned form (one dummy element per run), 2: general form
-int launch_stem(const OpArgs &a, void *stream, const OpArgs *mate = nullptr);
+int launch_stem(const OpArgs &a, void *stream, const OpArgs *mate = nullptr, int n_mates = 0);
 // K_ROWB: waves per workgroup of the instantiation for this window / channel counts, 0 if there is none.  Its packed
 // filter bank is slices x steps x tiles per slice x 64 lanes x 8 elements, a step being 16 consecutive elements of the
 // (r, s, c) reduction index and a tile 32 output channels.
@@ -147,13 +148,13 @@ int rowb_tiles(int R, int S, int C, int channels);   // 32-channel tiles per sli
 // K_PCONV: patch pixels of the instantiation that holds a map of width W (0: none).  Its filter bank is [n_pad][k_pad]
 // like the tile kernel's, with the reduction index ordered (64-channel chunk, tap, channel).
 int pconv_patch_pixels(int W);
-int launch_pconv(const OpArgs &a, void *stream, const OpArgs *mate = nullptr);
+int launch_pconv(const OpArgs &a, void *stream, const OpArgs *mate = nullptr, int n_mates = 0);
 bool rowb_patch_form(const OpArgs &a);   // 3x3, stride 1: activations staged once per tile as an input patch in LDS
-int launch_rowb(const OpArgs &a, void *stream, const OpArgs *mate = nullptr);
+int launch_rowb(const OpArgs &a, void *stream, const OpArgs *mate = nullptr, int n_mates = 0);
 
 // Launchers (defined in the .hip files).  Return a hipError_t as int.
-int launch_direct(const OpArgs &a, void *stream, const OpArgs *mate = nullptr);
-int launch_igemm(const OpArgs &a, void *stream, const OpArgs *mate = nullptr);
+int launch_direct(const OpArgs &a, void *stream, const OpArgs *mate = nullptr, int n_mates = 0);
+int launch_igemm(const OpArgs &a, void *stream, const OpArgs *mate = nullptr, int n_mates = 0);
 // Whether the launcher of this kernel can run two operators of equal launch shape as one launch.
 bool coissue_supported(const OpArgs &a);
 bool dwpw_fusable(const OpArgs &dw, const OpArgs &pw);

@@ -576,7 +576,7 @@ __global__ void fill_u32_kernel(uint32_t *p, size_t n, uint32_t v) {
 
 // ---------------------------------------------------------------------------------------------
 template <typename T>
-static int launch_typed(const OpArgs &a, hipStream_t st, const OpArgs *mate) {
+static int launch_typed(const OpArgs &a, hipStream_t st, const OpArgs *mate, int n_mates) {
     const dim3 block(256);
     auto blocks = [](int64_t threads) { return dim3((unsigned)((threads + 255) / 256)); };
     constexpr int VMAX = 16 / sizeof(T);          // 16-byte accesses
@@ -668,13 +668,14 @@ static int launch_typed(const OpArgs &a, hipStream_t st, const OpArgs *mate) {
     return (int)hipGetLastError();
 }
 
-int launch_direct(const OpArgs &a, void *stream, const OpArgs *mate) {
+int launch_direct(const OpArgs &a, void *stream, const OpArgs *mate, int n_mates) {
+    if (mate && (n_mates < 1 || n_mates >= COISSUE_MAX)) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
     if (mate && !coissue_supported(a)) return (int)hipErrorInvalidValue;
     switch (a.dtype) {
-        case MT_F32: return launch_typed<float>(a, st, mate);
-        case MT_F16: return launch_typed<f16>(a, st, mate);
-        case MT_BF16: return launch_typed<bf16>(a, st, mate);
+        case MT_F32: return launch_typed<float>(a, st, mate, n_mates);
+        case MT_F16: return launch_typed<f16>(a, st, mate, n_mates);
+        case MT_BF16: return launch_typed<bf16>(a, st, mate, n_mates);
     }
     return (int)hipErrorInvalidValue;
 }

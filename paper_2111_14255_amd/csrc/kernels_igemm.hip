@@ -864,10 +864,13 @@ __global__ void __launch_bounds__(256 * WK) igemm_pair_kernel(OpArgsPair p) {
 }
 
 template <typename T, int BN, int BM, int WN, int WM, int MF, int STAGES, int WK = 1>
-static void launch_cfg(const OpArgs &a, hipStream_t st, const OpArgs *mate) {
-    const dim3 grid(a.grid_x, mate ? 2 : 1);
+static void launch_cfg(const OpArgs &a, hipStream_t st, const OpArgs *mate, int n_mates) {
+    const dim3 grid(a.grid_x, mate ? 1 + n_mates : 1);
     OpArgsPair p;
-    if (mate) { p.a[0] = a; p.a[1] = *mate; }
+    if (mate) {
+        p.a[0] = a;
+        for (int i = 0; i < n_mates; ++i) p.a[1 + i] = mate[i];
+    }
     if (a.vec_a == A_UNIFORM) {
         if (mate) hipLaunchKernelGGL((igemm_pair_kernel<T, BN, BM, WN, WM, MF, STAGES, A_UNIFORM, WK>), grid, dim3(256 * WK), 0, st, p);
         else hipLaunchKernelGGL((igemm_kernel<T, BN, BM, WN, WM, MF, STAGES, A_UNIFORM, WK>), grid, dim3(256 * WK), 0, st, a);
@@ -880,18 +883,18 @@ static void launch_cfg(const OpArgs &a, hipStream_t st, const OpArgs *mate) {
 }
 
 template <typename T>
-static int launch_igemm_typed(const OpArgs &a, hipStream_t st, const OpArgs *mate) {
+static int launch_igemm_typed(const OpArgs &a, hipStream_t st, const OpArgs *mate, int n_mates) {
     switch (a.kernel_id) {
-        case K_IGEMM_128x128: launch_cfg<T, 128, 128, 2, 2, 32, 2>(a, st, mate); break;
+        case K_IGEMM_128x128: launch_cfg<T, 128, 128, 2, 2, 32, 2>(a, st, mate, n_mates); break;
         case K_IGEMM_128x64:
-            if (a.wk == 2) launch_cfg<T, 128, 64, 2, 2, 32, 2, 2>(a, st, mate);
-            else launch_cfg<T, 128, 64, 2, 2, 32, 2>(a, st, mate);
+            if (a.wk == 2) launch_cfg<T, 128, 64, 2, 2, 32, 2, 2>(a, st, mate, n_mates);
+            else launch_cfg<T, 128, 64, 2, 2, 32, 2>(a, st, mate, n_mates);
             break;
         case K_IGEMM_64x64:
-            if (a.wk == 2) launch_cfg<T, 64, 64, 2, 2, 32, 4, 2>(a, st, mate);
-            else launch_cfg<T, 64, 64, 2, 2, 32, 4, 1>(a, st, mate);
+            if (a.wk == 2) launch_cfg<T, 64, 64, 2, 2, 32, 4, 2>(a, st, mate, n_mates);
+            else launch_cfg<T, 64, 64, 2, 2, 32, 4, 1>(a, st, mate, n_mates);
             break;
-        case K_IGEMM_64x16: launch_cfg<T, 64, 16, 4, 1, 16, 4>(a, st, mate); break;
+        case K_IGEMM_64x16: launch_cfg<T, 64, 16, 4, 1, 16, 4>(a, st, mate, n_mates); break;
         case K_IGEMM_PW: {
             const dim3 grid(a.grid_x), block(256);
             if (a.split_k > 1) MT_LAUNCH((pw_direct_kernel<T, 4>), (pw_direct_pair_kernel<T, 4>), grid, block, st, a, mate);
@@ -1407,11 +1410,12 @@ int static_scratch_address(int device, void **ptr) {
     return 0;
 }
 
-int launch_igemm(const OpArgs &a, void *stream, const OpArgs *mate) {
+int launch_igemm(const OpArgs &a, void *stream, const OpArgs *mate, int n_mates) {
+    if (mate && (n_mates < 1 || n_mates >= COISSUE_MAX)) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
     if (mate && !coissue_supported(a)) return (int)hipErrorInvalidValue;
-    if (a.dtype == MT_F16) return launch_igemm_typed<f16>(a, st, mate);
-    if (a.dtype == MT_BF16) return launch_igemm_typed<bf16>(a, st, mate);
+    if (a.dtype == MT_F16) return launch_igemm_typed<f16>(a, st, mate, n_mates);
+    if (a.dtype == MT_BF16) return launch_igemm_typed<bf16>(a, st, mate, n_mates);
     return (int)hipErrorInvalidValue;
 }
 

@@ -255,7 +255,8 @@ int pconv_patch_pixels(int W) {
     return need <= 128 ? 128 : need <= 192 ? 192 : need <= 320 ? 320 : 0;
 }
 
-int launch_pconv(const OpArgs &a, void *stream, const OpArgs *mate) {
+int launch_pconv(const OpArgs &a, void *stream, const OpArgs *mate, int n_mates) {
+    if (mate && (n_mates < 1 || n_mates >= COISSUE_MAX)) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid(a.grid_x), block(512);
     const int ppx = pconv_patch_pixels(a.W);

@@ -366,7 +366,8 @@ bool rowb_patch_form(const OpArgs &a) { return a.R == 3 && a.S == 3 && a.sh == 1
 
 int rowb_waves(int R, int S, int C, int channels) { return rowb_tiles(R, S, C, channels) ? 8 : 0; }
 
-int launch_rowb(const OpArgs &a, void *stream, const OpArgs *mate) {
+int launch_rowb(const OpArgs &a, void *stream, const OpArgs *mate, int n_mates) {
+    if (mate && (n_mates < 1 || n_mates >= COISSUE_MAX)) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid(a.grid_x), block(a.block);
     const int nta = rowb_tiles(a.R, a.S, a.C, a.n_pad);

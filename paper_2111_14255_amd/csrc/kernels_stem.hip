@@ -249,7 +249,8 @@ int stem_form(int R, int S, int sw, int W, int pw, int channels) {
     return (sw % 2 == 0 && W % 2 == 0 && ((3 * pw) & 1)) ? 1 : 2;
 }
 
-int launch_stem(const OpArgs &a, void *stream, const OpArgs *mate) {
+int launch_stem(const OpArgs &a, void *stream, const OpArgs *mate, int n_mates) {
+    if (mate && (n_mates < 1 || n_mates >= COISSUE_MAX)) return (int)hipErrorInvalidValue;
     hipStream_t st = (hipStream_t)stream;
     const dim3 grid(a.grid_x), block(256);
     const int tn = a.n_pad / 32;

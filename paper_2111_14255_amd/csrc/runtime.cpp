@@ -496,15 +496,15 @@ namespace {
     } while (0)
 
 // One kernel launch; returns a hipError_t as int.
-int launch_kernel(const OpArgs &a, hipStream_t st, const OpArgs *mate = nullptr) {
-    if (a.kernel_id == K_STEM) return launch_stem(a, st, mate);
-    if (a.kernel_id == K_ROWB) return launch_rowb(a, st, mate);
-    if (a.kernel_id == K_PCONV) return launch_pconv(a, st, mate);
-    return is_gemm_kernel(a.kernel_id) ? launch_igemm(a, st, mate) : launch_direct(a, st, mate);
+int launch_kernel(const OpArgs &a, hipStream_t st, const OpArgs *mate = nullptr, int n_mates = 0) {
+    if (a.kernel_id == K_STEM) return launch_stem(a, st, mate, n_mates);
+    if (a.kernel_id == K_ROWB) return launch_rowb(a, st, mate, n_mates);
+    if (a.kernel_id == K_PCONV) return launch_pconv(a, st, mate, n_mates);
+    return is_gemm_kernel(a.kernel_id) ? launch_igemm(a, st, mate, n_mates) : launch_direct(a, st, mate, n_mates);
 }
 
-// Two operators can run as one launch if their kernel has a two-operator form and everything in their arguments but
-// the buffers (and the wave priority, which the launch takes from the first) is equal: same kernel, tile, split, shape.
+// Two operators can run in one launch if their kernel has a several-operator form and everything in their arguments
+// but the buffers (and the wave priority, which the launch takes from the first) is equal: same kernel, tile, split, shape.
 bool coissue_pair_ok(const OpArgs &a, const OpArgs &b) {
     if (!coissue_supported(a) || !coissue_supported(b)) return false;
     if ((a.res == nullptr) != (b.res == nullptr) || (a.ws == nullptr) != (b.ws == nullptr)) return false;
@@ -588,15 +588,20 @@ int launch_item(const mt_ctx *ctx, const mt_schedule *s, const IssueItem &it, co
         prev.prio = a.prio;
         return it.fuse == 2 ? launch_dwpw(prev, a, st) : launch_pwdw(prev, a, st);
     }
-    if (it.mate >= 0) {
-        const Tenant &tm = *ctx->tenants[it.mate];
-        OpArgs b = patched(tm, it.op, inputs[it.mate], outputs[it.mate]);
-        if (s->st_base && b.ws) {
-            b.ws = (float *)(s->st_base + s->st_ws_base[it.mate] + tm.st_ws_off[it.op]);
-            b.counters = (uint32_t *)(s->st_base + s->st_cnt_base[it.mate] + tm.st_cnt_off[it.op]);
+    if (it.mates[0] >= 0) {
+        OpArgs b[COISSUE_MAX - 1];
+        int nm = 0;
+        for (int k = 0; k < COISSUE_MAX - 1 && it.mates[k] >= 0; ++k, ++nm) {
+            const int m = it.mates[k];
+            const Tenant &tm = *ctx->tenants[m];
+            b[k] = patched(tm, it.op, inputs[m], outputs[m]);
+            if (s->st_base && b[k].ws) {
+                b[k].ws = (float *)(s->st_base + s->st_ws_base[m] + tm.st_ws_off[it.op]);
+                b[k].counters = (uint32_t *)(s->st_base + s->st_cnt_base[m] + tm.st_cnt_off[it.op]);
+            }
+            b[k].prio = a.prio;
         }
-        b.prio = a.prio;
-        return launch_kernel(a, st, &b);
+        return launch_kernel(a, st, b, nm);
     }
     if (it.fuse == 4) {
         OpArgs b = t.pool_args[it.op];
@@ -1900,39 +1905,52 @@ int32_t mt_schedule_create(mt_ctx *ctx, int32_t n_tenants, int32_t n_stages, con
             }
         };
         mark_pairs(sp.items, true);
-        // Co-issue: two tenants that share a stream and whose slices have the same length walk them together; operator i
-        // of the second runs inside the launch of operator i of the first where the two can (coissue_pair_ok), else
-        // right after it as a launch of its own.  The first tenant's items carry the mate, the second's stay in the list
-        // (they count as issued and carry the end-of-tenant timing) and launch nothing.
+        // Co-issue: up to `group` tenants that share a stream and whose slices have the same operator range walk them
+        // together; operator i of the others runs inside the launch of operator i of the first where they can
+        // (coissue_pair_ok with the first), else right after it as a launch of its own.  The first tenant's items carry
+        // the mates, the others' stay in the list (they count as issued and carry the end-of-tenant timing) and launch
+        // nothing.
         if (flags & MT_SCHED_COISSUE) {
+            const int group = COISSUE_MAX;
             int32_t hs[MT_MAX_TENANTS];
             stream_map(n_tenants, &slices[(size_t)st * n_tenants * 2], conc, hs);
+            auto range = [&](int t, int which) { return slices[((size_t)st * n_tenants + t) * 2 + which]; };
             for (int sm = 0; sm < n_tenants; ++sm) {
                 std::vector<int> on;                         // tenants of this stream, in tenant order
                 for (int i = 0; i < n_tenants; ++i)
                     if (hs[i] == sm) on.push_back(i);
-                for (size_t k = 0; k + 1 < on.size(); k += 2) {
-                    const int ta = on[k], tb = on[k + 1];
-                    const int ba = slices[((size_t)st * n_tenants + ta) * 2], ea = slices[((size_t)st * n_tenants + ta) * 2 + 1];
-                    const int bb = slices[((size_t)st * n_tenants + tb) * 2], eb = slices[((size_t)st * n_tenants + tb) * 2 + 1];
-                    if (ea - ba != eb - bb || ba != bb) continue;
-                    // operator i of the second tenant follows operator i of the first in the issue sequence
-                    std::vector<IssueItem> second(ea - ba), merged;
+                for (size_t k = 0; k + 1 < on.size();) {
+                    const int ta = on[k];
+                    std::vector<int> rest;                   // the following tenants of the same operator range
+                    while (k + 1 + rest.size() < on.size() && (int)rest.size() + 1 < group &&
+                           range(on[k + 1 + rest.size()], 0) == range(ta, 0) && range(on[k + 1 + rest.size()], 1) == range(ta, 1))
+                        rest.push_back(on[k + 1 + rest.size()]);
+                    k += 1 + rest.size();
+                    if (rest.empty()) continue;
+                    const int ba = range(ta, 0), ea = range(ta, 1);
+                    // operator i of the other tenants follows operator i of the first in the issue sequence
+                    std::vector<std::vector<IssueItem>> others(rest.size(), std::vector<IssueItem>(ea - ba));
+                    auto which = [&](int t) { for (size_t r = 0; r < rest.size(); ++r) if (rest[r] == t) return (int)r; return -1; };
                     for (const IssueItem &it : sp.items)
-                        if (it.tenant == tb) second[it.op - bb] = it;
+                        if (which(it.tenant) >= 0) others[which(it.tenant)][it.op - ba] = it;
+                    std::vector<IssueItem> merged;
                     merged.reserve(sp.items.size());
                     for (const IssueItem &it : sp.items) {
-                        if (it.tenant == tb) continue;
+                        if (which(it.tenant) >= 0) continue;
                         merged.push_back(it);
                         if (it.tenant != ta) continue;
-                        IssueItem other = second[it.op - ba];
-                        if (it.fuse == 0 && other.fuse == 0 &&
-                            coissue_pair_ok(ctx->tenants[ta]->args[it.op], ctx->tenants[tb]->args[it.op])) {
-                            merged.back().mate = tb;
-                            other.fuse = 1;
-                            ++s->n_fused;
+                        const size_t head = merged.size() - 1;
+                        int nm = 0;
+                        for (size_t r = 0; r < rest.size(); ++r) {
+                            IssueItem other = others[r][it.op - ba];
+                            if (it.fuse == 0 && other.fuse == 0 &&
+                                coissue_pair_ok(ctx->tenants[ta]->args[it.op], ctx->tenants[rest[r]]->args[it.op])) {
+                                merged[head].mates[nm++] = rest[r];
+                                other.fuse = 1;
+                                ++s->n_fused;
+                            }
+                            merged.push_back(other);
                         }
-                        merged.push_back(other);
                     }
                     sp.items.swap(merged);
                 }

@@ -1,4 +1,4 @@
-"""Co-issue on the GPU: two tenants that share a stream run operator i of both as one launch.  Outputs must have the
+"""Co-issue on the GPU: up to four tenants that share a stream run operator i of all of them as one launch.  Outputs must have the
 bits of the one-launch-per-operator schedule and match the oracle; tenants that cannot be paired must still run in order."""
 import numpy as np
 import pytest
@@ -44,7 +44,9 @@ def test_equal_tenants_are_paired_and_keep_their_bits():
                          ctx.schedule([[] for _ in lens], 1, concurrency=[1], flags=CO, label="co-issue, one stream"),
                          ctx.schedule(two, 2, concurrency=[2, 2], flags=CO | PAR, label="co-issue, two stages"),
                          ctx.schedule([[] for _ in lens], 1, flags=CO, label="co-issue asked for, a stream per tenant")], "bf16")
-        assert fused[:4] == [2 * lens[0]] * 4            # two pairs of tenants: one of every two operators runs inside its mate's launch
+        # two streams: two pairs of tenants, one of every two operators runs inside its mate's launch; one stream: the
+        # four tenants form one group and three of every four operators do
+        assert fused[0] == fused[1] == fused[3] == 2 * lens[0] and fused[2] == 3 * lens[0]
         assert fused[4] == 0                              # nothing shares a stream
         with pytest.raises(B.MtError):
             ctx.schedule([[] for _ in lens], 1, concurrency=[2], flags=CO | B.MT_SCHED_GRAPH)
@@ -102,22 +104,22 @@ def test_coissued_split_layers_in_the_fixed_scratch_array():
         t = g.gap(t)
         g.fc(t, 100)
         return g.done()
-    print("case two split-K tenants", flush=True)
-    mix = Mix([net(), net()], seed=924)
+    print("case three split-K tenants", flush=True)
+    mix = Mix([net(), net(), net()], seed=924)
     try:
         ctx = mix.ctx
         assert any(ctx.op_info(0, i).split_k > 1 for i in range(ctx.lens()[0]))
-        s = ctx.schedule([[], []], 1, concurrency=[1], flags=CO, label="co-issue")
+        s = ctx.schedule([[], [], []], 1, concurrency=[1], flags=CO, label="co-issue")
         fused = compare(mix, ctx.sequential(), [s], "f16")
-        assert fused[0] >= 2
+        assert fused[0] == 2 * ctx.lens()[0]              # one group of three: two of every three operators
         ref, _ = mix.run(ctx.sequential())
         for _ in range(2):
-            outs = [ctx.make_output(t) for t in range(2)]
+            outs = [ctx.make_output(t) for t in range(3)]
             for o in outs:
                 o.fill_(float("nan"))
             tm = ctx.run_static_scratch(s, mix.inputs, outs)
             assert tm["n_fused"] == fused[0]
-            for t in range(2):
+            for t in range(3):
                 np.testing.assert_array_equal(ctx.output_to_numpy(t, outs[t]), ref[t])
     finally:
         mix.close()
